@@ -1,0 +1,158 @@
+/* bmx.h - C ABI of the MI355X (gfx950) binary-layer library.
+ *
+ * The library computes the inference hot path of the binary layers of BMXNet
+ * (arXiv 1705.09864): sign-binarise and bit-pack fp32 activations and weights
+ * (paper Sec. 1, Sec. 2.2.1), then evaluate fully connected and convolution
+ * layers as xor + popcount dot products (Sec. 2.2.1; conv-as-GEMM mapping of
+ * Sec. 3.1), plus a k-bit generalisation built on the Eq. 1 quantiser.
+ *
+ * Conventions common to every call
+ *   - Returns an int status: BMX_OK (0) or a negative BMX_ERR_* code.  Nothing
+ *     throws or aborts.  All argument checks run on the host before any launch;
+ *     on an error return no kernel was launched and no output was touched.
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *     allocates nothing and keeps no state between calls.  Scratch memory is
+ *     passed in by the caller (`workspace`, sized with bmx_workspace_bytes).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
+ *     are asynchronous on it; the caller synchronises.
+ *   - Inputs and outputs must not overlap.
+ *   - Zero-sized problems (a row/batch/column count of 0) return BMX_OK without
+ *     launching.  Negative counts and K <= 0 give BMX_ERR_SHAPE.
+ *   - K (the dot-product length) must be < 2^24 so that float(dot) is exact.
+ *
+ * Packed format (part of the ABI; Sec. 2.2.1 BINARY_WORD, 64-bit flavour)
+ *   uint64 little-endian words; element k of a row is bit (k mod 64) of word
+ *   floor(k / 64), least significant bit first; bit 1 <-> +1, bit 0 <-> -1 with
+ *   sign(0) = +1, i.e. bit = (x >= 0.0f) (IEEE compare: -0.0 -> 1, NaN -> 0);
+ *   unused tail bits of the last word are 0.  Row stride ld_words >=
+ *   ceil(K / 64); words beyond ceil(K / 64) in a row are neither read nor
+ *   written.  Packed pointers must be 8-byte aligned.
+ *
+ * Output form
+ *   The integer result of a binary dot product is the +-1 dot product
+ *       dot = K - 2 * popcount(a XOR w),
+ *   which equals the float layer restricted to -1/+1 (Sec. 2.2.2).  The xnor
+ *   count of the paper's listing is (dot + K) / 2 (Eq. 2).
+ */
+#ifndef BMX_H
+#define BMX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BMX_OK 0
+#define BMX_ERR_NULL (-1)        /* a required pointer is NULL */
+#define BMX_ERR_SHAPE (-2)       /* negative size, K <= 0, K >= 2^24, empty conv output */
+#define BMX_ERR_LD (-3)          /* a leading dimension is smaller than the row it must hold */
+#define BMX_ERR_ALIGN (-4)       /* pointer not aligned (packed: 8 bytes, fp32/int32: 4 bytes) */
+#define BMX_ERR_UNSUPPORTED (-5) /* pack_dim, kernel size, stride, bit width outside the contract */
+#define BMX_ERR_WORKSPACE (-6)   /* workspace NULL or smaller than bmx_workspace_bytes says */
+#define BMX_ERR_HIP (-7)         /* the HIP runtime reported an error at launch */
+
+/* Operation selectors for bmx_workspace_bytes. */
+#define BMX_OP_BINARY_FC 1     /* dims = {batch, in_features, out_features} */
+#define BMX_OP_BINARY_CONV2D 2 /* dims = {N, C, H, W, O, KH, KW, stride, pad} */
+#define BMX_OP_QUANT_GEMM 3    /* dims = {M, N, K, bits_a, bits_w} */
+
+/* Sign-binarise and bit-pack (Sec. 1: binarisation with the sign function, 64
+ * values per word; Sec. 3.1: the per-forward-pass input binarisation step).
+ *   x        fp32 [rows, cols], row-major, leading dimension ldx >= cols (elements).
+ *   pack_dim 1: pack along cols: out is [rows][ceil(cols/64)]  (K contiguous in x);
+ *            0: pack along rows: out is [cols][ceil(rows/64)]  (x is stored K x N).
+ *   out      uint64, row stride out_ld_words >= ceil(K/64); written in full for the
+ *            first ceil(K/64) words of each row (tail bits 0). */
+int bmx_binarize_pack(const float* x, int64_t rows, int64_t cols, int64_t ldx, int pack_dim,
+                      uint64_t* out, int64_t out_ld_words, void* stream);
+
+/* xnor GEMM on packed operands (Sec. 2.2.1, the xnor GEMM kernel; output form per
+ * Sec. 2.2.2 / Eq. 2):  C[m][n] = K - 2 * sum_i popcount(A[m][i] ^ B[n][i]).
+ *   A  uint64 [M, lda_w], B uint64 [N, ldb_w], both packed along K (K contiguous),
+ *      tail bits zero.   C  int32 [M, ldc], ldc >= N; overwritten, not accumulated. */
+int bmx_xnor_gemm(const uint64_t* A, int64_t lda_w, const uint64_t* B, int64_t ldb_w, int32_t* C,
+                  int64_t ldc, int M, int N, int K, void* stream);
+
+/* Binary fully connected layer (Sec. 2, QFullyConnected): binarise + pack the fp32
+ * activations, xnor GEMM against pre-packed weights, optional scale.
+ *   x        fp32 [batch, in_features], leading dimension ldx.
+ *   Wp       uint64 [out_features, ldw_w], packed along in_features by
+ *            bmx_binarize_pack (pack_dim = 1 on [out, in] weights, or 0 on [in, out]).
+ *   alpha    fp32 [out_features] or NULL (= 1).
+ *   out_i32 / out_f32   exactly one is non-NULL; both are [batch, ldo], ldo >= out_features.
+ *            out_i32 = dot (alpha must be NULL);  out_f32 = alpha[o] * (float)dot.
+ *   workspace >= bmx_workspace_bytes(BMX_OP_BINARY_FC, {batch, in, out}, 3), 16-byte aligned. */
+int bmx_binary_fc(const float* x, int64_t ldx, const uint64_t* Wp, int64_t ldw_w,
+                  const float* alpha, int batch, int in_features, int out_features,
+                  int32_t* out_i32, float* out_f32, int64_t ldo, void* workspace,
+                  size_t workspace_bytes, void* stream);
+
+/* Pack OIHW fp32 convolution weights for bmx_binary_conv2d (the offline weight packing
+ * of Sec. 2.2.3).  Wp receives O * KH * KW * ceil(C/64) words: for filter o, tap
+ * (kh, kw), word cw holds channels 64*cw .. 64*cw+63 (missing channels = 0 bits).  This
+ * K order (tap-major, channel-minor) is private to the pair pack/conv; a dot product
+ * does not depend on a permutation applied to both operands. */
+int bmx_pack_conv_weights(const float* w_oihw, int O, int C, int KH, int KW, uint64_t* Wp,
+                          void* stream);
+
+/* Binary 2-D convolution (Sec. 2, QConvolution; Sec. 3.1: M = O, N = batch * Ho * Wo,
+ * K = KH * KW * C), NCHW in and out, Ho = (H + 2*pad - KH) / stride + 1 (same for Wo).
+ * The fp32 image is treated as zero padded BEFORE the sign function, so a padded tap
+ * counts as +1 (sign(0) = +1); this is what makes the layer equal to the float layer on
+ * -1/+1 data.  The im2col matrix is never materialised: activations are packed once
+ * along C per pixel into `workspace`, taps are gathered by the GEMM kernel.
+ *   x      fp32 [N, C, H, W];   Wp from bmx_pack_conv_weights;   alpha fp32 [O] or NULL.
+ *   out_i32 / out_f32   exactly one non-NULL, [N, O, Ho, Wo]; out_f32 = alpha[o]*(float)dot.
+ *   Supported: KH == KW in {1, 3, 5, 7}, stride in {1, 2}, 0 <= pad < KH, any C >= 1.
+ *   workspace >= bmx_workspace_bytes(BMX_OP_BINARY_CONV2D, {N,C,H,W,O,KH,KW,stride,pad}, 9). */
+int bmx_binary_conv2d(const float* x, int N, int C, int H, int W, const uint64_t* Wp, int O,
+                      int KH, int KW, int stride, int pad, const float* alpha, int32_t* out_i32,
+                      float* out_f32, void* workspace, size_t workspace_bytes, void* stream);
+
+/* The two stages of bmx_binary_conv2d as separate calls, for callers that keep the packed
+ * image (e.g. to feed several convolutions) or time the stages apart.
+ * bmx_pack_nchw: the fused im2col + pack step of Sec. 3.1 without the im2col matrix:
+ *   xp[n][h][w][cw] bit c = (x[n][64*cw + c][h][w] >= 0), missing channels = 0 bits;
+ *   xp holds N*H*W*ceil(C/64) words.
+ * bmx_binary_conv2d_packed: the implicit-GEMM stage on such an xp; all other arguments
+ *   as for bmx_binary_conv2d (no workspace). */
+int bmx_pack_nchw(const float* x, int N, int C, int H, int W, uint64_t* xp, void* stream);
+int bmx_binary_conv2d_packed(const uint64_t* xp, int N, int C, int H, int W, const uint64_t* Wp,
+                             int O, int KH, int KW, int stride, int pad, const float* alpha,
+                             int32_t* out_i32, float* out_f32, void* stream);
+
+/* k-bit activations x 1-bit weights (Sec. 1: arbitrary bit widths after DoReFa-Net;
+ * Sec. 2.1, Eq. 1).  a in [0, 1] (clamped) is quantised to the integer level
+ * q = round((2^bits_a - 1) * a), ties away from zero, and split into bits_a bit planes;
+ * w is binarised with the sign function.  With wb the weight bits,
+ *   S[m][n] = sum_k q[m][k] * sign(w[n][k])
+ *           = 2 * sum_p 2^p popcount(plane_p[m] & wb[n]) - sum_p 2^p popcount(plane_p[m]),
+ *   out_f32 = (float)S / (float)(2^bits_a - 1)      (the Eq. 1 scale applied once).
+ *   a fp32 [M, lda], w fp32 [N, ldw]; out_i32_scaled (S) and out_f32 are [M, ldo]; either
+ *   may be NULL, not both.  bits_a in 1..8, bits_w must be 1.
+ *   workspace >= bmx_workspace_bytes(BMX_OP_QUANT_GEMM, {M, N, K, bits_a, bits_w}, 5). */
+int bmx_quant_gemm(const float* a, int64_t lda, int bits_a, const float* w, int64_t ldw,
+                   int bits_w, int M, int N, int K, int32_t* out_i32_scaled, float* out_f32,
+                   int64_t ldo, void* workspace, size_t workspace_bytes, void* stream);
+
+/* alpha[r] = mean_j |w[r][j]| over cols entries per row (the XNOR-Net weight scale the
+ * abstract refers to), accumulated in fp64 and rounded once to fp32.
+ *   w fp32 [rows, ldw]; for OIHW conv weights pass rows = O, cols = ldw = C*KH*KW. */
+int bmx_alpha_mean_abs(const float* w, int64_t rows, int64_t cols, int64_t ldw, float* alpha,
+                       void* stream);
+
+/* Scratch bytes an operation needs (multiple of 256), or 0 if op/dims are invalid. */
+size_t bmx_workspace_bytes(int op, const int64_t* dims, int ndims);
+
+/* Static, human-readable name of a status code. */
+const char* bmx_status_string(int status);
+
+/* Library version, major * 10000 + minor * 100 + patch. */
+int bmx_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BMX_H */

@@ -14,7 +14,24 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "bmx_oracle.cpp")
-_LIB = os.path.join(_HERE, "libbmx_oracle.so")
+
+
+def _cpu_tag():
+    """The oracle is compiled with -march=native, so the library is keyed by the host's
+    instruction-set flags: a machine with another CPU builds its own copy."""
+    import hashlib
+    flags = ""
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("flags"):
+                flags = line
+                break
+    except OSError:
+        pass
+    return hashlib.sha1(flags.encode()).hexdigest()[:10]
+
+
+_LIB = os.path.join(_HERE, "libbmx_oracle.%s.so" % _cpu_tag())
 _lib = None
 
 _i64 = ctypes.c_int64

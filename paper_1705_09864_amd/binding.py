@@ -1,0 +1,207 @@
+"""Thin ctypes binding over libbmx.so: argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU (PyTorch is used for
+device memory and streams, nothing else), passes raw device pointers and sizes through
+the C ABI declared in include/bmx.h and raises BmxError on a non-zero status.  There is
+no CPU fallback: if the HIP library cannot be loaded the import of this module's
+functions fails loudly on first use.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbmx.so")
+_lib = None
+
+OP_BINARY_FC, OP_BINARY_CONV2D, OP_QUANT_GEMM = 1, 2, 3
+EXPORTS = ["bmx_binarize_pack", "bmx_xnor_gemm", "bmx_binary_fc", "bmx_pack_conv_weights",
+           "bmx_binary_conv2d", "bmx_quant_gemm", "bmx_alpha_mean_abs", "bmx_pack_nchw",
+           "bmx_binary_conv2d_packed", "bmx_workspace_bytes", "bmx_status_string", "bmx_version"]
+
+_i64, _int, _p, _sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+
+
+class BmxError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = status
+        super().__init__("%s failed: %s" % (what, status_string(status)))
+
+
+def lib():
+    """Load libbmx.so (building it first only if no built library is present)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            from . import build as _build
+            _build.build()
+        L = ctypes.CDLL(LIB_PATH)
+        L.bmx_binarize_pack.argtypes = [_p, _i64, _i64, _i64, _int, _p, _i64, _p]
+        L.bmx_xnor_gemm.argtypes = [_p, _i64, _p, _i64, _p, _i64, _int, _int, _int, _p]
+        L.bmx_binary_fc.argtypes = [_p, _i64, _p, _i64, _p, _int, _int, _int, _p, _p, _i64, _p, _sz, _p]
+        L.bmx_pack_conv_weights.argtypes = [_p, _int, _int, _int, _int, _p, _p]
+        L.bmx_binary_conv2d.argtypes = [_p, _int, _int, _int, _int, _p, _int, _int, _int, _int, _int,
+                                        _p, _p, _p, _p, _sz, _p]
+        L.bmx_quant_gemm.argtypes = [_p, _i64, _int, _p, _i64, _int, _int, _int, _int, _p, _p, _i64,
+                                     _p, _sz, _p]
+        L.bmx_alpha_mean_abs.argtypes = [_p, _i64, _i64, _i64, _p, _p]
+        L.bmx_workspace_bytes.argtypes = [_int, ctypes.POINTER(_i64), _int]
+        L.bmx_workspace_bytes.restype = _sz
+        L.bmx_status_string.argtypes = [_int]
+        L.bmx_status_string.restype = ctypes.c_char_p
+        L.bmx_version.restype = _int
+        L.bmx_pack_nchw.argtypes = [_p, _int, _int, _int, _int, _p, _p]
+        L.bmx_binary_conv2d_packed.argtypes = [_p, _int, _int, _int, _int, _p, _int, _int, _int, _int,
+                                               _int, _p, _p, _p, _p]
+        for name in EXPORTS[:9]:
+            getattr(L, name).restype = _int
+        _lib = L
+    return _lib
+
+
+def status_string(status):
+    return lib().bmx_status_string(int(status)).decode()
+
+
+def version():
+    return int(lib().bmx_version())
+
+
+def _ptr(t):
+    return _p(0) if t is None else _p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return _p(stream.cuda_stream)
+
+
+def _check(status, what):
+    if status != 0:
+        raise BmxError(status, what)
+
+
+def workspace_bytes(op, dims):
+    arr = (_i64 * len(dims))(*[int(d) for d in dims])
+    return int(lib().bmx_workspace_bytes(int(op), arr, len(dims)))
+
+
+def _workspace(op, dims, device, workspace):
+    need = workspace_bytes(op, dims)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+    return workspace, workspace.numel() * workspace.element_size()
+
+
+def _u64_as_i64(shape, device):
+    # torch has no general uint64 support; packed words are carried as int64 storage
+    return torch.empty(shape, dtype=torch.int64, device=device)
+
+
+def binarize_pack(x, pack_dim=1, out=None, stream=None):
+    """x: fp32 [rows, cols] device tensor (row-major, stride(1) == 1).  Returns packed int64
+    storage [R, ceil(K/64)] holding the uint64 words."""
+    rows, cols = x.shape
+    R, K = (rows, cols) if pack_dim else (cols, rows)
+    if out is None:
+        out = _u64_as_i64((R, (K + 63) // 64), x.device)
+    _check(lib().bmx_binarize_pack(_ptr(x), rows, cols, x.stride(0) if rows > 1 else cols, pack_dim,
+                                   _ptr(out), out.stride(0) if out.shape[0] > 1 else out.shape[1],
+                                   _stream(stream)), "bmx_binarize_pack")
+    return out
+
+
+def xnor_gemm(A, B, K, out=None, stream=None):
+    M, N = A.shape[0], B.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=A.device)
+    _check(lib().bmx_xnor_gemm(_ptr(A), A.shape[1], _ptr(B), B.shape[1], _ptr(out), max(N, 1), M, N, K,
+                               _stream(stream)), "bmx_xnor_gemm")
+    return out
+
+
+def binary_fc(x, Wp, alpha=None, integer_out=False, out=None, workspace=None, stream=None):
+    batch, fin = x.shape
+    fout = Wp.shape[0]
+    if out is None:
+        out = torch.empty((batch, fout), dtype=torch.int32 if integer_out else torch.float32,
+                          device=x.device)
+    ws, ws_bytes = _workspace(OP_BINARY_FC, (batch, fin, fout), x.device, workspace)
+    oi, of = (out, None) if integer_out else (None, out)
+    _check(lib().bmx_binary_fc(_ptr(x), x.stride(0) if batch > 1 else fin, _ptr(Wp), Wp.shape[1],
+                               _ptr(alpha), batch, fin, fout, _ptr(oi), _ptr(of), max(fout, 1),
+                               _ptr(ws), ws_bytes, _stream(stream)), "bmx_binary_fc")
+    return out
+
+
+def pack_conv_weights(w, stream=None):
+    O, C, KH, KW = w.shape
+    Wp = _u64_as_i64((O, KH * KW * ((C + 63) // 64)), w.device)
+    _check(lib().bmx_pack_conv_weights(_ptr(w), O, C, KH, KW, _ptr(Wp), _stream(stream)),
+           "bmx_pack_conv_weights")
+    return Wp
+
+
+def conv_out_hw(H, W, KH, KW, stride, pad):
+    return (H + 2 * pad - KH) // stride + 1, (W + 2 * pad - KW) // stride + 1
+
+
+def binary_conv2d(x, Wp, O, KH, KW, stride=1, pad=0, alpha=None, integer_out=False, out=None,
+                  workspace=None, stream=None):
+    N, C, H, W = x.shape
+    Ho, Wo = conv_out_hw(H, W, KH, KW, stride, pad)
+    if out is None:
+        out = torch.empty((N, O, Ho, Wo), dtype=torch.int32 if integer_out else torch.float32,
+                          device=x.device)
+    ws, ws_bytes = _workspace(OP_BINARY_CONV2D, (N, C, H, W, O, KH, KW, stride, pad), x.device,
+                              workspace)
+    oi, of = (out, None) if integer_out else (None, out)
+    _check(lib().bmx_binary_conv2d(_ptr(x), N, C, H, W, _ptr(Wp), O, KH, KW, stride, pad, _ptr(alpha),
+                                   _ptr(oi), _ptr(of), _ptr(ws), ws_bytes, _stream(stream)),
+           "bmx_binary_conv2d")
+    return out
+
+
+def pack_nchw(x, out=None, stream=None):
+    N, C, H, W = x.shape
+    if out is None:
+        out = _u64_as_i64((N, H, W, (C + 63) // 64), x.device)
+    _check(lib().bmx_pack_nchw(_ptr(x), N, C, H, W, _ptr(out), _stream(stream)), "bmx_pack_nchw")
+    return out
+
+
+def binary_conv2d_packed(xp, C, Wp, O, KH, KW, stride=1, pad=0, alpha=None, integer_out=False,
+                         out=None, stream=None):
+    N, H, W, _ = xp.shape
+    Ho, Wo = conv_out_hw(H, W, KH, KW, stride, pad)
+    if out is None:
+        out = torch.empty((N, O, Ho, Wo), dtype=torch.int32 if integer_out else torch.float32,
+                          device=xp.device)
+    oi, of = (out, None) if integer_out else (None, out)
+    _check(lib().bmx_binary_conv2d_packed(_ptr(xp), N, C, H, W, _ptr(Wp), O, KH, KW, stride, pad,
+                                          _ptr(alpha), _ptr(oi), _ptr(of), _stream(stream)),
+           "bmx_binary_conv2d_packed")
+    return out
+
+
+def quant_gemm(a, w, bits_a, bits_w=1, want_int=True, want_float=True, workspace=None, stream=None):
+    M, K = a.shape
+    N = w.shape[0]
+    S = torch.empty((M, N), dtype=torch.int32, device=a.device) if want_int else None
+    of = torch.empty((M, N), dtype=torch.float32, device=a.device) if want_float else None
+    ws, ws_bytes = _workspace(OP_QUANT_GEMM, (M, N, K, bits_a, bits_w), a.device, workspace)
+    _check(lib().bmx_quant_gemm(_ptr(a), a.stride(0) if M > 1 else K, bits_a, _ptr(w),
+                                w.stride(0) if N > 1 else K, bits_w, M, N, K, _ptr(S), _ptr(of),
+                                max(N, 1), _ptr(ws), ws_bytes, _stream(stream)), "bmx_quant_gemm")
+    return S, of
+
+
+def alpha_mean_abs(w, stream=None):
+    rows = w.shape[0]
+    cols = w.numel() // max(rows, 1)
+    alpha = torch.empty((rows,), dtype=torch.float32, device=w.device)
+    _check(lib().bmx_alpha_mean_abs(_ptr(w), rows, cols, cols, _ptr(alpha), _stream(stream)),
+           "bmx_alpha_mean_abs")
+    return alpha

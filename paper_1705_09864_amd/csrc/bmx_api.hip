@@ -1,0 +1,257 @@
+// C-ABI layer of libbmx: host-side argument validation and dispatch.
+// Every check happens before the first launch, so an error return means that no kernel
+// ran and no output byte was written.  The contract of each call is in include/bmx.h.
+#include "../../include/bmx.h"
+#include "bmx_internal.h"
+
+namespace {
+
+constexpr int64_t kMaxK = (int64_t)1 << 24;  // float(dot) stays exact below this
+
+inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p % a) != 0; }
+inline size_t round256(size_t b) { return (b + 255) & ~(size_t)255; }
+inline int hip_status(hipError_t e) { return e == hipSuccess ? BMX_OK : BMX_ERR_HIP; }
+
+struct ConvGeom {
+  int Ho, Wo, Cw;
+};
+
+int conv_check(int N, int C, int H, int W, int O, int KH, int KW, int stride, int pad,
+               ConvGeom* g) {
+  if (N < 0 || C <= 0 || H <= 0 || W <= 0 || O < 0) return BMX_ERR_SHAPE;
+  if (KH != KW || !(KH == 1 || KH == 3 || KH == 5 || KH == 7)) return BMX_ERR_UNSUPPORTED;
+  if (!(stride == 1 || stride == 2)) return BMX_ERR_UNSUPPORTED;
+  if (pad < 0 || pad >= KH) return BMX_ERR_UNSUPPORTED;
+  if ((int64_t)C * KH * KW >= kMaxK) return BMX_ERR_SHAPE;
+  if (H + 2 * pad < KH || W + 2 * pad < KW) return BMX_ERR_SHAPE;
+  g->Ho = (H + 2 * pad - KH) / stride + 1;
+  g->Wo = (W + 2 * pad - KW) / stride + 1;
+  g->Cw = (int)bmx::words_for(C);
+  return BMX_OK;
+}
+
+struct QuantWs {
+  size_t planes_off, wb_off, rowsum_off, total;
+};
+
+QuantWs quant_ws(int64_t M, int64_t N, int64_t K, int bits_a) {
+  const int64_t Kw = bmx::words_for(K);
+  QuantWs q;
+  q.planes_off = 0;
+  q.wb_off = round256((size_t)bits_a * M * Kw * 8);
+  q.rowsum_off = q.wb_off + round256((size_t)N * Kw * 8);
+  q.total = q.rowsum_off + round256((size_t)M * 4);
+  return q;
+}
+
+}  // namespace
+
+extern "C" {
+
+int bmx_version(void) { return 100; }
+
+const char* bmx_status_string(int status) {
+  switch (status) {
+    case BMX_OK: return "BMX_OK";
+    case BMX_ERR_NULL: return "BMX_ERR_NULL: required pointer is NULL";
+    case BMX_ERR_SHAPE: return "BMX_ERR_SHAPE: invalid size";
+    case BMX_ERR_LD: return "BMX_ERR_LD: leading dimension too small";
+    case BMX_ERR_ALIGN: return "BMX_ERR_ALIGN: misaligned pointer";
+    case BMX_ERR_UNSUPPORTED: return "BMX_ERR_UNSUPPORTED: argument outside the supported set";
+    case BMX_ERR_WORKSPACE: return "BMX_ERR_WORKSPACE: workspace missing or too small";
+    case BMX_ERR_HIP: return "BMX_ERR_HIP: HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+size_t bmx_workspace_bytes(int op, const int64_t* dims, int ndims) {
+  if (!dims) return 0;
+  switch (op) {
+    case BMX_OP_BINARY_FC: {
+      if (ndims != 3 || dims[0] < 0 || dims[1] <= 0 || dims[1] >= kMaxK || dims[2] < 0) return 0;
+      return round256((size_t)(dims[0] > 0 ? dims[0] : 1) * bmx::words_for(dims[1]) * 8);
+    }
+    case BMX_OP_BINARY_CONV2D: {
+      if (ndims != 9) return 0;
+      ConvGeom g;
+      if (conv_check((int)dims[0], (int)dims[1], (int)dims[2], (int)dims[3], (int)dims[4],
+                     (int)dims[5], (int)dims[6], (int)dims[7], (int)dims[8], &g) != BMX_OK)
+        return 0;
+      const size_t n = dims[0] > 0 ? (size_t)dims[0] : 1;
+      return round256(n * dims[2] * dims[3] * g.Cw * 8);
+    }
+    case BMX_OP_QUANT_GEMM: {
+      if (ndims != 5 || dims[0] < 0 || dims[1] < 0 || dims[2] <= 0 || dims[2] >= kMaxK) return 0;
+      if (dims[3] < 1 || dims[3] > 8 || dims[4] != 1) return 0;
+      return quant_ws(dims[0] > 0 ? dims[0] : 1, dims[1] > 0 ? dims[1] : 1, dims[2], (int)dims[3])
+          .total;
+    }
+    default: return 0;
+  }
+}
+
+int bmx_binarize_pack(const float* x, int64_t rows, int64_t cols, int64_t ldx, int pack_dim,
+                      uint64_t* out, int64_t out_ld_words, void* stream) {
+  if (pack_dim != 0 && pack_dim != 1) return BMX_ERR_UNSUPPORTED;
+  if (rows < 0 || cols < 0) return BMX_ERR_SHAPE;
+  const int64_t R = pack_dim ? rows : cols;
+  const int64_t K = pack_dim ? cols : rows;
+  if (R == 0) return BMX_OK;
+  if (K <= 0 || K >= kMaxK) return BMX_ERR_SHAPE;
+  if (!x || !out) return BMX_ERR_NULL;
+  if (ldx < cols) return BMX_ERR_LD;
+  if (out_ld_words < bmx::words_for(K)) return BMX_ERR_LD;
+  if (misaligned(x, 4) || misaligned(out, 8)) return BMX_ERR_ALIGN;
+  hipStream_t s = (hipStream_t)stream;
+  if (pack_dim)
+    return hip_status(bmx::launch_pack_rows(x, rows, cols, ldx, out, out_ld_words, s));
+  return hip_status(bmx::launch_pack_strided(x, 1, rows, cols, ldx, 0, out, out_ld_words, s));
+}
+
+int bmx_xnor_gemm(const uint64_t* A, int64_t lda_w, const uint64_t* B, int64_t ldb_w, int32_t* C,
+                  int64_t ldc, int M, int N, int K, void* stream) {
+  if (M < 0 || N < 0) return BMX_ERR_SHAPE;
+  if (K <= 0 || K >= kMaxK) return BMX_ERR_SHAPE;
+  if (M == 0 || N == 0) return BMX_OK;
+  if (!A || !B || !C) return BMX_ERR_NULL;
+  const int64_t Kw = bmx::words_for(K);
+  if (lda_w < Kw || ldb_w < Kw || ldc < N) return BMX_ERR_LD;
+  if (misaligned(A, 8) || misaligned(B, 8) || misaligned(C, 4)) return BMX_ERR_ALIGN;
+  return hip_status(bmx::launch_xnor_gemm(A, lda_w, B, ldb_w, M, N, K, nullptr, C, nullptr, ldc,
+                                          (hipStream_t)stream));
+}
+
+int bmx_binary_fc(const float* x, int64_t ldx, const uint64_t* Wp, int64_t ldw_w,
+                  const float* alpha, int batch, int in_features, int out_features,
+                  int32_t* out_i32, float* out_f32, int64_t ldo, void* workspace,
+                  size_t workspace_bytes, void* stream) {
+  if (batch < 0 || out_features < 0) return BMX_ERR_SHAPE;
+  if (in_features <= 0 || in_features >= kMaxK) return BMX_ERR_SHAPE;
+  if (batch == 0 || out_features == 0) return BMX_OK;
+  if (!x || !Wp) return BMX_ERR_NULL;
+  if ((out_i32 == nullptr) == (out_f32 == nullptr)) return BMX_ERR_NULL;
+  if (out_i32 && alpha) return BMX_ERR_UNSUPPORTED;
+  const int64_t Kw = bmx::words_for(in_features);
+  if (ldx < in_features || ldw_w < Kw || ldo < out_features) return BMX_ERR_LD;
+  if (misaligned(x, 4) || misaligned(Wp, 8) || misaligned(alpha, 4) || misaligned(out_i32, 4) ||
+      misaligned(out_f32, 4))
+    return BMX_ERR_ALIGN;
+  const int64_t dims[3] = {batch, in_features, out_features};
+  const size_t need = bmx_workspace_bytes(BMX_OP_BINARY_FC, dims, 3);
+  if (!workspace || workspace_bytes < need) return BMX_ERR_WORKSPACE;
+  if (misaligned(workspace, 16)) return BMX_ERR_ALIGN;
+  hipStream_t s = (hipStream_t)stream;
+  uint64_t* xp = (uint64_t*)workspace;
+  hipError_t e = bmx::launch_pack_rows(x, batch, in_features, ldx, xp, Kw, s);
+  if (e != hipSuccess) return BMX_ERR_HIP;
+  return hip_status(bmx::launch_xnor_gemm(xp, Kw, Wp, ldw_w, batch, out_features, in_features,
+                                          alpha, out_i32, out_f32, ldo, s));
+}
+
+int bmx_pack_conv_weights(const float* w_oihw, int O, int C, int KH, int KW, uint64_t* Wp,
+                          void* stream) {
+  ConvGeom g;
+  // geometry rules for the kernel window only; image size does not matter here
+  const int rc = conv_check(1, C, KH, KW, O, KH, KW, 1, 0, &g);
+  if (rc != BMX_OK) return rc;
+  if (O == 0) return BMX_OK;
+  if (!w_oihw || !Wp) return BMX_ERR_NULL;
+  if (misaligned(w_oihw, 4) || misaligned(Wp, 8)) return BMX_ERR_ALIGN;
+  return hip_status(bmx::launch_pack_conv_weights(w_oihw, O, C, KH, KW, Wp, (hipStream_t)stream));
+}
+
+int bmx_pack_nchw(const float* x, int N, int C, int H, int W, uint64_t* xp, void* stream) {
+  if (N < 0 || C <= 0 || H <= 0 || W <= 0) return BMX_ERR_SHAPE;
+  if (N == 0) return BMX_OK;
+  if (!x || !xp) return BMX_ERR_NULL;
+  if (misaligned(x, 4) || misaligned(xp, 8)) return BMX_ERR_ALIGN;
+  const int64_t HW = (int64_t)H * W;
+  // per image a [C][H*W] matrix packed down its rows -> [H*W][Cw]
+  return hip_status(bmx::launch_pack_strided(x, N, C, HW, HW, (int64_t)C * HW, xp,
+                                             bmx::words_for(C), (hipStream_t)stream));
+}
+
+int bmx_binary_conv2d_packed(const uint64_t* xp, int N, int C, int H, int W, const uint64_t* Wp,
+                             int O, int KH, int KW, int stride, int pad, const float* alpha,
+                             int32_t* out_i32, float* out_f32, void* stream) {
+  ConvGeom g;
+  const int rc = conv_check(N, C, H, W, O, KH, KW, stride, pad, &g);
+  if (rc != BMX_OK) return rc;
+  if (N == 0 || O == 0) return BMX_OK;
+  if (!xp || !Wp) return BMX_ERR_NULL;
+  if ((out_i32 == nullptr) == (out_f32 == nullptr)) return BMX_ERR_NULL;
+  if (out_i32 && alpha) return BMX_ERR_UNSUPPORTED;
+  if (misaligned(xp, 8) || misaligned(Wp, 8) || misaligned(alpha, 4) || misaligned(out_i32, 4) ||
+      misaligned(out_f32, 4))
+    return BMX_ERR_ALIGN;
+  return hip_status(bmx::launch_binary_conv2d(xp, N, C, H, W, Wp, O, KH, KW, stride, pad, alpha,
+                                              out_i32, out_f32, (hipStream_t)stream));
+}
+
+int bmx_binary_conv2d(const float* x, int N, int C, int H, int W, const uint64_t* Wp, int O,
+                      int KH, int KW, int stride, int pad, const float* alpha, int32_t* out_i32,
+                      float* out_f32, void* workspace, size_t workspace_bytes, void* stream) {
+  ConvGeom g;
+  const int rc = conv_check(N, C, H, W, O, KH, KW, stride, pad, &g);
+  if (rc != BMX_OK) return rc;
+  if (N == 0 || O == 0) return BMX_OK;
+  if (!x || !Wp) return BMX_ERR_NULL;
+  if ((out_i32 == nullptr) == (out_f32 == nullptr)) return BMX_ERR_NULL;
+  if (out_i32 && alpha) return BMX_ERR_UNSUPPORTED;
+  if (misaligned(x, 4) || misaligned(Wp, 8) || misaligned(alpha, 4) || misaligned(out_i32, 4) ||
+      misaligned(out_f32, 4))
+    return BMX_ERR_ALIGN;
+  const int64_t dims[9] = {N, C, H, W, O, KH, KW, stride, pad};
+  const size_t need = bmx_workspace_bytes(BMX_OP_BINARY_CONV2D, dims, 9);
+  if (!workspace || workspace_bytes < need) return BMX_ERR_WORKSPACE;
+  if (misaligned(workspace, 16)) return BMX_ERR_ALIGN;
+  uint64_t* xp = (uint64_t*)workspace;
+  int st = bmx_pack_nchw(x, N, C, H, W, xp, stream);
+  if (st != BMX_OK) return st;
+  return bmx_binary_conv2d_packed(xp, N, C, H, W, Wp, O, KH, KW, stride, pad, alpha, out_i32,
+                                  out_f32, stream);
+}
+
+int bmx_quant_gemm(const float* a, int64_t lda, int bits_a, const float* w, int64_t ldw,
+                   int bits_w, int M, int N, int K, int32_t* out_i32_scaled, float* out_f32,
+                   int64_t ldo, void* workspace, size_t workspace_bytes, void* stream) {
+  if (M < 0 || N < 0) return BMX_ERR_SHAPE;
+  if (K <= 0 || K >= kMaxK) return BMX_ERR_SHAPE;
+  if (bits_a < 1 || bits_a > 8 || bits_w != 1) return BMX_ERR_UNSUPPORTED;
+  if ((int64_t)K * ((1 << bits_a) - 1) >= ((int64_t)1 << 31)) return BMX_ERR_SHAPE;
+  if (M == 0 || N == 0) return BMX_OK;
+  if (!a || !w) return BMX_ERR_NULL;
+  if (!out_i32_scaled && !out_f32) return BMX_ERR_NULL;
+  if (lda < K || ldw < K || ldo < N) return BMX_ERR_LD;
+  if (misaligned(a, 4) || misaligned(w, 4) || misaligned(out_i32_scaled, 4) ||
+      misaligned(out_f32, 4))
+    return BMX_ERR_ALIGN;
+  const QuantWs q = quant_ws(M, N, K, bits_a);
+  if (!workspace || workspace_bytes < q.total) return BMX_ERR_WORKSPACE;
+  if (misaligned(workspace, 16)) return BMX_ERR_ALIGN;
+  hipStream_t s = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  uint64_t* planes = (uint64_t*)(ws + q.planes_off);
+  uint64_t* wb = (uint64_t*)(ws + q.wb_off);
+  int32_t* rowsum = (int32_t*)(ws + q.rowsum_off);
+  const int64_t Kw = bmx::words_for(K);
+  hipError_t e = bmx::launch_quant_pack(a, M, K, lda, bits_a, planes, rowsum, s);
+  if (e != hipSuccess) return BMX_ERR_HIP;
+  e = bmx::launch_pack_rows(w, N, K, ldw, wb, Kw, s);
+  if (e != hipSuccess) return BMX_ERR_HIP;
+  return hip_status(bmx::launch_plane_gemm(planes, bits_a, rowsum, wb, M, N, K, out_i32_scaled,
+                                           out_f32, ldo, s));
+}
+
+int bmx_alpha_mean_abs(const float* w, int64_t rows, int64_t cols, int64_t ldw, float* alpha,
+                       void* stream) {
+  if (rows < 0) return BMX_ERR_SHAPE;
+  if (cols <= 0) return BMX_ERR_SHAPE;
+  if (rows == 0) return BMX_OK;
+  if (!w || !alpha) return BMX_ERR_NULL;
+  if (ldw < cols) return BMX_ERR_LD;
+  if (misaligned(w, 4) || misaligned(alpha, 4)) return BMX_ERR_ALIGN;
+  return hip_status(bmx::launch_alpha_mean_abs(w, rows, cols, ldw, alpha, (hipStream_t)stream));
+}
+
+}  // extern "C"

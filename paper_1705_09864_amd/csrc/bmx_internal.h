@@ -1,0 +1,47 @@
+// Internal launcher declarations shared by the translation units of libbmx.
+// Every launcher assumes its arguments were validated by the C-ABI layer
+// (bmx_api.hip) and returns hipGetLastError() after enqueueing its kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace bmx {
+
+__host__ __device__ static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+__host__ __device__ static inline int64_t words_for(int64_t k) { return (k + 63) / 64; }
+
+// pack.hip -------------------------------------------------------------------
+// Row pack: out[r][w] bit j = (x[r*ldx + 64w + j] >= 0), K contiguous in x.
+hipError_t launch_pack_rows(const float* x, int64_t rows, int64_t cols, int64_t ldx, uint64_t* out,
+                            int64_t out_ld, hipStream_t s);
+// Strided pack of `batch` matrices stored [K][ncol] (row stride ldx, matrix stride
+// batch_stride): out[b][n][w] bit j = (x[b][64w + j][n] >= 0); out row stride out_ld,
+// matrix stride ncol*out_ld.  Serves pack_dim = 0 and the NCHW channel pack.
+hipError_t launch_pack_strided(const float* x, int64_t batch, int64_t K, int64_t ncol, int64_t ldx,
+                               int64_t batch_stride, uint64_t* out, int64_t out_ld, hipStream_t s);
+hipError_t launch_pack_conv_weights(const float* w, int O, int C, int KH, int KW, uint64_t* Wp,
+                                    hipStream_t s);
+hipError_t launch_alpha_mean_abs(const float* w, int64_t rows, int64_t cols, int64_t ldw,
+                                 float* alpha, hipStream_t s);
+// Eq. 1 quantise + bit-plane pack: planes[p][m][w], p < bits; rowsum[m] = sum_k q[m][k].
+hipError_t launch_quant_pack(const float* a, int64_t M, int64_t K, int64_t lda, int bits,
+                             uint64_t* planes, int32_t* rowsum, hipStream_t s);
+
+// gemm.hip -------------------------------------------------------------------
+// out = K - 2*popcount(A ^ B); exactly one of C_i32 / C_f32 non-null;
+// C_f32[m][n] = (alpha_n ? alpha_n[n] : 1) * float(dot).
+hipError_t launch_xnor_gemm(const uint64_t* A, int64_t lda_w, const uint64_t* B, int64_t ldb_w,
+                            int M, int N, int K, const float* alpha_n, int32_t* C_i32, float* C_f32,
+                            int64_t ldc, hipStream_t s);
+// S = 2*sum_p 2^p pc(plane_p & wb) - rowsum; out_f32 = float(S) / float(2^bits - 1).
+hipError_t launch_plane_gemm(const uint64_t* planes, int bits, const int32_t* rowsum,
+                             const uint64_t* Wb, int M, int N, int K, int32_t* S, float* out_f32,
+                             int64_t ldo, hipStream_t s);
+
+// conv.hip -------------------------------------------------------------------
+// Implicit-GEMM convolution on the channel-packed image Xp [N][H][W][Cw].
+hipError_t launch_binary_conv2d(const uint64_t* Xp, int N, int C, int H, int W, const uint64_t* Wp,
+                                int O, int KH, int KW, int stride, int pad, const float* alpha,
+                                int32_t* out_i32, float* out_f32, hipStream_t s);
+
+}  // namespace bmx

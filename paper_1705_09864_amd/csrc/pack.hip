@@ -1,0 +1,195 @@
+// Binarise / quantise + bit-pack kernels (HBM-bandwidth bound).
+// Paper: Sec. 1 (sign binarisation, 64 values per word), Sec. 3.1 (the per-forward
+// input binarisation step), Sec. 2.1 Eq. 1 (k-bit quantiser).
+#include "bmx_internal.h"
+
+namespace bmx {
+
+static constexpr int kWave = 64;
+
+// One wave packs 8 consecutive words (512 floats) of one row: lane <-> k, so every
+// load instruction is a 256-byte coalesced read and the 64-lane compare mask is the
+// packed word itself.  All 8 loads are issued before the first compare.
+__global__ void __launch_bounds__(256)
+pack_rows_kernel(const float* __restrict__ x, int64_t rows, int64_t cols, int64_t ldx,
+                 uint64_t* __restrict__ out, int64_t out_ld, int64_t Kw, int64_t blocks_per_row) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t wave = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+  if (wave >= rows * blocks_per_row) return;
+  const int64_t r = wave / blocks_per_row;
+  const int64_t b = wave - r * blocks_per_row;
+  const float* xr = x + r * ldx;
+  const int64_t k0 = b * 512 + lane;
+  float v[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int64_t k = k0 + 64 * j;
+    v[j] = (k < cols) ? xr[k] : -1.0f;  // out-of-row lanes contribute 0 bits
+  }
+  uint64_t mine = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const uint64_t m = __ballot(v[j] >= 0.0f);
+    if (lane == j) mine = m;
+  }
+  const int64_t w = b * 8 + lane;
+  if (lane < 8 && w < Kw) out[r * out_ld + w] = mine;
+}
+
+hipError_t launch_pack_rows(const float* x, int64_t rows, int64_t cols, int64_t ldx, uint64_t* out,
+                            int64_t out_ld, hipStream_t s) {
+  const int64_t Kw = words_for(cols);
+  // A dense matrix whose rows are whole words is one long row.
+  if (ldx == cols && out_ld == Kw && (cols % 64) == 0) {
+    cols = rows * cols;
+    ldx = cols;
+    rows = 1;
+    out_ld = cols / 64;
+  }
+  const int64_t Kw2 = words_for(cols);
+  const int64_t bpr = ceil_div(Kw2, 8);
+  const int64_t waves = rows * bpr;
+  const int64_t blocks = ceil_div(waves, 4);
+  hipLaunchKernelGGL(pack_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, s, x, rows, cols, ldx,
+                     out, out_ld, Kw2, bpr);
+  return hipGetLastError();
+}
+
+// Strided pack: thread <-> column n (coalesced along n for every k), 64 rows of the
+// K dimension folded into one word per thread.
+__global__ void __launch_bounds__(256)
+pack_strided_kernel(const float* __restrict__ x, int64_t batch, int64_t K, int64_t ncol,
+                    int64_t ldx, int64_t batch_stride, uint64_t* __restrict__ out, int64_t out_ld,
+                    int64_t Kw) {
+  const int64_t n = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (n >= ncol) return;
+  for (int64_t b = blockIdx.z; b < batch; b += gridDim.z) {
+    for (int64_t w = blockIdx.y; w < Kw; w += gridDim.y) {
+      const float* xb = x + b * batch_stride + (w * 64) * ldx + n;
+      const int64_t kmax = K - w * 64;  // rows left in this word (>= 1)
+      uint32_t lo = 0, hi = 0;
+#pragma unroll
+      for (int j = 0; j < 32; ++j) {
+        const float v = (j < kmax) ? xb[(int64_t)j * ldx] : -1.0f;
+        lo |= (v >= 0.0f ? 1u : 0u) << j;
+      }
+#pragma unroll
+      for (int j = 0; j < 32; ++j) {
+        const float v = (j + 32 < kmax) ? xb[(int64_t)(j + 32) * ldx] : -1.0f;
+        hi |= (v >= 0.0f ? 1u : 0u) << j;
+      }
+      out[(b * ncol + n) * out_ld + w] = ((uint64_t)hi << 32) | lo;
+    }
+  }
+}
+
+hipError_t launch_pack_strided(const float* x, int64_t batch, int64_t K, int64_t ncol, int64_t ldx,
+                               int64_t batch_stride, uint64_t* out, int64_t out_ld, hipStream_t s) {
+  const int64_t Kw = words_for(K);
+  dim3 grid((unsigned)ceil_div(ncol, 256), (unsigned)(Kw < 65535 ? Kw : 65535),
+            (unsigned)(batch < 65535 ? batch : 65535));
+  hipLaunchKernelGGL(pack_strided_kernel, grid, dim3(256), 0, s, x, batch, K, ncol, ldx,
+                     batch_stride, out, out_ld, Kw);
+  return hipGetLastError();
+}
+
+// Offline weight packing for the convolution: one thread per output word.
+// Wp[o][(kh*KW + kw)*Cw + cw] bit c = (w[o][64cw + c][kh][kw] >= 0).
+__global__ void __launch_bounds__(256)
+pack_conv_weights_kernel(const float* __restrict__ w, int O, int C, int KH, int KW, int Cw,
+                         uint64_t* __restrict__ Wp) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t total = (int64_t)O * KH * KW * Cw;
+  if (idx >= total) return;
+  const int cw = (int)(idx % Cw);
+  const int64_t t = idx / Cw;
+  const int kw = (int)(t % KW);
+  const int kh = (int)((t / KW) % KH);
+  const int64_t o = t / ((int64_t)KW * KH);
+  uint64_t word = 0;
+  for (int c = 0; c < 64; ++c) {
+    const int ch = cw * 64 + c;
+    if (ch < C) {
+      const float v = w[((o * C + ch) * KH + kh) * KW + kw];
+      if (v >= 0.0f) word |= (uint64_t)1 << c;
+    }
+  }
+  Wp[idx] = word;
+}
+
+hipError_t launch_pack_conv_weights(const float* w, int O, int C, int KH, int KW, uint64_t* Wp,
+                                    hipStream_t s) {
+  const int Cw = (int)words_for(C);
+  const int64_t total = (int64_t)O * KH * KW * Cw;
+  hipLaunchKernelGGL(pack_conv_weights_kernel, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, s,
+                     w, O, C, KH, KW, Cw, Wp);
+  return hipGetLastError();
+}
+
+// alpha[r] = mean |w[r][:]|, one workgroup per row, fp64 accumulation.
+__global__ void __launch_bounds__(256)
+alpha_mean_abs_kernel(const float* __restrict__ w, int64_t rows, int64_t cols, int64_t ldw,
+                      float* __restrict__ alpha) {
+  __shared__ double part[256];
+  for (int64_t r = blockIdx.x; r < rows; r += gridDim.x) {
+    double acc = 0.0;
+    for (int64_t j = threadIdx.x; j < cols; j += blockDim.x) acc += fabs((double)w[r * ldw + j]);
+    part[threadIdx.x] = acc;
+    __syncthreads();
+    for (int st = 128; st > 0; st >>= 1) {
+      if ((int)threadIdx.x < st) part[threadIdx.x] += part[threadIdx.x + st];
+      __syncthreads();
+    }
+    if (threadIdx.x == 0) alpha[r] = (float)(part[0] / (double)cols);
+    __syncthreads();
+  }
+}
+
+hipError_t launch_alpha_mean_abs(const float* w, int64_t rows, int64_t cols, int64_t ldw,
+                                 float* alpha, hipStream_t s) {
+  const int64_t blocks = rows < 65535 * 16 ? rows : 65535 * 16;
+  hipLaunchKernelGGL(alpha_mean_abs_kernel, dim3((unsigned)blocks), dim3(256), 0, s, w, rows, cols,
+                     ldw, alpha);
+  return hipGetLastError();
+}
+
+// Eq. 1 quantiser + bit-plane pack.  One wave per row; lane <-> k.  q = round(L * clamp(x)),
+// ties away from zero, from the single fp32 product L * x.  Plane p of word w is the
+// 64-lane mask of bit p of q.  The row sum of q (needed by the plane GEMM epilogue) is
+// accumulated on the fly.
+__global__ void __launch_bounds__(256)
+quant_pack_kernel(const float* __restrict__ a, int64_t M, int64_t K, int64_t lda, int bits,
+                  uint64_t* __restrict__ planes, int32_t* __restrict__ rowsum) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t m = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+  if (m >= M) return;
+  const int64_t Kw = words_for(K);
+  const float L = (float)((1u << bits) - 1u);
+  int32_t sum = 0;
+  for (int64_t w = 0; w < Kw; ++w) {
+    const int64_t k = w * 64 + lane;
+    int q = 0;
+    if (k < K) {
+      float v = a[m * lda + k];
+      v = fminf(fmaxf(v, 0.0f), 1.0f);
+      q = (int)roundf(__fmul_rn(L, v));
+    }
+    sum += q;
+    for (int p = 0; p < bits; ++p) {
+      const uint64_t mask = __ballot((q >> p) & 1);
+      if (lane == 0) planes[((int64_t)p * M + m) * Kw + w] = mask;
+    }
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) sum += __shfl_down(sum, off, kWave);
+  if (lane == 0) rowsum[m] = sum;
+}
+
+hipError_t launch_quant_pack(const float* a, int64_t M, int64_t K, int64_t lda, int bits,
+                             uint64_t* planes, int32_t* rowsum, hipStream_t s) {
+  hipLaunchKernelGGL(quant_pack_kernel, dim3((unsigned)ceil_div(M, 4)), dim3(256), 0, s, a, M, K,
+                     lda, bits, planes, rowsum);
+  return hipGetLastError();
+}
+
+}  // namespace bmx

@@ -1,0 +1,137 @@
+"""Host-side checks of the C-ABI library that need no GPU: the library loads, exports every
+symbol the header declares, and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_1705_09864_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+P = 0x7F0000001000  # a fake, well aligned, never dereferenced device address
+NULL = None
+OK, E_NULL, E_SHAPE, E_LD, E_ALIGN, E_UNSUP, E_WS = 0, -1, -2, -3, -4, -5, -6
+
+
+def test_header_symbols_exported():
+    text = open(os.path.join(ROOT, "include", "bmx.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(bmx_[a-z0-9_]+)\s*\(", text))
+    assert declared == set(B.EXPORTS)
+    L = B.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+    assert B.version() >= 100
+
+
+def test_status_strings():
+    for code in range(-7, 1):
+        assert B.status_string(code).startswith("BMX_")
+    assert "unknown" in B.status_string(-99)
+
+
+def test_workspace_query():
+    assert B.workspace_bytes(B.OP_BINARY_FC, (256, 9216, 4096)) == 256 * 144 * 8
+    assert B.workspace_bytes(B.OP_BINARY_CONV2D, (16, 64, 56, 56, 64, 3, 3, 1, 1)) == 16 * 56 * 56 * 8
+    assert B.workspace_bytes(B.OP_BINARY_CONV2D, (1, 65, 5, 5, 2, 3, 3, 1, 1)) == 512  # 25*2 words -> 400 B
+    q = B.workspace_bytes(B.OP_QUANT_GEMM, (1024, 1024, 4096, 2, 1))
+    assert q == 2 * 1024 * 64 * 8 + 1024 * 64 * 8 + 4096
+    assert B.workspace_bytes(B.OP_QUANT_GEMM, (4, 4, 64, 9, 1)) == 0      # bits_a out of range
+    assert B.workspace_bytes(B.OP_QUANT_GEMM, (4, 4, 64, 2, 2)) == 0      # k-bit weights unsupported
+    assert B.workspace_bytes(B.OP_BINARY_CONV2D, (1, 3, 8, 8, 2, 4, 4, 1, 0)) == 0  # even kernel
+    assert B.workspace_bytes(99, (1, 2, 3)) == 0
+    assert B.workspace_bytes(B.OP_BINARY_FC, (1, 2)) == 0
+
+
+def test_binarize_pack_validation():
+    f = B.lib().bmx_binarize_pack
+    assert f(P, 4, 64, 64, 2, P, 1, NULL) == E_UNSUP
+    assert f(P, -1, 64, 64, 1, P, 1, NULL) == E_SHAPE
+    assert f(P, 4, 0, 64, 1, P, 1, NULL) == E_SHAPE         # K = 0
+    assert f(NULL, 4, 64, 64, 1, P, 1, NULL) == E_NULL
+    assert f(P, 4, 64, 64, 1, NULL, 1, NULL) == E_NULL
+    assert f(P, 4, 65, 64, 1, P, 2, NULL) == E_LD           # ldx < cols
+    assert f(P, 4, 65, 65, 1, P, 1, NULL) == E_LD           # out_ld < ceil(65/64)
+    assert f(P + 2, 4, 64, 64, 1, P, 1, NULL) == E_ALIGN
+    assert f(P, 4, 64, 64, 1, P + 4, 1, NULL) == E_ALIGN
+    assert f(P, 0, 64, 64, 1, P, 1, NULL) == OK             # empty: no launch
+    assert f(P, 64, 0, 1, 0, P, 1, NULL) == OK              # pack_dim 0 with zero columns
+    assert f(P, 1 << 24, 4, 4, 0, P, 1 << 18, NULL) == E_SHAPE  # K too long
+
+
+def test_xnor_gemm_validation():
+    f = B.lib().bmx_xnor_gemm
+    assert f(P, 1, P, 1, P, 8, 4, 8, 0, NULL) == E_SHAPE
+    assert f(P, 1, P, 1, P, 8, -4, 8, 64, NULL) == E_SHAPE
+    assert f(P, 1, P, 1, P, 8, 4, 8, 1 << 24, NULL) == E_SHAPE
+    assert f(NULL, 1, P, 1, P, 8, 4, 8, 64, NULL) == E_NULL
+    assert f(P, 1, P, 1, P, 8, 4, 8, 65, NULL) == E_LD
+    assert f(P, 2, P, 2, P, 7, 4, 8, 65, NULL) == E_LD
+    assert f(P + 4, 2, P, 2, P, 8, 4, 8, 65, NULL) == E_ALIGN
+    assert f(P, 1, P, 1, P, 8, 0, 8, 64, NULL) == OK
+    assert f(P, 1, P, 1, P, 8, 4, 0, 64, NULL) == OK
+
+
+def test_binary_fc_validation():
+    f = B.lib().bmx_binary_fc
+    big = 1 << 20
+    assert f(P, 64, P, 1, NULL, 4, 64, 8, NULL, NULL, 8, P, big, NULL) == E_NULL    # no output
+    assert f(P, 64, P, 1, NULL, 4, 64, 8, P, P, 8, P, big, NULL) == E_NULL          # both outputs
+    assert f(P, 64, P, 1, P, 4, 64, 8, P, NULL, 8, P, big, NULL) == E_UNSUP         # alpha + int out
+    assert f(P, 63, P, 1, NULL, 4, 64, 8, NULL, P, 8, P, big, NULL) == E_LD
+    assert f(P, 64, P, 1, NULL, 4, 64, 8, NULL, P, 7, P, big, NULL) == E_LD
+    assert f(P, 64, P, 1, NULL, 4, 64, 8, NULL, P, 8, NULL, big, NULL) == E_WS
+    assert f(P, 64, P, 1, NULL, 4, 64, 8, NULL, P, 8, P, 16, NULL) == E_WS
+    assert f(P, 64, P, 1, NULL, 4, 64, 8, NULL, P, 8, P + 8, big, NULL) == E_ALIGN
+    assert f(P, 64, P, 1, NULL, 0, 64, 8, NULL, P, 8, P, big, NULL) == OK
+    assert f(P, 64, P, 1, NULL, 4, 0, 8, NULL, P, 8, P, big, NULL) == E_SHAPE
+
+
+def test_conv_validation():
+    f = B.lib().bmx_binary_conv2d
+    big = 1 << 24
+    args = dict(N=2, C=3, H=8, W=8, O=4, KH=3, KW=3, s=1, p=1)
+
+    def call(x=P, Wp=P, alpha=NULL, oi=NULL, of=P, ws=P, wsb=big, **kw):
+        a = dict(args, **kw)
+        return f(x, a["N"], a["C"], a["H"], a["W"], Wp, a["O"], a["KH"], a["KW"], a["s"], a["p"],
+                 alpha, oi, of, ws, wsb, NULL)
+
+    assert call(KH=4, KW=4) == E_UNSUP
+    assert call(KH=3, KW=5) == E_UNSUP
+    assert call(KH=9, KW=9) == E_UNSUP
+    assert call(s=3) == E_UNSUP
+    assert call(p=3) == E_UNSUP
+    assert call(p=-1) == E_UNSUP
+    assert call(C=0) == E_SHAPE
+    assert call(H=1, W=1, p=0) == E_SHAPE          # window larger than the image
+    assert call(x=NULL) == E_NULL
+    assert call(of=NULL) == E_NULL
+    assert call(oi=P, of=P) == E_NULL
+    assert call(oi=P, of=NULL, alpha=P) == E_UNSUP
+    assert call(ws=NULL) == E_WS
+    assert call(wsb=64) == E_WS
+    assert call(N=0) == OK
+    assert call(O=0) == OK
+    g = B.lib().bmx_pack_conv_weights
+    assert g(P, 4, 3, 3, 3, NULL, NULL) == E_NULL
+    assert g(P, 4, 3, 2, 2, P, NULL) == E_UNSUP
+    assert g(P, 0, 3, 3, 3, P, NULL) == OK
+
+
+def test_quant_and_alpha_validation():
+    f = B.lib().bmx_quant_gemm
+    big = 1 << 24
+    assert f(P, 64, 0, P, 64, 1, 4, 4, 64, P, P, 4, P, big, NULL) == E_UNSUP
+    assert f(P, 64, 9, P, 64, 1, 4, 4, 64, P, P, 4, P, big, NULL) == E_UNSUP
+    assert f(P, 64, 2, P, 64, 2, 4, 4, 64, P, P, 4, P, big, NULL) == E_UNSUP
+    assert f(P, 64, 2, P, 64, 1, 4, 4, 64, NULL, NULL, 4, P, big, NULL) == E_NULL
+    assert f(P, 63, 2, P, 64, 1, 4, 4, 64, P, P, 4, P, big, NULL) == E_LD
+    assert f(P, 64, 2, P, 64, 1, 4, 4, 64, P, P, 4, P, 100, NULL) == E_WS
+    assert f(P, 64, 2, P, 64, 1, 0, 4, 64, P, P, 4, P, big, NULL) == OK
+    g = B.lib().bmx_alpha_mean_abs
+    assert g(P, 4, 0, 0, P, NULL) == E_SHAPE
+    assert g(P, 4, 8, 7, P, NULL) == E_LD
+    assert g(NULL, 4, 8, 8, P, NULL) == E_NULL
+    assert g(P, 0, 8, 8, P, NULL) == OK
