@@ -63,7 +63,8 @@ def main():
     ws = torch.empty(B.workspace_bytes(B.OP_BINARY_CONV2D, (N, C, H, W, O, KH, KW, stride, pad)),
                      dtype=torch.uint8, device="cuda")
     out = torch.empty((N, O, Ho, Wo), dtype=torch.float32, device="cuda")
-    xp = ws.view(torch.int64).view(N, H, W, (C + 63) // 64)
+    xp = ws.view(torch.int64)[: N * (H + 2 * pad) * (W + 2 * pad) * ((C + 63) // 64)].view(
+        N, H + 2 * pad, W + 2 * pad, (C + 63) // 64)
 
     def step():
         B.binary_conv2d(x, Wp, O, KH, KW, stride, pad, alpha=alpha, out=out, workspace=ws)
@@ -83,7 +84,7 @@ def main():
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
     for i in range(args.steps):
         ev[i][0].record()
-        B.pack_nchw(x, out=xp)
+        B.pack_nchw(x, pad, out=xp)
         ev[i][1].record()
         B.binary_conv2d_packed(xp, C, Wp, O, KH, KW, stride, pad, alpha=alpha, out=out)
         ev[i][2].record()

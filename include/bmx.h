@@ -46,7 +46,8 @@ extern "C" {
 
 #define BMX_OK 0
 #define BMX_ERR_NULL (-1)        /* a required pointer is NULL */
-#define BMX_ERR_SHAPE (-2)       /* negative size, K <= 0, K >= 2^24, empty conv output */
+#define BMX_ERR_SHAPE (-2)       /* negative size, K <= 0, K >= 2^24, empty conv output, or more
+                                    than 2^31 - 1 output pixels / 65535 images / 2^18 filters */
 #define BMX_ERR_LD (-3)          /* a leading dimension is smaller than the row it must hold */
 #define BMX_ERR_ALIGN (-4)       /* pointer not aligned (packed: 8 bytes, fp32/int32: 4 bytes) */
 #define BMX_ERR_UNSUPPORTED (-5) /* pack_dim, kernel size, stride, bit width outside the contract */
@@ -112,13 +113,15 @@ int bmx_binary_conv2d(const float* x, int N, int C, int H, int W, const uint64_t
                       float* out_f32, void* workspace, size_t workspace_bytes, void* stream);
 
 /* The two stages of bmx_binary_conv2d as separate calls, for callers that keep the packed
- * image (e.g. to feed several convolutions) or time the stages apart.
- * bmx_pack_nchw: the fused im2col + pack step of Sec. 3.1 without the im2col matrix:
- *   xp[n][h][w][cw] bit c = (x[n][64*cw + c][h][w] >= 0), missing channels = 0 bits;
- *   xp holds N*H*W*ceil(C/64) words.
- * bmx_binary_conv2d_packed: the implicit-GEMM stage on such an xp; all other arguments
- *   as for bmx_binary_conv2d (no workspace). */
-int bmx_pack_nchw(const float* x, int N, int C, int H, int W, uint64_t* xp, void* stream);
+ * image (e.g. to feed several convolutions with the same pad) or time the stages apart.
+ * bmx_pack_nchw: the fused im2col + pack step of Sec. 3.1 without the im2col matrix.
+ *   xp is [N][H + 2*pad][W + 2*pad][ceil(C/64)] words; pixel (h, w) sits at row h + pad,
+ *   column w + pad, and bit c of word cw is (x[n][64*cw + c][h][w] >= 0), missing channels
+ *   0 bits.  The halo pixels hold "every real channel = +1" (the sign of the zero padding).
+ *   0 <= pad <= 6.
+ * bmx_binary_conv2d_packed: the implicit-GEMM stage on an xp packed with the same pad; all
+ *   other arguments as for bmx_binary_conv2d (no workspace). */
+int bmx_pack_nchw(const float* x, int N, int C, int H, int W, int pad, uint64_t* xp, void* stream);
 int bmx_binary_conv2d_packed(const uint64_t* xp, int N, int C, int H, int W, const uint64_t* Wp,
                              int O, int KH, int KW, int stride, int pad, const float* alpha,
                              int32_t* out_i32, float* out_f32, void* stream);

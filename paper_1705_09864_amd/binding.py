@@ -51,7 +51,7 @@ def lib():
         L.bmx_status_string.argtypes = [_int]
         L.bmx_status_string.restype = ctypes.c_char_p
         L.bmx_version.restype = _int
-        L.bmx_pack_nchw.argtypes = [_p, _int, _int, _int, _int, _p, _p]
+        L.bmx_pack_nchw.argtypes = [_p, _int, _int, _int, _int, _int, _p, _p]
         L.bmx_binary_conv2d_packed.argtypes = [_p, _int, _int, _int, _int, _p, _int, _int, _int, _int,
                                                _int, _p, _p, _p, _p]
         for name in EXPORTS[:9]:
@@ -164,17 +164,17 @@ def binary_conv2d(x, Wp, O, KH, KW, stride=1, pad=0, alpha=None, integer_out=Fal
     return out
 
 
-def pack_nchw(x, out=None, stream=None):
+def pack_nchw(x, pad=0, out=None, stream=None):
     N, C, H, W = x.shape
     if out is None:
-        out = _u64_as_i64((N, H, W, (C + 63) // 64), x.device)
-    _check(lib().bmx_pack_nchw(_ptr(x), N, C, H, W, _ptr(out), _stream(stream)), "bmx_pack_nchw")
+        out = _u64_as_i64((N, H + 2 * pad, W + 2 * pad, (C + 63) // 64), x.device)
+    _check(lib().bmx_pack_nchw(_ptr(x), N, C, H, W, pad, _ptr(out), _stream(stream)), "bmx_pack_nchw")
     return out
 
 
 def binary_conv2d_packed(xp, C, Wp, O, KH, KW, stride=1, pad=0, alpha=None, integer_out=False,
                          out=None, stream=None):
-    N, H, W, _ = xp.shape
+    N, H, W = xp.shape[0], xp.shape[1] - 2 * pad, xp.shape[2] - 2 * pad
     Ho, Wo = conv_out_hw(H, W, KH, KW, stride, pad)
     if out is None:
         out = torch.empty((N, O, Ho, Wo), dtype=torch.int32 if integer_out else torch.float32,

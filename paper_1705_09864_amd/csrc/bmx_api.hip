@@ -27,6 +27,9 @@ int conv_check(int N, int C, int H, int W, int O, int KH, int KW, int stride, in
   g->Ho = (H + 2 * pad - KH) / stride + 1;
   g->Wo = (W + 2 * pad - KW) / stride + 1;
   g->Cw = (int)bmx::words_for(C);
+  if ((int64_t)N * g->Ho * g->Wo >= ((int64_t)1 << 31) || N > 65535 || O >= (1 << 18))
+    return BMX_ERR_SHAPE;
+  if ((int64_t)(H + 2 * pad) * (W + 2 * pad) >= ((int64_t)1 << 31)) return BMX_ERR_SHAPE;
   return BMX_OK;
 }
 
@@ -46,7 +49,19 @@ QuantWs quant_ws(int64_t M, int64_t N, int64_t K, int bits_a) {
 
 }  // namespace
 
+namespace bmx {
+extern int conv_filters_per_wave;
+}
+
 extern "C" {
+
+// Undeclared tuning hook used by kernel sweeps: key 1 = filters per wave of the stationary
+// convolution kernel (0 restores the automatic choice).
+int bmx_tune_set(int key, int value) {
+  if (key == 1) bmx::conv_filters_per_wave = value;
+  else return BMX_ERR_UNSUPPORTED;
+  return BMX_OK;
+}
 
 int bmx_version(void) { return 100; }
 
@@ -78,7 +93,7 @@ size_t bmx_workspace_bytes(int op, const int64_t* dims, int ndims) {
                      (int)dims[5], (int)dims[6], (int)dims[7], (int)dims[8], &g) != BMX_OK)
         return 0;
       const size_t n = dims[0] > 0 ? (size_t)dims[0] : 1;
-      return round256(n * dims[2] * dims[3] * g.Cw * 8);
+      return round256(n * (dims[2] + 2 * dims[8]) * (dims[3] + 2 * dims[8]) * g.Cw * 8);
     }
     case BMX_OP_QUANT_GEMM: {
       if (ndims != 5 || dims[0] < 0 || dims[1] < 0 || dims[2] <= 0 || dims[2] >= kMaxK) return 0;
@@ -160,15 +175,16 @@ int bmx_pack_conv_weights(const float* w_oihw, int O, int C, int KH, int KW, uin
   return hip_status(bmx::launch_pack_conv_weights(w_oihw, O, C, KH, KW, Wp, (hipStream_t)stream));
 }
 
-int bmx_pack_nchw(const float* x, int N, int C, int H, int W, uint64_t* xp, void* stream) {
+int bmx_pack_nchw(const float* x, int N, int C, int H, int W, int pad, uint64_t* xp, void* stream) {
   if (N < 0 || C <= 0 || H <= 0 || W <= 0) return BMX_ERR_SHAPE;
+  if (pad < 0 || pad > 6) return BMX_ERR_UNSUPPORTED;
+  if (N > 65535 || (int64_t)(H + 2 * pad) * (W + 2 * pad) >= ((int64_t)1 << 31) ||
+      bmx::words_for(C) > 65535)
+    return BMX_ERR_SHAPE;
   if (N == 0) return BMX_OK;
   if (!x || !xp) return BMX_ERR_NULL;
   if (misaligned(x, 4) || misaligned(xp, 8)) return BMX_ERR_ALIGN;
-  const int64_t HW = (int64_t)H * W;
-  // per image a [C][H*W] matrix packed down its rows -> [H*W][Cw]
-  return hip_status(bmx::launch_pack_strided(x, N, C, HW, HW, (int64_t)C * HW, xp,
-                                             bmx::words_for(C), (hipStream_t)stream));
+  return hip_status(bmx::launch_pack_nchw(x, N, C, H, W, pad, xp, (hipStream_t)stream));
 }
 
 int bmx_binary_conv2d_packed(const uint64_t* xp, int N, int C, int H, int W, const uint64_t* Wp,
@@ -206,7 +222,7 @@ int bmx_binary_conv2d(const float* x, int N, int C, int H, int W, const uint64_t
   if (!workspace || workspace_bytes < need) return BMX_ERR_WORKSPACE;
   if (misaligned(workspace, 16)) return BMX_ERR_ALIGN;
   uint64_t* xp = (uint64_t*)workspace;
-  int st = bmx_pack_nchw(x, N, C, H, W, xp, stream);
+  int st = bmx_pack_nchw(x, N, C, H, W, pad, xp, stream);
   if (st != BMX_OK) return st;
   return bmx_binary_conv2d_packed(xp, N, C, H, W, Wp, O, KH, KW, stride, pad, alpha, out_i32,
                                   out_f32, stream);

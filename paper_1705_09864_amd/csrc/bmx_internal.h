@@ -8,6 +8,12 @@
 namespace bmx {
 
 __host__ __device__ static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+// Division of a 32-bit unsigned by a runtime constant as multiply-high + shifts.
+struct FastDiv {
+  uint32_t mul, sh1, sh2;
+};
+FastDiv make_fast_div(uint32_t d);
+
 __host__ __device__ static inline int64_t words_for(int64_t k) { return (k + 63) / 64; }
 
 // pack.hip -------------------------------------------------------------------
@@ -19,6 +25,10 @@ hipError_t launch_pack_rows(const float* x, int64_t rows, int64_t cols, int64_t 
 // matrix stride ncol*out_ld.  Serves pack_dim = 0 and the NCHW channel pack.
 hipError_t launch_pack_strided(const float* x, int64_t batch, int64_t K, int64_t ncol, int64_t ldx,
                                int64_t batch_stride, uint64_t* out, int64_t out_ld, hipStream_t s);
+// NCHW channel pack into the halo-padded layout xp [N][H+2*pad][W+2*pad][Cw]; the halo is
+// filled with the word "all real channels = +1".
+hipError_t launch_pack_nchw(const float* x, int N, int C, int H, int W, int pad, uint64_t* xp,
+                            hipStream_t s);
 hipError_t launch_pack_conv_weights(const float* w, int O, int C, int KH, int KW, uint64_t* Wp,
                                     hipStream_t s);
 hipError_t launch_alpha_mean_abs(const float* w, int64_t rows, int64_t cols, int64_t ldw,
@@ -39,7 +49,7 @@ hipError_t launch_plane_gemm(const uint64_t* planes, int bits, const int32_t* ro
                              int64_t ldo, hipStream_t s);
 
 // conv.hip -------------------------------------------------------------------
-// Implicit-GEMM convolution on the channel-packed image Xp [N][H][W][Cw].
+// Implicit-GEMM convolution on the halo-padded channel-packed image from launch_pack_nchw.
 hipError_t launch_binary_conv2d(const uint64_t* Xp, int N, int C, int H, int W, const uint64_t* Wp,
                                 int O, int KH, int KW, int stride, int pad, const float* alpha,
                                 int32_t* out_i32, float* out_f32, hipStream_t s);

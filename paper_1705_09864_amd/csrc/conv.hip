@@ -1,57 +1,369 @@
-// Implicit-GEMM binary convolution on the channel-packed image (VALU integer bound).
-// Paper: Sec. 3.1 (M = filters, N = batch * output pixels, K = kh * kw * C); the
-// im2col matrix is never formed: each lane gathers its taps from Xp [N][H][W][Cw].
+// Implicit-GEMM binary convolution on the channel-packed, halo-padded image.
+// Paper: Sec. 3.1 (M = filters, N = batch * output pixels, K = kh * kw * C).  The im2col
+// matrix is never formed.
+//
+// Data layout.  The activation pack writes Xp [N][H + 2*pad][W + 2*pad][Cw] uint64, pixel
+// (h, w) at row h + pad, column w + pad.  The halo holds the constant word "every real
+// channel = +1": the float image is zero padded before the sign function and sign(0) = +1,
+// so a padded tap is a +1 for every channel.  With the halo in memory the convolution
+// gathers taps without any bounds test: the address of tap (kh, kw), word cw of output
+// pixel (n, ho, wo) is  base(n, ho, wo) + (kh * Wp + kw) * Cw + cw  with a wave-uniform
+// offset.
+//
+// Kernel shape.  Lanes span 64 consecutive output pixels (flat over n, ho, wo), so the NCHW
+// stores are coalesced.  A lane keeps its whole K (KW uint64 words = taps * Cw) in VGPRs
+// ("B stationary") and the wave streams filter rows past it: the row is wave-uniform, lives
+// in SGPRs (scalar loads) and enters v_xor_b32 as the scalar operand, so the inner loop is
+// nothing but v_xor_b32 + v_bcnt_u32_b32 (the popcount instruction also accumulates).
 #include "bmx_internal.h"
 
 namespace bmx {
 
-// Lanes span output pixels (coalesced NCHW stores), the filter row is wave-uniform.
-// A tap outside the image reads as "all real channels = +1": the float image is zero
-// padded before the sign function and sign(0) = +1.
+namespace {
+
+// q = n / d for 0 <= n < 2^32 by multiply-high (Granlund-Montgomery round-up method).
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, FastDiv f) {
+  const uint32_t t = __umulhi(f.mul, n);
+  return (t + ((n - t) >> f.sh1)) >> f.sh2;
+}
+
+constexpr int kMaxStationaryWords = 36;
+
+struct ConvParams {
+  const uint64_t* Xp;   // halo-padded packed image
+  const uint32_t* Wp;   // [O][KW words] as dwords
+  const float* alpha;   // [O] or null
+  int32_t* out_i32;
+  float* out_f32;
+  int64_t P;            // N * Ho * Wo
+  int O, HoWo, Wo, Hp, Wp_pix, Cw, stride, Kreal, cn;  // cn: filters per wave
+  FastDiv div_howo, div_wo;
+  int off[kMaxStationaryWords];  // word offset of K-word j relative to the pixel base
+};
+
+// Wave-uniform read-only data (filter rows, alpha) is read through the constant address
+// space so that the loads are scalar (s_load into SGPRs) and never occupy vector lanes.
+typedef const uint32_t __attribute__((address_space(4))) * const_u32_ptr;
+typedef const float __attribute__((address_space(4))) * const_f32_ptr;
+
+// A filter row of 2*KW dwords is consumed in NSEG segments of SEG dwords; two SGPR buffers
+// alternate so that the scalar loads of the next segment are in flight while the VALU works
+// through the current one.
+template <int KW>
+struct SegShape {
+  static constexpr int kDwords = 2 * KW;
+  static constexpr int kNseg = (kDwords + 31) / 32;
+  static constexpr int kSeg = kDwords / kNseg;
+  static_assert(kSeg * kNseg == kDwords, "row must split into equal segments");
+};
+
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+
+// SEG dwords of wave-uniform data held in SGPRs, fetched with explicit scalar loads.
+// Scalar loads return out of order, so the only usable wait is lgkmcnt(0); issuing the
+// loads and waiting for them are therefore separate, explicitly placed steps: wait for the
+// current buffer, then issue the next one, then compute.  The loads are written as
+// volatile asm so that the compiler neither tracks them (it would merge both buffers into
+// one wait) nor moves them.
+template <int SEG>
+struct ScalarSeg {
+  static constexpr int n16 = SEG / 16, r16 = SEG % 16;
+  static constexpr int n8 = r16 / 8, r8 = r16 % 8;
+  static constexpr int n4 = r8 / 4, r4 = r8 % 4;
+  static constexpr int n2 = r4 / 2, n1 = r4 % 2;
+  static_assert(n16 <= 1, "segment longer than 31 dwords");
+  u32x16 a16;
+  u32x8 a8;
+  u32x4 a4;
+  u32x2 a2;
+  uint32_t a1;
+
+  // `tie` is an accumulator the following VALU work depends on: threading it through the
+  // first load keeps that work behind the issue point.
+  __device__ __forceinline__ void issue(const_u32_ptr src, int& tie) {
+    asm volatile("" : "+v"(tie));
+    if constexpr (n16) asm volatile("s_load_dwordx16 %0, %1, 0x0" : "=s"(a16) : "s"(src));
+    if constexpr (n8) asm volatile("s_load_dwordx8 %0, %1, %2" : "=s"(a8) : "s"(src), "i"(64 * n16));
+    if constexpr (n4)
+      asm volatile("s_load_dwordx4 %0, %1, %2" : "=s"(a4) : "s"(src), "i"(64 * n16 + 32 * n8));
+    if constexpr (n2)
+      asm volatile("s_load_dwordx2 %0, %1, %2" : "=s"(a2)
+                   : "s"(src), "i"(64 * n16 + 32 * n8 + 16 * n4));
+    if constexpr (n1)
+      asm volatile("s_load_dword %0, %1, %2" : "=s"(a1)
+                   : "s"(src), "i"(64 * n16 + 32 * n8 + 16 * n4 + 8 * n2));
+    asm volatile("" : "+v"(tie));
+  }
+  // All outstanding scalar loads have landed after this; every piece is threaded through
+  // an asm statement so that no use can be placed before the wait.
+  __device__ __forceinline__ void wait() {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if constexpr (n16) asm volatile("" : "+s"(a16));
+    if constexpr (n8) asm volatile("" : "+s"(a8));
+    if constexpr (n4) asm volatile("" : "+s"(a4));
+    if constexpr (n2) asm volatile("" : "+s"(a2));
+    if constexpr (n1) asm volatile("" : "+s"(a1));
+  }
+  template <int J>
+  __device__ __forceinline__ uint32_t get() const {
+    if constexpr (J < 16 * n16) return a16[J];
+    else if constexpr (J < 16 * n16 + 8 * n8) return a8[J - 16 * n16];
+    else if constexpr (J < 16 * n16 + 8 * n8 + 4 * n4) return a4[J - 16 * n16 - 8 * n8];
+    else if constexpr (J < 16 * n16 + 8 * n8 + 4 * n4 + 2 * n2) return a2[J - 16 * n16 - 8 * n8 - 4 * n4];
+    else return a1;
+  }
+};
+
+// FRESH: the segment opens a row, so its first popcount starts the count instead of adding.
+template <int SEG, bool FRESH, int J = 0>
+__device__ __forceinline__ int seg_popcount(const ScalarSeg<SEG>& a, const uint32_t* b, int pc) {
+  if constexpr (J < SEG) {
+    const int c = __builtin_popcount(b[J] ^ a.template get<J>());
+    pc = (FRESH && J == 0) ? c : pc + c;
+    asm volatile("" : "+v"(pc));  // keep the xor / popcount-accumulate chain as written
+    return seg_popcount<SEG, FRESH, J + 1>(a, b, pc);
+  } else {
+    return pc;
+  }
+}
+
+// Rebuild a wave-uniform address from two readfirstlane halves so that it provably lives
+// in SGPRs (64-bit pointer arithmetic is otherwise free to end up on the vector ALU).
+__device__ __forceinline__ uint64_t uniform_addr(uint64_t a) {
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+  return ((uint64_t)hi << 32) | lo;
+}
+
+enum ConvOut { kOutI32 = 0, kOutF32 = 1, kOutF32Alpha = 2 };
+
+template <int KW, int OUT>
 __global__ void __launch_bounds__(256)
-binary_conv2d_kernel(const uint64_t* __restrict__ Xp, int N, int C, int H, int W,
-                     const uint64_t* __restrict__ Wp, int O, int KH, int KW, int stride, int pad,
-                     int Ho, int Wo, int Cw, const float* __restrict__ alpha,
-                     int32_t* __restrict__ out_i32, float* __restrict__ out_f32) {
-  const int64_t P = (int64_t)N * Ho * Wo;
-  const int64_t p = (int64_t)blockIdx.x * 64 + (threadIdx.x & 63);
-  const int o = blockIdx.y * 4 + (threadIdx.x >> 6);
-  if (p >= P || o >= O) return;
-  const int wo = (int)(p % Wo);
-  const int ho = (int)((p / Wo) % Ho);
-  const int n = (int)(p / ((int64_t)Wo * Ho));
-  const uint64_t tail = (C % 64) ? (((uint64_t)1 << (C % 64)) - 1) : ~(uint64_t)0;
-  const uint64_t* wrow = Wp + (int64_t)o * KH * KW * Cw;
+conv_stationary_kernel(const ConvParams p) {
+  constexpr int SEG = SegShape<KW>::kSeg;
+  constexpr int NSEG = SegShape<KW>::kNseg;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t group = (int64_t)blockIdx.x * 4 + wave;  // 64-pixel group
+  const int64_t pix0 = group * 64;
+  if (pix0 >= p.P) return;
+  // Lanes past the last pixel repeat pixel P-1: they compute and store the same values to
+  // the same addresses as the lane that owns it, so no lane is ever masked off.
+  const int64_t pix = min(pix0 + lane, p.P - 1);
+  const uint32_t img = fast_div((uint32_t)pix, p.div_howo);
+  const uint32_t rem = (uint32_t)pix - img * (uint32_t)p.HoWo;
+  const uint32_t ho = fast_div(rem, p.div_wo);
+  const uint32_t wo = rem - ho * (uint32_t)p.Wo;
+  // Per-lane byte offsets are 32-bit and every base is wave-uniform, so loads and stores
+  // use the scalar-base + vector-offset addressing form and need no vector address math.
+  // (The host routes shapes whose packed image or per-wave output span exceed 4 GiB to the
+  // general kernel.)
+  const uint32_t xoff =
+      (((img * (uint32_t)p.Hp + ho * (uint32_t)p.stride) * (uint32_t)p.Wp_pix + wo * (uint32_t)p.stride) *
+       (uint32_t)p.Cw) * 8u;
+  const char* xbase = (const char*)p.Xp;
+  uint32_t b[2 * KW];
+#pragma unroll
+  for (int j = 0; j < KW; ++j) {
+    const uint32_t voff = xoff + (uint32_t)p.off[j] * 8u;  // one 32-bit add per tap
+    const uint64_t v = *(const uint64_t*)(xbase + voff);
+    b[2 * j] = (uint32_t)v;
+    b[2 * j + 1] = (uint32_t)(v >> 32);
+  }
+  const int o0 = blockIdx.y * p.cn;
+  const int nrows = min(p.cn, p.O - o0);
+  const_f32_ptr alpha = (const_f32_ptr)uniform_addr((uint64_t)(uintptr_t)p.alpha + 4 * (int64_t)o0);
+  // Rows o0 .. o0+nrows-1 are one contiguous stream of nrows * NSEG segments.
+  const int nseg_total = nrows * NSEG;
+  const_u32_ptr stream =
+      (const_u32_ptr)uniform_addr((uint64_t)(uintptr_t)p.Wp + (int64_t)o0 * (8 * KW));
+  // output: uniform base of (image of lane 0, filter o0), advanced by one plane per row
+  const uint32_t img0 = __builtin_amdgcn_readfirstlane(img);
+  const uint32_t ooff = ((img - img0) * (uint32_t)p.O * (uint32_t)p.HoWo + rem) * 4u;
+  char* obase = (char*)(OUT == kOutI32 ? (void*)p.out_i32 : (void*)p.out_f32) +
+                ((int64_t)img0 * p.O + o0) * p.HoWo * 4;
+  const int64_t ostride = (int64_t)p.HoWo * 4;
+
+  ScalarSeg<SEG> buf[2];
+  float sc[2] = {1.0f, 1.0f};  // alpha of the row whose last segment sits in buf[k]
   int pc = 0;
-  for (int kh = 0; kh < KH; ++kh) {
-    const int h = ho * stride - pad + kh;
-    for (int kw = 0; kw < KW; ++kw) {
-      const int w = wo * stride - pad + kw;
-      const bool in = (h >= 0 && h < H && w >= 0 && w < W);
-      const uint64_t* xp = Xp + (((int64_t)n * H + h) * W + w) * Cw;
-      const uint64_t* wp = wrow + (kh * KW + kw) * Cw;
-      for (int cw = 0; cw < Cw; ++cw) {
-        const uint64_t ones = (cw == Cw - 1) ? tail : ~(uint64_t)0;
-        const uint64_t xv = in ? xp[cw] : ones;
-        pc += __popcll(xv ^ wp[cw]);
+  asm volatile("" : "+v"(pc));
+  const_u32_ptr src = stream;
+  int left = nseg_total - 1;  // segments after the one at src
+  const_f32_ptr aptr = alpha;  // alpha of the row whose last segment is requested next
+  int rows_left = nrows - 1;   // rows after the one at aptr
+  buf[0].issue(src, pc);
+  if (OUT == kOutF32Alpha && NSEG == 1) asm volatile("s_load_dword %0, %1, 0x0" : "=s"(sc[0]) : "s"(aptr));
+  for (int t = 0; t < nseg_total; t += 2 * NSEG) {  // two rows per trip
+#pragma unroll
+    for (int i = 0; i < 2 * NSEG; ++i) {
+      const int cur = i & 1, nxt = cur ^ 1;
+      const int seg_in_row = i % NSEG;
+      const int row = t / NSEG + i / NSEG;  // row within the wave's range (uniform)
+      buf[cur].wait();
+      if (OUT == kOutF32Alpha) asm volatile("" : "+s"(sc[cur]));
+      // prefetch the following segment; past the end of this wave's stream the last
+      // segment is fetched again, so nothing beyond the weights is ever read
+      src += (left > 0) ? SEG : 0;
+      left -= 1;
+      buf[nxt].issue(src, pc);
+      if (OUT == kOutF32Alpha && (i + 1) % NSEG == NSEG - 1) {
+        // the segment just requested ends a row: fetch that row's alpha with it
+        if (NSEG == 1 || (i + 1) / NSEG > 0 || t > 0) {  // not the very first row
+          aptr = (const_f32_ptr)((uint64_t)aptr + ((rows_left > 0) ? 4u : 0u));
+          rows_left -= 1;
+        }
+        asm volatile("s_load_dword %0, %1, 0x0" : "=s"(sc[nxt]) : "s"(aptr));
+      }
+      if (seg_in_row == 0) pc = seg_popcount<SEG, true>(buf[cur], b, pc);
+      else pc = seg_popcount<SEG, false>(buf[cur], b + seg_in_row * SEG, pc);
+      if (seg_in_row == NSEG - 1) {
+        // The finished count passes through an ordered asm statement: every VALU read of
+        // buf[cur] is thereby issued before the next trip overwrites that buffer.
+        asm volatile("" : "+v"(pc));
+        if (row < nrows) {
+          int dot;  // K - 2 * popcount in one VALU op (both operands are below 2^23)
+          asm("v_mad_i32_i24 %0, %1, -2, %2" : "=v"(dot) : "v"(pc), "s"(p.Kreal));
+          // scalar base + 32-bit lane offset: the store needs no vector address arithmetic
+          if (OUT == kOutF32Alpha) {
+            const float v = sc[cur] * (float)dot;
+            asm volatile("global_store_dword %0, %1, %2" ::"v"(ooff), "v"(v), "s"(obase) : "memory");
+          } else if (OUT == kOutF32) {
+            const float v = (float)dot;
+            asm volatile("global_store_dword %0, %1, %2" ::"v"(ooff), "v"(v), "s"(obase) : "memory");
+          } else {
+            asm volatile("global_store_dword %0, %1, %2" ::"v"(ooff), "v"(dot), "s"(obase) : "memory");
+          }
+        }
+        obase += ostride;
       }
     }
   }
-  const int dot = C * KH * KW - 2 * pc;
-  const int64_t idx = (((int64_t)n * O + o) * Ho + ho) * Wo + wo;
+  // drain the last prefetch before the wave ends
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+}
+
+// General shape: any number of K words, one filter per wave-row, taps addressed with the
+// same halo trick.  Used when K does not fit the stationary kernel.
+__global__ void __launch_bounds__(256)
+conv_general_kernel(const uint64_t* __restrict__ Xp, const uint64_t* __restrict__ Wp,
+                    const float* __restrict__ alpha, int32_t* __restrict__ out_i32,
+                    float* __restrict__ out_f32, int64_t P, int O, int HoWo, int Wo, int Hp,
+                    int Wp_pix, int Cw, int stride, int KH, int KWid, int Kreal, FastDiv div_howo,
+                    FastDiv div_wo) {
+  const int64_t pix = (int64_t)blockIdx.x * 64 + (threadIdx.x & 63);
+  const int o = blockIdx.y * 4 + (threadIdx.x >> 6);
+  if (pix >= P || o >= O) return;
+  const uint32_t img = fast_div((uint32_t)pix, div_howo);
+  const uint32_t rem = (uint32_t)pix - img * (uint32_t)HoWo;
+  const uint32_t ho = fast_div(rem, div_wo);
+  const uint32_t wo = rem - ho * (uint32_t)Wo;
+  const uint64_t* xb = Xp + (((int64_t)img * Hp + ho * stride) * Wp_pix + wo * stride) * Cw;
+  const uint64_t* wrow = Wp + (int64_t)o * KH * KWid * Cw;
+  int pc = 0;
+  for (int kh = 0; kh < KH; ++kh)
+    for (int kw = 0; kw < KWid; ++kw) {
+      const uint64_t* xp = xb + ((int64_t)kh * Wp_pix + kw) * Cw;
+      const uint64_t* wp = wrow + (kh * KWid + kw) * Cw;
+      for (int cw = 0; cw < Cw; ++cw) pc += __popcll(xp[cw] ^ wp[cw]);
+    }
+  const int dot = Kreal - 2 * pc;
+  const int64_t idx = ((int64_t)img * O + o) * HoWo + rem;
   if (out_i32) out_i32[idx] = dot;
   else out_f32[idx] = (alpha ? alpha[o] : 1.0f) * (float)dot;
 }
+
+template <int KW>
+void launch_stationary(const ConvParams& p, int64_t groups, int cblocks, hipStream_t s) {
+  dim3 grid((unsigned)ceil_div(groups, 4), (unsigned)cblocks);
+  if (p.out_f32 && p.alpha)
+    hipLaunchKernelGGL((conv_stationary_kernel<KW, kOutF32Alpha>), grid, dim3(256), 0, s, p);
+  else if (p.out_f32)
+    hipLaunchKernelGGL((conv_stationary_kernel<KW, kOutF32>), grid, dim3(256), 0, s, p);
+  else
+    hipLaunchKernelGGL((conv_stationary_kernel<KW, kOutI32>), grid, dim3(256), 0, s, p);
+}
+
+}  // namespace
+
+FastDiv make_fast_div(uint32_t d) {
+  FastDiv f;
+  uint32_t s = 0;
+  while (((uint64_t)1 << s) < d) ++s;  // s = ceil(log2 d)
+  f.mul = (uint32_t)((((uint64_t)1 << 32) * (((uint64_t)1 << s) - d)) / d + 1);
+  f.sh1 = s < 1 ? s : 1;
+  f.sh2 = s < 1 ? 0 : s - 1;
+  return f;
+}
+
+int conv_filters_per_wave = 0;  // 0 = automatic; settable for tuning sweeps
 
 hipError_t launch_binary_conv2d(const uint64_t* Xp, int N, int C, int H, int W, const uint64_t* Wp,
                                 int O, int KH, int KW, int stride, int pad, const float* alpha,
                                 int32_t* out_i32, float* out_f32, hipStream_t s) {
   const int Ho = (H + 2 * pad - KH) / stride + 1;
   const int Wo = (W + 2 * pad - KW) / stride + 1;
+  const int Cw = (int)words_for(C);
   const int64_t P = (int64_t)N * Ho * Wo;
-  dim3 grid((unsigned)ceil_div(P, 64), (unsigned)ceil_div(O, 4));
-  hipLaunchKernelGGL(binary_conv2d_kernel, grid, dim3(256), 0, s, Xp, N, C, H, W, Wp, O, KH, KW,
-                     stride, pad, Ho, Wo, (int)words_for(C), alpha, out_i32, out_f32);
+  const int Hp = H + 2 * pad, Wpp = W + 2 * pad;
+  const int kwords = KH * KW * Cw;
+  const FastDiv d1 = make_fast_div((uint32_t)(Ho * Wo)), d2 = make_fast_div((uint32_t)Wo);
+  const int64_t groups = ceil_div(P, 64);
+  // the stationary kernel addresses the packed image and a wave's output span with 32-bit
+  // byte offsets from uniform bases
+  const bool fits32 = (int64_t)N * Hp * Wpp * Cw * 8 < ((int64_t)1 << 32) &&
+                      (int64_t)(64 / (Ho * Wo) + 2) * O * Ho * Wo * 4 < ((int64_t)1 << 32);
+  if (fits32 && kwords <= kMaxStationaryWords && (kwords == 1 || kwords == 2 || kwords == 4 || kwords == 9 ||
+                                        kwords == 18 || kwords == 25 || kwords == 27 ||
+                                        kwords == 36)) {
+    ConvParams p;
+    p.Xp = Xp;
+    p.Wp = (const uint32_t*)Wp;
+    p.alpha = alpha;
+    p.out_i32 = out_i32;
+    p.out_f32 = out_f32;
+    p.P = P;
+    p.O = O;
+    p.HoWo = Ho * Wo;
+    p.Wo = Wo;
+    p.Hp = Hp;
+    p.Wp_pix = Wpp;
+    p.Cw = Cw;
+    p.stride = stride;
+    p.Kreal = C * KH * KW;
+    p.div_howo = d1;
+    p.div_wo = d2;
+    for (int j = 0; j < kMaxStationaryWords; ++j) p.off[j] = 0;
+    for (int kh = 0; kh < KH; ++kh)
+      for (int kw = 0; kw < KW; ++kw)
+        for (int cw = 0; cw < Cw; ++cw)
+          p.off[(kh * KW + kw) * Cw + cw] = (kh * Wpp + kw) * Cw + cw;
+    // filters per wave: enough waves to cover the 1024 SIMDs several times over
+    int cn = conv_filters_per_wave;
+    if (cn <= 0) {
+      cn = O;
+      while (cn > 4 && groups * ceil_div(O, cn) < 4096) cn = (cn + 1) / 2;
+    }
+    p.cn = cn;
+    const int cblocks = (int)ceil_div(O, cn);
+    switch (kwords) {
+      case 1: launch_stationary<1>(p, groups, cblocks, s); break;
+      case 2: launch_stationary<2>(p, groups, cblocks, s); break;
+      case 4: launch_stationary<4>(p, groups, cblocks, s); break;
+      case 9: launch_stationary<9>(p, groups, cblocks, s); break;
+      case 18: launch_stationary<18>(p, groups, cblocks, s); break;
+      case 25: launch_stationary<25>(p, groups, cblocks, s); break;
+      case 27: launch_stationary<27>(p, groups, cblocks, s); break;
+      default: launch_stationary<36>(p, groups, cblocks, s); break;
+    }
+    return hipGetLastError();
+  }
+  dim3 grid((unsigned)groups, (unsigned)ceil_div(O, 4));
+  hipLaunchKernelGGL(conv_general_kernel, grid, dim3(256), 0, s, Xp, Wp, alpha, out_i32, out_f32, P,
+                     O, Ho * Wo, Wo, Hp, Wpp, Cw, stride, KH, KW, C * KH * KW, d1, d2);
   return hipGetLastError();
 }
 

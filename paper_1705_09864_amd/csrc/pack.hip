@@ -93,6 +93,73 @@ hipError_t launch_pack_strided(const float* x, int64_t batch, int64_t K, int64_t
   return hipGetLastError();
 }
 
+// NCHW channel pack.  A workgroup packs 64 consecutive pixels of one image for one 64-channel
+// word: lanes span pixels (every load instruction is a coalesced 256-byte read of one
+// channel plane), the four waves take 16 channels each so that a lane has 16 independent
+// loads in flight, and the four 16-bit pieces meet in LDS.  Workgroup 0 of every (image,
+// word) also writes the constant halo words.
+__global__ void __launch_bounds__(256)
+pack_nchw_kernel(const float* __restrict__ x, int C, int HW, int W, int pad, int Hp, int Wp, int Cw,
+                 uint64_t* __restrict__ xp) {
+  __shared__ uint32_t part[4][64];
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int cw = blockIdx.y;
+  const int n = blockIdx.z;
+  const int p = blockIdx.x * 64 + lane;
+  const int pc = p < HW ? p : HW - 1;
+  const int c0 = cw * 64 + wave * 16;
+  const float* xb = x + ((int64_t)n * C + c0) * HW + pc;
+  float v[16];
+#pragma unroll
+  for (int j = 0; j < 16; ++j) v[j] = (c0 + j < C) ? xb[(int64_t)j * HW] : -1.0f;
+  uint32_t bits = 0;
+#pragma unroll
+  for (int j = 0; j < 16; ++j) bits |= (v[j] >= 0.0f ? 1u : 0u) << j;
+  part[wave][lane] = bits;
+  __syncthreads();
+  uint64_t* xpn = xp + (int64_t)n * Hp * Wp * Cw;
+  if (wave == 0 && p < HW) {
+    const uint32_t lo = part[0][lane] | (part[1][lane] << 16);
+    const uint32_t hi = part[2][lane] | (part[3][lane] << 16);
+    const int h = p / W, w = p - h * W;
+    xpn[((int64_t)(h + pad) * Wp + (w + pad)) * Cw + cw] = ((uint64_t)hi << 32) | lo;
+  }
+  if (pad > 0 && blockIdx.x == 0) {
+    const uint64_t ones = (cw == Cw - 1 && (C % 64)) ? (((uint64_t)1 << (C % 64)) - 1) : ~(uint64_t)0;
+    const int H = HW / W;
+    const int nh = Hp * Wp - HW;
+    for (int i = threadIdx.x; i < nh; i += 256) {
+      int hh, ww;
+      if (i < pad * Wp) {
+        hh = i / Wp;
+        ww = i - hh * Wp;
+      } else if (i < 2 * pad * Wp) {
+        const int j = i - pad * Wp;
+        hh = j / Wp;
+        ww = j - hh * Wp;
+        hh += pad + H;
+      } else {
+        const int j = i - 2 * pad * Wp;
+        const int r = j / (2 * pad), c = j - r * (2 * pad);
+        hh = pad + r;
+        ww = c < pad ? c : W + c;
+      }
+      xpn[((int64_t)hh * Wp + ww) * Cw + cw] = ones;
+    }
+  }
+}
+
+hipError_t launch_pack_nchw(const float* x, int N, int C, int H, int W, int pad, uint64_t* xp,
+                            hipStream_t s) {
+  const int Cw = (int)words_for(C);
+  const int HW = H * W;
+  dim3 grid((unsigned)ceil_div(HW, 64), (unsigned)Cw, (unsigned)N);
+  hipLaunchKernelGGL(pack_nchw_kernel, grid, dim3(256), 0, s, x, C, HW, W, pad, H + 2 * pad,
+                     W + 2 * pad, Cw, xp);
+  return hipGetLastError();
+}
+
 // Offline weight packing for the convolution: one thread per output word.
 // Wp[o][(kh*KW + kw)*Cw + cw] bit c = (w[o][64cw + c][kh][kw] >= 0).
 __global__ void __launch_bounds__(256)
