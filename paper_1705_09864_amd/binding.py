@@ -186,11 +186,14 @@ def binary_conv2d_packed(xp, C, Wp, O, KH, KW, stride=1, pad=0, alpha=None, inte
     return out
 
 
-def quant_gemm(a, w, bits_a, bits_w=1, want_int=True, want_float=True, workspace=None, stream=None):
+def quant_gemm(a, w, bits_a, bits_w=1, want_int=True, want_float=True, out_int=None, out_float=None,
+               workspace=None, stream=None):
     M, K = a.shape
     N = w.shape[0]
-    S = torch.empty((M, N), dtype=torch.int32, device=a.device) if want_int else None
-    of = torch.empty((M, N), dtype=torch.float32, device=a.device) if want_float else None
+    S = out_int if out_int is not None else (
+        torch.empty((M, N), dtype=torch.int32, device=a.device) if want_int else None)
+    of = out_float if out_float is not None else (
+        torch.empty((M, N), dtype=torch.float32, device=a.device) if want_float else None)
     ws, ws_bytes = _workspace(OP_QUANT_GEMM, (M, N, K, bits_a, bits_w), a.device, workspace)
     _check(lib().bmx_quant_gemm(_ptr(a), a.stride(0) if M > 1 else K, bits_a, _ptr(w),
                                 w.stride(0) if N > 1 else K, bits_w, M, N, K, _ptr(S), _ptr(of),
