@@ -41,7 +41,7 @@ QuantWs quant_ws(int64_t M, int64_t N, int64_t K, int bits_a) {
   const int64_t Kw = bmx::words_for(K);
   QuantWs q;
   q.planes_off = 0;
-  q.wb_off = round256((size_t)bits_a * M * Kw * 8);
+  q.wb_off = round256((size_t)bits_a * bmx::tiled_bytes(M, K));
   q.rowsum_off = q.wb_off + round256((size_t)N * Kw * 8);
   q.total = q.rowsum_off + round256((size_t)M * 4);
   return q;
@@ -84,7 +84,7 @@ size_t bmx_workspace_bytes(int op, const int64_t* dims, int ndims) {
   switch (op) {
     case BMX_OP_BINARY_FC: {
       if (ndims != 3 || dims[0] < 0 || dims[1] <= 0 || dims[1] >= kMaxK || dims[2] < 0) return 0;
-      return round256((size_t)(dims[0] > 0 ? dims[0] : 1) * bmx::words_for(dims[1]) * 8);
+      return round256((size_t)bmx::tiled_bytes(dims[0] > 0 ? dims[0] : 1, dims[1]));
     }
     case BMX_OP_BINARY_CONV2D: {
       if (ndims != 9) return 0;
@@ -132,8 +132,8 @@ int bmx_xnor_gemm(const uint64_t* A, int64_t lda_w, const uint64_t* B, int64_t l
   const int64_t Kw = bmx::words_for(K);
   if (lda_w < Kw || ldb_w < Kw || ldc < N) return BMX_ERR_LD;
   if (misaligned(A, 8) || misaligned(B, 8) || misaligned(C, 4)) return BMX_ERR_ALIGN;
-  return hip_status(bmx::launch_xnor_gemm(A, lda_w, B, ldb_w, M, N, K, nullptr, C, nullptr, ldc,
-                                          (hipStream_t)stream));
+  return hip_status(bmx::launch_xnor_gemm((const uint32_t*)A, false, lda_w * 2, B, ldb_w, M, N, K,
+                                          nullptr, C, nullptr, ldc, (hipStream_t)stream));
 }
 
 int bmx_binary_fc(const float* x, int64_t ldx, const uint64_t* Wp, int64_t ldw_w,
@@ -156,10 +156,10 @@ int bmx_binary_fc(const float* x, int64_t ldx, const uint64_t* Wp, int64_t ldw_w
   if (!workspace || workspace_bytes < need) return BMX_ERR_WORKSPACE;
   if (misaligned(workspace, 16)) return BMX_ERR_ALIGN;
   hipStream_t s = (hipStream_t)stream;
-  uint64_t* xp = (uint64_t*)workspace;
-  hipError_t e = bmx::launch_pack_rows(x, batch, in_features, ldx, xp, Kw, s);
+  uint32_t* xt = (uint32_t*)workspace;  // activations, packed straight into the row-tiled layout
+  hipError_t e = bmx::launch_pack_rows_tiled(x, batch, in_features, ldx, xt, s);
   if (e != hipSuccess) return BMX_ERR_HIP;
-  return hip_status(bmx::launch_xnor_gemm(xp, Kw, Wp, ldw_w, batch, out_features, in_features,
+  return hip_status(bmx::launch_xnor_gemm(xt, true, 0, Wp, ldw_w, batch, out_features, in_features,
                                           alpha, out_i32, out_f32, ldo, s));
 }
 
@@ -247,7 +247,7 @@ int bmx_quant_gemm(const float* a, int64_t lda, int bits_a, const float* w, int6
   if (misaligned(workspace, 16)) return BMX_ERR_ALIGN;
   hipStream_t s = (hipStream_t)stream;
   char* ws = (char*)workspace;
-  uint64_t* planes = (uint64_t*)(ws + q.planes_off);
+  uint32_t* planes = (uint32_t*)(ws + q.planes_off);
   uint64_t* wb = (uint64_t*)(ws + q.wb_off);
   int32_t* rowsum = (int32_t*)(ws + q.rowsum_off);
   const int64_t Kw = bmx::words_for(K);

@@ -16,6 +16,16 @@ FastDiv make_fast_div(uint32_t d);
 
 __host__ __device__ static inline int64_t words_for(int64_t k) { return (k + 63) / 64; }
 
+// Row-tiled copy of a packed matrix for the scalar side of the GEMM kernel:
+// At[m / 8][kq][m % 8][4] dwords, kq < tiled_kq(K), zero padded in m and k.
+__host__ __device__ static inline int64_t tiled_kq(int64_t K) {
+  const int64_t kq = (2 * words_for(K) + 3) / 4;
+  return (kq + 1) & ~(int64_t)1;
+}
+__host__ __device__ static inline int64_t tiled_bytes(int64_t M, int64_t K) {
+  return ceil_div(M, 8) * tiled_kq(K) * 128;
+}
+
 // pack.hip -------------------------------------------------------------------
 // Row pack: out[r][w] bit j = (x[r*ldx + 64w + j] >= 0), K contiguous in x.
 hipError_t launch_pack_rows(const float* x, int64_t rows, int64_t cols, int64_t ldx, uint64_t* out,
@@ -33,18 +43,23 @@ hipError_t launch_pack_conv_weights(const float* w, int O, int C, int KH, int KW
                                     hipStream_t s);
 hipError_t launch_alpha_mean_abs(const float* w, int64_t rows, int64_t cols, int64_t ldw,
                                  float* alpha, hipStream_t s);
-// Eq. 1 quantise + bit-plane pack: planes[p][m][w], p < bits; rowsum[m] = sum_k q[m][k].
+// Row pack straight into the row-tiled layout At (see tiled_kq above).
+hipError_t launch_pack_rows_tiled(const float* x, int64_t rows, int64_t cols, int64_t ldx,
+                                  uint32_t* At, hipStream_t s);
+// Eq. 1 quantise + bit-plane pack into `bits` row-tiled planes (plane stride
+// tiled_bytes(M, K)); rowsum[m] = sum_k q[m][k].
 hipError_t launch_quant_pack(const float* a, int64_t M, int64_t K, int64_t lda, int bits,
-                             uint64_t* planes, int32_t* rowsum, hipStream_t s);
+                             uint32_t* planes_tiled, int32_t* rowsum, hipStream_t s);
 
 // gemm.hip -------------------------------------------------------------------
 // out = K - 2*popcount(A ^ B); exactly one of C_i32 / C_f32 non-null;
 // C_f32[m][n] = (alpha_n ? alpha_n[n] : 1) * float(dot).
-hipError_t launch_xnor_gemm(const uint64_t* A, int64_t lda_w, const uint64_t* B, int64_t ldb_w,
-                            int M, int N, int K, const float* alpha_n, int32_t* C_i32, float* C_f32,
-                            int64_t ldc, hipStream_t s);
+// A is either row-tiled (a_tiled) or row-major with lda_dw dwords per row.
+hipError_t launch_xnor_gemm(const uint32_t* A, bool a_tiled, int64_t lda_dw, const uint64_t* B,
+                            int64_t ldb_w, int M, int N, int K, const float* alpha_n, int32_t* C_i32,
+                            float* C_f32, int64_t ldc, hipStream_t s);
 // S = 2*sum_p 2^p pc(plane_p & wb) - rowsum; out_f32 = float(S) / float(2^bits - 1).
-hipError_t launch_plane_gemm(const uint64_t* planes, int bits, const int32_t* rowsum,
+hipError_t launch_plane_gemm(const uint32_t* planes_tiled, int bits, const int32_t* rowsum,
                              const uint64_t* Wb, int M, int N, int K, int32_t* S, float* out_f32,
                              int64_t ldo, hipStream_t s);
 

@@ -55,6 +55,49 @@ hipError_t launch_pack_rows(const float* x, int64_t rows, int64_t cols, int64_t 
   return hipGetLastError();
 }
 
+// Row pack into the row-tiled layout At[m/8][kq][m%8][4] read by the scalar side of the
+// GEMM kernel.  Same wave-per-8-words scheme as pack_rows_kernel; rows past the matrix and
+// words past the row are written as zero so that the whole tiled buffer is defined.
+__global__ void __launch_bounds__(256)
+pack_rows_tiled_kernel(const float* __restrict__ x, int64_t rows, int64_t cols, int64_t ldx,
+                       uint32_t* __restrict__ At, int64_t kq_total, int64_t blocks_per_row) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t wave = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+  const int64_t rows8 = ceil_div(rows, 8) * 8;
+  if (wave >= rows8 * blocks_per_row) return;
+  const int64_t r = wave / blocks_per_row;
+  const int64_t b = wave - r * blocks_per_row;
+  const float* xr = x + r * ldx;
+  const int64_t k0 = b * 512 + lane;
+  float v[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int64_t k = k0 + 64 * j;
+    v[j] = (r < rows && k < cols) ? xr[k] : -1.0f;
+  }
+  uint64_t mine = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const uint64_t m = __ballot(v[j] >= 0.0f);
+    if (lane == j) mine = m;
+  }
+  const int64_t w = b * 8 + lane;  // word index in the row; two words per k-quad
+  if (lane < 8 && w < kq_total * 2) {
+    uint32_t* dst = At + (((r >> 3) * kq_total + (w >> 1)) * 8 + (r & 7)) * 4 + (w & 1) * 2;
+    *(uint2*)dst = make_uint2((uint32_t)mine, (uint32_t)(mine >> 32));
+  }
+}
+
+hipError_t launch_pack_rows_tiled(const float* x, int64_t rows, int64_t cols, int64_t ldx,
+                                  uint32_t* At, hipStream_t s) {
+  const int64_t kq = tiled_kq(cols);
+  const int64_t bpr = ceil_div(kq * 2, 8);
+  const int64_t waves = ceil_div(rows, 8) * 8 * bpr;
+  hipLaunchKernelGGL(pack_rows_tiled_kernel, dim3((unsigned)ceil_div(waves, 4)), dim3(256), 0, s, x,
+                     rows, cols, ldx, At, kq, bpr);
+  return hipGetLastError();
+}
+
 // Strided pack: thread <-> column n (coalesced along n for every k), 64 rows of the
 // K dimension folded into one word per thread.
 __global__ void __launch_bounds__(256)
@@ -220,42 +263,46 @@ hipError_t launch_alpha_mean_abs(const float* w, int64_t rows, int64_t cols, int
   return hipGetLastError();
 }
 
-// Eq. 1 quantiser + bit-plane pack.  One wave per row; lane <-> k.  q = round(L * clamp(x)),
-// ties away from zero, from the single fp32 product L * x.  Plane p of word w is the
-// 64-lane mask of bit p of q.  The row sum of q (needed by the plane GEMM epilogue) is
-// accumulated on the fly.
+// Eq. 1 quantiser + bit-plane pack into row-tiled planes.  One wave per row (rows padded
+// to a multiple of 8 are written as zero); lane <-> k.  q = round(L * clamp(x)), ties away
+// from zero, from the single fp32 product L * x.  Plane p of word w is the 64-lane mask of
+// bit p of q.  The row sum of q (needed by the plane GEMM epilogue) is accumulated on the
+// fly.
 __global__ void __launch_bounds__(256)
 quant_pack_kernel(const float* __restrict__ a, int64_t M, int64_t K, int64_t lda, int bits,
-                  uint64_t* __restrict__ planes, int32_t* __restrict__ rowsum) {
+                  uint32_t* __restrict__ planes, int64_t plane_stride_dw, int64_t kq_total,
+                  int32_t* __restrict__ rowsum) {
   const int lane = threadIdx.x & (kWave - 1);
   const int64_t m = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
-  if (m >= M) return;
-  const int64_t Kw = words_for(K);
+  if (m >= ceil_div(M, 8) * 8) return;
   const float L = (float)((1u << bits) - 1u);
   int32_t sum = 0;
-  for (int64_t w = 0; w < Kw; ++w) {
+  for (int64_t w = 0; w < kq_total * 2; ++w) {
     const int64_t k = w * 64 + lane;
     int q = 0;
-    if (k < K) {
+    if (m < M && k < K) {
       float v = a[m * lda + k];
       v = fminf(fmaxf(v, 0.0f), 1.0f);
       q = (int)roundf(__fmul_rn(L, v));
     }
     sum += q;
+    uint32_t* dst = planes + (((m >> 3) * kq_total + (w >> 1)) * 8 + (m & 7)) * 4 + (w & 1) * 2;
     for (int p = 0; p < bits; ++p) {
       const uint64_t mask = __ballot((q >> p) & 1);
-      if (lane == 0) planes[((int64_t)p * M + m) * Kw + w] = mask;
+      if (lane == 0)
+        *(uint2*)(dst + p * plane_stride_dw) = make_uint2((uint32_t)mask, (uint32_t)(mask >> 32));
     }
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) sum += __shfl_down(sum, off, kWave);
-  if (lane == 0) rowsum[m] = sum;
+  if (lane == 0 && m < M) rowsum[m] = sum;
 }
 
 hipError_t launch_quant_pack(const float* a, int64_t M, int64_t K, int64_t lda, int bits,
-                             uint64_t* planes, int32_t* rowsum, hipStream_t s) {
-  hipLaunchKernelGGL(quant_pack_kernel, dim3((unsigned)ceil_div(M, 4)), dim3(256), 0, s, a, M, K,
-                     lda, bits, planes, rowsum);
+                             uint32_t* planes_tiled, int32_t* rowsum, hipStream_t s) {
+  const int64_t rows8 = ceil_div(M, 8) * 8;
+  hipLaunchKernelGGL(quant_pack_kernel, dim3((unsigned)ceil_div(rows8, 4)), dim3(256), 0, s, a, M, K,
+                     lda, bits, planes_tiled, tiled_bytes(M, K) / 4, tiled_kq(K), rowsum);
   return hipGetLastError();
 }
 
