@@ -41,7 +41,7 @@ QuantWs quant_ws(int64_t M, int64_t N, int64_t K, int bits_a) {
   const int64_t Kw = bmx::words_for(K);
   QuantWs q;
   q.planes_off = 0;
-  q.wb_off = round256((size_t)bits_a * bmx::tiled_bytes(M, K));
+  q.wb_off = round256((size_t)bits_a * M * bmx::padded_words(K) * 8);
   q.rowsum_off = q.wb_off + round256((size_t)N * Kw * 8);
   q.total = q.rowsum_off + round256((size_t)M * 4);
   return q;
@@ -51,14 +51,18 @@ QuantWs quant_ws(int64_t M, int64_t N, int64_t K, int bits_a) {
 
 namespace bmx {
 extern int conv_filters_per_wave;
+extern int gemm_tune_rows, gemm_tune_ksplit;
 }
 
 extern "C" {
 
-// Undeclared tuning hook used by kernel sweeps: key 1 = filters per wave of the stationary
-// convolution kernel (0 restores the automatic choice).
+// Undeclared tuning hook used by kernel sweeps (0 restores the automatic choice):
+// key 1 = filters per wave of the stationary convolution kernel, key 2 = rows per wave
+// and key 3 = K-split waves of the GEMM kernel.
 int bmx_tune_set(int key, int value) {
   if (key == 1) bmx::conv_filters_per_wave = value;
+  else if (key == 2) bmx::gemm_tune_rows = value;
+  else if (key == 3) bmx::gemm_tune_ksplit = value;
   else return BMX_ERR_UNSUPPORTED;
   return BMX_OK;
 }
@@ -84,7 +88,7 @@ size_t bmx_workspace_bytes(int op, const int64_t* dims, int ndims) {
   switch (op) {
     case BMX_OP_BINARY_FC: {
       if (ndims != 3 || dims[0] < 0 || dims[1] <= 0 || dims[1] >= kMaxK || dims[2] < 0) return 0;
-      return round256((size_t)bmx::tiled_bytes(dims[0] > 0 ? dims[0] : 1, dims[1]));
+      return round256((size_t)(dims[0] > 0 ? dims[0] : 1) * bmx::padded_words(dims[1]) * 8);
     }
     case BMX_OP_BINARY_CONV2D: {
       if (ndims != 9) return 0;
@@ -156,11 +160,14 @@ int bmx_binary_fc(const float* x, int64_t ldx, const uint64_t* Wp, int64_t ldw_w
   if (!workspace || workspace_bytes < need) return BMX_ERR_WORKSPACE;
   if (misaligned(workspace, 16)) return BMX_ERR_ALIGN;
   hipStream_t s = (hipStream_t)stream;
-  uint32_t* xt = (uint32_t*)workspace;  // activations, packed straight into the row-tiled layout
-  hipError_t e = bmx::launch_pack_rows_tiled(x, batch, in_features, ldx, xt, s);
+  // activations packed into chunk-padded rows: the scalar side of the GEMM kernel
+  uint64_t* xp = (uint64_t*)workspace;
+  const int64_t ldp = bmx::padded_words(in_features);
+  hipError_t e = bmx::launch_pack_rows_padded(x, batch, in_features, ldx, xp, ldp, s);
   if (e != hipSuccess) return BMX_ERR_HIP;
-  return hip_status(bmx::launch_xnor_gemm(xt, true, 0, Wp, ldw_w, batch, out_features, in_features,
-                                          alpha, out_i32, out_f32, ldo, s));
+  return hip_status(bmx::launch_xnor_gemm((const uint32_t*)xp, true, ldp * 2, Wp, ldw_w, batch,
+                                          out_features, in_features, alpha, out_i32, out_f32, ldo,
+                                          s));
 }
 
 int bmx_pack_conv_weights(const float* w_oihw, int O, int C, int KH, int KW, uint64_t* Wp,
@@ -235,6 +242,7 @@ int bmx_quant_gemm(const float* a, int64_t lda, int bits_a, const float* w, int6
   if (K <= 0 || K >= kMaxK) return BMX_ERR_SHAPE;
   if (bits_a < 1 || bits_a > 8 || bits_w != 1) return BMX_ERR_UNSUPPORTED;
   if ((int64_t)K * ((1 << bits_a) - 1) >= ((int64_t)1 << 31)) return BMX_ERR_SHAPE;
+  if ((int64_t)M * bits_a >= ((int64_t)1 << 31)) return BMX_ERR_SHAPE;
   if (M == 0 || N == 0) return BMX_OK;
   if (!a || !w) return BMX_ERR_NULL;
   if (!out_i32_scaled && !out_f32) return BMX_ERR_NULL;
@@ -247,16 +255,17 @@ int bmx_quant_gemm(const float* a, int64_t lda, int bits_a, const float* w, int6
   if (misaligned(workspace, 16)) return BMX_ERR_ALIGN;
   hipStream_t s = (hipStream_t)stream;
   char* ws = (char*)workspace;
-  uint32_t* planes = (uint32_t*)(ws + q.planes_off);
+  uint64_t* planes = (uint64_t*)(ws + q.planes_off);
   uint64_t* wb = (uint64_t*)(ws + q.wb_off);
   int32_t* rowsum = (int32_t*)(ws + q.rowsum_off);
   const int64_t Kw = bmx::words_for(K);
-  hipError_t e = bmx::launch_quant_pack(a, M, K, lda, bits_a, planes, rowsum, s);
+  const int64_t ldp = bmx::padded_words(K);
+  hipError_t e = bmx::launch_quant_pack(a, M, K, lda, bits_a, planes, ldp, rowsum, s);
   if (e != hipSuccess) return BMX_ERR_HIP;
   e = bmx::launch_pack_rows(w, N, K, ldw, wb, Kw, s);
   if (e != hipSuccess) return BMX_ERR_HIP;
-  return hip_status(bmx::launch_plane_gemm(planes, bits_a, rowsum, wb, M, N, K, out_i32_scaled,
-                                           out_f32, ldo, s));
+  return hip_status(bmx::launch_plane_gemm((const uint32_t*)planes, ldp * 2, bits_a, rowsum, wb, Kw,
+                                           M, N, K, out_i32_scaled, out_f32, ldo, s));
 }
 
 int bmx_alpha_mean_abs(const float* w, int64_t rows, int64_t cols, int64_t ldw, float* alpha,

@@ -16,14 +16,10 @@ FastDiv make_fast_div(uint32_t d);
 
 __host__ __device__ static inline int64_t words_for(int64_t k) { return (k + 63) / 64; }
 
-// Row-tiled copy of a packed matrix for the scalar side of the GEMM kernel:
-// At[m / 8][kq][m % 8][4] dwords, kq < tiled_kq(K), zero padded in m and k.
-__host__ __device__ static inline int64_t tiled_kq(int64_t K) {
-  const int64_t kq = (2 * words_for(K) + 3) / 4;
-  return (kq + 1) & ~(int64_t)1;
-}
-__host__ __device__ static inline int64_t tiled_bytes(int64_t M, int64_t K) {
-  return ceil_div(M, 8) * tiled_kq(K) * 128;
+// Packed rows that feed the scalar side of the GEMM kernel are zero padded to whole
+// 32-dword chunks, so that every chunk of a row can be fetched with two 64-byte scalar loads.
+__host__ __device__ static inline int64_t padded_words(int64_t K) {
+  return ceil_div(words_for(K), 16) * 16;
 }
 
 // pack.hip -------------------------------------------------------------------
@@ -43,25 +39,29 @@ hipError_t launch_pack_conv_weights(const float* w, int O, int C, int KH, int KW
                                     hipStream_t s);
 hipError_t launch_alpha_mean_abs(const float* w, int64_t rows, int64_t cols, int64_t ldw,
                                  float* alpha, hipStream_t s);
-// Row pack straight into the row-tiled layout At (see tiled_kq above).
-hipError_t launch_pack_rows_tiled(const float* x, int64_t rows, int64_t cols, int64_t ldx,
-                                  uint32_t* At, hipStream_t s);
-// Eq. 1 quantise + bit-plane pack into `bits` row-tiled planes (plane stride
-// tiled_bytes(M, K)); rowsum[m] = sum_k q[m][k].
+// Row pack into rows of out_ld words where every word up to out_ld is written (zeros past
+// ceil(cols/64)): the chunk-padded activation rows of the FC layer.
+hipError_t launch_pack_rows_padded(const float* x, int64_t rows, int64_t cols, int64_t ldx,
+                                   uint64_t* out, int64_t out_ld, hipStream_t s);
+// Eq. 1 quantise + bit-plane pack: plane p of row m is row m * bits + p of `planes`
+// (row stride ld_words, zero padded to it); rowsum[m] = sum_k q[m][k].
 hipError_t launch_quant_pack(const float* a, int64_t M, int64_t K, int64_t lda, int bits,
-                             uint32_t* planes_tiled, int32_t* rowsum, hipStream_t s);
+                             uint64_t* planes, int64_t ld_words, int32_t* rowsum, hipStream_t s);
 
 // gemm.hip -------------------------------------------------------------------
 // out = K - 2*popcount(A ^ B); exactly one of C_i32 / C_f32 non-null;
 // C_f32[m][n] = (alpha_n ? alpha_n[n] : 1) * float(dot).
-// A is either row-tiled (a_tiled) or row-major with lda_dw dwords per row.
-hipError_t launch_xnor_gemm(const uint32_t* A, bool a_tiled, int64_t lda_dw, const uint64_t* B,
+// A is row-major with lda_dw dwords per row.  a_padded: every row is readable and zero up
+// to a multiple of 32 dwords (workspace copies); otherwise only ceil(K/64) words per row
+// are touched.
+hipError_t launch_xnor_gemm(const uint32_t* A, bool a_padded, int64_t lda_dw, const uint64_t* B,
                             int64_t ldb_w, int M, int N, int K, const float* alpha_n, int32_t* C_i32,
                             float* C_f32, int64_t ldc, hipStream_t s);
 // S = 2*sum_p 2^p pc(plane_p & wb) - rowsum; out_f32 = float(S) / float(2^bits - 1).
-hipError_t launch_plane_gemm(const uint32_t* planes_tiled, int bits, const int32_t* rowsum,
-                             const uint64_t* Wb, int M, int N, int K, int32_t* S, float* out_f32,
-                             int64_t ldo, hipStream_t s);
+// planes_rows as written by launch_quant_pack (lda_dw dwords per row, chunk padded).
+hipError_t launch_plane_gemm(const uint32_t* planes_rows, int64_t lda_dw, int bits,
+                             const int32_t* rowsum, const uint64_t* Wb, int64_t ldb_w, int M, int N,
+                             int K, int32_t* S, float* out_f32, int64_t ldo, hipStream_t s);
 
 // conv.hip -------------------------------------------------------------------
 // Implicit-GEMM convolution on the halo-padded channel-packed image from launch_pack_nchw.

@@ -2,257 +2,302 @@
 // Paper: Sec. 2.2.1 (xnor GEMM on packed words), Sec. 2.2.2 / Eq. 2 (output form), Sec. 2.1
 // Eq. 1 for the bit-plane variant.
 //
-// Shape of the kernel.  C[m][n] = f(sum_k popcount(A[m][k] op B[n][k])).  Lanes span 64
-// consecutive columns n (coalesced C rows); a wave owns 8 rows m.  The 8 A rows are the
-// same for every lane, so they are streamed through SGPRs with scalar loads and feed
-// v_xor_b32 / v_and_b32 as the scalar operand; B rows are staged through LDS in a
-// [k-quad][column] layout so that lane n reads its own row 16 bytes at a time without bank
-// conflicts.  The inner step is 4 k-dwords x 8 rows = 64 VALU ops against 128 bytes of
-// scalar loads and one ds_read_b128.  A workgroup is four waves (32 rows) sharing one B tile.
+// C[m][n] = f(sum_k popcount(A[m][k] op B[n][k])), both operands packed along K.
 //
-// The scalar side wants whole cache lines per request, so A is read from a row-tiled copy
-// At[m/8][k/4][m%8][k%4] (dwords; zero padded in m and k) that the activation pack kernels
-// write directly.  bmx_xnor_gemm, whose A arrives row-major and which has no workspace,
-// uses the second instantiation that fetches 8 x 16 bytes per step instead.
+// Shape of the kernel.  Lanes span 64 consecutive columns n, so C rows are written
+// coalesced.  A lane keeps a 32-dword chunk of its own B row in registers ("B stationary")
+// and the wave streams rows of A past it: an A row chunk is the same for every lane, so it
+// is fetched with two scalar loads into 32 SGPRs and enters v_xor_b32 / v_and_b32 as the
+// scalar source.  One row step is 64 VALU instructions (v_xor + v_bcnt, the popcount
+// instruction also accumulates) against 128 bytes of scalar loads and nothing else; the
+// scalar loads of the next row are in flight while the current one is consumed.  A wave
+// owns R rows (one accumulator register per row) and a contiguous range of K chunks; the S
+// waves of a workgroup split K between them and add their partial counts through LDS at
+// the end.  Splitting K is what gives a skinny problem (a few hundred rows) enough waves
+// to keep four per SIMD, which the VALU needs to issue at full rate.
+//
+// The B chunk of a wave (64 rows x 128 bytes) is read with coalesced 16-byte loads,
+// transposed through a wave-private LDS tile, and prefetched one chunk ahead.
+//
+// Bit planes (k-bit activations): plane p of row m is virtual row m * planes + p of A, so
+// the main loop is unaware of planes; the final reduction weights plane p by 2^p.
 #include "bmx_internal.h"
 #include "scalar_stream.h"
 
 namespace bmx {
 
+int gemm_tune_rows = 0;    // 0 = automatic; otherwise force R (8, 16 or 32)
+int gemm_tune_ksplit = 0;  // 0 = automatic; otherwise force the number of K-split waves
+
 namespace {
 
-constexpr int kTileKq = 16;                    // k-quads (of 4 dwords) per LDS tile
-constexpr int kLdsCols = 65;                   // 64 columns + 1 pad unit against bank conflicts
-constexpr int kTileUnits = kTileKq * kLdsCols;  // 16-byte units per tile buffer
+constexpr int kChunk = 32;  // dwords of K per register chunk
+constexpr int kTRow = 36;   // LDS row stride of the transposition tile (dwords, 16-byte multiple)
+constexpr int kTileDw = 64 * kTRow;
 
 enum GemmOut { kGemmI32 = 0, kGemmF32 = 1, kGemmF32Alpha = 2, kGemmPlanes = 3 };
 
 struct GemmParams {
-  const uint32_t* A;      // tiled: At (see above); row-major: [M][lda] dwords
-  const uint32_t* B;      // [N][ldb] dwords, K contiguous
+  const uint32_t* A;      // [Mv][lda] dwords, virtual rows (row m, plane p -> m * planes + p)
+  const uint32_t* B;      // [N][ldb] dwords
   int64_t lda, ldb;       // dwords
-  int64_t plane_stride;   // dwords between bit planes of At (planes mode)
-  int M, N, Kd;           // Kd = dwords per packed row (even)
-  int kq_total;           // k-quads staged through LDS (covers every dword of a row)
-  int kq_main;            // k-quads the pipelined loop runs over (== kq_total when tiled)
+  int Mv, N;
+  int planes;             // 1 in xor mode
+  int rows_per_block;     // virtual rows per workgroup, a multiple of planes, <= R
+  int nch;                // chunks the main loop covers; A rows are readable up to nch * 32 dwords
+  int Kd;                 // dwords of a B row that may be read (the rest of a chunk reads as 0)
+  int tail0, tail1;       // dword range finished in the epilogue with plain loads (may be empty)
   int Kreal;              // K in bits (xor modes)
-  int planes;             // 1 unless planes mode
   const int32_t* rowsum;  // planes mode: sum_k q[m][k]
   const float* alpha;     // per column n (F32Alpha)
   float levels;           // planes mode: 2^bits - 1
   int32_t* C_i32;
   float* C_f32;
   int64_t ldc;
+  int out;                // GemmOut
 };
 
-// Eight A rows x four k-dwords in SGPRs.
-template <bool TILED>
-struct ABlock;
-
-template <>
-struct ABlock<true> {  // one contiguous 128-byte record of At
+// One 32-dword chunk of an A row in SGPRs.  The loads are volatile asm so that their
+// position relative to the waits is exactly as written.
+struct ARow {
   u32x16 lo, hi;
-  __device__ __forceinline__ void issue(const_u32_ptr rec) {
-    asm volatile("s_load_dwordx16 %0, %1, 0x0" : "=s"(lo) : "s"(rec));
-    asm volatile("s_load_dwordx16 %0, %1, 0x40" : "=s"(hi) : "s"(rec));
+  __device__ __forceinline__ void issue(const_u32_ptr src) {
+    asm volatile("s_load_dwordx16 %0, %1, 0x0" : "=s"(lo) : "s"(src));
+    asm volatile("s_load_dwordx16 %0, %1, 0x40" : "=s"(hi) : "s"(src));
   }
-  __device__ __forceinline__ void tie() {
+  // after s_waitcnt lgkmcnt(0): make every later use depend on this point
+  __device__ __forceinline__ void landed() {
     asm volatile("" : "+s"(lo));
     asm volatile("" : "+s"(hi));
   }
-  template <int R, int J>
+  template <int J>
   __device__ __forceinline__ uint32_t get() const {
-    if constexpr (R < 4) return lo[R * 4 + J];
-    else return hi[(R - 4) * 4 + J];
+    if constexpr (J < 16) return lo[J];
+    else return hi[J - 16];
   }
 };
 
-template <>
-struct ABlock<false> {  // eight 16-byte pieces, one per row-major A row
-  u32x4 r[8];
-  __device__ __forceinline__ void issue(const const_u32_ptr* rows, int kq) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-      asm volatile("s_load_dwordx4 %0, %1, 0x0" : "=s"(r[i]) : "s"(rows[i] + (int64_t)kq * 4));
-  }
-  __device__ __forceinline__ void tie() {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) asm volatile("" : "+s"(r[i]));
-  }
-  template <int R, int J>
-  __device__ __forceinline__ uint32_t get() const {
-    return r[R][J];
-  }
-};
-
-template <bool OP_AND, class AB, int R = 0, int J = 0>
-__device__ __forceinline__ void quad_popcount(const AB& a, const uint32_t (&b)[4], int (&pc)[8]) {
-  if constexpr (R < 8) {
-    const uint32_t av = a.template get<R, J>();
-    pc[R] += __builtin_popcount(OP_AND ? (b[J] & av) : (b[J] ^ av));
-    asm volatile("" : "+v"(pc[R]));  // keep the op / popcount-accumulate pairs as written
-    if constexpr (J < 3) quad_popcount<OP_AND, AB, R, J + 1>(a, b, pc);
-    else quad_popcount<OP_AND, AB, R + 1, 0>(a, b, pc);
+template <bool OP_AND, int J = 0>
+__device__ __forceinline__ void row_popcount(const ARow& a, const uint32_t (&b)[kChunk], int& acc) {
+  if constexpr (J < kChunk) {
+    const uint32_t av = a.template get<J>();
+    acc += __builtin_popcount(OP_AND ? (b[J] & av) : (b[J] ^ av));
+    asm volatile("" : "+v"(acc));  // keep the op / popcount-accumulate pairs as written
+    row_popcount<OP_AND, J + 1>(a, b, acc);
   }
 }
 
-template <bool TILED, bool OP_AND, int OUT>
-__global__ void __launch_bounds__(256)
+// The R row steps of one chunk, unrolled so that every accumulator has a fixed register.
+// Invariant on entry of step r: the loads of row r are in flight in buf[r & 1].
+template <int R, bool OP_AND, int r = 0>
+__device__ __forceinline__ void row_steps(ARow (&buf)[2], const uint32_t (&b)[kChunk], int (&acc)[R],
+                                          const_u32_ptr& src, uint64_t row_bytes, int& rows_valid,
+                                          const_u32_ptr next_chunk_row0) {
+  if constexpr (r < R) {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    buf[r & 1].landed();
+    // Request the next row of this chunk (rows past the block's last valid row repeat
+    // it), or row 0 of the wave's next chunk after the last row.
+    // (the select is kept opaque so that it stays two scalar instructions per row instead
+    // of R loop-invariant values that would not fit the scalar register file)
+    if constexpr (r + 1 < R) {
+      asm volatile("" : "+s"(rows_valid));
+      src = (const_u32_ptr)((uint64_t)src + ((r + 1 < rows_valid) ? row_bytes : (uint64_t)0));
+    } else {
+      src = next_chunk_row0;
+    }
+    buf[(r + 1) & 1].issue(src);
+    row_popcount<OP_AND>(buf[r & 1], b, acc[r]);
+    row_steps<R, OP_AND, r + 1>(buf, b, acc, src, row_bytes, rows_valid, next_chunk_row0);
+  }
+}
+
+template <int R, bool OP_AND>
+__global__ void __launch_bounds__(512, 4)
 gemm_kernel(const GemmParams p) {
-  __shared__ uint4 lds[2][kTileUnits];
+  static_assert(R % 2 == 0, "buffer parity must repeat from chunk to chunk");
+  extern __shared__ __align__(16) uint32_t lds[];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int n = blockIdx.x * 64 + lane;
-  const int m0 = (blockIdx.y * 4 + wave) * 8;  // first row of this wave (may be >= M)
+  const int S = __builtin_amdgcn_readfirstlane((int)(blockDim.x >> 6));
+  const int n0 = blockIdx.x * 64;
+  const int m0 = blockIdx.y * p.rows_per_block;  // first virtual row of the block
+  int rows_valid = min(p.rows_per_block, p.Mv - m0);
+  const int c0 = (int)((int64_t)wave * p.nch / S);
+  const int c1 = (int)((int64_t)(wave + 1) * p.nch / S);
 
-  // ---- B tile loader: thread -> (row within 16, k-quad); four passes cover 64 rows
-  const int ld_kq = tid & 15;
-  const int ld_row = tid >> 4;
-  const uint32_t* brow[4];
+  int acc[R];
 #pragma unroll
-  for (int ps = 0; ps < 4; ++ps) {
-    const int row = min(blockIdx.x * 64 + ps * 16 + ld_row, p.N - 1);
-    brow[ps] = p.B + (int64_t)row * p.ldb;
-  }
-  uint2 stage[4][2];
-  auto fetch_tile = [&](int tile) {
-    const int d0 = (tile * kTileKq + ld_kq) * 4;
-    if ((tile + 1) * kTileKq * 4 <= p.Kd) {  // whole tile inside the rows (wave-uniform)
-#pragma unroll
-      for (int ps = 0; ps < 4; ++ps) {
-        stage[ps][0] = *(const uint2*)(brow[ps] + d0);
-        stage[ps][1] = *(const uint2*)(brow[ps] + d0 + 2);
-      }
-    } else {  // last tile: dwords past the row read as zero
-#pragma unroll
-      for (int ps = 0; ps < 4; ++ps) {
-        stage[ps][0] = (d0 < p.Kd) ? *(const uint2*)(brow[ps] + d0) : make_uint2(0, 0);
-        stage[ps][1] = (d0 + 2 < p.Kd) ? *(const uint2*)(brow[ps] + d0 + 2) : make_uint2(0, 0);
-      }
-    }
-  };
-  auto store_tile = [&](int buf) {
-#pragma unroll
-    for (int ps = 0; ps < 4; ++ps)
-      lds[buf][ld_kq * kLdsCols + ps * 16 + ld_row] =
-          make_uint4(stage[ps][0].x, stage[ps][0].y, stage[ps][1].x, stage[ps][1].y);
-  };
+  for (int r = 0; r < R; ++r) acc[r] = 0;
 
-  // ---- A stream (wave-uniform)
-  const int m8 = min(m0 / 8, (p.M - 1) / 8);  // waves past the last row block repeat it
-  const_u32_ptr arows[8];
-  if constexpr (!TILED) {
+  if (c0 < c1) {
+    // ---- B chunk loader: lane -> (row within 8, 16-byte piece of the 128-byte chunk)
+    const int srow = lane >> 3, spiece = lane & 7;
+    const uint32_t* bsrc[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i)
-      arows[i] = (const_u32_ptr)uniform_addr((uint64_t)(uintptr_t)p.A +
-                                             (int64_t)min(m8 * 8 + i, p.M - 1) * p.lda * 4);
-  }
-
-  int acc[8];
+      bsrc[i] = p.B + (int64_t)min(n0 + i * 8 + srow, p.N - 1) * p.ldb + spiece * 4;
+    uint4 stage[8];
+    auto fetch = [&](int c) {
+      if ((c + 1) * kChunk <= p.Kd) {  // whole chunk inside the rows (wave-uniform)
 #pragma unroll
-  for (int r = 0; r < 8; ++r) acc[r] = 0;
-  const int ntiles = (p.kq_total + kTileKq - 1) / kTileKq;
-
-  for (int plane = 0; plane < p.planes; ++plane) {
-    const_u32_ptr arec = (const_u32_ptr)uniform_addr(
-        (uint64_t)(uintptr_t)p.A + ((int64_t)plane * p.plane_stride + (int64_t)m8 * p.kq_total * 32) * 4);
-    int pc[8];
-#pragma unroll
-    for (int r = 0; r < 8; ++r) {
-      pc[r] = 0;
-      asm volatile("" : "+v"(pc[r]));
-    }
-    ABlock<TILED> ab[2];
-    if (p.kq_main > 0) {
-      if constexpr (TILED) ab[0].issue(arec);
-      else ab[0].issue(arows, 0);
-    }
-    int kq_next = 1;  // global k-quad the next issue fetches
-
-    fetch_tile(0);  // (the barrier closing the previous plane's last tile protects buffer 0)
-    store_tile(0);
-    __syncthreads();
-
-    for (int tile = 0; tile < ntiles; ++tile) {
-      const int buf = tile & 1;
-      const int nkq = min(kTileKq, p.kq_main - tile * kTileKq);
-      if (tile + 1 < ntiles) fetch_tile(tile + 1);
-      uint4 bv[2];
-      bv[0] = lds[buf][lane];
-      for (int s = 0; s < nkq; s += 2) {
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          if (h == 1 && s + 1 >= nkq) break;  // odd tail (row-major A only), wave-uniform
-          const uint32_t b[4] = {bv[h].x, bv[h].y, bv[h].z, bv[h].w};
-          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-          ab[h].tie();
-          // request the next A block and the next B quad, then work on the current ones
-          asm volatile("" : "+v"(pc[0]));
-          const int kqn = min(kq_next, p.kq_main - 1);
-          if constexpr (TILED) ab[h ^ 1].issue(arec + (int64_t)kqn * 32);
-          else ab[h ^ 1].issue(arows, kqn);
-          kq_next += 1;
-          asm volatile("" : "+v"(pc[0]));
-          bv[h ^ 1] = lds[buf][min(s + h + 1, nkq - 1) * kLdsCols + lane];
-          quad_popcount<OP_AND>(ab[h], b, pc);
-        }
-      }
-      if (tile + 1 < ntiles) store_tile(buf ^ 1);
-      __syncthreads();
-    }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    if constexpr (!TILED) {
-      if (p.Kd & 2) {
-        // Row-major A with a trailing half quad: two dwords per row, fetched exactly (a
-        // 16-byte piece would run past the row) against the B quad still held in LDS.
-        const int kq = p.Kd / 4;
-        const uint4 bq = lds[(kq / kTileKq) & 1][(kq % kTileKq) * kLdsCols + lane];
+        for (int i = 0; i < 8; ++i) stage[i] = *(const uint4*)(bsrc[i] + c * kChunk);
+      } else {  // last chunk: dwords past the row read as zero (Kd is even)
+        const int left = p.Kd - (c * kChunk + spiece * 4);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-          const uint32_t a0 = arows[i][kq * 4], a1 = arows[i][kq * 4 + 1];
-          pc[i] += __builtin_popcount(OP_AND ? (bq.x & a0) : (bq.x ^ a0)) +
-                   __builtin_popcount(OP_AND ? (bq.y & a1) : (bq.y ^ a1));
+          uint4 v = make_uint4(0, 0, 0, 0);
+          if (left >= 4) {
+            v = *(const uint4*)(bsrc[i] + c * kChunk);
+          } else if (left >= 2) {
+            const uint2 h = *(const uint2*)(bsrc[i] + c * kChunk);
+            v.x = h.x;
+            v.y = h.y;
+          }
+          stage[i] = v;
         }
       }
-    }
+    };
+    uint32_t* tile = lds + wave * kTileDw;
+
+    // ---- A stream (wave-uniform addresses)
+    const uint64_t row_bytes = (uint64_t)p.lda * 4;
+    const uint64_t arow0 = uniform_addr((uint64_t)(uintptr_t)p.A + (int64_t)m0 * p.lda * 4);
+    ARow buf[2];
+    const_u32_ptr src = (const_u32_ptr)(arow0 + (uint64_t)c0 * (kChunk * 4));
+    buf[0].issue(src);
+    fetch(c0);
+    for (int c = c0; c < c1; ++c) {
+      // transpose the staged chunk: row n of the tile is lane n's 32 dwords
 #pragma unroll
-    for (int r = 0; r < 8; ++r) acc[r] += pc[r] << plane;
+      for (int i = 0; i < 8; ++i) *(uint4*)(tile + (i * 8 + srow) * kTRow + spiece * 4) = stage[i];
+      uint32_t b[kChunk];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const uint4 v = *(const uint4*)(tile + lane * kTRow + j * 4);
+        b[4 * j] = v.x;
+        b[4 * j + 1] = v.y;
+        b[4 * j + 2] = v.z;
+        b[4 * j + 3] = v.w;
+      }
+      if (c + 1 < c1) fetch(c + 1);
+      const int cn = min(c + 1, c1 - 1);  // after the last chunk the last row 0 is fetched again
+      const const_u32_ptr next_row0 = (const_u32_ptr)(arow0 + (uint64_t)cn * (kChunk * 4));
+      row_steps<R, OP_AND>(buf, b, acc, src, row_bytes, rows_valid, next_row0);
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // drain the last prefetch
   }
 
-  // ---- epilogue: lanes write 64 consecutive columns of each of the wave's rows
-  if (n < p.N) {
-    float al = 1.0f;
-    if (OUT == kGemmF32Alpha) al = p.alpha[n];
+  // ---- add the S partial counts of every (row, column) through LDS
+  __syncthreads();  // every wave is done with its transposition tile
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {
-      const int m = m0 + r;
-      if (m < p.M) {
-        const int64_t idx = (int64_t)m * p.ldc + n;
-        if (OUT == kGemmPlanes) {
-          const int sv = 2 * acc[r] - p.rowsum[m];
-          if (p.C_i32) p.C_i32[idx] = sv;
-          if (p.C_f32) p.C_f32[idx] = (float)sv / p.levels;
-        } else {
-          const int dot = p.Kreal - 2 * acc[r];
-          if (OUT == kGemmI32) p.C_i32[idx] = dot;
-          else if (OUT == kGemmF32) p.C_f32[idx] = (float)dot;
-          else p.C_f32[idx] = al * (float)dot;
+  for (int r = 0; r < R; ++r) lds[(wave * R + r) * 64 + lane] = (uint32_t)acc[r];
+  __syncthreads();
+
+  const int n = n0 + lane;
+  const int nc = min(n, p.N - 1);
+  const int rows_out = rows_valid / p.planes;
+  const int64_t mbase = m0 / p.planes;
+  float al = 1.0f;
+  if (p.out == kGemmF32Alpha) al = p.alpha[nc];
+  for (int rr = wave; rr < rows_out; rr += S) {
+    int total = 0;
+    for (int pl = 0; pl < p.planes; ++pl) {
+      const int v = rr * p.planes + pl;
+      int t = 0;
+      for (int s = 0; s < S; ++s) t += (int)lds[(s * R + v) * 64 + lane];
+      if (p.tail0 < p.tail1) {
+        // K words outside the chunked range (row-major A that may not be read past its
+        // last word): plain loads, two dwords per step
+        const uint32_t* ar = p.A + (int64_t)(m0 + v) * p.lda;
+        const uint32_t* br = p.B + (int64_t)nc * p.ldb;
+        for (int d = p.tail0; d < p.tail1; d += 2) {
+          const uint2 av = *(const uint2*)(ar + d);
+          const uint2 bv = *(const uint2*)(br + d);
+          t += __builtin_popcount(OP_AND ? (av.x & bv.x) : (av.x ^ bv.x)) +
+               __builtin_popcount(OP_AND ? (av.y & bv.y) : (av.y ^ bv.y));
         }
+      }
+      total += t << pl;
+    }
+    if (n < p.N) {
+      const int64_t m = mbase + rr;
+      const int64_t idx = m * p.ldc + n;
+      if (p.out == kGemmPlanes) {
+        const int sv = 2 * total - p.rowsum[m];
+        if (p.C_i32) p.C_i32[idx] = sv;
+        if (p.C_f32) p.C_f32[idx] = (float)sv / p.levels;
+      } else {
+        const int dot = p.Kreal - 2 * total;
+        if (p.out == kGemmI32) p.C_i32[idx] = dot;
+        else if (p.out == kGemmF32) p.C_f32[idx] = (float)dot;
+        else p.C_f32[idx] = al * (float)dot;
       }
     }
   }
 }
 
-template <bool TILED, bool OP_AND, int OUT>
-void launch(const GemmParams& p, hipStream_t s) {
-  dim3 grid((unsigned)ceil_div(p.N, 64), (unsigned)ceil_div(p.M, 32));
-  hipLaunchKernelGGL((gemm_kernel<TILED, OP_AND, OUT>), grid, dim3(256), 0, s, p);
+template <int R, bool OP_AND>
+void launch_rs(const GemmParams& p, int S, hipStream_t s) {
+  auto kern = gemm_kernel<R, OP_AND>;
+  const size_t lds_bytes = (size_t)S * (kTileDw > R * 64 ? kTileDw : R * 64) * 4;
+  static bool raised = false;  // more than the default 64 KiB of dynamic LDS for S = 8
+  if (!raised) {
+    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+    raised = true;
+  }
+  dim3 grid((unsigned)ceil_div(p.N, 64), (unsigned)ceil_div(p.Mv, p.rows_per_block));
+  hipLaunchKernelGGL(kern, grid, dim3(64 * S), lds_bytes, s, p);
+}
+
+// Rows per wave and K split.  A wave's work is (chunks per wave) x (R row steps + a fixed
+// per-chunk cost); the grid should put at least four waves on each of the 1024 SIMDs and
+// come out close to a whole number of waves per SIMD.
+void choose_shape(const GemmParams& p, int& R_out, int& S_out) {
+  static const double eff[5] = {0.0, 0.71, 0.88, 0.93, 0.96};  // VALU issue rate vs waves per SIMD
+  double best = 1e300;
+  R_out = 32;
+  S_out = 1;
+  for (int R : {32, 16, 8}) {
+    if (R < p.planes) continue;
+    const int rpb = (R / p.planes) * p.planes;
+    const int64_t blocks = ceil_div(p.N, 64) * ceil_div(p.Mv, rpb);
+    const int smax = p.nch < 8 ? (p.nch > 0 ? p.nch : 1) : 8;
+    for (int S = 1; S <= smax; ++S) {
+      const int64_t waves = blocks * S;
+      const double per_wave = (double)ceil_div(p.nch > 0 ? p.nch : 1, S) * (R + 3) + 0.5 * R + 2.0 * S;
+      const int64_t per_simd = ceil_div(waves, 1024);
+      const double t = (double)per_simd * per_wave / eff[per_simd < 4 ? per_simd : 4];
+      if (t < best * 0.999) {
+        best = t;
+        R_out = R;
+        S_out = S;
+      }
+    }
+  }
+  if (gemm_tune_rows == 8 || gemm_tune_rows == 16 || gemm_tune_rows == 32) {
+    if (gemm_tune_rows >= p.planes) R_out = gemm_tune_rows;
+  }
+  if (gemm_tune_ksplit > 0) {
+    S_out = gemm_tune_ksplit < 8 ? gemm_tune_ksplit : 8;
+    if (S_out > p.nch) S_out = p.nch > 0 ? p.nch : 1;
+  }
+}
+
+template <bool OP_AND>
+void launch(GemmParams& p, hipStream_t s) {
+  int R, S;
+  choose_shape(p, R, S);
+  p.rows_per_block = (R / p.planes) * p.planes;
+  if (R == 32) launch_rs<32, OP_AND>(p, S, s);
+  else if (R == 16) launch_rs<16, OP_AND>(p, S, s);
+  else launch_rs<8, OP_AND>(p, S, s);
 }
 
 }  // namespace
 
-hipError_t launch_xnor_gemm(const uint32_t* A, bool a_tiled, int64_t lda_dw, const uint64_t* B,
+hipError_t launch_xnor_gemm(const uint32_t* A, bool a_padded, int64_t lda_dw, const uint64_t* B,
                             int64_t ldb_w, int M, int N, int K, const float* alpha_n, int32_t* C_i32,
                             float* C_f32, int64_t ldc, hipStream_t s) {
   GemmParams p;
@@ -260,56 +305,53 @@ hipError_t launch_xnor_gemm(const uint32_t* A, bool a_tiled, int64_t lda_dw, con
   p.B = (const uint32_t*)B;
   p.lda = lda_dw;
   p.ldb = ldb_w * 2;
-  p.plane_stride = 0;
-  p.M = M;
+  p.Mv = M;
   p.N = N;
+  p.planes = 1;
   p.Kd = (int)(2 * words_for(K));
   p.Kreal = K;
-  p.planes = 1;
   p.rowsum = nullptr;
   p.alpha = alpha_n;
   p.levels = 1.0f;
   p.C_i32 = C_i32;
   p.C_f32 = C_f32;
   p.ldc = ldc;
-  if (a_tiled) {
-    p.kq_total = p.kq_main = (int)tiled_kq(K);
-    if (C_i32) launch<true, false, kGemmI32>(p, s);
-    else if (alpha_n) launch<true, false, kGemmF32Alpha>(p, s);
-    else launch<true, false, kGemmF32>(p, s);
-  } else {
-    // whole k-quads in the pipelined loop; a trailing half quad gets its own exact step
-    p.kq_total = (p.Kd + 3) / 4;
-    p.kq_main = p.Kd / 4;
-    if (C_i32) launch<false, false, kGemmI32>(p, s);
-    else if (alpha_n) launch<false, false, kGemmF32Alpha>(p, s);
-    else launch<false, false, kGemmF32>(p, s);
+  p.out = C_i32 ? kGemmI32 : (alpha_n ? kGemmF32Alpha : kGemmF32);
+  if (a_padded) {  // A rows are zero padded to whole chunks: everything runs in the main loop
+    p.nch = (int)ceil_div(p.Kd, kChunk);
+    p.tail0 = p.tail1 = 0;
+  } else {  // whole chunks in the main loop, the remaining words in the epilogue
+    p.nch = p.Kd / kChunk;
+    p.tail0 = p.nch * kChunk;
+    p.tail1 = p.Kd;
   }
+  launch<false>(p, s);
   return hipGetLastError();
 }
 
-hipError_t launch_plane_gemm(const uint32_t* planes_tiled, int bits, const int32_t* rowsum,
-                             const uint64_t* Wb, int M, int N, int K, int32_t* S, float* out_f32,
-                             int64_t ldo, hipStream_t s) {
+hipError_t launch_plane_gemm(const uint32_t* planes_rows, int64_t lda_dw, int bits,
+                             const int32_t* rowsum, const uint64_t* Wb, int64_t ldb_w, int M, int N,
+                             int K, int32_t* S, float* out_f32, int64_t ldo, hipStream_t s) {
   GemmParams p;
-  p.A = planes_tiled;
+  p.A = planes_rows;
   p.B = (const uint32_t*)Wb;
-  p.lda = 0;
-  p.ldb = 2 * words_for(K);
-  p.plane_stride = tiled_bytes(M, K) / 4;
-  p.M = M;
+  p.lda = lda_dw;
+  p.ldb = ldb_w * 2;
+  p.Mv = M * bits;
   p.N = N;
-  p.Kd = (int)(2 * words_for(K));
-  p.kq_total = p.kq_main = (int)tiled_kq(K);
-  p.Kreal = K;
   p.planes = bits;
+  p.Kd = (int)(2 * words_for(K));
+  p.nch = (int)ceil_div(p.Kd, kChunk);
+  p.tail0 = p.tail1 = 0;
+  p.Kreal = K;
   p.rowsum = rowsum;
   p.alpha = nullptr;
   p.levels = (float)((1u << bits) - 1u);
   p.C_i32 = S;
   p.C_f32 = out_f32;
   p.ldc = ldo;
-  launch<true, true, kGemmPlanes>(p, s);
+  p.out = kGemmPlanes;
+  launch<true>(p, s);
   return hipGetLastError();
 }
 

@@ -55,46 +55,14 @@ hipError_t launch_pack_rows(const float* x, int64_t rows, int64_t cols, int64_t 
   return hipGetLastError();
 }
 
-// Row pack into the row-tiled layout At[m/8][kq][m%8][4] read by the scalar side of the
-// GEMM kernel.  Same wave-per-8-words scheme as pack_rows_kernel; rows past the matrix and
-// words past the row are written as zero so that the whole tiled buffer is defined.
-__global__ void __launch_bounds__(256)
-pack_rows_tiled_kernel(const float* __restrict__ x, int64_t rows, int64_t cols, int64_t ldx,
-                       uint32_t* __restrict__ At, int64_t kq_total, int64_t blocks_per_row) {
-  const int lane = threadIdx.x & (kWave - 1);
-  const int64_t wave = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
-  const int64_t rows8 = ceil_div(rows, 8) * 8;
-  if (wave >= rows8 * blocks_per_row) return;
-  const int64_t r = wave / blocks_per_row;
-  const int64_t b = wave - r * blocks_per_row;
-  const float* xr = x + r * ldx;
-  const int64_t k0 = b * 512 + lane;
-  float v[8];
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const int64_t k = k0 + 64 * j;
-    v[j] = (r < rows && k < cols) ? xr[k] : -1.0f;
-  }
-  uint64_t mine = 0;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const uint64_t m = __ballot(v[j] >= 0.0f);
-    if (lane == j) mine = m;
-  }
-  const int64_t w = b * 8 + lane;  // word index in the row; two words per k-quad
-  if (lane < 8 && w < kq_total * 2) {
-    uint32_t* dst = At + (((r >> 3) * kq_total + (w >> 1)) * 8 + (r & 7)) * 4 + (w & 1) * 2;
-    *(uint2*)dst = make_uint2((uint32_t)mine, (uint32_t)(mine >> 32));
-  }
-}
-
-hipError_t launch_pack_rows_tiled(const float* x, int64_t rows, int64_t cols, int64_t ldx,
-                                  uint32_t* At, hipStream_t s) {
-  const int64_t kq = tiled_kq(cols);
-  const int64_t bpr = ceil_div(kq * 2, 8);
-  const int64_t waves = ceil_div(rows, 8) * 8 * bpr;
-  hipLaunchKernelGGL(pack_rows_tiled_kernel, dim3((unsigned)ceil_div(waves, 4)), dim3(256), 0, s, x,
-                     rows, cols, ldx, At, kq, bpr);
+// Row pack into rows of out_ld words, writing every word of a row (zeros past the last
+// data word): the chunk-padded activation rows read by the scalar side of the GEMM kernel.
+hipError_t launch_pack_rows_padded(const float* x, int64_t rows, int64_t cols, int64_t ldx,
+                                   uint64_t* out, int64_t out_ld, hipStream_t s) {
+  const int64_t bpr = ceil_div(out_ld, 8);
+  const int64_t waves = rows * bpr;
+  hipLaunchKernelGGL(pack_rows_kernel, dim3((unsigned)ceil_div(waves, 4)), dim3(256), 0, s, x, rows,
+                     cols, ldx, out, out_ld, out_ld, bpr);
   return hipGetLastError();
 }
 
@@ -263,46 +231,57 @@ hipError_t launch_alpha_mean_abs(const float* w, int64_t rows, int64_t cols, int
   return hipGetLastError();
 }
 
-// Eq. 1 quantiser + bit-plane pack into row-tiled planes.  One wave per row (rows padded
-// to a multiple of 8 are written as zero); lane <-> k.  q = round(L * clamp(x)), ties away
-// from zero, from the single fp32 product L * x.  Plane p of word w is the 64-lane mask of
-// bit p of q.  The row sum of q (needed by the plane GEMM epilogue) is accumulated on the
-// fly.
+// Eq. 1 quantiser + bit-plane pack.  One workgroup per row m, lane <-> k: the four waves
+// take every fourth group of 8 words, so a lane has 8 independent loads in flight.
+// q = round(L * clamp(x)), ties away from zero, from the single fp32 product L * x.  Plane p
+// of word w is the 64-lane mask of bit p of q and goes to row m * bits + p of `planes`
+// (words up to ld_words are written, zeros past the data).  The row sum of q, needed by the
+// plane GEMM epilogue, is reduced through LDS.
 __global__ void __launch_bounds__(256)
 quant_pack_kernel(const float* __restrict__ a, int64_t M, int64_t K, int64_t lda, int bits,
-                  uint32_t* __restrict__ planes, int64_t plane_stride_dw, int64_t kq_total,
-                  int32_t* __restrict__ rowsum) {
+                  uint64_t* __restrict__ planes, int64_t ld_words, int32_t* __restrict__ rowsum) {
+  __shared__ int32_t part[4];
   const int lane = threadIdx.x & (kWave - 1);
-  const int64_t m = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
-  if (m >= ceil_div(M, 8) * 8) return;
+  const int wave = threadIdx.x / kWave;
+  const int64_t m = blockIdx.x;
   const float L = (float)((1u << bits) - 1u);
+  const float* ar = a + m * lda;
+  uint64_t* prow = planes + m * bits * ld_words;
   int32_t sum = 0;
-  for (int64_t w = 0; w < kq_total * 2; ++w) {
-    const int64_t k = w * 64 + lane;
-    int q = 0;
-    if (m < M && k < K) {
-      float v = a[m * lda + k];
-      v = fminf(fmaxf(v, 0.0f), 1.0f);
-      q = (int)roundf(__fmul_rn(L, v));
+  for (int64_t w0 = (int64_t)wave * 8; w0 < ld_words; w0 += 32) {
+    float v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int64_t k = (w0 + j) * 64 + lane;
+      v[j] = (k < K) ? ar[k] : 0.0f;
     }
-    sum += q;
-    uint32_t* dst = planes + (((m >> 3) * kq_total + (w >> 1)) * 8 + (m & 7)) * 4 + (w & 1) * 2;
+    int q[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      q[j] = (int)roundf(__fmul_rn(L, fminf(fmaxf(v[j], 0.0f), 1.0f)));
+      sum += q[j];
+    }
     for (int p = 0; p < bits; ++p) {
-      const uint64_t mask = __ballot((q >> p) & 1);
-      if (lane == 0)
-        *(uint2*)(dst + p * plane_stride_dw) = make_uint2((uint32_t)mask, (uint32_t)(mask >> 32));
+      uint64_t mine = 0;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const uint64_t mask = __ballot((q[j] >> p) & 1);
+        if (lane == j) mine = mask;
+      }
+      if (lane < 8 && w0 + lane < ld_words) prow[p * ld_words + w0 + lane] = mine;
     }
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) sum += __shfl_down(sum, off, kWave);
-  if (lane == 0 && m < M) rowsum[m] = sum;
+  if (lane == 0) part[wave] = sum;
+  __syncthreads();
+  if (threadIdx.x == 0) rowsum[m] = part[0] + part[1] + part[2] + part[3];
 }
 
 hipError_t launch_quant_pack(const float* a, int64_t M, int64_t K, int64_t lda, int bits,
-                             uint32_t* planes_tiled, int32_t* rowsum, hipStream_t s) {
-  const int64_t rows8 = ceil_div(M, 8) * 8;
-  hipLaunchKernelGGL(quant_pack_kernel, dim3((unsigned)ceil_div(rows8, 4)), dim3(256), 0, s, a, M, K,
-                     lda, bits, planes_tiled, tiled_bytes(M, K) / 4, tiled_kq(K), rowsum);
+                             uint64_t* planes, int64_t ld_words, int32_t* rowsum, hipStream_t s) {
+  hipLaunchKernelGGL(quant_pack_kernel, dim3((unsigned)M), dim3(256), 0, s, a, M, K, lda, bits,
+                     planes, ld_words, rowsum);
   return hipGetLastError();
 }
 

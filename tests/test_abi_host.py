@@ -33,11 +33,11 @@ def test_status_strings():
 
 def test_workspace_query():
     assert B.workspace_bytes(B.OP_BINARY_FC, (256, 9216, 4096)) == 256 * 144 * 8
-    assert B.workspace_bytes(B.OP_BINARY_FC, (5, 65, 3)) == 256  # 1 row block x 2 quads x 128 B
+    assert B.workspace_bytes(B.OP_BINARY_FC, (5, 65, 3)) == 5 * 16 * 8 + 128  # 5 rows padded to 16 words, rounded up to 256 B
     assert B.workspace_bytes(B.OP_BINARY_CONV2D, (16, 64, 56, 56, 64, 3, 3, 1, 1)) == 16 * 58 * 58 * 8
     assert B.workspace_bytes(B.OP_BINARY_CONV2D, (1, 65, 5, 5, 2, 3, 3, 1, 1)) == 1024  # 49*2 words -> 784 B
     q = B.workspace_bytes(B.OP_QUANT_GEMM, (1024, 1024, 4096, 2, 1))
-    assert q == 2 * 1024 * 64 * 8 + 1024 * 64 * 8 + 4096  # tiled planes take no extra space here
+    assert q == 2 * 1024 * 64 * 8 + 1024 * 64 * 8 + 4096  # plane rows, weight bits, row sums
     assert B.workspace_bytes(B.OP_QUANT_GEMM, (4, 4, 64, 9, 1)) == 0      # bits_a out of range
     assert B.workspace_bytes(B.OP_QUANT_GEMM, (4, 4, 64, 2, 2)) == 0      # k-bit weights unsupported
     assert B.workspace_bytes(B.OP_BINARY_CONV2D, (1, 3, 8, 8, 2, 4, 4, 1, 0)) == 0  # even kernel
