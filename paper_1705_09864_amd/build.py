@@ -23,8 +23,30 @@ def _stale(out, deps):
     return any(os.path.getmtime(d) > t for d in deps)
 
 
+def device_asm(src):
+    """Path of the gfx950 assembly that -save-temps leaves next to the object of `src`."""
+    return os.path.join(BUILD, os.path.splitext(src)[0] + "-hip-amdgcn-amd-amdhsa-gfx950.s")
+
+
+def check_scalar_loads():
+    """Scan the compiled device code of every source for registers of a hand-placed scalar
+    load that are touched while the load is still in flight (see isa_check.py)."""
+    from . import isa_check
+    for src in SOURCES:
+        path = device_asm(src)
+        s = os.path.join(CSRC, src)
+        if _stale(path, [s]):  # e.g. a fresh checkout: emit the device assembly alone
+            os.makedirs(BUILD, exist_ok=True)
+            subprocess.check_call([HIPCC] + FLAGS + ["-S", "--cuda-device-only", s, "-o", path],
+                                  stderr=subprocess.DEVNULL)
+        bad = isa_check.scan(path)
+        if bad:
+            raise RuntimeError("in-flight scalar load hazard in %s:\n%s" % (src, isa_check.report(bad)))
+
+
 def build(force=True, verbose=False):
-    """Compile every translation unit and link the shared library.  Returns its path."""
+    """Compile every translation unit, verify the hand-placed scalar loads in the generated
+    code, and link the shared library.  Returns its path."""
     os.makedirs(BUILD, exist_ok=True)
     headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".h", ".hpp"))]
     headers.append(os.path.join(os.path.dirname(HERE), "include", "bmx.h"))
@@ -33,7 +55,7 @@ def build(force=True, verbose=False):
         s = os.path.join(CSRC, src)
         o = os.path.join(BUILD, src + ".o")
         if force or _stale(o, [s] + headers):
-            cmd = [HIPCC] + FLAGS + ["-c", s, "-o", o]
+            cmd = [HIPCC] + FLAGS + ["-save-temps=obj", "-c", s, "-o", o]
             if verbose:
                 print(" ".join(cmd), flush=True)
             r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -46,6 +68,7 @@ def build(force=True, verbose=False):
 
     with ThreadPoolExecutor(max_workers=min(4, len(SOURCES))) as ex:
         objs = list(ex.map(compile_one, SOURCES))
+    check_scalar_loads()
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB]
     subprocess.check_call(cmd)
     return LIB

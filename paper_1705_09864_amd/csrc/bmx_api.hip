@@ -51,7 +51,7 @@ QuantWs quant_ws(int64_t M, int64_t N, int64_t K, int bits_a) {
 
 namespace bmx {
 extern int conv_filters_per_wave;
-extern int gemm_tune_rows, gemm_tune_ksplit;
+extern int gemm_tune_rows, gemm_tune_ksplit, gemm_tune_order;
 }
 
 extern "C" {
@@ -63,6 +63,7 @@ int bmx_tune_set(int key, int value) {
   if (key == 1) bmx::conv_filters_per_wave = value;
   else if (key == 2) bmx::gemm_tune_rows = value;
   else if (key == 3) bmx::gemm_tune_ksplit = value;
+  else if (key == 4) bmx::gemm_tune_order = value;
   else return BMX_ERR_UNSUPPORTED;
   return BMX_OK;
 }

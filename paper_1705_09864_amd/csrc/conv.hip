@@ -170,8 +170,11 @@ conv_stationary_kernel(const ConvParams p) {
       }
     }
   }
-  // drain the last prefetch before the wave ends
-  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  // Drain the last prefetch (it went to buffer 0).  Its destination registers must stay
+  // allocated until the data has landed: were they dead here, the tail of the loop could be
+  // given the same registers while the load is still in flight.
+  buf[0].wait();
+  if (OUT == kOutF32Alpha) asm volatile("" : "+s"(sc[0]));
 }
 
 // General shape: any number of K words, one filter per wave-row, taps addressed with the

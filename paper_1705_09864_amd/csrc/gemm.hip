@@ -28,6 +28,7 @@ namespace bmx {
 
 int gemm_tune_rows = 0;    // 0 = automatic; otherwise force R (8, 16 or 32)
 int gemm_tune_ksplit = 0;  // 0 = automatic; otherwise force the number of K-split waves
+int gemm_tune_order = 0;   // 1 = row blocks fastest over the workgroup id
 
 namespace {
 
@@ -55,6 +56,8 @@ struct GemmParams {
   float* C_f32;
   int64_t ldc;
   int out;                // GemmOut
+  int row_blocks;         // ceil(Mv / rows_per_block)
+  int rows_fastest;       // tuning: row blocks fastest over the workgroup id instead
 };
 
 // One 32-dword chunk of an A row in SGPRs.  The loads are volatile asm so that their
@@ -121,8 +124,13 @@ gemm_kernel(const GemmParams p) {
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int S = __builtin_amdgcn_readfirstlane((int)(blockDim.x >> 6));
-  const int n0 = blockIdx.x * 64;
-  const int m0 = blockIdx.y * p.rows_per_block;  // first virtual row of the block
+  // Column blocks vary fastest over the linear workgroup id (measured faster than the
+  // other order on the FC shapes: neighbouring workgroups stream the same A rows).
+  const int col_blocks = (p.N + 63) / 64;
+  const int rb = p.rows_fastest ? (int)(blockIdx.x % p.row_blocks) : (int)(blockIdx.x / col_blocks);
+  const int cb = p.rows_fastest ? (int)(blockIdx.x / p.row_blocks) : (int)(blockIdx.x % col_blocks);
+  const int n0 = cb * 64;
+  const int m0 = rb * p.rows_per_block;  // first virtual row of the block
   int rows_valid = min(p.rows_per_block, p.Mv - m0);
   const int c0 = (int)((int64_t)wave * p.nch / S);
   const int c1 = (int)((int64_t)(wave + 1) * p.nch / S);
@@ -186,7 +194,11 @@ gemm_kernel(const GemmParams p) {
       const const_u32_ptr next_row0 = (const_u32_ptr)(arow0 + (uint64_t)cn * (kChunk * 4));
       row_steps<R, OP_AND>(buf, b, acc, src, row_bytes, rows_valid, next_row0);
     }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // drain the last prefetch
+    // Drain the last prefetch.  Its destination registers must stay allocated until the
+    // data has landed: were they dead here, the code that follows could be given the same
+    // registers while the load is still in flight.
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    buf[0].landed();
   }
 
   // ---- add the S partial counts of every (row, column) through LDS
@@ -247,7 +259,7 @@ void launch_rs(const GemmParams& p, int S, hipStream_t s) {
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
     raised = true;
   }
-  dim3 grid((unsigned)ceil_div(p.N, 64), (unsigned)ceil_div(p.Mv, p.rows_per_block));
+  dim3 grid((unsigned)(ceil_div(p.N, 64) * p.row_blocks));
   hipLaunchKernelGGL(kern, grid, dim3(64 * S), lds_bytes, s, p);
 }
 
@@ -290,6 +302,8 @@ void launch(GemmParams& p, hipStream_t s) {
   int R, S;
   choose_shape(p, R, S);
   p.rows_per_block = (R / p.planes) * p.planes;
+  p.row_blocks = (int)ceil_div(p.Mv, p.rows_per_block);
+  p.rows_fastest = gemm_tune_order;
   if (R == 32) launch_rs<32, OP_AND>(p, S, s);
   else if (R == 16) launch_rs<16, OP_AND>(p, S, s);
   else launch_rs<8, OP_AND>(p, S, s);
