@@ -31,7 +31,11 @@ def device_asm(src):
 def check_scalar_loads():
     """Scan the compiled device code of every source for registers of a hand-placed scalar
     load that are touched while the load is still in flight (see isa_check.py)."""
-    from . import isa_check
+    try:
+        from . import isa_check
+    except ImportError:  # run as a script
+        sys.path.insert(0, HERE)
+        import isa_check
     for src in SOURCES:
         path = device_asm(src)
         s = os.path.join(CSRC, src)
