@@ -7,33 +7,55 @@ namespace bmx {
 
 static constexpr int kWave = 64;
 
-// One wave packs 8 consecutive words (512 floats) of one row: lane <-> k, so every
-// load instruction is a 256-byte coalesced read and the 64-lane compare mask is the
-// packed word itself.  All 8 loads are issued before the first compare.
+// Row pack.  A wave packs segments of 16 consecutive words (1024 floats) of one row: lane
+// <-> k, so every load instruction is a 256-byte coalesced read and the 64-lane compare
+// mask is the packed word itself.  All 16 loads of a segment are issued before the first
+// compare, and waves walk the segment list with a grid stride so that a large matrix is
+// streamed by a grid that just fills the chip (8 waves per SIMD, 4 KiB in flight each).
+constexpr int kSegWords = 16;
+
 __global__ void __launch_bounds__(256)
 pack_rows_kernel(const float* __restrict__ x, int64_t rows, int64_t cols, int64_t ldx,
-                 uint64_t* __restrict__ out, int64_t out_ld, int64_t Kw, int64_t blocks_per_row) {
+                 uint64_t* __restrict__ out, int64_t out_ld, int64_t Kw, int64_t segs_per_row) {
   const int lane = threadIdx.x & (kWave - 1);
-  const int64_t wave = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
-  if (wave >= rows * blocks_per_row) return;
-  const int64_t r = wave / blocks_per_row;
-  const int64_t b = wave - r * blocks_per_row;
-  const float* xr = x + r * ldx;
-  const int64_t k0 = b * 512 + lane;
-  float v[8];
+  const int64_t nwaves = (int64_t)gridDim.x * (blockDim.x / kWave);
+  const int64_t total = rows * segs_per_row;
+  for (int64_t seg = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave); seg < total;
+       seg += nwaves) {
+    const int64_t r = segs_per_row == total ? 0 : seg / segs_per_row;
+    const int64_t b = seg - r * segs_per_row;
+    const float* xr = x + r * ldx;
+    const int64_t k0 = b * (64 * kSegWords) + lane;
+    float v[kSegWords];
+    if (k0 - lane + 64 * kSegWords <= cols) {  // whole segment inside the row (wave-uniform)
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const int64_t k = k0 + 64 * j;
-    v[j] = (k < cols) ? xr[k] : -1.0f;  // out-of-row lanes contribute 0 bits
-  }
-  uint64_t mine = 0;
+      for (int j = 0; j < kSegWords; ++j) v[j] = xr[k0 + 64 * j];
+    } else {
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const uint64_t m = __ballot(v[j] >= 0.0f);
-    if (lane == j) mine = m;
+      for (int j = 0; j < kSegWords; ++j) {
+        const int64_t k = k0 + 64 * j;
+        v[j] = (k < cols) ? xr[k] : -1.0f;  // out-of-row lanes contribute 0 bits
+      }
+    }
+    uint64_t mine = 0;
+#pragma unroll
+    for (int j = 0; j < kSegWords; ++j) {
+      const uint64_t m = __ballot(v[j] >= 0.0f);
+      if (lane == j) mine = m;
+    }
+    const int64_t w = b * kSegWords + lane;
+    if (lane < kSegWords && w < Kw) out[r * out_ld + w] = mine;
   }
-  const int64_t w = b * 8 + lane;
-  if (lane < 8 && w < Kw) out[r * out_ld + w] = mine;
+}
+
+static void launch_pack_rows_grid(const float* x, int64_t rows, int64_t cols, int64_t ldx,
+                                  uint64_t* out, int64_t out_ld, int64_t words_per_row,
+                                  hipStream_t s) {
+  const int64_t spr = ceil_div(words_per_row, kSegWords);
+  const int64_t blocks = ceil_div(rows * spr, 4);
+  const int64_t cap = 256 * 8;  // 8 workgroups of 4 waves per CU
+  hipLaunchKernelGGL(pack_rows_kernel, dim3((unsigned)(blocks < cap ? blocks : cap)), dim3(256), 0, s,
+                     x, rows, cols, ldx, out, out_ld, words_per_row, spr);
 }
 
 hipError_t launch_pack_rows(const float* x, int64_t rows, int64_t cols, int64_t ldx, uint64_t* out,
@@ -46,12 +68,7 @@ hipError_t launch_pack_rows(const float* x, int64_t rows, int64_t cols, int64_t 
     rows = 1;
     out_ld = cols / 64;
   }
-  const int64_t Kw2 = words_for(cols);
-  const int64_t bpr = ceil_div(Kw2, 8);
-  const int64_t waves = rows * bpr;
-  const int64_t blocks = ceil_div(waves, 4);
-  hipLaunchKernelGGL(pack_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, s, x, rows, cols, ldx,
-                     out, out_ld, Kw2, bpr);
+  launch_pack_rows_grid(x, rows, cols, ldx, out, out_ld, words_for(cols), s);
   return hipGetLastError();
 }
 
@@ -59,10 +76,7 @@ hipError_t launch_pack_rows(const float* x, int64_t rows, int64_t cols, int64_t 
 // data word): the chunk-padded activation rows read by the scalar side of the GEMM kernel.
 hipError_t launch_pack_rows_padded(const float* x, int64_t rows, int64_t cols, int64_t ldx,
                                    uint64_t* out, int64_t out_ld, hipStream_t s) {
-  const int64_t bpr = ceil_div(out_ld, 8);
-  const int64_t waves = rows * bpr;
-  hipLaunchKernelGGL(pack_rows_kernel, dim3((unsigned)ceil_div(waves, 4)), dim3(256), 0, s, x, rows,
-                     cols, ldx, out, out_ld, out_ld, bpr);
+  launch_pack_rows_grid(x, rows, cols, ldx, out, out_ld, out_ld, s);
   return hipGetLastError();
 }
 
@@ -104,37 +118,41 @@ hipError_t launch_pack_strided(const float* x, int64_t batch, int64_t K, int64_t
   return hipGetLastError();
 }
 
-// NCHW channel pack.  A workgroup packs 64 consecutive pixels of one image for one 64-channel
-// word: lanes span pixels (every load instruction is a coalesced 256-byte read of one
-// channel plane), the four waves take 16 channels each so that a lane has 16 independent
-// loads in flight, and the four 16-bit pieces meet in LDS.  Workgroup 0 of every (image,
-// word) also writes the constant halo words.
+// NCHW channel pack.  A wave packs 64 consecutive pixels of one image for one 64-channel
+// word: lanes span pixels, so every load instruction is a coalesced 256-byte read of one
+// channel plane, and all 64 channel loads of a lane are issued before the first compare
+// (16 KiB in flight per wave).  The word is assembled in two 32-bit halves.  Workgroup 0 of
+// every (image, word) also writes the constant halo words.
 __global__ void __launch_bounds__(256)
 pack_nchw_kernel(const float* __restrict__ x, int C, int HW, int W, int pad, int Hp, int Wp, int Cw,
                  uint64_t* __restrict__ xp) {
-  __shared__ uint32_t part[4][64];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int cw = blockIdx.y;
   const int n = blockIdx.z;
-  const int p = blockIdx.x * 64 + lane;
-  const int pc = p < HW ? p : HW - 1;
-  const int c0 = cw * 64 + wave * 16;
-  const float* xb = x + ((int64_t)n * C + c0) * HW + pc;
-  float v[16];
-#pragma unroll
-  for (int j = 0; j < 16; ++j) v[j] = (c0 + j < C) ? xb[(int64_t)j * HW] : -1.0f;
-  uint32_t bits = 0;
-#pragma unroll
-  for (int j = 0; j < 16; ++j) bits |= (v[j] >= 0.0f ? 1u : 0u) << j;
-  part[wave][lane] = bits;
-  __syncthreads();
+  const int p = (blockIdx.x * 4 + wave) * 64 + lane;
   uint64_t* xpn = xp + (int64_t)n * Hp * Wp * Cw;
-  if (wave == 0 && p < HW) {
-    const uint32_t lo = part[0][lane] | (part[1][lane] << 16);
-    const uint32_t hi = part[2][lane] | (part[3][lane] << 16);
-    const int h = p / W, w = p - h * W;
-    xpn[((int64_t)(h + pad) * Wp + (w + pad)) * Cw + cw] = ((uint64_t)hi << 32) | lo;
+  if (p - lane < HW) {  // wave-uniform: this 64-pixel group exists
+    const int pc = p < HW ? p : HW - 1;
+    const int c0 = cw * 64;
+    const float* xb = x + ((int64_t)n * C + c0) * HW + pc;
+    float v[64];
+    if (c0 + 64 <= C) {
+#pragma unroll
+      for (int j = 0; j < 64; ++j) v[j] = xb[(int64_t)j * HW];
+    } else {
+#pragma unroll
+      for (int j = 0; j < 64; ++j) v[j] = (c0 + j < C) ? xb[(int64_t)j * HW] : -1.0f;
+    }
+    uint32_t lo = 0, hi = 0;
+#pragma unroll
+    for (int j = 0; j < 32; ++j) lo |= (v[j] >= 0.0f ? 1u : 0u) << j;
+#pragma unroll
+    for (int j = 0; j < 32; ++j) hi |= (v[32 + j] >= 0.0f ? 1u : 0u) << j;
+    if (p < HW) {
+      const int h = p / W, w = p - h * W;
+      xpn[((int64_t)(h + pad) * Wp + (w + pad)) * Cw + cw] = ((uint64_t)hi << 32) | lo;
+    }
   }
   if (pad > 0 && blockIdx.x == 0) {
     const uint64_t ones = (cw == Cw - 1 && (C % 64)) ? (((uint64_t)1 << (C % 64)) - 1) : ~(uint64_t)0;
@@ -165,7 +183,7 @@ hipError_t launch_pack_nchw(const float* x, int N, int C, int H, int W, int pad,
                             hipStream_t s) {
   const int Cw = (int)words_for(C);
   const int HW = H * W;
-  dim3 grid((unsigned)ceil_div(HW, 64), (unsigned)Cw, (unsigned)N);
+  dim3 grid((unsigned)ceil_div(HW, 256), (unsigned)Cw, (unsigned)N);
   hipLaunchKernelGGL(pack_nchw_kernel, grid, dim3(256), 0, s, x, C, HW, W, pad, H + 2 * pad,
                      W + 2 * pad, Cw, xp);
   return hipGetLastError();
