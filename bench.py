@@ -7,6 +7,11 @@ with the alpha epilogue.  Weights are packed and alpha is computed once, outside
 (the paper packs weights offline with its model converter).  Inputs are seeded synthetic
 tensors that are resident in HBM before the timed region starts.
 
+HBM residency.  One step touches 26 MB, far less than the 256 MB memory-side cache of the
+part, so a loop over one buffer set would measure the cache.  The steps therefore rotate
+over enough copies of (input, workspace, output) to exceed that cache; the cache-hot rate
+(one buffer set) is reported beside it in `config`.
+
 The kernels run for a few microseconds each, less than the host needs to enqueue them, so
 the K timed steps are captured once into a HIP graph (the library launches on the capturing
 stream) and the timed region is one replay of that graph: exactly K steps, device-bound.
@@ -14,9 +19,9 @@ The eager (host-enqueued) rate is reported next to it.
 
 Prints ONE JSON line.  `value` is 2*M*N*K binary operations per second over the whole step;
 `roofline` prices the dominant kernel (the convolution) against the VALU xor+popcount peak,
-its duration measured with HIP events on the launch stream around K back-to-back launches;
-`cpu_baseline` times the CPU oracle on the same layer on the host cores; `other_configs`
-gives the same event-timed kernel figures for BASELINE configurations 1, 3, 4 and 5.
+its duration measured with HIP events on the launch stream around K back-to-back launches
+on the same rotating buffers; `cpu_baseline` times the CPU oracle on the same layer on the
+host cores; `other_configs` gives event-timed figures for BASELINE configurations 1, 3, 4, 5.
 """
 import argparse
 import json
@@ -32,6 +37,7 @@ if ROOT not in sys.path:
 # v_bcnt_u32_b32 (popcount-accumulate) handle 32 bit pairs = 64 binary ops per 2 lane-ops.
 VALU_PEAK_BINOPS = 256 * 64 * 2.4e9 * 32
 HBM_PEAK = 8.0e12
+MALL_BYTES = 256 << 20  # memory-side cache the rotation has to exceed
 
 
 def main():
@@ -55,12 +61,12 @@ def main():
     torch.cuda.set_device(0)
     K_STEPS = args.steps
 
-    def graph_of(fn, reps):
-        """Capture `reps` calls of fn (library launches on the capturing stream)."""
+    def graph_of(fns):
+        """Capture the calls in `fns`, in order (library launches on the capturing stream)."""
         g = torch.cuda.CUDAGraph()
         st = torch.cuda.Stream()
         with torch.cuda.graph(g, stream=st):
-            for _ in range(reps):
+            for fn in fns:
                 fn()
         torch.cuda.synchronize()
         return g
@@ -84,7 +90,14 @@ def main():
         for _ in range(3):
             fn()
         torch.cuda.synchronize()
-        return event_us(graph_of(fn, reps), reps)
+        return event_us(graph_of([fn] * reps), reps)
+
+    def rotating_us(make_fn, nsets, reps):
+        fns = [make_fn(i % nsets) for i in range(reps)]
+        for f in fns[:nsets]:
+            f()
+        torch.cuda.synchronize()
+        return event_us(graph_of(fns), reps)
 
     # ------------------------------------------------------------------ config 2 (headline)
     c = synth.config2()
@@ -96,24 +109,30 @@ def main():
     M_, N_, K_ = O, N * Ho * Wo, C * KH * KW
     binops = 2.0 * M_ * N_ * K_
 
-    x = torch.from_numpy(x_h).cuda()
     w = torch.from_numpy(w_h).cuda()
     Wp = B.pack_conv_weights(w)
     alpha = B.alpha_mean_abs(w)
-    ws = torch.empty(B.workspace_bytes(B.OP_BINARY_CONV2D, (N, C, H, W, O, KH, KW, stride, pad)),
-                     dtype=torch.uint8, device="cuda")
-    out = torch.empty((N, O, Ho, Wo), dtype=torch.float32, device="cuda")
+    ws_bytes = B.workspace_bytes(B.OP_BINARY_CONV2D, (N, C, H, W, O, KH, KW, stride, pad))
     Cw = (C + 63) // 64
-    xp = ws.view(torch.int64)[: N * (H + 2 * pad) * (W + 2 * pad) * Cw].view(
-        N, H + 2 * pad, W + 2 * pad, Cw)
+    out_bytes = N * O * Ho * Wo * 4
+    step_bytes = x_h.nbytes + ws_bytes + out_bytes
+    nsets = MALL_BYTES // step_bytes + 2
+    x0 = torch.from_numpy(x_h).cuda()
+    xs = [x0] + [x0.clone() for _ in range(nsets - 1)]
+    wss = [torch.empty(ws_bytes, dtype=torch.uint8, device="cuda") for _ in range(nsets)]
+    outs = [torch.empty((N, O, Ho, Wo), dtype=torch.float32, device="cuda") for _ in range(nsets)]
+    xps = [t.view(torch.int64)[: N * (H + 2 * pad) * (W + 2 * pad) * Cw].view(
+        N, H + 2 * pad, W + 2 * pad, Cw) for t in wss]
 
-    def step():
-        B.binary_conv2d(x, Wp, O, KH, KW, stride, pad, alpha=alpha, out=out, workspace=ws)
+    def make_step(i):
+        return lambda: B.binary_conv2d(xs[i], Wp, O, KH, KW, stride, pad, alpha=alpha, out=outs[i],
+                                       workspace=wss[i])
 
-    for _ in range(args.warmup):
-        step()
+    steps = [make_step(i % nsets) for i in range(K_STEPS)]
+    for i in range(args.warmup):
+        steps[i % K_STEPS]()
     torch.cuda.synchronize()
-    g_steps = graph_of(step, K_STEPS)
+    g_steps = graph_of(steps)
     g_steps.replay()  # untimed replay: graph upload
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -123,31 +142,35 @@ def main():
     ms_per_step = dt / K_STEPS * 1e3
     value = binops / (dt / K_STEPS) / 1e9
 
-    # eager rate (host enqueues every launch): context only
+    # cache-hot rate (one buffer set) and eager rate (host enqueues every launch): context
+    hot_us = kernel_us(steps[0], K_STEPS)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(K_STEPS):
-        step()
+    for f in steps:
+        f()
     torch.cuda.synchronize()
     eager_ms = (time.perf_counter() - t0) / K_STEPS * 1e3
 
-    conv_us = kernel_us(lambda: B.binary_conv2d_packed(xp, C, Wp, O, KH, KW, stride, pad,
-                                                       alpha=alpha, out=out), K_STEPS)
-    pack_us = kernel_us(lambda: B.pack_nchw(x, pad, out=xp), K_STEPS)
+    conv_us = rotating_us(lambda i: (lambda: B.binary_conv2d_packed(
+        xps[i], C, Wp, O, KH, KW, stride, pad, alpha=alpha, out=outs[i])), nsets, K_STEPS)
+    pack_us = rotating_us(lambda i: (lambda: B.pack_nchw(xs[i], pad, out=xps[i])), nsets, K_STEPS)
     achieved = binops / (conv_us * 1e-6)
-    pack_bytes = x_h.nbytes + xp.numel() * 8
+    pack_bytes = x_h.nbytes + xps[0].numel() * 8
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic_conv2d_config2.json")
     if os.path.exists(tpath):
         traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
-    roofline = {"bound": "alu", "kernel": "conv_stationary_kernel<9> (implicit-GEMM xor+popcount)",
+    roofline = {"bound": "alu", "kernel": "conv_stationary_kernel<9,2> (implicit-GEMM xor+popcount)",
                 "achieved": achieved / 1e12, "peak": VALU_PEAK_BINOPS / 1e12, "unit": "Tbinop/s",
                 "frac": achieved / VALU_PEAK_BINOPS, "traffic": traffic, "avg_us": conv_us,
                 "algorithmic_binops_per_launch": binops,
-                "pack_kernel": {"bound": "hbm", "achieved": pack_bytes / (pack_us * 1e-6) / 1e9,
+                "output_bytes_per_launch": out_bytes,
+                "pack_kernel": {"kernel": "pack_nchw_kernel", "bound": "hbm",
+                                "achieved": pack_bytes / (pack_us * 1e-6) / 1e9,
                                 "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                                 "frac": pack_bytes / (pack_us * 1e-6) / HBM_PEAK, "avg_us": pack_us,
                                 "algorithmic_bytes_per_launch": pack_bytes}}
+    del xs, wss, outs, xps, steps, g_steps
 
     # ------------------------------------------------------------------ other configurations
     other = None
@@ -166,9 +189,10 @@ def main():
         W1p = B.binarize_pack(torch.from_numpy(c1["w_kn"]).cuda(), 0)
         o1 = torch.empty((64, 256), dtype=torch.int32, device="cuda")
         ws1 = torch.empty(B.workspace_bytes(B.OP_BINARY_FC, (64, 512, 256)), dtype=torch.uint8, device="cuda")
-        other["config1_fc_64x256x512"] = alu(2.0 * 64 * 256 * 512, kernel_us(
+        other["config1_fc_call_64x256x512"] = alu(2.0 * 64 * 256 * 512, kernel_us(
             lambda: B.binary_fc(a1, W1p, integer_out=True, out=o1, workspace=ws1)))
-        # config 3: AlexNet classifier layers (pack + GEMM + alpha), and the big weight pack
+        # config 3: AlexNet classifier layers: GEMM kernel alone (pre-packed activations),
+        # the layer call (pack + GEMM + alpha), and the big weight pack
         c3 = synth.config3()
         x3 = torch.from_numpy(c3["x"]).cuda()
         w31 = torch.from_numpy(c3["w1"]).cuda()
@@ -177,14 +201,28 @@ def main():
         al1, al2 = B.alpha_mean_abs(w31), B.alpha_mean_abs(w32)
         h1 = torch.empty((256, 4096), dtype=torch.float32, device="cuda")
         h2 = torch.empty((256, 4096), dtype=torch.float32, device="cuda")
+        i3 = torch.empty((256, 4096), dtype=torch.int32, device="cuda")
         ws3 = torch.empty(B.workspace_bytes(B.OP_BINARY_FC, (256, 9216, 4096)), dtype=torch.uint8, device="cuda")
-        other["config3_fc1_256x4096x9216"] = alu(2.0 * 256 * 4096 * 9216, kernel_us(
+        other["config3_fc1_call_256x4096x9216"] = alu(2.0 * 256 * 4096 * 9216, kernel_us(
             lambda: B.binary_fc(x3, W31p, alpha=al1, out=h1, workspace=ws3), 50))
-        other["config3_fc2_256x4096x4096"] = alu(2.0 * 256 * 4096 * 4096, kernel_us(
+        other["config3_fc2_call_256x4096x4096"] = alu(2.0 * 256 * 4096 * 4096, kernel_us(
             lambda: B.binary_fc(h1, W32p, alpha=al2, out=h2, workspace=ws3), 50))
-        other["config3_weight_pack_4096x9216"] = hbm(w31.numel() * 4 + W31p.numel() * 8, kernel_us(
+        X3p, H1p = B.binarize_pack(x3, 1), B.binarize_pack(h1, 1)
+        other["config3_fc1_gemm_kernel"] = alu(2.0 * 256 * 4096 * 9216, kernel_us(
+            lambda: B.xnor_gemm(X3p, W31p, 9216, out=i3), 50))
+        other["config3_fc2_gemm_kernel"] = alu(2.0 * 256 * 4096 * 4096, kernel_us(
+            lambda: B.xnor_gemm(H1p, W32p, 4096, out=i3), 50))
+        other["config3_activation_pack_256x9216"] = hbm(x3.numel() * 4 + X3p.numel() * 8, kernel_us(
+            lambda: B.binarize_pack(x3, 1, out=X3p)))
+        other["config3_weight_pack_4096x9216_cache_assisted"] = hbm(w31.numel() * 4 + W31p.numel() * 8, kernel_us(
             lambda: B.binarize_pack(w31, 1, out=W31p), 20))
         del w31, w32
+        # a 1 GiB row pack: larger than the memory-side cache, the sustained HBM figure
+        big = torch.empty((8192, 32768), dtype=torch.float32, device="cuda").normal_()
+        bigp = B.binarize_pack(big, 1)
+        other["row_pack_1GiB_hbm_resident"] = hbm(big.numel() * 4 + bigp.numel() * 8, kernel_us(
+            lambda: B.binarize_pack(big, 1, out=bigp), 5))
+        del big, bigp
         # config 4: deep conv stage, stride 1 and 2 (conv kernel alone, and pack alone)
         for s4 in (1, 2):
             c4 = synth.config4(stride=s4)
@@ -195,8 +233,12 @@ def main():
             ho4, wo4 = B.conv_out_hw(14, 14, 3, 3, s4, 1)
             o4 = torch.empty((64, 256, ho4, wo4), dtype=torch.float32, device="cuda")
             ops4 = 2.0 * 256 * 64 * ho4 * wo4 * 2304
-            other["config4_conv_s%d" % s4] = alu(ops4, kernel_us(
+            other["config4_conv_s%d_kernel" % s4] = alu(ops4, kernel_us(
                 lambda: B.binary_conv2d_packed(xp4, 256, W4p, 256, 3, 3, s4, 1, alpha=al4, out=o4)))
+            ws4 = torch.empty(B.workspace_bytes(B.OP_BINARY_CONV2D, (64, 256, 14, 14, 256, 3, 3, s4, 1)),
+                              dtype=torch.uint8, device="cuda")
+            other["config4_conv_s%d_call" % s4] = alu(ops4, kernel_us(
+                lambda: B.binary_conv2d(x4, W4p, 256, 3, 3, s4, 1, alpha=al4, out=o4, workspace=ws4)))
             if s4 == 1:
                 other["config4_pack_nchw"] = hbm(x4.numel() * 4 + xp4.numel() * 8, kernel_us(
                     lambda: B.pack_nchw(x4, 1, out=xp4)))
@@ -217,13 +259,13 @@ def main():
         alpha_h = oracle.alpha_mean_abs(w_h)
         oracle.binary_conv2d(x_h[:1], w_h, stride, pad, alpha_h)  # page in
         reps, t_cpu = 0, 0.0
-        while t_cpu < 10.0 and reps < 20:
+        while t_cpu < 10.0 and reps < 400:
             t1 = time.perf_counter()
             oracle.binary_conv2d(x_h, w_h, stride, pad, alpha_h)
             t_cpu += time.perf_counter() - t1
             reps += 1
         cpu = {"value": binops * reps / t_cpu / 1e9, "unit": "GOPS", "cores": oracle.num_threads(),
-               "kind": "oracle", "sample": "%d full passes of the config-2 layer (%.2f s each)"
+               "kind": "oracle", "sample": "%d full passes of the config-2 layer (%.3f s each)"
                % (reps, t_cpu / reps)}
 
     line = {"metric": "binary GOPS (2*M*N*K xnor-popcount)", "value": value, "unit": "GOPS",
@@ -234,6 +276,8 @@ def main():
                                    "alpha epilogue, fp32 out (GEMM view M=64 N=50176 K=576)",
                        "step": "bmx_binary_conv2d = channel pack + implicit-GEMM conv + alpha",
                        "timed_region": "one replay of a HIP graph holding the K steps",
+                       "buffer_sets_rotated": int(nsets),
+                       "ms_per_step_cache_hot": hot_us * 1e-3,
                        "ms_per_step_eager": eager_ms},
             "roofline": roofline, "cpu_baseline": cpu, "other_configs": other}
     print(json.dumps(line))

@@ -80,41 +80,52 @@ hipError_t launch_pack_rows_padded(const float* x, int64_t rows, int64_t cols, i
   return hipGetLastError();
 }
 
-// Strided pack: thread <-> column n (coalesced along n for every k), 64 rows of the
-// K dimension folded into one word per thread.
+// Strided pack (the matrix is stored K x ncol, pack down the columns): a wave packs one
+// word of 64 consecutive columns: lanes span columns, so every load instruction is a
+// coalesced 256-byte read of one K row, and all 64 row loads of a lane are issued before
+// the first compare.  The word is assembled in two 32-bit halves.
 __global__ void __launch_bounds__(256)
 pack_strided_kernel(const float* __restrict__ x, int64_t batch, int64_t K, int64_t ncol,
                     int64_t ldx, int64_t batch_stride, uint64_t* __restrict__ out, int64_t out_ld,
-                    int64_t Kw) {
-  const int64_t n = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (n >= ncol) return;
-  for (int64_t b = blockIdx.z; b < batch; b += gridDim.z) {
-    for (int64_t w = blockIdx.y; w < Kw; w += gridDim.y) {
-      const float* xb = x + b * batch_stride + (w * 64) * ldx + n;
-      const int64_t kmax = K - w * 64;  // rows left in this word (>= 1)
-      uint32_t lo = 0, hi = 0;
+                    int64_t Kw, int64_t col_groups) {
+  const int lane = threadIdx.x & 63;
+  const int64_t nwaves = (int64_t)gridDim.x * (blockDim.x / kWave);
+  const int64_t total = batch * Kw * col_groups;
+  for (int64_t item = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+       item < total; item += nwaves) {
+    const int64_t g = item % col_groups;
+    const int64_t t = item / col_groups;
+    const int64_t w = t % Kw;
+    const int64_t b = t / Kw;
+    const int64_t n = g * 64 + lane;
+    const int64_t nc = n < ncol ? n : ncol - 1;
+    const float* xb = x + b * batch_stride + (w * 64) * ldx + nc;
+    const int64_t kmax = K - w * 64;  // rows left in this word (>= 1)
+    float v[64];
+    if (kmax >= 64) {
 #pragma unroll
-      for (int j = 0; j < 32; ++j) {
-        const float v = (j < kmax) ? xb[(int64_t)j * ldx] : -1.0f;
-        lo |= (v >= 0.0f ? 1u : 0u) << j;
-      }
+      for (int j = 0; j < 64; ++j) v[j] = xb[(int64_t)j * ldx];
+    } else {
 #pragma unroll
-      for (int j = 0; j < 32; ++j) {
-        const float v = (j + 32 < kmax) ? xb[(int64_t)(j + 32) * ldx] : -1.0f;
-        hi |= (v >= 0.0f ? 1u : 0u) << j;
-      }
-      out[(b * ncol + n) * out_ld + w] = ((uint64_t)hi << 32) | lo;
+      for (int j = 0; j < 64; ++j) v[j] = (j < kmax) ? xb[(int64_t)j * ldx] : -1.0f;
     }
+    uint32_t lo = 0, hi = 0;
+#pragma unroll
+    for (int j = 0; j < 32; ++j) lo |= (v[j] >= 0.0f ? 1u : 0u) << j;
+#pragma unroll
+    for (int j = 0; j < 32; ++j) hi |= (v[32 + j] >= 0.0f ? 1u : 0u) << j;
+    if (n < ncol) out[(b * ncol + n) * out_ld + w] = ((uint64_t)hi << 32) | lo;
   }
 }
 
 hipError_t launch_pack_strided(const float* x, int64_t batch, int64_t K, int64_t ncol, int64_t ldx,
                                int64_t batch_stride, uint64_t* out, int64_t out_ld, hipStream_t s) {
   const int64_t Kw = words_for(K);
-  dim3 grid((unsigned)ceil_div(ncol, 256), (unsigned)(Kw < 65535 ? Kw : 65535),
-            (unsigned)(batch < 65535 ? batch : 65535));
-  hipLaunchKernelGGL(pack_strided_kernel, grid, dim3(256), 0, s, x, batch, K, ncol, ldx,
-                     batch_stride, out, out_ld, Kw);
+  const int64_t groups = ceil_div(ncol, 64);
+  const int64_t blocks = ceil_div(batch * Kw * groups, 4);
+  const int64_t cap = 256 * 6;  // the kernel holds 64 loaded values per lane: 6 waves per SIMD
+  hipLaunchKernelGGL(pack_strided_kernel, dim3((unsigned)(blocks < cap ? blocks : cap)), dim3(256), 0,
+                     s, x, batch, K, ncol, ldx, batch_stride, out, out_ld, Kw, groups);
   return hipGetLastError();
 }
 
