@@ -47,6 +47,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-configs", action="store_true")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="run the steps eagerly next to a plain 256 MiB device copy and exit: the "
+                         "workload for the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
@@ -129,6 +132,18 @@ def main():
                                        workspace=wss[i])
 
     steps = [make_step(i % nsets) for i in range(K_STEPS)]
+    if args.traffic_probe:
+        # the copy of known size that calibrates the counters: reads 256 MiB, writes 256 MiB
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        for f in steps:
+            f()
+        torch.cuda.synchronize()
+        print(json.dumps({"traffic_probe": True, "steps": K_STEPS, "copy_bytes_each_way": 256 << 20,
+                          "buffer_sets_rotated": int(nsets)}))
+        return
     for i in range(args.warmup):
         steps[i % K_STEPS]()
     torch.cuda.synchronize()
@@ -157,9 +172,11 @@ def main():
     achieved = binops / (conv_us * 1e-6)
     pack_bytes = x_h.nbytes + xps[0].numel() * 8
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic_conv2d_config2.json")
-    if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+    tpath = os.path.join(ROOT, "profiles", "traffic_conv2d_config2.txt")
+    if os.path.exists(tpath):  # scaled FETCH_SIZE + WRITE_SIZE of the convolution kernel
+        for ln in open(tpath):
+            if ln.startswith("hbm_bytes_per_launch:"):
+                traffic = int(ln.split(":")[1])
     roofline = {"bound": "alu", "kernel": "conv_stationary_kernel<9,2> (implicit-GEMM xor+popcount)",
                 "achieved": achieved / 1e12, "peak": VALU_PEAK_BINOPS / 1e12, "unit": "Tbinop/s",
                 "frac": achieved / VALU_PEAK_BINOPS, "traffic": traffic, "avg_us": conv_us,

@@ -68,6 +68,28 @@ __device__ __forceinline__ int seg_popcount(const ScalarSeg<SEG>& a, const uint3
 
 enum ConvOut { kOutI32 = 0, kOutF32 = 1, kOutF32Alpha = 2 };
 
+// Every kernel argument the wave is going to need, consumed by empty asm statements at the
+// top of the kernel: the compiler then requests all of them in one batch of scalar loads
+// and waits once, instead of paying one memory round trip per group of first uses.
+template <int KW, int J = 0>
+__device__ __forceinline__ void touch_offsets(const ConvParams& p) {
+  if constexpr (J + 4 <= KW) {
+    asm volatile("" ::"s"(p.off[J]), "s"(p.off[J + 1]), "s"(p.off[J + 2]), "s"(p.off[J + 3]));
+    touch_offsets<KW, J + 4>(p);
+  } else if constexpr (J < KW) {
+    asm volatile("" ::"s"(p.off[J]));
+    touch_offsets<KW, J + 1>(p);
+  }
+}
+template <int KW>
+__device__ __forceinline__ void touch_args(const ConvParams& p) {
+  asm volatile("" ::"s"(p.Xp), "s"(p.Wp), "s"(p.alpha), "s"(p.out_i32), "s"(p.out_f32), "s"(p.P),
+               "s"(p.O), "s"(p.HoWo), "s"(p.Wo), "s"(p.Hp), "s"(p.Wp_pix), "s"(p.Cw), "s"(p.stride),
+               "s"(p.Kreal), "s"(p.cn), "s"(p.div_howo.mul), "s"(p.div_howo.sh1), "s"(p.div_howo.sh2),
+               "s"(p.div_wo.mul), "s"(p.div_wo.sh1), "s"(p.div_wo.sh2));
+  if constexpr (KW <= 9) touch_offsets<KW>(p);  // longer tables would not stay in SGPRs anyway
+}
+
 template <int KW, int OUT>
 __global__ void __launch_bounds__(256)
 conv_stationary_kernel(const ConvParams p) {
@@ -75,12 +97,12 @@ conv_stationary_kernel(const ConvParams p) {
   constexpr int NSEG = SegShape<KW>::kNseg;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int64_t group = (int64_t)blockIdx.x * 4 + wave;  // 64-pixel group
-  const int64_t pix0 = group * 64;
-  if (pix0 >= p.P) return;
-  // Lanes past the last pixel repeat pixel P-1: they compute and store the same values to
-  // the same addresses as the lane that owns it, so no lane is ever masked off.
-  const int64_t pix = min(pix0 + lane, p.P - 1);
+  // Lanes (and whole waves of the last workgroup) past the last pixel repeat pixel P-1: they
+  // compute and store the same values to the same addresses as the lane that owns it.  No
+  // lane is ever masked off and there is no early exit, so every kernel argument can be
+  // fetched in one batch at the top.
+  touch_args<KW>(p);
+  const int64_t pix = min(((int64_t)blockIdx.x * 4 + wave) * 64 + lane, p.P - 1);
   const uint32_t img = fast_div((uint32_t)pix, p.div_howo);
   const uint32_t rem = (uint32_t)pix - img * (uint32_t)p.HoWo;
   const uint32_t ho = fast_div(rem, p.div_wo);
@@ -272,11 +294,14 @@ hipError_t launch_binary_conv2d(const uint64_t* Xp, int N, int C, int H, int W, 
       for (int kw = 0; kw < KW; ++kw)
         for (int cw = 0; cw < Cw; ++cw)
           p.off[(kh * KW + kw) * Cw + cw] = (kh * Wpp + kw) * Cw + cw;
-    // filters per wave: enough waves to cover the 1024 SIMDs several times over
+    // Filters per wave.  A wave pays its gather once and then streams cn filter rows, so
+    // more filters per wave amortise the gather better, but the grid must still put about
+    // six waves on each of the 1024 SIMDs; below 8 filters the gather dominates (sweeps of
+    // the ResNet-stage shapes put the optimum at 8 whenever the grid is short of waves).
     int cn = conv_filters_per_wave;
     if (cn <= 0) {
       cn = O;
-      while (cn > 4 && groups * ceil_div(O, cn) < 4096) cn = (cn + 1) / 2;
+      while (cn > 8 && groups * ceil_div(O, cn) < 6144) cn = (cn + 1) / 2;
     }
     p.cn = cn;
     const int cblocks = (int)ceil_div(O, cn);
