@@ -16,8 +16,9 @@
 // the end.  Splitting K is what gives a skinny problem (a few hundred rows) enough waves
 // to keep four per SIMD, which the VALU needs to issue at full rate.
 //
-// The B chunk of a wave (64 rows x 128 bytes) is read with coalesced 16-byte loads,
-// transposed through a wave-private LDS tile, and prefetched one chunk ahead.
+// The B chunk of a wave (64 rows x 128 bytes) is read with coalesced 16-byte loads and
+// transposed through a wave-private LDS tile (with 32 rows per wave it is also prefetched
+// one chunk ahead; the leaner shapes rely on the other waves of the SIMD instead).
 //
 // Bit planes (k-bit activations): plane p of row m is virtual row m * planes + p of A, so
 // the main loop is unaware of planes; the final reduction weights plane p by 2^p.
@@ -68,7 +69,8 @@ struct ARow {
     asm volatile("s_load_dwordx16 %0, %1, 0x0" : "=s"(lo) : "s"(src));
     asm volatile("s_load_dwordx16 %0, %1, 0x40" : "=s"(hi) : "s"(src));
   }
-  // after s_waitcnt lgkmcnt(0): make every later use depend on this point
+  // after s_waitcnt lgkmcnt(0): make every later use depend on this point (and keep the
+  // destination registers allocated up to it)
   __device__ __forceinline__ void landed() {
     asm volatile("" : "+s"(lo));
     asm volatile("" : "+s"(hi));
@@ -115,8 +117,8 @@ __device__ __forceinline__ void row_steps(ARow (&buf)[2], const uint32_t (&b)[kC
   }
 }
 
-template <int R, bool OP_AND>
-__global__ void __launch_bounds__(512, 4)
+template <int R, bool OP_AND, bool PF>
+__global__ void __launch_bounds__(512, PF ? 4 : 6)
 gemm_kernel(const GemmParams p) {
   static_assert(R % 2 == 0, "buffer parity must repeat from chunk to chunk");
   extern __shared__ __align__(16) uint32_t lds[];
@@ -175,8 +177,14 @@ gemm_kernel(const GemmParams p) {
     ARow buf[2];
     const_u32_ptr src = (const_u32_ptr)(arow0 + (uint64_t)c0 * (kChunk * 4));
     buf[0].issue(src);
-    fetch(c0);
+    // Lane r touches row r of the chunk that comes next, so that the scalar loads of a row
+    // step find their line in L2 instead of paying a cold miss each (the first pass over
+    // a block would otherwise cost one memory round trip per row).
+    const uint32_t* warm_row = p.A + (int64_t)(m0 + min(lane, rows_valid - 1)) * p.lda;
+    uint32_t warm = warm_row[(int64_t)c0 * kChunk];
+    if (PF) fetch(c0);
     for (int c = c0; c < c1; ++c) {
+      if (!PF) fetch(c);
       // transpose the staged chunk: row n of the tile is lane n's 32 dwords
 #pragma unroll
       for (int i = 0; i < 8; ++i) *(uint4*)(tile + (i * 8 + srow) * kTRow + spiece * 4) = stage[i];
@@ -189,9 +197,11 @@ gemm_kernel(const GemmParams p) {
         b[4 * j + 2] = v.z;
         b[4 * j + 3] = v.w;
       }
-      if (c + 1 < c1) fetch(c + 1);
+      if (PF && c + 1 < c1) fetch(c + 1);
       const int cn = min(c + 1, c1 - 1);  // after the last chunk the last row 0 is fetched again
       const const_u32_ptr next_row0 = (const_u32_ptr)(arow0 + (uint64_t)cn * (kChunk * 4));
+      asm volatile("" ::"v"(warm));  // consume the previous touch
+      warm = warm_row[(int64_t)cn * kChunk];
       row_steps<R, OP_AND>(buf, b, acc, src, row_bytes, rows_valid, next_row0);
     }
     // Drain the last prefetch.  Its destination registers must stay allocated until the
@@ -199,6 +209,35 @@ gemm_kernel(const GemmParams p) {
     // registers while the load is still in flight.
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     buf[0].landed();
+    asm volatile("" ::"v"(warm));
+  }
+
+  const int n = n0 + lane;
+  const int nc = min(n, p.N - 1);
+  float al = 1.0f;
+  if (p.out == kGemmF32Alpha) al = p.alpha[nc];
+  auto finish = [&](int64_t m, int total) {  // count of output row m -> result -> C[m][n]
+    if (n < p.N) {
+      const int64_t idx = m * p.ldc + n;
+      if (p.out == kGemmPlanes) {
+        const int sv = 2 * total - p.rowsum[m];
+        if (p.C_i32) p.C_i32[idx] = sv;
+        if (p.C_f32) p.C_f32[idx] = (float)sv / p.levels;
+      } else {
+        const int dot = p.Kreal - 2 * total;
+        if (p.out == kGemmI32) p.C_i32[idx] = dot;
+        else if (p.out == kGemmF32) p.C_f32[idx] = (float)dot;
+        else p.C_f32[idx] = al * (float)dot;
+      }
+    }
+  };
+
+  if (S == 1 && p.planes == 1 && p.tail0 >= p.tail1) {
+    // one wave holds the whole count of its rows: straight from the accumulators
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+      if (r < rows_valid) finish(m0 + r, acc[r]);
+    return;
   }
 
   // ---- add the S partial counts of every (row, column) through LDS
@@ -207,18 +246,20 @@ gemm_kernel(const GemmParams p) {
   for (int r = 0; r < R; ++r) lds[(wave * R + r) * 64 + lane] = (uint32_t)acc[r];
   __syncthreads();
 
-  const int n = n0 + lane;
-  const int nc = min(n, p.N - 1);
   const int rows_out = rows_valid / p.planes;
   const int64_t mbase = m0 / p.planes;
-  float al = 1.0f;
-  if (p.out == kGemmF32Alpha) al = p.alpha[nc];
   for (int rr = wave; rr < rows_out; rr += S) {
     int total = 0;
     for (int pl = 0; pl < p.planes; ++pl) {
       const int v = rr * p.planes + pl;
       int t = 0;
-      for (int s = 0; s < S; ++s) t += (int)lds[(s * R + v) * 64 + lane];
+      // eight independent reads (waves past S repeat the last one and count as zero), so
+      // that the LDS round trips overlap instead of adding up
+#pragma unroll
+      for (int s = 0; s < 8; ++s) {
+        const int x = (int)lds[((s < S ? s : S - 1) * R + v) * 64 + lane];
+        t += (s < S) ? x : 0;
+      }
       if (p.tail0 < p.tail1) {
         // K words outside the chunked range (row-major A that may not be read past its
         // last word): plain loads, two dwords per step
@@ -233,26 +274,13 @@ gemm_kernel(const GemmParams p) {
       }
       total += t << pl;
     }
-    if (n < p.N) {
-      const int64_t m = mbase + rr;
-      const int64_t idx = m * p.ldc + n;
-      if (p.out == kGemmPlanes) {
-        const int sv = 2 * total - p.rowsum[m];
-        if (p.C_i32) p.C_i32[idx] = sv;
-        if (p.C_f32) p.C_f32[idx] = (float)sv / p.levels;
-      } else {
-        const int dot = p.Kreal - 2 * total;
-        if (p.out == kGemmI32) p.C_i32[idx] = dot;
-        else if (p.out == kGemmF32) p.C_f32[idx] = (float)dot;
-        else p.C_f32[idx] = al * (float)dot;
-      }
-    }
+    finish(mbase + rr, total);
   }
 }
 
-template <int R, bool OP_AND>
+template <int R, bool OP_AND, bool PF>
 void launch_rs(const GemmParams& p, int S, hipStream_t s) {
-  auto kern = gemm_kernel<R, OP_AND>;
+  auto kern = gemm_kernel<R, OP_AND, PF>;
   const size_t lds_bytes = (size_t)S * (kTileDw > R * 64 ? kTileDw : R * 64) * 4;
   static bool raised = false;  // more than the default 64 KiB of dynamic LDS for S = 8
   if (!raised) {
@@ -263,29 +291,34 @@ void launch_rs(const GemmParams& p, int S, hipStream_t s) {
   hipLaunchKernelGGL(kern, grid, dim3(64 * S), lds_bytes, s, p);
 }
 
-// Rows per wave and K split.  A wave's work is (chunks per wave) x (R row steps + a fixed
-// per-chunk cost); the grid should put at least four waves on each of the 1024 SIMDs and
-// come out close to a whole number of waves per SIMD.
+// Rows per wave and K split.  The kernel runs at full VALU rate once about four waves sit
+// on each of the 1024 SIMDs, and its fixed costs (launch, first B chunk, store drain) do not
+// shrink with fatter waves, so: the largest R whose grid alone reaches 4096 waves, else the
+// smallest K split that gets a 16-row (then 8-row) grid there.
 void choose_shape(const GemmParams& p, int& R_out, int& S_out) {
-  static const double eff[5] = {0.0, 0.71, 0.88, 0.93, 0.96};  // VALU issue rate vs waves per SIMD
-  double best = 1e300;
-  R_out = 32;
-  S_out = 1;
-  for (int R : {32, 16, 8}) {
-    if (R < p.planes) continue;
+  const int64_t want = 4096;
+  const int smax = p.nch < 8 ? (p.nch > 0 ? p.nch : 1) : 8;
+  R_out = 8;
+  S_out = smax;
+  bool found = false;
+  for (int R : {32, 16, 8}) {  // no split needed
+    if (R < p.planes || found) continue;
+    const int rpb = (R / p.planes) * p.planes;
+    if (ceil_div(p.N, 64) * ceil_div(p.Mv, rpb) >= want) {
+      R_out = R;
+      S_out = 1;
+      found = true;
+    }
+  }
+  for (int R : {16, 8}) {
+    if (R < p.planes || found) continue;
     const int rpb = (R / p.planes) * p.planes;
     const int64_t blocks = ceil_div(p.N, 64) * ceil_div(p.Mv, rpb);
-    const int smax = p.nch < 8 ? (p.nch > 0 ? p.nch : 1) : 8;
-    for (int S = 1; S <= smax; ++S) {
-      const int64_t waves = blocks * S;
-      const double per_wave = (double)ceil_div(p.nch > 0 ? p.nch : 1, S) * (R + 3) + 0.5 * R + 2.0 * S;
-      const int64_t per_simd = ceil_div(waves, 1024);
-      const double t = (double)per_simd * per_wave / eff[per_simd < 4 ? per_simd : 4];
-      if (t < best * 0.999) {
-        best = t;
-        R_out = R;
-        S_out = S;
-      }
+    const int64_t S = ceil_div(want, blocks);
+    if (S <= smax) {
+      R_out = R;
+      S_out = (int)S;
+      found = true;
     }
   }
   if (gemm_tune_rows == 8 || gemm_tune_rows == 16 || gemm_tune_rows == 32) {
@@ -304,9 +337,10 @@ void launch(GemmParams& p, hipStream_t s) {
   p.rows_per_block = (R / p.planes) * p.planes;
   p.row_blocks = (int)ceil_div(p.Mv, p.rows_per_block);
   p.rows_fastest = gemm_tune_order;
-  if (R == 32) launch_rs<32, OP_AND>(p, S, s);
-  else if (R == 16) launch_rs<16, OP_AND>(p, S, s);
-  else launch_rs<8, OP_AND>(p, S, s);
+  // (B prefetch registers only where the grid is short of waves anyway: R = 32)
+  if (R == 32) launch_rs<32, OP_AND, true>(p, S, s);
+  else if (R == 16) launch_rs<16, OP_AND, false>(p, S, s);
+  else launch_rs<8, OP_AND, false>(p, S, s);
 }
 
 }  // namespace

@@ -261,11 +261,11 @@ hipError_t launch_alpha_mean_abs(const float* w, int64_t rows, int64_t cols, int
 }
 
 // Eq. 1 quantiser + bit-plane pack.  One workgroup per row m, lane <-> k: the four waves
-// take every fourth group of 8 words, so a lane has 8 independent loads in flight.
-// q = round(L * clamp(x)), ties away from zero, from the single fp32 product L * x.  Plane p
-// of word w is the 64-lane mask of bit p of q and goes to row m * bits + p of `planes`
-// (words up to ld_words are written, zeros past the data).  The row sum of q, needed by the
-// plane GEMM epilogue, is reduced through LDS.
+// take every fourth segment of 16 words, and all 16 loads of a segment are issued before
+// the first of them is used.  q = round(L * clamp(x)), ties away from zero, from the single
+// fp32 product L * x.  Plane p of word w is the 64-lane mask of bit p of q and goes to row
+// m * bits + p of `planes` (words up to ld_words are written, zeros past the data).  The row
+// sum of q, needed by the plane GEMM epilogue, is reduced through LDS.
 __global__ void __launch_bounds__(256)
 quant_pack_kernel(const float* __restrict__ a, int64_t M, int64_t K, int64_t lda, int bits,
                   uint64_t* __restrict__ planes, int64_t ld_words, int32_t* __restrict__ rowsum) {
@@ -277,27 +277,32 @@ quant_pack_kernel(const float* __restrict__ a, int64_t M, int64_t K, int64_t lda
   const float* ar = a + m * lda;
   uint64_t* prow = planes + m * bits * ld_words;
   int32_t sum = 0;
-  for (int64_t w0 = (int64_t)wave * 8; w0 < ld_words; w0 += 32) {
-    float v[8];
+  for (int64_t w0 = (int64_t)wave * kSegWords; w0 < ld_words; w0 += 4 * kSegWords) {
+    float v[kSegWords];
+    if ((w0 + kSegWords) * 64 <= K) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int64_t k = (w0 + j) * 64 + lane;
-      v[j] = (k < K) ? ar[k] : 0.0f;
+      for (int j = 0; j < kSegWords; ++j) v[j] = ar[(w0 + j) * 64 + lane];
+    } else {
+#pragma unroll
+      for (int j = 0; j < kSegWords; ++j) {
+        const int64_t k = (w0 + j) * 64 + lane;
+        v[j] = (k < K) ? ar[k] : 0.0f;
+      }
     }
-    int q[8];
+    int q[kSegWords];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
+    for (int j = 0; j < kSegWords; ++j) {
       q[j] = (int)roundf(__fmul_rn(L, fminf(fmaxf(v[j], 0.0f), 1.0f)));
       sum += q[j];
     }
     for (int p = 0; p < bits; ++p) {
       uint64_t mine = 0;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
+      for (int j = 0; j < kSegWords; ++j) {
         const uint64_t mask = __ballot((q[j] >> p) & 1);
         if (lane == j) mine = mask;
       }
-      if (lane < 8 && w0 + lane < ld_words) prow[p * ld_words + w0 + lane] = mine;
+      if (lane < kSegWords && w0 + lane < ld_words) prow[p * ld_words + w0 + lane] = mine;
     }
   }
 #pragma unroll

@@ -279,3 +279,42 @@ def test_repeatable_and_empty():
     z = B.xnor_gemm(torch.empty((0, 1), dtype=torch.int64, device="cuda"),
                     torch.empty((5, 1), dtype=torch.int64, device="cuda"), 64)
     assert z.shape == (0, 5)
+
+
+# ------------------------------------------------------------------ GEMM kernel shapes
+@pytest.mark.parametrize("rows_per_wave", [8, 16, 32])
+@pytest.mark.parametrize("ksplit", [1, 2, 3, 8])
+def test_gemm_every_kernel_shape(rows_per_wave, ksplit):
+    """Every (rows per wave, K split, workgroup order) the launcher can pick, forced through
+    the tuning hook, on shapes with ragged rows, columns, K tails and bit planes."""
+    L = B.lib()
+    rng = np.random.default_rng(rows_per_wave * 10 + ksplit)
+    try:
+        for order in (0, 1):
+            assert L.bmx_tune_set(2, rows_per_wave) == 0
+            assert L.bmx_tune_set(3, ksplit) == 0
+            assert L.bmx_tune_set(4, order) == 0
+            for (M, N, K) in [(37, 70, 5000), (8, 64, 1024), (100, 129, 3072 + 64)]:
+                A = oracle.binarize_pack(rng.standard_normal((M, K)).astype(np.float32), 1)
+                Bm = oracle.binarize_pack(rng.standard_normal((N, K)).astype(np.float32), 1)
+                got = B.xnor_gemm(dev(A.view(np.int64)), dev(Bm.view(np.int64)), K).cpu().numpy()
+                np.testing.assert_array_equal(got, oracle.xnor_gemm(A, Bm, K))
+            x = rng.standard_normal((19, 2500)).astype(np.float32)
+            w = rng.uniform(-1, 1, (75, 2500)).astype(np.float32)
+            alpha = oracle.alpha_mean_abs(w)
+            ri, rf = oracle.binary_fc(x, w, alpha)
+            Wp = B.binarize_pack(dev(w), 1)
+            np.testing.assert_array_equal(B.binary_fc(dev(x), Wp, integer_out=True).cpu().numpy(), ri)
+            assert_f32_close(B.binary_fc(dev(x), Wp, alpha=dev(alpha)).cpu().numpy(), rf)
+            for bits in (1, 3):
+                if rows_per_wave < bits:
+                    continue
+                a = rng.uniform(0, 1, (21, 2200)).astype(np.float32)
+                wq = rng.standard_normal((70, 2200)).astype(np.float32)
+                S, f = B.quant_gemm(dev(a), dev(wq), bits)
+                rS, r64, r32 = oracle.quant_gemm(a, wq, bits)
+                np.testing.assert_array_equal(S.cpu().numpy(), rS)
+                assert_f32_close(f.cpu().numpy(), r32)
+    finally:
+        for key in (2, 3, 4):
+            L.bmx_tune_set(key, 0)
