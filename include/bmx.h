@@ -91,10 +91,15 @@ int bmx_binary_fc(const float* x, int64_t ldx, const uint64_t* Wp, int64_t ldw_w
                   size_t workspace_bytes, void* stream);
 
 /* Pack OIHW fp32 convolution weights for bmx_binary_conv2d (the offline weight packing
- * of Sec. 2.2.3).  Wp receives O * KH * KW * ceil(C/64) words: for filter o, tap
- * (kh, kw), word cw holds channels 64*cw .. 64*cw+63 (missing channels = 0 bits).  This
- * K order (tap-major, channel-minor) is private to the pair pack/conv; a dot product
- * does not depend on a permutation applied to both operands. */
+ * of Sec. 2.2.3).  Wp is a matrix of O rows of bmx_conv_weight_row_words(C, KH, KW) words:
+ * row o holds filter o, tap (kh, kw) at words (kh*KW + kw)*ceil(C/64) .., word cw of a tap
+ * holding channels 64*cw .. 64*cw+63 (missing channels = 0 bits), followed by zero words up
+ * to the row length (the kernels read filter rows in whole register chunks).  This K order
+ * (tap-major, channel-minor) and the row length are private to the pair pack/conv; a dot
+ * product does not depend on a permutation applied to both operands.
+ * bmx_conv_weight_row_words returns the row length in words (0 if KH, KW or C are outside
+ * the supported set); the caller allocates O times that many words. */
+int64_t bmx_conv_weight_row_words(int C, int KH, int KW);
 int bmx_pack_conv_weights(const float* w_oihw, int O, int C, int KH, int KW, uint64_t* Wp,
                           void* stream);
 

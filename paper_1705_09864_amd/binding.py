@@ -18,7 +18,8 @@ _lib = None
 OP_BINARY_FC, OP_BINARY_CONV2D, OP_QUANT_GEMM = 1, 2, 3
 EXPORTS = ["bmx_binarize_pack", "bmx_xnor_gemm", "bmx_binary_fc", "bmx_pack_conv_weights",
            "bmx_binary_conv2d", "bmx_quant_gemm", "bmx_alpha_mean_abs", "bmx_pack_nchw",
-           "bmx_binary_conv2d_packed", "bmx_workspace_bytes", "bmx_status_string", "bmx_version"]
+           "bmx_binary_conv2d_packed", "bmx_workspace_bytes", "bmx_status_string", "bmx_version",
+           "bmx_conv_weight_row_words"]
 
 _i64, _int, _p, _sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
 
@@ -51,6 +52,8 @@ def lib():
         L.bmx_status_string.argtypes = [_int]
         L.bmx_status_string.restype = ctypes.c_char_p
         L.bmx_version.restype = _int
+        L.bmx_conv_weight_row_words.argtypes = [_int, _int, _int]
+        L.bmx_conv_weight_row_words.restype = _i64
         L.bmx_pack_nchw.argtypes = [_p, _int, _int, _int, _int, _int, _p, _p]
         L.bmx_binary_conv2d_packed.argtypes = [_p, _int, _int, _int, _int, _p, _int, _int, _int, _int,
                                                _int, _p, _p, _p, _p]
@@ -138,7 +141,10 @@ def binary_fc(x, Wp, alpha=None, integer_out=False, out=None, workspace=None, st
 
 def pack_conv_weights(w, stream=None):
     O, C, KH, KW = w.shape
-    Wp = _u64_as_i64((O, KH * KW * ((C + 63) // 64)), w.device)
+    ld = int(lib().bmx_conv_weight_row_words(C, KH, KW))
+    if ld <= 0:
+        raise BmxError(-5, "bmx_conv_weight_row_words")
+    Wp = _u64_as_i64((O, ld), w.device)
     _check(lib().bmx_pack_conv_weights(_ptr(w), O, C, KH, KW, _ptr(Wp), _stream(stream)),
            "bmx_pack_conv_weights")
     return Wp

@@ -50,20 +50,22 @@ QuantWs quant_ws(int64_t M, int64_t N, int64_t K, int bits_a) {
 }  // namespace
 
 namespace bmx {
-extern int conv_filters_per_wave;
+extern int conv_filters_per_wave, conv_path;
 extern int gemm_tune_rows, gemm_tune_ksplit, gemm_tune_order;
 }
 
 extern "C" {
 
 // Undeclared tuning hook used by kernel sweeps (0 restores the automatic choice):
-// key 1 = filters per wave of the stationary convolution kernel, key 2 = rows per wave
-// and key 3 = K-split waves of the GEMM kernel.
+// key 1 = filters per wave of the stationary convolution kernel, key 2 = rows per wave,
+// key 3 = K-split waves and key 4 = workgroup order of the GEMM kernel, key 5 = convolution
+// path (1 stationary, 2 GEMM kernel, 3 general).
 int bmx_tune_set(int key, int value) {
   if (key == 1) bmx::conv_filters_per_wave = value;
   else if (key == 2) bmx::gemm_tune_rows = value;
   else if (key == 3) bmx::gemm_tune_ksplit = value;
   else if (key == 4) bmx::gemm_tune_order = value;
+  else if (key == 5) bmx::conv_path = value;
   else return BMX_ERR_UNSUPPORTED;
   return BMX_OK;
 }
@@ -169,6 +171,12 @@ int bmx_binary_fc(const float* x, int64_t ldx, const uint64_t* Wp, int64_t ldw_w
   return hip_status(bmx::launch_xnor_gemm((const uint32_t*)xp, true, ldp * 2, Wp, ldw_w, batch,
                                           out_features, in_features, alpha, out_i32, out_f32, ldo,
                                           s));
+}
+
+int64_t bmx_conv_weight_row_words(int C, int KH, int KW) {
+  ConvGeom g;
+  if (conv_check(1, C, KH, KW, 1, KH, KW, 1, 0, &g) != BMX_OK) return 0;
+  return bmx::conv_weight_row_words((int64_t)KH * KW * g.Cw);
 }
 
 int bmx_pack_conv_weights(const float* w_oihw, int O, int C, int KH, int KW, uint64_t* Wp,

@@ -13,6 +13,11 @@ struct FastDiv {
   uint32_t mul, sh1, sh2;
 };
 FastDiv make_fast_div(uint32_t d);
+// q = n / d for 0 <= n < 2^32 by multiply-high (Granlund-Montgomery round-up method).
+__device__ static inline uint32_t fast_div(uint32_t n, FastDiv f) {
+  const uint32_t t = __umulhi(f.mul, n);
+  return (t + ((n - t) >> f.sh1)) >> f.sh2;
+}
 
 __host__ __device__ static inline int64_t words_for(int64_t k) { return (k + 63) / 64; }
 
@@ -20,6 +25,19 @@ __host__ __device__ static inline int64_t words_for(int64_t k) { return (k + 63)
 // 32-dword chunks, so that every chunk of a row can be fetched with two 64-byte scalar loads.
 __host__ __device__ static inline int64_t padded_words(int64_t K) {
   return ceil_div(words_for(K), 16) * 16;
+}
+
+// Packed convolution weights: filter o is row o of a matrix with kwords = KH * KW * ceil(C/64)
+// data words per row, zero padded to whole register chunks of the GEMM kernel.  The chunk is
+// 24 or 32 dwords, whichever wastes less padding (3 x 3 kernels over a multiple of 256
+// channels fit 24 exactly).
+__host__ __device__ static inline int conv_weight_chunk_dwords(int64_t kwords) {
+  const int64_t p24 = ceil_div(2 * kwords, 24) * 24, p32 = ceil_div(2 * kwords, 32) * 32;
+  return p24 < p32 ? 24 : 32;
+}
+__host__ __device__ static inline int64_t conv_weight_row_words(int64_t kwords) {
+  const int ch = conv_weight_chunk_dwords(kwords);
+  return ceil_div(2 * kwords, ch) * ch / 2;
 }
 
 // pack.hip -------------------------------------------------------------------
@@ -62,6 +80,13 @@ hipError_t launch_xnor_gemm(const uint32_t* A, bool a_padded, int64_t lda_dw, co
 hipError_t launch_plane_gemm(const uint32_t* planes_rows, int64_t lda_dw, int bits,
                              const int32_t* rowsum, const uint64_t* Wb, int64_t ldb_w, int M, int N,
                              int K, int32_t* S, float* out_f32, int64_t ldo, hipStream_t s);
+
+// The same convolution on the GEMM kernel (filters = A rows streamed through SGPRs, im2col
+// rows gathered per chunk): for K that does not fit the stationary kernel or grids with too
+// few pixel groups for it.
+hipError_t launch_conv_gemm(const uint64_t* Xp, int Nimg, int C, int H, int W, const uint64_t* Wp,
+                            int O, int KH, int KW, int stride, int pad, const float* alpha,
+                            int32_t* out_i32, float* out_f32, hipStream_t s);
 
 // conv.hip -------------------------------------------------------------------
 // Implicit-GEMM convolution on the halo-padded channel-packed image from launch_pack_nchw.

@@ -22,17 +22,12 @@ namespace bmx {
 
 namespace {
 
-// q = n / d for 0 <= n < 2^32 by multiply-high (Granlund-Montgomery round-up method).
-__device__ __forceinline__ uint32_t fast_div(uint32_t n, FastDiv f) {
-  const uint32_t t = __umulhi(f.mul, n);
-  return (t + ((n - t) >> f.sh1)) >> f.sh2;
-}
-
 constexpr int kMaxStationaryWords = 36;
 
 struct ConvParams {
   const uint64_t* Xp;   // halo-padded packed image
-  const uint32_t* Wp;   // [O][KW words] as dwords
+  const uint32_t* Wp;   // [O][ld] words as dwords, KW data words per row
+  int row_pad_dw;       // dwords between the end of a row's data and the next row
   const float* alpha;   // [O] or null
   int32_t* out_i32;
   float* out_f32;
@@ -85,7 +80,7 @@ template <int KW>
 __device__ __forceinline__ void touch_args(const ConvParams& p) {
   asm volatile("" ::"s"(p.Xp), "s"(p.Wp), "s"(p.alpha), "s"(p.out_i32), "s"(p.out_f32), "s"(p.P),
                "s"(p.O), "s"(p.HoWo), "s"(p.Wo), "s"(p.Hp), "s"(p.Wp_pix), "s"(p.Cw), "s"(p.stride),
-               "s"(p.Kreal), "s"(p.cn), "s"(p.div_howo.mul), "s"(p.div_howo.sh1), "s"(p.div_howo.sh2),
+               "s"(p.Kreal), "s"(p.cn), "s"(p.row_pad_dw), "s"(p.div_howo.mul), "s"(p.div_howo.sh1), "s"(p.div_howo.sh2),
                "s"(p.div_wo.mul), "s"(p.div_wo.sh1), "s"(p.div_wo.sh2));
   if constexpr (KW <= 9) touch_offsets<KW>(p);  // longer tables would not stay in SGPRs anyway
 }
@@ -126,10 +121,11 @@ conv_stationary_kernel(const ConvParams p) {
   const int o0 = blockIdx.y * p.cn;
   const int nrows = min(p.cn, p.O - o0);
   const_f32_ptr alpha = (const_f32_ptr)uniform_addr((uint64_t)(uintptr_t)p.alpha + 4 * (int64_t)o0);
-  // Rows o0 .. o0+nrows-1 are one contiguous stream of nrows * NSEG segments.
+  // Rows o0 .. o0+nrows-1 are a stream of nrows * NSEG segments (row_pad_dw dwords of
+  // padding follow the last segment of every row).
   const int nseg_total = nrows * NSEG;
-  const_u32_ptr stream =
-      (const_u32_ptr)uniform_addr((uint64_t)(uintptr_t)p.Wp + (int64_t)o0 * (8 * KW));
+  const_u32_ptr stream = (const_u32_ptr)uniform_addr(
+      (uint64_t)(uintptr_t)p.Wp + (int64_t)o0 * (4 * (2 * KW + p.row_pad_dw)));
   // output: uniform base of (image of lane 0, filter o0), advanced by one plane per row
   const uint32_t img0 = __builtin_amdgcn_readfirstlane(img);
   const uint32_t ooff = ((img - img0) * (uint32_t)p.O * (uint32_t)p.HoWo + rem) * 4u;
@@ -157,7 +153,7 @@ conv_stationary_kernel(const ConvParams p) {
       if (OUT == kOutF32Alpha) asm volatile("" : "+s"(sc[cur]));
       // prefetch the following segment; past the end of this wave's stream the last
       // segment is fetched again, so nothing beyond the weights is ever read
-      src += (left > 0) ? SEG : 0;
+      src += (left > 0) ? (SEG + (seg_in_row == NSEG - 1 ? p.row_pad_dw : 0)) : 0;
       left -= 1;
       buf[nxt].issue(src, pc);
       if (OUT == kOutF32Alpha && (i + 1) % NSEG == NSEG - 1) {
@@ -199,14 +195,14 @@ conv_stationary_kernel(const ConvParams p) {
   if (OUT == kOutF32Alpha) asm volatile("" : "+s"(sc[0]));
 }
 
-// General shape: any number of K words, one filter per wave-row, taps addressed with the
-// same halo trick.  Used when K does not fit the stationary kernel.
+// General shape: any number of K words, one thread per output, taps addressed with the
+// same halo trick.  Only for images too large for the 32-bit offsets of the other two paths.
 __global__ void __launch_bounds__(256)
 conv_general_kernel(const uint64_t* __restrict__ Xp, const uint64_t* __restrict__ Wp,
                     const float* __restrict__ alpha, int32_t* __restrict__ out_i32,
                     float* __restrict__ out_f32, int64_t P, int O, int HoWo, int Wo, int Hp,
-                    int Wp_pix, int Cw, int stride, int KH, int KWid, int Kreal, FastDiv div_howo,
-                    FastDiv div_wo) {
+                    int Wp_pix, int Cw, int stride, int KH, int KWid, int Kreal, int ld_words,
+                    FastDiv div_howo, FastDiv div_wo) {
   const int64_t pix = (int64_t)blockIdx.x * 64 + (threadIdx.x & 63);
   const int o = blockIdx.y * 4 + (threadIdx.x >> 6);
   if (pix >= P || o >= O) return;
@@ -215,7 +211,7 @@ conv_general_kernel(const uint64_t* __restrict__ Xp, const uint64_t* __restrict_
   const uint32_t ho = fast_div(rem, div_wo);
   const uint32_t wo = rem - ho * (uint32_t)Wo;
   const uint64_t* xb = Xp + (((int64_t)img * Hp + ho * stride) * Wp_pix + wo * stride) * Cw;
-  const uint64_t* wrow = Wp + (int64_t)o * KH * KWid * Cw;
+  const uint64_t* wrow = Wp + (int64_t)o * ld_words;
   int pc = 0;
   for (int kh = 0; kh < KH; ++kh)
     for (int kw = 0; kw < KWid; ++kw) {
@@ -253,6 +249,7 @@ FastDiv make_fast_div(uint32_t d) {
 }
 
 int conv_filters_per_wave = 0;  // 0 = automatic; settable for tuning sweeps
+int conv_path = 0;              // 0 = automatic, 1 = stationary, 2 = GEMM kernel, 3 = general
 
 hipError_t launch_binary_conv2d(const uint64_t* Xp, int N, int C, int H, int W, const uint64_t* Wp,
                                 int O, int KH, int KW, int stride, int pad, const float* alpha,
@@ -263,18 +260,29 @@ hipError_t launch_binary_conv2d(const uint64_t* Xp, int N, int C, int H, int W, 
   const int64_t P = (int64_t)N * Ho * Wo;
   const int Hp = H + 2 * pad, Wpp = W + 2 * pad;
   const int kwords = KH * KW * Cw;
+  const int ld_words = (int)conv_weight_row_words(kwords);
   const FastDiv d1 = make_fast_div((uint32_t)(Ho * Wo)), d2 = make_fast_div((uint32_t)Wo);
   const int64_t groups = ceil_div(P, 64);
-  // the stationary kernel addresses the packed image and a wave's output span with 32-bit
-  // byte offsets from uniform bases
-  const bool fits32 = (int64_t)N * Hp * Wpp * Cw * 8 < ((int64_t)1 << 32) &&
-                      (int64_t)(64 / (Ho * Wo) + 2) * O * Ho * Wo * 4 < ((int64_t)1 << 32);
-  if (fits32 && kwords <= kMaxStationaryWords && (kwords == 1 || kwords == 2 || kwords == 4 || kwords == 9 ||
-                                        kwords == 18 || kwords == 25 || kwords == 27 ||
-                                        kwords == 36)) {
+  // both fast kernels address the packed image with 32-bit byte offsets from a uniform base
+  // (the stationary kernel also a wave's output span)
+  const bool image32 = (int64_t)N * Hp * Wpp * Cw * 8 < ((int64_t)1 << 32);
+  const bool fits32 = image32 && (int64_t)(64 / (Ho * Wo) + 2) * O * Ho * Wo * 4 < ((int64_t)1 << 32);
+  const bool stationary_ok =
+      fits32 && (kwords == 1 || kwords == 2 || kwords == 4 || kwords == 9 || kwords == 18 ||
+                 kwords == 25 || kwords == 27 || kwords == 36);
+  // The stationary kernel (whole K in registers, no accumulators) is the faster one on every
+  // shape it can hold; a K beyond 36 words goes to the GEMM kernel, which splits K and rows.
+  int path = conv_path;
+  if (path == 1 && !stationary_ok) path = 0;
+  if (path == 2 && !image32) path = 0;
+  if (path == 0) path = stationary_ok ? 1 : (image32 ? 2 : 3);
+  if (path == 2)
+    return launch_conv_gemm(Xp, N, C, H, W, Wp, O, KH, KW, stride, pad, alpha, out_i32, out_f32, s);
+  if (path == 1) {
     ConvParams p;
     p.Xp = Xp;
     p.Wp = (const uint32_t*)Wp;
+    p.row_pad_dw = 2 * (ld_words - kwords);
     p.alpha = alpha;
     p.out_i32 = out_i32;
     p.out_f32 = out_f32;
@@ -319,7 +327,7 @@ hipError_t launch_binary_conv2d(const uint64_t* Xp, int N, int C, int H, int W, 
   }
   dim3 grid((unsigned)groups, (unsigned)ceil_div(O, 4));
   hipLaunchKernelGGL(conv_general_kernel, grid, dim3(256), 0, s, Xp, Wp, alpha, out_i32, out_f32, P,
-                     O, Ho * Wo, Wo, Hp, Wpp, Cw, stride, KH, KW, C * KH * KW, d1, d2);
+                     O, Ho * Wo, Wo, Hp, Wpp, Cw, stride, KH, KW, C * KH * KW, ld_words, d1, d2);
   return hipGetLastError();
 }
 

@@ -1,27 +1,38 @@
-// xor/and + popcount GEMM on packed operands (VALU integer bound).
+// xor/and + popcount GEMM on packed operands (VALU integer bound), and the implicit-GEMM
+// convolution that runs on the same kernel.
 // Paper: Sec. 2.2.1 (xnor GEMM on packed words), Sec. 2.2.2 / Eq. 2 (output form), Sec. 2.1
-// Eq. 1 for the bit-plane variant.
+// Eq. 1 for the bit-plane variant, Sec. 3.1 for the convolution as a GEMM (M = filters,
+// N = batch * output pixels, K = kh * kw * C).
 //
 // C[m][n] = f(sum_k popcount(A[m][k] op B[n][k])), both operands packed along K.
 //
 // Shape of the kernel.  Lanes span 64 consecutive columns n, so C rows are written
-// coalesced.  A lane keeps a 32-dword chunk of its own B row in registers ("B stationary")
-// and the wave streams rows of A past it: an A row chunk is the same for every lane, so it
-// is fetched with two scalar loads into 32 SGPRs and enters v_xor_b32 / v_and_b32 as the
-// scalar source.  One row step is 64 VALU instructions (v_xor + v_bcnt, the popcount
-// instruction also accumulates) against 128 bytes of scalar loads and nothing else; the
-// scalar loads of the next row are in flight while the current one is consumed.  A wave
-// owns R rows (one accumulator register per row) and a contiguous range of K chunks; the S
-// waves of a workgroup split K between them and add their partial counts through LDS at
-// the end.  Splitting K is what gives a skinny problem (a few hundred rows) enough waves
-// to keep four per SIMD, which the VALU needs to issue at full rate.
+// coalesced.  A lane keeps a chunk of CH (32 or 24) dwords of its own B row in registers
+// ("B stationary") and the wave streams rows of A past it: an A row chunk is the same for
+// every lane, so it is fetched with two scalar loads into SGPRs and enters v_xor_b32 /
+// v_and_b32 as the scalar source.  One row step is 2 * CH VALU instructions (v_xor +
+// v_bcnt, the popcount instruction also accumulates) against 4 * CH bytes of scalar loads
+// and nothing else; the scalar loads of the next row are in flight while the current one is
+// consumed.  A wave owns R rows (one accumulator register per row) and a contiguous range of
+// K chunks; the S waves of a workgroup split K between them and add their partial counts
+// through LDS at the end.  Splitting K is what gives a skinny problem (a few hundred rows)
+// enough waves to keep four per SIMD, which the VALU needs to issue at full rate.
 //
-// The B chunk of a wave (64 rows x 128 bytes) is read with coalesced 16-byte loads and
-// transposed through a wave-private LDS tile (with 32 rows per wave it is also prefetched
-// one chunk ahead; the leaner shapes rely on the other waves of the SIMD instead).
+// GEMM mode: the B chunk of a wave (64 rows x 128 bytes) is read with coalesced 16-byte
+// loads and transposed through a wave-private LDS tile (with 32 rows per wave it is also
+// prefetched one chunk ahead; the leaner shapes rely on the other waves of the SIMD).
+//
+// Convolution mode: column n is output pixel n (flat over image, row, column), its B row is
+// the im2col row of that pixel, which is never formed: word j of it is word (j mod Cw) of tap
+// (j div Cw) and is gathered straight from the halo-padded channel-packed image, 8 bytes per
+// lane and word (neighbouring lanes are neighbouring pixels, so the gather is coalesced; the
+// offset of a word is the same for every lane and is tracked on the scalar unit).
+// A is the filter matrix, rows zero padded to whole chunks.
 //
 // Bit planes (k-bit activations): plane p of row m is virtual row m * planes + p of A, so
 // the main loop is unaware of planes; the final reduction weights plane p by 2^p.
+#include <type_traits>
+
 #include "bmx_internal.h"
 #include "scalar_stream.h"
 
@@ -33,7 +44,7 @@ int gemm_tune_order = 0;   // 1 = row blocks fastest over the workgroup id
 
 namespace {
 
-constexpr int kChunk = 32;  // dwords of K per register chunk
+constexpr int kChunk = 32;  // dwords of K per register chunk in GEMM mode
 constexpr int kTRow = 36;   // LDS row stride of the transposition tile (dwords, 16-byte multiple)
 constexpr int kTileDw = 64 * kTRow;
 
@@ -41,33 +52,40 @@ enum GemmOut { kGemmI32 = 0, kGemmF32 = 1, kGemmF32Alpha = 2, kGemmPlanes = 3 };
 
 struct GemmParams {
   const uint32_t* A;      // [Mv][lda] dwords, virtual rows (row m, plane p -> m * planes + p)
-  const uint32_t* B;      // [N][ldb] dwords
+  const uint32_t* B;      // GEMM: [N][ldb] dwords.  Convolution: the packed image Xp
   int64_t lda, ldb;       // dwords
   int Mv, N;
   int planes;             // 1 in xor mode
   int rows_per_block;     // virtual rows per workgroup, a multiple of planes, <= R
-  int nch;                // chunks the main loop covers; A rows are readable up to nch * 32 dwords
+  int nch;                // chunks the main loop covers; A rows are readable up to nch * CH dwords
   int Kd;                 // dwords of a B row that may be read (the rest of a chunk reads as 0)
   int tail0, tail1;       // dword range finished in the epilogue with plain loads (may be empty)
   int Kreal;              // K in bits (xor modes)
   const int32_t* rowsum;  // planes mode: sum_k q[m][k]
-  const float* alpha;     // per column n (F32Alpha)
+  const float* alpha;     // GEMM: per column n.  Convolution: per row (filter) m
   float levels;           // planes mode: 2^bits - 1
   int32_t* C_i32;
   float* C_f32;
-  int64_t ldc;
+  int64_t ldc;            // GEMM: elements between C rows.  Convolution: Ho * Wo
   int out;                // GemmOut
   int row_blocks;         // ceil(Mv / rows_per_block)
   int rows_fastest;       // tuning: row blocks fastest over the workgroup id instead
+  // convolution geometry (N = images * Ho * Wo output pixels, Mv = O filters)
+  int HoWo, Wo, Hp, Wp_pix, Cw, stride, KWid;
+  FastDiv div_howo, div_wo, div_rw;  // div_rw: by KW * Cw, the words of one kernel row
 };
 
-// One 32-dword chunk of an A row in SGPRs.  The loads are volatile asm so that their
+// One CH-dword chunk of an A row in SGPRs.  The loads are volatile asm so that their
 // position relative to the waits is exactly as written.
+template <int CH>
 struct ARow {
-  u32x16 lo, hi;
+  static_assert(CH == 32 || CH == 24, "chunk is two scalar loads: 16 + 16 or 16 + 8 dwords");
+  u32x16 lo;
+  typename std::conditional<CH == 32, u32x16, u32x8>::type hi;
   __device__ __forceinline__ void issue(const_u32_ptr src) {
     asm volatile("s_load_dwordx16 %0, %1, 0x0" : "=s"(lo) : "s"(src));
-    asm volatile("s_load_dwordx16 %0, %1, 0x40" : "=s"(hi) : "s"(src));
+    if constexpr (CH == 32) asm volatile("s_load_dwordx16 %0, %1, 0x40" : "=s"(hi) : "s"(src));
+    else asm volatile("s_load_dwordx8 %0, %1, 0x40" : "=s"(hi) : "s"(src));
   }
   // after s_waitcnt lgkmcnt(0): make every later use depend on this point (and keep the
   // destination registers allocated up to it)
@@ -82,20 +100,20 @@ struct ARow {
   }
 };
 
-template <bool OP_AND, int J = 0>
-__device__ __forceinline__ void row_popcount(const ARow& a, const uint32_t (&b)[kChunk], int& acc) {
-  if constexpr (J < kChunk) {
+template <int CH, bool OP_AND, int J = 0>
+__device__ __forceinline__ void row_popcount(const ARow<CH>& a, const uint32_t (&b)[CH], int& acc) {
+  if constexpr (J < CH) {
     const uint32_t av = a.template get<J>();
     acc += __builtin_popcount(OP_AND ? (b[J] & av) : (b[J] ^ av));
     asm volatile("" : "+v"(acc));  // keep the op / popcount-accumulate pairs as written
-    row_popcount<OP_AND, J + 1>(a, b, acc);
+    row_popcount<CH, OP_AND, J + 1>(a, b, acc);
   }
 }
 
 // The R row steps of one chunk, unrolled so that every accumulator has a fixed register.
 // Invariant on entry of step r: the loads of row r are in flight in buf[r & 1].
-template <int R, bool OP_AND, int r = 0>
-__device__ __forceinline__ void row_steps(ARow (&buf)[2], const uint32_t (&b)[kChunk], int (&acc)[R],
+template <int R, int CH, bool OP_AND, int r = 0>
+__device__ __forceinline__ void row_steps(ARow<CH> (&buf)[2], const uint32_t (&b)[CH], int (&acc)[R],
                                           const_u32_ptr& src, uint64_t row_bytes, int& rows_valid,
                                           const_u32_ptr next_chunk_row0) {
   if constexpr (r < R) {
@@ -112,15 +130,17 @@ __device__ __forceinline__ void row_steps(ARow (&buf)[2], const uint32_t (&b)[kC
       src = next_chunk_row0;
     }
     buf[(r + 1) & 1].issue(src);
-    row_popcount<OP_AND>(buf[r & 1], b, acc[r]);
-    row_steps<R, OP_AND, r + 1>(buf, b, acc, src, row_bytes, rows_valid, next_chunk_row0);
+    row_popcount<CH, OP_AND>(buf[r & 1], b, acc[r]);
+    row_steps<R, CH, OP_AND, r + 1>(buf, b, acc, src, row_bytes, rows_valid, next_chunk_row0);
   }
 }
 
-template <int R, bool OP_AND, bool PF>
+template <int R, int CH, bool OP_AND, bool PF, bool CONV>
 __global__ void __launch_bounds__(512, PF ? 4 : 6)
 gemm_kernel(const GemmParams p) {
   static_assert(R % 2 == 0, "buffer parity must repeat from chunk to chunk");
+  static_assert(CONV || CH == kChunk, "the LDS transposition tile is laid out for 32-dword chunks");
+  static_assert(!(CONV && PF), "the gather has no staging registers to prefetch into");
   extern __shared__ __align__(16) uint32_t lds[];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -136,19 +156,36 @@ gemm_kernel(const GemmParams p) {
   int rows_valid = min(p.rows_per_block, p.Mv - m0);
   const int c0 = (int)((int64_t)wave * p.nch / S);
   const int c1 = (int)((int64_t)(wave + 1) * p.nch / S);
+  const int n = n0 + lane;
+  const int nc = min(n, p.N - 1);
+
+  // Convolution: where pixel nc sits in the packed image and in the NCHW output.
+  uint32_t xoff = 0;      // byte offset of the pixel's receptive field in Xp
+  int64_t lane_off = nc;  // element offset of (row 0, column n) in C; rows are ldc apart
+  if constexpr (CONV) {
+    const uint32_t img = fast_div((uint32_t)nc, p.div_howo);
+    const uint32_t rem = (uint32_t)nc - img * (uint32_t)p.HoWo;
+    const uint32_t ho = fast_div(rem, p.div_wo);
+    const uint32_t wo = rem - ho * (uint32_t)p.Wo;
+    xoff = (((img * (uint32_t)p.Hp + ho * (uint32_t)p.stride) * (uint32_t)p.Wp_pix +
+             wo * (uint32_t)p.stride) * (uint32_t)p.Cw) * 8u;
+    lane_off = (int64_t)img * p.Mv * p.HoWo + rem;
+  }
 
   int acc[R];
 #pragma unroll
   for (int r = 0; r < R; ++r) acc[r] = 0;
 
   if (c0 < c1) {
-    // ---- B chunk loader: lane -> (row within 8, 16-byte piece of the 128-byte chunk)
+    // ---- GEMM B chunk loader: lane -> (row within 8, 16-byte piece of the 128-byte chunk)
     const int srow = lane >> 3, spiece = lane & 7;
     const uint32_t* bsrc[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-      bsrc[i] = p.B + (int64_t)min(n0 + i * 8 + srow, p.N - 1) * p.ldb + spiece * 4;
     uint4 stage[8];
+    if constexpr (!CONV) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        bsrc[i] = p.B + (int64_t)min(n0 + i * 8 + srow, p.N - 1) * p.ldb + spiece * 4;
+    }
     auto fetch = [&](int c) {
       if ((c + 1) * kChunk <= p.Kd) {  // whole chunk inside the rows (wave-uniform)
 #pragma unroll
@@ -170,39 +207,69 @@ gemm_kernel(const GemmParams p) {
       }
     };
     uint32_t* tile = lds + wave * kTileDw;
+    // ---- convolution B chunk loader.  Word j of the im2col row is word j % rw of kernel row
+    // j / rw (rw = KW * Cw words, contiguous both in K order and in the packed image), so the
+    // chunk is walked with a running (word in row, byte offset) pair: one division per chunk.
+    const char* xbase = (const char*)p.B;
+    const uint32_t rw = (uint32_t)(p.KWid * p.Cw);
+    const uint32_t row_skip = (uint32_t)(p.Wp_pix * p.Cw) * 8u - rw * 8u;  // end of row -> next row
+    auto gather = [&](int c, uint32_t (&b)[CH]) {
+      const uint32_t j0 = (uint32_t)c * (CH / 2);  // wave-uniform
+      const uint32_t kh = fast_div(j0, p.div_rw);
+      uint32_t r = j0 - kh * rw;
+      uint32_t off = kh * (uint32_t)(p.Wp_pix * p.Cw) * 8u + r * 8u;
+      const bool whole = (int)(2 * j0 + CH) <= p.Kd;  // no word of the chunk is padding
+#pragma unroll
+      for (int i = 0; i < CH / 2; ++i) {
+        uint64_t v = 0;
+        if (whole || (int)(2 * (j0 + i)) < p.Kd) v = *(const uint64_t*)(xbase + off + xoff);
+        b[2 * i] = (uint32_t)v;
+        b[2 * i + 1] = (uint32_t)(v >> 32);
+        r += 1;
+        off += 8;
+        if (r == rw) {
+          r = 0;
+          off += row_skip;
+        }
+      }
+    };
 
     // ---- A stream (wave-uniform addresses)
     const uint64_t row_bytes = (uint64_t)p.lda * 4;
     const uint64_t arow0 = uniform_addr((uint64_t)(uintptr_t)p.A + (int64_t)m0 * p.lda * 4);
-    ARow buf[2];
-    const_u32_ptr src = (const_u32_ptr)(arow0 + (uint64_t)c0 * (kChunk * 4));
+    ARow<CH> buf[2];
+    const_u32_ptr src = (const_u32_ptr)(arow0 + (uint64_t)c0 * (CH * 4));
     buf[0].issue(src);
     // Lane r touches row r of the chunk that comes next, so that the scalar loads of a row
     // step find their line in L2 instead of paying a cold miss each (the first pass over
     // a block would otherwise cost one memory round trip per row).
     const uint32_t* warm_row = p.A + (int64_t)(m0 + min(lane, rows_valid - 1)) * p.lda;
-    uint32_t warm = warm_row[(int64_t)c0 * kChunk];
+    uint32_t warm = warm_row[(int64_t)c0 * CH];
     if (PF) fetch(c0);
     for (int c = c0; c < c1; ++c) {
-      if (!PF) fetch(c);
-      // transpose the staged chunk: row n of the tile is lane n's 32 dwords
+      uint32_t b[CH];
+      if constexpr (CONV) {
+        gather(c, b);
+      } else {
+        if (!PF) fetch(c);
+        // transpose the staged chunk: row n of the tile is lane n's 32 dwords
 #pragma unroll
-      for (int i = 0; i < 8; ++i) *(uint4*)(tile + (i * 8 + srow) * kTRow + spiece * 4) = stage[i];
-      uint32_t b[kChunk];
+        for (int i = 0; i < 8; ++i) *(uint4*)(tile + (i * 8 + srow) * kTRow + spiece * 4) = stage[i];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const uint4 v = *(const uint4*)(tile + lane * kTRow + j * 4);
-        b[4 * j] = v.x;
-        b[4 * j + 1] = v.y;
-        b[4 * j + 2] = v.z;
-        b[4 * j + 3] = v.w;
+        for (int j = 0; j < 8; ++j) {
+          const uint4 v = *(const uint4*)(tile + lane * kTRow + j * 4);
+          b[4 * j] = v.x;
+          b[4 * j + 1] = v.y;
+          b[4 * j + 2] = v.z;
+          b[4 * j + 3] = v.w;
+        }
+        if (PF && c + 1 < c1) fetch(c + 1);
       }
-      if (PF && c + 1 < c1) fetch(c + 1);
       const int cn = min(c + 1, c1 - 1);  // after the last chunk the last row 0 is fetched again
-      const const_u32_ptr next_row0 = (const_u32_ptr)(arow0 + (uint64_t)cn * (kChunk * 4));
+      const const_u32_ptr next_row0 = (const_u32_ptr)(arow0 + (uint64_t)cn * (CH * 4));
       asm volatile("" ::"v"(warm));  // consume the previous touch
-      warm = warm_row[(int64_t)cn * kChunk];
-      row_steps<R, OP_AND>(buf, b, acc, src, row_bytes, rows_valid, next_row0);
+      warm = warm_row[(int64_t)cn * CH];
+      row_steps<R, CH, OP_AND>(buf, b, acc, src, row_bytes, rows_valid, next_row0);
     }
     // Drain the last prefetch.  Its destination registers must stay allocated until the
     // data has landed: were they dead here, the code that follows could be given the same
@@ -212,13 +279,11 @@ gemm_kernel(const GemmParams p) {
     asm volatile("" ::"v"(warm));
   }
 
-  const int n = n0 + lane;
-  const int nc = min(n, p.N - 1);
   float al = 1.0f;
-  if (p.out == kGemmF32Alpha) al = p.alpha[nc];
+  if (!CONV && p.out == kGemmF32Alpha) al = p.alpha[nc];
   auto finish = [&](int64_t m, int total) {  // count of output row m -> result -> C[m][n]
     if (n < p.N) {
-      const int64_t idx = m * p.ldc + n;
+      const int64_t idx = m * p.ldc + lane_off;
       if (p.out == kGemmPlanes) {
         const int sv = 2 * total - p.rowsum[m];
         if (p.C_i32) p.C_i32[idx] = sv;
@@ -227,7 +292,7 @@ gemm_kernel(const GemmParams p) {
         const int dot = p.Kreal - 2 * total;
         if (p.out == kGemmI32) p.C_i32[idx] = dot;
         else if (p.out == kGemmF32) p.C_f32[idx] = (float)dot;
-        else p.C_f32[idx] = al * (float)dot;
+        else p.C_f32[idx] = (CONV ? p.alpha[m] : al) * (float)dot;
       }
     }
   };
@@ -278,10 +343,11 @@ gemm_kernel(const GemmParams p) {
   }
 }
 
-template <int R, bool OP_AND, bool PF>
+template <int R, int CH, bool OP_AND, bool PF, bool CONV>
 void launch_rs(const GemmParams& p, int S, hipStream_t s) {
-  auto kern = gemm_kernel<R, OP_AND, PF>;
-  const size_t lds_bytes = (size_t)S * (kTileDw > R * 64 ? kTileDw : R * 64) * 4;
+  auto kern = gemm_kernel<R, CH, OP_AND, PF, CONV>;
+  const int tile_dw = CONV ? 0 : kTileDw;
+  const size_t lds_bytes = (size_t)S * (tile_dw > R * 64 ? tile_dw : R * 64) * 4;
   static bool raised = false;  // more than the default 64 KiB of dynamic LDS for S = 8
   if (!raised) {
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
@@ -294,15 +360,17 @@ void launch_rs(const GemmParams& p, int S, hipStream_t s) {
 // Rows per wave and K split.  The kernel runs at full VALU rate once about four waves sit
 // on each of the 1024 SIMDs, and its fixed costs (launch, first B chunk, store drain) do not
 // shrink with fatter waves, so: the largest R whose grid alone reaches 4096 waves, else the
-// smallest K split that gets a 16-row (then 8-row) grid there.
-void choose_shape(const GemmParams& p, int& R_out, int& S_out) {
+// smallest K split that gets a 16-row (then 8-row) grid there.  Splits beyond 4 are a last
+// resort: the LDS a workgroup then holds (transposition tiles, partial counts) cuts the
+// workgroups per CU, which costs more than the extra waves bring.
+void choose_shape(const GemmParams& p, bool allow32, int& R_out, int& S_out) {
   const int64_t want = 4096;
   const int smax = p.nch < 8 ? (p.nch > 0 ? p.nch : 1) : 8;
   R_out = 8;
-  S_out = smax;
+  S_out = smax < 4 ? smax : 4;
   bool found = false;
   for (int R : {32, 16, 8}) {  // no split needed
-    if (R < p.planes || found) continue;
+    if (R < p.planes || found || (R == 32 && !allow32)) continue;
     const int rpb = (R / p.planes) * p.planes;
     if (ceil_div(p.N, 64) * ceil_div(p.Mv, rpb) >= want) {
       R_out = R;
@@ -315,13 +383,18 @@ void choose_shape(const GemmParams& p, int& R_out, int& S_out) {
     const int rpb = (R / p.planes) * p.planes;
     const int64_t blocks = ceil_div(p.N, 64) * ceil_div(p.Mv, rpb);
     const int64_t S = ceil_div(want, blocks);
-    if (S <= smax) {
+    if (S <= smax && S <= 4) {
       R_out = R;
       S_out = (int)S;
       found = true;
     }
   }
-  if (gemm_tune_rows == 8 || gemm_tune_rows == 16 || gemm_tune_rows == 32) {
+  if (!found && p.planes <= 8) {  // small problem: 8 rows per wave and as much split as helps
+    const int64_t blocks = ceil_div(p.N, 64) * ceil_div(p.Mv, (8 / p.planes) * p.planes);
+    const int64_t S = ceil_div(want, blocks);
+    S_out = (int)(S < smax ? S : smax);
+  }
+  if (gemm_tune_rows == 8 || gemm_tune_rows == 16 || (gemm_tune_rows == 32 && allow32)) {
     if (gemm_tune_rows >= p.planes) R_out = gemm_tune_rows;
   }
   if (gemm_tune_ksplit > 0) {
@@ -333,14 +406,19 @@ void choose_shape(const GemmParams& p, int& R_out, int& S_out) {
 template <bool OP_AND>
 void launch(GemmParams& p, hipStream_t s) {
   int R, S;
-  choose_shape(p, R, S);
+  choose_shape(p, true, R, S);
   p.rows_per_block = (R / p.planes) * p.planes;
   p.row_blocks = (int)ceil_div(p.Mv, p.rows_per_block);
   p.rows_fastest = gemm_tune_order;
   // (B prefetch registers only where the grid is short of waves anyway: R = 32)
-  if (R == 32) launch_rs<32, OP_AND, true>(p, S, s);
-  else if (R == 16) launch_rs<16, OP_AND, false>(p, S, s);
-  else launch_rs<8, OP_AND, false>(p, S, s);
+  if (R == 32) launch_rs<32, kChunk, OP_AND, true, false>(p, S, s);
+  else if (R == 16) launch_rs<16, kChunk, OP_AND, false, false>(p, S, s);
+  else launch_rs<8, kChunk, OP_AND, false, false>(p, S, s);
+}
+
+void no_conv(GemmParams& p) {
+  p.HoWo = p.Wo = p.Hp = p.Wp_pix = p.Cw = p.stride = p.KWid = 1;
+  p.div_howo = p.div_wo = p.div_rw = make_fast_div(1);
 }
 
 }  // namespace
@@ -349,6 +427,7 @@ hipError_t launch_xnor_gemm(const uint32_t* A, bool a_padded, int64_t lda_dw, co
                             int64_t ldb_w, int M, int N, int K, const float* alpha_n, int32_t* C_i32,
                             float* C_f32, int64_t ldc, hipStream_t s) {
   GemmParams p;
+  no_conv(p);
   p.A = A;
   p.B = (const uint32_t*)B;
   p.lda = lda_dw;
@@ -381,6 +460,7 @@ hipError_t launch_plane_gemm(const uint32_t* planes_rows, int64_t lda_dw, int bi
                              const int32_t* rowsum, const uint64_t* Wb, int64_t ldb_w, int M, int N,
                              int K, int32_t* S, float* out_f32, int64_t ldo, hipStream_t s) {
   GemmParams p;
+  no_conv(p);
   p.A = planes_rows;
   p.B = (const uint32_t*)Wb;
   p.lda = lda_dw;
@@ -400,6 +480,59 @@ hipError_t launch_plane_gemm(const uint32_t* planes_rows, int64_t lda_dw, int bi
   p.ldc = ldo;
   p.out = kGemmPlanes;
   launch<true>(p, s);
+  return hipGetLastError();
+}
+
+hipError_t launch_conv_gemm(const uint64_t* Xp, int Nimg, int C, int H, int W, const uint64_t* Wp,
+                            int O, int KH, int KW, int stride, int pad, const float* alpha,
+                            int32_t* out_i32, float* out_f32, hipStream_t s) {
+  const int Ho = (H + 2 * pad - KH) / stride + 1;
+  const int Wo = (W + 2 * pad - KW) / stride + 1;
+  const int Cw = (int)words_for(C);
+  const int kwords = KH * KW * Cw;
+  const int ld_words = (int)conv_weight_row_words(kwords);
+  const int CH = conv_weight_chunk_dwords(kwords);
+  GemmParams p;
+  p.A = (const uint32_t*)Wp;
+  p.B = (const uint32_t*)Xp;
+  p.lda = 2 * (int64_t)ld_words;
+  p.ldb = 0;
+  p.Mv = O;
+  p.N = Nimg * Ho * Wo;
+  p.planes = 1;
+  p.Kd = 2 * kwords;
+  p.nch = 2 * ld_words / CH;
+  p.tail0 = p.tail1 = 0;
+  p.Kreal = C * KH * KW;
+  p.rowsum = nullptr;
+  p.alpha = alpha;
+  p.levels = 1.0f;
+  p.C_i32 = out_i32;
+  p.C_f32 = out_f32;
+  p.ldc = (int64_t)Ho * Wo;
+  p.out = out_i32 ? kGemmI32 : (alpha ? kGemmF32Alpha : kGemmF32);
+  p.HoWo = Ho * Wo;
+  p.Wo = Wo;
+  p.Hp = H + 2 * pad;
+  p.Wp_pix = W + 2 * pad;
+  p.Cw = Cw;
+  p.stride = stride;
+  p.KWid = KW;
+  p.div_howo = make_fast_div((uint32_t)(Ho * Wo));
+  p.div_wo = make_fast_div((uint32_t)Wo);
+  p.div_rw = make_fast_div((uint32_t)(KW * Cw));
+  int R, S;
+  choose_shape(p, false, R, S);  // (32 rows per wave measured slower than 16 on every shape)
+  p.rows_per_block = R;
+  p.row_blocks = (int)ceil_div(p.Mv, R);
+  p.rows_fastest = gemm_tune_order;
+  if (CH == 32) {
+    if (R == 16) launch_rs<16, 32, false, false, true>(p, S, s);
+    else launch_rs<8, 32, false, false, true>(p, S, s);
+  } else {
+    if (R == 16) launch_rs<16, 24, false, false, true>(p, S, s);
+    else launch_rs<8, 24, false, false, true>(p, S, s);
+  }
   return hipGetLastError();
 }
 

@@ -201,24 +201,28 @@ hipError_t launch_pack_nchw(const float* x, int N, int C, int H, int W, int pad,
 }
 
 // Offline weight packing for the convolution: one thread per output word.
-// Wp[o][(kh*KW + kw)*Cw + cw] bit c = (w[o][64cw + c][kh][kw] >= 0).
+// Wp[o][(kh*KW + kw)*Cw + cw] bit c = (w[o][64cw + c][kh][kw] >= 0); rows are ld words apart
+// and the words between the data and ld are written as zero.
 __global__ void __launch_bounds__(256)
-pack_conv_weights_kernel(const float* __restrict__ w, int O, int C, int KH, int KW, int Cw,
+pack_conv_weights_kernel(const float* __restrict__ w, int O, int C, int KH, int KW, int Cw, int ld,
                          uint64_t* __restrict__ Wp) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int64_t total = (int64_t)O * KH * KW * Cw;
+  const int64_t total = (int64_t)O * ld;
   if (idx >= total) return;
-  const int cw = (int)(idx % Cw);
-  const int64_t t = idx / Cw;
-  const int kw = (int)(t % KW);
-  const int kh = (int)((t / KW) % KH);
-  const int64_t o = t / ((int64_t)KW * KH);
+  const int64_t o = idx / ld;
+  const int j = (int)(idx - o * ld);
   uint64_t word = 0;
-  for (int c = 0; c < 64; ++c) {
-    const int ch = cw * 64 + c;
-    if (ch < C) {
-      const float v = w[((o * C + ch) * KH + kh) * KW + kw];
-      if (v >= 0.0f) word |= (uint64_t)1 << c;
+  if (j < KH * KW * Cw) {
+    const int cw = j % Cw;
+    const int t = j / Cw;
+    const int kw = t % KW;
+    const int kh = t / KW;
+    for (int c = 0; c < 64; ++c) {
+      const int ch = cw * 64 + c;
+      if (ch < C) {
+        const float v = w[((o * C + ch) * KH + kh) * KW + kw];
+        if (v >= 0.0f) word |= (uint64_t)1 << c;
+      }
     }
   }
   Wp[idx] = word;
@@ -227,9 +231,10 @@ pack_conv_weights_kernel(const float* __restrict__ w, int O, int C, int KH, int 
 hipError_t launch_pack_conv_weights(const float* w, int O, int C, int KH, int KW, uint64_t* Wp,
                                     hipStream_t s) {
   const int Cw = (int)words_for(C);
-  const int64_t total = (int64_t)O * KH * KW * Cw;
+  const int ld = (int)conv_weight_row_words((int64_t)KH * KW * Cw);
+  const int64_t total = (int64_t)O * ld;
   hipLaunchKernelGGL(pack_conv_weights_kernel, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, s,
-                     w, O, C, KH, KW, Cw, Wp);
+                     w, O, C, KH, KW, Cw, ld, Wp);
   return hipGetLastError();
 }
 

@@ -318,3 +318,62 @@ def test_gemm_every_kernel_shape(rows_per_wave, ksplit):
     finally:
         for key in (2, 3, 4):
             L.bmx_tune_set(key, 0)
+
+
+# ------------------------------------------------------------------ convolution kernel paths
+BIG_K_CONV_CASES = [
+    # K beyond the 36 words the register-stationary kernel holds: runs on the GEMM kernel
+    # N, C, H, W, O, k, s, p
+    (1, 320, 6, 7, 20, 3, 1, 1),      # 45 words, 24-dword chunks
+    (2, 128, 9, 9, 33, 5, 2, 2),      # 50 words
+    (1, 64, 12, 12, 5, 7, 1, 3),      # 49 words
+    (2, 500, 5, 5, 70, 1, 1, 0),      # 8 words, 1x1, ragged channels
+    (1, 1024, 4, 4, 17, 3, 1, 1),     # 144 words, many chunks
+    (3, 200, 12, 12, 64, 5, 1, 0),    # the paper's efficiency shape (5x5, 64 filters, 8x8 out)
+]
+
+
+@pytest.mark.parametrize("N,C,H,W,O,k,s,p", BIG_K_CONV_CASES)
+def test_conv_big_k(N, C, H, W, O, k, s, p):
+    rng = np.random.default_rng(N + 10 * C + 100 * H + 1000 * O + k + s + p)
+    x = rng.standard_normal((N, C, H, W)).astype(np.float32)
+    w = rng.standard_normal((O, C, k, k)).astype(np.float32)
+    alpha = oracle.alpha_mean_abs(w)
+    ri, rf = oracle.binary_conv2d(x, w, s, p, alpha)
+    np.testing.assert_array_equal(run_conv(x, w, s, p, integer_out=True), ri)
+    assert_f32_close(run_conv(x, w, s, p, alpha=alpha), rf)
+
+
+@pytest.mark.parametrize("path", [1, 2, 3])
+def test_conv_every_path(path):
+    """The three convolution kernels (register-stationary, GEMM kernel, one-thread-per-output),
+    each forced through the tuning hook on the shapes it accepts, with every K split."""
+    L = B.lib()
+    try:
+        assert L.bmx_tune_set(5, path) == 0
+        for ksplit in ((0, 2, 3) if path == 2 else (0,)):
+            L.bmx_tune_set(3, ksplit)
+            for (N, C, H, W, O, k, s, p) in CONV_CASES[:10] + BIG_K_CONV_CASES[:2]:
+                rng = np.random.default_rng(N + 10 * C + 100 * H + 1000 * O + k + s + p + path)
+                x = rng.standard_normal((N, C, H, W)).astype(np.float32)
+                w = rng.standard_normal((O, C, k, k)).astype(np.float32)
+                alpha = oracle.alpha_mean_abs(w)
+                ri, rf = oracle.binary_conv2d(x, w, s, p, alpha)
+                np.testing.assert_array_equal(run_conv(x, w, s, p, integer_out=True), ri)
+                assert_f32_close(run_conv(x, w, s, p, alpha=alpha), rf)
+    finally:
+        L.bmx_tune_set(5, 0)
+        L.bmx_tune_set(3, 0)
+
+
+def test_conv_weight_rows_are_zero_padded():
+    """Packed filter rows are as long as bmx_conv_weight_row_words says and zero past the data."""
+    rng = np.random.default_rng(3)
+    for (O, C, k) in [(3, 64, 3), (2, 256, 3), (2, 130, 5), (4, 1, 1)]:
+        w = rng.standard_normal((O, C, k, k)).astype(np.float32)
+        Wp = host_u64(B.pack_conv_weights(dev(w)))
+        kwords = k * k * ((C + 63) // 64)
+        assert Wp.shape == (O, B.lib().bmx_conv_weight_row_words(C, k, k)) and Wp.shape[1] >= kwords
+        assert (Wp[:, kwords:] == 0).all()
+        ref = oracle.binarize_pack(np.transpose(w, (0, 2, 3, 1)).reshape(O * k * k, C), 1)
+        np.testing.assert_array_equal(Wp[:, :kwords].reshape(O * k * k, -1), ref)
