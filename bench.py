@@ -269,6 +269,18 @@ def main():
         other["config5_quant_gemm_call_2planes"] = alu(2.0 * 2 * 1024 * 1024 * 4096, kernel_us(
             lambda: B.quant_gemm(a5, w5, 2, want_int=False, out_float=o5, workspace=ws5), 20))
 
+        # the paper's own efficiency workload (Sec. 3.1): 5x5 kernels, 64 filters, batch 200,
+        # 8x8 outputs -> GEMM view M = 64, N = 12800, K = 25 * C_in, C_in swept
+        for cin in (64, 128, 256, 512):
+            xq = torch.empty((200, cin, 12, 12), dtype=torch.float32, device="cuda").normal_()
+            wq = torch.empty((64, cin, 5, 5), dtype=torch.float32, device="cuda").normal_()
+            Wq, alq = B.pack_conv_weights(wq), B.alpha_mean_abs(wq)
+            oq = torch.empty((200, 64, 8, 8), dtype=torch.float32, device="cuda")
+            wsq = torch.empty(B.workspace_bytes(B.OP_BINARY_CONV2D, (200, cin, 12, 12, 64, 5, 5, 1, 0)),
+                              dtype=torch.uint8, device="cuda")
+            other["paper_sec3_1_conv5x5_cin%d_call" % cin] = alu(2.0 * 64 * 12800 * 25 * cin, kernel_us(
+                lambda: B.binary_conv2d(xq, Wq, 64, 5, 5, 1, 0, alpha=alq, out=oq, workspace=wsq)))
+
     # ------------------------------------------------------------------ CPU oracle beside it
     cpu = None
     if not args.no_cpu_baseline:
