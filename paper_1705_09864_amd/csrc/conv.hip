@@ -303,13 +303,15 @@ hipError_t launch_binary_conv2d(const uint64_t* Xp, int N, int C, int H, int W, 
         for (int cw = 0; cw < Cw; ++cw)
           p.off[(kh * KW + kw) * Cw + cw] = (kh * Wpp + kw) * Cw + cw;
     // Filters per wave.  A wave pays its gather once and then streams cn filter rows, so
-    // more filters per wave amortise the gather better, but the grid must still put about
-    // six waves on each of the 1024 SIMDs; below 8 filters the gather dominates (sweeps of
-    // the ResNet-stage shapes put the optimum at 8 whenever the grid is short of waves).
+    // more filters per wave amortise the gather better (below 8 the gather dominates), but
+    // the grid should still fill the chip.  The 36-word kernel holds 88 VGPRs, i.e. five
+    // waves per SIMD: a grid of at most 5 * 1024 waves is resident at once, and sweeps of the
+    // ResNet-stage shapes put the optimum at the smallest cn >= 8 that gets there (a grid
+    // slightly over it pays a second, mostly empty round).
     int cn = conv_filters_per_wave;
     if (cn <= 0) {
-      cn = O;
-      while (cn > 8 && groups * ceil_div(O, cn) < 6144) cn = (cn + 1) / 2;
+      cn = 8;
+      while (cn < O && cn < 64 && groups * ceil_div(O, cn) > 5 * 1024) ++cn;
     }
     p.cn = cn;
     const int cblocks = (int)ceil_div(O, cn);
