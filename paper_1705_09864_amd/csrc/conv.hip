@@ -37,14 +37,18 @@ struct ConvParams {
   int off[kMaxStationaryWords];  // word offset of K-word j relative to the pixel base
 };
 
-// A filter row of 2*KW dwords is consumed in NSEG segments of SEG dwords; two SGPR buffers
-// alternate so that the scalar loads of the next segment are in flight while the VALU works
-// through the current one.
+// The filter rows of a wave are consumed in steps of at most 36 dwords, two sets of SGPR
+// buffers alternating so that the scalar loads of the next step are in flight while the VALU
+// works through the current one.  A scalar wait always covers every outstanding load, so a
+// wave pays one memory round trip per step; steps are therefore made as large as the SGPR
+// file allows: a long row (more than 36 dwords) is NSEG segments of SEG dwords, a short row
+// (18 dwords or less) is fetched RPS rows at a time.
 template <int KW>
-struct SegShape {
+struct StepShape {
   static constexpr int kDwords = 2 * KW;
-  static constexpr int kNseg = (kDwords + 31) / 32;
+  static constexpr int kNseg = kDwords > 36 ? (kDwords + 35) / 36 : 1;
   static constexpr int kSeg = kDwords / kNseg;
+  static constexpr int kRps = kDwords <= 18 ? (36 / kDwords > 4 ? 4 : 36 / kDwords) : 1;
   static_assert(kSeg * kNseg == kDwords, "row must split into equal segments");
 };
 
@@ -88,8 +92,9 @@ __device__ __forceinline__ void touch_args(const ConvParams& p) {
 template <int KW, int OUT>
 __global__ void __launch_bounds__(256)
 conv_stationary_kernel(const ConvParams p) {
-  constexpr int SEG = SegShape<KW>::kSeg;
-  constexpr int NSEG = SegShape<KW>::kNseg;
+  constexpr int SEG = StepShape<KW>::kSeg;
+  constexpr int NSEG = StepShape<KW>::kNseg;
+  constexpr int RPS = StepShape<KW>::kRps;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   // Lanes (and whole waves of the last workgroup) past the last pixel repeat pixel P-1: they
@@ -120,12 +125,10 @@ conv_stationary_kernel(const ConvParams p) {
   }
   const int o0 = blockIdx.y * p.cn;
   const int nrows = min(p.cn, p.O - o0);
-  const_f32_ptr alpha = (const_f32_ptr)uniform_addr((uint64_t)(uintptr_t)p.alpha + 4 * (int64_t)o0);
-  // Rows o0 .. o0+nrows-1 are a stream of nrows * NSEG segments (row_pad_dw dwords of
-  // padding follow the last segment of every row).
-  const int nseg_total = nrows * NSEG;
-  const_u32_ptr stream = (const_u32_ptr)uniform_addr(
-      (uint64_t)(uintptr_t)p.Wp + (int64_t)o0 * (4 * (2 * KW + p.row_pad_dw)));
+  // Rows o0 .. o0+nrows-1 of the filter matrix and of alpha (rows are row_bytes apart).
+  const uint32_t row_bytes = (uint32_t)(2 * KW + p.row_pad_dw) * 4u;
+  const uint64_t wbase = uniform_addr((uint64_t)(uintptr_t)p.Wp + (int64_t)o0 * row_bytes);
+  const uint64_t abase = uniform_addr((uint64_t)(uintptr_t)p.alpha + 4 * (int64_t)o0);
   // output: uniform base of (image of lane 0, filter o0), advanced by one plane per row
   const uint32_t img0 = __builtin_amdgcn_readfirstlane(img);
   const uint32_t ooff = ((img - img0) * (uint32_t)p.O * (uint32_t)p.HoWo + rem) * 4u;
@@ -133,66 +136,79 @@ conv_stationary_kernel(const ConvParams p) {
                 ((int64_t)img0 * p.O + o0) * p.HoWo * 4;
   const int64_t ostride = (int64_t)p.HoWo * 4;
 
-  ScalarSeg<SEG> buf[2];
-  float sc[2] = {1.0f, 1.0f};  // alpha of the row whose last segment sits in buf[k]
-  int pc = 0;
-  asm volatile("" : "+v"(pc));
-  const_u32_ptr src = stream;
-  int left = nseg_total - 1;  // segments after the one at src
-  const_f32_ptr aptr = alpha;  // alpha of the row whose last segment is requested next
-  int rows_left = nrows - 1;   // rows after the one at aptr
-  buf[0].issue(src, pc);
-  if (OUT == kOutF32Alpha && NSEG == 1) asm volatile("s_load_dword %0, %1, 0x0" : "=s"(sc[0]) : "s"(aptr));
-  for (int t = 0; t < nseg_total; t += 2 * NSEG) {  // two rows per trip
+  ScalarSeg<SEG> buf[2][RPS];
+  float sc[2][RPS];  // alpha of the rows whose last segment sits in buf[k]
+  int pc[RPS];
+#pragma unroll
+  for (int k = 0; k < RPS; ++k) {
+    pc[k] = 0;
+    sc[0][k] = sc[1][k] = 1.0f;
+  }
+  asm volatile("" : "+v"(pc[0]));
+  // Request segment `seg` of the rows of group g (rows g*RPS .. g*RPS+RPS-1; rows past the
+  // wave's last one repeat it, so nothing outside the wave's rows is ever read) into
+  // buffer set nb, and their alpha with the segment that ends the rows.
+  auto issue = [&](int g, int seg, int nb) {
+#pragma unroll
+    for (int k = 0; k < RPS; ++k) {
+      const int row = min(g * RPS + k, nrows - 1);
+      buf[nb][k].issue((const_u32_ptr)(wbase + (uint64_t)((uint32_t)row * row_bytes + (uint32_t)seg * (SEG * 4))),
+                       pc[0]);
+      if (OUT == kOutF32Alpha && seg == NSEG - 1)
+        asm volatile("s_load_dword %0, %1, 0x0" : "=s"(sc[nb][k]) : "s"((const_f32_ptr)(abase + 4u * (uint32_t)row)));
+    }
+  };
+  const int ngroups = (nrows + RPS - 1) / RPS;
+  issue(0, 0, 0);
+  for (int g0 = 0; g0 < ngroups; g0 += 2) {  // two row groups per trip
 #pragma unroll
     for (int i = 0; i < 2 * NSEG; ++i) {
       const int cur = i & 1, nxt = cur ^ 1;
-      const int seg_in_row = i % NSEG;
-      const int row = t / NSEG + i / NSEG;  // row within the wave's range (uniform)
-      buf[cur].wait();
-      if (OUT == kOutF32Alpha) asm volatile("" : "+s"(sc[cur]));
-      // prefetch the following segment; past the end of this wave's stream the last
-      // segment is fetched again, so nothing beyond the weights is ever read
-      src += (left > 0) ? (SEG + (seg_in_row == NSEG - 1 ? p.row_pad_dw : 0)) : 0;
-      left -= 1;
-      buf[nxt].issue(src, pc);
-      if (OUT == kOutF32Alpha && (i + 1) % NSEG == NSEG - 1) {
-        // the segment just requested ends a row: fetch that row's alpha with it
-        if (NSEG == 1 || (i + 1) / NSEG > 0 || t > 0) {  // not the very first row
-          aptr = (const_f32_ptr)((uint64_t)aptr + ((rows_left > 0) ? 4u : 0u));
-          rows_left -= 1;
-        }
-        asm volatile("s_load_dword %0, %1, 0x0" : "=s"(sc[nxt]) : "s"(aptr));
+      const int seg = i % NSEG;
+      const int g = g0 + i / NSEG;  // row group of this step (uniform)
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+      for (int k = 0; k < RPS; ++k) {
+        buf[cur][k].landed();
+        if (OUT == kOutF32Alpha) asm volatile("" : "+s"(sc[cur][k]));
       }
-      if (seg_in_row == 0) pc = seg_popcount<SEG, true>(buf[cur], b, pc);
-      else pc = seg_popcount<SEG, false>(buf[cur], b + seg_in_row * SEG, pc);
-      if (seg_in_row == NSEG - 1) {
-        // The finished count passes through an ordered asm statement: every VALU read of
-        // buf[cur] is thereby issued before the next trip overwrites that buffer.
-        asm volatile("" : "+v"(pc));
-        if (row < nrows) {
-          int dot;  // K - 2 * popcount in one VALU op (both operands are below 2^23)
-          asm("v_mad_i32_i24 %0, %1, -2, %2" : "=v"(dot) : "v"(pc), "s"(p.Kreal));
-          // scalar base + 32-bit lane offset: the store needs no vector address arithmetic
-          if (OUT == kOutF32Alpha) {
-            const float v = sc[cur] * (float)dot;
-            asm volatile("global_store_dword %0, %1, %2" ::"v"(ooff), "v"(v), "s"(obase) : "memory");
-          } else if (OUT == kOutF32) {
-            const float v = (float)dot;
-            asm volatile("global_store_dword %0, %1, %2" ::"v"(ooff), "v"(v), "s"(obase) : "memory");
-          } else {
-            asm volatile("global_store_dword %0, %1, %2" ::"v"(ooff), "v"(dot), "s"(obase) : "memory");
+      issue(g0 + (i + 1) / NSEG, (i + 1) % NSEG, nxt);
+#pragma unroll
+      for (int k = 0; k < RPS; ++k) {
+        if (seg == 0) pc[k] = seg_popcount<SEG, true>(buf[cur][k], b, pc[k]);
+        else pc[k] = seg_popcount<SEG, false>(buf[cur][k], b + seg * SEG, pc[k]);
+        if (seg == NSEG - 1) {
+          // The finished count passes through an ordered asm statement: every VALU read of
+          // buf[cur] is thereby issued before the next trip overwrites that buffer.
+          asm volatile("" : "+v"(pc[k]));
+          if (g * RPS + k < nrows) {
+            int dot;  // K - 2 * popcount in one VALU op (both operands are below 2^23)
+            asm("v_mad_i32_i24 %0, %1, -2, %2" : "=v"(dot) : "v"(pc[k]), "s"(p.Kreal));
+            // scalar base + 32-bit lane offset: the store needs no vector address arithmetic
+            if (OUT == kOutF32Alpha) {
+              const float v = sc[cur][k] * (float)dot;
+              asm volatile("global_store_dword %0, %1, %2" ::"v"(ooff), "v"(v), "s"(obase) : "memory");
+            } else if (OUT == kOutF32) {
+              const float v = (float)dot;
+              asm volatile("global_store_dword %0, %1, %2" ::"v"(ooff), "v"(v), "s"(obase) : "memory");
+            } else {
+              asm volatile("global_store_dword %0, %1, %2" ::"v"(ooff), "v"(dot), "s"(obase) : "memory");
+            }
           }
+          obase += ostride;
         }
-        obase += ostride;
       }
     }
   }
-  // Drain the last prefetch (it went to buffer 0).  Its destination registers must stay
+  // Drain the last prefetch (it went to buffer set 0).  Its destination registers must stay
   // allocated until the data has landed: were they dead here, the tail of the loop could be
   // given the same registers while the load is still in flight.
-  buf[0].wait();
-  if (OUT == kOutF32Alpha) asm volatile("" : "+s"(sc[0]));
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+  for (int k = 0; k < RPS; ++k) {
+    buf[0][k].landed();
+    if (OUT == kOutF32Alpha) asm volatile("" : "+s"(sc[0][k]));
+  }
 }
 
 // General shape: any number of K words, one thread per output, taps addressed with the
