@@ -33,6 +33,7 @@ struct ConvParams {
   float* out_f32;
   int64_t P;            // N * Ho * Wo
   int O, HoWo, Wo, Hp, Wp_pix, Cw, stride, Kreal, cn;  // cn: filters per wave
+  int pg_shift;         // log2 of the pixel groups per workgroup (1, 2 or 4 groups)
   FastDiv div_howo, div_wo;
   int off[kMaxStationaryWords];  // word offset of K-word j relative to the pixel base
 };
@@ -84,13 +85,13 @@ template <int KW>
 __device__ __forceinline__ void touch_args(const ConvParams& p) {
   asm volatile("" ::"s"(p.Xp), "s"(p.Wp), "s"(p.alpha), "s"(p.out_i32), "s"(p.out_f32), "s"(p.P),
                "s"(p.O), "s"(p.HoWo), "s"(p.Wo), "s"(p.Hp), "s"(p.Wp_pix), "s"(p.Cw), "s"(p.stride),
-               "s"(p.Kreal), "s"(p.cn), "s"(p.row_pad_dw), "s"(p.div_howo.mul), "s"(p.div_howo.sh1), "s"(p.div_howo.sh2),
+               "s"(p.Kreal), "s"(p.cn), "s"(p.row_pad_dw), "s"(p.pg_shift), "s"(p.div_howo.mul), "s"(p.div_howo.sh1), "s"(p.div_howo.sh2),
                "s"(p.div_wo.mul), "s"(p.div_wo.sh1), "s"(p.div_wo.sh2));
   if constexpr (KW <= 9) touch_offsets<KW>(p);  // longer tables would not stay in SGPRs anyway
 }
 
 template <int KW, int OUT>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(512)
 conv_stationary_kernel(const ConvParams p) {
   constexpr int SEG = StepShape<KW>::kSeg;
   constexpr int NSEG = StepShape<KW>::kNseg;
@@ -102,7 +103,15 @@ conv_stationary_kernel(const ConvParams p) {
   // lane is ever masked off and there is no early exit, so every kernel argument can be
   // fetched in one batch at the top.
   touch_args<KW>(p);
-  const int64_t pix = min(((int64_t)blockIdx.x * 4 + wave) * 64 + lane, p.P - 1);
+  // A workgroup is pg pixel groups x fb filter blocks of waves.  Waves with the same filter
+  // block stream the same filter rows at the same time, so all but the first find them in
+  // the scalar cache; waves with the same pixel group share one gather of the receptive
+  // fields (wave f of the group fetches words f, f + fb, ...) through LDS.
+  extern __shared__ uint64_t field[];  // [pg][KW][64]
+  const int npg = 1 << p.pg_shift;
+  const int nfb = __builtin_amdgcn_readfirstlane((int)(blockDim.x >> 6)) >> p.pg_shift;
+  const int my_pg = wave & (npg - 1), my_fb = wave >> p.pg_shift;
+  const int64_t pix = min(((int64_t)blockIdx.x * npg + my_pg) * 64 + lane, p.P - 1);
   const uint32_t img = fast_div((uint32_t)pix, p.div_howo);
   const uint32_t rem = (uint32_t)pix - img * (uint32_t)p.HoWo;
   const uint32_t ho = fast_div(rem, p.div_wo);
@@ -115,16 +124,36 @@ conv_stationary_kernel(const ConvParams p) {
       (((img * (uint32_t)p.Hp + ho * (uint32_t)p.stride) * (uint32_t)p.Wp_pix + wo * (uint32_t)p.stride) *
        (uint32_t)p.Cw) * 8u;
   const char* xbase = (const char*)p.Xp;
+  uint64_t* my_field = field + my_pg * (KW * 64);
   uint32_t b[2 * KW];
+  if (nfb == 1) {  // nothing to share: straight into registers
 #pragma unroll
-  for (int j = 0; j < KW; ++j) {
-    const uint32_t voff = xoff + (uint32_t)p.off[j] * 8u;  // one 32-bit add per tap
-    const uint64_t v = *(const uint64_t*)(xbase + voff);
-    b[2 * j] = (uint32_t)v;
-    b[2 * j + 1] = (uint32_t)(v >> 32);
+    for (int j = 0; j < KW; ++j) {
+      const uint64_t v = *(const uint64_t*)(xbase + (xoff + (uint32_t)p.off[j] * 8u));
+      b[2 * j] = (uint32_t)v;
+      b[2 * j + 1] = (uint32_t)(v >> 32);
+    }
+  } else {
+    int mine = my_fb;  // next word this wave fetches
+#pragma unroll
+    for (int j = 0; j < KW; ++j) {
+      if (j == mine) {  // wave-uniform
+        const uint32_t voff = xoff + (uint32_t)p.off[j] * 8u;  // one 32-bit add per tap
+        my_field[j * 64 + lane] = *(const uint64_t*)(xbase + voff);
+        mine += nfb;
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < KW; ++j) {
+      const uint64_t v = my_field[j * 64 + lane];
+      b[2 * j] = (uint32_t)v;
+      b[2 * j + 1] = (uint32_t)(v >> 32);
+    }
   }
-  const int o0 = blockIdx.y * p.cn;
+  const int o0 = ((int)blockIdx.y * nfb + my_fb) * p.cn;
   const int nrows = min(p.cn, p.O - o0);
+  if (nrows <= 0) return;  // (after the barrier) the last workgroup row may have spare waves
   // Rows o0 .. o0+nrows-1 of the filter matrix and of alpha (rows are row_bytes apart).
   const uint32_t row_bytes = (uint32_t)(2 * KW + p.row_pad_dw) * 4u;
   const uint64_t wbase = uniform_addr((uint64_t)(uintptr_t)p.Wp + (int64_t)o0 * row_bytes);
@@ -242,14 +271,17 @@ conv_general_kernel(const uint64_t* __restrict__ Xp, const uint64_t* __restrict_
 }
 
 template <int KW>
-void launch_stationary(const ConvParams& p, int64_t groups, int cblocks, hipStream_t s) {
-  dim3 grid((unsigned)ceil_div(groups, 4), (unsigned)cblocks);
+void launch_stationary(const ConvParams& p, int64_t groups, int cblocks, int fb, hipStream_t s) {
+  const int pg = 1 << p.pg_shift;
+  dim3 grid((unsigned)ceil_div(groups, pg), (unsigned)ceil_div(cblocks, fb));
+  const dim3 block(64 * pg * fb);
+  const size_t lds = fb > 1 ? (size_t)pg * KW * 64 * 8 : 0;
   if (p.out_f32 && p.alpha)
-    hipLaunchKernelGGL((conv_stationary_kernel<KW, kOutF32Alpha>), grid, dim3(256), 0, s, p);
+    hipLaunchKernelGGL((conv_stationary_kernel<KW, kOutF32Alpha>), grid, block, lds, s, p);
   else if (p.out_f32)
-    hipLaunchKernelGGL((conv_stationary_kernel<KW, kOutF32>), grid, dim3(256), 0, s, p);
+    hipLaunchKernelGGL((conv_stationary_kernel<KW, kOutF32>), grid, block, lds, s, p);
   else
-    hipLaunchKernelGGL((conv_stationary_kernel<KW, kOutI32>), grid, dim3(256), 0, s, p);
+    hipLaunchKernelGGL((conv_stationary_kernel<KW, kOutI32>), grid, block, lds, s, p);
 }
 
 }  // namespace
@@ -265,6 +297,7 @@ FastDiv make_fast_div(uint32_t d) {
 }
 
 int conv_filters_per_wave = 0;  // 0 = automatic; settable for tuning sweeps
+int conv_waves_per_block = 0;   // 0 = automatic; else 10 * pixel groups + filter blocks per workgroup
 int conv_path = 0;              // 0 = automatic, 1 = stationary, 2 = GEMM kernel, 3 = general
 
 hipError_t launch_binary_conv2d(const uint64_t* Xp, int N, int C, int H, int W, const uint64_t* Wp,
@@ -331,15 +364,29 @@ hipError_t launch_binary_conv2d(const uint64_t* Xp, int N, int C, int H, int W, 
     }
     p.cn = cn;
     const int cblocks = (int)ceil_div(O, cn);
+    // Workgroup shape.  Four pixel groups sharing one filter block is the fastest layout
+    // whenever the grid has waves to spare (the scalar cache serves three of the four filter
+    // streams; sharing the gather instead measured slower).  Only a grid with very few pixel
+    // groups gains from the other extreme, one pixel group gathered once for four blocks.
+    int pg = 4, fb = 1;
+    if (groups * cblocks <= 2048 && cblocks >= 4) pg = 1, fb = 4;
+    if (conv_waves_per_block > 0) {
+      pg = conv_waves_per_block / 10;
+      fb = conv_waves_per_block % 10;
+      if ((pg != 1 && pg != 2 && pg != 4) || fb < 1 || fb > 4 || pg * fb > 8) pg = 4, fb = 1;
+    }
+    if (fb > cblocks) fb = cblocks;
+    p.pg_shift = pg == 4 ? 2 : (pg == 2 ? 1 : 0);
+    const int wpb = fb;
     switch (kwords) {
-      case 1: launch_stationary<1>(p, groups, cblocks, s); break;
-      case 2: launch_stationary<2>(p, groups, cblocks, s); break;
-      case 4: launch_stationary<4>(p, groups, cblocks, s); break;
-      case 9: launch_stationary<9>(p, groups, cblocks, s); break;
-      case 18: launch_stationary<18>(p, groups, cblocks, s); break;
-      case 25: launch_stationary<25>(p, groups, cblocks, s); break;
-      case 27: launch_stationary<27>(p, groups, cblocks, s); break;
-      default: launch_stationary<36>(p, groups, cblocks, s); break;
+      case 1: launch_stationary<1>(p, groups, cblocks, wpb, s); break;
+      case 2: launch_stationary<2>(p, groups, cblocks, wpb, s); break;
+      case 4: launch_stationary<4>(p, groups, cblocks, wpb, s); break;
+      case 9: launch_stationary<9>(p, groups, cblocks, wpb, s); break;
+      case 18: launch_stationary<18>(p, groups, cblocks, wpb, s); break;
+      case 25: launch_stationary<25>(p, groups, cblocks, wpb, s); break;
+      case 27: launch_stationary<27>(p, groups, cblocks, wpb, s); break;
+      default: launch_stationary<36>(p, groups, cblocks, wpb, s); break;
     }
     return hipGetLastError();
   }
