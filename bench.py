@@ -229,6 +229,23 @@ def main():
             lambda: B.xnor_gemm(X3p, W31p, 9216, out=i3), 50))
         other["config3_fc2_gemm_kernel"] = alu(2.0 * 256 * 4096 * 4096, kernel_us(
             lambda: B.xnor_gemm(H1p, W32p, 4096, out=i3), 50))
+        # the two layers chained: through fp32 activations (pack + GEMM, twice) and through
+        # packed sign bits handed from layer to layer (one pack, two GEMMs)
+        chain_ops = 2.0 * 256 * 4096 * (9216 + 4096)
+
+        def chain_fp32():
+            B.binary_fc(x3, W31p, alpha=al1, out=h1, workspace=ws3)
+            B.binary_fc(h1, W32p, alpha=al2, out=h2, workspace=ws3)
+
+        bits1 = B.binary_fc_packed(X3p, 9216, W31p, alpha=al1, mode="bits")
+
+        def chain_bits():
+            B.binarize_pack(x3, 1, out=X3p)
+            B.binary_fc_packed(X3p, 9216, W31p, alpha=al1, mode="bits", out=bits1)
+            B.binary_fc_packed(bits1, 4096, W32p, alpha=al2, mode="f32", out=h2)
+
+        other["config3_chain_via_fp32_activations"] = alu(chain_ops, kernel_us(chain_fp32, 50))
+        other["config3_chain_via_packed_bits"] = alu(chain_ops, kernel_us(chain_bits, 50))
         other["config3_activation_pack_256x9216"] = hbm(x3.numel() * 4 + X3p.numel() * 8, kernel_us(
             lambda: B.binarize_pack(x3, 1, out=X3p)))
         other["config3_weight_pack_4096x9216_cache_assisted"] = hbm(w31.numel() * 4 + W31p.numel() * 8, kernel_us(

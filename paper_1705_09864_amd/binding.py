@@ -19,7 +19,7 @@ OP_BINARY_FC, OP_BINARY_CONV2D, OP_QUANT_GEMM = 1, 2, 3
 EXPORTS = ["bmx_binarize_pack", "bmx_xnor_gemm", "bmx_binary_fc", "bmx_pack_conv_weights",
            "bmx_binary_conv2d", "bmx_quant_gemm", "bmx_alpha_mean_abs", "bmx_pack_nchw",
            "bmx_binary_conv2d_packed", "bmx_workspace_bytes", "bmx_status_string", "bmx_version",
-           "bmx_conv_weight_row_words"]
+           "bmx_conv_weight_row_words", "bmx_binary_fc_packed"]
 
 _i64, _int, _p, _sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
 
@@ -52,6 +52,8 @@ def lib():
         L.bmx_status_string.argtypes = [_int]
         L.bmx_status_string.restype = ctypes.c_char_p
         L.bmx_version.restype = _int
+        L.bmx_binary_fc_packed.argtypes = [_p, _i64, _p, _i64, _p, _int, _int, _int, _p, _p, _p, _i64, _p]
+        L.bmx_binary_fc_packed.restype = _int
         L.bmx_conv_weight_row_words.argtypes = [_int, _int, _int]
         L.bmx_conv_weight_row_words.restype = _i64
         L.bmx_pack_nchw.argtypes = [_p, _int, _int, _int, _int, _int, _p, _p]
@@ -136,6 +138,23 @@ def binary_fc(x, Wp, alpha=None, integer_out=False, out=None, workspace=None, st
     _check(lib().bmx_binary_fc(_ptr(x), x.stride(0) if batch > 1 else fin, _ptr(Wp), Wp.shape[1],
                                _ptr(alpha), batch, fin, fout, _ptr(oi), _ptr(of), max(fout, 1),
                                _ptr(ws), ws_bytes, _stream(stream)), "bmx_binary_fc")
+    return out
+
+
+def binary_fc_packed(xp, in_features, Wp, alpha=None, mode="f32", out=None, stream=None):
+    """xp: packed activations [batch, words].  mode: "f32", "i32" or "bits" (packed sign bits)."""
+    batch, fout = xp.shape[0], Wp.shape[0]
+    if out is None:
+        if mode == "bits":
+            out = _u64_as_i64((batch, (fout + 63) // 64), xp.device)
+        else:
+            out = torch.empty((batch, fout), dtype=torch.int32 if mode == "i32" else torch.float32,
+                              device=xp.device)
+    oi, of, ob = (out if mode == "i32" else None, out if mode == "f32" else None,
+                  out if mode == "bits" else None)
+    _check(lib().bmx_binary_fc_packed(_ptr(xp), xp.shape[1], _ptr(Wp), Wp.shape[1], _ptr(alpha), batch,
+                                      in_features, fout, _ptr(oi), _ptr(of), _ptr(ob),
+                                      max(out.shape[1], 1), _stream(stream)), "bmx_binary_fc_packed")
     return out
 
 

@@ -67,14 +67,15 @@ hipError_t launch_quant_pack(const float* a, int64_t M, int64_t K, int64_t lda, 
                              uint64_t* planes, int64_t ld_words, int32_t* rowsum, hipStream_t s);
 
 // gemm.hip -------------------------------------------------------------------
-// out = K - 2*popcount(A ^ B); exactly one of C_i32 / C_f32 non-null;
+// out = K - 2*popcount(A ^ B); exactly one of C_i32 / C_f32 / C_bits non-null;
 // C_f32[m][n] = (alpha_n ? alpha_n[n] : 1) * float(dot).
 // A is row-major with lda_dw dwords per row.  a_padded: every row is readable and zero up
 // to a multiple of 32 dwords (workspace copies); otherwise only ceil(K/64) words per row
 // are touched.
+// C_bits (instead of C_i32 / C_f32): packed (alpha_n[n] * float(dot) >= 0), ldc words per row.
 hipError_t launch_xnor_gemm(const uint32_t* A, bool a_padded, int64_t lda_dw, const uint64_t* B,
                             int64_t ldb_w, int M, int N, int K, const float* alpha_n, int32_t* C_i32,
-                            float* C_f32, int64_t ldc, hipStream_t s);
+                            float* C_f32, uint64_t* C_bits, int64_t ldc, hipStream_t s);
 // S = 2*sum_p 2^p pc(plane_p & wb) - rowsum; out_f32 = float(S) / float(2^bits - 1).
 // planes_rows as written by launch_quant_pack (lda_dw dwords per row, chunk padded).
 hipError_t launch_plane_gemm(const uint32_t* planes_rows, int64_t lda_dw, int bits,

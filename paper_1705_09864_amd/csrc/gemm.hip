@@ -48,7 +48,7 @@ constexpr int kChunk = 32;  // dwords of K per register chunk in GEMM mode
 constexpr int kTRow = 36;   // LDS row stride of the transposition tile (dwords, 16-byte multiple)
 constexpr int kTileDw = 64 * kTRow;
 
-enum GemmOut { kGemmI32 = 0, kGemmF32 = 1, kGemmF32Alpha = 2, kGemmPlanes = 3 };
+enum GemmOut { kGemmI32 = 0, kGemmF32 = 1, kGemmF32Alpha = 2, kGemmPlanes = 3, kGemmBits = 4 };
 
 struct GemmParams {
   const uint32_t* A;      // [Mv][lda] dwords, virtual rows (row m, plane p -> m * planes + p)
@@ -66,6 +66,7 @@ struct GemmParams {
   float levels;           // planes mode: 2^bits - 1
   int32_t* C_i32;
   float* C_f32;
+  uint64_t* C_bits;       // kGemmBits: packed sign of the scaled result, ldc words per row
   int64_t ldc;            // GEMM: elements between C rows.  Convolution: Ho * Wo
   int out;                // GemmOut
   int row_blocks;         // ceil(Mv / rows_per_block)
@@ -280,9 +281,13 @@ gemm_kernel(const GemmParams p) {
   }
 
   float al = 1.0f;
-  if (!CONV && p.out == kGemmF32Alpha) al = p.alpha[nc];
+  if (!CONV && (p.out == kGemmF32Alpha || p.out == kGemmBits) && p.alpha) al = p.alpha[nc];
   auto finish = [&](int64_t m, int total) {  // count of output row m -> result -> C[m][n]
-    if (n < p.N) {
+    if (p.out == kGemmBits) {
+      // the 64-lane mask of (scaled result >= 0) is the packed word of columns n0 .. n0+63
+      const uint64_t word = __ballot(n < p.N && al * (float)(p.Kreal - 2 * total) >= 0.0f);
+      if (lane == 0) p.C_bits[m * p.ldc + cb] = word;
+    } else if (n < p.N) {
       const int64_t idx = m * p.ldc + lane_off;
       if (p.out == kGemmPlanes) {
         const int sv = 2 * total - p.rowsum[m];
@@ -425,7 +430,7 @@ void no_conv(GemmParams& p) {
 
 hipError_t launch_xnor_gemm(const uint32_t* A, bool a_padded, int64_t lda_dw, const uint64_t* B,
                             int64_t ldb_w, int M, int N, int K, const float* alpha_n, int32_t* C_i32,
-                            float* C_f32, int64_t ldc, hipStream_t s) {
+                            float* C_f32, uint64_t* C_bits, int64_t ldc, hipStream_t s) {
   GemmParams p;
   no_conv(p);
   p.A = A;
@@ -442,8 +447,9 @@ hipError_t launch_xnor_gemm(const uint32_t* A, bool a_padded, int64_t lda_dw, co
   p.levels = 1.0f;
   p.C_i32 = C_i32;
   p.C_f32 = C_f32;
+  p.C_bits = C_bits;
   p.ldc = ldc;
-  p.out = C_i32 ? kGemmI32 : (alpha_n ? kGemmF32Alpha : kGemmF32);
+  p.out = C_bits ? kGemmBits : (C_i32 ? kGemmI32 : (alpha_n ? kGemmF32Alpha : kGemmF32));
   if (a_padded) {  // A rows are zero padded to whole chunks: everything runs in the main loop
     p.nch = (int)ceil_div(p.Kd, kChunk);
     p.tail0 = p.tail1 = 0;
@@ -477,6 +483,7 @@ hipError_t launch_plane_gemm(const uint32_t* planes_rows, int64_t lda_dw, int bi
   p.levels = (float)((1u << bits) - 1u);
   p.C_i32 = S;
   p.C_f32 = out_f32;
+  p.C_bits = nullptr;
   p.ldc = ldo;
   p.out = kGemmPlanes;
   launch<true>(p, s);
@@ -509,6 +516,7 @@ hipError_t launch_conv_gemm(const uint64_t* Xp, int Nimg, int C, int H, int W, c
   p.levels = 1.0f;
   p.C_i32 = out_i32;
   p.C_f32 = out_f32;
+  p.C_bits = nullptr;
   p.ldc = (int64_t)Ho * Wo;
   p.out = out_i32 ? kGemmI32 : (alpha ? kGemmF32Alpha : kGemmF32);
   p.HoWo = Ho * Wo;

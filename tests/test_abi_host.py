@@ -136,3 +136,24 @@ def test_quant_and_alpha_validation():
     assert g(P, 4, 8, 7, P, NULL) == E_LD
     assert g(NULL, 4, 8, 8, P, NULL) == E_NULL
     assert g(P, 0, 8, 8, P, NULL) == OK
+
+
+def test_fc_packed_validation():
+    f = B.lib().bmx_binary_fc_packed
+    ok = dict(xp=P, ldx=8, Wp=P, ldw=8, alpha=NULL, b=4, fin=512, fout=70, oi=NULL, of=NULL, ob=P, ldo=2)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(a["xp"], a["ldx"], a["Wp"], a["ldw"], a["alpha"], a["b"], a["fin"], a["fout"], a["oi"],
+                 a["of"], a["ob"], a["ldo"], NULL)
+
+    assert call(b=0) == OK and call(fout=0) == OK                       # empty: no launch
+    assert call(b=-1) == E_SHAPE and call(fin=0) == E_SHAPE
+    assert call(xp=NULL) == E_NULL and call(Wp=NULL) == E_NULL
+    assert call(ob=NULL) == E_NULL                                      # no output at all
+    assert call(of=P, ldo=70) == E_NULL                                 # two outputs
+    assert call(oi=P, ob=NULL, alpha=P, ldo=70) == E_UNSUP              # int output with a scale
+    assert call(ldx=7) == E_LD and call(ldw=7) == E_LD
+    assert call(ldo=1) == E_LD                                          # 70 features need 2 words
+    assert call(ob=NULL, of=P, ldo=69) == E_LD
+    assert call(ob=P + 4) == E_ALIGN and call(xp=P + 4) == E_ALIGN

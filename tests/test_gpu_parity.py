@@ -377,3 +377,45 @@ def test_conv_weight_rows_are_zero_padded():
         assert (Wp[:, kwords:] == 0).all()
         ref = oracle.binarize_pack(np.transpose(w, (0, 2, 3, 1)).reshape(O * k * k, C), 1)
         np.testing.assert_array_equal(Wp[:, :kwords].reshape(O * k * k, -1), ref)
+
+
+# ------------------------------------------------------------------ chained FC on packed bits
+@pytest.mark.parametrize("small", [True, False])
+def test_fc_packed_chain(small):
+    """Two chained binary layers that hand packed sign bits to each other: the bits must be
+    exactly what packing the first layer's fp32 output gives, and the second layer's output
+    the same as through the fp32 route."""
+    c = synth.config3(small=small)
+    x, w1, w2 = c["x"], c["w1"], c["w2"]
+    a1, a2 = oracle.alpha_mean_abs(w1), oracle.alpha_mean_abs(w2)
+    r1i, r1f = oracle.binary_fc(x, w1, a1)
+    r2i, r2f = oracle.binary_fc(r1f, w2, a2)
+    W1p, W2p = B.binarize_pack(dev(w1), 1), B.binarize_pack(dev(w2), 1)
+    Xp = B.binarize_pack(dev(x), 1)
+    bits1 = B.binary_fc_packed(Xp, x.shape[1], W1p, alpha=dev(a1), mode="bits")
+    np.testing.assert_array_equal(host_u64(bits1), oracle.binarize_pack(r1f, 1))
+    np.testing.assert_array_equal(B.binary_fc_packed(Xp, x.shape[1], W1p, mode="i32").cpu().numpy(), r1i)
+    h2 = B.binary_fc_packed(bits1, w1.shape[0], W2p, alpha=dev(a2), mode="f32")
+    assert_f32_close(h2.cpu().numpy(), r2f)
+    np.testing.assert_array_equal(B.binary_fc_packed(bits1, w1.shape[0], W2p, mode="i32").cpu().numpy(), r2i)
+
+
+@pytest.mark.parametrize("batch,fin,fout", [(1, 1, 1), (5, 27, 3), (3, 180, 70), (66, 1000, 130), (9, 2100, 64)])
+def test_fc_packed_bits_ragged(batch, fin, fout):
+    """Ragged shapes, poisoned output, and scales of either sign and zero: the bit is the
+    IEEE compare (alpha * dot >= 0) of the fp32 product, as bmx_binarize_pack would see it."""
+    rng = np.random.default_rng(batch + fin + fout)
+    x = rng.standard_normal((batch, fin)).astype(np.float32)
+    w = rng.uniform(-1, 1, (fout, fin)).astype(np.float32)
+    alpha = rng.standard_normal(fout).astype(np.float32)
+    alpha[::3] = 0.0
+    _, rf = oracle.binary_fc(x, w, alpha)
+    Xp, Wp = B.binarize_pack(dev(x), 1), B.binarize_pack(dev(w), 1)
+    out = dev(np.full((batch, (fout + 63) // 64 + 1), -1, dtype=np.int64))   # one spare word
+    B.binary_fc_packed(Xp, fin, Wp, alpha=dev(alpha), mode="bits", out=out)
+    got = host_u64(out)
+    np.testing.assert_array_equal(got[:, :-1], oracle.binarize_pack(rf, 1))
+    assert (got[:, -1] == np.uint64(0xFFFFFFFFFFFFFFFF)).all()              # spare word untouched
+    nob = B.binary_fc_packed(Xp, fin, Wp, mode="bits")                       # no scale: sign of dot
+    ri, _ = oracle.binary_fc(x, w)
+    np.testing.assert_array_equal(host_u64(nob), oracle.binarize_pack(ri.astype(np.float32), 1))
