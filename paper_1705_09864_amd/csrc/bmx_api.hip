@@ -50,7 +50,7 @@ QuantWs quant_ws(int64_t M, int64_t N, int64_t K, int bits_a) {
 }  // namespace
 
 namespace bmx {
-extern int conv_filters_per_wave, conv_path, conv_waves_per_block;
+extern int conv_filters_per_wave, conv_path;
 extern int gemm_tune_rows, gemm_tune_ksplit, gemm_tune_order;
 }
 
@@ -59,15 +59,13 @@ extern "C" {
 // Undeclared tuning hook used by kernel sweeps (0 restores the automatic choice):
 // key 1 = filters per wave of the stationary convolution kernel, key 2 = rows per wave,
 // key 3 = K-split waves and key 4 = workgroup order of the GEMM kernel, key 5 = convolution
-// path (1 stationary, 2 GEMM kernel, 3 general), key 6 = waves per workgroup of the stationary
-// convolution kernel.
+// path (1 stationary, 2 GEMM kernel, 3 general).
 int bmx_tune_set(int key, int value) {
   if (key == 1) bmx::conv_filters_per_wave = value;
   else if (key == 2) bmx::gemm_tune_rows = value;
   else if (key == 3) bmx::gemm_tune_ksplit = value;
   else if (key == 4) bmx::gemm_tune_order = value;
   else if (key == 5) bmx::conv_path = value;
-  else if (key == 6) bmx::conv_waves_per_block = value;
   else return BMX_ERR_UNSUPPORTED;
   return BMX_OK;
 }

@@ -33,23 +33,18 @@ struct ConvParams {
   float* out_f32;
   int64_t P;            // N * Ho * Wo
   int O, HoWo, Wo, Hp, Wp_pix, Cw, stride, Kreal, cn;  // cn: filters per wave
-  int pg_shift;         // log2 of the pixel groups per workgroup (1, 2 or 4 groups)
   FastDiv div_howo, div_wo;
   int off[kMaxStationaryWords];  // word offset of K-word j relative to the pixel base
 };
 
-// The filter rows of a wave are consumed in steps of at most 36 dwords, two sets of SGPR
-// buffers alternating so that the scalar loads of the next step are in flight while the VALU
-// works through the current one.  A scalar wait always covers every outstanding load, so a
-// wave pays one memory round trip per step; steps are therefore made as large as the SGPR
-// file allows: a long row (more than 36 dwords) is NSEG segments of SEG dwords, a short row
-// (18 dwords or less) is fetched RPS rows at a time.
+// A filter row of 2*KW dwords is consumed in NSEG segments of SEG dwords; two SGPR buffers
+// alternate so that the scalar loads of the next segment are in flight while the VALU works
+// through the current one.
 template <int KW>
-struct StepShape {
+struct SegShape {
   static constexpr int kDwords = 2 * KW;
-  static constexpr int kNseg = kDwords > 36 ? (kDwords + 35) / 36 : 1;
+  static constexpr int kNseg = (kDwords + 31) / 32;
   static constexpr int kSeg = kDwords / kNseg;
-  static constexpr int kRps = kDwords <= 18 ? (36 / kDwords > 4 ? 4 : 36 / kDwords) : 1;
   static_assert(kSeg * kNseg == kDwords, "row must split into equal segments");
 };
 
@@ -85,17 +80,16 @@ template <int KW>
 __device__ __forceinline__ void touch_args(const ConvParams& p) {
   asm volatile("" ::"s"(p.Xp), "s"(p.Wp), "s"(p.alpha), "s"(p.out_i32), "s"(p.out_f32), "s"(p.P),
                "s"(p.O), "s"(p.HoWo), "s"(p.Wo), "s"(p.Hp), "s"(p.Wp_pix), "s"(p.Cw), "s"(p.stride),
-               "s"(p.Kreal), "s"(p.cn), "s"(p.row_pad_dw), "s"(p.pg_shift), "s"(p.div_howo.mul), "s"(p.div_howo.sh1), "s"(p.div_howo.sh2),
+               "s"(p.Kreal), "s"(p.cn), "s"(p.row_pad_dw), "s"(p.div_howo.mul), "s"(p.div_howo.sh1), "s"(p.div_howo.sh2),
                "s"(p.div_wo.mul), "s"(p.div_wo.sh1), "s"(p.div_wo.sh2));
   if constexpr (KW <= 9) touch_offsets<KW>(p);  // longer tables would not stay in SGPRs anyway
 }
 
 template <int KW, int OUT>
-__global__ void __launch_bounds__(512)
+__global__ void __launch_bounds__(256)
 conv_stationary_kernel(const ConvParams p) {
-  constexpr int SEG = StepShape<KW>::kSeg;
-  constexpr int NSEG = StepShape<KW>::kNseg;
-  constexpr int RPS = StepShape<KW>::kRps;
+  constexpr int SEG = SegShape<KW>::kSeg;
+  constexpr int NSEG = SegShape<KW>::kNseg;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   // Lanes (and whole waves of the last workgroup) past the last pixel repeat pixel P-1: they
@@ -103,15 +97,7 @@ conv_stationary_kernel(const ConvParams p) {
   // lane is ever masked off and there is no early exit, so every kernel argument can be
   // fetched in one batch at the top.
   touch_args<KW>(p);
-  // A workgroup is pg pixel groups x fb filter blocks of waves.  Waves with the same filter
-  // block stream the same filter rows at the same time, so all but the first find them in
-  // the scalar cache; waves with the same pixel group share one gather of the receptive
-  // fields (wave f of the group fetches words f, f + fb, ...) through LDS.
-  extern __shared__ uint64_t field[];  // [pg][KW][64]
-  const int npg = 1 << p.pg_shift;
-  const int nfb = __builtin_amdgcn_readfirstlane((int)(blockDim.x >> 6)) >> p.pg_shift;
-  const int my_pg = wave & (npg - 1), my_fb = wave >> p.pg_shift;
-  const int64_t pix = min(((int64_t)blockIdx.x * npg + my_pg) * 64 + lane, p.P - 1);
+  const int64_t pix = min(((int64_t)blockIdx.x * 4 + wave) * 64 + lane, p.P - 1);
   const uint32_t img = fast_div((uint32_t)pix, p.div_howo);
   const uint32_t rem = (uint32_t)pix - img * (uint32_t)p.HoWo;
   const uint32_t ho = fast_div(rem, p.div_wo);
@@ -124,40 +110,22 @@ conv_stationary_kernel(const ConvParams p) {
       (((img * (uint32_t)p.Hp + ho * (uint32_t)p.stride) * (uint32_t)p.Wp_pix + wo * (uint32_t)p.stride) *
        (uint32_t)p.Cw) * 8u;
   const char* xbase = (const char*)p.Xp;
-  uint64_t* my_field = field + my_pg * (KW * 64);
   uint32_t b[2 * KW];
-  if (nfb == 1) {  // nothing to share: straight into registers
 #pragma unroll
-    for (int j = 0; j < KW; ++j) {
-      const uint64_t v = *(const uint64_t*)(xbase + (xoff + (uint32_t)p.off[j] * 8u));
-      b[2 * j] = (uint32_t)v;
-      b[2 * j + 1] = (uint32_t)(v >> 32);
-    }
-  } else {
-    int mine = my_fb;  // next word this wave fetches
-#pragma unroll
-    for (int j = 0; j < KW; ++j) {
-      if (j == mine) {  // wave-uniform
-        const uint32_t voff = xoff + (uint32_t)p.off[j] * 8u;  // one 32-bit add per tap
-        my_field[j * 64 + lane] = *(const uint64_t*)(xbase + voff);
-        mine += nfb;
-      }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int j = 0; j < KW; ++j) {
-      const uint64_t v = my_field[j * 64 + lane];
-      b[2 * j] = (uint32_t)v;
-      b[2 * j + 1] = (uint32_t)(v >> 32);
-    }
+  for (int j = 0; j < KW; ++j) {
+    const uint32_t voff = xoff + (uint32_t)p.off[j] * 8u;  // one 32-bit add per tap
+    const uint64_t v = *(const uint64_t*)(xbase + voff);
+    b[2 * j] = (uint32_t)v;
+    b[2 * j + 1] = (uint32_t)(v >> 32);
   }
-  const int o0 = ((int)blockIdx.y * nfb + my_fb) * p.cn;
+  const int o0 = blockIdx.y * p.cn;
   const int nrows = min(p.cn, p.O - o0);
-  if (nrows <= 0) return;  // (after the barrier) the last workgroup row may have spare waves
-  // Rows o0 .. o0+nrows-1 of the filter matrix and of alpha (rows are row_bytes apart).
-  const uint32_t row_bytes = (uint32_t)(2 * KW + p.row_pad_dw) * 4u;
-  const uint64_t wbase = uniform_addr((uint64_t)(uintptr_t)p.Wp + (int64_t)o0 * row_bytes);
-  const uint64_t abase = uniform_addr((uint64_t)(uintptr_t)p.alpha + 4 * (int64_t)o0);
+  const_f32_ptr alpha = (const_f32_ptr)uniform_addr((uint64_t)(uintptr_t)p.alpha + 4 * (int64_t)o0);
+  // Rows o0 .. o0+nrows-1 are a stream of nrows * NSEG segments (row_pad_dw dwords of
+  // padding follow the last segment of every row).
+  const int nseg_total = nrows * NSEG;
+  const_u32_ptr stream = (const_u32_ptr)uniform_addr(
+      (uint64_t)(uintptr_t)p.Wp + (int64_t)o0 * (4 * (2 * KW + p.row_pad_dw)));
   // output: uniform base of (image of lane 0, filter o0), advanced by one plane per row
   const uint32_t img0 = __builtin_amdgcn_readfirstlane(img);
   const uint32_t ooff = ((img - img0) * (uint32_t)p.O * (uint32_t)p.HoWo + rem) * 4u;
@@ -165,79 +133,66 @@ conv_stationary_kernel(const ConvParams p) {
                 ((int64_t)img0 * p.O + o0) * p.HoWo * 4;
   const int64_t ostride = (int64_t)p.HoWo * 4;
 
-  ScalarSeg<SEG> buf[2][RPS];
-  float sc[2][RPS];  // alpha of the rows whose last segment sits in buf[k]
-  int pc[RPS];
-#pragma unroll
-  for (int k = 0; k < RPS; ++k) {
-    pc[k] = 0;
-    sc[0][k] = sc[1][k] = 1.0f;
-  }
-  asm volatile("" : "+v"(pc[0]));
-  // Request segment `seg` of the rows of group g (rows g*RPS .. g*RPS+RPS-1; rows past the
-  // wave's last one repeat it, so nothing outside the wave's rows is ever read) into
-  // buffer set nb, and their alpha with the segment that ends the rows.
-  auto issue = [&](int g, int seg, int nb) {
-#pragma unroll
-    for (int k = 0; k < RPS; ++k) {
-      const int row = min(g * RPS + k, nrows - 1);
-      buf[nb][k].issue((const_u32_ptr)(wbase + (uint64_t)((uint32_t)row * row_bytes + (uint32_t)seg * (SEG * 4))),
-                       pc[0]);
-      if (OUT == kOutF32Alpha && seg == NSEG - 1)
-        asm volatile("s_load_dword %0, %1, 0x0" : "=s"(sc[nb][k]) : "s"((const_f32_ptr)(abase + 4u * (uint32_t)row)));
-    }
-  };
-  const int ngroups = (nrows + RPS - 1) / RPS;
-  issue(0, 0, 0);
-  for (int g0 = 0; g0 < ngroups; g0 += 2) {  // two row groups per trip
+  ScalarSeg<SEG> buf[2];
+  float sc[2] = {1.0f, 1.0f};  // alpha of the row whose last segment sits in buf[k]
+  int pc = 0;
+  asm volatile("" : "+v"(pc));
+  const_u32_ptr src = stream;
+  int left = nseg_total - 1;  // segments after the one at src
+  const_f32_ptr aptr = alpha;  // alpha of the row whose last segment is requested next
+  int rows_left = nrows - 1;   // rows after the one at aptr
+  buf[0].issue(src, pc);
+  if (OUT == kOutF32Alpha && NSEG == 1) asm volatile("s_load_dword %0, %1, 0x0" : "=s"(sc[0]) : "s"(aptr));
+  for (int t = 0; t < nseg_total; t += 2 * NSEG) {  // two rows per trip
 #pragma unroll
     for (int i = 0; i < 2 * NSEG; ++i) {
       const int cur = i & 1, nxt = cur ^ 1;
-      const int seg = i % NSEG;
-      const int g = g0 + i / NSEG;  // row group of this step (uniform)
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll
-      for (int k = 0; k < RPS; ++k) {
-        buf[cur][k].landed();
-        if (OUT == kOutF32Alpha) asm volatile("" : "+s"(sc[cur][k]));
-      }
-      issue(g0 + (i + 1) / NSEG, (i + 1) % NSEG, nxt);
-#pragma unroll
-      for (int k = 0; k < RPS; ++k) {
-        if (seg == 0) pc[k] = seg_popcount<SEG, true>(buf[cur][k], b, pc[k]);
-        else pc[k] = seg_popcount<SEG, false>(buf[cur][k], b + seg * SEG, pc[k]);
-        if (seg == NSEG - 1) {
-          // The finished count passes through an ordered asm statement: every VALU read of
-          // buf[cur] is thereby issued before the next trip overwrites that buffer.
-          asm volatile("" : "+v"(pc[k]));
-          if (g * RPS + k < nrows) {
-            int dot;  // K - 2 * popcount in one VALU op (both operands are below 2^23)
-            asm("v_mad_i32_i24 %0, %1, -2, %2" : "=v"(dot) : "v"(pc[k]), "s"(p.Kreal));
-            // scalar base + 32-bit lane offset: the store needs no vector address arithmetic
-            if (OUT == kOutF32Alpha) {
-              const float v = sc[cur][k] * (float)dot;
-              asm volatile("global_store_dword %0, %1, %2" ::"v"(ooff), "v"(v), "s"(obase) : "memory");
-            } else if (OUT == kOutF32) {
-              const float v = (float)dot;
-              asm volatile("global_store_dword %0, %1, %2" ::"v"(ooff), "v"(v), "s"(obase) : "memory");
-            } else {
-              asm volatile("global_store_dword %0, %1, %2" ::"v"(ooff), "v"(dot), "s"(obase) : "memory");
-            }
-          }
-          obase += ostride;
+      const int seg_in_row = i % NSEG;
+      const int row = t / NSEG + i / NSEG;  // row within the wave's range (uniform)
+      buf[cur].wait();
+      if (OUT == kOutF32Alpha) asm volatile("" : "+s"(sc[cur]));
+      // prefetch the following segment; past the end of this wave's stream the last
+      // segment is fetched again, so nothing beyond the weights is ever read
+      src += (left > 0) ? (SEG + (seg_in_row == NSEG - 1 ? p.row_pad_dw : 0)) : 0;
+      left -= 1;
+      buf[nxt].issue(src, pc);
+      if (OUT == kOutF32Alpha && (i + 1) % NSEG == NSEG - 1) {
+        // the segment just requested ends a row: fetch that row's alpha with it
+        if (NSEG == 1 || (i + 1) / NSEG > 0 || t > 0) {  // not the very first row
+          aptr = (const_f32_ptr)((uint64_t)aptr + ((rows_left > 0) ? 4u : 0u));
+          rows_left -= 1;
         }
+        asm volatile("s_load_dword %0, %1, 0x0" : "=s"(sc[nxt]) : "s"(aptr));
+      }
+      if (seg_in_row == 0) pc = seg_popcount<SEG, true>(buf[cur], b, pc);
+      else pc = seg_popcount<SEG, false>(buf[cur], b + seg_in_row * SEG, pc);
+      if (seg_in_row == NSEG - 1) {
+        // The finished count passes through an ordered asm statement: every VALU read of
+        // buf[cur] is thereby issued before the next trip overwrites that buffer.
+        asm volatile("" : "+v"(pc));
+        if (row < nrows) {
+          int dot;  // K - 2 * popcount in one VALU op (both operands are below 2^23)
+          asm("v_mad_i32_i24 %0, %1, -2, %2" : "=v"(dot) : "v"(pc), "s"(p.Kreal));
+          // scalar base + 32-bit lane offset: the store needs no vector address arithmetic
+          if (OUT == kOutF32Alpha) {
+            const float v = sc[cur] * (float)dot;
+            asm volatile("global_store_dword %0, %1, %2" ::"v"(ooff), "v"(v), "s"(obase) : "memory");
+          } else if (OUT == kOutF32) {
+            const float v = (float)dot;
+            asm volatile("global_store_dword %0, %1, %2" ::"v"(ooff), "v"(v), "s"(obase) : "memory");
+          } else {
+            asm volatile("global_store_dword %0, %1, %2" ::"v"(ooff), "v"(dot), "s"(obase) : "memory");
+          }
+        }
+        obase += ostride;
       }
     }
   }
-  // Drain the last prefetch (it went to buffer set 0).  Its destination registers must stay
+  // Drain the last prefetch (it went to buffer 0).  Its destination registers must stay
   // allocated until the data has landed: were they dead here, the tail of the loop could be
   // given the same registers while the load is still in flight.
-  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll
-  for (int k = 0; k < RPS; ++k) {
-    buf[0][k].landed();
-    if (OUT == kOutF32Alpha) asm volatile("" : "+s"(sc[0][k]));
-  }
+  buf[0].wait();
+  if (OUT == kOutF32Alpha) asm volatile("" : "+s"(sc[0]));
 }
 
 // General shape: any number of K words, one thread per output, taps addressed with the
@@ -271,17 +226,14 @@ conv_general_kernel(const uint64_t* __restrict__ Xp, const uint64_t* __restrict_
 }
 
 template <int KW>
-void launch_stationary(const ConvParams& p, int64_t groups, int cblocks, int fb, hipStream_t s) {
-  const int pg = 1 << p.pg_shift;
-  dim3 grid((unsigned)ceil_div(groups, pg), (unsigned)ceil_div(cblocks, fb));
-  const dim3 block(64 * pg * fb);
-  const size_t lds = fb > 1 ? (size_t)pg * KW * 64 * 8 : 0;
+void launch_stationary(const ConvParams& p, int64_t groups, int cblocks, hipStream_t s) {
+  dim3 grid((unsigned)ceil_div(groups, 4), (unsigned)cblocks);
   if (p.out_f32 && p.alpha)
-    hipLaunchKernelGGL((conv_stationary_kernel<KW, kOutF32Alpha>), grid, block, lds, s, p);
+    hipLaunchKernelGGL((conv_stationary_kernel<KW, kOutF32Alpha>), grid, dim3(256), 0, s, p);
   else if (p.out_f32)
-    hipLaunchKernelGGL((conv_stationary_kernel<KW, kOutF32>), grid, block, lds, s, p);
+    hipLaunchKernelGGL((conv_stationary_kernel<KW, kOutF32>), grid, dim3(256), 0, s, p);
   else
-    hipLaunchKernelGGL((conv_stationary_kernel<KW, kOutI32>), grid, block, lds, s, p);
+    hipLaunchKernelGGL((conv_stationary_kernel<KW, kOutI32>), grid, dim3(256), 0, s, p);
 }
 
 }  // namespace
@@ -297,7 +249,6 @@ FastDiv make_fast_div(uint32_t d) {
 }
 
 int conv_filters_per_wave = 0;  // 0 = automatic; settable for tuning sweeps
-int conv_waves_per_block = 0;   // 0 = automatic; else 10 * pixel groups + filter blocks per workgroup
 int conv_path = 0;              // 0 = automatic, 1 = stationary, 2 = GEMM kernel, 3 = general
 
 hipError_t launch_binary_conv2d(const uint64_t* Xp, int N, int C, int H, int W, const uint64_t* Wp,
@@ -355,38 +306,25 @@ hipError_t launch_binary_conv2d(const uint64_t* Xp, int N, int C, int H, int W, 
     // more filters per wave amortise the gather better (below 8 the gather dominates), but
     // the grid should still fill the chip.  The 36-word kernel holds 88 VGPRs, i.e. five
     // waves per SIMD: a grid of at most 5 * 1024 waves is resident at once, and sweeps of the
-    // ResNet-stage shapes put the optimum at the smallest cn >= 8 that gets there (a grid
-    // slightly over it pays a second, mostly empty round).
+    // ResNet-stage shapes put the optimum at the smallest even cn >= 8 that gets there (a
+    // grid slightly over it pays a second, mostly empty round; the kernel consumes rows in
+    // pairs, so an odd count costs a row that is computed and dropped).
     int cn = conv_filters_per_wave;
     if (cn <= 0) {
       cn = 8;
-      while (cn < O && cn < 64 && groups * ceil_div(O, cn) > 5 * 1024) ++cn;
+      while (cn < O && cn < 64 && groups * ceil_div(O, cn) > 5 * 1024) cn += 2;
     }
     p.cn = cn;
     const int cblocks = (int)ceil_div(O, cn);
-    // Workgroup shape.  Four pixel groups sharing one filter block is the fastest layout
-    // whenever the grid has waves to spare (the scalar cache serves three of the four filter
-    // streams; sharing the gather instead measured slower).  Only a grid with very few pixel
-    // groups gains from the other extreme, one pixel group gathered once for four blocks.
-    int pg = 4, fb = 1;
-    if (groups * cblocks <= 2048 && cblocks >= 4) pg = 1, fb = 4;
-    if (conv_waves_per_block > 0) {
-      pg = conv_waves_per_block / 10;
-      fb = conv_waves_per_block % 10;
-      if ((pg != 1 && pg != 2 && pg != 4) || fb < 1 || fb > 4 || pg * fb > 8) pg = 4, fb = 1;
-    }
-    if (fb > cblocks) fb = cblocks;
-    p.pg_shift = pg == 4 ? 2 : (pg == 2 ? 1 : 0);
-    const int wpb = fb;
     switch (kwords) {
-      case 1: launch_stationary<1>(p, groups, cblocks, wpb, s); break;
-      case 2: launch_stationary<2>(p, groups, cblocks, wpb, s); break;
-      case 4: launch_stationary<4>(p, groups, cblocks, wpb, s); break;
-      case 9: launch_stationary<9>(p, groups, cblocks, wpb, s); break;
-      case 18: launch_stationary<18>(p, groups, cblocks, wpb, s); break;
-      case 25: launch_stationary<25>(p, groups, cblocks, wpb, s); break;
-      case 27: launch_stationary<27>(p, groups, cblocks, wpb, s); break;
-      default: launch_stationary<36>(p, groups, cblocks, wpb, s); break;
+      case 1: launch_stationary<1>(p, groups, cblocks, s); break;
+      case 2: launch_stationary<2>(p, groups, cblocks, s); break;
+      case 4: launch_stationary<4>(p, groups, cblocks, s); break;
+      case 9: launch_stationary<9>(p, groups, cblocks, s); break;
+      case 18: launch_stationary<18>(p, groups, cblocks, s); break;
+      case 25: launch_stationary<25>(p, groups, cblocks, s); break;
+      case 27: launch_stationary<27>(p, groups, cblocks, s); break;
+      default: launch_stationary<36>(p, groups, cblocks, s); break;
     }
     return hipGetLastError();
   }

@@ -32,8 +32,8 @@ struct ScalarSeg {
   static constexpr int n8 = r16 / 8, r8 = r16 % 8;
   static constexpr int n4 = r8 / 4, r4 = r8 % 4;
   static constexpr int n2 = r4 / 2, n1 = r4 % 2;
-  static_assert(n16 <= 2, "segment longer than 47 dwords");
-  u32x16 a16, b16;
+  static_assert(n16 <= 1, "segment longer than 31 dwords");
+  u32x16 a16;
   u32x8 a8;
   u32x4 a4;
   u32x2 a2;
@@ -43,8 +43,7 @@ struct ScalarSeg {
   // first load keeps that work behind the issue point.
   __device__ __forceinline__ void issue(const_u32_ptr src, int& tie) {
     asm volatile("" : "+v"(tie));
-    if constexpr (n16 >= 1) asm volatile("s_load_dwordx16 %0, %1, 0x0" : "=s"(a16) : "s"(src));
-    if constexpr (n16 >= 2) asm volatile("s_load_dwordx16 %0, %1, 0x40" : "=s"(b16) : "s"(src));
+    if constexpr (n16) asm volatile("s_load_dwordx16 %0, %1, 0x0" : "=s"(a16) : "s"(src));
     if constexpr (n8) asm volatile("s_load_dwordx8 %0, %1, %2" : "=s"(a8) : "s"(src), "i"(64 * n16));
     if constexpr (n4)
       asm volatile("s_load_dwordx4 %0, %1, %2" : "=s"(a4) : "s"(src), "i"(64 * n16 + 32 * n8));
@@ -56,25 +55,19 @@ struct ScalarSeg {
                    : "s"(src), "i"(64 * n16 + 32 * n8 + 16 * n4 + 8 * n2));
     asm volatile("" : "+v"(tie));
   }
-  // After s_waitcnt lgkmcnt(0): every piece is threaded through an asm statement so that no
-  // use can be placed before the wait (and the registers stay allocated up to it).
-  __device__ __forceinline__ void landed() {
-    if constexpr (n16 >= 1) asm volatile("" : "+s"(a16));
-    if constexpr (n16 >= 2) asm volatile("" : "+s"(b16));
+  // All outstanding scalar loads have landed after this; every piece is threaded through
+  // an asm statement so that no use can be placed before the wait.
+  __device__ __forceinline__ void wait() {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if constexpr (n16) asm volatile("" : "+s"(a16));
     if constexpr (n8) asm volatile("" : "+s"(a8));
     if constexpr (n4) asm volatile("" : "+s"(a4));
     if constexpr (n2) asm volatile("" : "+s"(a2));
     if constexpr (n1) asm volatile("" : "+s"(a1));
   }
-  // All outstanding scalar loads have landed after this.
-  __device__ __forceinline__ void wait() {
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    landed();
-  }
   template <int J>
   __device__ __forceinline__ uint32_t get() const {
-    if constexpr (J < 16 && n16 >= 1) return a16[J];
-    else if constexpr (J < 32 && n16 >= 2) return b16[J - 16];
+    if constexpr (J < 16 * n16) return a16[J];
     else if constexpr (J < 16 * n16 + 8 * n8) return a8[J - 16 * n16];
     else if constexpr (J < 16 * n16 + 8 * n8 + 4 * n4) return a4[J - 16 * n16 - 8 * n8];
     else if constexpr (J < 16 * n16 + 8 * n8 + 4 * n4 + 2 * n2) return a2[J - 16 * n16 - 8 * n8 - 4 * n4];
