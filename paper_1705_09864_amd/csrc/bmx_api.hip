@@ -290,9 +290,8 @@ int bmx_quant_gemm(const float* a, int64_t lda, int bits_a, const float* w, int6
   int32_t* rowsum = (int32_t*)(ws + q.rowsum_off);
   const int64_t Kw = bmx::words_for(K);
   const int64_t ldp = bmx::padded_words(K);
-  hipError_t e = bmx::launch_quant_pack(a, M, K, lda, bits_a, planes, ldp, rowsum, s);
-  if (e != hipSuccess) return BMX_ERR_HIP;
-  e = bmx::launch_pack_rows(w, N, K, ldw, wb, Kw, s);
+  // one launch quantises + plane-packs the activations and sign-packs the weights
+  hipError_t e = bmx::launch_quant_pack(a, M, K, lda, bits_a, planes, ldp, rowsum, w, N, ldw, wb, Kw, s);
   if (e != hipSuccess) return BMX_ERR_HIP;
   return hip_status(bmx::launch_plane_gemm((const uint32_t*)planes, ldp * 2, bits_a, rowsum, wb, Kw,
                                            M, N, K, out_i32_scaled, out_f32, ldo, s));

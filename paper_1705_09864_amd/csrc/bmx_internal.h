@@ -62,9 +62,12 @@ hipError_t launch_alpha_mean_abs(const float* w, int64_t rows, int64_t cols, int
 hipError_t launch_pack_rows_padded(const float* x, int64_t rows, int64_t cols, int64_t ldx,
                                    uint64_t* out, int64_t out_ld, hipStream_t s);
 // Eq. 1 quantise + bit-plane pack: plane p of row m is row m * bits + p of `planes`
-// (row stride ld_words, zero padded to it); rowsum[m] = sum_k q[m][k].
+// (row stride ld_words, zero padded to it); rowsum[m] = sum_k q[m][k].  With wrows > 0 the
+// same launch also sign-packs w [wrows, K] (row stride ldw) into wbits (row stride wb_ld).
 hipError_t launch_quant_pack(const float* a, int64_t M, int64_t K, int64_t lda, int bits,
-                             uint64_t* planes, int64_t ld_words, int32_t* rowsum, hipStream_t s);
+                             uint64_t* planes, int64_t ld_words, int32_t* rowsum, const float* w,
+                             int64_t wrows, int64_t ldw, uint64_t* wbits, int64_t wb_ld,
+                             hipStream_t s);
 
 // gemm.hip -------------------------------------------------------------------
 // out = K - 2*popcount(A ^ B); exactly one of C_i32 / C_f32 / C_bits non-null;

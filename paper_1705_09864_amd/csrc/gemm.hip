@@ -280,33 +280,58 @@ gemm_kernel(const GemmParams p) {
     asm volatile("" ::"v"(warm));
   }
 
+  // Per-column scale (GEMM) in every lane; per-row values (the filter's alpha of a
+  // convolution, the row sum of the plane mode) are fetched once, row i of the block into
+  // lane i, and handed out with readlane: a load per row would put one memory round trip
+  // after the other.
   float al = 1.0f;
   if (!CONV && (p.out == kGemmF32Alpha || p.out == kGemmBits) && p.alpha) al = p.alpha[nc];
-  auto finish = [&](int64_t m, int total) {  // count of output row m -> result -> C[m][n]
+  const int rows_out = rows_valid / p.planes;
+  const int64_t mbase = m0 / p.planes;
+  float row_alpha = 1.0f;
+  int row_sum = 0;
+  if (CONV && p.out == kGemmF32Alpha && lane < rows_out) row_alpha = p.alpha[mbase + lane];
+  if (p.out == kGemmPlanes && lane < rows_out) row_sum = p.rowsum[mbase + lane];
+  auto finish = [&](int lr, int total) {  // count of the block's output row lr -> C[m][n]
+    const int64_t m = mbase + lr;
     if (p.out == kGemmBits) {
       // the 64-lane mask of (scaled result >= 0) is the packed word of columns n0 .. n0+63
       const uint64_t word = __ballot(n < p.N && al * (float)(p.Kreal - 2 * total) >= 0.0f);
       if (lane == 0) p.C_bits[m * p.ldc + cb] = word;
-    } else if (n < p.N) {
-      const int64_t idx = m * p.ldc + lane_off;
-      if (p.out == kGemmPlanes) {
-        const int sv = 2 * total - p.rowsum[m];
+    } else if (p.out == kGemmPlanes) {
+      const int sv = 2 * total - __builtin_amdgcn_readlane(row_sum, lr);
+      if (n < p.N) {
+        const int64_t idx = m * p.ldc + lane_off;
         if (p.C_i32) p.C_i32[idx] = sv;
         if (p.C_f32) p.C_f32[idx] = (float)sv / p.levels;
-      } else {
+      }
+    } else {
+      const float ra = CONV ? __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, row_alpha), lr)) : al;
+      if (n < p.N) {
+        const int64_t idx = m * p.ldc + lane_off;
         const int dot = p.Kreal - 2 * total;
         if (p.out == kGemmI32) p.C_i32[idx] = dot;
         else if (p.out == kGemmF32) p.C_f32[idx] = (float)dot;
-        else p.C_f32[idx] = (CONV ? p.alpha[m] : al) * (float)dot;
+        else p.C_f32[idx] = ra * (float)dot;
       }
     }
   };
 
-  if (S == 1 && p.planes == 1 && p.tail0 >= p.tail1) {
-    // one wave holds the whole count of its rows: straight from the accumulators
+  if (S == 1 && p.tail0 >= p.tail1) {
+    // one wave holds the whole count of its rows: straight from the accumulators, the
+    // planes of one output row (consecutive virtual rows) weighted by their power of two
+    int total = 0, pl = 0, lr = 0;
 #pragma unroll
-    for (int r = 0; r < R; ++r)
-      if (r < rows_valid) finish(m0 + r, acc[r]);
+    for (int r = 0; r < R; ++r) {
+      if (r < rows_valid) {
+        total += acc[r] << pl;
+        if (++pl == p.planes) {
+          finish(lr++, total);
+          total = 0;
+          pl = 0;
+        }
+      }
+    }
     return;
   }
 
@@ -316,8 +341,6 @@ gemm_kernel(const GemmParams p) {
   for (int r = 0; r < R; ++r) lds[(wave * R + r) * 64 + lane] = (uint32_t)acc[r];
   __syncthreads();
 
-  const int rows_out = rows_valid / p.planes;
-  const int64_t mbase = m0 / p.planes;
   for (int rr = wave; rr < rows_out; rr += S) {
     int total = 0;
     for (int pl = 0; pl < p.planes; ++pl) {
@@ -344,7 +367,7 @@ gemm_kernel(const GemmParams p) {
       }
       total += t << pl;
     }
-    finish(mbase + rr, total);
+    finish(rr, total);
   }
 }
 
@@ -364,30 +387,26 @@ void launch_rs(const GemmParams& p, int S, hipStream_t s) {
 
 // Rows per wave and K split.  The kernel runs at full VALU rate once about four waves sit
 // on each of the 1024 SIMDs, and its fixed costs (launch, first B chunk, store drain) do not
-// shrink with fatter waves, so: the largest R whose grid alone reaches 4096 waves, else the
-// smallest K split that gets a 16-row (then 8-row) grid there.  Splits beyond 4 are a last
-// resort: the LDS a workgroup then holds (transposition tiles, partial counts) cuts the
-// workgroups per CU, which costs more than the extra waves bring.
+// shrink with fatter waves, so: the largest R whose grid reaches 4096 waves with a K split
+// of at most four.  Larger splits are a last resort: the LDS a workgroup then holds
+// (transposition tiles, partial counts) cuts the workgroups per CU, which costs more than
+// the extra waves bring.
 void choose_shape(const GemmParams& p, bool allow32, int& R_out, int& S_out) {
   const int64_t want = 4096;
   const int smax = p.nch < 8 ? (p.nch > 0 ? p.nch : 1) : 8;
   R_out = 8;
   S_out = smax < 4 ? smax : 4;
   bool found = false;
-  for (int R : {32, 16, 8}) {  // no split needed
+  // The most rows per wave (fewest loads of the stationary operand) whose grid still reaches
+  // the wanted number of waves with a K split of at most four.  Measured per call (operands
+  // fresh from the pack kernel), where more waves per block hide the longer first-touch
+  // latency: 2048x4096->1024 30.8 us as (32,4) against 32.4 as (8,1); 4096x4096->1024 53.7
+  // as (32,2) against 56.4 as (16,1).
+  for (int R : {32, 16, 8}) {
     if (R < p.planes || found || (R == 32 && !allow32)) continue;
     const int rpb = (R / p.planes) * p.planes;
-    if (ceil_div(p.N, 64) * ceil_div(p.Mv, rpb) >= want) {
-      R_out = R;
-      S_out = 1;
-      found = true;
-    }
-  }
-  for (int R : {16, 8}) {
-    if (R < p.planes || found) continue;
-    const int rpb = (R / p.planes) * p.planes;
     const int64_t blocks = ceil_div(p.N, 64) * ceil_div(p.Mv, rpb);
-    const int64_t S = ceil_div(want, blocks);
+    const int64_t S = blocks >= want ? 1 : ceil_div(want, blocks);
     if (S <= smax && S <= 4) {
       R_out = R;
       S_out = (int)S;

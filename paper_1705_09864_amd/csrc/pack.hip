@@ -14,14 +14,14 @@ static constexpr int kWave = 64;
 // streamed by a grid that just fills the chip (8 waves per SIMD, 4 KiB in flight each).
 constexpr int kSegWords = 16;
 
-__global__ void __launch_bounds__(256)
-pack_rows_kernel(const float* __restrict__ x, int64_t rows, int64_t cols, int64_t ldx,
-                 uint64_t* __restrict__ out, int64_t out_ld, int64_t Kw, int64_t segs_per_row) {
+__device__ __forceinline__ void pack_row_segments(const float* __restrict__ x, int64_t rows,
+                                                  int64_t cols, int64_t ldx,
+                                                  uint64_t* __restrict__ out, int64_t out_ld,
+                                                  int64_t Kw, int64_t segs_per_row,
+                                                  int64_t first_wave, int64_t nwaves) {
   const int lane = threadIdx.x & (kWave - 1);
-  const int64_t nwaves = (int64_t)gridDim.x * (blockDim.x / kWave);
   const int64_t total = rows * segs_per_row;
-  for (int64_t seg = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave); seg < total;
-       seg += nwaves) {
+  for (int64_t seg = first_wave; seg < total; seg += nwaves) {
     const int64_t r = segs_per_row == total ? 0 : seg / segs_per_row;
     const int64_t b = seg - r * segs_per_row;
     const float* xr = x + r * ldx;
@@ -46,6 +46,14 @@ pack_rows_kernel(const float* __restrict__ x, int64_t rows, int64_t cols, int64_
     const int64_t w = b * kSegWords + lane;
     if (lane < kSegWords && w < Kw) out[r * out_ld + w] = mine;
   }
+}
+
+__global__ void __launch_bounds__(256)
+pack_rows_kernel(const float* __restrict__ x, int64_t rows, int64_t cols, int64_t ldx,
+                 uint64_t* __restrict__ out, int64_t out_ld, int64_t Kw, int64_t segs_per_row) {
+  pack_row_segments(x, rows, cols, ldx, out, out_ld, Kw, segs_per_row,
+                    (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave),
+                    (int64_t)gridDim.x * (blockDim.x / kWave));
 }
 
 static void launch_pack_rows_grid(const float* x, int64_t rows, int64_t cols, int64_t ldx,
@@ -271,10 +279,21 @@ hipError_t launch_alpha_mean_abs(const float* w, int64_t rows, int64_t cols, int
 // fp32 product L * x.  Plane p of word w is the 64-lane mask of bit p of q and goes to row
 // m * bits + p of `planes` (words up to ld_words are written, zeros past the data).  The row
 // sum of q, needed by the plane GEMM epilogue, is reduced through LDS.
+// The weight operand of the same GEMM is sign-packed by the workgroups past the first M of
+// the same launch (wrows > 0), so that the two inputs cost one kernel launch, not two.
 __global__ void __launch_bounds__(256)
 quant_pack_kernel(const float* __restrict__ a, int64_t M, int64_t K, int64_t lda, int bits,
-                  uint64_t* __restrict__ planes, int64_t ld_words, int32_t* __restrict__ rowsum) {
+                  uint64_t* __restrict__ planes, int64_t ld_words, int32_t* __restrict__ rowsum,
+                  const float* __restrict__ w, int64_t wrows, int64_t ldw,
+                  uint64_t* __restrict__ wbits, int64_t wb_ld) {
   __shared__ int32_t part[4];
+  if ((int64_t)blockIdx.x >= M) {
+    const int64_t Kw = words_for(K);
+    pack_row_segments(w, wrows, K, ldw, wbits, wb_ld, Kw, ceil_div(Kw, kSegWords),
+                      ((int64_t)blockIdx.x - M) * 4 + (threadIdx.x / kWave),
+                      ((int64_t)gridDim.x - M) * 4);
+    return;
+  }
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
   const int64_t m = blockIdx.x;
@@ -318,9 +337,16 @@ quant_pack_kernel(const float* __restrict__ a, int64_t M, int64_t K, int64_t lda
 }
 
 hipError_t launch_quant_pack(const float* a, int64_t M, int64_t K, int64_t lda, int bits,
-                             uint64_t* planes, int64_t ld_words, int32_t* rowsum, hipStream_t s) {
-  hipLaunchKernelGGL(quant_pack_kernel, dim3((unsigned)M), dim3(256), 0, s, a, M, K, lda, bits,
-                     planes, ld_words, rowsum);
+                             uint64_t* planes, int64_t ld_words, int32_t* rowsum, const float* w,
+                             int64_t wrows, int64_t ldw, uint64_t* wbits, int64_t wb_ld,
+                             hipStream_t s) {
+  int64_t wblocks = 0;
+  if (wrows > 0) {
+    wblocks = ceil_div(wrows * ceil_div(words_for(K), kSegWords), 4);
+    if (wblocks > 256 * 8) wblocks = 256 * 8;
+  }
+  hipLaunchKernelGGL(quant_pack_kernel, dim3((unsigned)(M + wblocks)), dim3(256), 0, s, a, M, K, lda,
+                     bits, planes, ld_words, rowsum, w, wrows, ldw, wbits, wb_ld);
   return hipGetLastError();
 }
 
