@@ -79,6 +79,12 @@ hipError_t launch_quant_pack(const float* a, int64_t M, int64_t K, int64_t lda, 
 hipError_t launch_xnor_gemm(const uint32_t* A, bool a_padded, int64_t lda_dw, const uint64_t* B,
                             int64_t ldb_w, int M, int N, int K, const float* alpha_n, int32_t* C_i32,
                             float* C_f32, uint64_t* C_bits, int64_t ldc, hipStream_t s);
+// gemm_mfma.hip: the same product on the int8 matrix cores (operands expanded from bits in
+// registers).  Returns false when it does not take the problem (engine choice, alignment).
+bool launch_xnor_gemm_mfma(const uint64_t* A, int64_t lda_w, const uint64_t* B, int64_t ldb_w, int M,
+                           int N, int K, const float* alpha_n, int32_t* C_i32, float* C_f32,
+                           uint64_t* C_bits, int64_t ldc, hipStream_t s, hipError_t* err);
+extern int gemm_engine, gemm_mfma_ksplit;
 // S = 2*sum_p 2^p pc(plane_p & wb) - rowsum; out_f32 = float(S) / float(2^bits - 1).
 // planes_rows as written by launch_quant_pack (lda_dw dwords per row, chunk padded).
 hipError_t launch_plane_gemm(const uint32_t* planes_rows, int64_t lda_dw, int bits,

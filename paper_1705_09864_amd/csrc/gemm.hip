@@ -450,6 +450,12 @@ void no_conv(GemmParams& p) {
 hipError_t launch_xnor_gemm(const uint32_t* A, bool a_padded, int64_t lda_dw, const uint64_t* B,
                             int64_t ldb_w, int M, int N, int K, const float* alpha_n, int32_t* C_i32,
                             float* C_f32, uint64_t* C_bits, int64_t ldc, hipStream_t s) {
+  if ((lda_dw & 1) == 0) {
+    hipError_t err = hipSuccess;
+    if (launch_xnor_gemm_mfma((const uint64_t*)A, lda_dw / 2, B, ldb_w, M, N, K, alpha_n, C_i32, C_f32,
+                              C_bits, ldc, s, &err))
+      return err;
+  }
   GemmParams p;
   no_conv(p);
   p.A = A;

@@ -1,0 +1,290 @@
+// xnor GEMM on the int8 matrix cores.
+// Paper: Sec. 2.2.1 / Sec. 2.2.2 (Eq. 2): C[m][n] = K - 2 * popcount(A[m] xor B[n]).
+//
+// With a, b in {0, 1}:  a xor b = a + b - 2ab, so
+//     C[m][n] = K - 2 * pc(A[m]) - 2 * pc(B[n]) + 4 * sum_k a[m][k] * b[n][k],
+// and the last sum is an integer matrix product.  The operands stay bit-packed in memory and
+// in the loads (that is what keeps the traffic 32x below fp32, Sec. 1); a lane turns its
+// bits into 0/1 bytes in registers right before v_mfma_i32_32x32x32_i8 consumes them.
+// Expansion: for a 32-bit word w, (w >> j) & 0x01010101 puts bits j, j+8, j+16, j+24 into the
+// four bytes of a dword, so eight shift/and pairs give the 32 bytes two MFMA steps take.
+// Which bit lands in which byte does not matter as long as both operands use the same order:
+// a dot product is invariant under a permutation of k applied to both.
+//
+// Layout facts of the instruction (established on the hardware with a 32 x 32 x 64 tile
+// against a CPU count): operand A: lane l supplies row l % 32, operand B: lane l supplies
+// column l % 32, both the 16 bytes of k-half l / 32; result register v of lane l is
+// D[8 * (v / 4) + 4 * (l / 32) + v % 4][l % 32].  Lanes therefore run along n (the B
+// operand = weight rows), and stores are two 128-byte runs per instruction.
+//
+// A wave owns a (32 * TM) x (32 * TN) tile of C and a range of K; per row and "macro step"
+// of 1024 bits a lane loads its 64 bytes (one half of a 128-byte line, the other half-wave
+// takes the rest), counts their ones (pc(A[m]), pc(B[n]) come for free this way), and feeds
+// 32 MFMA steps.  The S waves of a workgroup split K and add their partial results in LDS.
+#include "bmx_internal.h"
+
+namespace bmx {
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+struct MfmaParams {
+  const uint64_t* A;  // [M][lda] words, tail bits zero
+  const uint64_t* B;  // [N][ldb] words
+  int64_t lda, ldb;   // in words, even (16-byte aligned rows)
+  int M, N, Kw, Kreal;  // Kw data words per row
+  int nsteps;           // piece steps in all: 4 per whole macro step + those of the last one
+  int tail_half;        // words per half-wave in the last macro step (8 when it is whole)
+  int tiles_n;
+  const float* alpha;  // per column n, or null
+  int32_t* C_i32;
+  float* C_f32;
+  uint32_t* C_bits;  // packed sign bits, addressed in 32-bit halves of the output words
+  int64_t ldc;       // elements per row (C_bits: 64-bit words per row)
+};
+
+// A macro step covers up to 16 words (1024 bits) of every row: half h of the wave takes
+// words h * half .. h * half + half - 1 of it (half = 8 except in a shorter last step), in
+// pieces of two words; piece step q is words h * half + 2q, + 1.  One piece step of all rows
+// feeds eight MFMA steps, and piece steps are the unit in which K is split over waves.
+__device__ __forceinline__ void load_row(const uint64_t* row, int w0, int Kw, bool whole, int qlo,
+                                         int qhi, uint4 (&r)[4]) {
+  const uint64_t* src = row + w0;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    if (q < qlo || q >= qhi) {  // wave-uniform: not this wave's piece
+      r[q] = make_uint4(0, 0, 0, 0);
+    } else if (whole) {
+      r[q] = *(const uint4*)(src + 2 * q);
+    } else {
+      const uint64_t lo = (w0 + 2 * q < Kw) ? src[2 * q] : 0;
+      const uint64_t hi = (w0 + 2 * q + 1 < Kw) ? src[2 * q + 1] : 0;
+      r[q] = make_uint4((uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32));
+    }
+  }
+}
+
+__device__ __forceinline__ int popcount_row(const uint4 (&r)[4]) {
+  int pc = 0;
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+    pc += __builtin_popcount(r[q].x) + __builtin_popcount(r[q].y) + __builtin_popcount(r[q].z) +
+          __builtin_popcount(r[q].w);
+  return pc;
+}
+
+__device__ __forceinline__ uint32_t dword_of(const uint4& v, int d) {
+  return d == 0 ? v.x : (d == 1 ? v.y : (d == 2 ? v.z : v.w));
+}
+
+__device__ __forceinline__ v4i expand(uint32_t w, int s) {
+  v4i e;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) e[j] = (int)((w >> (4 * s + j)) & 0x01010101u);
+  return e;
+}
+
+// One macro step of a wave's tile: load the pieces, count their ones, expand and multiply.
+template <int TM, int TN, bool ALL>
+__device__ __forceinline__ void macro_step(const uint64_t* (&arow)[TM], const uint64_t* (&brow)[TN],
+                                           int w0, int Kw, bool whole, int qlo, int qhi,
+                                           v16i (&acc)[TM][TN], int (&pa)[TM], int (&pb)[TN]) {
+  uint4 ra[TM][4], rb[TN][4];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) load_row(arow[i], w0, Kw, whole, qlo, qhi, ra[i]);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) load_row(brow[j], w0, Kw, whole, qlo, qhi, rb[j]);
+#pragma unroll
+  for (int i = 0; i < TM; ++i) pa[i] += popcount_row(ra[i]);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) pb[j] += popcount_row(rb[j]);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    if (!ALL && (q < qlo || q >= qhi)) continue;
+#pragma unroll
+    for (int d = 0; d < 4; ++d)
+#pragma unroll
+      for (int s = 0; s < 2; ++s) {
+        v4i ea[TM], eb[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) ea[i] = expand(dword_of(ra[i][q], d), s);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) eb[j] = expand(dword_of(rb[j][q], d), s);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ea[i], eb[j], acc[i][j], 0, 0, 0);
+      }
+  }
+}
+
+template <int TM, int TN>
+__global__ void __launch_bounds__(512)
+gemm_mfma_kernel(const MfmaParams p) {
+  extern __shared__ int red[];  // [TM * TN * 16][64] partial results when K is split
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int S = blockDim.x >> 6;
+  const int r = lane & 31, h = lane >> 5;
+  const int tile_n = blockIdx.x % p.tiles_n, tile_m = blockIdx.x / p.tiles_n;
+  const int m0 = tile_m * (32 * TM), n0 = tile_n * (32 * TN);
+
+  // rows past the matrix repeat its last row; their results are never stored
+  const uint64_t* arow[TM];
+  const uint64_t* brow[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) arow[i] = p.A + (int64_t)min(m0 + 32 * i + r, p.M - 1) * p.lda;
+#pragma unroll
+  for (int j = 0; j < TN; ++j) brow[j] = p.B + (int64_t)min(n0 + 32 * j + r, p.N - 1) * p.ldb;
+
+  v16i acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
+  int pa[TM], pb[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) pa[i] = 0;
+#pragma unroll
+  for (int j = 0; j < TN; ++j) pb[j] = 0;
+
+  // this wave's piece steps [ps0, ps1); step ps is piece ps % 4 of macro step ps / 4
+  const int ps0 = (int)((int64_t)wave * p.nsteps / S), ps1 = (int)((int64_t)(wave + 1) * p.nsteps / S);
+  const int last_mac = (p.nsteps - 1) >> 2;
+  for (int mac = ps0 >> 2; mac <= ((ps1 - 1) >> 2) && ps0 < ps1; ++mac) {
+    const int qlo = max(ps0 - 4 * mac, 0), qhi = min(ps1 - 4 * mac, 4);
+    const bool whole = mac < last_mac || (p.tail_half == 8 && (p.Kw & 15) == 0);  // wave-uniform
+    const int half = mac < last_mac ? 8 : p.tail_half;
+    const int w0 = mac * 16 + h * half;
+    // the common case (a whole macro step, all of it this wave's) without the piece tests
+    if (whole && qlo == 0 && qhi == 4) macro_step<TM, TN, true>(arow, brow, w0, p.Kw, true, 0, 4, acc, pa, pb);
+    else macro_step<TM, TN, false>(arow, brow, w0, p.Kw, whole, qlo, qhi, acc, pa, pb);
+  }
+
+  // ---- this wave's share of C - K:  4 * and_count - 2 * pc(A row) - 2 * pc(B row), all over
+  // the wave's K range.  A lane holds the counts of row / column r for its k-half; the other
+  // half sits 32 lanes away.
+#pragma unroll
+  for (int i = 0; i < TM; ++i) pa[i] += __shfl_xor(pa[i], 32);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) pb[j] += __shfl_xor(pb[j], 32);
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int row_in_block = 8 * (v / 4) + 4 * h + (v % 4);
+      const int pai = __shfl(pa[i], row_in_block);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) acc[i][j][v] = 4 * acc[i][j][v] - 2 * pai - 2 * pb[j];
+    }
+
+  auto store = [&](int i, int j, int v, int t) {  // called by whole waves only
+    const int m = m0 + 32 * i + 8 * (v / 4) + 4 * h + (v % 4);
+    const int n = n0 + 32 * j + r;
+    const int dot = p.Kreal + t;
+    if (p.C_bits) {
+      // the 64-lane mask of (scaled result >= 0): its low half is 32 columns of row m as seen
+      // by lanes 0..31, its high half the same columns of the row four below
+      const float al = (p.alpha && n < p.N) ? p.alpha[n] : 1.0f;
+      const uint64_t mask = __ballot(n < p.N && al * (float)dot >= 0.0f);
+      if (r == 0 && m < p.M)
+        p.C_bits[(int64_t)m * (2 * p.ldc) + (n >> 5)] = h ? (uint32_t)(mask >> 32) : (uint32_t)mask;
+    } else if (m < p.M && n < p.N) {
+      const int64_t idx = (int64_t)m * p.ldc + n;
+      if (p.C_i32) p.C_i32[idx] = dot;
+      else p.C_f32[idx] = p.alpha ? p.alpha[n] * (float)dot : (float)dot;
+    }
+  };
+
+  if (S == 1) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) store(i, j, v, acc[i][j][v]);
+    return;
+  }
+
+  // ---- K split: wave 0 writes its share, the others add theirs, then the entries are
+  // finished and stored by the waves in turn
+  if (wave == 0) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) red[((i * TN + j) * 16 + v) * 64 + lane] = acc[i][j][v];
+  }
+  __syncthreads();
+  if (wave != 0) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) atomicAdd(&red[((i * TN + j) * 16 + v) * 64 + lane], acc[i][j][v]);
+  }
+  __syncthreads();
+  for (int e = wave; e < TM * TN * 16; e += S) {
+    const int v = e & 15, blk = e >> 4;
+    store(blk / TN, blk % TN, v, red[e * 64 + lane]);
+  }
+}
+
+}  // namespace
+
+int gemm_engine = 0;  // 0 = automatic, 1 = xor/popcount kernel, 2 = matrix-core kernel when eligible
+int gemm_mfma_ksplit = 0;
+
+bool launch_xnor_gemm_mfma(const uint64_t* A, int64_t lda_w, const uint64_t* B, int64_t ldb_w, int M,
+                           int N, int K, const float* alpha_n, int32_t* C_i32, float* C_f32,
+                           uint64_t* C_bits, int64_t ldc, hipStream_t s, hipError_t* err) {
+  if (gemm_engine == 1) return false;
+  // 16-byte row pieces are loaded as one vector: rows must start 16-byte aligned
+  if ((lda_w & 1) || (ldb_w & 1) || ((uintptr_t)A & 15) || ((uintptr_t)B & 15)) return false;
+  MfmaParams p;
+  p.A = A;
+  p.B = B;
+  p.lda = lda_w;
+  p.ldb = ldb_w;
+  p.M = M;
+  p.N = N;
+  p.Kw = (int)words_for(K);
+  p.Kreal = K;
+  {
+    const int span = p.Kw - (int)((p.Kw - 1) / 16) * 16;  // words of the last macro step, 1..16
+    p.tail_half = (int)ceil_div(ceil_div(span, 2), 2) * 2;  // per half-wave, whole pieces
+    p.nsteps = (int)((p.Kw - 1) / 16) * 4 + p.tail_half / 2;
+  }
+  p.alpha = alpha_n;
+  p.C_i32 = C_i32;
+  p.C_f32 = C_f32;
+  p.C_bits = (uint32_t*)C_bits;
+  p.ldc = ldc;
+  // 64 x 64 per wave; 32 x 32 when that grid would leave most of the chip idle even with the
+  // deepest K split
+  const bool small = ceil_div(M, 64) * ceil_div(N, 64) * 8 < 1024;
+  const int T = small ? 1 : 2;
+  const int tiles_m = (int)ceil_div(M, 32 * T);
+  // (packed output: both 32-bit halves of the last word of a row get a block that writes them)
+  p.tiles_n = C_bits ? (int)(ceil_div(N, 64) * (2 / T)) : (int)ceil_div(N, 32 * T);
+  const int64_t tiles = (int64_t)tiles_m * p.tiles_n;
+  int S = gemm_mfma_ksplit;
+  if (S <= 0) S = (int)ceil_div(2048, tiles);  // about two waves per SIMD
+  if (S > 8) S = 8;
+  if (S > p.nsteps) S = p.nsteps;
+  if (S < 1) S = 1;
+  const size_t lds = S > 1 ? (size_t)T * T * 16 * 64 * 4 : 0;
+  if (small) hipLaunchKernelGGL((gemm_mfma_kernel<1, 1>), dim3((unsigned)tiles), dim3(64 * S), lds, s, p);
+  else hipLaunchKernelGGL((gemm_mfma_kernel<2, 2>), dim3((unsigned)tiles), dim3(64 * S), lds, s, p);
+  *err = hipGetLastError();
+  return true;
+}
+
+}  // namespace bmx

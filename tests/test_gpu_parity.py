@@ -290,6 +290,7 @@ def test_gemm_every_kernel_shape(rows_per_wave, ksplit):
     L = B.lib()
     rng = np.random.default_rng(rows_per_wave * 10 + ksplit)
     try:
+        assert L.bmx_tune_set(7, 1) == 0  # the xor/popcount engine
         for order in (0, 1):
             assert L.bmx_tune_set(2, rows_per_wave) == 0
             assert L.bmx_tune_set(3, ksplit) == 0
@@ -316,8 +317,44 @@ def test_gemm_every_kernel_shape(rows_per_wave, ksplit):
                 np.testing.assert_array_equal(S.cpu().numpy(), rS)
                 assert_f32_close(f.cpu().numpy(), r32)
     finally:
-        for key in (2, 3, 4):
+        for key in (2, 3, 4, 7):
             L.bmx_tune_set(key, 0)
+
+
+@pytest.mark.parametrize("ksplit", [0, 1, 2, 3, 8])
+def test_gemm_matrix_core_engine(ksplit):
+    """The matrix-core kernel (bits expanded to int8 in registers), forced through the tuning
+    hook: ragged tiles in M and N, K tails inside and at the end of a 1024-bit step, every
+    K split, every output kind."""
+    L = B.lib()
+    rng = np.random.default_rng(100 + ksplit)
+    try:
+        assert L.bmx_tune_set(7, 2) == 0
+        assert L.bmx_tune_set(8, ksplit) == 0
+        for (M, N, K) in [(37, 70, 5000), (8, 64, 1024), (100, 129, 3072 + 64), (1, 1, 1), (64, 64, 63),
+                          (65, 33, 1025), (130, 200, 2048 + 128),
+                          # enough tiles for the 64 x 64 per wave variant
+                          (700, 801, 1100), (1031, 640, 2048 + 64)]:
+            A = oracle.binarize_pack(rng.standard_normal((M, K)).astype(np.float32), 1)
+            Bm = oracle.binarize_pack(rng.standard_normal((N, K)).astype(np.float32), 1)
+            # rows padded to an even number of words: the kernel's 16-byte pieces need it
+            ld = (A.shape[1] + 1) // 2 * 2
+            Ad = np.zeros((M, ld), dtype=np.uint64); Ad[:, :A.shape[1]] = A
+            Bd = np.zeros((N, ld), dtype=np.uint64); Bd[:, :A.shape[1]] = Bm
+            got = B.xnor_gemm(dev(Ad.view(np.int64)), dev(Bd.view(np.int64)), K).cpu().numpy()
+            np.testing.assert_array_equal(got, oracle.xnor_gemm(A, Bm, K))
+        for (batch, fin, fout) in [(19, 2500, 75), (70, 4096, 130)]:
+            x = rng.standard_normal((batch, fin)).astype(np.float32)
+            w = rng.uniform(-1, 1, (fout, fin)).astype(np.float32)
+            alpha = oracle.alpha_mean_abs(w)
+            ri, rf = oracle.binary_fc(x, w, alpha)
+            Wp = B.binarize_pack(dev(w), 1)
+            np.testing.assert_array_equal(B.binary_fc(dev(x), Wp, integer_out=True).cpu().numpy(), ri)
+            assert_f32_close(B.binary_fc(dev(x), Wp, alpha=dev(alpha)).cpu().numpy(), rf)
+            assert_f32_close(B.binary_fc(dev(x), Wp).cpu().numpy(), ri.astype(np.float32))
+    finally:
+        L.bmx_tune_set(7, 0)
+        L.bmx_tune_set(8, 0)
 
 
 # ------------------------------------------------------------------ convolution kernel paths
@@ -400,22 +437,38 @@ def test_fc_packed_chain(small):
     np.testing.assert_array_equal(B.binary_fc_packed(bits1, w1.shape[0], W2p, mode="i32").cpu().numpy(), r2i)
 
 
-@pytest.mark.parametrize("batch,fin,fout", [(1, 1, 1), (5, 27, 3), (3, 180, 70), (66, 1000, 130), (9, 2100, 64)])
-def test_fc_packed_bits_ragged(batch, fin, fout):
+@pytest.mark.parametrize("engine", [1, 2])
+@pytest.mark.parametrize("batch,fin,fout", [(1, 1, 1), (5, 27, 3), (3, 180, 70), (66, 1000, 130), (9, 2100, 64),
+                                            (300, 1100, 700)])
+def test_fc_packed_bits_ragged(batch, fin, fout, engine):
     """Ragged shapes, poisoned output, and scales of either sign and zero: the bit is the
-    IEEE compare (alpha * dot >= 0) of the fp32 product, as bmx_binarize_pack would see it."""
+    IEEE compare (alpha * dot >= 0) of the fp32 product, as bmx_binarize_pack would see it.
+    Both GEMM engines (xor/popcount and matrix cores), forced through the tuning hook; rows
+    are padded to an even word count, which the matrix-core kernel needs to take the problem."""
     rng = np.random.default_rng(batch + fin + fout)
     x = rng.standard_normal((batch, fin)).astype(np.float32)
     w = rng.uniform(-1, 1, (fout, fin)).astype(np.float32)
     alpha = rng.standard_normal(fout).astype(np.float32)
     alpha[::3] = 0.0
     _, rf = oracle.binary_fc(x, w, alpha)
-    Xp, Wp = B.binarize_pack(dev(x), 1), B.binarize_pack(dev(w), 1)
-    out = dev(np.full((batch, (fout + 63) // 64 + 1), -1, dtype=np.int64))   # one spare word
-    B.binary_fc_packed(Xp, fin, Wp, alpha=dev(alpha), mode="bits", out=out)
-    got = host_u64(out)
-    np.testing.assert_array_equal(got[:, :-1], oracle.binarize_pack(rf, 1))
-    assert (got[:, -1] == np.uint64(0xFFFFFFFFFFFFFFFF)).all()              # spare word untouched
-    nob = B.binary_fc_packed(Xp, fin, Wp, mode="bits")                       # no scale: sign of dot
-    ri, _ = oracle.binary_fc(x, w)
-    np.testing.assert_array_equal(host_u64(nob), oracle.binarize_pack(ri.astype(np.float32), 1))
+
+    def even_rows(a):
+        p = oracle.binarize_pack(a, 1)
+        out = np.zeros((p.shape[0], (p.shape[1] + 1) // 2 * 2), dtype=np.uint64)
+        out[:, :p.shape[1]] = p
+        return dev(out.view(np.int64))
+
+    Xp, Wp = even_rows(x), even_rows(w)
+    L = B.lib()
+    try:
+        assert L.bmx_tune_set(7, engine) == 0
+        out = dev(np.full((batch, (fout + 63) // 64 + 1), -1, dtype=np.int64))   # one spare word
+        B.binary_fc_packed(Xp, fin, Wp, alpha=dev(alpha), mode="bits", out=out)
+        got = host_u64(out)
+        np.testing.assert_array_equal(got[:, :-1], oracle.binarize_pack(rf, 1))
+        assert (got[:, -1] == np.uint64(0xFFFFFFFFFFFFFFFF)).all()              # spare word untouched
+        nob = B.binary_fc_packed(Xp, fin, Wp, mode="bits")                       # no scale: sign of dot
+        ri, _ = oracle.binary_fc(x, w)
+        np.testing.assert_array_equal(host_u64(nob), oracle.binarize_pack(ri.astype(np.float32), 1))
+    finally:
+        L.bmx_tune_set(7, 0)
