@@ -84,6 +84,9 @@ hipError_t launch_xnor_gemm(const uint32_t* A, bool a_padded, int64_t lda_dw, co
 bool launch_xnor_gemm_mfma(const uint64_t* A, int64_t lda_w, const uint64_t* B, int64_t ldb_w, int M,
                            int N, int K, const float* alpha_n, int32_t* C_i32, float* C_f32,
                            uint64_t* C_bits, int64_t ldc, hipStream_t s, hipError_t* err);
+bool launch_plane_gemm_mfma(const uint64_t* planes_rows, int64_t lda_w, int bits, const int32_t* rowsum,
+                            const uint64_t* Wb, int64_t ldb_w, int M, int N, int K, int32_t* S_out,
+                            float* out_f32, int64_t ldo, hipStream_t s, hipError_t* err);
 extern int gemm_engine, gemm_mfma_ksplit;
 // S = 2*sum_p 2^p pc(plane_p & wb) - rowsum; out_f32 = float(S) / float(2^bits - 1).
 // planes_rows as written by launch_quant_pack (lda_dw dwords per row, chunk padded).

@@ -490,6 +490,12 @@ hipError_t launch_xnor_gemm(const uint32_t* A, bool a_padded, int64_t lda_dw, co
 hipError_t launch_plane_gemm(const uint32_t* planes_rows, int64_t lda_dw, int bits,
                              const int32_t* rowsum, const uint64_t* Wb, int64_t ldb_w, int M, int N,
                              int K, int32_t* S, float* out_f32, int64_t ldo, hipStream_t s) {
+  if ((lda_dw & 1) == 0) {
+    hipError_t err = hipSuccess;
+    if (launch_plane_gemm_mfma((const uint64_t*)planes_rows, lda_dw / 2, bits, rowsum, Wb, ldb_w, M, N, K, S,
+                               out_f32, ldo, s, &err))
+      return err;
+  }
   GemmParams p;
   no_conv(p);
   p.A = planes_rows;

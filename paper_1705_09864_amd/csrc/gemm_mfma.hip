@@ -21,6 +21,11 @@
 // of 1024 bits a lane loads its 64 bytes (one half of a 128-byte line, the other half-wave
 // takes the rest), counts their ones (pc(A[m]), pc(B[n]) come for free this way), and feeds
 // 32 MFMA steps.  The S waves of a workgroup split K and add their partial results in LDS.
+//
+// The k-bit activations of the quantised GEMM (Sec. 2.1, Eq. 1) ride the same kernel: the A
+// byte becomes the quantised value itself, q = sum_p 2^p * plane_p, assembled from the bit
+// planes during the expansion, the B byte stays the weight bit, and one pass gives
+// sum_k q * wb for all planes at once; S = 2 * that - rowsum as in the plane-by-plane form.
 #include "bmx_internal.h"
 
 namespace bmx {
@@ -39,6 +44,8 @@ struct MfmaParams {
   int tail_half;        // words per half-wave in the last macro step (8 when it is whole)
   int tiles_n;
   const float* alpha;  // per column n, or null
+  const int32_t* rowsum;  // plane mode: sum_k q[m][k]
+  float levels;           // plane mode: 2^bits - 1
   int32_t* C_i32;
   float* C_f32;
   uint32_t* C_bits;  // packed sign bits, addressed in 32-bit halves of the output words
@@ -86,20 +93,36 @@ __device__ __forceinline__ v4i expand(uint32_t w, int s) {
   return e;
 }
 
-// One macro step of a wave's tile: load the pieces, count their ones, expand and multiply.
-template <int TM, int TN, bool ALL>
-__device__ __forceinline__ void macro_step(const uint64_t* (&arow)[TM], const uint64_t* (&brow)[TN],
+// Plane pl of a k-bit value: the same bits as expand(), shifted to bit pl of every byte.
+__device__ __forceinline__ v4i expand_plane(uint32_t w, int s, int pl, v4i e) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int sh = 4 * s + j - pl;  // (w >> (4s + j)) << pl
+    const uint32_t x = sh >= 0 ? (w >> sh) : (w << -sh);
+    e[j] |= (int)(x & (0x01010101u << pl));
+  }
+  return e;
+}
+
+// One macro step of a wave's tile: load the pieces, count their ones (XNOR form only),
+// expand and multiply.  PL bit planes make up the A operand.
+template <int TM, int TN, int PL, bool XNOR, bool ALL>
+__device__ __forceinline__ void macro_step(const uint64_t* (&arow)[TM][PL], const uint64_t* (&brow)[TN],
                                            int w0, int Kw, bool whole, int qlo, int qhi,
                                            v16i (&acc)[TM][TN], int (&pa)[TM], int (&pb)[TN]) {
-  uint4 ra[TM][4], rb[TN][4];
+  uint4 ra[TM][PL][4], rb[TN][4];
 #pragma unroll
-  for (int i = 0; i < TM; ++i) load_row(arow[i], w0, Kw, whole, qlo, qhi, ra[i]);
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int pl = 0; pl < PL; ++pl) load_row(arow[i][pl], w0, Kw, whole, qlo, qhi, ra[i][pl]);
 #pragma unroll
   for (int j = 0; j < TN; ++j) load_row(brow[j], w0, Kw, whole, qlo, qhi, rb[j]);
+  if (XNOR) {
 #pragma unroll
-  for (int i = 0; i < TM; ++i) pa[i] += popcount_row(ra[i]);
+    for (int i = 0; i < TM; ++i) pa[i] += popcount_row(ra[i][0]);
 #pragma unroll
-  for (int j = 0; j < TN; ++j) pb[j] += popcount_row(rb[j]);
+    for (int j = 0; j < TN; ++j) pb[j] += popcount_row(rb[j]);
+  }
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     if (!ALL && (q < qlo || q >= qhi)) continue;
@@ -109,7 +132,11 @@ __device__ __forceinline__ void macro_step(const uint64_t* (&arow)[TM], const ui
       for (int s = 0; s < 2; ++s) {
         v4i ea[TM], eb[TN];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) ea[i] = expand(dword_of(ra[i][q], d), s);
+        for (int i = 0; i < TM; ++i) {
+          ea[i] = expand(dword_of(ra[i][0][q], d), s);
+#pragma unroll
+          for (int pl = 1; pl < PL; ++pl) ea[i] = expand_plane(dword_of(ra[i][pl][q], d), s, pl, ea[i]);
+        }
 #pragma unroll
         for (int j = 0; j < TN; ++j) eb[j] = expand(dword_of(rb[j][q], d), s);
 #pragma unroll
@@ -121,7 +148,7 @@ __device__ __forceinline__ void macro_step(const uint64_t* (&arow)[TM], const ui
   }
 }
 
-template <int TM, int TN>
+template <int TM, int TN, int PL, bool XNOR>
 __global__ void __launch_bounds__(512)
 gemm_mfma_kernel(const MfmaParams p) {
   extern __shared__ int red[];  // [TM * TN * 16][64] partial results when K is split
@@ -133,10 +160,14 @@ gemm_mfma_kernel(const MfmaParams p) {
   const int m0 = tile_m * (32 * TM), n0 = tile_n * (32 * TN);
 
   // rows past the matrix repeat its last row; their results are never stored
-  const uint64_t* arow[TM];
+  // (plane pl of row m is row m * PL + pl of A)
+  const uint64_t* arow[TM][PL];
   const uint64_t* brow[TN];
 #pragma unroll
-  for (int i = 0; i < TM; ++i) arow[i] = p.A + (int64_t)min(m0 + 32 * i + r, p.M - 1) * p.lda;
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int pl = 0; pl < PL; ++pl)
+      arow[i][pl] = p.A + ((int64_t)min(m0 + 32 * i + r, p.M - 1) * PL + pl) * p.lda;
 #pragma unroll
   for (int j = 0; j < TN; ++j) brow[j] = p.B + (int64_t)min(n0 + 32 * j + r, p.N - 1) * p.ldb;
 
@@ -162,30 +193,44 @@ gemm_mfma_kernel(const MfmaParams p) {
     const int half = mac < last_mac ? 8 : p.tail_half;
     const int w0 = mac * 16 + h * half;
     // the common case (a whole macro step, all of it this wave's) without the piece tests
-    if (whole && qlo == 0 && qhi == 4) macro_step<TM, TN, true>(arow, brow, w0, p.Kw, true, 0, 4, acc, pa, pb);
-    else macro_step<TM, TN, false>(arow, brow, w0, p.Kw, whole, qlo, qhi, acc, pa, pb);
+    if (whole && qlo == 0 && qhi == 4)
+      macro_step<TM, TN, PL, XNOR, true>(arow, brow, w0, p.Kw, true, 0, 4, acc, pa, pb);
+    else
+      macro_step<TM, TN, PL, XNOR, false>(arow, brow, w0, p.Kw, whole, qlo, qhi, acc, pa, pb);
   }
 
   // ---- this wave's share of C - K:  4 * and_count - 2 * pc(A row) - 2 * pc(B row), all over
   // the wave's K range.  A lane holds the counts of row / column r for its k-half; the other
-  // half sits 32 lanes away.
+  // half sits 32 lanes away.  (The plane form keeps the plain sums: its row term is the
+  // given rowsum, applied once at the end.)
+  if (XNOR) {
 #pragma unroll
-  for (int i = 0; i < TM; ++i) pa[i] += __shfl_xor(pa[i], 32);
+    for (int i = 0; i < TM; ++i) pa[i] += __shfl_xor(pa[i], 32);
 #pragma unroll
-  for (int j = 0; j < TN; ++j) pb[j] += __shfl_xor(pb[j], 32);
+    for (int j = 0; j < TN; ++j) pb[j] += __shfl_xor(pb[j], 32);
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int row_in_block = 8 * (v / 4) + 4 * h + (v % 4);
-      const int pai = __shfl(pa[i], row_in_block);
+      for (int v = 0; v < 16; ++v) {
+        const int row_in_block = 8 * (v / 4) + 4 * h + (v % 4);
+        const int pai = __shfl(pa[i], row_in_block);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) acc[i][j][v] = 4 * acc[i][j][v] - 2 * pai - 2 * pb[j];
-    }
+        for (int j = 0; j < TN; ++j) acc[i][j][v] = 4 * acc[i][j][v] - 2 * pai - 2 * pb[j];
+      }
+  }
 
   auto store = [&](int i, int j, int v, int t) {  // called by whole waves only
     const int m = m0 + 32 * i + 8 * (v / 4) + 4 * h + (v % 4);
     const int n = n0 + 32 * j + r;
+    if (!XNOR) {
+      if (m < p.M && n < p.N) {
+        const int sv = 2 * t - p.rowsum[m];
+        const int64_t idx = (int64_t)m * p.ldc + n;
+        if (p.C_i32) p.C_i32[idx] = sv;
+        if (p.C_f32) p.C_f32[idx] = (float)sv / p.levels;
+      }
+      return;
+    }
     const int dot = p.Kreal + t;
     if (p.C_bits) {
       // the 64-lane mask of (scaled result >= 0): its low half is 32 columns of row m as seen
@@ -242,6 +287,26 @@ gemm_mfma_kernel(const MfmaParams p) {
 int gemm_engine = 0;  // 0 = automatic, 1 = xor/popcount kernel, 2 = matrix-core kernel when eligible
 int gemm_mfma_ksplit = 0;
 
+namespace {
+
+void set_k_steps(MfmaParams& p, int K) {
+  p.Kw = (int)words_for(K);
+  p.Kreal = K;
+  const int span = p.Kw - (int)((p.Kw - 1) / 16) * 16;    // words of the last macro step, 1..16
+  p.tail_half = (int)ceil_div(ceil_div(span, 2), 2) * 2;  // per half-wave, whole pieces
+  p.nsteps = (int)((p.Kw - 1) / 16) * 4 + p.tail_half / 2;
+}
+
+int choose_split(int64_t tiles, int nsteps) {
+  int S = gemm_mfma_ksplit;
+  if (S <= 0) S = (int)ceil_div(2048, tiles);  // about two waves per SIMD
+  if (S > 8) S = 8;
+  if (S > nsteps) S = nsteps;
+  return S < 1 ? 1 : S;
+}
+
+}  // namespace
+
 bool launch_xnor_gemm_mfma(const uint64_t* A, int64_t lda_w, const uint64_t* B, int64_t ldb_w, int M,
                            int N, int K, const float* alpha_n, int32_t* C_i32, float* C_f32,
                            uint64_t* C_bits, int64_t ldc, hipStream_t s, hipError_t* err) {
@@ -255,14 +320,10 @@ bool launch_xnor_gemm_mfma(const uint64_t* A, int64_t lda_w, const uint64_t* B, 
   p.ldb = ldb_w;
   p.M = M;
   p.N = N;
-  p.Kw = (int)words_for(K);
-  p.Kreal = K;
-  {
-    const int span = p.Kw - (int)((p.Kw - 1) / 16) * 16;  // words of the last macro step, 1..16
-    p.tail_half = (int)ceil_div(ceil_div(span, 2), 2) * 2;  // per half-wave, whole pieces
-    p.nsteps = (int)((p.Kw - 1) / 16) * 4 + p.tail_half / 2;
-  }
+  set_k_steps(p, K);
   p.alpha = alpha_n;
+  p.rowsum = nullptr;
+  p.levels = 1.0f;
   p.C_i32 = C_i32;
   p.C_f32 = C_f32;
   p.C_bits = (uint32_t*)C_bits;
@@ -275,14 +336,47 @@ bool launch_xnor_gemm_mfma(const uint64_t* A, int64_t lda_w, const uint64_t* B, 
   // (packed output: both 32-bit halves of the last word of a row get a block that writes them)
   p.tiles_n = C_bits ? (int)(ceil_div(N, 64) * (2 / T)) : (int)ceil_div(N, 32 * T);
   const int64_t tiles = (int64_t)tiles_m * p.tiles_n;
-  int S = gemm_mfma_ksplit;
-  if (S <= 0) S = (int)ceil_div(2048, tiles);  // about two waves per SIMD
-  if (S > 8) S = 8;
-  if (S > p.nsteps) S = p.nsteps;
-  if (S < 1) S = 1;
+  const int S = choose_split(tiles, p.nsteps);
   const size_t lds = S > 1 ? (size_t)T * T * 16 * 64 * 4 : 0;
-  if (small) hipLaunchKernelGGL((gemm_mfma_kernel<1, 1>), dim3((unsigned)tiles), dim3(64 * S), lds, s, p);
-  else hipLaunchKernelGGL((gemm_mfma_kernel<2, 2>), dim3((unsigned)tiles), dim3(64 * S), lds, s, p);
+  if (small)
+    hipLaunchKernelGGL((gemm_mfma_kernel<1, 1, 1, true>), dim3((unsigned)tiles), dim3(64 * S), lds, s, p);
+  else
+    hipLaunchKernelGGL((gemm_mfma_kernel<2, 2, 1, true>), dim3((unsigned)tiles), dim3(64 * S), lds, s, p);
+  *err = hipGetLastError();
+  return true;
+}
+
+// S = 2 * sum_k q[m][k] * wb[n][k] - rowsum[m] with q assembled from `bits` planes (1 or 2).
+bool launch_plane_gemm_mfma(const uint64_t* planes_rows, int64_t lda_w, int bits, const int32_t* rowsum,
+                            const uint64_t* Wb, int64_t ldb_w, int M, int N, int K, int32_t* S_out,
+                            float* out_f32, int64_t ldo, hipStream_t s, hipError_t* err) {
+  if (gemm_engine == 1 || bits > 2) return false;
+  if ((lda_w & 1) || (ldb_w & 1) || ((uintptr_t)planes_rows & 15) || ((uintptr_t)Wb & 15)) return false;
+  MfmaParams p;
+  p.A = planes_rows;
+  p.B = Wb;
+  p.lda = lda_w;
+  p.ldb = ldb_w;
+  p.M = M;
+  p.N = N;
+  set_k_steps(p, K);
+  p.alpha = nullptr;
+  p.rowsum = rowsum;
+  p.levels = (float)((1u << bits) - 1u);
+  p.C_i32 = S_out;
+  p.C_f32 = out_f32;
+  p.C_bits = nullptr;
+  p.ldc = ldo;
+  // 32 rows x 64 columns per wave: the two planes of a row double the A registers
+  const int tiles_m = (int)ceil_div(M, 32);
+  p.tiles_n = (int)ceil_div(N, 64);
+  const int64_t tiles = (int64_t)tiles_m * p.tiles_n;
+  const int S = choose_split(tiles, p.nsteps);
+  const size_t lds = S > 1 ? (size_t)2 * 16 * 64 * 4 : 0;
+  if (bits == 1)
+    hipLaunchKernelGGL((gemm_mfma_kernel<1, 2, 1, false>), dim3((unsigned)tiles), dim3(64 * S), lds, s, p);
+  else
+    hipLaunchKernelGGL((gemm_mfma_kernel<1, 2, 2, false>), dim3((unsigned)tiles), dim3(64 * S), lds, s, p);
   *err = hipGetLastError();
   return true;
 }

@@ -352,6 +352,16 @@ def test_gemm_matrix_core_engine(ksplit):
             np.testing.assert_array_equal(B.binary_fc(dev(x), Wp, integer_out=True).cpu().numpy(), ri)
             assert_f32_close(B.binary_fc(dev(x), Wp, alpha=dev(alpha)).cpu().numpy(), rf)
             assert_f32_close(B.binary_fc(dev(x), Wp).cpu().numpy(), ri.astype(np.float32))
+        # k-bit activations (1 and 2 bit planes assembled into the int8 operand)
+        for bits in (1, 2):
+            for (M, N, K) in [(21, 70, 2200), (1, 1, 1), (33, 65, 1024), (100, 130, 4096 + 200)]:
+                a = rng.uniform(0, 1, (M, K)).astype(np.float32)
+                a[rng.random(a.shape) < 0.05] = 0.5  # a rounding tie of Eq. 1 for k = 2
+                wq = rng.standard_normal((N, K)).astype(np.float32)
+                Sg, fg = B.quant_gemm(dev(a), dev(wq), bits)
+                rS, r64, r32 = oracle.quant_gemm(a, wq, bits)
+                np.testing.assert_array_equal(Sg.cpu().numpy(), rS)
+                assert_f32_close(fg.cpu().numpy(), r32)
     finally:
         L.bmx_tune_set(7, 0)
         L.bmx_tune_set(8, 0)
