@@ -197,6 +197,24 @@ def main():
         def alu(ops, us):
             return {"us": us, "Tbinop_s": ops / us / 1e6, "frac_valu": ops / (us * 1e-6) / VALU_PEAK_BINOPS}
 
+        MFMA_INT8_PEAK = 5.0e15  # dense int8 matrix-core peak, op/s
+
+        def mfma(ops, us, int8_ops=None):
+            # kernels that run on the int8 matrix cores: binary ops as for the popcount path,
+            # plus the int8 multiply-adds actually issued (all bit planes in one pass) against
+            # the matrix-core peak
+            d = alu(ops, us)
+            d["engine"] = "int8 matrix cores"
+            d["frac_mfma_int8"] = (int8_ops if int8_ops is not None else ops) / (us * 1e-6) / MFMA_INT8_PEAK
+            return d
+
+        def popcount_engine(fn):
+            B.lib().bmx_tune_set(7, 1)
+            try:
+                return kernel_us(fn, 50)
+            finally:
+                B.lib().bmx_tune_set(7, 0)
+
         def hbm(nbytes, us):
             return {"us": us, "GB_s": nbytes / us / 1e3, "frac_hbm": nbytes / (us * 1e-6) / HBM_PEAK}
 
@@ -220,15 +238,20 @@ def main():
         h2 = torch.empty((256, 4096), dtype=torch.float32, device="cuda")
         i3 = torch.empty((256, 4096), dtype=torch.int32, device="cuda")
         ws3 = torch.empty(B.workspace_bytes(B.OP_BINARY_FC, (256, 9216, 4096)), dtype=torch.uint8, device="cuda")
-        other["config3_fc1_call_256x4096x9216"] = alu(2.0 * 256 * 4096 * 9216, kernel_us(
+        other["config3_fc1_call_256x4096x9216"] = mfma(2.0 * 256 * 4096 * 9216, kernel_us(
             lambda: B.binary_fc(x3, W31p, alpha=al1, out=h1, workspace=ws3), 50))
-        other["config3_fc2_call_256x4096x4096"] = alu(2.0 * 256 * 4096 * 4096, kernel_us(
+        other["config3_fc2_call_256x4096x4096"] = mfma(2.0 * 256 * 4096 * 4096, kernel_us(
             lambda: B.binary_fc(h1, W32p, alpha=al2, out=h2, workspace=ws3), 50))
         X3p, H1p = B.binarize_pack(x3, 1), B.binarize_pack(h1, 1)
-        other["config3_fc1_gemm_kernel"] = alu(2.0 * 256 * 4096 * 9216, kernel_us(
+        other["config3_fc1_gemm_kernel"] = mfma(2.0 * 256 * 4096 * 9216, kernel_us(
             lambda: B.xnor_gemm(X3p, W31p, 9216, out=i3), 50))
-        other["config3_fc2_gemm_kernel"] = alu(2.0 * 256 * 4096 * 4096, kernel_us(
+        other["config3_fc2_gemm_kernel"] = mfma(2.0 * 256 * 4096 * 4096, kernel_us(
             lambda: B.xnor_gemm(H1p, W32p, 4096, out=i3), 50))
+        # the same products on the xor/popcount kernel (the engine is kept where it wins)
+        other["config3_fc1_gemm_kernel_popcount_engine"] = alu(2.0 * 256 * 4096 * 9216, popcount_engine(
+            lambda: B.xnor_gemm(X3p, W31p, 9216, out=i3)))
+        other["config3_fc2_gemm_kernel_popcount_engine"] = alu(2.0 * 256 * 4096 * 4096, popcount_engine(
+            lambda: B.xnor_gemm(H1p, W32p, 4096, out=i3)))
         # the two layers chained: through fp32 activations (pack + GEMM, twice) and through
         # packed sign bits handed from layer to layer (one pack, two GEMMs)
         chain_ops = 2.0 * 256 * 4096 * (9216 + 4096)
@@ -244,8 +267,8 @@ def main():
             B.binary_fc_packed(X3p, 9216, W31p, alpha=al1, mode="bits", out=bits1)
             B.binary_fc_packed(bits1, 4096, W32p, alpha=al2, mode="f32", out=h2)
 
-        other["config3_chain_via_fp32_activations"] = alu(chain_ops, kernel_us(chain_fp32, 50))
-        other["config3_chain_via_packed_bits"] = alu(chain_ops, kernel_us(chain_bits, 50))
+        other["config3_chain_via_fp32_activations"] = mfma(chain_ops, kernel_us(chain_fp32, 50))
+        other["config3_chain_via_packed_bits"] = mfma(chain_ops, kernel_us(chain_bits, 50))
         other["config3_activation_pack_256x9216"] = hbm(x3.numel() * 4 + X3p.numel() * 8, kernel_us(
             lambda: B.binarize_pack(x3, 1, out=X3p)))
         other["config3_weight_pack_4096x9216_cache_assisted"] = hbm(w31.numel() * 4 + W31p.numel() * 8, kernel_us(
@@ -283,8 +306,11 @@ def main():
         ws5 = torch.empty(B.workspace_bytes(B.OP_QUANT_GEMM, (1024, 1024, 4096, 2, 1)), dtype=torch.uint8,
                           device="cuda")
         o5 = torch.empty((1024, 1024), dtype=torch.float32, device="cuda")
-        other["config5_quant_gemm_call_2planes"] = alu(2.0 * 2 * 1024 * 1024 * 4096, kernel_us(
-            lambda: B.quant_gemm(a5, w5, 2, want_int=False, out_float=o5, workspace=ws5), 20))
+        other["config5_quant_gemm_call_2planes"] = mfma(2.0 * 2 * 1024 * 1024 * 4096, kernel_us(
+            lambda: B.quant_gemm(a5, w5, 2, want_int=False, out_float=o5, workspace=ws5), 20),
+            int8_ops=2.0 * 1024 * 1024 * 4096)
+        other["config5_quant_gemm_call_2planes_popcount_engine"] = alu(2.0 * 2 * 1024 * 1024 * 4096, popcount_engine(
+            lambda: B.quant_gemm(a5, w5, 2, want_int=False, out_float=o5, workspace=ws5)))
 
         # the paper's own efficiency workload (Sec. 3.1): 5x5 kernels, 64 filters, batch 200,
         # 8x8 outputs -> GEMM view M = 64, N = 12800, K = 25 * C_in, C_in swept
@@ -295,8 +321,9 @@ def main():
             oq = torch.empty((200, 64, 8, 8), dtype=torch.float32, device="cuda")
             wsq = torch.empty(B.workspace_bytes(B.OP_BINARY_CONV2D, (200, cin, 12, 12, 64, 5, 5, 1, 0)),
                               dtype=torch.uint8, device="cuda")
-            other["paper_sec3_1_conv5x5_cin%d_call" % cin] = alu(2.0 * 64 * 12800 * 25 * cin, kernel_us(
-                lambda: B.binary_conv2d(xq, Wq, 64, 5, 5, 1, 0, alpha=alq, out=oq, workspace=wsq)))
+            other["paper_sec3_1_conv5x5_cin%d_call" % cin] = (alu if cin == 64 else mfma)(
+                2.0 * 64 * 12800 * 25 * cin, kernel_us(
+                    lambda: B.binary_conv2d(xq, Wq, 64, 5, 5, 1, 0, alpha=alq, out=oq, workspace=wsq)))
 
     # ------------------------------------------------------------------ CPU oracle beside it
     cpu = None

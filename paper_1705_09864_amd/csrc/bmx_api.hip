@@ -68,6 +68,7 @@ int bmx_tune_set(int key, int value) {
   else if (key == 5) bmx::conv_path = value;
   else if (key == 7) bmx::gemm_engine = value;
   else if (key == 8) bmx::gemm_mfma_ksplit = value;
+  else if (key == 9) bmx::gemm_mfma_tile = value;
   else return BMX_ERR_UNSUPPORTED;
   return BMX_OK;
 }

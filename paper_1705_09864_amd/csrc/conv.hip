@@ -273,9 +273,17 @@ hipError_t launch_binary_conv2d(const uint64_t* Xp, int N, int C, int H, int W, 
   // The stationary kernel (whole K in registers, no accumulators) is the faster one on every
   // shape it can hold; a K beyond 36 words goes to the GEMM kernel, which splits K and rows.
   int path = conv_path;
+  if (path == 4) path = 0;
   if (path == 1 && !stationary_ok) path = 0;
   if (path == 2 && !image32) path = 0;
   if (path == 0) path = stationary_ok ? 1 : (image32 ? 2 : 3);
+  if (conv_path == 4 || (conv_path == 0 && !stationary_ok)) {
+    // K beyond the stationary kernel: the matrix cores (measured 1.4 to 1.9 times faster
+    // than the xor/popcount GEMM kernel on 5 x 5 kernels over 128 .. 512 channels)
+    hipError_t err = hipSuccess;
+    if (launch_conv_mfma(Xp, N, C, H, W, Wp, O, KH, KW, stride, pad, alpha, out_i32, out_f32, s, &err))
+      return err;
+  }
   if (path == 2)
     return launch_conv_gemm(Xp, N, C, H, W, Wp, O, KH, KW, stride, pad, alpha, out_i32, out_f32, s);
   if (path == 1) {

@@ -26,6 +26,11 @@
 // byte becomes the quantised value itself, q = sum_p 2^p * plane_p, assembled from the bit
 // planes during the expansion, the B byte stays the weight bit, and one pass gives
 // sum_k q * wb for all planes at once; S = 2 * that - rowsum as in the plane-by-plane form.
+//
+// Convolution (Sec. 3.1: M = filters, N = batch * output pixels, K = kh * kw * C): operand A
+// is the packed filter matrix, operand B the im2col row of a pixel, gathered word by word
+// from the halo-padded packed image (word w of the row is channel word w % Cw of tap w / Cw);
+// lanes run along pixels, so the NCHW stores stay coalesced, and alpha is per row.
 #include "bmx_internal.h"
 
 namespace bmx {
@@ -46,6 +51,9 @@ struct MfmaParams {
   const float* alpha;  // per column n, or null
   const int32_t* rowsum;  // plane mode: sum_k q[m][k]
   float levels;           // plane mode: 2^bits - 1
+  // convolution mode: B is the packed image, column n is output pixel n (flat over images)
+  int HoWo, Wo, Hp, Wpp, Cw, stride, KWid;
+  FastDiv div_howo, div_wo, div_cw, div_kw;
   int32_t* C_i32;
   float* C_f32;
   uint32_t* C_bits;  // packed sign bits, addressed in 32-bit halves of the output words
@@ -68,6 +76,26 @@ __device__ __forceinline__ void load_row(const uint64_t* row, int w0, int Kw, bo
     } else {
       const uint64_t lo = (w0 + 2 * q < Kw) ? src[2 * q] : 0;
       const uint64_t hi = (w0 + 2 * q + 1 < Kw) ? src[2 * q + 1] : 0;
+      r[q] = make_uint4((uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32));
+    }
+  }
+}
+
+// The same pieces of an im2col row: word w sits at the pixel's base + tab[w], the offset of
+// its tap and channel word (a table the workgroup builds once in LDS).  With an even number
+// of channel words per pixel a piece never straddles two taps and is one 16-byte load.
+__device__ __forceinline__ void load_im2col(const uint64_t* base, int w0, const MfmaParams& p, const int* tab,
+                                            int qlo, int qhi, uint4 (&r)[4]) {
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int w = w0 + 2 * q;
+    r[q] = make_uint4(0, 0, 0, 0);
+    if (q < qlo || q >= qhi) continue;
+    if ((p.Cw & 1) == 0) {
+      if (w < p.Kw) r[q] = *(const uint4*)(base + tab[w]);
+    } else {
+      const uint64_t lo = w < p.Kw ? base[tab[w]] : 0;
+      const uint64_t hi = w + 1 < p.Kw ? base[tab[w + 1]] : 0;
       r[q] = make_uint4((uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32));
     }
   }
@@ -106,9 +134,10 @@ __device__ __forceinline__ v4i expand_plane(uint32_t w, int s, int pl, v4i e) {
 
 // One macro step of a wave's tile: load the pieces, count their ones (XNOR form only),
 // expand and multiply.  PL bit planes make up the A operand.
-template <int TM, int TN, int PL, bool XNOR, bool ALL>
+template <int TM, int TN, int PL, bool XNOR, bool CONV, bool ALL>
 __device__ __forceinline__ void macro_step(const uint64_t* (&arow)[TM][PL], const uint64_t* (&brow)[TN],
-                                           int w0, int Kw, bool whole, int qlo, int qhi,
+                                           int w0, int Kw, bool whole, int qlo, int qhi, const MfmaParams& p,
+                                           const int* tab,
                                            v16i (&acc)[TM][TN], int (&pa)[TM], int (&pb)[TN]) {
   uint4 ra[TM][PL][4], rb[TN][4];
 #pragma unroll
@@ -116,7 +145,10 @@ __device__ __forceinline__ void macro_step(const uint64_t* (&arow)[TM][PL], cons
 #pragma unroll
     for (int pl = 0; pl < PL; ++pl) load_row(arow[i][pl], w0, Kw, whole, qlo, qhi, ra[i][pl]);
 #pragma unroll
-  for (int j = 0; j < TN; ++j) load_row(brow[j], w0, Kw, whole, qlo, qhi, rb[j]);
+  for (int j = 0; j < TN; ++j) {
+    if (CONV) load_im2col(brow[j], w0, p, tab, qlo, qhi, rb[j]);
+    else load_row(brow[j], w0, Kw, whole, qlo, qhi, rb[j]);
+  }
   if (XNOR) {
 #pragma unroll
     for (int i = 0; i < TM; ++i) pa[i] += popcount_row(ra[i][0]);
@@ -148,7 +180,7 @@ __device__ __forceinline__ void macro_step(const uint64_t* (&arow)[TM][PL], cons
   }
 }
 
-template <int TM, int TN, int PL, bool XNOR>
+template <int TM, int TN, int PL, bool XNOR, bool CONV>
 __global__ void __launch_bounds__(512)
 gemm_mfma_kernel(const MfmaParams p) {
   extern __shared__ int red[];  // [TM * TN * 16][64] partial results when K is split
@@ -158,6 +190,17 @@ gemm_mfma_kernel(const MfmaParams p) {
   const int r = lane & 31, h = lane >> 5;
   const int tile_n = blockIdx.x % p.tiles_n, tile_m = blockIdx.x / p.tiles_n;
   const int m0 = tile_m * (32 * TM), n0 = tile_n * (32 * TN);
+  // convolution: word offset of im2col word w from a pixel's base, behind the reduction buffer
+  int* tab = red + (S > 1 ? TM * TN * 16 * 64 : 0);
+  if (CONV) {
+    for (int w = threadIdx.x; w < p.Kw; w += blockDim.x) {
+      const uint32_t tap = fast_div((uint32_t)w, p.div_cw);
+      const uint32_t kh = fast_div(tap, p.div_kw);
+      tab[w] = (int)((kh * (uint32_t)p.Wpp + (tap - kh * (uint32_t)p.KWid)) * (uint32_t)p.Cw +
+                     ((uint32_t)w - tap * (uint32_t)p.Cw));
+    }
+    __syncthreads();
+  }
 
   // rows past the matrix repeat its last row; their results are never stored
   // (plane pl of row m is row m * PL + pl of A)
@@ -168,8 +211,21 @@ gemm_mfma_kernel(const MfmaParams p) {
 #pragma unroll
     for (int pl = 0; pl < PL; ++pl)
       arow[i][pl] = p.A + ((int64_t)min(m0 + 32 * i + r, p.M - 1) * PL + pl) * p.lda;
+  uint32_t pix_img[TN], pix_rem[TN];  // convolution: image and pixel within it of column n
 #pragma unroll
-  for (int j = 0; j < TN; ++j) brow[j] = p.B + (int64_t)min(n0 + 32 * j + r, p.N - 1) * p.ldb;
+  for (int j = 0; j < TN; ++j) {
+    const int n = min(n0 + 32 * j + r, p.N - 1);
+    if (CONV) {
+      pix_img[j] = fast_div((uint32_t)n, p.div_howo);
+      pix_rem[j] = (uint32_t)n - pix_img[j] * (uint32_t)p.HoWo;
+      const uint32_t ho = fast_div(pix_rem[j], p.div_wo);
+      const uint32_t wo = pix_rem[j] - ho * (uint32_t)p.Wo;
+      brow[j] = p.B + (((int64_t)pix_img[j] * p.Hp + ho * p.stride) * p.Wpp + wo * p.stride) * p.Cw;
+    } else {
+      pix_img[j] = pix_rem[j] = 0;
+      brow[j] = p.B + (int64_t)n * p.ldb;
+    }
+  }
 
   v16i acc[TM][TN];
 #pragma unroll
@@ -194,9 +250,9 @@ gemm_mfma_kernel(const MfmaParams p) {
     const int w0 = mac * 16 + h * half;
     // the common case (a whole macro step, all of it this wave's) without the piece tests
     if (whole && qlo == 0 && qhi == 4)
-      macro_step<TM, TN, PL, XNOR, true>(arow, brow, w0, p.Kw, true, 0, 4, acc, pa, pb);
+      macro_step<TM, TN, PL, XNOR, CONV, true>(arow, brow, w0, p.Kw, true, 0, 4, p, tab, acc, pa, pb);
     else
-      macro_step<TM, TN, PL, XNOR, false>(arow, brow, w0, p.Kw, whole, qlo, qhi, acc, pa, pb);
+      macro_step<TM, TN, PL, XNOR, CONV, false>(arow, brow, w0, p.Kw, whole, qlo, qhi, p, tab, acc, pa, pb);
   }
 
   // ---- this wave's share of C - K:  4 * and_count - 2 * pc(A row) - 2 * pc(B row), all over
@@ -232,6 +288,14 @@ gemm_mfma_kernel(const MfmaParams p) {
       return;
     }
     const int dot = p.Kreal + t;
+    if (CONV) {
+      if (m < p.M && n < p.N) {  // NCHW: plane m of the pixel's image
+        const int64_t idx = ((int64_t)pix_img[j] * p.M + m) * p.HoWo + pix_rem[j];
+        if (p.C_i32) p.C_i32[idx] = dot;
+        else p.C_f32[idx] = p.alpha ? p.alpha[m] * (float)dot : (float)dot;
+      }
+      return;
+    }
     if (p.C_bits) {
       // the 64-lane mask of (scaled result >= 0): its low half is 32 columns of row m as seen
       // by lanes 0..31, its high half the same columns of the row four below
@@ -286,6 +350,7 @@ gemm_mfma_kernel(const MfmaParams p) {
 
 int gemm_engine = 0;  // 0 = automatic, 1 = xor/popcount kernel, 2 = matrix-core kernel when eligible
 int gemm_mfma_ksplit = 0;
+int gemm_mfma_tile = 0;  // 1 forces the 32 x 32 per wave variant
 
 namespace {
 
@@ -330,7 +395,7 @@ bool launch_xnor_gemm_mfma(const uint64_t* A, int64_t lda_w, const uint64_t* B, 
   p.ldc = ldc;
   // 64 x 64 per wave; 32 x 32 when that grid would leave most of the chip idle even with the
   // deepest K split
-  const bool small = ceil_div(M, 64) * ceil_div(N, 64) * 8 < 1024;
+  const bool small = ceil_div(M, 64) * ceil_div(N, 64) * 8 < 1024 || gemm_mfma_tile == 1;
   const int T = small ? 1 : 2;
   const int tiles_m = (int)ceil_div(M, 32 * T);
   // (packed output: both 32-bit halves of the last word of a row get a block that writes them)
@@ -339,9 +404,9 @@ bool launch_xnor_gemm_mfma(const uint64_t* A, int64_t lda_w, const uint64_t* B, 
   const int S = choose_split(tiles, p.nsteps);
   const size_t lds = S > 1 ? (size_t)T * T * 16 * 64 * 4 : 0;
   if (small)
-    hipLaunchKernelGGL((gemm_mfma_kernel<1, 1, 1, true>), dim3((unsigned)tiles), dim3(64 * S), lds, s, p);
+    hipLaunchKernelGGL((gemm_mfma_kernel<1, 1, 1, true, false>), dim3((unsigned)tiles), dim3(64 * S), lds, s, p);
   else
-    hipLaunchKernelGGL((gemm_mfma_kernel<2, 2, 1, true>), dim3((unsigned)tiles), dim3(64 * S), lds, s, p);
+    hipLaunchKernelGGL((gemm_mfma_kernel<2, 2, 1, true, false>), dim3((unsigned)tiles), dim3(64 * S), lds, s, p);
   *err = hipGetLastError();
   return true;
 }
@@ -374,9 +439,69 @@ bool launch_plane_gemm_mfma(const uint64_t* planes_rows, int64_t lda_w, int bits
   const int S = choose_split(tiles, p.nsteps);
   const size_t lds = S > 1 ? (size_t)2 * 16 * 64 * 4 : 0;
   if (bits == 1)
-    hipLaunchKernelGGL((gemm_mfma_kernel<1, 2, 1, false>), dim3((unsigned)tiles), dim3(64 * S), lds, s, p);
+    hipLaunchKernelGGL((gemm_mfma_kernel<1, 2, 1, false, false>), dim3((unsigned)tiles), dim3(64 * S), lds, s, p);
   else
-    hipLaunchKernelGGL((gemm_mfma_kernel<1, 2, 2, false>), dim3((unsigned)tiles), dim3(64 * S), lds, s, p);
+    hipLaunchKernelGGL((gemm_mfma_kernel<1, 2, 2, false, false>), dim3((unsigned)tiles), dim3(64 * S), lds, s, p);
+  *err = hipGetLastError();
+  return true;
+}
+
+static inline int64_t Wpp_host(int W, int pad) { return (int64_t)W + 2 * pad; }
+
+// The convolution on the matrix cores; Xp, Wp as for launch_binary_conv2d.
+bool launch_conv_mfma(const uint64_t* Xp, int Nimg, int C, int H, int W, const uint64_t* Wp, int O, int KH,
+                      int KW, int stride, int pad, const float* alpha, int32_t* out_i32, float* out_f32,
+                      hipStream_t s, hipError_t* err) {
+  if (gemm_engine == 1) return false;
+  const int Ho = (H + 2 * pad - KH) / stride + 1;
+  const int Wo = (W + 2 * pad - KW) / stride + 1;
+  const int Cw = (int)words_for(C);
+  const int kwords = KH * KW * Cw;
+  const int64_t ld_words = conv_weight_row_words(kwords);
+  const int64_t P = (int64_t)Nimg * Ho * Wo;
+  if ((ld_words & 1) || ((uintptr_t)Wp & 15) || ((uintptr_t)Xp & 15) || P >= ((int64_t)1 << 31)) return false;
+  if ((int64_t)KH * Wpp_host(W, pad) * Cw >= ((int64_t)1 << 31)) return false;
+  MfmaParams p;
+  p.A = Wp;
+  p.B = Xp;
+  p.lda = ld_words;
+  p.ldb = 0;
+  p.M = O;
+  p.N = (int)P;
+  set_k_steps(p, 64 * kwords);
+  p.Kreal = C * KH * KW;
+  p.alpha = alpha;
+  p.rowsum = nullptr;
+  p.levels = 1.0f;
+  p.C_i32 = out_i32;
+  p.C_f32 = out_f32;
+  p.C_bits = nullptr;
+  p.ldc = 0;
+  p.HoWo = Ho * Wo;
+  p.Wo = Wo;
+  p.Hp = H + 2 * pad;
+  p.Wpp = W + 2 * pad;
+  p.Cw = Cw;
+  p.stride = stride;
+  p.KWid = KW;
+  p.div_howo = make_fast_div((uint32_t)(Ho * Wo));
+  p.div_wo = make_fast_div((uint32_t)Wo);
+  p.div_cw = make_fast_div((uint32_t)Cw);
+  p.div_kw = make_fast_div((uint32_t)KW);
+  // (32 x 32 tiles up to twice the grid size of the GEMM rule: measured on the 5 x 5 shapes)
+  const bool small = ceil_div(O, 64) * ceil_div(P, 64) * 8 < 2048 || gemm_mfma_tile == 1;
+  const int T = small ? 1 : 2;
+  const int tiles_m = (int)ceil_div(O, 32 * T);
+  p.tiles_n = (int)ceil_div(P, 32 * T);
+  const int64_t tiles = (int64_t)tiles_m * p.tiles_n;
+  if (tiles >= ((int64_t)1 << 31)) return false;
+  const int S = choose_split(tiles, p.nsteps);
+  const size_t lds = (S > 1 ? (size_t)T * T * 16 * 64 * 4 : 0) + (size_t)kwords * 4;
+  if (lds > 64 * 1024) return false;
+  if (small)
+    hipLaunchKernelGGL((gemm_mfma_kernel<1, 1, 1, true, true>), dim3((unsigned)tiles), dim3(64 * S), lds, s, p);
+  else
+    hipLaunchKernelGGL((gemm_mfma_kernel<2, 2, 1, true, true>), dim3((unsigned)tiles), dim3(64 * S), lds, s, p);
   *err = hipGetLastError();
   return true;
 }

@@ -391,16 +391,18 @@ def test_conv_big_k(N, C, H, W, O, k, s, p):
     assert_f32_close(run_conv(x, w, s, p, alpha=alpha), rf)
 
 
-@pytest.mark.parametrize("path", [1, 2, 3])
+@pytest.mark.parametrize("path", [1, 2, 3, 4])
 def test_conv_every_path(path):
-    """The three convolution kernels (register-stationary, GEMM kernel, one-thread-per-output),
-    each forced through the tuning hook on the shapes it accepts, with every K split."""
+    """The four convolution kernels (register-stationary, GEMM kernel, one-thread-per-output,
+    matrix cores), each forced through the tuning hook on the shapes it accepts, with every K
+    split."""
     L = B.lib()
     try:
         assert L.bmx_tune_set(5, path) == 0
-        for ksplit in ((0, 2, 3) if path == 2 else (0,)):
+        for ksplit in ((0, 2, 3) if path in (2, 4) else (0,)):
             L.bmx_tune_set(3, ksplit)
-            for (N, C, H, W, O, k, s, p) in CONV_CASES[:10] + BIG_K_CONV_CASES[:2]:
+            L.bmx_tune_set(8, ksplit)
+            for (N, C, H, W, O, k, s, p) in (CONV_CASES if path == 4 else CONV_CASES[:10]) + BIG_K_CONV_CASES[:2]:
                 rng = np.random.default_rng(N + 10 * C + 100 * H + 1000 * O + k + s + p + path)
                 x = rng.standard_normal((N, C, H, W)).astype(np.float32)
                 w = rng.standard_normal((O, C, k, k)).astype(np.float32)
@@ -411,6 +413,7 @@ def test_conv_every_path(path):
     finally:
         L.bmx_tune_set(5, 0)
         L.bmx_tune_set(3, 0)
+        L.bmx_tune_set(8, 0)
 
 
 def test_conv_weight_rows_are_zero_padded():
