@@ -197,15 +197,15 @@ def main():
         def alu(ops, us):
             return {"us": us, "Tbinop_s": ops / us / 1e6, "frac_valu": ops / (us * 1e-6) / VALU_PEAK_BINOPS}
 
-        MFMA_INT8_PEAK = 5.0e15  # dense int8 matrix-core peak, op/s
+        MFMA_FP4_PEAK = 10.1e15  # dense FP4 matrix-core peak, flop/s
 
-        def mfma(ops, us, int8_ops=None):
-            # kernels that run on the int8 matrix cores: binary ops as for the popcount path,
-            # plus the int8 multiply-adds actually issued (all bit planes in one pass) against
-            # the matrix-core peak
+        def mfma(ops, us, mfma_flops=None):
+            # kernels that run on the matrix cores (bits expanded to FP4 nibbles in registers):
+            # binary ops as for the popcount path, plus the multiply-adds actually issued (all
+            # bit planes of a k-bit operand in one pass) against the FP4 matrix-core peak
             d = alu(ops, us)
-            d["engine"] = "int8 matrix cores"
-            d["frac_mfma_int8"] = (int8_ops if int8_ops is not None else ops) / (us * 1e-6) / MFMA_INT8_PEAK
+            d["engine"] = "FP4 matrix cores"
+            d["frac_mfma_fp4"] = (mfma_flops if mfma_flops is not None else ops) / (us * 1e-6) / MFMA_FP4_PEAK
             return d
 
         def popcount_engine(fn):
@@ -290,12 +290,18 @@ def main():
             ho4, wo4 = B.conv_out_hw(14, 14, 3, 3, s4, 1)
             o4 = torch.empty((64, 256, ho4, wo4), dtype=torch.float32, device="cuda")
             ops4 = 2.0 * 256 * 64 * ho4 * wo4 * 2304
-            other["config4_conv_s%d_kernel" % s4] = alu(ops4, kernel_us(
+            other["config4_conv_s%d_kernel" % s4] = mfma(ops4, kernel_us(
                 lambda: B.binary_conv2d_packed(xp4, 256, W4p, 256, 3, 3, s4, 1, alpha=al4, out=o4)))
             ws4 = torch.empty(B.workspace_bytes(B.OP_BINARY_CONV2D, (64, 256, 14, 14, 256, 3, 3, s4, 1)),
                               dtype=torch.uint8, device="cuda")
-            other["config4_conv_s%d_call" % s4] = alu(ops4, kernel_us(
+            other["config4_conv_s%d_call" % s4] = mfma(ops4, kernel_us(
                 lambda: B.binary_conv2d(x4, W4p, 256, 3, 3, s4, 1, alpha=al4, out=o4, workspace=ws4)))
+            B.lib().bmx_tune_set(5, 1)  # the register-stationary xor/popcount kernel beside it
+            try:
+                other["config4_conv_s%d_kernel_popcount_engine" % s4] = alu(ops4, kernel_us(
+                    lambda: B.binary_conv2d_packed(xp4, 256, W4p, 256, 3, 3, s4, 1, alpha=al4, out=o4)))
+            finally:
+                B.lib().bmx_tune_set(5, 0)
             if s4 == 1:
                 other["config4_pack_nchw"] = hbm(x4.numel() * 4 + xp4.numel() * 8, kernel_us(
                     lambda: B.pack_nchw(x4, 1, out=xp4)))
@@ -308,7 +314,7 @@ def main():
         o5 = torch.empty((1024, 1024), dtype=torch.float32, device="cuda")
         other["config5_quant_gemm_call_2planes"] = mfma(2.0 * 2 * 1024 * 1024 * 4096, kernel_us(
             lambda: B.quant_gemm(a5, w5, 2, want_int=False, out_float=o5, workspace=ws5), 20),
-            int8_ops=2.0 * 1024 * 1024 * 4096)
+            mfma_flops=2.0 * 1024 * 1024 * 4096)
         other["config5_quant_gemm_call_2planes_popcount_engine"] = alu(2.0 * 2 * 1024 * 1024 * 4096, popcount_engine(
             lambda: B.quant_gemm(a5, w5, 2, want_int=False, out_float=o5, workspace=ws5)))
 

@@ -277,9 +277,12 @@ hipError_t launch_binary_conv2d(const uint64_t* Xp, int N, int C, int H, int W, 
   if (path == 1 && !stationary_ok) path = 0;
   if (path == 2 && !image32) path = 0;
   if (path == 0) path = stationary_ok ? 1 : (image32 ? 2 : 3);
-  if (conv_path == 4 || (conv_path == 0 && !stationary_ok)) {
-    // K beyond the stationary kernel: the matrix cores (measured 1.4 to 1.9 times faster
-    // than the xor/popcount GEMM kernel on 5 x 5 kernels over 128 .. 512 channels)
+  if (conv_path == 4 || (conv_path == 0 && (!stationary_ok || kwords >= 36))) {
+    // From K = 36 words (3 x 3 over 256 channels) on, the matrix cores: measured 15.7 against
+    // 18.6 us on 64 x 256 x 14 x 14 -> 256 filters, 7.8 against 10.2 us on its stride-2 twin,
+    // and 1.4 to 2.3 times faster than the xor/popcount GEMM kernel beyond the stationary
+    // kernel's reach (5 x 5 kernels over 128 .. 512 channels).  Below that (18 words: 8.8
+    // against 7.9 us; 9 words: 11.1 against 8.3 us) the stationary kernel stays ahead.
     hipError_t err = hipSuccess;
     if (launch_conv_mfma(Xp, N, C, H, W, Wp, O, KH, KW, stride, pad, alpha, out_i32, out_f32, s, &err))
       return err;

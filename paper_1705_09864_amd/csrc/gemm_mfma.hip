@@ -39,6 +39,11 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+template <bool F4> struct AccOf { typedef v16i type; };
+template <> struct AccOf<true> { typedef v16f type; };
 
 struct MfmaParams {
   const uint64_t* A;  // [M][lda] words, tail bits zero
@@ -121,6 +126,33 @@ __device__ __forceinline__ v4i expand(uint32_t w, int s) {
   return e;
 }
 
+// The FP4 form (v_mfma_scale_f32_32x32x64_f8f6f4 with both operands E2M1): an element is a
+// nibble, and the E2M1 codes 0, 1, 2, 3 are the values 0, 0.5, 1, 1.5, i.e. half the code.
+// With a block scale of 2 on both operands (E8M0 code 128) a nibble holding q in 0..3 is
+// the value q: a bit in nibble bit 0 gives {0, 1}, a second plane in nibble bit 1 gives the
+// 2-bit quantised value, every product is a small integer and the fp32 accumulation is
+// exact below 2^24.  One 32-bit word expands into four dwords of eight nibbles each
+// ((w >> d) & 0x11111111), which is one MFMA step of K = 64: half the VALU work and half
+// the matrix-core time per bit of the int8 form.  (Checked on the hardware against a CPU
+// count before use, like the int8 layout.)
+__device__ __forceinline__ v8i expand4(uint32_t w) {
+  v8i e;
+#pragma unroll
+  for (int d = 0; d < 4; ++d) e[d] = (int)((w >> d) & 0x11111111u);
+#pragma unroll
+  for (int d = 4; d < 8; ++d) e[d] = 0;
+  return e;
+}
+__device__ __forceinline__ v8i expand4_plane(uint32_t w, int pl, v8i e) {
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    const int sh = d - pl;
+    const uint32_t x = sh >= 0 ? (w >> sh) : (w << -sh);
+    e[d] |= (int)(x & (0x11111111u << pl));
+  }
+  return e;
+}
+
 // Plane pl of a k-bit value: the same bits as expand(), shifted to bit pl of every byte.
 __device__ __forceinline__ v4i expand_plane(uint32_t w, int s, int pl, v4i e) {
 #pragma unroll
@@ -134,11 +166,12 @@ __device__ __forceinline__ v4i expand_plane(uint32_t w, int s, int pl, v4i e) {
 
 // One macro step of a wave's tile: load the pieces, count their ones (XNOR form only),
 // expand and multiply.  PL bit planes make up the A operand.
-template <int TM, int TN, int PL, bool XNOR, bool CONV, bool ALL>
+template <int TM, int TN, int PL, bool XNOR, bool CONV, bool F4, bool ALL>
 __device__ __forceinline__ void macro_step(const uint64_t* (&arow)[TM][PL], const uint64_t* (&brow)[TN],
                                            int w0, int Kw, bool whole, int qlo, int qhi, const MfmaParams& p,
                                            const int* tab,
-                                           v16i (&acc)[TM][TN], int (&pa)[TM], int (&pb)[TN]) {
+                                           typename AccOf<F4>::type (&acc)[TM][TN], int (&pa)[TM],
+                                           int (&pb)[TN]) {
   uint4 ra[TM][PL][4], rb[TN][4];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
@@ -159,7 +192,24 @@ __device__ __forceinline__ void macro_step(const uint64_t* (&arow)[TM][PL], cons
   for (int q = 0; q < 4; ++q) {
     if (!ALL && (q < qlo || q >= qhi)) continue;
 #pragma unroll
-    for (int d = 0; d < 4; ++d)
+    for (int d = 0; d < 4; ++d) {
+      if constexpr (F4) {
+        v8i ea[TM], eb[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          ea[i] = expand4(dword_of(ra[i][0][q], d));
+#pragma unroll
+          for (int pl = 1; pl < PL; ++pl) ea[i] = expand4_plane(dword_of(ra[i][pl][q], d), pl, ea[i]);
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) eb[j] = expand4(dword_of(rb[j][q], d));
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ea[i], eb[j], acc[i][j], 4, 4, 0, 128, 0,
+                                                                          128);
+      } else {
 #pragma unroll
       for (int s = 0; s < 2; ++s) {
         v4i ea[TM], eb[TN];
@@ -177,10 +227,12 @@ __device__ __forceinline__ void macro_step(const uint64_t* (&arow)[TM][PL], cons
           for (int j = 0; j < TN; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ea[i], eb[j], acc[i][j], 0, 0, 0);
       }
+      }
+    }
   }
 }
 
-template <int TM, int TN, int PL, bool XNOR, bool CONV>
+template <int TM, int TN, int PL, bool XNOR, bool CONV, bool F4>
 __global__ void __launch_bounds__(512)
 gemm_mfma_kernel(const MfmaParams p) {
   extern __shared__ int red[];  // [TM * TN * 16][64] partial results when K is split
@@ -227,13 +279,13 @@ gemm_mfma_kernel(const MfmaParams p) {
     }
   }
 
-  v16i acc[TM][TN];
+  typename AccOf<F4>::type sum[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
+      for (int e = 0; e < 16; ++e) sum[i][j][e] = 0;
   int pa[TM], pb[TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i) pa[i] = 0;
@@ -250,10 +302,19 @@ gemm_mfma_kernel(const MfmaParams p) {
     const int w0 = mac * 16 + h * half;
     // the common case (a whole macro step, all of it this wave's) without the piece tests
     if (whole && qlo == 0 && qhi == 4)
-      macro_step<TM, TN, PL, XNOR, CONV, true>(arow, brow, w0, p.Kw, true, 0, 4, p, tab, acc, pa, pb);
+      macro_step<TM, TN, PL, XNOR, CONV, F4, true>(arow, brow, w0, p.Kw, true, 0, 4, p, tab, sum, pa, pb);
     else
-      macro_step<TM, TN, PL, XNOR, CONV, false>(arow, brow, w0, p.Kw, whole, qlo, qhi, p, tab, acc, pa, pb);
+      macro_step<TM, TN, PL, XNOR, CONV, F4, false>(arow, brow, w0, p.Kw, whole, qlo, qhi, p, tab, sum, pa, pb);
   }
+
+  // the sums as integers (the fp32 sums of the FP4 form are exact integers)
+  v16i acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = (int)sum[i][j][e];
 
   // ---- this wave's share of C - K:  4 * and_count - 2 * pc(A row) - 2 * pc(B row), all over
   // the wave's K range.  A lane holds the counts of row / column r for its k-half; the other
@@ -348,11 +409,24 @@ gemm_mfma_kernel(const MfmaParams p) {
 
 }  // namespace
 
-int gemm_engine = 0;  // 0 = automatic, 1 = xor/popcount kernel, 2 = matrix-core kernel when eligible
+int gemm_engine = 0;  // 0 = automatic, 1 = xor/popcount kernel, 2 = int8 matrix cores, 3 = FP4 matrix cores
 int gemm_mfma_ksplit = 0;
 int gemm_mfma_tile = 0;  // 1 forces the 32 x 32 per wave variant
 
 namespace {
+
+template <int TM, int TN, int PL, bool XNOR, bool CONV>
+void launch_engine(const MfmaParams& p, bool f4, int64_t tiles, int S, size_t lds, hipStream_t s) {
+  if (f4)
+    hipLaunchKernelGGL((gemm_mfma_kernel<TM, TN, PL, XNOR, CONV, true>), dim3((unsigned)tiles), dim3(64 * S), lds,
+                       s, p);
+  else
+    hipLaunchKernelGGL((gemm_mfma_kernel<TM, TN, PL, XNOR, CONV, false>), dim3((unsigned)tiles), dim3(64 * S), lds,
+                       s, p);
+}
+
+// FP4 unless told otherwise or the sums could leave the exact range of fp32
+bool use_fp4(int64_t max_sum) { return gemm_engine != 2 && max_sum < ((int64_t)1 << 24); }
 
 void set_k_steps(MfmaParams& p, int K) {
   p.Kw = (int)words_for(K);
@@ -393,9 +467,9 @@ bool launch_xnor_gemm_mfma(const uint64_t* A, int64_t lda_w, const uint64_t* B, 
   p.C_f32 = C_f32;
   p.C_bits = (uint32_t*)C_bits;
   p.ldc = ldc;
-  // 64 x 64 per wave; 32 x 32 when that grid would leave most of the chip idle even with the
-  // deepest K split
-  const bool small = ceil_div(M, 64) * ceil_div(N, 64) * 8 < 1024 || gemm_mfma_tile == 1;
+  // 64 x 64 per wave; 32 x 32 when that grid has fewer than two tiles per CU (measured:
+  // 256 x 4096 x 4096 8.7 against 9.5 us, 1024^3 6.0 against 8.1 us)
+  const bool small = ceil_div(M, 64) * ceil_div(N, 64) < 512 || gemm_mfma_tile == 1;
   const int T = small ? 1 : 2;
   const int tiles_m = (int)ceil_div(M, 32 * T);
   // (packed output: both 32-bit halves of the last word of a row get a block that writes them)
@@ -403,10 +477,11 @@ bool launch_xnor_gemm_mfma(const uint64_t* A, int64_t lda_w, const uint64_t* B, 
   const int64_t tiles = (int64_t)tiles_m * p.tiles_n;
   const int S = choose_split(tiles, p.nsteps);
   const size_t lds = S > 1 ? (size_t)T * T * 16 * 64 * 4 : 0;
+  const bool f4 = use_fp4(K);
   if (small)
-    hipLaunchKernelGGL((gemm_mfma_kernel<1, 1, 1, true, false>), dim3((unsigned)tiles), dim3(64 * S), lds, s, p);
+    launch_engine<1, 1, 1, true, false>(p, f4, tiles, S, lds, s);
   else
-    hipLaunchKernelGGL((gemm_mfma_kernel<2, 2, 1, true, false>), dim3((unsigned)tiles), dim3(64 * S), lds, s, p);
+    launch_engine<2, 2, 1, true, false>(p, f4, tiles, S, lds, s);
   *err = hipGetLastError();
   return true;
 }
@@ -438,10 +513,11 @@ bool launch_plane_gemm_mfma(const uint64_t* planes_rows, int64_t lda_w, int bits
   const int64_t tiles = (int64_t)tiles_m * p.tiles_n;
   const int S = choose_split(tiles, p.nsteps);
   const size_t lds = S > 1 ? (size_t)2 * 16 * 64 * 4 : 0;
+  const bool f4 = use_fp4((int64_t)K * ((1 << bits) - 1));
   if (bits == 1)
-    hipLaunchKernelGGL((gemm_mfma_kernel<1, 2, 1, false, false>), dim3((unsigned)tiles), dim3(64 * S), lds, s, p);
+    launch_engine<1, 2, 1, false, false>(p, f4, tiles, S, lds, s);
   else
-    hipLaunchKernelGGL((gemm_mfma_kernel<1, 2, 2, false, false>), dim3((unsigned)tiles), dim3(64 * S), lds, s, p);
+    launch_engine<1, 2, 2, false, false>(p, f4, tiles, S, lds, s);
   *err = hipGetLastError();
   return true;
 }
@@ -488,8 +564,8 @@ bool launch_conv_mfma(const uint64_t* Xp, int Nimg, int C, int H, int W, const u
   p.div_wo = make_fast_div((uint32_t)Wo);
   p.div_cw = make_fast_div((uint32_t)Cw);
   p.div_kw = make_fast_div((uint32_t)KW);
-  // (32 x 32 tiles up to twice the grid size of the GEMM rule: measured on the 5 x 5 shapes)
-  const bool small = ceil_div(O, 64) * ceil_div(P, 64) * 8 < 2048 || gemm_mfma_tile == 1;
+  // (32 x 32 tiles further up than in the GEMM: 15.7 against 19.0 us at 784 tiles of 64 x 64)
+  const bool small = ceil_div(O, 64) * ceil_div(P, 64) < 2048 || gemm_mfma_tile == 1;
   const int T = small ? 1 : 2;
   const int tiles_m = (int)ceil_div(O, 32 * T);
   p.tiles_n = (int)ceil_div(P, 32 * T);
@@ -498,10 +574,11 @@ bool launch_conv_mfma(const uint64_t* Xp, int Nimg, int C, int H, int W, const u
   const int S = choose_split(tiles, p.nsteps);
   const size_t lds = (S > 1 ? (size_t)T * T * 16 * 64 * 4 : 0) + (size_t)kwords * 4;
   if (lds > 64 * 1024) return false;
+  const bool f4 = use_fp4(64 * (int64_t)kwords);
   if (small)
-    hipLaunchKernelGGL((gemm_mfma_kernel<1, 1, 1, true, true>), dim3((unsigned)tiles), dim3(64 * S), lds, s, p);
+    launch_engine<1, 1, 1, true, true>(p, f4, tiles, S, lds, s);
   else
-    hipLaunchKernelGGL((gemm_mfma_kernel<2, 2, 1, true, true>), dim3((unsigned)tiles), dim3(64 * S), lds, s, p);
+    launch_engine<2, 2, 1, true, true>(p, f4, tiles, S, lds, s);
   *err = hipGetLastError();
   return true;
 }

@@ -321,15 +321,16 @@ def test_gemm_every_kernel_shape(rows_per_wave, ksplit):
             L.bmx_tune_set(key, 0)
 
 
+@pytest.mark.parametrize("engine", [2, 3])
 @pytest.mark.parametrize("ksplit", [0, 1, 2, 3, 8])
-def test_gemm_matrix_core_engine(ksplit):
-    """The matrix-core kernel (bits expanded to int8 in registers), forced through the tuning
-    hook: ragged tiles in M and N, K tails inside and at the end of a 1024-bit step, every
-    K split, every output kind."""
+def test_gemm_matrix_core_engine(ksplit, engine):
+    """The matrix-core kernel (bits expanded in registers to int8, engine 2, or to FP4 nibbles,
+    engine 3), forced through the tuning hook: ragged tiles in M and N, K tails inside and at
+    the end of a 1024-bit step, every K split, every output kind."""
     L = B.lib()
     rng = np.random.default_rng(100 + ksplit)
     try:
-        assert L.bmx_tune_set(7, 2) == 0
+        assert L.bmx_tune_set(7, engine) == 0
         assert L.bmx_tune_set(8, ksplit) == 0
         for (M, N, K) in [(37, 70, 5000), (8, 64, 1024), (100, 129, 3072 + 64), (1, 1, 1), (64, 64, 63),
                           (65, 33, 1025), (130, 200, 2048 + 128),
@@ -402,6 +403,7 @@ def test_conv_every_path(path):
         for ksplit in ((0, 2, 3) if path in (2, 4) else (0,)):
             L.bmx_tune_set(3, ksplit)
             L.bmx_tune_set(8, ksplit)
+            L.bmx_tune_set(7, 2 if (path == 4 and ksplit == 2) else 0)  # int8 form once, FP4 otherwise
             for (N, C, H, W, O, k, s, p) in (CONV_CASES if path == 4 else CONV_CASES[:10]) + BIG_K_CONV_CASES[:2]:
                 rng = np.random.default_rng(N + 10 * C + 100 * H + 1000 * O + k + s + p + path)
                 x = rng.standard_normal((N, C, H, W)).astype(np.float32)
@@ -414,6 +416,7 @@ def test_conv_every_path(path):
         L.bmx_tune_set(5, 0)
         L.bmx_tune_set(3, 0)
         L.bmx_tune_set(8, 0)
+        L.bmx_tune_set(7, 0)
 
 
 def test_conv_weight_rows_are_zero_padded():
@@ -450,13 +453,13 @@ def test_fc_packed_chain(small):
     np.testing.assert_array_equal(B.binary_fc_packed(bits1, w1.shape[0], W2p, mode="i32").cpu().numpy(), r2i)
 
 
-@pytest.mark.parametrize("engine", [1, 2])
+@pytest.mark.parametrize("engine", [1, 2, 3])
 @pytest.mark.parametrize("batch,fin,fout", [(1, 1, 1), (5, 27, 3), (3, 180, 70), (66, 1000, 130), (9, 2100, 64),
                                             (300, 1100, 700)])
 def test_fc_packed_bits_ragged(batch, fin, fout, engine):
     """Ragged shapes, poisoned output, and scales of either sign and zero: the bit is the
     IEEE compare (alpha * dot >= 0) of the fp32 product, as bmx_binarize_pack would see it.
-    Both GEMM engines (xor/popcount and matrix cores), forced through the tuning hook; rows
+    Every GEMM engine (xor/popcount, int8 and FP4 matrix cores), forced through the tuning hook; rows
     are padded to an even word count, which the matrix-core kernel needs to take the problem."""
     rng = np.random.default_rng(batch + fin + fout)
     x = rng.standard_normal((batch, fin)).astype(np.float32)
