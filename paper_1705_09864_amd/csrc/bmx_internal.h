@@ -90,7 +90,7 @@ bool launch_plane_gemm_mfma(const uint64_t* planes_rows, int64_t lda_w, int bits
 bool launch_conv_mfma(const uint64_t* Xp, int Nimg, int C, int H, int W, const uint64_t* Wp, int O, int KH,
                       int KW, int stride, int pad, const float* alpha, int32_t* out_i32, float* out_f32,
                       hipStream_t s, hipError_t* err);
-extern int gemm_engine, gemm_mfma_ksplit, gemm_mfma_tile;
+extern int gemm_engine, gemm_mfma_ksplit, gemm_mfma_tile, conv_filters_per_wave, conv_path;
 // S = 2*sum_p 2^p pc(plane_p & wb) - rowsum; out_f32 = float(S) / float(2^bits - 1).
 // planes_rows as written by launch_quant_pack (lda_dw dwords per row, chunk padded).
 hipError_t launch_plane_gemm(const uint32_t* planes_rows, int64_t lda_dw, int bits,

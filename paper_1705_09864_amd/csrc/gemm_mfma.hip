@@ -69,20 +69,47 @@ struct MfmaParams {
 // words h * half .. h * half + half - 1 of it (half = 8 except in a shorter last step), in
 // pieces of two words; piece step q is words h * half + 2q, + 1.  One piece step of all rows
 // feeds eight MFMA steps, and piece steps are the unit in which K is split over waves.
-__device__ __forceinline__ void load_row(const uint64_t* row, int w0, int Kw, bool whole, int qlo,
-                                         int qhi, uint4 (&r)[4]) {
-  const uint64_t* src = row + w0;
+//
+// Loading.  The layout the MFMA wants (lane = row) makes every lane of a load touch a
+// different cache line, and the vector memory pipeline then spends one access per lane: it,
+// not the matrix cores, set the pace (11 M cache accesses for 0.2 M load instructions on a
+// convolution).  So the 32 rows x 128 bytes of a block are loaded the coalesced way (eight
+// consecutive lanes read the eight 16-byte pieces of one row) and turned into the MFMA layout
+// through a 4 KiB LDS tile private to the wave.  Piece p of row w lives in slot p ^ (w & 7),
+// which makes both the row-wise writes and the column-wise reads conflict free.
+__device__ __forceinline__ void load_rows_coalesced(const uint64_t* mat, int64_t ld, int row0, int nrows, int planes,
+                                                    int pl, int mac, int Kw, bool whole, int lane,
+                                                    uint4 (&r)[4]) {
+  const int pp = lane & 7;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int row = min(row0 + 8 * t + (lane >> 3), nrows - 1);  // rows past the matrix repeat its last
+    const uint64_t* src = mat + ((int64_t)row * planes + pl) * ld + mac * 16 + 2 * pp;
+    if (whole) {
+      r[t] = *(const uint4*)src;
+    } else {
+      const int w = mac * 16 + 2 * pp;
+      const uint64_t lo = w < Kw ? src[0] : 0;
+      const uint64_t hi = w + 1 < Kw ? src[1] : 0;
+      r[t] = make_uint4((uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32));
+    }
+  }
+}
+
+// Coalesced layout (r[t] = piece lane % 8 of row 8t + lane / 8) -> MFMA layout (r[q] = piece
+// h * half / 2 + q of row lane % 32), pieces outside [qlo, qhi) zero.
+__device__ __forceinline__ void to_mfma_layout(uint4* tile, int lane, int half, int qlo, int qhi, uint4 (&r)[4]) {
+  const int pp = lane & 7;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int row = 8 * t + (lane >> 3);
+    tile[row * 8 + (pp ^ (row & 7))] = r[t];
+  }
+  const int row = lane & 31, c0 = (lane >> 5) * (half >> 1);
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
-    if (q < qlo || q >= qhi) {  // wave-uniform: not this wave's piece
-      r[q] = make_uint4(0, 0, 0, 0);
-    } else if (whole) {
-      r[q] = *(const uint4*)(src + 2 * q);
-    } else {
-      const uint64_t lo = (w0 + 2 * q < Kw) ? src[2 * q] : 0;
-      const uint64_t hi = (w0 + 2 * q + 1 < Kw) ? src[2 * q + 1] : 0;
-      r[q] = make_uint4((uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32));
-    }
+    if (q >= qlo && q < qhi) r[q] = tile[row * 8 + (((c0 + q) & 7) ^ (row & 7))];
+    else r[q] = make_uint4(0, 0, 0, 0);
   }
 }
 
@@ -167,20 +194,30 @@ __device__ __forceinline__ v4i expand_plane(uint32_t w, int s, int pl, v4i e) {
 // One macro step of a wave's tile: load the pieces, count their ones (XNOR form only),
 // expand and multiply.  PL bit planes make up the A operand.
 template <int TM, int TN, int PL, bool XNOR, bool CONV, bool F4, bool ALL>
-__device__ __forceinline__ void macro_step(const uint64_t* (&arow)[TM][PL], const uint64_t* (&brow)[TN],
-                                           int w0, int Kw, bool whole, int qlo, int qhi, const MfmaParams& p,
-                                           const int* tab,
+__device__ __forceinline__ void macro_step(int m0, int n0, const uint64_t* (&brow)[TN], int mac, int half,
+                                           bool whole, int qlo, int qhi, const MfmaParams& p,
+                                           const int* tab, uint4* tile, int lane,
                                            typename AccOf<F4>::type (&acc)[TM][TN], int (&pa)[TM],
                                            int (&pb)[TN]) {
   uint4 ra[TM][PL][4], rb[TN][4];
+  // every block's loads first, then the blocks through the tile one after the other
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int pl = 0; pl < PL; ++pl) load_row(arow[i][pl], w0, Kw, whole, qlo, qhi, ra[i][pl]);
+    for (int pl = 0; pl < PL; ++pl)
+      load_rows_coalesced(p.A, p.lda, m0 + 32 * i, p.M, PL, pl, mac, p.Kw, whole, lane, ra[i][pl]);
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
-    if (CONV) load_im2col(brow[j], w0, p, tab, qlo, qhi, rb[j]);
-    else load_row(brow[j], w0, Kw, whole, qlo, qhi, rb[j]);
+    if (CONV) load_im2col(brow[j], mac * 16 + (lane >> 5) * half, p, tab, qlo, qhi, rb[j]);
+    else load_rows_coalesced(p.B, p.ldb, n0 + 32 * j, p.N, 1, 0, mac, p.Kw, whole, lane, rb[j]);
+  }
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int pl = 0; pl < PL; ++pl) to_mfma_layout(tile, lane, half, qlo, qhi, ra[i][pl]);
+  if (!CONV) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j) to_mfma_layout(tile, lane, half, qlo, qhi, rb[j]);
   }
   if (XNOR) {
 #pragma unroll
@@ -242,8 +279,25 @@ gemm_mfma_kernel(const MfmaParams p) {
   const int r = lane & 31, h = lane >> 5;
   const int tile_n = blockIdx.x % p.tiles_n, tile_m = blockIdx.x / p.tiles_n;
   const int m0 = tile_m * (32 * TM), n0 = tile_n * (32 * TN);
-  // convolution: word offset of im2col word w from a pixel's base, behind the reduction buffer
-  int* tab = red + (S > 1 ? TM * TN * 16 * 64 : 0);
+  // LDS: a 4 KiB transposition tile per wave; once the main loop is over the same memory holds
+  // the partial results of a K split; behind both, the convolution's table of im2col offsets
+  uint4* tile = (uint4*)red + wave * 256;
+  const int red_ints = S > 1 ? TM * TN * 16 * 64 : 0;
+  int* tab = red + (S * 1024 > red_ints ? S * 1024 : red_ints);
+  // ... and the per-row constants of the epilogue (a convolution's alpha, the plane form's row
+  // sums), fetched once here instead of once per stored value; the per-column alpha of the
+  // GEMM sits in a register per column block
+  int* rowk = tab + (CONV ? p.Kw : 0);
+  float aln[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+    aln[j] = (XNOR && !CONV && p.alpha) ? p.alpha[min(n0 + 32 * j + (lane & 31), p.N - 1)] : 1.0f;
+  if (wave == 0 && (CONV || !XNOR)) {
+    for (int i = lane; i < 32 * TM; i += 64) {
+      const int m = min(m0 + i, p.M - 1);
+      rowk[i] = !XNOR ? p.rowsum[m] : (p.alpha ? __float_as_int(p.alpha[m]) : __float_as_int(1.0f));
+    }
+  }
   if (CONV) {
     for (int w = threadIdx.x; w < p.Kw; w += blockDim.x) {
       const uint32_t tap = fast_div((uint32_t)w, p.div_cw);
@@ -255,14 +309,8 @@ gemm_mfma_kernel(const MfmaParams p) {
   }
 
   // rows past the matrix repeat its last row; their results are never stored
-  // (plane pl of row m is row m * PL + pl of A)
-  const uint64_t* arow[TM][PL];
+  // (plane pl of row m is row m * PL + pl of A; the row addresses are formed per load)
   const uint64_t* brow[TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int pl = 0; pl < PL; ++pl)
-      arow[i][pl] = p.A + ((int64_t)min(m0 + 32 * i + r, p.M - 1) * PL + pl) * p.lda;
   uint32_t pix_img[TN], pix_rem[TN];  // convolution: image and pixel within it of column n
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
@@ -299,12 +347,13 @@ gemm_mfma_kernel(const MfmaParams p) {
     const int qlo = max(ps0 - 4 * mac, 0), qhi = min(ps1 - 4 * mac, 4);
     const bool whole = mac < last_mac || (p.tail_half == 8 && (p.Kw & 15) == 0);  // wave-uniform
     const int half = mac < last_mac ? 8 : p.tail_half;
-    const int w0 = mac * 16 + h * half;
     // the common case (a whole macro step, all of it this wave's) without the piece tests
     if (whole && qlo == 0 && qhi == 4)
-      macro_step<TM, TN, PL, XNOR, CONV, F4, true>(arow, brow, w0, p.Kw, true, 0, 4, p, tab, sum, pa, pb);
+      macro_step<TM, TN, PL, XNOR, CONV, F4, true>(m0, n0, brow, mac, 8, true, 0, 4, p, tab, tile, lane, sum, pa,
+                                                   pb);
     else
-      macro_step<TM, TN, PL, XNOR, CONV, F4, false>(arow, brow, w0, p.Kw, whole, qlo, qhi, p, tab, sum, pa, pb);
+      macro_step<TM, TN, PL, XNOR, CONV, F4, false>(m0, n0, brow, mac, half, whole, qlo, qhi, p, tab, tile, lane,
+                                                    sum, pa, pb);
   }
 
   // the sums as integers (the fp32 sums of the FP4 form are exact integers)
@@ -337,11 +386,12 @@ gemm_mfma_kernel(const MfmaParams p) {
   }
 
   auto store = [&](int i, int j, int v, int t) {  // called by whole waves only
-    const int m = m0 + 32 * i + 8 * (v / 4) + 4 * h + (v % 4);
+    const int mi = 32 * i + 8 * (v / 4) + 4 * h + (v % 4);
+    const int m = m0 + mi;
     const int n = n0 + 32 * j + r;
     if (!XNOR) {
+      const int sv = 2 * t - rowk[mi];
       if (m < p.M && n < p.N) {
-        const int sv = 2 * t - p.rowsum[m];
         const int64_t idx = (int64_t)m * p.ldc + n;
         if (p.C_i32) p.C_i32[idx] = sv;
         if (p.C_f32) p.C_f32[idx] = (float)sv / p.levels;
@@ -350,24 +400,25 @@ gemm_mfma_kernel(const MfmaParams p) {
     }
     const int dot = p.Kreal + t;
     if (CONV) {
+      const float al = __int_as_float(rowk[mi]);
       if (m < p.M && n < p.N) {  // NCHW: plane m of the pixel's image
         const int64_t idx = ((int64_t)pix_img[j] * p.M + m) * p.HoWo + pix_rem[j];
         if (p.C_i32) p.C_i32[idx] = dot;
-        else p.C_f32[idx] = p.alpha ? p.alpha[m] * (float)dot : (float)dot;
+        else p.C_f32[idx] = al * (float)dot;
       }
       return;
     }
+    const float al = (TN > 1 && j == 1) ? aln[TN - 1] : aln[0];
     if (p.C_bits) {
       // the 64-lane mask of (scaled result >= 0): its low half is 32 columns of row m as seen
       // by lanes 0..31, its high half the same columns of the row four below
-      const float al = (p.alpha && n < p.N) ? p.alpha[n] : 1.0f;
       const uint64_t mask = __ballot(n < p.N && al * (float)dot >= 0.0f);
       if (r == 0 && m < p.M)
         p.C_bits[(int64_t)m * (2 * p.ldc) + (n >> 5)] = h ? (uint32_t)(mask >> 32) : (uint32_t)mask;
     } else if (m < p.M && n < p.N) {
       const int64_t idx = (int64_t)m * p.ldc + n;
       if (p.C_i32) p.C_i32[idx] = dot;
-      else p.C_f32[idx] = p.alpha ? p.alpha[n] * (float)dot : (float)dot;
+      else p.C_f32[idx] = al * (float)dot;
     }
   };
 
@@ -383,6 +434,7 @@ gemm_mfma_kernel(const MfmaParams p) {
 
   // ---- K split: wave 0 writes its share, the others add theirs, then the entries are
   // finished and stored by the waves in turn
+  __syncthreads();  // every wave is done with its transposition tile (same memory)
   if (wave == 0) {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -401,9 +453,16 @@ gemm_mfma_kernel(const MfmaParams p) {
         for (int v = 0; v < 16; ++v) atomicAdd(&red[((i * TN + j) * 16 + v) * 64 + lane], acc[i][j][v]);
   }
   __syncthreads();
-  for (int e = wave; e < TM * TN * 16; e += S) {
-    const int v = e & 15, blk = e >> 4;
-    store(blk / TN, blk % TN, v, red[e * 64 + lane]);
+  // (four entries per trip: their LDS reads go out together)
+  for (int e0 = wave; e0 < TM * TN * 16; e0 += 4 * S) {
+    int t[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) t[k] = red[min(e0 + k * S, TM * TN * 16 - 1) * 64 + lane];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int e = e0 + k * S;
+      if (e < TM * TN * 16) store((e >> 4) / TN, (e >> 4) % TN, e & 15, t[k]);
+    }
   }
 }
 
@@ -434,6 +493,13 @@ void set_k_steps(MfmaParams& p, int K) {
   const int span = p.Kw - (int)((p.Kw - 1) / 16) * 16;    // words of the last macro step, 1..16
   p.tail_half = (int)ceil_div(ceil_div(span, 2), 2) * 2;  // per half-wave, whole pieces
   p.nsteps = (int)((p.Kw - 1) / 16) * 4 + p.tail_half / 2;
+}
+
+// transposition tiles (4 KiB per wave) and, in the same memory, the partial results of a K
+// split (16 x 64 ints per 32 x 32 block of the wave tile)
+size_t lds_bytes(int S, int blocks) {
+  const size_t tiles = (size_t)S * 4096, red = S > 1 ? (size_t)blocks * 16 * 64 * 4 : 0;
+  return (tiles > red ? tiles : red) + 64 * 4;  // + the table of row constants (up to 64 rows)
 }
 
 int choose_split(int64_t tiles, int nsteps) {
@@ -476,7 +542,7 @@ bool launch_xnor_gemm_mfma(const uint64_t* A, int64_t lda_w, const uint64_t* B, 
   p.tiles_n = C_bits ? (int)(ceil_div(N, 64) * (2 / T)) : (int)ceil_div(N, 32 * T);
   const int64_t tiles = (int64_t)tiles_m * p.tiles_n;
   const int S = choose_split(tiles, p.nsteps);
-  const size_t lds = S > 1 ? (size_t)T * T * 16 * 64 * 4 : 0;
+  const size_t lds = lds_bytes(S, T * T);
   const bool f4 = use_fp4(K);
   if (small)
     launch_engine<1, 1, 1, true, false>(p, f4, tiles, S, lds, s);
@@ -512,7 +578,7 @@ bool launch_plane_gemm_mfma(const uint64_t* planes_rows, int64_t lda_w, int bits
   p.tiles_n = (int)ceil_div(N, 64);
   const int64_t tiles = (int64_t)tiles_m * p.tiles_n;
   const int S = choose_split(tiles, p.nsteps);
-  const size_t lds = S > 1 ? (size_t)2 * 16 * 64 * 4 : 0;
+  const size_t lds = lds_bytes(S, 2);
   const bool f4 = use_fp4((int64_t)K * ((1 << bits) - 1));
   if (bits == 1)
     launch_engine<1, 2, 1, false, false>(p, f4, tiles, S, lds, s);
@@ -572,7 +638,7 @@ bool launch_conv_mfma(const uint64_t* Xp, int Nimg, int C, int H, int W, const u
   const int64_t tiles = (int64_t)tiles_m * p.tiles_n;
   if (tiles >= ((int64_t)1 << 31)) return false;
   const int S = choose_split(tiles, p.nsteps);
-  const size_t lds = (S > 1 ? (size_t)T * T * 16 * 64 * 4 : 0) + (size_t)kwords * 4;
+  const size_t lds = lds_bytes(S, T * T) + (size_t)kwords * 4;
   if (lds > 64 * 1024) return false;
   const bool f4 = use_fp4(64 * (int64_t)kwords);
   if (small)
