@@ -171,6 +171,19 @@ int bmx_alpha_mean_abs(const float* w, int64_t rows, int64_t cols, int64_t ldw, 
 /* Scratch bytes an operation needs (multiple of 256), or 0 if op/dims are invalid. */
 size_t bmx_workspace_bytes(int op, const int64_t* dims, int ndims);
 
+/* Kernel-selection hook for measurements and for tests that must reach every kernel
+ * variant; not part of the layers the paper defines.  Results never depend on it: every
+ * engine and shape computes the same integers (Sec. 2.2.2).  Process-wide, not thread safe;
+ * value 0 restores the automatic choice.  Returns BMX_ERR_UNSUPPORTED for an unknown key.
+ *   key 1  filters per wave of the register-stationary convolution kernel
+ *   key 2  rows per wave (8, 16, 32), key 3  K-split waves, key 4  workgroup order of the
+ *          xor/popcount GEMM kernel
+ *   key 5  convolution kernel: 1 register-stationary, 2 xor/popcount GEMM kernel,
+ *          3 one thread per output, 4 matrix cores
+ *   key 7  GEMM engine: 1 xor/popcount, 2 int8 matrix cores, 3 FP4 matrix cores
+ *   key 8  K-split waves, key 9  (value 1) 32 x 32 tiles per wave of the matrix-core kernel */
+int bmx_tune_set(int key, int value);
+
 /* Static, human-readable name of a status code. */
 const char* bmx_status_string(int status);
 

@@ -19,7 +19,7 @@ OP_BINARY_FC, OP_BINARY_CONV2D, OP_QUANT_GEMM = 1, 2, 3
 EXPORTS = ["bmx_binarize_pack", "bmx_xnor_gemm", "bmx_binary_fc", "bmx_pack_conv_weights",
            "bmx_binary_conv2d", "bmx_quant_gemm", "bmx_alpha_mean_abs", "bmx_pack_nchw",
            "bmx_binary_conv2d_packed", "bmx_workspace_bytes", "bmx_status_string", "bmx_version",
-           "bmx_conv_weight_row_words", "bmx_binary_fc_packed"]
+           "bmx_conv_weight_row_words", "bmx_binary_fc_packed", "bmx_tune_set"]
 
 _i64, _int, _p, _sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
 
@@ -59,6 +59,8 @@ def lib():
         L.bmx_pack_nchw.argtypes = [_p, _int, _int, _int, _int, _int, _p, _p]
         L.bmx_binary_conv2d_packed.argtypes = [_p, _int, _int, _int, _int, _p, _int, _int, _int, _int,
                                                _int, _p, _p, _p, _p]
+        L.bmx_tune_set.argtypes = [_int, _int]
+        L.bmx_tune_set.restype = _int
         for name in EXPORTS[:9]:
             getattr(L, name).restype = _int
         _lib = L

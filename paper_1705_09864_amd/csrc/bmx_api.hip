@@ -56,10 +56,7 @@ extern int gemm_tune_rows, gemm_tune_ksplit, gemm_tune_order;
 
 extern "C" {
 
-// Undeclared tuning hook used by kernel sweeps (0 restores the automatic choice):
-// key 1 = filters per wave of the stationary convolution kernel, key 2 = rows per wave,
-// key 3 = K-split waves and key 4 = workgroup order of the GEMM kernel, key 5 = convolution
-// path (1 stationary, 2 GEMM kernel, 3 general).
+// Kernel-selection hook (keys documented at its declaration).
 int bmx_tune_set(int key, int value) {
   if (key == 1) bmx::conv_filters_per_wave = value;
   else if (key == 2) bmx::gemm_tune_rows = value;
