@@ -102,6 +102,26 @@ def test_xnor_gemm_wide_rows_and_invariants():
     assert (np.diag(same) == K).all()
 
 
+class tuned:
+    """Pin kernel choices through bmx_tune_set for a block of code (results must not depend on them)."""
+
+    def __init__(self, **kv):
+        self.kv = kv
+
+    def __enter__(self):
+        for k, v in self.kv.items():
+            assert B.lib().bmx_tune_set(int(k[1:]), v) == 0
+        return self
+
+    def __exit__(self, *exc):
+        for k in self.kv:
+            B.lib().bmx_tune_set(int(k[1:]), 0)
+
+
+# every GEMM engine: automatic (FP4 matrix cores), xor/popcount, int8 matrix cores
+GEMM_ENGINES = [dict(), dict(k7=1), dict(k7=2)]
+
+
 # ------------------------------------------------------------------ binary FC
 def test_config1_fc_gemm_exact():
     c = synth.config1()
@@ -123,17 +143,19 @@ def test_config3_fc_chain(small):
     x, w1, w2 = c["x"], c["w1"], c["w2"]
     a1, a2 = oracle.alpha_mean_abs(w1), oracle.alpha_mean_abs(w2)
     W1p, W2p = B.binarize_pack(dev(w1), 1), B.binarize_pack(dev(w2), 1)
-    h1 = B.binary_fc(dev(x), W1p, alpha=dev(a1))
-    h2 = B.binary_fc(h1, W2p, alpha=dev(a2))
-    i1 = B.binary_fc(dev(x), W1p, integer_out=True)
     r1i, r1f = oracle.binary_fc(x, w1, a1)
     r2i, r2f = oracle.binary_fc(r1f, w2, a2)
-    np.testing.assert_array_equal(i1.cpu().numpy(), r1i)
-    assert_f32_close(h1.cpu().numpy(), r1f)
-    np.testing.assert_array_equal(h1.cpu().numpy(), r1f)   # one fp32 multiply: bit-identical
-    assert_f32_close(h2.cpu().numpy(), r2f)
-    i2 = B.binary_fc(h1, W2p, integer_out=True)
-    np.testing.assert_array_equal(i2.cpu().numpy(), r2i)
+    for engine in GEMM_ENGINES:
+        with tuned(**engine):
+            h1 = B.binary_fc(dev(x), W1p, alpha=dev(a1))
+            h2 = B.binary_fc(h1, W2p, alpha=dev(a2))
+            i1 = B.binary_fc(dev(x), W1p, integer_out=True)
+            np.testing.assert_array_equal(i1.cpu().numpy(), r1i)
+            assert_f32_close(h1.cpu().numpy(), r1f)
+            np.testing.assert_array_equal(h1.cpu().numpy(), r1f)   # one fp32 multiply: bit-identical
+            assert_f32_close(h2.cpu().numpy(), r2f)
+            i2 = B.binary_fc(h1, W2p, integer_out=True)
+            np.testing.assert_array_equal(i2.cpu().numpy(), r2i)
 
 
 @pytest.mark.parametrize("batch,fin,fout", [(1, 1, 1), (5, 27, 3), (3, 180, 70), (66, 1000, 130)])
@@ -202,10 +224,14 @@ def test_config2_conv_full():
     alpha = oracle.alpha_mean_abs(c["w"])
     assert_f32_close(B.alpha_mean_abs(dev(c["w"])).cpu().numpy(), alpha)
     ri, rf = oracle.binary_conv2d(c["x"], c["w"], 1, 1, alpha)
-    got = run_conv(c["x"], c["w"], 1, 1, alpha=alpha)
-    assert got.shape == (16, 64, 56, 56)
-    assert_f32_close(got, rf)
-    np.testing.assert_array_equal(run_conv(c["x"], c["w"], 1, 1, integer_out=True), ri)
+    # automatic (register-stationary popcount kernel at this K), popcount GEMM kernel, FP4 and
+    # int8 matrix cores
+    for choice in (dict(), dict(k5=2), dict(k5=4), dict(k5=4, k7=2)):
+        with tuned(**choice):
+            got = run_conv(c["x"], c["w"], 1, 1, alpha=alpha)
+            assert got.shape == (16, 64, 56, 56)
+            assert_f32_close(got, rf)
+            np.testing.assert_array_equal(run_conv(c["x"], c["w"], 1, 1, integer_out=True), ri)
 
 
 @pytest.mark.parametrize("stride", [1, 2])
@@ -215,10 +241,14 @@ def test_config4_conv_full(stride):
     assert 0.60 < frac_pos < 0.635                     # skewed sign balance, P(|z| >= 0.5) = 0.617
     alpha = oracle.alpha_mean_abs(c["w"])
     ri, rf = oracle.binary_conv2d(c["x"], c["w"], stride, 1, alpha)
-    got = run_conv(c["x"], c["w"], stride, 1, alpha=alpha)
-    assert got.shape == (64, 256, 14 // stride, 14 // stride)
-    assert_f32_close(got, rf)
-    np.testing.assert_array_equal(run_conv(c["x"], c["w"], stride, 1, integer_out=True), ri)
+    # automatic (FP4 matrix cores at this K), register-stationary popcount kernel, popcount GEMM
+    # kernel, int8 matrix cores
+    for choice in (dict(), dict(k5=1), dict(k5=2), dict(k5=4, k7=2)):
+        with tuned(**choice):
+            got = run_conv(c["x"], c["w"], stride, 1, alpha=alpha)
+            assert got.shape == (64, 256, 14 // stride, 14 // stride)
+            assert_f32_close(got, rf)
+            np.testing.assert_array_equal(run_conv(c["x"], c["w"], stride, 1, integer_out=True), ri)
 
 
 # ------------------------------------------------------------------ alpha helper
@@ -257,14 +287,20 @@ def test_config5_quant_gemm():
 def test_config5_quant_gemm_full_size_sampled_rows():
     """Full 1024 x 1024 x 4096 on the GPU; the oracle recomputes 96 sampled rows of a."""
     c = synth.config5()
-    S, of = B.quant_gemm(dev(c["a"]), dev(c["w"]), 2)
     rows = np.random.default_rng(9).choice(1024, 96, replace=False)
     rS, r64, r32 = oracle.quant_gemm(c["a"][rows], c["w"], 2)
-    np.testing.assert_array_equal(S.cpu().numpy()[rows], rS)
-    assert_f32_close(of.cpu().numpy()[rows], r64, atol=1e-9)
-    assert_f32_close(of.cpu().numpy()[rows], r32)
-    Sall = S.cpu().numpy()
-    assert (np.abs(Sall) <= 3 * 4096).all()
+    first = None
+    for engine in GEMM_ENGINES:
+        with tuned(**engine):
+            S, of = B.quant_gemm(dev(c["a"]), dev(c["w"]), 2)
+        np.testing.assert_array_equal(S.cpu().numpy()[rows], rS)
+        assert_f32_close(of.cpu().numpy()[rows], r64, atol=1e-9)
+        assert_f32_close(of.cpu().numpy()[rows], r32)
+        Sall = S.cpu().numpy()
+        assert (np.abs(Sall) <= 3 * 4096).all()
+        # the rows the oracle did not recompute: every engine gives the same integers
+        first = Sall if first is None else first
+        np.testing.assert_array_equal(Sall, first)
 
 
 # ------------------------------------------------------------------ determinism, empties
