@@ -303,6 +303,22 @@ def test_config5_quant_gemm_full_size_sampled_rows():
         np.testing.assert_array_equal(Sall, first)
 
 
+def test_quant_gemm_long_k_leaves_fp4_range():
+    """K * (2^bits - 1) >= 2^24: fp32 sums could round, so the launcher must take the int8 form
+    (int32 accumulation); the result stays exact."""
+    M, N, K = 2, 3, 5_700_000
+    rng = np.random.default_rng(77)
+    a = rng.uniform(0, 1, (M, K)).astype(np.float32)
+    a[0] = 1.0                                  # q = 3 everywhere: the largest possible sums
+    w = rng.standard_normal((N, K)).astype(np.float32)
+    w[0] = 1.0
+    S, of = B.quant_gemm(dev(a), dev(w), 2)
+    rS, r64, r32 = oracle.quant_gemm(a, w, 2)
+    assert rS[0, 0] == 3 * K and 3 * K > (1 << 24)
+    np.testing.assert_array_equal(S.cpu().numpy(), rS)
+    assert_f32_close(of.cpu().numpy(), r32)
+
+
 # ------------------------------------------------------------------ determinism, empties
 def test_repeatable_and_empty():
     c = synth.config2(small=True)
