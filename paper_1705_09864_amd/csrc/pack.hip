@@ -157,7 +157,9 @@ hipError_t launch_pack_strided(const float* x, int64_t batch, int64_t K, int64_t
 // word: lanes span pixels, so every load instruction is a coalesced 256-byte read of one
 // channel plane, and all 64 channel loads of a lane are issued before the first compare
 // (16 KiB in flight per wave).  The word is assembled in two 32-bit halves.  Workgroup 0 of
-// every (image, word) also writes the constant halo words.
+// every (image, word) also writes the constant halo words.  The image is read exactly once, so
+// the loads are non-temporal (they do not displace what the convolution that follows needs:
+// 12.8 us against 13.4 us per configuration-2 layer with the input coming from HBM).
 __global__ void __launch_bounds__(256)
 pack_nchw_kernel(const float* __restrict__ x, int C, int HW, int W, int pad, int Hp, int Wp, int Cw,
                  uint64_t* __restrict__ xp) {
@@ -174,7 +176,7 @@ pack_nchw_kernel(const float* __restrict__ x, int C, int HW, int W, int pad, int
     float v[64];
     if (c0 + 64 <= C) {
 #pragma unroll
-      for (int j = 0; j < 64; ++j) v[j] = xb[(int64_t)j * HW];
+      for (int j = 0; j < 64; ++j) v[j] = __builtin_nontemporal_load(xb + (int64_t)j * HW);
     } else {
 #pragma unroll
       for (int j = 0; j < 64; ++j) v[j] = (c0 + j < C) ? xb[(int64_t)j * HW] : -1.0f;
