@@ -393,8 +393,8 @@ gemm_mfma_kernel(const MfmaParams p) {
       const int sv = 2 * t - rowk[mi];
       if (m < p.M && n < p.N) {
         const int64_t idx = (int64_t)m * p.ldc + n;
-        if (p.C_i32) p.C_i32[idx] = sv;
-        if (p.C_f32) p.C_f32[idx] = (float)sv / p.levels;
+        if (p.C_i32) __builtin_nontemporal_store(sv, p.C_i32 + idx);
+        if (p.C_f32) __builtin_nontemporal_store((float)sv / p.levels, p.C_f32 + idx);
       }
       return;
     }
@@ -417,8 +417,8 @@ gemm_mfma_kernel(const MfmaParams p) {
         p.C_bits[(int64_t)m * (2 * p.ldc) + (n >> 5)] = h ? (uint32_t)(mask >> 32) : (uint32_t)mask;
     } else if (m < p.M && n < p.N) {
       const int64_t idx = (int64_t)m * p.ldc + n;
-      if (p.C_i32) p.C_i32[idx] = dot;
-      else p.C_f32[idx] = al * (float)dot;
+      if (p.C_i32) __builtin_nontemporal_store(dot, p.C_i32 + idx);
+      else __builtin_nontemporal_store(al * (float)dot, p.C_f32 + idx);
     }
   };
 
