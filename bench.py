@@ -50,6 +50,8 @@ def main():
     ap.add_argument("--traffic-probe", action="store_true",
                     help="run the steps eagerly next to a plain 256 MiB device copy and exit: the "
                          "workload for the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes")
+    ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
+                    help="pin a kernel choice through bmx_tune_set for the whole run (A/B measurements)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
@@ -63,6 +65,9 @@ def main():
 
     torch.cuda.set_device(0)
     K_STEPS = args.steps
+    for kv in args.tune:
+        k, v = kv.split("=")
+        assert B.lib().bmx_tune_set(int(k), int(v)) == 0
 
     def graph_of(fns):
         """Capture the calls in `fns`, in order (library launches on the capturing stream)."""

@@ -1,0 +1,277 @@
+// Binary convolution on the FP4 matrix cores for short K (9, 18 or 36 words).
+// Paper: Sec. 3.1 (M = filters, N = batch * output pixels, K = kh * kw * C), result
+// out = alpha[o] * (K - 2 * popcount(filter xor patch)) (Sec. 2.2.2, Eq. 2).
+//
+// Same arithmetic as the matrix-core GEMM: with bits a, b in {0, 1},
+// K - 2 * pc(a xor b) = K - 2 * pc(a) - 2 * pc(b) + 4 * sum a * b, the sum on
+// v_mfma_scale_f32_32x32x64_f8f6f4 with both operands FP4: a bit becomes a nibble of code 1
+// (0.5), the block scales of 2 make it 1.0, products and fp32 sums are exact integers.
+//
+// Shape.  The filters arrive already expanded (the weight pack does it offline, Sec. 2.2.3):
+// a workgroup copies the FP4 operands of its 32 * TM filters into LDS once, and every MFMA
+// step reads its A operand from there (16 bytes per lane), so filters cost no registers and
+// no VALU work.  A wave walks over blocks of 32 output pixels: it fetches the pixels' KW
+// words (one MFMA step of K = 64 consumes exactly one 64-bit word: lane (r, h) supplies half
+// h of the word of pixel r), expands them (8 VALU instructions per word) and issues KW * TM
+// MFMAs.  Lanes run along pixels (operand B), so the NCHW stores are two 128-byte runs per
+// instruction.
+#include "bmx_internal.h"
+
+namespace bmx {
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+// 64-bit stores into the dword-typed LDS tiles: without may_alias the compiler is entitled to
+// move the 32-bit reads of the same memory across them (type-based alias analysis)
+typedef uint64_t __attribute__((may_alias)) u64_alias;
+typedef v4i __attribute__((may_alias)) v4i_alias;
+
+constexpr int kMaxWsWords = 36;
+
+struct WsParams {
+  const uint64_t* Xp;  // halo-padded packed image
+  const uint32_t* Wp;  // [O][ld_dw] dwords: bits, then the FP4 section at dword fp4_dw
+  int ld_dw, fp4_dw;
+  const float* alpha;  // [O] or null
+  int32_t* out_i32;
+  float* out_f32;
+  int P;  // N * Ho * Wo
+  int O, HoWo, Wo, Hp, Wpp, Cw, stride;
+  int nblocks, nb;  // blocks of 32 pixels in all; blocks per wave
+  FastDiv div_howo, div_wo;
+  int off[kMaxWsWords];  // word offset of K-word j relative to the pixel base
+};
+
+__device__ __forceinline__ v8i widen(v4i e) {
+  v8i x;
+#pragma unroll
+  for (int d = 0; d < 4; ++d) x[d] = e[d];
+#pragma unroll
+  for (int d = 4; d < 8; ++d) x[d] = 0;
+  return x;
+}
+
+__device__ __forceinline__ v4i expand4(uint32_t w) {
+  v4i e;
+#pragma unroll
+  for (int d = 0; d < 4; ++d) e[d] = (int)((w >> d) & 0x11111111u);
+  return e;
+}
+
+// Where lane (r, hh) finds the patch of pixel r of a block, and where the block's results go.
+struct PixelBlock {
+  const uint64_t* xb;  // base of the pixel's patch (tap (0, 0), channel word 0)
+  int64_t obase;       // element index of (image, filter 0, pixel)
+  bool valid;
+};
+
+__device__ __forceinline__ PixelBlock locate(const WsParams& p, int b, int r) {
+  PixelBlock pb;
+  const int n = b * 32 + r;
+  const int nc = min(n, p.P - 1);  // lanes past the last pixel repeat it and store nothing
+  const uint32_t img = fast_div((uint32_t)nc, p.div_howo);
+  const uint32_t rem = (uint32_t)nc - img * (uint32_t)p.HoWo;
+  const uint32_t ho = fast_div(rem, p.div_wo);
+  const uint32_t wo = rem - ho * (uint32_t)p.Wo;
+  pb.xb = p.Xp + (((int64_t)img * p.Hp + ho * p.stride) * p.Wpp + wo * p.stride) * p.Cw;
+  pb.obase = (int64_t)img * p.O * p.HoWo + rem;
+  pb.valid = n < p.P;
+  return pb;
+}
+
+// LDS.  Filters: row i of the workgroup's block holds its 8 * KW expanded dwords, the float
+// K - 2 * popcount and alpha; the row stride of 8 * KW + 4 dwords (4, 12 or 20 mod 32) lets
+// eight lanes read eight different bank groups with one 16-byte read each.
+// Pixels: a wave-private tile [32 pixels][KW words] through which the words, fetched with
+// neighbouring lanes on neighbouring addresses (lane (r, hh) takes word 2i + hh of pixel r;
+// a load in which every lane gathers its own pixel's words costs the memory pipeline one
+// access per lane), are turned into the MFMA's order (dword h of every word of pixel r).  Its
+// row stride is 2 * odd dwords, free of bank conflicts beyond the two-way one of 64 lanes
+// on 32 banks.
+template <int KW>
+struct Lds {
+  static constexpr int kFilterStride = 8 * KW + 4;                       // dwords
+  static constexpr int kPixelStride = ((KW % 2) ? 2 * KW : 2 * KW + 2);  // dwords; 2 * odd
+};
+
+// WPS: waves per SIMD the register allocation is held to.
+template <int KW, int TM, int WPS>
+__global__ void __launch_bounds__(256, WPS)
+conv_mfma_ws_kernel(const WsParams p) {
+  constexpr int NI = (KW + 1) / 2;  // load instructions per block: two words per pixel each
+  constexpr int FS = Lds<KW>::kFilterStride, PS = Lds<KW>::kPixelStride;
+  __shared__ __attribute__((aligned(16))) uint32_t filt[32 * TM * FS];
+  __shared__ uint32_t tiles[4][32 * PS];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int r = lane & 31, h = lane >> 5;
+  const int m0 = blockIdx.y * (32 * TM);
+  const int chunk = blockIdx.x * 4 + wave;
+  const int b0 = chunk * p.nb, b1 = min(b0 + p.nb, p.nblocks);
+  uint32_t* tile = tiles[wave];
+
+  // words 2i + h of the pixel's patch, i = 0 .. NI-1 (the odd KW's last one only for h = 0)
+  auto fetch = [&](const PixelBlock& pb, uint64_t (&st)[NI]) {
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+      st[i] = (2 * i + 1 < KW || h == 0) ? pb.xb[h ? p.off[2 * i + 1 < KW ? 2 * i + 1 : 0] : p.off[2 * i]] : 0;
+  };
+  // staged words -> tile -> dword h of every word of pixel r
+  auto transpose = [&](const uint64_t (&st)[NI], uint32_t (&raw)[KW]) {
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+      if (2 * i + 1 < KW || h == 0) *(u64_alias*)(tile + r * PS + 2 * (2 * i + h)) = st[i];
+#pragma unroll
+    for (int j = 0; j < KW; ++j) raw[j] = tile[r * PS + 2 * j + h];
+  };
+
+  // the first block's pixel words are requested before anything else (waves of the last
+  // workgroup that have no block fetch block 0 and drop it)
+  PixelBlock cur = locate(p, b0 < b1 ? b0 : 0, r);
+  uint64_t st[NI];
+  fetch(cur, st);
+
+  // ---- the workgroup's filters: 16-byte pieces, neighbouring threads on neighbouring pieces
+  for (int c = threadIdx.x; c < 32 * TM * (2 * KW + 1); c += 256) {
+    const int row = c / (2 * KW + 1), piece = c - row * (2 * KW + 1);
+    // rows past the last filter repeat it; their results are never stored
+    const uint32_t* src = p.Wp + (int64_t)min(m0 + row, p.O - 1) * p.ld_dw + p.fp4_dw + 4 * piece;
+    v4i v = *(const v4i*)src;
+    if (piece == 2 * KW) v[1] = p.alpha ? __float_as_int(p.alpha[min(m0 + row, p.O - 1)]) : __float_as_int(1.0f);
+    *(v4i_alias*)(filt + row * FS + 4 * piece) = v;
+  }
+  __syncthreads();
+  if (b0 >= b1) return;
+
+  // ---- blocks of 32 output pixels
+  for (int b = b0; b < b1; ++b) {
+    uint32_t raw[KW];
+    transpose(st, raw);
+    // the next block's words are requested before this block is multiplied
+    const PixelBlock nxt = locate(p, min(b + 1, b1 - 1), r);
+    fetch(nxt, st);
+    // (the filter reads below are the same in every trip: an opaque copy of their base keeps
+    // the compiler from hoisting all of them out of the loop and into registers for good)
+    int fbase = r * FS + 4 * h;
+    asm volatile("" : "+v"(fbase));
+    int pb = 0;
+    v16f acc[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][e] = 0.0f;
+#pragma unroll
+    for (int j = 0; j < KW; ++j) {
+      pb += __builtin_popcount(raw[j]);
+      const v8i eb = widen(expand4(raw[j]));
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const v4i a = *(const v4i_alias*)(filt + fbase + 32 * i * FS + 8 * j);
+        acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(a), eb, acc[i], 4, 4, 0, 128, 0, 128);
+      }
+      // keep the operands of step j + 4 and later behind this MFMA: gathered at the top of the
+      // block (the scheduler's preference) they would hold 8 * KW registers at once
+      if (j % 4 == 3) __builtin_amdgcn_sched_barrier(0);
+    }
+    pb += __shfl_xor(pb, 32);
+    // out = alpha * (K - 2 pc(filter) - 2 pc(patch) + 4 * sum): exact integers in fp32 up to
+    // the single rounding of the alpha product.  (The row constants of all result registers
+    // in one batch of LDS reads: read one by one inside the store loop, every value would pay
+    // a full LDS round trip.)
+    const float pb2 = 2.0f * (float)pb;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      float c0[16], al[16];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int mi = 32 * i + 8 * (v / 4) + 4 * h + (v % 4);  // row of result register v
+        c0[v] = __uint_as_float(filt[mi * FS + 8 * KW]);
+        al[v] = __uint_as_float(filt[mi * FS + 8 * KW + 1]);
+      }
+      if (p.out_i32) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int m = m0 + 32 * i + 8 * (v / 4) + 4 * h + (v % 4);
+          const float t = fmaf(4.0f, acc[i][v], c0[v]) - pb2;
+          if (cur.valid && m < p.O) __builtin_nontemporal_store((int)t, p.out_i32 + cur.obase + (int64_t)m * p.HoWo);
+        }
+      } else {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int m = m0 + 32 * i + 8 * (v / 4) + 4 * h + (v % 4);
+          const float t = fmaf(4.0f, acc[i][v], c0[v]) - pb2;
+          if (cur.valid && m < p.O) __builtin_nontemporal_store(al[v] * t, p.out_f32 + cur.obase + (int64_t)m * p.HoWo);
+        }
+      }
+    }
+    cur = nxt;
+  }
+}
+
+template <int KW, int TM, int WPS>
+void launch_ws(const WsParams& p, int m_tiles, hipStream_t s) {
+  const int chunks = (int)ceil_div(p.nblocks, p.nb);
+  hipLaunchKernelGGL((conv_mfma_ws_kernel<KW, TM, WPS>), dim3((unsigned)ceil_div(chunks, 4), (unsigned)m_tiles),
+                     dim3(256), 0, s, p);
+}
+
+}  // namespace
+
+bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, const uint64_t* Wp, int O,
+                         int KH, int KW, int stride, int pad, const float* alpha, int32_t* out_i32,
+                         float* out_f32, hipStream_t s, hipError_t* err) {
+  const int Ho = (H + 2 * pad - KH) / stride + 1;
+  const int Wo = (W + 2 * pad - KW) / stride + 1;
+  const int Cw = (int)words_for(C);
+  const int kwords = KH * KW * Cw;
+  if (!conv_weight_has_fp4(kwords) || ((uintptr_t)Wp & 15)) return false;
+  const int64_t P = (int64_t)Nimg * Ho * Wo;
+  if (P >= ((int64_t)1 << 31) || (int64_t)C * KH * KW >= ((int64_t)1 << 22)) return false;
+  WsParams p;
+  p.Xp = Xp;
+  p.Wp = (const uint32_t*)Wp;
+  p.ld_dw = 2 * (int)conv_weight_row_words(kwords);
+  p.fp4_dw = 2 * (int)conv_weight_bits_words(kwords);
+  p.alpha = alpha;
+  p.out_i32 = out_i32;
+  p.out_f32 = out_f32;
+  p.P = (int)P;
+  p.O = O;
+  p.HoWo = Ho * Wo;
+  p.Wo = Wo;
+  p.Hp = H + 2 * pad;
+  p.Wpp = W + 2 * pad;
+  p.Cw = Cw;
+  p.stride = stride;
+  p.div_howo = make_fast_div((uint32_t)(Ho * Wo));
+  p.div_wo = make_fast_div((uint32_t)Wo);
+  if ((int64_t)(KH * p.Wpp + KW) * Cw >= ((int64_t)1 << 30)) return false;
+  for (int j = 0; j < kMaxWsWords; ++j) p.off[j] = 0;
+  for (int kh = 0; kh < KH; ++kh)
+    for (int kw = 0; kw < KW; ++kw)
+      for (int cw = 0; cw < Cw; ++cw) p.off[(kh * KW + kw) * Cw + cw] = (kh * p.Wpp + kw) * Cw + cw;
+  p.nblocks = (int)ceil_div(P, 32);
+  // (64 filters per workgroup, two accumulator sets sharing every expanded pixel word, is kept
+  // for measurements only: it lost to 32 everywhere, 8.0 against 7.2 us on 16 x 64 x 56 x 56)
+  const int TM = (kwords == 9 && O > 32 && gemm_mfma_tile == 2) ? 2 : 1;
+  const int m_tiles = (int)ceil_div(O, 32 * TM);
+  if (m_tiles > 65535) return false;
+  // blocks per wave: the grid about four waves per SIMD
+  p.nb = (int)ceil_div((int64_t)m_tiles * p.nblocks, 4096);
+  if (conv_filters_per_wave > 0) p.nb = conv_filters_per_wave;  // (tuning hook reused: blocks per wave)
+  if (kwords == 9) {
+    if (TM == 2) launch_ws<9, 2, 2>(p, m_tiles, s);
+    else launch_ws<9, 1, 4>(p, m_tiles, s);
+  } else if (kwords == 18) {
+    launch_ws<18, 1, 3>(p, m_tiles, s);
+  } else {
+    launch_ws<36, 1, 2>(p, m_tiles, s);
+  }
+  *err = hipGetLastError();
+  return true;
+}
+
+}  // namespace bmx

@@ -528,7 +528,7 @@ hipError_t launch_conv_gemm(const uint64_t* Xp, int Nimg, int C, int H, int W, c
   const int Wo = (W + 2 * pad - KW) / stride + 1;
   const int Cw = (int)words_for(C);
   const int kwords = KH * KW * Cw;
-  const int ld_words = (int)conv_weight_row_words(kwords);
+  const int ld_words = (int)conv_weight_row_words(kwords);  // row stride
   const int CH = conv_weight_chunk_dwords(kwords);
   GemmParams p;
   p.A = (const uint32_t*)Wp;
@@ -539,7 +539,7 @@ hipError_t launch_conv_gemm(const uint64_t* Xp, int Nimg, int C, int H, int W, c
   p.N = Nimg * Ho * Wo;
   p.planes = 1;
   p.Kd = 2 * kwords;
-  p.nch = 2 * ld_words / CH;
+  p.nch = 2 * (int)conv_weight_bits_words(kwords) / CH;
   p.tail0 = p.tail1 = 0;
   p.Kreal = C * KH * KW;
   p.rowsum = nullptr;

@@ -226,19 +226,23 @@ hipError_t launch_pack_nchw(const float* x, int N, int C, int H, int W, int pad,
   return hipGetLastError();
 }
 
-// Offline weight packing for the convolution: one thread per output word.
+// Offline weight packing for the convolution: one thread per word of the bit section.
 // Wp[o][(kh*KW + kw)*Cw + cw] bit c = (w[o][64cw + c][kh][kw] >= 0); rows are ld words apart
-// and the words between the data and ld are written as zero.
+// and the words between the data and ldb (the chunk-padded bit section) are written as zero.
+// With fp4 set the thread of data word j also writes that word's two expanded halves into the
+// FP4 section behind the bits, and the row's K - 2 * popcount is summed with atomics into the
+// float slot the launcher zeroed.
 __global__ void __launch_bounds__(256)
-pack_conv_weights_kernel(const float* __restrict__ w, int O, int C, int KH, int KW, int Cw, int ld,
-                         uint64_t* __restrict__ Wp) {
+pack_conv_weights_kernel(const float* __restrict__ w, int O, int C, int KH, int KW, int Cw, int ld, int ldb,
+                         int fp4, uint64_t* __restrict__ Wp) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int64_t total = (int64_t)O * ld;
+  const int64_t total = (int64_t)O * ldb;
   if (idx >= total) return;
-  const int64_t o = idx / ld;
-  const int j = (int)(idx - o * ld);
+  const int64_t o = idx / ldb;
+  const int j = (int)(idx - o * ldb);
+  const int kwords = KH * KW * Cw;
   uint64_t word = 0;
-  if (j < KH * KW * Cw) {
+  if (j < kwords) {
     const int cw = j % Cw;
     const int t = j / Cw;
     const int kw = t % KW;
@@ -251,16 +255,41 @@ pack_conv_weights_kernel(const float* __restrict__ w, int O, int C, int KH, int 
       }
     }
   }
-  Wp[idx] = word;
+  uint64_t* row = Wp + o * ld;
+  row[j] = word;
+  if (fp4 && j < kwords) {
+    uint32_t* e = (uint32_t*)(row + ldb) + 8 * j;
+    for (int h = 0; h < 2; ++h) {
+      const uint32_t half = (uint32_t)(word >> (32 * h));
+      for (int d = 0; d < 4; ++d) e[4 * h + d] = (half >> d) & 0x11111111u;
+    }
+    // (integers below 2^24: the float sum is exact in any order)
+    atomicAdd((float*)((uint32_t*)(row + ldb) + 8 * kwords), -2.0f * (float)__popcll(word));
+  }
+}
+
+// The float slot of every row starts at K (C * KH * KW); the pad word behind it at zero.
+__global__ void __launch_bounds__(256)
+init_conv_weight_consts_kernel(int O, int ld, int ldb, int kwords, float K, uint64_t* __restrict__ Wp) {
+  const int o = blockIdx.x * blockDim.x + threadIdx.x;
+  if (o >= O) return;
+  uint32_t* c = (uint32_t*)(Wp + (int64_t)o * ld + ldb) + 8 * kwords;
+  c[0] = __float_as_uint(K);
+  c[1] = c[2] = c[3] = 0;
 }
 
 hipError_t launch_pack_conv_weights(const float* w, int O, int C, int KH, int KW, uint64_t* Wp,
                                     hipStream_t s) {
   const int Cw = (int)words_for(C);
-  const int ld = (int)conv_weight_row_words((int64_t)KH * KW * Cw);
-  const int64_t total = (int64_t)O * ld;
+  const int kwords = KH * KW * Cw;
+  const int ld = (int)conv_weight_row_words(kwords), ldb = (int)conv_weight_bits_words(kwords);
+  const int fp4 = conv_weight_has_fp4(kwords) ? 1 : 0;
+  if (fp4)
+    hipLaunchKernelGGL(init_conv_weight_consts_kernel, dim3((unsigned)ceil_div(O, 256)), dim3(256), 0, s, O, ld,
+                       ldb, kwords, (float)((int64_t)C * KH * KW), Wp);
+  const int64_t total = (int64_t)O * ldb;
   hipLaunchKernelGGL(pack_conv_weights_kernel, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, s,
-                     w, O, C, KH, KW, Cw, ld, Wp);
+                     w, O, C, KH, KW, Cw, ld, ldb, fp4, Wp);
   return hipGetLastError();
 }
 

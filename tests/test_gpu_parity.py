@@ -471,17 +471,68 @@ def test_conv_every_path(path):
         L.bmx_tune_set(7, 0)
 
 
+WS_CONV_CASES = [
+    # N, C, H, W, O, s, p   (3x3 with 9, 18 or 36 words of K: the short-K matrix-core kernel)
+    (1, 1, 3, 3, 1, 1, 0),
+    (2, 3, 5, 5, 4, 1, 1),
+    (1, 20, 8, 5, 3, 2, 1),
+    (2, 64, 5, 8, 5, 1, 1),
+    (3, 33, 7, 9, 70, 1, 2),
+    (2, 64, 56, 56, 64, 1, 1),
+    (1, 32, 57, 57, 130, 2, 0),
+    (2, 128, 28, 28, 128, 2, 1),
+    (3, 100, 9, 11, 33, 1, 1),
+    (1, 256, 14, 14, 19, 1, 2),
+    (5, 200, 9, 9, 256, 1, 1),
+    (64, 256, 14, 14, 40, 2, 1),
+]
+
+
+@pytest.mark.parametrize("N,C,H,W,O,s,p", WS_CONV_CASES)
+def test_conv_short_k_matrix_core(N, C, H, W, O, s, p):
+    """The convolution kernel that reads pre-expanded FP4 filters from LDS and streams pixel
+    blocks through the matrix cores, forced through the tuning hook: ragged filter and pixel
+    tiles, both filter-tile heights, several blocks per wave, every output kind."""
+    L = B.lib()
+    rng = np.random.default_rng(N + 10 * C + 100 * H + 1000 * O + s + p)
+    x = rng.standard_normal((N, C, H, W)).astype(np.float32)
+    x[rng.random(x.shape) < 0.05] = 0.0
+    w = rng.standard_normal((O, C, 3, 3)).astype(np.float32)
+    alpha = oracle.alpha_mean_abs(w)
+    ri, rf = oracle.binary_conv2d(x, w, s, p, alpha)
+    for tile, per_wave in ((0, 0), (2, 3), (0, 7)):
+        with tuned(k5=5, k9=tile, k1=per_wave):
+            np.testing.assert_array_equal(run_conv(x, w, s, p, integer_out=True), ri)
+            assert_f32_close(run_conv(x, w, s, p, alpha=alpha), rf)
+            np.testing.assert_array_equal(run_conv(x, w, s, p), ri.astype(np.float32))
+
+
 def test_conv_weight_rows_are_zero_padded():
-    """Packed filter rows are as long as bmx_conv_weight_row_words says and zero past the data."""
+    """Packed filter rows are as long as bmx_conv_weight_row_words says: the bits (zero past the
+    data up to a whole register chunk), and for K of 9, 18 or 36 words the same filter expanded
+    to FP4 nibbles with K - 2 * popcount behind it."""
     rng = np.random.default_rng(3)
-    for (O, C, k) in [(3, 64, 3), (2, 256, 3), (2, 130, 5), (4, 1, 1)]:
+    for (O, C, k) in [(3, 64, 3), (2, 256, 3), (2, 130, 5), (4, 1, 1), (5, 100, 3)]:
         w = rng.standard_normal((O, C, k, k)).astype(np.float32)
         Wp = host_u64(B.pack_conv_weights(dev(w)))
         kwords = k * k * ((C + 63) // 64)
         assert Wp.shape == (O, B.lib().bmx_conv_weight_row_words(C, k, k)) and Wp.shape[1] >= kwords
-        assert (Wp[:, kwords:] == 0).all()
         ref = oracle.binarize_pack(np.transpose(w, (0, 2, 3, 1)).reshape(O * k * k, C), 1)
-        np.testing.assert_array_equal(Wp[:, :kwords].reshape(O * k * k, -1), ref)
+        ref = ref.reshape(O, kwords)
+        np.testing.assert_array_equal(Wp[:, :kwords], ref)
+        if kwords not in (9, 18, 36):
+            assert (Wp[:, kwords:] == 0).all()
+            continue
+        ldb = Wp.shape[1] - 4 * kwords - 2
+        assert ldb >= kwords and (Wp[:, kwords:ldb] == 0).all()
+        fp4 = Wp[:, ldb:ldb + 4 * kwords].copy().view(np.uint32).reshape(O, kwords, 2, 4)
+        halves = ref.copy().view(np.uint32).reshape(O, kwords, 2)
+        for d in range(4):
+            np.testing.assert_array_equal(fp4[:, :, :, d], (halves >> d) & 0x11111111)
+        consts = Wp[:, ldb + 4 * kwords:].copy().view(np.float32)
+        pc = np.array([[bin(int(v)).count("1") for v in row] for row in ref]).sum(axis=1)
+        np.testing.assert_array_equal(consts[:, 0], (C * k * k - 2 * pc).astype(np.float32))
+        assert (consts[:, 1:] == 0).all()
 
 
 # ------------------------------------------------------------------ chained FC on packed bits
