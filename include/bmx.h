@@ -111,9 +111,10 @@ int bmx_binary_fc_packed(const uint64_t* xp, int64_t ldx_w, const uint64_t* Wp, 
  * of Sec. 2.2.3).  Wp is a matrix of O rows of bmx_conv_weight_row_words(C, KH, KW) words:
  * row o holds filter o, tap (kh, kw) at words (kh*KW + kw)*ceil(C/64) .., word cw of a tap
  * holding channels 64*cw .. 64*cw+63 (missing channels = 0 bits), followed by zero words up
- * to the row length (the kernels read filter rows in whole register chunks).  This K order
- * (tap-major, channel-minor) and the row length are private to the pair pack/conv; a dot
- * product does not depend on a permutation applied to both operands.
+ * to a whole register chunk, and for some K by the same filter expanded into matrix-core
+ * operands (the rest of the row).  This K order (tap-major, channel-minor), the row length
+ * and what lies behind the bits are private to the pair pack/conv; a dot product does not
+ * depend on a permutation applied to both operands.
  * bmx_conv_weight_row_words returns the row length in words (0 if KH, KW or C are outside
  * the supported set); the caller allocates O times that many words. */
 int64_t bmx_conv_weight_row_words(int C, int KH, int KW);
@@ -179,9 +180,10 @@ size_t bmx_workspace_bytes(int op, const int64_t* dims, int ndims);
  *   key 2  rows per wave (8, 16, 32), key 3  K-split waves, key 4  workgroup order of the
  *          xor/popcount GEMM kernel
  *   key 5  convolution kernel: 1 register-stationary, 2 xor/popcount GEMM kernel,
- *          3 one thread per output, 4 matrix cores
+ *          3 one thread per output, 4 matrix cores (GEMM-shaped), 5 matrix cores (short K,
+ *          filters in LDS)
  *   key 7  GEMM engine: 1 xor/popcount, 2 int8 matrix cores, 3 FP4 matrix cores
- *   key 8  K-split waves, key 9  (value 1) 32 x 32 tiles per wave of the matrix-core kernel */
+ *   key 8  K-split waves, key 9  tile variant (1: 32 x 32 per wave) of the matrix-core kernels */
 int bmx_tune_set(int key, int value);
 
 /* Static, human-readable name of a status code. */
