@@ -336,6 +336,24 @@ def main():
                 2.0 * 64 * 12800 * 25 * cin, kernel_us(
                     lambda: B.binary_conv2d(xq, Wq, 64, 5, 5, 1, 0, alpha=alq, out=oq, workspace=wsq)))
 
+        # Sec. 3.1's other two sweeps at 256 input channels, batch 200: filter count (5x5) and
+        # kernel size (64 filters), whole calls
+        def conv_call(cin, cout, k):
+            hw = 8 + k - 1
+            xq = torch.empty((200, cin, hw, hw), dtype=torch.float32, device="cuda").normal_()
+            wq = torch.empty((cout, cin, k, k), dtype=torch.float32, device="cuda").normal_()
+            Wq, alq = B.pack_conv_weights(wq), B.alpha_mean_abs(wq)
+            oq = torch.empty((200, cout, 8, 8), dtype=torch.float32, device="cuda")
+            wsq = torch.empty(B.workspace_bytes(B.OP_BINARY_CONV2D, (200, cin, hw, hw, cout, k, k, 1, 0)),
+                              dtype=torch.uint8, device="cuda")
+            us = kernel_us(lambda: B.binary_conv2d(xq, Wq, cout, k, k, 1, 0, alpha=alq, out=oq, workspace=wsq))
+            return alu(2.0 * cout * 12800 * k * k * cin, us)
+
+        for cout in (16, 128, 512):
+            other["paper_sec3_1_conv5x5_cin256_filters%d_call" % cout] = conv_call(256, cout, 5)
+        for k in (1, 3, 7):
+            other["paper_sec3_1_conv%dx%d_cin256_call" % (k, k)] = conv_call(256, 64, k)
+
     # ------------------------------------------------------------------ CPU oracle beside it
     cpu = None
     if not args.no_cpu_baseline:
@@ -351,6 +369,20 @@ def main():
         cpu = {"value": binops * reps / t_cpu / 1e9, "unit": "GOPS", "cores": oracle.num_threads(),
                "kind": "oracle", "sample": "%d full passes of the config-2 layer (%.3f s each)"
                % (reps, t_cpu / reps)}
+        # the paper's own method on the same host cores (Sec. 2.2.1: xnor + popcount over 64-bit
+        # words), GEMM only on the layer's im2col view, as the paper times it (Sec. 3.1)
+        col = oracle.im2col(x_h, KH, KW, stride, pad)
+        Ap = oracle.binarize_pack(w_h.reshape(O, -1), 1)
+        Bp = oracle.binarize_pack(col, 1)
+        del col
+        oracle.xnor_gemm(Ap, Bp, C * KH * KW)
+        t1 = time.perf_counter()
+        for _ in range(5):
+            oracle.xnor_gemm(Ap, Bp, C * KH * KW)
+        t_x = (time.perf_counter() - t1) / 5
+        cpu["xnor_popcount_gemm_only"] = {"value": binops / t_x / 1e9, "unit": "GOPS",
+                                          "sample": "5 passes of the 64 x 50176 x 576 GEMM on packed words (%.4f s each), "
+                                                    "packing not timed" % t_x}
 
     line = {"metric": "binary GOPS (2*M*N*K xnor-popcount)", "value": value, "unit": "GOPS",
             "n_gpus": 1, "steps": K_STEPS, "warmup": args.warmup, "ms_per_step": ms_per_step,
