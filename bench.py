@@ -18,8 +18,11 @@ stream) and the timed region is one replay of that graph: exactly K steps, devic
 The eager (host-enqueued) rate is reported next to it.
 
 Prints ONE JSON line.  `value` is 2*M*N*K binary operations per second over the whole step;
-`roofline` prices the dominant kernel (the convolution) against the VALU xor+popcount peak,
-its duration measured with HIP events on the launch stream around K back-to-back launches
+`roofline` prices the dominant kernel (the convolution).  It runs on the FP4 matrix cores,
+where its 3.7 G multiply-adds x 2 are 0.37 us of work against 1.66 us for the 13.3 MB it must
+move, so HBM is the roof that bounds it; the fractions of the VALU xor+popcount peak and of
+the FP4 peak are given beside it, and `--tune 5=1` puts the xor/popcount kernel in its place.
+Its duration is measured with HIP events on the launch stream around K back-to-back launches
 on the same rotating buffers; `cpu_baseline` times the CPU oracle on the same layer on the
 host cores; `other_configs` gives event-timed figures for BASELINE configurations 1, 3, 4, 5.
 """
@@ -182,16 +185,28 @@ def main():
         for ln in open(tpath):
             if ln.startswith("hbm_bytes_per_launch:"):
                 traffic = int(ln.split(":")[1])
-    roofline = {"bound": "alu", "kernel": "conv_stationary_kernel<9,2> (implicit-GEMM xor+popcount)",
-                "achieved": achieved / 1e12, "peak": VALU_PEAK_BINOPS / 1e12, "unit": "Tbinop/s",
-                "frac": achieved / VALU_PEAK_BINOPS, "traffic": traffic, "avg_us": conv_us,
+    popcount_conv = any(kv.split("=") == ["5", "1"] for kv in args.tune)
+    # bytes the convolution kernel must move: packed image in, packed filters in, fp32 out
+    conv_bytes = xps[0].numel() * 8 + Wp.numel() * 8 + out_bytes
+    if popcount_conv:
+        roofline = {"bound": "alu", "kernel": "conv_stationary_kernel<9,2> (implicit-GEMM xor+popcount)",
+                    "achieved": achieved / 1e12, "peak": VALU_PEAK_BINOPS / 1e12, "unit": "Tbinop/s",
+                    "frac": achieved / VALU_PEAK_BINOPS}
+    else:
+        roofline = {"bound": "hbm", "kernel": "conv_mfma_ws_kernel<9,1,4> (implicit GEMM on the FP4 matrix cores)",
+                    "achieved": conv_bytes / (conv_us * 1e-6) / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+                    "frac": conv_bytes / (conv_us * 1e-6) / HBM_PEAK,
+                    "algorithmic_bytes_per_launch": conv_bytes,
+                    "binops_frac_of_valu_xor_popcount_peak": achieved / VALU_PEAK_BINOPS,
+                    "flops_frac_of_fp4_matrix_core_peak": achieved / 10.1e15}
+    roofline.update({"traffic": traffic, "avg_us": conv_us,
                 "algorithmic_binops_per_launch": binops,
                 "output_bytes_per_launch": out_bytes,
                 "pack_kernel": {"kernel": "pack_nchw_kernel", "bound": "hbm",
                                 "achieved": pack_bytes / (pack_us * 1e-6) / 1e9,
                                 "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                                 "frac": pack_bytes / (pack_us * 1e-6) / HBM_PEAK, "avg_us": pack_us,
-                                "algorithmic_bytes_per_launch": pack_bytes}}
+                                "algorithmic_bytes_per_launch": pack_bytes}})
     del xs, wss, outs, xps, steps, g_steps
 
     # ------------------------------------------------------------------ other configurations
@@ -391,6 +406,8 @@ def main():
             "config": {"workload": "config2: binary conv2d 3x3 s1 p1, x[16,64,56,56], 64 filters, "
                                    "alpha epilogue, fp32 out (GEMM view M=64 N=50176 K=576)",
                        "step": "bmx_binary_conv2d = channel pack + implicit-GEMM conv + alpha",
+                       "kernels": "pack_nchw_kernel + " + ("conv_stationary_kernel<9,2>" if popcount_conv
+                                                           else "conv_mfma_ws_kernel<9,1,4>"),
                        "timed_region": "one replay of a HIP graph holding the K steps",
                        "buffer_sets_rotated": int(nsets),
                        "ms_per_step_cache_hot": hot_us * 1e-3,

@@ -134,14 +134,30 @@ conv_mfma_ws_kernel(const WsParams p) {
   uint64_t st[NI];
   fetch(cur, st);
 
-  // ---- the workgroup's filters: 16-byte pieces, neighbouring threads on neighbouring pieces
-  for (int c = threadIdx.x; c < 32 * TM * (2 * KW + 1); c += 256) {
-    const int row = c / (2 * KW + 1), piece = c - row * (2 * KW + 1);
-    // rows past the last filter repeat it; their results are never stored
-    const uint32_t* src = p.Wp + (int64_t)min(m0 + row, p.O - 1) * p.ld_dw + p.fp4_dw + 4 * piece;
-    v4i v = *(const v4i*)src;
-    if (piece == 2 * KW) v[1] = p.alpha ? __float_as_int(p.alpha[min(m0 + row, p.O - 1)]) : __float_as_int(1.0f);
-    *(v4i_alias*)(filt + row * FS + 4 * piece) = v;
+  // ---- the workgroup's filters: 16-byte pieces, neighbouring threads on neighbouring pieces;
+  // all of a thread's loads are issued before the first is written to LDS (one after the
+  // other, every piece would cost a full memory round trip: 6 of 9 us at K = 36 words)
+  constexpr int kPieces = 32 * TM * (2 * KW + 1);
+  constexpr int kCopies = (kPieces + 255) / 256;
+  {
+    v4i buf[kCopies];
+#pragma unroll
+    for (int t = 0; t < kCopies; ++t) {
+      const int c = min((int)threadIdx.x + 256 * t, kPieces - 1);
+      const int row = c / (2 * KW + 1), piece = c - row * (2 * KW + 1);
+      // rows past the last filter repeat it; their results are never stored
+      buf[t] = *(const v4i*)(p.Wp + (int64_t)min(m0 + row, p.O - 1) * p.ld_dw + p.fp4_dw + 4 * piece);
+    }
+    float myalpha = 1.0f;  // thread t < 32 * TM carries alpha of row t
+    if ((int)threadIdx.x < 32 * TM && p.alpha) myalpha = p.alpha[min(m0 + (int)threadIdx.x, p.O - 1)];
+#pragma unroll
+    for (int t = 0; t < kCopies; ++t) {
+      const int c = (int)threadIdx.x + 256 * t;
+      const int row = c / (2 * KW + 1), piece = c - row * (2 * KW + 1);
+      if (c < kPieces) *(v4i_alias*)(filt + row * FS + 4 * piece) = buf[t];
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < 32 * TM) filt[(int)threadIdx.x * FS + 8 * KW + 1] = __float_as_uint(myalpha);
   }
   __syncthreads();
   if (b0 >= b1) return;
@@ -259,8 +275,9 @@ bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, cons
   const int TM = (kwords == 9 && O > 32 && gemm_mfma_tile == 2) ? 2 : 1;
   const int m_tiles = (int)ceil_div(O, 32 * TM);
   if (m_tiles > 65535) return false;
-  // blocks per wave: the grid about four waves per SIMD
-  p.nb = (int)ceil_div((int64_t)m_tiles * p.nblocks, 4096);
+  // blocks per wave: one, except where the filter copy of a workgroup is long (36 words: 37 KB)
+  // and the grid large enough to stay full with two (15.6 against 17.7 us)
+  p.nb = (kwords == 36 && (int64_t)m_tiles * p.nblocks >= 2048) ? 2 : 1;
   if (conv_filters_per_wave > 0) p.nb = conv_filters_per_wave;  // (tuning hook reused: blocks per wave)
   if (kwords == 9) {
     if (TM == 2) launch_ws<9, 2, 2>(p, m_tiles, s);
