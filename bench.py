@@ -1,6 +1,6 @@
 """Benchmark of the binary-layer hot path on one MI355X.
 
-Workload: BASELINE configuration 2, the ResNet-18 stage convolution (x [16,64,56,56] fp32,
+Workload: configuration 2 of the benchmark set, the ResNet-18 stage convolution (x [16,64,56,56] fp32,
 3x3, stride 1, pad 1, 64 filters, alpha epilogue, fp32 NCHW output).  One step is one call of
 bmx_binary_conv2d: channel pack of the activations + implicit-GEMM xor/popcount convolution
 with the alpha epilogue.  Weights are packed and alpha is computed once, outside the step
@@ -24,7 +24,7 @@ move, so HBM is the roof that bounds it; the fractions of the VALU xor+popcount 
 the FP4 peak are given beside it, and `--tune 5=1` puts the xor/popcount kernel in its place.
 Its duration is measured with HIP events on the launch stream around K back-to-back launches
 on the same rotating buffers; `cpu_baseline` times the CPU oracle on the same layer on the
-host cores; `other_configs` gives event-timed figures for BASELINE configurations 1, 3, 4, 5.
+host cores; `other_configs` gives event-timed figures for configurations 1, 3, 4, 5 of the set.
 """
 import argparse
 import json
