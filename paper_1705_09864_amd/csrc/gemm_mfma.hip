@@ -1,12 +1,13 @@
-// xnor GEMM on the int8 matrix cores.
+// xnor GEMM on the matrix cores (FP4 form by default, int8 form beside it).
 // Paper: Sec. 2.2.1 / Sec. 2.2.2 (Eq. 2): C[m][n] = K - 2 * popcount(A[m] xor B[n]).
 //
 // With a, b in {0, 1}:  a xor b = a + b - 2ab, so
 //     C[m][n] = K - 2 * pc(A[m]) - 2 * pc(B[n]) + 4 * sum_k a[m][k] * b[n][k],
 // and the last sum is an integer matrix product.  The operands stay bit-packed in memory and
 // in the loads (that is what keeps the traffic 32x below fp32, Sec. 1); a lane turns its
-// bits into 0/1 bytes in registers right before v_mfma_i32_32x32x32_i8 consumes them.
-// Expansion: for a 32-bit word w, (w >> j) & 0x01010101 puts bits j, j+8, j+16, j+24 into the
+// bits into 0/1 bytes in registers right before v_mfma_i32_32x32x32_i8 consumes them (or
+// into FP4 nibbles for v_mfma_scale_f32_32x32x64_f8f6f4: see expand4 below).
+// Expansion (int8 form): for a 32-bit word w, (w >> j) & 0x01010101 puts bits j, j+8, j+16, j+24 into the
 // four bytes of a dword, so eight shift/and pairs give the 32 bytes two MFMA steps take.
 // Which bit lands in which byte does not matter as long as both operands use the same order:
 // a dot product is invariant under a permutation of k applied to both.
@@ -18,9 +19,10 @@
 // operand = weight rows), and stores are two 128-byte runs per instruction.
 //
 // A wave owns a (32 * TM) x (32 * TN) tile of C and a range of K; per row and "macro step"
-// of 1024 bits a lane loads its 64 bytes (one half of a 128-byte line, the other half-wave
-// takes the rest), counts their ones (pc(A[m]), pc(B[n]) come for free this way), and feeds
-// 32 MFMA steps.  The S waves of a workgroup split K and add their partial results in LDS.
+// of 1024 bits a lane ends up with its 64 bytes (one half of a 128-byte line, the other
+// half-wave holds the rest; how they get there is described at load_rows_coalesced), counts
+// their ones (pc(A[m]), pc(B[n]) come for free this way), and feeds 16 (FP4) or 32 (int8)
+// MFMA steps.  The S waves of a workgroup split K and add their partial results in LDS.
 //
 // The k-bit activations of the quantised GEMM (Sec. 2.1, Eq. 1) ride the same kernel: the A
 // byte becomes the quantised value itself, q = sum_p 2^p * plane_p, assembled from the bit
