@@ -171,7 +171,9 @@ conv_mfma_ws_kernel(const WsParams p) {
     fetch(nxt, st);
     // (the filter reads below are the same in every trip: an opaque copy of their base keeps
     // the compiler from hoisting all of them out of the loop and into registers for good)
-    int fbase = r * FS + 4 * h;
+    // (counted in 16-byte pieces from the aligned base, so that the read is one ds_read_b128:
+    // split into dword pairs, the lanes of eight rows would meet on four banks)
+    int fbase = r * (FS / 4) + h;
     asm volatile("" : "+v"(fbase));
     int pb = 0;
     v16f acc[TM];
@@ -185,7 +187,7 @@ conv_mfma_ws_kernel(const WsParams p) {
       const v8i eb = widen(expand4(raw[j]));
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
-        const v4i a = *(const v4i_alias*)(filt + fbase + 32 * i * FS + 8 * j);
+        const v4i a = ((const v4i_alias*)filt)[fbase + 8 * i * FS + 2 * j];
         acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(a), eb, acc[i], 4, 4, 0, 128, 0, 128);
       }
       // keep the operands of step j + 4 and later behind this MFMA: gathered at the top of the
