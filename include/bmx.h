@@ -176,7 +176,9 @@ size_t bmx_workspace_bytes(int op, const int64_t* dims, int ndims);
  * variant; not part of the layers the paper defines.  Results never depend on it: every
  * engine and shape computes the same integers (Sec. 2.2.2).  Process-wide, not thread safe;
  * value 0 restores the automatic choice.  Returns BMX_ERR_UNSUPPORTED for an unknown key.
- *   key 1  filters per wave of the register-stationary convolution kernel
+ *   key 1  filters per wave of the register-stationary convolution kernel; for the short-K
+ *          matrix-core kernel, pixel blocks per wave (below 100) or the number of waves the
+ *          blocks are dealt out to per filter tile (100 and above)
  *   key 2  rows per wave (8, 16, 32), key 3  K-split waves, key 4  workgroup order of the
  *          xor/popcount GEMM kernel
  *   key 5  convolution kernel: 1 register-stationary, 2 xor/popcount GEMM kernel,

@@ -15,6 +15,8 @@
 // h of the word of pixel r), expands them (8 VALU instructions per word) and issues KW * TM
 // MFMAs.  Lanes run along pixels (operand B), so the NCHW stores are two 128-byte runs per
 // instruction.
+#include <algorithm>
+
 #include "bmx_internal.h"
 
 namespace bmx {
@@ -40,7 +42,7 @@ struct WsParams {
   float* out_f32;
   int P;  // N * Ho * Wo
   int O, HoWo, Wo, Hp, Wpp, Cw, stride;
-  int nblocks, nb;  // blocks of 32 pixels in all; blocks per wave
+  int nblocks, nchunks;  // blocks of 32 pixels in all; waves they are dealt out to (evenly)
   FastDiv div_howo, div_wo;
   int off[kMaxWsWords];  // word offset of K-word j relative to the pixel base
 };
@@ -110,7 +112,10 @@ conv_mfma_ws_kernel(const WsParams p) {
   const int r = lane & 31, h = lane >> 5;
   const int m0 = blockIdx.y * (32 * TM);
   const int chunk = blockIdx.x * 4 + wave;
-  const int b0 = chunk * p.nb, b1 = min(b0 + p.nb, p.nblocks);
+  // chunk c takes blocks [c * nblocks / nchunks, (c + 1) * nblocks / nchunks)
+  const int cc = min(chunk, p.nchunks);
+  const int b0 = (int)(((int64_t)cc * p.nblocks) / p.nchunks);
+  const int b1 = (int)(((int64_t)min(cc + 1, p.nchunks) * p.nblocks) / p.nchunks);
   uint32_t* tile = tiles[wave];
 
   // words 2i + h of the pixel's patch, i = 0 .. NI-1 (the odd KW's last one only for h = 0)
@@ -231,7 +236,7 @@ conv_mfma_ws_kernel(const WsParams p) {
 
 template <int KW, int TM, int WPS>
 void launch_ws(const WsParams& p, int m_tiles, hipStream_t s) {
-  const int chunks = (int)ceil_div(p.nblocks, p.nb);
+  const int chunks = p.nchunks;
   hipLaunchKernelGGL((conv_mfma_ws_kernel<KW, TM, WPS>), dim3((unsigned)ceil_div(chunks, 4), (unsigned)m_tiles),
                      dim3(256), 0, s, p);
 }
@@ -277,10 +282,15 @@ bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, cons
   const int TM = (kwords == 9 && O > 32 && gemm_mfma_tile == 2) ? 2 : 1;
   const int m_tiles = (int)ceil_div(O, 32 * TM);
   if (m_tiles > 65535) return false;
-  // blocks per wave: one, except where the filter copy of a workgroup is long (36 words: 37 KB)
-  // and the grid large enough to stay full with two (15.6 against 17.7 us)
-  p.nb = (kwords == 36 && (int64_t)m_tiles * p.nblocks >= 2048) ? 2 : 1;
-  if (conv_filters_per_wave > 0) p.nb = conv_filters_per_wave;  // (tuning hook reused: blocks per wave)
+  // Waves: one per block while all of them are resident at once (4, 3 and 2 workgroups per CU
+  // for 9, 18 and 36 words); beyond that, as many waves as are resident in one round,
+  // the blocks dealt out evenly: every workgroup copies its filters once
+  // and no CU is left with a second round of a few workgroups (configuration 4: 11.5 -> 10.8 us,
+  // 64 x 128 x 28 x 28: 12.2 -> 10.1 us).
+  const int resident_waves = 256 * 4 * (kwords == 9 ? 4 : kwords == 18 ? 3 : 2);
+  p.nchunks = (int)std::min<int64_t>(p.nblocks, std::max(1, resident_waves / m_tiles));
+  if (conv_filters_per_wave >= 100) p.nchunks = std::min(p.nblocks, conv_filters_per_wave);  // (tuning hook reused: chunks)
+  else if (conv_filters_per_wave > 0) p.nchunks = (int)ceil_div(p.nblocks, conv_filters_per_wave);  // (or blocks per wave)
   if (kwords == 9) {
     if (TM == 2) launch_ws<9, 2, 2>(p, m_tiles, s);
     else launch_ws<9, 1, 4>(p, m_tiles, s);

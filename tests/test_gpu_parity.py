@@ -492,7 +492,8 @@ WS_CONV_CASES = [
 def test_conv_short_k_matrix_core(N, C, H, W, O, s, p):
     """The convolution kernel that reads pre-expanded FP4 filters from LDS and streams pixel
     blocks through the matrix cores, forced through the tuning hook: ragged filter and pixel
-    tiles, both filter-tile heights, several blocks per wave, every output kind."""
+    tiles, both filter-tile heights, several blocks per wave (a fixed count, and an uneven deal
+    of the blocks over 101 waves), every output kind."""
     L = B.lib()
     rng = np.random.default_rng(N + 10 * C + 100 * H + 1000 * O + s + p)
     x = rng.standard_normal((N, C, H, W)).astype(np.float32)
@@ -500,7 +501,7 @@ def test_conv_short_k_matrix_core(N, C, H, W, O, s, p):
     w = rng.standard_normal((O, C, 3, 3)).astype(np.float32)
     alpha = oracle.alpha_mean_abs(w)
     ri, rf = oracle.binary_conv2d(x, w, s, p, alpha)
-    for tile, per_wave in ((0, 0), (2, 3), (0, 7)):
+    for tile, per_wave in ((0, 0), (2, 3), (0, 7), (0, 101)):
         with tuned(k5=5, k9=tile, k1=per_wave):
             np.testing.assert_array_equal(run_conv(x, w, s, p, integer_out=True), ri)
             assert_f32_close(run_conv(x, w, s, p, alpha=alpha), rf)
