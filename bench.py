@@ -347,6 +347,40 @@ def main():
             if s4 == 1:
                 other["config4_pack_nchw"] = hbm(x4.numel() * 4 + xp4.numel() * 8, kernel_us(
                     lambda: B.pack_nchw(x4, 1, out=xp4)))
+        # configuration-2 blocks chained (Sec. 2: QActivation -> QConvolution -> BatchNorm, three in
+        # a row, 64 -> 64 channels on 16 x 56 x 56): every layer through an fp32 feature map
+        # (pack + convolution each), or handing the next layer its packed image (one pack, the
+        # BatchNorm folded into a per-channel threshold)
+        xc = torch.from_numpy(x_h).cuda()
+        wc = [torch.empty((64, 64, 3, 3), dtype=torch.float32, device="cuda").normal_() for _ in range(3)]
+        Wc = [B.pack_conv_weights(t) for t in wc]
+        alc = [B.alpha_mean_abs(t) for t in wc]
+        thc = torch.empty((64,), dtype=torch.float32, device="cuda").normal_()
+        wsc = torch.empty(B.workspace_bytes(B.OP_BINARY_CONV2D, (16, 64, 56, 56, 64, 3, 3, 1, 1)),
+                          dtype=torch.uint8, device="cuda")
+        fa = torch.empty((16, 64, 56, 56), dtype=torch.float32, device="cuda")
+        fb = torch.empty_like(fa)
+        xpc = B.pack_nchw(xc, 1)
+        ia = torch.empty_like(xpc)
+        ib = torch.empty_like(xpc)
+        ops_c = 3 * 2.0 * 64 * 16 * 56 * 56 * 576
+
+        def blocks_fp32():
+            B.binary_conv2d(xc, Wc[0], 64, 3, 3, 1, 1, alpha=alc[0], out=fa, workspace=wsc)
+            B.binary_conv2d(fa, Wc[1], 64, 3, 3, 1, 1, alpha=alc[1], out=fb, workspace=wsc)
+            B.binary_conv2d(fb, Wc[2], 64, 3, 3, 1, 1, alpha=alc[2], out=fa, workspace=wsc)
+
+        def blocks_packed():
+            B.pack_nchw(xc, 1, out=xpc)
+            B.binary_conv2d_bits(xpc, 64, Wc[0], 64, 3, 3, 1, 1, alpha=alc[0], thr=thc, out_pad=1, out=ia)
+            B.binary_conv2d_bits(ia, 64, Wc[1], 64, 3, 3, 1, 1, alpha=alc[1], thr=thc, out_pad=1, out=ib)
+            B.binary_conv2d_packed(ib, 64, Wc[2], 64, 3, 3, 1, 1, alpha=alc[2], out=fa)
+
+        other["config2_three_blocks_via_fp32_maps"] = mfma(ops_c, kernel_us(blocks_fp32, 50))
+        other["config2_three_blocks_via_packed_images"] = mfma(ops_c, kernel_us(blocks_packed, 50))
+        other["config2_conv_to_packed_image_kernel"] = mfma(ops_c / 3, kernel_us(
+            lambda: B.binary_conv2d_bits(xpc, 64, Wc[0], 64, 3, 3, 1, 1, alpha=alc[0], thr=thc, out_pad=1, out=ia)))
+        del xc, fa, fb
         # config 5: 2-bit x 1-bit GEMM, whole call (quantise + plane pack + weight pack + GEMM)
         c5 = synth.config5()
         a5 = torch.from_numpy(c5["a"]).cuda()

@@ -58,6 +58,7 @@ extern "C" {
 #define BMX_OP_BINARY_FC 1     /* dims = {batch, in_features, out_features} */
 #define BMX_OP_BINARY_CONV2D 2 /* dims = {N, C, H, W, O, KH, KW, stride, pad} */
 #define BMX_OP_QUANT_GEMM 3    /* dims = {M, N, K, bits_a, bits_w} */
+#define BMX_OP_BINARY_CONV2D_BITS 4 /* dims = {N, C, H, W, O, KH, KW, stride, pad, out_pad} */
 
 /* Sign-binarise and bit-pack (Sec. 1: binarisation with the sign function, 64
  * values per word; Sec. 3.1: the per-forward-pass input binarisation step).
@@ -148,6 +149,28 @@ int bmx_pack_nchw(const float* x, int N, int C, int H, int W, int pad, uint64_t*
 int bmx_binary_conv2d_packed(const uint64_t* xp, int N, int C, int H, int W, const uint64_t* Wp,
                              int O, int KH, int KW, int stride, int pad, const float* alpha,
                              int32_t* out_i32, float* out_f32, void* stream);
+
+/* Binary convolution whose result leaves as the packed image the next binary convolution
+ * reads, for chains of binary blocks (Sec. 2: QActivation -> QConvolution -> BatchNorm, block
+ * after block): the fp32 feature map between two binary convolutions is neither written nor
+ * read, and the next layer needs no bmx_pack_nchw.
+ *   xp, N, C, H, W, Wp, O, KH, KW, stride, pad, alpha as for bmx_binary_conv2d_packed.
+ *   thr    fp32 [O] or NULL (= 0): bit o of an output pixel is
+ *            (alpha[o] * (float)dot >= thr[o])     (the IEEE compare of the fp32 product),
+ *          with thr NULL exactly what bmx_pack_nchw makes of the out_f32 result.  A BatchNorm
+ *          behind the convolution folds into thr: gamma * (v - mean) / sigma + beta >= 0 is
+ *          v >= mean - beta * sigma / gamma for gamma > 0 (for gamma < 0 negate alpha and thr).
+ *   out_xp uint64 [N][Ho + 2*out_pad][Wo + 2*out_pad][ceil(O/64)], the layout of bmx_pack_nchw
+ *          for an image of O channels: written whole, the halo with every real channel +1 (the
+ *          sign of the next layer's zero padding), missing channels 0 bits.  0 <= out_pad <= 6.
+ *   workspace >= bmx_workspace_bytes(BMX_OP_BINARY_CONV2D_BITS, {N,C,H,W,O,KH,KW,stride,pad,
+ *          out_pad}, 10): 0 where the convolution kernel writes the bits itself (3 x 3 kernels
+ *          over at most 256 channels, Wp 16-byte aligned), else room for the fp32 result, which
+ *          then passes through the channel pack with the same compare. */
+int bmx_binary_conv2d_bits(const uint64_t* xp, int N, int C, int H, int W, const uint64_t* Wp, int O,
+                           int KH, int KW, int stride, int pad, const float* alpha, const float* thr,
+                           uint64_t* out_xp, int out_pad, void* workspace, size_t workspace_bytes,
+                           void* stream);
 
 /* k-bit activations x 1-bit weights (Sec. 1: arbitrary bit widths after DoReFa-Net;
  * Sec. 2.1, Eq. 1).  a in [0, 1] (clamped) is quantised to the integer level

@@ -15,11 +15,12 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libbmx.so")
 _lib = None
 
-OP_BINARY_FC, OP_BINARY_CONV2D, OP_QUANT_GEMM = 1, 2, 3
+OP_BINARY_FC, OP_BINARY_CONV2D, OP_QUANT_GEMM, OP_BINARY_CONV2D_BITS = 1, 2, 3, 4
 EXPORTS = ["bmx_binarize_pack", "bmx_xnor_gemm", "bmx_binary_fc", "bmx_pack_conv_weights",
            "bmx_binary_conv2d", "bmx_quant_gemm", "bmx_alpha_mean_abs", "bmx_pack_nchw",
            "bmx_binary_conv2d_packed", "bmx_workspace_bytes", "bmx_status_string", "bmx_version",
-           "bmx_conv_weight_row_words", "bmx_binary_fc_packed", "bmx_tune_set"]
+           "bmx_conv_weight_row_words", "bmx_binary_fc_packed", "bmx_tune_set",
+           "bmx_binary_conv2d_bits"]
 
 _i64, _int, _p, _sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
 
@@ -59,6 +60,9 @@ def lib():
         L.bmx_pack_nchw.argtypes = [_p, _int, _int, _int, _int, _int, _p, _p]
         L.bmx_binary_conv2d_packed.argtypes = [_p, _int, _int, _int, _int, _p, _int, _int, _int, _int,
                                                _int, _p, _p, _p, _p]
+        L.bmx_binary_conv2d_bits.argtypes = [_p, _int, _int, _int, _int, _p, _int, _int, _int, _int, _int,
+                                             _p, _p, _p, _int, _p, _sz, _p]
+        L.bmx_binary_conv2d_bits.restype = _int
         L.bmx_tune_set.argtypes = [_int, _int]
         L.bmx_tune_set.restype = _int
         for name in EXPORTS[:9]:
@@ -210,6 +214,22 @@ def binary_conv2d_packed(xp, C, Wp, O, KH, KW, stride=1, pad=0, alpha=None, inte
     _check(lib().bmx_binary_conv2d_packed(_ptr(xp), N, C, H, W, _ptr(Wp), O, KH, KW, stride, pad,
                                           _ptr(alpha), _ptr(oi), _ptr(of), _stream(stream)),
            "bmx_binary_conv2d_packed")
+    return out
+
+
+def binary_conv2d_bits(xp, C, Wp, O, KH, KW, stride=1, pad=0, alpha=None, thr=None, out_pad=1,
+                       out=None, workspace=None, stream=None):
+    """Convolution on a packed image whose result is the next convolution's packed image
+    [N, Ho + 2*out_pad, Wo + 2*out_pad, ceil(O/64)] (int64 storage holding the uint64 words)."""
+    N, H, W = xp.shape[0], xp.shape[1] - 2 * pad, xp.shape[2] - 2 * pad
+    Ho, Wo = conv_out_hw(H, W, KH, KW, stride, pad)
+    if out is None:
+        out = _u64_as_i64((N, Ho + 2 * out_pad, Wo + 2 * out_pad, (O + 63) // 64), xp.device)
+    ws, ws_bytes = _workspace(OP_BINARY_CONV2D_BITS, (N, C, H, W, O, KH, KW, stride, pad, out_pad),
+                              xp.device, workspace)
+    _check(lib().bmx_binary_conv2d_bits(_ptr(xp), N, C, H, W, _ptr(Wp), O, KH, KW, stride, pad,
+                                        _ptr(alpha), _ptr(thr), _ptr(out), out_pad, _ptr(ws), ws_bytes,
+                                        _stream(stream)), "bmx_binary_conv2d_bits")
     return out
 
 

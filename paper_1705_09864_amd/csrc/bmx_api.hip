@@ -102,6 +102,18 @@ size_t bmx_workspace_bytes(int op, const int64_t* dims, int ndims) {
       const size_t n = dims[0] > 0 ? (size_t)dims[0] : 1;
       return round256(n * (dims[2] + 2 * dims[8]) * (dims[3] + 2 * dims[8]) * g.Cw * 8);
     }
+    case BMX_OP_BINARY_CONV2D_BITS: {
+      if (ndims != 10 || dims[9] < 0 || dims[9] > 6) return 0;
+      ConvGeom g;
+      if (conv_check((int)dims[0], (int)dims[1], (int)dims[2], (int)dims[3], (int)dims[4],
+                     (int)dims[5], (int)dims[6], (int)dims[7], (int)dims[8], &g) != BMX_OK)
+        return 0;
+      if (bmx::conv_mfma_ws_takes((int)dims[0], (int)dims[1], (int)dims[2], (int)dims[3], (int)dims[4],
+                                  (int)dims[5], (int)dims[6], (int)dims[7], (int)dims[8], (int)dims[9]))
+        return 0;  // the convolution kernel writes the bits itself
+      const size_t n = dims[0] > 0 ? (size_t)dims[0] : 1;
+      return round256(n * (dims[4] > 0 ? dims[4] : 1) * g.Ho * g.Wo * 4);
+    }
     case BMX_OP_QUANT_GEMM: {
       if (ndims != 5 || dims[0] < 0 || dims[1] < 0 || dims[2] <= 0 || dims[2] >= kMaxK) return 0;
       if (dims[3] < 1 || dims[3] > 8 || dims[4] != 1) return 0;
@@ -239,6 +251,39 @@ int bmx_binary_conv2d_packed(const uint64_t* xp, int N, int C, int H, int W, con
     return BMX_ERR_ALIGN;
   return hip_status(bmx::launch_binary_conv2d(xp, N, C, H, W, Wp, O, KH, KW, stride, pad, alpha,
                                               out_i32, out_f32, (hipStream_t)stream));
+}
+
+int bmx_binary_conv2d_bits(const uint64_t* xp, int N, int C, int H, int W, const uint64_t* Wp, int O,
+                           int KH, int KW, int stride, int pad, const float* alpha, const float* thr,
+                           uint64_t* out_xp, int out_pad, void* workspace, size_t workspace_bytes,
+                           void* stream) {
+  ConvGeom g;
+  const int rc = conv_check(N, C, H, W, O, KH, KW, stride, pad, &g);
+  if (rc != BMX_OK) return rc;
+  if (O <= 0) return BMX_ERR_SHAPE;
+  if (out_pad < 0 || out_pad > 6) return BMX_ERR_UNSUPPORTED;
+  if (N > 65535 || bmx::words_for(O) > 65535 ||
+      (int64_t)(g.Ho + 2 * out_pad) * (g.Wo + 2 * out_pad) >= ((int64_t)1 << 31))
+    return BMX_ERR_SHAPE;
+  if (N == 0) return BMX_OK;
+  if (!xp || !Wp || !out_xp) return BMX_ERR_NULL;
+  if (misaligned(xp, 8) || misaligned(Wp, 8) || misaligned(alpha, 4) || misaligned(thr, 4) ||
+      misaligned(out_xp, 8))
+    return BMX_ERR_ALIGN;
+  hipStream_t s = (hipStream_t)stream;
+  hipError_t err = hipSuccess;
+  if (bmx::launch_conv_mfma_ws(xp, N, C, H, W, Wp, O, KH, KW, stride, pad, alpha, nullptr, nullptr, out_xp, thr,
+                               out_pad, s, &err))
+    return hip_status(err);
+  // every other shape: the fp32 result through the workspace, then the channel pack with the
+  // same compare
+  const size_t need = round256((size_t)N * O * g.Ho * g.Wo * 4);
+  if (!workspace || workspace_bytes < need) return BMX_ERR_WORKSPACE;
+  if (misaligned(workspace, 16)) return BMX_ERR_ALIGN;
+  float* tmp = (float*)workspace;
+  err = bmx::launch_binary_conv2d(xp, N, C, H, W, Wp, O, KH, KW, stride, pad, alpha, nullptr, tmp, s);
+  if (err != hipSuccess) return BMX_ERR_HIP;
+  return hip_status(bmx::launch_pack_nchw_thr(tmp, N, O, g.Ho, g.Wo, out_pad, thr, out_xp, s));
 }
 
 int bmx_binary_conv2d(const float* x, int N, int C, int H, int W, const uint64_t* Wp, int O,

@@ -62,6 +62,9 @@ hipError_t launch_pack_strided(const float* x, int64_t batch, int64_t K, int64_t
                                int64_t batch_stride, uint64_t* out, int64_t out_ld, hipStream_t s);
 // NCHW channel pack into the halo-padded layout xp [N][H+2*pad][W+2*pad][Cw]; the halo is
 // filled with the word "all real channels = +1".
+// (thr: per-channel threshold the value is compared with, null = 0)
+hipError_t launch_pack_nchw_thr(const float* x, int N, int C, int H, int W, int pad, const float* thr,
+                                uint64_t* xp, hipStream_t s);
 hipError_t launch_pack_nchw(const float* x, int N, int C, int H, int W, int pad, uint64_t* xp,
                             hipStream_t s);
 hipError_t launch_pack_conv_weights(const float* w, int O, int C, int KH, int KW, uint64_t* Wp,
@@ -102,10 +105,15 @@ bool launch_conv_mfma(const uint64_t* Xp, int Nimg, int C, int H, int W, const u
                       int KW, int stride, int pad, const float* alpha, int32_t* out_i32, float* out_f32,
                       hipStream_t s, hipError_t* err);
 // conv_mfma.hip: the convolution on the FP4 matrix cores with the pre-expanded filters of a
-// workgroup in LDS (K of 9, 18 or 36 words).  Returns false outside its domain.
+// workgroup in LDS (K of 9, 18 or 36 words).  Returns false outside its domain.  With out_bits
+// the result leaves as the packed image of the next convolution (halo out_pad, written too):
+// bit o = (alpha[o] * dot >= thr[o]), thr null = 0.
+bool conv_mfma_ws_takes(int Nimg, int C, int H, int W, int O, int KH, int KW, int stride, int pad,
+                        int out_pad);  // its domain, the 16-byte alignment of Wp aside
 bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, const uint64_t* Wp, int O,
                          int KH, int KW, int stride, int pad, const float* alpha, int32_t* out_i32,
-                         float* out_f32, hipStream_t s, hipError_t* err);
+                         float* out_f32, uint64_t* out_bits, const float* thr, int out_pad, hipStream_t s,
+                         hipError_t* err);
 extern int gemm_engine, gemm_mfma_ksplit, gemm_mfma_tile, conv_filters_per_wave, conv_path;
 // S = 2*sum_p 2^p pc(plane_p & wb) - rowsum; out_f32 = float(S) / float(2^bits - 1).
 // planes_rows as written by launch_quant_pack (lda_dw dwords per row, chunk padded).

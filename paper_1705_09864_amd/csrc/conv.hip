@@ -287,7 +287,8 @@ hipError_t launch_binary_conv2d(const uint64_t* Xp, int N, int C, int H, int W, 
   // kernel (64 x 256 x 14 x 14 -> 256) and 8.2 against 8.6 us at stride 2.
   if ((conv_path == 5 || (conv_path == 0 && conv_weight_has_fp4(kwords))) && gemm_engine != 1) {
     hipError_t err = hipSuccess;
-    if (launch_conv_mfma_ws(Xp, N, C, H, W, Wp, O, KH, KW, stride, pad, alpha, out_i32, out_f32, s, &err))
+    if (launch_conv_mfma_ws(Xp, N, C, H, W, Wp, O, KH, KW, stride, pad, alpha, out_i32, out_f32, nullptr, nullptr, 0,
+                            s, &err))
       return err;
   }
   if (conv_path == 4 || (conv_path == 0 && (!stationary_ok || kwords >= 36))) {

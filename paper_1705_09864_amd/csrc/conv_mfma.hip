@@ -40,6 +40,11 @@ struct WsParams {
   const float* alpha;  // [O] or null
   int32_t* out_i32;
   float* out_f32;
+  // packed-bit output (the next convolution's input image): [Nimg][oHp][oWp][oCw] words seen as
+  // dwords, interior offset opad; bit = (alpha * dot >= thr)
+  uint32_t* out_bits;
+  const float* thr;  // [O] or null (= 0)
+  int Nimg, Ho, oHp, oWp, oCw, opad;
   int P;  // N * Ho * Wo
   int O, HoWo, Wo, Hp, Wpp, Cw, stride;
   int nblocks, nchunks;  // blocks of 32 pixels in all; waves they are dealt out to (evenly)
@@ -67,6 +72,7 @@ __device__ __forceinline__ v4i expand4(uint32_t w) {
 struct PixelBlock {
   const uint64_t* xb;  // base of the pixel's patch (tap (0, 0), channel word 0)
   int64_t obase;       // element index of (image, filter 0, pixel)
+  int64_t bword;       // packed-bit output: index of the pixel's first word
   bool valid;
 };
 
@@ -80,6 +86,7 @@ __device__ __forceinline__ PixelBlock locate(const WsParams& p, int b, int r) {
   const uint32_t wo = rem - ho * (uint32_t)p.Wo;
   pb.xb = p.Xp + (((int64_t)img * p.Hp + ho * p.stride) * p.Wpp + wo * p.stride) * p.Cw;
   pb.obase = (int64_t)img * p.O * p.HoWo + rem;
+  pb.bword = (((int64_t)img * p.oHp + ho + p.opad) * p.oWp + wo + p.opad) * p.oCw;
   pb.valid = n < p.P;
   return pb;
 }
@@ -100,7 +107,9 @@ struct Lds {
 };
 
 // WPS: waves per SIMD the register allocation is held to.
-template <int KW, int TM, int WPS>
+// BITS: the result leaves as packed sign bits (see WsParams::out_bits); the workgroups also
+// write the constant halo words of the output image.
+template <int KW, int TM, int WPS, bool BITS>
 __global__ void __launch_bounds__(256, WPS)
 conv_mfma_ws_kernel(const WsParams p) {
   constexpr int NI = (KW + 1) / 2;  // load instructions per block: two words per pixel each
@@ -139,6 +148,33 @@ conv_mfma_ws_kernel(const WsParams p) {
   uint64_t st[NI];
   fetch(cur, st);
 
+  // (behind the first fetch, so that its index arithmetic runs under the loads)
+  if (BITS && p.opad > 0 && (m0 & 63) == 0) {
+    // halo of the output image, word m0 / 64 of every halo pixel: every real channel +1 (the
+    // sign of the next layer's zero padding), missing channels 0; spread over the workgroups of
+    // this filter tile (left to one of them, its few thousand index computations set the
+    // duration of the whole launch)
+    const int cw = m0 >> 6;
+    const uint64_t ones = (cw == p.oCw - 1 && (p.O & 63)) ? (((uint64_t)1 << (p.O & 63)) - 1) : ~(uint64_t)0;
+    const int nh = p.oHp * p.oWp - p.HoWo;
+    uint64_t* ob = (uint64_t*)p.out_bits;
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < nh * p.Nimg; i += gridDim.x * 256) {
+      const int n = i / nh, k = i - n * nh;
+      int hh, ww;
+      if (k < 2 * p.opad * p.oWp) {  // rows above and below
+        hh = k / p.oWp;
+        ww = k - hh * p.oWp;
+        if (hh >= p.opad) hh += p.Ho;
+      } else {  // left and right of the interior rows
+        const int j = k - 2 * p.opad * p.oWp;
+        const int rr = j / (2 * p.opad), c = j - rr * (2 * p.opad);
+        hh = p.opad + rr;
+        ww = c < p.opad ? c : p.Wo + c;
+      }
+      ob[(((int64_t)n * p.oHp + hh) * p.oWp + ww) * p.oCw + cw] = ones;
+    }
+  }
+
   // ---- the workgroup's filters: 16-byte pieces, neighbouring threads on neighbouring pieces;
   // all of a thread's loads are issued before the first is written to LDS (one after the
   // other, every piece would cost a full memory round trip: 6 of 9 us at K = 36 words)
@@ -155,6 +191,8 @@ conv_mfma_ws_kernel(const WsParams p) {
     }
     float myalpha = 1.0f;  // thread t < 32 * TM carries alpha of row t
     if ((int)threadIdx.x < 32 * TM && p.alpha) myalpha = p.alpha[min(m0 + (int)threadIdx.x, p.O - 1)];
+    float mythr = 0.0f;
+    if (BITS && (int)threadIdx.x < 32 * TM && p.thr) mythr = p.thr[min(m0 + (int)threadIdx.x, p.O - 1)];
 #pragma unroll
     for (int t = 0; t < kCopies; ++t) {
       const int c = (int)threadIdx.x + 256 * t;
@@ -162,7 +200,10 @@ conv_mfma_ws_kernel(const WsParams p) {
       if (c < kPieces) *(v4i_alias*)(filt + row * FS + 4 * piece) = buf[t];
     }
     __syncthreads();
-    if ((int)threadIdx.x < 32 * TM) filt[(int)threadIdx.x * FS + 8 * KW + 1] = __float_as_uint(myalpha);
+    if ((int)threadIdx.x < 32 * TM) {
+      filt[(int)threadIdx.x * FS + 8 * KW + 1] = __float_as_uint(myalpha);
+      if (BITS) filt[(int)threadIdx.x * FS + 8 * KW + 2] = __float_as_uint(mythr);
+    }
   }
   __syncthreads();
   if (b0 >= b1) return;
@@ -214,7 +255,25 @@ conv_mfma_ws_kernel(const WsParams p) {
         c0[v] = __uint_as_float(filt[mi * FS + 8 * KW]);
         al[v] = __uint_as_float(filt[mi * FS + 8 * KW + 1]);
       }
-      if (p.out_i32) {
+      if constexpr (BITS) {
+        // bit o of the pixel's word: the IEEE compare of the fp32 product, as packing the fp32
+        // result would see it; the lane pair (r, 0), (r, 1) holds the 32 filters between them
+        uint32_t mask = 0;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int mi = 8 * (v / 4) + 4 * h + (v % 4);
+          const float th = __uint_as_float(filt[(32 * i + mi) * FS + 8 * KW + 2]);
+          const float t = fmaf(4.0f, acc[i][v], c0[v]) - pb2;
+          if (al[v] * t >= th && m0 + 32 * i + mi < p.O) mask |= 1u << mi;
+        }
+        mask |= (uint32_t)__shfl_xor((int)mask, 32);
+        const int mb = m0 + 32 * i;
+        if (h == 0 && cur.valid && mb < p.O) {
+          uint32_t* dst = p.out_bits + 2 * (cur.bword + (mb >> 6)) + ((mb >> 5) & 1);
+          dst[0] = mask;
+          if ((mb & 32) == 0 && mb + 32 >= p.O) dst[1] = 0;  // nobody else owns the upper half
+        }
+      } else if (p.out_i32) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int m = m0 + 32 * i + 8 * (v / 4) + 4 * h + (v % 4);
@@ -234,25 +293,41 @@ conv_mfma_ws_kernel(const WsParams p) {
   }
 }
 
-template <int KW, int TM, int WPS>
+template <int KW, int TM, int WPS, bool BITS = false>
 void launch_ws(const WsParams& p, int m_tiles, hipStream_t s) {
   const int chunks = p.nchunks;
-  hipLaunchKernelGGL((conv_mfma_ws_kernel<KW, TM, WPS>), dim3((unsigned)ceil_div(chunks, 4), (unsigned)m_tiles),
+  hipLaunchKernelGGL((conv_mfma_ws_kernel<KW, TM, WPS, BITS>), dim3((unsigned)ceil_div(chunks, 4), (unsigned)m_tiles),
                      dim3(256), 0, s, p);
 }
 
 }  // namespace
 
-bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, const uint64_t* Wp, int O,
-                         int KH, int KW, int stride, int pad, const float* alpha, int32_t* out_i32,
-                         float* out_f32, hipStream_t s, hipError_t* err) {
+bool conv_mfma_ws_takes(int Nimg, int C, int H, int W, int O, int KH, int KW, int stride, int pad,
+                        int out_pad) {
   const int Ho = (H + 2 * pad - KH) / stride + 1;
   const int Wo = (W + 2 * pad - KW) / stride + 1;
   const int Cw = (int)words_for(C);
   const int kwords = KH * KW * Cw;
-  if (!conv_weight_has_fp4(kwords) || ((uintptr_t)Wp & 15)) return false;
+  if (!conv_weight_has_fp4(kwords)) return false;
   const int64_t P = (int64_t)Nimg * Ho * Wo;
   if (P >= ((int64_t)1 << 31) || (int64_t)C * KH * KW >= ((int64_t)1 << 22)) return false;
+  if ((int64_t)Nimg * (Ho + 2 * out_pad) * (Wo + 2 * out_pad) >= ((int64_t)1 << 31)) return false;
+  if ((int64_t)(KH * (W + 2 * pad) + KW) * Cw >= ((int64_t)1 << 30)) return false;
+  return ceil_div(O, 32) <= 65535;
+}
+
+bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, const uint64_t* Wp, int O,
+                         int KH, int KW, int stride, int pad, const float* alpha, int32_t* out_i32,
+                         float* out_f32, uint64_t* out_bits, const float* thr, int out_pad, hipStream_t s,
+                         hipError_t* err) {
+  if (!conv_mfma_ws_takes(Nimg, C, H, W, O, KH, KW, stride, pad, out_bits ? out_pad : 0) ||
+      ((uintptr_t)Wp & 15))
+    return false;
+  const int Ho = (H + 2 * pad - KH) / stride + 1;
+  const int Wo = (W + 2 * pad - KW) / stride + 1;
+  const int Cw = (int)words_for(C);
+  const int kwords = KH * KW * Cw;
+  const int64_t P = (int64_t)Nimg * Ho * Wo;
   WsParams p;
   p.Xp = Xp;
   p.Wp = (const uint32_t*)Wp;
@@ -261,6 +336,14 @@ bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, cons
   p.alpha = alpha;
   p.out_i32 = out_i32;
   p.out_f32 = out_f32;
+  p.out_bits = (uint32_t*)out_bits;
+  p.thr = thr;
+  p.Nimg = Nimg;
+  p.Ho = Ho;
+  p.opad = out_pad;
+  p.oHp = Ho + 2 * out_pad;
+  p.oWp = Wo + 2 * out_pad;
+  p.oCw = (int)words_for(O);
   p.P = (int)P;
   p.O = O;
   p.HoWo = Ho * Wo;
@@ -271,7 +354,6 @@ bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, cons
   p.stride = stride;
   p.div_howo = make_fast_div((uint32_t)(Ho * Wo));
   p.div_wo = make_fast_div((uint32_t)Wo);
-  if ((int64_t)(KH * p.Wpp + KW) * Cw >= ((int64_t)1 << 30)) return false;
   for (int j = 0; j < kMaxWsWords; ++j) p.off[j] = 0;
   for (int kh = 0; kh < KH; ++kh)
     for (int kw = 0; kw < KW; ++kw)
@@ -279,9 +361,8 @@ bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, cons
   p.nblocks = (int)ceil_div(P, 32);
   // (64 filters per workgroup, two accumulator sets sharing every expanded pixel word, is kept
   // for measurements only: it lost to 32 everywhere, 8.0 against 7.2 us on 16 x 64 x 56 x 56)
-  const int TM = (kwords == 9 && O > 32 && gemm_mfma_tile == 2) ? 2 : 1;
+  const int TM = (kwords == 9 && O > 32 && gemm_mfma_tile == 2 && !out_bits) ? 2 : 1;
   const int m_tiles = (int)ceil_div(O, 32 * TM);
-  if (m_tiles > 65535) return false;
   // Waves: one per block while all of them are resident at once (4, 3 and 2 workgroups per CU
   // for 9, 18 and 36 words); beyond that, as many waves as are resident in one round,
   // the blocks dealt out evenly: every workgroup copies its filters once
@@ -291,7 +372,11 @@ bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, cons
   p.nchunks = (int)std::min<int64_t>(p.nblocks, std::max(1, resident_waves / m_tiles));
   if (conv_filters_per_wave >= 100) p.nchunks = std::min(p.nblocks, conv_filters_per_wave);  // (tuning hook reused: chunks)
   else if (conv_filters_per_wave > 0) p.nchunks = (int)ceil_div(p.nblocks, conv_filters_per_wave);  // (or blocks per wave)
-  if (kwords == 9) {
+  if (out_bits) {
+    if (kwords == 9) launch_ws<9, 1, 4, true>(p, m_tiles, s);
+    else if (kwords == 18) launch_ws<18, 1, 3, true>(p, m_tiles, s);
+    else launch_ws<36, 1, 2, true>(p, m_tiles, s);
+  } else if (kwords == 9) {
     if (TM == 2) launch_ws<9, 2, 2>(p, m_tiles, s);
     else launch_ws<9, 1, 4>(p, m_tiles, s);
   } else if (kwords == 18) {

@@ -160,9 +160,12 @@ hipError_t launch_pack_strided(const float* x, int64_t batch, int64_t K, int64_t
 // every (image, word) also writes the constant halo words.  The image is read exactly once, so
 // the loads are non-temporal (they do not displace what the convolution that follows needs:
 // 12.8 us against 13.4 us per configuration-2 layer with the input coming from HBM).
+// THR: bit = (value >= thr[channel]) instead of (value >= 0): the packing behind a layer whose
+// sign decision carries a folded per-channel threshold.
+template <bool THR>
 __global__ void __launch_bounds__(256)
 pack_nchw_kernel(const float* __restrict__ x, int C, int HW, int W, int pad, int Hp, int Wp, int Cw,
-                 uint64_t* __restrict__ xp) {
+                 const float* __restrict__ thr, uint64_t* __restrict__ xp) {
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int cw = blockIdx.y;
@@ -182,10 +185,18 @@ pack_nchw_kernel(const float* __restrict__ x, int C, int HW, int W, int pad, int
       for (int j = 0; j < 64; ++j) v[j] = (c0 + j < C) ? xb[(int64_t)j * HW] : -1.0f;
     }
     uint32_t lo = 0, hi = 0;
+    if constexpr (THR) {
+      // (missing channels hold -1 and compare against 0)
 #pragma unroll
-    for (int j = 0; j < 32; ++j) lo |= (v[j] >= 0.0f ? 1u : 0u) << j;
+      for (int j = 0; j < 32; ++j) lo |= (v[j] >= (c0 + j < C ? thr[c0 + j] : 0.0f) ? 1u : 0u) << j;
 #pragma unroll
-    for (int j = 0; j < 32; ++j) hi |= (v[32 + j] >= 0.0f ? 1u : 0u) << j;
+      for (int j = 0; j < 32; ++j) hi |= (v[32 + j] >= (c0 + 32 + j < C ? thr[c0 + 32 + j] : 0.0f) ? 1u : 0u) << j;
+    } else {
+#pragma unroll
+      for (int j = 0; j < 32; ++j) lo |= (v[j] >= 0.0f ? 1u : 0u) << j;
+#pragma unroll
+      for (int j = 0; j < 32; ++j) hi |= (v[32 + j] >= 0.0f ? 1u : 0u) << j;
+    }
     if (p < HW) {
       const int h = p / W, w = p - h * W;
       xpn[((int64_t)(h + pad) * Wp + (w + pad)) * Cw + cw] = ((uint64_t)hi << 32) | lo;
@@ -216,14 +227,23 @@ pack_nchw_kernel(const float* __restrict__ x, int C, int HW, int W, int pad, int
   }
 }
 
-hipError_t launch_pack_nchw(const float* x, int N, int C, int H, int W, int pad, uint64_t* xp,
-                            hipStream_t s) {
+hipError_t launch_pack_nchw_thr(const float* x, int N, int C, int H, int W, int pad, const float* thr,
+                                uint64_t* xp, hipStream_t s) {
   const int Cw = (int)words_for(C);
   const int HW = H * W;
   dim3 grid((unsigned)ceil_div(HW, 256), (unsigned)Cw, (unsigned)N);
-  hipLaunchKernelGGL(pack_nchw_kernel, grid, dim3(256), 0, s, x, C, HW, W, pad, H + 2 * pad,
-                     W + 2 * pad, Cw, xp);
+  if (thr)
+    hipLaunchKernelGGL(pack_nchw_kernel<true>, grid, dim3(256), 0, s, x, C, HW, W, pad, H + 2 * pad,
+                       W + 2 * pad, Cw, thr, xp);
+  else
+    hipLaunchKernelGGL(pack_nchw_kernel<false>, grid, dim3(256), 0, s, x, C, HW, W, pad, H + 2 * pad,
+                       W + 2 * pad, Cw, thr, xp);
   return hipGetLastError();
+}
+
+hipError_t launch_pack_nchw(const float* x, int N, int C, int H, int W, int pad, uint64_t* xp,
+                            hipStream_t s) {
+  return launch_pack_nchw_thr(x, N, C, H, W, pad, nullptr, xp, s);
 }
 
 // Offline weight packing for the convolution: one thread per word of the bit section.

@@ -41,6 +41,14 @@ def test_workspace_query():
     assert B.workspace_bytes(B.OP_QUANT_GEMM, (4, 4, 64, 9, 1)) == 0      # bits_a out of range
     assert B.workspace_bytes(B.OP_QUANT_GEMM, (4, 4, 64, 2, 2)) == 0      # k-bit weights unsupported
     assert B.workspace_bytes(B.OP_BINARY_CONV2D, (1, 3, 8, 8, 2, 4, 4, 1, 0)) == 0  # even kernel
+    # packed-bit convolution: nothing where the convolution kernel writes the bits itself (3 x 3
+    # over at most 256 channels), else the fp32 result of the two-kernel route
+    assert B.workspace_bytes(B.OP_BINARY_CONV2D_BITS, (16, 64, 56, 56, 64, 3, 3, 1, 1, 1)) == 0
+    assert B.workspace_bytes(B.OP_BINARY_CONV2D_BITS, (2, 256, 14, 14, 40, 3, 3, 2, 1, 0)) == 0
+    assert B.workspace_bytes(B.OP_BINARY_CONV2D_BITS, (2, 64, 8, 8, 5, 5, 5, 1, 2, 1)) == 2 * 5 * 8 * 8 * 4
+    assert B.workspace_bytes(B.OP_BINARY_CONV2D_BITS, (2, 300, 8, 8, 5, 3, 3, 1, 1, 1)) == 2 * 5 * 8 * 8 * 4
+    assert B.workspace_bytes(B.OP_BINARY_CONV2D_BITS, (2, 64, 8, 8, 5, 3, 3, 1, 1, 7)) == 0   # out_pad out of range
+    assert B.workspace_bytes(B.OP_BINARY_CONV2D_BITS, (2, 64, 8, 8, 5, 3, 3, 1, 1)) == 0      # too few dims
     assert B.workspace_bytes(99, (1, 2, 3)) == 0
     assert B.workspace_bytes(B.OP_BINARY_FC, (1, 2)) == 0
 
@@ -119,6 +127,31 @@ def test_conv_validation():
     assert g(P, 4, 3, 3, 3, NULL, NULL) == E_NULL
     assert g(P, 4, 3, 2, 2, P, NULL) == E_UNSUP
     assert g(P, 0, 3, 3, 3, P, NULL) == OK
+
+
+def test_conv_bits_validation():
+    f = B.lib().bmx_binary_conv2d_bits
+    big = 1 << 24
+    args = dict(N=2, C=3, H=8, W=8, O=4, KH=5, KW=5, s=1, p=1, op=1)
+
+    def call(xp=P, Wp=P, alpha=NULL, thr=NULL, out=P, ws=P, wsb=big, **kw):
+        a = dict(args, **kw)
+        return f(xp, a["N"], a["C"], a["H"], a["W"], Wp, a["O"], a["KH"], a["KW"], a["s"], a["p"],
+                 alpha, thr, out, a["op"], ws, wsb, NULL)
+
+    assert call(KH=4, KW=4) == E_UNSUP
+    assert call(s=3) == E_UNSUP
+    assert call(op=-1) == E_UNSUP
+    assert call(op=7) == E_UNSUP
+    assert call(C=0) == E_SHAPE
+    assert call(O=0) == E_SHAPE
+    assert call(xp=NULL) == E_NULL
+    assert call(Wp=NULL) == E_NULL
+    assert call(out=NULL) == E_NULL
+    assert call(N=0) == OK
+    # a 5 x 5 kernel goes through the fp32 result: the workspace is checked before any launch
+    assert call(ws=NULL) == E_WS
+    assert call(wsb=64) == E_WS
 
 
 def test_quant_and_alpha_validation():

@@ -592,3 +592,76 @@ def test_fc_packed_bits_ragged(batch, fin, fout, engine):
         np.testing.assert_array_equal(host_u64(nob), oracle.binarize_pack(ri.astype(np.float32), 1))
     finally:
         L.bmx_tune_set(7, 0)
+
+
+# ------------------------------------------------------------------ convolutions chained on packed images
+def packed_image(bits_nchw, out_pad):
+    """[N, O, Ho, Wo] booleans -> the packed image bmx_pack_nchw would hand the next layer:
+    [N, Ho + 2*out_pad, Wo + 2*out_pad, ceil(O/64)] words, halo = every real channel set."""
+    N, O, Ho, Wo = bits_nchw.shape
+    rows = np.where(bits_nchw.transpose(0, 2, 3, 1).reshape(-1, O), 1.0, -1.0).astype(np.float32)
+    words = oracle.binarize_pack(rows, 1)
+    halo = oracle.binarize_pack(np.ones((1, O), dtype=np.float32), 1)[0]
+    img = np.empty((N, Ho + 2 * out_pad, Wo + 2 * out_pad, words.shape[1]), dtype=np.uint64)
+    img[:] = halo
+    img[:, out_pad:out_pad + Ho, out_pad:out_pad + Wo, :] = words.reshape(N, Ho, Wo, -1)
+    return img
+
+
+CONV_BITS_CASES = [c + (op,) for c, op in zip(
+    [(N, C, H, W, O, 3, s, p) for (N, C, H, W, O, s, p) in WS_CONV_CASES] + CONV_CASES,
+    [1, 0, 2, 1, 3, 1, 0, 1, 2, 1, 1, 6] + [1, 0, 1, 2, 1, 0, 1, 1, 3, 1, 1, 0, 2])]
+
+
+@pytest.mark.parametrize("N,C,H,W,O,k,s,p,out_pad", CONV_BITS_CASES)
+def test_conv_packed_bits(N, C, H, W, O, k, s, p, out_pad):
+    """The convolution that hands the next one its packed image: bit o of a pixel is the fp32
+    compare (alpha * dot >= thr), thr folded from a BatchNorm or absent, scales of either sign
+    and zero; the halo carries the +1 of the next layer's zero padding; the image is written
+    whole (poisoned beforehand).  3 x 3 kernels over up to 256 channels take the kernel that
+    writes the bits itself, the rest go through the fp32 result and the channel pack."""
+    rng = np.random.default_rng(7 + N + 10 * C + 100 * H + 1000 * O + k + s + p)
+    x = rng.standard_normal((N, C, H, W)).astype(np.float32)
+    w = rng.standard_normal((O, C, k, k)).astype(np.float32)
+    alpha = rng.standard_normal(O).astype(np.float32)
+    alpha[::5] = 0.0
+    thr = (rng.standard_normal(O) * np.sqrt(C * k * k)).astype(np.float32)
+    thr[1::4] = 0.0
+    ri, rf = oracle.binary_conv2d(x, w, s, p, alpha)
+    Ho, Wo = ri.shape[2:]
+    Wp = B.pack_conv_weights(dev(w))
+    xp = B.pack_nchw(dev(x), p)
+    shape = (N, Ho + 2 * out_pad, Wo + 2 * out_pad, (O + 63) // 64)
+    for al, th, ref in ((alpha, thr, rf >= thr[None, :, None, None]),
+                        (alpha, None, rf >= 0.0),
+                        (None, thr, ri.astype(np.float32) >= thr[None, :, None, None]),
+                        (None, None, ri >= 0)):
+        out = dev(np.full(shape, -1, dtype=np.int64))
+        B.binary_conv2d_bits(xp, C, Wp, O, k, k, s, p, alpha=None if al is None else dev(al),
+                             thr=None if th is None else dev(th), out_pad=out_pad, out=out)
+        np.testing.assert_array_equal(host_u64(out), packed_image(ref, out_pad))
+
+
+@pytest.mark.parametrize("N,C,H,W,O1,O2,s1", [(2, 64, 20, 20, 64, 48, 1), (3, 100, 17, 13, 130, 70, 2),
+                                               (16, 64, 56, 56, 64, 64, 1)])
+def test_conv_chain_on_packed_images(N, C, H, W, O1, O2, s1):
+    """Two binary blocks chained without an fp32 feature map in between: the second layer reads
+    the image the first wrote, and matches the oracle run on the +-1 feature map (zero padded
+    before the sign, like every layer input)."""
+    rng = np.random.default_rng(N + C + H + O1 + O2)
+    x = rng.standard_normal((N, C, H, W)).astype(np.float32)
+    w1 = rng.standard_normal((O1, C, 3, 3)).astype(np.float32)
+    w2 = rng.standard_normal((O2, O1, 3, 3)).astype(np.float32)
+    a1, a2 = oracle.alpha_mean_abs(w1), oracle.alpha_mean_abs(w2)
+    thr = (rng.standard_normal(O1) * 5.0).astype(np.float32)
+    _, r1 = oracle.binary_conv2d(x, w1, s1, 1, a1)
+    h1 = np.where(r1 >= thr[None, :, None, None], 1.0, -1.0).astype(np.float32)
+    r2i, r2f = oracle.binary_conv2d(h1, w2, 1, 1, a2)
+    W1p, W2p = B.pack_conv_weights(dev(w1)), B.pack_conv_weights(dev(w2))
+    xp = B.pack_nchw(dev(x), 1)
+    img = B.binary_conv2d_bits(xp, C, W1p, O1, 3, 3, s1, 1, alpha=dev(a1), thr=dev(thr), out_pad=1)
+    np.testing.assert_array_equal(host_u64(img), packed_image(h1 > 0, 1))
+    got = B.binary_conv2d_packed(img, O1, W2p, O2, 3, 3, 1, 1, alpha=dev(a2))
+    assert_f32_close(got.cpu().numpy(), r2f)
+    goti = B.binary_conv2d_packed(img, O1, W2p, O2, 3, 3, 1, 1, integer_out=True)
+    np.testing.assert_array_equal(goti.cpu().numpy(), r2i)
