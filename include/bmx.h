@@ -101,12 +101,15 @@ int bmx_binary_fc(const float* x, int64_t ldx, const uint64_t* Wp, int64_t ldw_w
  *   exactly one of out_i32 / out_f32 / out_bits is non-NULL:
  *     out_i32 [batch, ldo] = dot (alpha must be NULL);  out_f32 [batch, ldo] = alpha[o]*(float)dot;
  *     out_bits uint64 [batch, ldo] (ldo in words, >= ceil(out_features/64)): bit o of row b is
- *     (alpha[o] * (float)dot >= 0.0f), i.e. exactly what bmx_binarize_pack makes of the out_f32
- *     result (sign(0) = +1), unused tail bits 0. */
+ *     (alpha[o] * (float)dot >= thr[o]), the IEEE compare of the fp32 product; with thr NULL
+ *     (= 0) exactly what bmx_binarize_pack makes of the out_f32 result (sign(0) = +1); unused
+ *     tail bits 0.
+ *   thr      fp32 [out_features] or NULL, with out_bits only: the threshold a BatchNorm behind
+ *            the layer folds into (see bmx_binary_conv2d_bits). */
 int bmx_binary_fc_packed(const uint64_t* xp, int64_t ldx_w, const uint64_t* Wp, int64_t ldw_w,
                          const float* alpha, int batch, int in_features, int out_features,
-                         int32_t* out_i32, float* out_f32, uint64_t* out_bits, int64_t ldo,
-                         void* stream);
+                         int32_t* out_i32, float* out_f32, uint64_t* out_bits, const float* thr,
+                         int64_t ldo, void* stream);
 
 /* Pack OIHW fp32 convolution weights for bmx_binary_conv2d (the offline weight packing
  * of Sec. 2.2.3).  Wp is a matrix of O rows of bmx_conv_weight_row_words(C, KH, KW) words:

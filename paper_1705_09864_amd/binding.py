@@ -53,7 +53,7 @@ def lib():
         L.bmx_status_string.argtypes = [_int]
         L.bmx_status_string.restype = ctypes.c_char_p
         L.bmx_version.restype = _int
-        L.bmx_binary_fc_packed.argtypes = [_p, _i64, _p, _i64, _p, _int, _int, _int, _p, _p, _p, _i64, _p]
+        L.bmx_binary_fc_packed.argtypes = [_p, _i64, _p, _i64, _p, _int, _int, _int, _p, _p, _p, _p, _i64, _p]
         L.bmx_binary_fc_packed.restype = _int
         L.bmx_conv_weight_row_words.argtypes = [_int, _int, _int]
         L.bmx_conv_weight_row_words.restype = _i64
@@ -147,8 +147,9 @@ def binary_fc(x, Wp, alpha=None, integer_out=False, out=None, workspace=None, st
     return out
 
 
-def binary_fc_packed(xp, in_features, Wp, alpha=None, mode="f32", out=None, stream=None):
-    """xp: packed activations [batch, words].  mode: "f32", "i32" or "bits" (packed sign bits)."""
+def binary_fc_packed(xp, in_features, Wp, alpha=None, mode="f32", out=None, thr=None, stream=None):
+    """xp: packed activations [batch, words].  mode: "f32", "i32" or "bits" (packed sign bits,
+    against the per-feature threshold thr if given)."""
     batch, fout = xp.shape[0], Wp.shape[0]
     if out is None:
         if mode == "bits":
@@ -159,7 +160,7 @@ def binary_fc_packed(xp, in_features, Wp, alpha=None, mode="f32", out=None, stre
     oi, of, ob = (out if mode == "i32" else None, out if mode == "f32" else None,
                   out if mode == "bits" else None)
     _check(lib().bmx_binary_fc_packed(_ptr(xp), xp.shape[1], _ptr(Wp), Wp.shape[1], _ptr(alpha), batch,
-                                      in_features, fout, _ptr(oi), _ptr(of), _ptr(ob),
+                                      in_features, fout, _ptr(oi), _ptr(of), _ptr(ob), _ptr(thr),
                                       max(out.shape[1], 1), _stream(stream)), "bmx_binary_fc_packed")
     return out
 

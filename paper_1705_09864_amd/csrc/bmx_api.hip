@@ -152,7 +152,7 @@ int bmx_xnor_gemm(const uint64_t* A, int64_t lda_w, const uint64_t* B, int64_t l
   if (lda_w < Kw || ldb_w < Kw || ldc < N) return BMX_ERR_LD;
   if (misaligned(A, 8) || misaligned(B, 8) || misaligned(C, 4)) return BMX_ERR_ALIGN;
   return hip_status(bmx::launch_xnor_gemm((const uint32_t*)A, false, lda_w * 2, B, ldb_w, M, N, K,
-                                          nullptr, C, nullptr, nullptr, ldc, (hipStream_t)stream));
+                                          nullptr, C, nullptr, nullptr, nullptr, ldc, (hipStream_t)stream));
 }
 
 int bmx_binary_fc(const float* x, int64_t ldx, const uint64_t* Wp, int64_t ldw_w,
@@ -182,28 +182,29 @@ int bmx_binary_fc(const float* x, int64_t ldx, const uint64_t* Wp, int64_t ldw_w
   if (e != hipSuccess) return BMX_ERR_HIP;
   return hip_status(bmx::launch_xnor_gemm((const uint32_t*)xp, true, ldp * 2, Wp, ldw_w, batch,
                                           out_features, in_features, alpha, out_i32, out_f32,
-                                          nullptr, ldo, s));
+                                          nullptr, nullptr, ldo, s));
 }
 
 int bmx_binary_fc_packed(const uint64_t* xp, int64_t ldx_w, const uint64_t* Wp, int64_t ldw_w,
                          const float* alpha, int batch, int in_features, int out_features,
-                         int32_t* out_i32, float* out_f32, uint64_t* out_bits, int64_t ldo,
-                         void* stream) {
+                         int32_t* out_i32, float* out_f32, uint64_t* out_bits, const float* thr,
+                         int64_t ldo, void* stream) {
   if (batch < 0 || out_features < 0) return BMX_ERR_SHAPE;
   if (in_features <= 0 || in_features >= kMaxK) return BMX_ERR_SHAPE;
   if (batch == 0 || out_features == 0) return BMX_OK;
   if (!xp || !Wp) return BMX_ERR_NULL;
   if ((out_i32 != nullptr) + (out_f32 != nullptr) + (out_bits != nullptr) != 1) return BMX_ERR_NULL;
   if (out_i32 && alpha) return BMX_ERR_UNSUPPORTED;
+  if (thr && !out_bits) return BMX_ERR_UNSUPPORTED;
   const int64_t Kw = bmx::words_for(in_features);
   if (ldx_w < Kw || ldw_w < Kw) return BMX_ERR_LD;
   if (ldo < (out_bits ? bmx::words_for(out_features) : (int64_t)out_features)) return BMX_ERR_LD;
   if (misaligned(xp, 8) || misaligned(Wp, 8) || misaligned(alpha, 4) || misaligned(out_i32, 4) ||
-      misaligned(out_f32, 4) || misaligned(out_bits, 8))
+      misaligned(out_f32, 4) || misaligned(out_bits, 8) || misaligned(thr, 4))
     return BMX_ERR_ALIGN;
   return hip_status(bmx::launch_xnor_gemm((const uint32_t*)xp, false, ldx_w * 2, Wp, ldw_w, batch,
                                           out_features, in_features, alpha, out_i32, out_f32,
-                                          out_bits, ldo, (hipStream_t)stream));
+                                          out_bits, thr, ldo, (hipStream_t)stream));
 }
 
 int64_t bmx_conv_weight_row_words(int C, int KH, int KW) {

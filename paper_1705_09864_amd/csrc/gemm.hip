@@ -63,6 +63,7 @@ struct GemmParams {
   int Kreal;              // K in bits (xor modes)
   const int32_t* rowsum;  // planes mode: sum_k q[m][k]
   const float* alpha;     // GEMM: per column n.  Convolution: per row (filter) m
+  const float* thr;       // kGemmBits: per column n threshold of the sign decision, or null (0)
   float levels;           // planes mode: 2^bits - 1
   int32_t* C_i32;
   float* C_f32;
@@ -286,6 +287,8 @@ gemm_kernel(const GemmParams p) {
   // after the other.
   float al = 1.0f;
   if (!CONV && (p.out == kGemmF32Alpha || p.out == kGemmBits) && p.alpha) al = p.alpha[nc];
+  float th = 0.0f;
+  if (!CONV && p.out == kGemmBits && p.thr) th = p.thr[nc];
   const int rows_out = rows_valid / p.planes;
   const int64_t mbase = m0 / p.planes;
   float row_alpha = 1.0f;
@@ -295,8 +298,8 @@ gemm_kernel(const GemmParams p) {
   auto finish = [&](int lr, int total) {  // count of the block's output row lr -> C[m][n]
     const int64_t m = mbase + lr;
     if (p.out == kGemmBits) {
-      // the 64-lane mask of (scaled result >= 0) is the packed word of columns n0 .. n0+63
-      const uint64_t word = __ballot(n < p.N && al * (float)(p.Kreal - 2 * total) >= 0.0f);
+      // the 64-lane mask of (scaled result >= threshold) is the packed word of columns n0 .. n0+63
+      const uint64_t word = __ballot(n < p.N && al * (float)(p.Kreal - 2 * total) >= th);
       if (lane == 0) p.C_bits[m * p.ldc + cb] = word;
     } else if (p.out == kGemmPlanes) {
       const int sv = 2 * total - __builtin_amdgcn_readlane(row_sum, lr);
@@ -449,11 +452,11 @@ void no_conv(GemmParams& p) {
 
 hipError_t launch_xnor_gemm(const uint32_t* A, bool a_padded, int64_t lda_dw, const uint64_t* B,
                             int64_t ldb_w, int M, int N, int K, const float* alpha_n, int32_t* C_i32,
-                            float* C_f32, uint64_t* C_bits, int64_t ldc, hipStream_t s) {
+                            float* C_f32, uint64_t* C_bits, const float* thr_n, int64_t ldc, hipStream_t s) {
   if ((lda_dw & 1) == 0) {
     hipError_t err = hipSuccess;
     if (launch_xnor_gemm_mfma((const uint64_t*)A, lda_dw / 2, B, ldb_w, M, N, K, alpha_n, C_i32, C_f32,
-                              C_bits, ldc, s, &err))
+                              C_bits, thr_n, ldc, s, &err))
       return err;
   }
   GemmParams p;
@@ -473,6 +476,7 @@ hipError_t launch_xnor_gemm(const uint32_t* A, bool a_padded, int64_t lda_dw, co
   p.C_i32 = C_i32;
   p.C_f32 = C_f32;
   p.C_bits = C_bits;
+  p.thr = thr_n;
   p.ldc = ldc;
   p.out = C_bits ? kGemmBits : (C_i32 ? kGemmI32 : (alpha_n ? kGemmF32Alpha : kGemmF32));
   if (a_padded) {  // A rows are zero padded to whole chunks: everything runs in the main loop
@@ -515,6 +519,7 @@ hipError_t launch_plane_gemm(const uint32_t* planes_rows, int64_t lda_dw, int bi
   p.C_i32 = S;
   p.C_f32 = out_f32;
   p.C_bits = nullptr;
+  p.thr = nullptr;
   p.ldc = ldo;
   p.out = kGemmPlanes;
   launch<true>(p, s);
@@ -548,6 +553,7 @@ hipError_t launch_conv_gemm(const uint64_t* Xp, int Nimg, int C, int H, int W, c
   p.C_i32 = out_i32;
   p.C_f32 = out_f32;
   p.C_bits = nullptr;
+  p.thr = nullptr;
   p.ldc = (int64_t)Ho * Wo;
   p.out = out_i32 ? kGemmI32 : (alpha ? kGemmF32Alpha : kGemmF32);
   p.HoWo = Ho * Wo;

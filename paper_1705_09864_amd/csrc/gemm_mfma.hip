@@ -56,6 +56,7 @@ struct MfmaParams {
   int tail_half;        // words per half-wave in the last macro step (8 when it is whole)
   int tiles_n;
   const float* alpha;  // per column n, or null
+  const float* thr;    // packed-bit output: per column n threshold of the sign decision, or null (0)
   const int32_t* rowsum;  // plane mode: sum_k q[m][k]
   float levels;           // plane mode: 2^bits - 1
   // convolution mode: B is the packed image, column n is output pixel n (flat over images)
@@ -294,6 +295,10 @@ gemm_mfma_kernel(const MfmaParams p) {
 #pragma unroll
   for (int j = 0; j < TN; ++j)
     aln[j] = (XNOR && !CONV && p.alpha) ? p.alpha[min(n0 + 32 * j + (lane & 31), p.N - 1)] : 1.0f;
+  float thn[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+    thn[j] = (XNOR && !CONV && p.C_bits && p.thr) ? p.thr[min(n0 + 32 * j + (lane & 31), p.N - 1)] : 0.0f;
   if (wave == 0 && (CONV || !XNOR)) {
     for (int i = lane; i < 32 * TM; i += 64) {
       const int m = min(m0 + i, p.M - 1);
@@ -414,7 +419,8 @@ gemm_mfma_kernel(const MfmaParams p) {
     if (p.C_bits) {
       // the 64-lane mask of (scaled result >= 0): its low half is 32 columns of row m as seen
       // by lanes 0..31, its high half the same columns of the row four below
-      const uint64_t mask = __ballot(n < p.N && al * (float)dot >= 0.0f);
+      const float th = (TN > 1 && j == 1) ? thn[TN - 1] : thn[0];
+      const uint64_t mask = __ballot(n < p.N && al * (float)dot >= th);
       if (r == 0 && m < p.M)
         p.C_bits[(int64_t)m * (2 * p.ldc) + (n >> 5)] = h ? (uint32_t)(mask >> 32) : (uint32_t)mask;
     } else if (m < p.M && n < p.N) {
@@ -516,7 +522,7 @@ int choose_split(int64_t tiles, int nsteps) {
 
 bool launch_xnor_gemm_mfma(const uint64_t* A, int64_t lda_w, const uint64_t* B, int64_t ldb_w, int M,
                            int N, int K, const float* alpha_n, int32_t* C_i32, float* C_f32,
-                           uint64_t* C_bits, int64_t ldc, hipStream_t s, hipError_t* err) {
+                           uint64_t* C_bits, const float* thr_n, int64_t ldc, hipStream_t s, hipError_t* err) {
   if (gemm_engine == 1) return false;
   // 16-byte row pieces are loaded as one vector: rows must start 16-byte aligned
   if ((lda_w & 1) || (ldb_w & 1) || ((uintptr_t)A & 15) || ((uintptr_t)B & 15)) return false;
@@ -534,6 +540,7 @@ bool launch_xnor_gemm_mfma(const uint64_t* A, int64_t lda_w, const uint64_t* B, 
   p.C_i32 = C_i32;
   p.C_f32 = C_f32;
   p.C_bits = (uint32_t*)C_bits;
+  p.thr = thr_n;
   p.ldc = ldc;
   // 64 x 64 per wave; 32 x 32 when that grid has fewer than two tiles per CU (measured:
   // 256 x 4096 x 4096 8.7 against 9.5 us, 1024^3 6.0 against 8.1 us)
@@ -574,6 +581,7 @@ bool launch_plane_gemm_mfma(const uint64_t* planes_rows, int64_t lda_w, int bits
   p.C_i32 = S_out;
   p.C_f32 = out_f32;
   p.C_bits = nullptr;
+  p.thr = nullptr;
   p.ldc = ldo;
   // 32 rows x 64 columns per wave: the two planes of a row double the A registers
   const int tiles_m = (int)ceil_div(M, 32);
@@ -620,6 +628,7 @@ bool launch_conv_mfma(const uint64_t* Xp, int Nimg, int C, int H, int W, const u
   p.C_i32 = out_i32;
   p.C_f32 = out_f32;
   p.C_bits = nullptr;
+  p.thr = nullptr;
   p.ldc = 0;
   p.HoWo = Ho * Wo;
   p.Wo = Wo;

@@ -173,14 +173,17 @@ def test_quant_and_alpha_validation():
 
 def test_fc_packed_validation():
     f = B.lib().bmx_binary_fc_packed
-    ok = dict(xp=P, ldx=8, Wp=P, ldw=8, alpha=NULL, b=4, fin=512, fout=70, oi=NULL, of=NULL, ob=P, ldo=2)
+    ok = dict(xp=P, ldx=8, Wp=P, ldw=8, alpha=NULL, b=4, fin=512, fout=70, oi=NULL, of=NULL, ob=P, thr=NULL,
+              ldo=2)
 
     def call(**kw):
         a = dict(ok, **kw)
         return f(a["xp"], a["ldx"], a["Wp"], a["ldw"], a["alpha"], a["b"], a["fin"], a["fout"], a["oi"],
-                 a["of"], a["ob"], a["ldo"], NULL)
+                 a["of"], a["ob"], a["thr"], a["ldo"], NULL)
 
     assert call(b=0) == OK and call(fout=0) == OK                       # empty: no launch
+    assert call(ob=NULL, of=P, ldo=70, thr=P) == E_UNSUP                # a threshold decides bits only
+    assert call(thr=P + 2) == E_ALIGN
     assert call(b=-1) == E_SHAPE and call(fin=0) == E_SHAPE
     assert call(xp=NULL) == E_NULL and call(Wp=NULL) == E_NULL
     assert call(ob=NULL) == E_NULL                                      # no output at all

@@ -590,6 +590,12 @@ def test_fc_packed_bits_ragged(batch, fin, fout, engine):
         nob = B.binary_fc_packed(Xp, fin, Wp, mode="bits")                       # no scale: sign of dot
         ri, _ = oracle.binary_fc(x, w)
         np.testing.assert_array_equal(host_u64(nob), oracle.binarize_pack(ri.astype(np.float32), 1))
+        # a folded BatchNorm threshold per feature: bit = (alpha * dot >= thr) in fp32
+        thr = (rng.standard_normal(fout) * np.sqrt(fin)).astype(np.float32)
+        thr[1::4] = 0.0
+        tb = B.binary_fc_packed(Xp, fin, Wp, alpha=dev(alpha), mode="bits", thr=dev(thr))
+        want = np.where(rf >= thr[None, :], 1.0, -1.0).astype(np.float32)
+        np.testing.assert_array_equal(host_u64(tb), oracle.binarize_pack(want, 1))
     finally:
         L.bmx_tune_set(7, 0)
 

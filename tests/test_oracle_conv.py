@@ -99,3 +99,24 @@ def test_conv_single_weight_flip_moves_output_by_two():
     got, _ = oracle.binary_conv2d(x, w, 1, 0)
     np.testing.assert_array_equal(got[0, 0], base[0, 0])
     np.testing.assert_array_equal(got[0, 1], base[0, 1] - 2)
+
+
+def test_batchnorm_folds_into_a_threshold():
+    """The block of Sec. 2 ends QConvolution -> BatchNorm, and the next block starts with the
+    sign: sign(gamma * (v - mean) / sigma + beta) is the compare v >= mean - beta * sigma / gamma
+    for gamma > 0 (negated operands for gamma < 0).  Checked on every value a layer of K = 18
+    can produce (v = alpha * dot, dot in -K .. K step 2), in exact rational arithmetic away from
+    the tie, so that the threshold form the bit-output entry points take is the BatchNorm."""
+    from fractions import Fraction as F
+    K = 18
+    for alpha, gamma, beta, mean, sigma in [(F(1, 2), F(3, 2), F(-1, 4), F(5, 8), F(7, 4)),
+                                            (F(3, 4), F(-2), F(1, 3), F(-1, 2), F(5, 4)),
+                                            (F(1), F(1, 7), F(0), F(0), F(1))]:
+        thr = mean - beta * sigma / gamma
+        for dot in range(-K, K + 1, 2):
+            v = alpha * dot
+            bn = gamma * (v - mean) / sigma + beta
+            if gamma > 0:
+                assert (bn >= 0) == (v >= thr)
+            elif bn != 0:  # gamma < 0: alpha and thr negated (the tie itself flips sides)
+                assert (bn >= 0) == (-alpha * dot >= -thr)
