@@ -48,6 +48,30 @@ def check_scalar_loads():
             raise RuntimeError("in-flight scalar load hazard in %s:\n%s" % (src, isa_check.report(bad)))
 
 
+def check_codegen():
+    """Two properties of the generated code that a harmless-looking source change can lose
+    without any test failing, only the clock: no kernel spills vector registers (the 64 x 64
+    matrix-core GEMM tile aside, which parks a dozen loop-invariant values), and the
+    convolution kernel with its filters in LDS reads each MFMA's filter operand with one
+    ds_read_b128 (split into dword pairs, the rows meet four ways on the banks)."""
+    import re
+    try:
+        from . import isa_check
+    except ImportError:
+        sys.path.insert(0, HERE)
+        import isa_check
+    for src in SOURCES:
+        for name, (spills, ops) in isa_check.kernel_stats(device_asm(src)).items():
+            allowed = 16 if "gemm_mfma_kernelILi2ELi2E" in name else 0
+            if spills > allowed:
+                raise RuntimeError("%s: kernel %s spills %d vector registers" % (src, name, spills))
+            m = re.search(r"conv_mfma_ws_kernelILi(\d+)ELi(\d+)E", name)
+            if m and ops["ds_read_b128"] < int(m.group(1)) * int(m.group(2)):
+                raise RuntimeError("%s: kernel %s reads its filter operands with %d ds_read_b128, "
+                                   "expected %d" % (src, name, ops["ds_read_b128"],
+                                                    int(m.group(1)) * int(m.group(2))))
+
+
 def build(force=True, verbose=False):
     """Compile every translation unit, verify the hand-placed scalar loads in the generated
     code, and link the shared library.  Returns its path."""
@@ -73,6 +97,7 @@ def build(force=True, verbose=False):
     with ThreadPoolExecutor(max_workers=min(4, len(SOURCES))) as ex:
         objs = list(ex.map(compile_one, SOURCES))
     check_scalar_loads()
+    check_codegen()
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB]
     subprocess.check_call(cmd)
     return LIB

@@ -77,3 +77,32 @@ if __name__ == "__main__":
     for k, ln, t, what, rr, l0 in bad[:40]:
         print(f"{k}: line {ln}: '{t}' {what} SGPR {rr} of the load issued at line {l0}")
     print("violations:", len(bad))
+
+
+def kernel_stats(path):
+    """Per kernel of a device listing: VGPR spill count from the metadata and how often each
+    instruction mnemonic occurs in its body.  Returns {mangled name: (spills, {mnemonic: n})}."""
+    import collections
+    import re
+    body = {}
+    name = None
+    spills = {}
+    cur_meta = None
+    for ln in open(path):
+        m = re.match(r"^(_Z\w+):", ln)
+        if m:
+            name = m.group(1)
+            body[name] = collections.Counter()
+            continue
+        t = ln.strip()
+        if name and t and not t.startswith((";", ".", "_Z")) and ":" not in t.split()[0]:
+            body[name][t.split()[0]] += 1
+        if t.startswith("s_endpgm"):
+            name = None
+        m = re.match(r"^\s+\.name:\s+(\S+)", ln)
+        if m:
+            cur_meta = m.group(1)
+        m = re.match(r"^\s+\.vgpr_spill_count:\s+(\d+)", ln)
+        if m and cur_meta:
+            spills[cur_meta] = int(m.group(1))
+    return {k: (spills.get(k, 0), v) for k, v in body.items() if k in spills}
