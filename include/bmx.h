@@ -211,7 +211,8 @@ size_t bmx_workspace_bytes(int op, const int64_t* dims, int ndims);
  *          3 one thread per output, 4 matrix cores (GEMM-shaped), 5 matrix cores (short K,
  *          filters in LDS)
  *   key 7  GEMM engine: 1 xor/popcount, 2 int8 matrix cores, 3 FP4 matrix cores
- *   key 8  K-split waves, key 9  tile variant (1: 32 x 32 per wave) of the matrix-core kernels */
+ *   key 8  K-split waves, key 9  tile variant (1: 32 x 32, 2: 64 x 64 per wave) of the matrix-core
+ *          kernels */
 int bmx_tune_set(int key, int value);
 
 /* Static, human-readable name of a status code. */

@@ -478,7 +478,7 @@ gemm_mfma_kernel(const MfmaParams p) {
 
 int gemm_engine = 0;  // 0 = automatic, 1 = xor/popcount kernel, 2 = int8 matrix cores, 3 = FP4 matrix cores
 int gemm_mfma_ksplit = 0;
-int gemm_mfma_tile = 0;  // 1 forces the 32 x 32 per wave variant
+int gemm_mfma_tile = 0;  // 1 forces the 32 x 32 per wave variant, 2 the 64 x 64 one
 
 namespace {
 
@@ -512,7 +512,13 @@ size_t lds_bytes(int S, int blocks) {
 
 int choose_split(int64_t tiles, int nsteps) {
   int S = gemm_mfma_ksplit;
-  if (S <= 0) S = (int)ceil_div(2048, tiles);  // about two waves per SIMD
+  if (S <= 0) {
+    S = (int)ceil_div(2048, tiles);  // about two waves per SIMD
+    // a third where every wave still keeps a long run of K (12 piece steps = 3072 bits):
+    // 256 x 4096 x 9216 10.7 against 12.1 us; shorter runs lose to the reduction
+    const int S3 = (int)(3072 / tiles);
+    if (S3 > S && S3 <= 8 && nsteps / S3 >= 12) S = S3;
+  }
   if (S > 8) S = 8;
   if (S > nsteps) S = nsteps;
   return S < 1 ? 1 : S;
@@ -542,9 +548,10 @@ bool launch_xnor_gemm_mfma(const uint64_t* A, int64_t lda_w, const uint64_t* B, 
   p.C_bits = (uint32_t*)C_bits;
   p.thr = thr_n;
   p.ldc = ldc;
-  // 64 x 64 per wave; 32 x 32 when that grid has fewer than two tiles per CU (measured:
-  // 256 x 4096 x 4096 8.7 against 9.5 us, 1024^3 6.0 against 8.1 us)
-  const bool small = ceil_div(M, 64) * ceil_div(N, 64) < 512 || gemm_mfma_tile == 1;
+  // 64 x 64 per wave; 32 x 32 while that grid has at most four tiles per CU (measured:
+  // 256 x 4096 x 4096 8.0 against 10.1 us, 2048 x 2048 x 1024 9.7 against 12.6 us,
+  // 2048 x 2048 x 4096 18.7 against 19.5 us; 4096 x 2048 x 4096 28.7 against 25.5 us)
+  const bool small = gemm_mfma_tile ? gemm_mfma_tile == 1 : ceil_div(M, 64) * ceil_div(N, 64) <= 1024;
   const int T = small ? 1 : 2;
   const int tiles_m = (int)ceil_div(M, 32 * T);
   // (packed output: both 32-bit halves of the last word of a row get a block that writes them)
@@ -642,7 +649,7 @@ bool launch_conv_mfma(const uint64_t* Xp, int Nimg, int C, int H, int W, const u
   p.div_cw = make_fast_div((uint32_t)Cw);
   p.div_kw = make_fast_div((uint32_t)KW);
   // (32 x 32 tiles further up than in the GEMM: 15.7 against 19.0 us at 784 tiles of 64 x 64)
-  const bool small = ceil_div(O, 64) * ceil_div(P, 64) < 2048 || gemm_mfma_tile == 1;
+  const bool small = gemm_mfma_tile ? gemm_mfma_tile == 1 : ceil_div(O, 64) * ceil_div(P, 64) < 2048;
   const int T = small ? 1 : 2;
   const int tiles_m = (int)ceil_div(O, 32 * T);
   p.tiles_n = (int)ceil_div(P, 32 * T);
