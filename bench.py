@@ -215,7 +215,7 @@ def main():
                     "achieved": achieved / 1e12, "peak": VALU_PEAK_BINOPS / 1e12, "unit": "Tbinop/s",
                     "frac": achieved / VALU_PEAK_BINOPS}
     else:
-        roofline = {"bound": "hbm", "kernel": "conv_mfma_ws_kernel<9,1,4> (implicit GEMM on the FP4 matrix cores)",
+        roofline = {"bound": "hbm", "kernel": "conv_mfma_ws_kernel<9,1,4,false> (implicit GEMM on the FP4 matrix cores)",
                     "achieved": conv_bytes / (conv_us * 1e-6) / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                     "frac": conv_bytes / (conv_us * 1e-6) / HBM_PEAK,
                     "algorithmic_bytes_per_launch": conv_bytes,
@@ -463,7 +463,7 @@ def main():
                                    "alpha epilogue, fp32 out (GEMM view M=64 N=50176 K=576)",
                        "step": "bmx_binary_conv2d = channel pack + implicit-GEMM conv + alpha",
                        "kernels": "pack_nchw_kernel + " + ("conv_stationary_kernel<9,2>" if popcount_conv
-                                                           else "conv_mfma_ws_kernel<9,1,4>"),
+                                                           else "conv_mfma_ws_kernel<9,1,4,false>"),
                        "timed_region": "one replay of a HIP graph holding the K steps",
                        "buffer_sets_rotated": int(nsets),
                        "ms_per_step_cache_hot": hot_us * 1e-3,
