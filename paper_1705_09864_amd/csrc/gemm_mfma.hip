@@ -157,30 +157,47 @@ __device__ __forceinline__ v4i expand(uint32_t w, int s) {
 }
 
 // The FP4 form (v_mfma_scale_f32_32x32x64_f8f6f4 with both operands E2M1): an element is a
-// nibble, and the E2M1 codes 0, 1, 2, 3 are the values 0, 0.5, 1, 1.5, i.e. half the code.
-// With a block scale of 2 on both operands (E8M0 code 128) a nibble holding q in 0..3 is
-// the value q: a bit in nibble bit 0 gives {0, 1}, a second plane in nibble bit 1 gives the
-// 2-bit quantised value, every product is a small integer and the fp32 accumulation is
-// exact below 2^24.  One 32-bit word expands into four dwords of eight nibbles each
-// ((w >> d) & 0x11111111), which is one MFMA step of K = 64: half the VALU work and half
-// the matrix-core time per bit of the int8 form.  (Checked on the hardware against a CPU
-// count before use, like the int8 layout.)
-__device__ __forceinline__ v8i expand4(uint32_t w) {
+// nibble, and the E2M1 codes 0, 1, 2, 3, 4 are the values 0, 0.5, 1, 1.5, 2.  A bit left where it
+// stands in its nibble is therefore worth 0.5, 1 or 2 (the nibble's top bit is the sign and
+// carries no value), and the E8M0 block scale of the instruction, one per lane and MFMA,
+// brings every product back to 1: one MFMA takes one nibble plane n of four dwords,
+//   n = 0: w & 0x11111111, scale 2     n = 1: w & 0x22222222, scale 1
+//   n = 2: w & 0x44444444, scale 1/2   n = 3: (w >> 3) & 0x11111111, scale 2
+// on both operands (five VALU instructions per dword and operand instead of the seven of
+// shifting every plane down to bit 0; the four MFMAs of a 16-byte piece are K = 4 x 64 as
+// before).  Products and fp32 sums are exact integers below 2^24.  A k-bit operand (planes
+// p = 0, 1 of a quantised value q) has to sit at the bottom of the nibble, where the codes
+// 0..3 are q/2: its planes are shifted down and keep the scale of 2, the 1-bit operand beside
+// it still takes the cheap form.  (Checked on the hardware against a CPU count before use,
+// like the int8 layout.)
+__device__ __forceinline__ v8i plane4(const uint4& v, int n) {
   v8i e;
 #pragma unroll
-  for (int d = 0; d < 4; ++d) e[d] = (int)((w >> d) & 0x11111111u);
+  for (int s = 0; s < 4; ++s) {
+    const uint32_t w = dword_of(v, s);
+    e[s] = (int)(n == 3 ? (w >> 3) & 0x11111111u : w & (0x11111111u << n));
+  }
 #pragma unroll
-  for (int d = 4; d < 8; ++d) e[d] = 0;
+  for (int s = 4; s < 8; ++s) e[s] = 0;
   return e;
 }
-__device__ __forceinline__ v8i expand4_plane(uint32_t w, int pl, v8i e) {
+// nibble plane n of plane pl of a k-bit value, at nibble bit pl
+__device__ __forceinline__ v8i plane4_low(const uint4& v, int n, int pl) {
+  v8i e;
 #pragma unroll
-  for (int d = 0; d < 4; ++d) {
-    const int sh = d - pl;
-    const uint32_t x = sh >= 0 ? (w >> sh) : (w << -sh);
-    e[d] |= (int)(x & (0x11111111u << pl));
+  for (int s = 0; s < 4; ++s) {
+    const uint32_t w = dword_of(v, s);
+    const int sh = n - pl;
+    e[s] = (int)((sh >= 0 ? (w >> sh) : (w << -sh)) & (0x11111111u << pl));
   }
+#pragma unroll
+  for (int s = 4; s < 8; ++s) e[s] = 0;
   return e;
+}
+__device__ __forceinline__ v8i or8(v8i a, v8i b) {
+#pragma unroll
+  for (int s = 0; s < 4; ++s) a[s] |= b[s];
+  return a;
 }
 
 // Plane pl of a k-bit value: the same bits as expand(), shifted to bit pl of every byte.
@@ -231,42 +248,52 @@ __device__ __forceinline__ void macro_step(int m0, int n0, const uint64_t* (&bro
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     if (!ALL && (q < qlo || q >= qhi)) continue;
+    if constexpr (F4) {
+      // one MFMA per nibble plane n of the piece's four dwords (see plane4)
 #pragma unroll
-    for (int d = 0; d < 4; ++d) {
-      if constexpr (F4) {
+      for (int n = 0; n < 4; ++n) {
         v8i ea[TM], eb[TN];
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-          ea[i] = expand4(dword_of(ra[i][0][q], d));
+          if constexpr (PL == 1) {
+            ea[i] = plane4(ra[i][0][q], n);
+          } else {
+            ea[i] = plane4_low(ra[i][0][q], n, 0);
 #pragma unroll
-          for (int pl = 1; pl < PL; ++pl) ea[i] = expand4_plane(dword_of(ra[i][pl][q], d), pl, ea[i]);
+            for (int pl = 1; pl < PL; ++pl) ea[i] = or8(ea[i], plane4_low(ra[i][pl][q], n, pl));
+          }
         }
 #pragma unroll
-        for (int j = 0; j < TN; ++j) eb[j] = expand4(dword_of(rb[j][q], d));
+        for (int j = 0; j < TN; ++j) eb[j] = plane4(rb[j][q], n);
+        // plane 1 holds 1.0 and plane 2 holds 2.0 where planes 0 and 3 hold 0.5
+        const int sb = n == 1 ? 127 : (n == 2 ? 126 : 128);
+        const int sa = PL == 1 ? sb : 128;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
           for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ea[i], eb[j], acc[i][j], 4, 4, 0, 128, 0,
-                                                                          128);
-      } else {
-#pragma unroll
-      for (int s = 0; s < 2; ++s) {
-        v4i ea[TM], eb[TN];
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-          ea[i] = expand(dword_of(ra[i][0][q], d), s);
-#pragma unroll
-          for (int pl = 1; pl < PL; ++pl) ea[i] = expand_plane(dword_of(ra[i][pl][q], d), s, pl, ea[i]);
-        }
-#pragma unroll
-        for (int j = 0; j < TN; ++j) eb[j] = expand(dword_of(rb[j][q], d), s);
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ea[i], eb[j], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ea[i], eb[j], acc[i][j], 4, 4, 0, sa, 0, sb);
       }
+    } else {
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+          v4i ea[TM], eb[TN];
+#pragma unroll
+          for (int i = 0; i < TM; ++i) {
+            ea[i] = expand(dword_of(ra[i][0][q], d), s);
+#pragma unroll
+            for (int pl = 1; pl < PL; ++pl) ea[i] = expand_plane(dword_of(ra[i][pl][q], d), s, pl, ea[i]);
+          }
+#pragma unroll
+          for (int j = 0; j < TN; ++j) eb[j] = expand(dword_of(rb[j][q], d), s);
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+              acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ea[i], eb[j], acc[i][j], 0, 0, 0);
+        }
       }
     }
   }
