@@ -6,7 +6,7 @@
 // and the last sum is an integer matrix product.  The operands stay bit-packed in memory and
 // in the loads (that is what keeps the traffic 32x below fp32, Sec. 1); a lane turns its
 // bits into 0/1 bytes in registers right before v_mfma_i32_32x32x32_i8 consumes them (or
-// into FP4 nibbles for v_mfma_scale_f32_32x32x64_f8f6f4: see expand4 below).
+// into FP4 nibbles for v_mfma_scale_f32_32x32x64_f8f6f4: see plane4 below).
 // Expansion (int8 form): for a 32-bit word w, (w >> j) & 0x01010101 puts bits j, j+8, j+16, j+24 into the
 // four bytes of a dword, so eight shift/and pairs give the 32 bytes two MFMA steps take.
 // Which bit lands in which byte does not matter as long as both operands use the same order:
