@@ -77,6 +77,12 @@ int bmx_binarize_pack(const float* x, int64_t rows, int64_t cols, int64_t ldx, i
 int bmx_xnor_gemm(const uint64_t* A, int64_t lda_w, const uint64_t* B, int64_t ldb_w, int32_t* C,
                   int64_t ldc, int M, int N, int K, void* stream);
 
+/* The same product in the other range of Eq. 2 (Sec. 2.2.2): the xnor count
+ *   C[m][n] = number of k with A[m][k] == B[n][k] = (dot + K) / 2, in 0 .. K,
+ * which is what the listing of Sec. 2.2.1 accumulates.  Arguments as for bmx_xnor_gemm. */
+int bmx_xnor_gemm_count(const uint64_t* A, int64_t lda_w, const uint64_t* B, int64_t ldb_w, int32_t* C,
+                        int64_t ldc, int M, int N, int K, void* stream);
+
 /* Binary fully connected layer (Sec. 2, QFullyConnected): binarise + pack the fp32
  * activations, xnor GEMM against pre-packed weights, optional scale.
  *   x        fp32 [batch, in_features], leading dimension ldx.

@@ -20,7 +20,7 @@ EXPORTS = ["bmx_binarize_pack", "bmx_xnor_gemm", "bmx_binary_fc", "bmx_pack_conv
            "bmx_binary_conv2d", "bmx_quant_gemm", "bmx_alpha_mean_abs", "bmx_pack_nchw",
            "bmx_binary_conv2d_packed", "bmx_workspace_bytes", "bmx_status_string", "bmx_version",
            "bmx_conv_weight_row_words", "bmx_binary_fc_packed", "bmx_tune_set",
-           "bmx_binary_conv2d_bits"]
+           "bmx_binary_conv2d_bits", "bmx_xnor_gemm_count"]
 
 _i64, _int, _p, _sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
 
@@ -41,6 +41,8 @@ def lib():
         L = ctypes.CDLL(LIB_PATH)
         L.bmx_binarize_pack.argtypes = [_p, _i64, _i64, _i64, _int, _p, _i64, _p]
         L.bmx_xnor_gemm.argtypes = [_p, _i64, _p, _i64, _p, _i64, _int, _int, _int, _p]
+        L.bmx_xnor_gemm_count.argtypes = L.bmx_xnor_gemm.argtypes
+        L.bmx_xnor_gemm_count.restype = _int
         L.bmx_binary_fc.argtypes = [_p, _i64, _p, _i64, _p, _int, _int, _int, _p, _p, _i64, _p, _sz, _p]
         L.bmx_pack_conv_weights.argtypes = [_p, _int, _int, _int, _int, _p, _p]
         L.bmx_binary_conv2d.argtypes = [_p, _int, _int, _int, _int, _p, _int, _int, _int, _int, _int,
@@ -124,12 +126,14 @@ def binarize_pack(x, pack_dim=1, out=None, stream=None):
     return out
 
 
-def xnor_gemm(A, B, K, out=None, stream=None):
+def xnor_gemm(A, B, K, out=None, stream=None, count=False):
+    """count: the xnor count (dot + K) / 2 of Eq. 2 instead of the dot product."""
     M, N = A.shape[0], B.shape[0]
     if out is None:
         out = torch.empty((M, N), dtype=torch.int32, device=A.device)
-    _check(lib().bmx_xnor_gemm(_ptr(A), A.shape[1], _ptr(B), B.shape[1], _ptr(out), max(N, 1), M, N, K,
-                               _stream(stream)), "bmx_xnor_gemm")
+    f = lib().bmx_xnor_gemm_count if count else lib().bmx_xnor_gemm
+    _check(f(_ptr(A), A.shape[1], _ptr(B), B.shape[1], _ptr(out), max(N, 1), M, N, K, _stream(stream)),
+           "bmx_xnor_gemm_count" if count else "bmx_xnor_gemm")
     return out
 
 

@@ -142,8 +142,9 @@ int bmx_binarize_pack(const float* x, int64_t rows, int64_t cols, int64_t ldx, i
   return hip_status(bmx::launch_pack_strided(x, 1, rows, cols, ldx, 0, out, out_ld_words, s));
 }
 
-int bmx_xnor_gemm(const uint64_t* A, int64_t lda_w, const uint64_t* B, int64_t ldb_w, int32_t* C,
-                  int64_t ldc, int M, int N, int K, void* stream) {
+namespace {
+int xnor_gemm_checked(const uint64_t* A, int64_t lda_w, const uint64_t* B, int64_t ldb_w, int32_t* C,
+                      int64_t ldc, int M, int N, int K, void* stream, bool as_count) {
   if (M < 0 || N < 0) return BMX_ERR_SHAPE;
   if (K <= 0 || K >= kMaxK) return BMX_ERR_SHAPE;
   if (M == 0 || N == 0) return BMX_OK;
@@ -152,7 +153,19 @@ int bmx_xnor_gemm(const uint64_t* A, int64_t lda_w, const uint64_t* B, int64_t l
   if (lda_w < Kw || ldb_w < Kw || ldc < N) return BMX_ERR_LD;
   if (misaligned(A, 8) || misaligned(B, 8) || misaligned(C, 4)) return BMX_ERR_ALIGN;
   return hip_status(bmx::launch_xnor_gemm((const uint32_t*)A, false, lda_w * 2, B, ldb_w, M, N, K,
-                                          nullptr, C, nullptr, nullptr, nullptr, ldc, (hipStream_t)stream));
+                                          nullptr, C, nullptr, nullptr, nullptr, ldc, (hipStream_t)stream,
+                                          as_count));
+}
+}  // namespace
+
+int bmx_xnor_gemm(const uint64_t* A, int64_t lda_w, const uint64_t* B, int64_t ldb_w, int32_t* C,
+                  int64_t ldc, int M, int N, int K, void* stream) {
+  return xnor_gemm_checked(A, lda_w, B, ldb_w, C, ldc, M, N, K, stream, false);
+}
+
+int bmx_xnor_gemm_count(const uint64_t* A, int64_t lda_w, const uint64_t* B, int64_t ldb_w, int32_t* C,
+                        int64_t ldc, int M, int N, int K, void* stream) {
+  return xnor_gemm_checked(A, lda_w, B, ldb_w, C, ldc, M, N, K, stream, true);
 }
 
 int bmx_binary_fc(const float* x, int64_t ldx, const uint64_t* Wp, int64_t ldw_w,

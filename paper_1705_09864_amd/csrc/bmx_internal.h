@@ -93,12 +93,14 @@ hipError_t launch_quant_pack(const float* a, int64_t M, int64_t K, int64_t lda, 
 // = 0, ldc words per row.
 hipError_t launch_xnor_gemm(const uint32_t* A, bool a_padded, int64_t lda_dw, const uint64_t* B,
                             int64_t ldb_w, int M, int N, int K, const float* alpha_n, int32_t* C_i32,
-                            float* C_f32, uint64_t* C_bits, const float* thr_n, int64_t ldc, hipStream_t s);
+                            float* C_f32, uint64_t* C_bits, const float* thr_n, int64_t ldc, hipStream_t s,
+                            bool as_count = false);  // as_count: C_i32 = (dot + K) / 2, the xnor count of Eq. 2
 // gemm_mfma.hip: the same product on the int8 matrix cores (operands expanded from bits in
 // registers).  Returns false when it does not take the problem (engine choice, alignment).
 bool launch_xnor_gemm_mfma(const uint64_t* A, int64_t lda_w, const uint64_t* B, int64_t ldb_w, int M,
                            int N, int K, const float* alpha_n, int32_t* C_i32, float* C_f32,
-                           uint64_t* C_bits, const float* thr_n, int64_t ldc, hipStream_t s, hipError_t* err);
+                           uint64_t* C_bits, const float* thr_n, int64_t ldc, hipStream_t s, hipError_t* err,
+                           bool as_count = false);
 bool launch_plane_gemm_mfma(const uint64_t* planes_rows, int64_t lda_w, int bits, const int32_t* rowsum,
                             const uint64_t* Wb, int64_t ldb_w, int M, int N, int K, int32_t* S_out,
                             float* out_f32, int64_t ldo, hipStream_t s, hipError_t* err);

@@ -63,6 +63,7 @@ struct GemmParams {
   int Kreal;              // K in bits (xor modes)
   const int32_t* rowsum;  // planes mode: sum_k q[m][k]
   const float* alpha;     // GEMM: per column n.  Convolution: per row (filter) m
+  int as_count;           // kGemmI32: store the xnor count (dot + K) / 2 instead of the dot product
   const float* thr;       // kGemmBits: per column n threshold of the sign decision, or null (0)
   float levels;           // planes mode: 2^bits - 1
   int32_t* C_i32;
@@ -313,7 +314,7 @@ gemm_kernel(const GemmParams p) {
       if (n < p.N) {
         const int64_t idx = m * p.ldc + lane_off;
         const int dot = p.Kreal - 2 * total;
-        if (p.out == kGemmI32) p.C_i32[idx] = dot;
+        if (p.out == kGemmI32) p.C_i32[idx] = p.as_count ? p.Kreal - total : dot;
         else if (p.out == kGemmF32) p.C_f32[idx] = (float)dot;
         else p.C_f32[idx] = ra * (float)dot;
       }
@@ -452,11 +453,12 @@ void no_conv(GemmParams& p) {
 
 hipError_t launch_xnor_gemm(const uint32_t* A, bool a_padded, int64_t lda_dw, const uint64_t* B,
                             int64_t ldb_w, int M, int N, int K, const float* alpha_n, int32_t* C_i32,
-                            float* C_f32, uint64_t* C_bits, const float* thr_n, int64_t ldc, hipStream_t s) {
+                            float* C_f32, uint64_t* C_bits, const float* thr_n, int64_t ldc, hipStream_t s,
+                            bool as_count) {
   if ((lda_dw & 1) == 0) {
     hipError_t err = hipSuccess;
     if (launch_xnor_gemm_mfma((const uint64_t*)A, lda_dw / 2, B, ldb_w, M, N, K, alpha_n, C_i32, C_f32,
-                              C_bits, thr_n, ldc, s, &err))
+                              C_bits, thr_n, ldc, s, &err, as_count))
       return err;
   }
   GemmParams p;
@@ -477,6 +479,7 @@ hipError_t launch_xnor_gemm(const uint32_t* A, bool a_padded, int64_t lda_dw, co
   p.C_f32 = C_f32;
   p.C_bits = C_bits;
   p.thr = thr_n;
+  p.as_count = as_count ? 1 : 0;
   p.ldc = ldc;
   p.out = C_bits ? kGemmBits : (C_i32 ? kGemmI32 : (alpha_n ? kGemmF32Alpha : kGemmF32));
   if (a_padded) {  // A rows are zero padded to whole chunks: everything runs in the main loop
@@ -520,6 +523,7 @@ hipError_t launch_plane_gemm(const uint32_t* planes_rows, int64_t lda_dw, int bi
   p.C_f32 = out_f32;
   p.C_bits = nullptr;
   p.thr = nullptr;
+  p.as_count = 0;
   p.ldc = ldo;
   p.out = kGemmPlanes;
   launch<true>(p, s);
@@ -554,6 +558,7 @@ hipError_t launch_conv_gemm(const uint64_t* Xp, int Nimg, int C, int H, int W, c
   p.C_f32 = out_f32;
   p.C_bits = nullptr;
   p.thr = nullptr;
+  p.as_count = 0;
   p.ldc = (int64_t)Ho * Wo;
   p.out = out_i32 ? kGemmI32 : (alpha ? kGemmF32Alpha : kGemmF32);
   p.HoWo = Ho * Wo;

@@ -56,6 +56,7 @@ struct MfmaParams {
   int tail_half;        // words per half-wave in the last macro step (8 when it is whole)
   int tiles_n;
   const float* alpha;  // per column n, or null
+  int as_count;        // int32 GEMM output: the xnor count (dot + K) / 2 instead of the dot product
   const float* thr;    // packed-bit output: per column n threshold of the sign decision, or null (0)
   const int32_t* rowsum;  // plane mode: sum_k q[m][k]
   float levels;           // plane mode: 2^bits - 1
@@ -452,7 +453,7 @@ gemm_mfma_kernel(const MfmaParams p) {
         p.C_bits[(int64_t)m * (2 * p.ldc) + (n >> 5)] = h ? (uint32_t)(mask >> 32) : (uint32_t)mask;
     } else if (m < p.M && n < p.N) {
       const int64_t idx = (int64_t)m * p.ldc + n;
-      if (p.C_i32) __builtin_nontemporal_store(dot, p.C_i32 + idx);
+      if (p.C_i32) __builtin_nontemporal_store(p.as_count ? (dot + p.Kreal) >> 1 : dot, p.C_i32 + idx);
       else __builtin_nontemporal_store(al * (float)dot, p.C_f32 + idx);
     }
   };
@@ -555,7 +556,8 @@ int choose_split(int64_t tiles, int nsteps) {
 
 bool launch_xnor_gemm_mfma(const uint64_t* A, int64_t lda_w, const uint64_t* B, int64_t ldb_w, int M,
                            int N, int K, const float* alpha_n, int32_t* C_i32, float* C_f32,
-                           uint64_t* C_bits, const float* thr_n, int64_t ldc, hipStream_t s, hipError_t* err) {
+                           uint64_t* C_bits, const float* thr_n, int64_t ldc, hipStream_t s, hipError_t* err,
+                           bool as_count) {
   if (gemm_engine == 1) return false;
   // 16-byte row pieces are loaded as one vector: rows must start 16-byte aligned
   if ((lda_w & 1) || (ldb_w & 1) || ((uintptr_t)A & 15) || ((uintptr_t)B & 15)) return false;
@@ -574,6 +576,7 @@ bool launch_xnor_gemm_mfma(const uint64_t* A, int64_t lda_w, const uint64_t* B, 
   p.C_f32 = C_f32;
   p.C_bits = (uint32_t*)C_bits;
   p.thr = thr_n;
+  p.as_count = as_count ? 1 : 0;
   p.ldc = ldc;
   // 64 x 64 per wave; 32 x 32 while that grid has at most four tiles per CU (measured:
   // 256 x 4096 x 4096 8.0 against 10.1 us, 2048 x 2048 x 1024 9.7 against 12.6 us,
@@ -616,6 +619,7 @@ bool launch_plane_gemm_mfma(const uint64_t* planes_rows, int64_t lda_w, int bits
   p.C_f32 = out_f32;
   p.C_bits = nullptr;
   p.thr = nullptr;
+  p.as_count = 0;
   p.ldc = ldo;
   // 32 rows x 64 columns per wave: the two planes of a row double the A registers
   const int tiles_m = (int)ceil_div(M, 32);
@@ -663,6 +667,7 @@ bool launch_conv_mfma(const uint64_t* Xp, int Nimg, int C, int H, int W, const u
   p.C_f32 = out_f32;
   p.C_bits = nullptr;
   p.thr = nullptr;
+  p.as_count = 0;
   p.ldc = 0;
   p.HoWo = Ho * Wo;
   p.Wo = Wo;

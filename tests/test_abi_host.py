@@ -69,8 +69,9 @@ def test_binarize_pack_validation():
     assert f(P, 1 << 24, 4, 4, 0, P, 1 << 18, NULL) == E_SHAPE  # K too long
 
 
-def test_xnor_gemm_validation():
-    f = B.lib().bmx_xnor_gemm
+@pytest.mark.parametrize("name", ["bmx_xnor_gemm", "bmx_xnor_gemm_count"])
+def test_xnor_gemm_validation(name):
+    f = getattr(B.lib(), name)
     assert f(P, 1, P, 1, P, 8, 4, 8, 0, NULL) == E_SHAPE
     assert f(P, 1, P, 1, P, 8, -4, 8, 64, NULL) == E_SHAPE
     assert f(P, 1, P, 1, P, 8, 4, 8, 1 << 24, NULL) == E_SHAPE

@@ -87,6 +87,29 @@ def test_xnor_gemm(M, N, K):
     np.testing.assert_array_equal(got, oracle.xnor_gemm(A, Bm, K))
 
 
+@pytest.mark.parametrize("engine", [1, 2, 3])
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (5, 7, 63), (33, 65, 500), (70, 130, 1100), (256, 300, 4096)])
+def test_xnor_gemm_count_range(M, N, K, engine):
+    """The other range of Eq. 2: the number of agreeing positions, counted from the definition on
+    the unpacked +-1 values, from every GEMM engine (rows padded to an even word count so that
+    the matrix-core kernels take the problem)."""
+    rng = np.random.default_rng(M + N + K)
+    a = rng.standard_normal((M, K)).astype(np.float32)
+    b = rng.standard_normal((N, K)).astype(np.float32)
+    want = (oracle.sign(a)[:, None, :] == oracle.sign(b)[None, :, :]).sum(axis=2).astype(np.int32)
+
+    def even_rows(x):
+        p = oracle.binarize_pack(x, 1)
+        out = np.zeros((p.shape[0], (p.shape[1] + 1) // 2 * 2), dtype=np.uint64)
+        out[:, :p.shape[1]] = p
+        return dev(out.view(np.int64))
+
+    with tuned(k7=engine):
+        got = B.xnor_gemm(even_rows(a), even_rows(b), K, count=True).cpu().numpy()
+    np.testing.assert_array_equal(got, want)
+    np.testing.assert_array_equal(2 * got - K, oracle.xnor_gemm(oracle.binarize_pack(a, 1), oracle.binarize_pack(b, 1), K))
+
+
 def test_xnor_gemm_wide_rows_and_invariants():
     """Row stride wider than ceil(K/64): extra words are ignored (they hold garbage here)."""
     rng = np.random.default_rng(5)
