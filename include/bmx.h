@@ -70,6 +70,14 @@ extern "C" {
 int bmx_binarize_pack(const float* x, int64_t rows, int64_t cols, int64_t ldx, int pack_dim,
                       uint64_t* out, int64_t out_ld_words, void* stream);
 
+/* The inverse of bmx_binarize_pack(pack_dim = 1): out[r][k] = bit k of row r ? +1.0f : -1.0f.
+ * A model stored with 1-bit weights (Sec. 2.2.3: the converter's output, 32x smaller than
+ * fp32) goes back through this to the +-1 floats every pack routine of the library starts
+ * from, e.g. bmx_pack_conv_weights with its private row layout.
+ *   bits uint64 [rows, ld_words], ld_words >= ceil(K/64);  out fp32 [rows, ldo], ldo >= K. */
+int bmx_unpack_pm1(const uint64_t* bits, int64_t rows, int64_t K, int64_t ld_words, float* out,
+                   int64_t ldo, void* stream);
+
 /* xnor GEMM on packed operands (Sec. 2.2.1, the xnor GEMM kernel; output form per
  * Sec. 2.2.2 / Eq. 2):  C[m][n] = K - 2 * sum_i popcount(A[m][i] ^ B[n][i]).
  *   A  uint64 [M, lda_w], B uint64 [N, ldb_w], both packed along K (K contiguous),

@@ -20,7 +20,7 @@ EXPORTS = ["bmx_binarize_pack", "bmx_xnor_gemm", "bmx_binary_fc", "bmx_pack_conv
            "bmx_binary_conv2d", "bmx_quant_gemm", "bmx_alpha_mean_abs", "bmx_pack_nchw",
            "bmx_binary_conv2d_packed", "bmx_workspace_bytes", "bmx_status_string", "bmx_version",
            "bmx_conv_weight_row_words", "bmx_binary_fc_packed", "bmx_tune_set",
-           "bmx_binary_conv2d_bits", "bmx_xnor_gemm_count"]
+           "bmx_binary_conv2d_bits", "bmx_xnor_gemm_count", "bmx_unpack_pm1"]
 
 _i64, _int, _p, _sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
 
@@ -42,6 +42,8 @@ def lib():
         L.bmx_binarize_pack.argtypes = [_p, _i64, _i64, _i64, _int, _p, _i64, _p]
         L.bmx_xnor_gemm.argtypes = [_p, _i64, _p, _i64, _p, _i64, _int, _int, _int, _p]
         L.bmx_xnor_gemm_count.argtypes = L.bmx_xnor_gemm.argtypes
+        L.bmx_unpack_pm1.argtypes = [_p, _i64, _i64, _i64, _p, _i64, _p]
+        L.bmx_unpack_pm1.restype = _int
         L.bmx_xnor_gemm_count.restype = _int
         L.bmx_binary_fc.argtypes = [_p, _i64, _p, _i64, _p, _int, _int, _int, _p, _p, _i64, _p, _sz, _p]
         L.bmx_pack_conv_weights.argtypes = [_p, _int, _int, _int, _int, _p, _p]
@@ -123,6 +125,16 @@ def binarize_pack(x, pack_dim=1, out=None, stream=None):
     _check(lib().bmx_binarize_pack(_ptr(x), rows, cols, x.stride(0) if rows > 1 else cols, pack_dim,
                                    _ptr(out), out.stride(0) if out.shape[0] > 1 else out.shape[1],
                                    _stream(stream)), "bmx_binarize_pack")
+    return out
+
+
+def unpack_pm1(bits, K, out=None, stream=None):
+    """bits: packed int64 storage [rows, words] -> fp32 [rows, K] of +1 / -1."""
+    rows = bits.shape[0]
+    if out is None:
+        out = torch.empty((rows, K), dtype=torch.float32, device=bits.device)
+    _check(lib().bmx_unpack_pm1(_ptr(bits), rows, K, bits.shape[1], _ptr(out), K, _stream(stream)),
+           "bmx_unpack_pm1")
     return out
 
 

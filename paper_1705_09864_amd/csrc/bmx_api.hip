@@ -142,6 +142,17 @@ int bmx_binarize_pack(const float* x, int64_t rows, int64_t cols, int64_t ldx, i
   return hip_status(bmx::launch_pack_strided(x, 1, rows, cols, ldx, 0, out, out_ld_words, s));
 }
 
+int bmx_unpack_pm1(const uint64_t* bits, int64_t rows, int64_t K, int64_t ld_words, float* out,
+                   int64_t ldo, void* stream) {
+  if (rows < 0) return BMX_ERR_SHAPE;
+  if (K <= 0 || K >= kMaxK) return BMX_ERR_SHAPE;
+  if (rows == 0) return BMX_OK;
+  if (!bits || !out) return BMX_ERR_NULL;
+  if (ld_words < bmx::words_for(K) || ldo < K) return BMX_ERR_LD;
+  if (misaligned(bits, 8) || misaligned(out, 4)) return BMX_ERR_ALIGN;
+  return hip_status(bmx::launch_unpack_pm1(bits, rows, K, ld_words, out, ldo, (hipStream_t)stream));
+}
+
 namespace {
 int xnor_gemm_checked(const uint64_t* A, int64_t lda_w, const uint64_t* B, int64_t ldb_w, int32_t* C,
                       int64_t ldc, int M, int N, int K, void* stream, bool as_count) {

@@ -104,6 +104,31 @@ hipError_t launch_pack_rows_padded(const float* x, int64_t rows, int64_t cols, i
   return hipGetLastError();
 }
 
+// Inverse of the row pack: element k of row r -> +1.0f / -1.0f (a stored 1-bit model back
+// to the float weights every pack routine starts from, Sec. 2.2.3).  A wave per word, lane =
+// bit; grid-stride over the words.
+__global__ void __launch_bounds__(256)
+unpack_pm1_kernel(const uint64_t* __restrict__ bits, int64_t rows, int64_t K, int64_t ld_words,
+                  float* __restrict__ out, int64_t ldo) {
+  const int lane = threadIdx.x & 63;
+  const int64_t Kw = words_for(K);
+  const int64_t total = rows * Kw;
+  for (int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); i < total; i += (int64_t)gridDim.x * 4) {
+    const int64_t r = i / Kw, w = i - r * Kw;
+    const int64_t k = w * 64 + lane;
+    const uint64_t word = bits[r * ld_words + w];
+    if (k < K) out[r * ldo + k] = ((word >> lane) & 1) ? 1.0f : -1.0f;
+  }
+}
+
+hipError_t launch_unpack_pm1(const uint64_t* bits, int64_t rows, int64_t K, int64_t ld_words, float* out,
+                             int64_t ldo, hipStream_t s) {
+  const int64_t blocks = ceil_div(rows * words_for(K), 4);
+  hipLaunchKernelGGL(unpack_pm1_kernel, dim3((unsigned)(blocks < 65536 ? blocks : 65536)), dim3(256), 0, s, bits,
+                     rows, K, ld_words, out, ldo);
+  return hipGetLastError();
+}
+
 // Strided pack (the matrix is stored K x ncol, pack down the columns): a wave packs one
 // word of 64 consecutive columns: lanes span columns, so every load instruction is a
 // coalesced 256-byte read of one K row, and all 64 row loads of a lane are issued before
