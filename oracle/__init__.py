@@ -183,9 +183,20 @@ def quantize(x, bits):
     return q, v
 
 
-def quant_gemm(a, w, bits_a):
-    """a: [M,K] in [0,1], w: [N,K].  Returns (S int32, out float64, out float32), all [M,N]."""
+def quant_gemm(a, w, bits_a, bits_w=1):
+    """a: [M,K] in [0,1], w: [N,K] (bits_w = 1: any sign; bits_w > 1: in [-1,1]).  Returns
+    (S int32, out float64, out float32), all [M,N]."""
     a, w = _f32(a), _f32(w)
+    if bits_w != 1:
+        M, K = a.shape
+        N = w.shape[0]
+        assert w.shape[1] == K
+        S = np.empty((M, N), dtype=np.int32)
+        o64 = np.empty((M, N), dtype=np.float64)
+        o32 = np.empty((M, N), dtype=np.float32)
+        lib().orc_quant_gemm_kw(_ptr(a), _i64(K), _int(bits_a), _ptr(w), _i64(K), _int(bits_w), _i64(M),
+                                _i64(N), _i64(K), _ptr(S), _ptr(o64), _ptr(o32), _i64(N))
+        return S, o64, o32
     M, K = a.shape
     N = w.shape[0]
     assert w.shape[1] == K

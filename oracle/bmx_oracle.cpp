@@ -25,6 +25,11 @@
 //     over each output row, accumulated in double and rounded once to float.
 //   * Eq. 1 "round" is round-half-away-from-zero (C roundf) of the single fp32
 //     product (2^k - 1) * x, after clamping x to [0, 1].
+//   * k-bit weights (Sec. 2.1 says only that weights follow the same linear
+//     quantisation, which Eq. 1 defines on [0, 1]): a weight in [-1, 1] is moved
+//     to [0, 1] by u = (w + 1) / 2 (fp32), quantised with Eq. 1 and moved back,
+//     w_q = 2 * quantize(u, k) - 1, the affine pair DoReFa-Net wraps around the
+//     same quantiser; for k = 1 this is the sign function (threshold at w = 0).
 //
 // Pins: every function below is checked by tests/test_oracle_*.py against brute
 // force, closed forms, invariants and library routines (see those files).
@@ -263,6 +268,38 @@ void orc_quant_gemm(const float* a, int64_t lda, int bits_a, const float* w, int
       if (out_f64) out_f64[m * ldo + n] = accf;
       if (S) S[m * ldo + n] = (int32_t)acci;
       if (out_f32) out_f32[m * ldo + n] = (float)acci / levels;
+    }
+}
+
+// k-bit activations times k-bit weights (reading above):
+//   out_f64[m][n] = sum_k quantize(a[m][k], bits_a) * (2 * quantize((w[n][k] + 1) / 2, bits_w) - 1)
+//   S[m][n]       = sum_k level_a * (2 * level_w - (2^bits_w - 1))      (exact integer)
+//   out_f32[m][n] = (float)S / (float)((2^bits_a - 1) * (2^bits_w - 1))
+void orc_quant_gemm_kw(const float* a, int64_t lda, int bits_a, const float* w, int64_t ldw, int bits_w,
+                       int64_t M, int64_t N, int64_t K, int32_t* S, double* out_f64, float* out_f32,
+                       int64_t ldo) {
+  std::vector<int32_t> qa((size_t)M * K), qw((size_t)N * K);
+  std::vector<double> va((size_t)M * K), vw((size_t)N * K);
+  for (int64_t m = 0; m < M; ++m) orc_quantize(a + m * lda, K, bits_a, &qa[m * K], &va[m * K]);
+  std::vector<float> u((size_t)K);
+  for (int64_t n = 0; n < N; ++n) {
+    for (int64_t k = 0; k < K; ++k) u[k] = (w[n * ldw + k] + 1.0f) * 0.5f;
+    orc_quantize(u.data(), K, bits_w, &qw[n * K], &vw[n * K]);
+    for (int64_t k = 0; k < K; ++k) vw[n * K + k] = 2.0 * vw[n * K + k] - 1.0;
+  }
+  const int64_t La = (1 << bits_a) - 1, Lw = (1 << bits_w) - 1;
+#pragma omp parallel for schedule(static)
+  for (int64_t m = 0; m < M; ++m)
+    for (int64_t n = 0; n < N; ++n) {
+      double accf = 0.0;
+      int64_t acci = 0;
+      for (int64_t k = 0; k < K; ++k) {
+        accf += va[m * K + k] * vw[n * K + k];
+        acci += (int64_t)qa[m * K + k] * (2 * (int64_t)qw[n * K + k] - Lw);
+      }
+      if (out_f64) out_f64[m * ldo + n] = accf;
+      if (S) S[m * ldo + n] = (int32_t)acci;
+      if (out_f32) out_f32[m * ldo + n] = (float)acci / (float)(La * Lw);
     }
 }
 

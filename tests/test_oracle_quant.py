@@ -82,3 +82,69 @@ def test_quant_gemm_k1_reduces_to_and_count():
     b[a == 0.5] = 1
     wb = (w >= 0).astype(np.int64)
     np.testing.assert_array_equal(S, 2 * (b @ wb.T) - b.sum(1, keepdims=True))
+
+
+# ------------------------------------------------------------------ k-bit weights
+def test_kbit_weights_one_bit_is_the_sign_layer():
+    """bits_w = 1 through the k-bit route (u = (w+1)/2, one level, threshold u = 1/2) is the
+    sign layer for weights in [-1, 1] that are not within rounding of zero."""
+    a = RNG.uniform(0, 1, (6, 150)).astype(np.float32)
+    w = RNG.uniform(-1, 1, (9, 150)).astype(np.float32)
+    w[np.abs(w) < 1e-3] = 0.25
+    w[0, :5] = [1.0, -1.0, 0.0, 0.5, -0.5]
+    for bits in (1, 2, 4):
+        S1, f1, o1 = oracle.quant_gemm(a, w, bits)
+        M, N, K = 6, 9, 150
+        Sk = np.empty((M, N), dtype=np.int32); fk = np.empty((M, N)); ok = np.empty((M, N), dtype=np.float32)
+        from oracle import lib, _ptr, _i64, _int
+        lib().orc_quant_gemm_kw(_ptr(a), _i64(K), _int(bits), _ptr(w), _i64(K), _int(1), _i64(M), _i64(N),
+                                _i64(K), _ptr(Sk), _ptr(fk), _ptr(ok), _i64(N))
+        np.testing.assert_array_equal(Sk, S1)
+        np.testing.assert_array_equal(ok, o1)
+        np.testing.assert_allclose(fk, f1, rtol=1e-12)
+
+
+def test_kbit_weights_closed_forms():
+    K = 77
+    ones = np.ones((2, K), dtype=np.float32)
+    for ba, bw in [(1, 2), (2, 2), (3, 4), (8, 8)]:
+        La, Lw = 2 ** ba - 1, 2 ** bw - 1
+        S, f64, f32 = oracle.quant_gemm(ones, ones, ba, bw)           # 1 * 1 summed K times
+        assert (S == K * La * Lw).all() and (f32 == K).all() and np.allclose(f64, K)
+        S, _, f32 = oracle.quant_gemm(ones, -ones, ba, bw)
+        assert (S == -K * La * Lw).all() and (f32 == -K).all()
+        S, _, _ = oracle.quant_gemm(0 * ones, ones, ba, bw)
+        assert (S == 0).all()
+        # w = 0 -> u = 1/2 -> level round(Lw / 2) = (Lw + 1) / 2 (tie away) -> w_q = 1 / Lw
+        S, f64, _ = oracle.quant_gemm(ones, 0 * ones, ba, bw)
+        assert (S == K * La).all() and np.allclose(f64, K / Lw)
+    # values outside [-1, 1] clamp
+    S, _, _ = oracle.quant_gemm(ones, 5 * ones, 2, 2)
+    assert (S == K * 9).all()
+
+
+def test_kbit_weights_brute_force_in_exact_arithmetic():
+    """Inputs on a dyadic grid, where every fp32 step is exact: Eq. 1 and the affine pair
+    evaluated with fractions, ties away from zero."""
+    from fractions import Fraction as F
+    import math
+
+    def rnd(v):  # half away from zero, v >= 0
+        return math.floor(v + F(1, 2))
+
+    M, N, K = 3, 4, 19
+    a = RNG.integers(0, 17, (M, K)) / 16.0
+    w = RNG.integers(-8, 9, (N, K)) / 8.0
+    for ba, bw in [(2, 2), (1, 3), (4, 2)]:
+        La, Lw = 2 ** ba - 1, 2 ** bw - 1
+        S, f64, f32 = oracle.quant_gemm(a.astype(np.float32), w.astype(np.float32), ba, bw)
+        for m in range(M):
+            for n in range(N):
+                acc = 0
+                for k in range(K):
+                    qa = rnd(La * F(a[m, k]))
+                    qw = rnd(Lw * (F(w[n, k]) + 1) / 2)
+                    acc += qa * (2 * qw - Lw)
+                assert S[m, n] == acc
+                assert abs(f64[m, n] - acc / (La * Lw)) < 1e-12
+                assert f32[m, n] == np.float32(acc) / np.float32(La * Lw)
