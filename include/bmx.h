@@ -189,15 +189,22 @@ int bmx_binary_conv2d_bits(const uint64_t* xp, int N, int C, int H, int W, const
                            uint64_t* out_xp, int out_pad, void* workspace, size_t workspace_bytes,
                            void* stream);
 
-/* k-bit activations x 1-bit weights (Sec. 1: arbitrary bit widths after DoReFa-Net;
+/* k-bit activations x 1-bit or k-bit weights (Sec. 1: arbitrary bit widths after DoReFa-Net;
  * Sec. 2.1, Eq. 1).  a in [0, 1] (clamped) is quantised to the integer level
- * q = round((2^bits_a - 1) * a), ties away from zero, and split into bits_a bit planes;
- * w is binarised with the sign function.  With wb the weight bits,
+ * q = round((2^bits_a - 1) * a), ties away from zero, and split into bits_a bit planes.
+ * bits_w = 1: w is binarised with the sign function.  With wb the weight bits,
  *   S[m][n] = sum_k q[m][k] * sign(w[n][k])
  *           = 2 * sum_p 2^p popcount(plane_p[m] & wb[n]) - sum_p 2^p popcount(plane_p[m]),
  *   out_f32 = (float)S / (float)(2^bits_a - 1)      (the Eq. 1 scale applied once).
+ * bits_w in 2..8: w in [-1, 1] (clamped) goes onto [0, 1] by u = (w + 1) / 2, through the same
+ * quantiser to the level q_w, and back: w_q = (2 * q_w - L_w) / L_w with L_w = 2^bits_w - 1
+ * (Eq. 1 is defined on [0, 1]; the affine pair is DoReFa-Net's).  Then
+ *   S[m][n] = sum_k q[m][k] * (2 * q_w[n][k] - L_w),
+ *   out_f32 = (float)S / (float)((2^bits_a - 1) * L_w),
+ * computed as the bits_w = 1 form against every weight plane, the planes added up by powers
+ * of two.  K * (2^bits_a - 1) * (2^bits_w - 1) must stay below 2^31.
  *   a fp32 [M, lda], w fp32 [N, ldw]; out_i32_scaled (S) and out_f32 are [M, ldo]; either
- *   may be NULL, not both.  bits_a in 1..8, bits_w must be 1.
+ *   may be NULL, not both.  bits_a, bits_w in 1..8.
  *   workspace >= bmx_workspace_bytes(BMX_OP_QUANT_GEMM, {M, N, K, bits_a, bits_w}, 5). */
 int bmx_quant_gemm(const float* a, int64_t lda, int bits_a, const float* w, int64_t ldw,
                    int bits_w, int M, int N, int K, int32_t* out_i32_scaled, float* out_f32,

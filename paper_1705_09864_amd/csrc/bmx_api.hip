@@ -34,16 +34,21 @@ int conv_check(int N, int C, int H, int W, int O, int KH, int KW, int stride, in
 }
 
 struct QuantWs {
-  size_t planes_off, wb_off, rowsum_off, total;
+  size_t planes_off, wb_off, rowsum_off, wrowsum_off, tmp_off, total;
 };
 
-QuantWs quant_ws(int64_t M, int64_t N, int64_t K, int bits_a) {
+// bits_w = 1: sign-packed weights [N][Kw].  bits_w > 1: weight planes [N * bits_w][padded K]
+// like the activations', their (unused) row sums, and the int32 results per weight plane.
+QuantWs quant_ws(int64_t M, int64_t N, int64_t K, int bits_a, int bits_w) {
   const int64_t Kw = bmx::words_for(K);
   QuantWs q;
   q.planes_off = 0;
   q.wb_off = round256((size_t)bits_a * M * bmx::padded_words(K) * 8);
-  q.rowsum_off = q.wb_off + round256((size_t)N * Kw * 8);
-  q.total = q.rowsum_off + round256((size_t)M * 4);
+  q.rowsum_off = q.wb_off + round256(bits_w == 1 ? (size_t)N * Kw * 8
+                                                   : (size_t)bits_w * N * bmx::padded_words(K) * 8);
+  q.wrowsum_off = q.rowsum_off + round256((size_t)M * 4);
+  q.tmp_off = q.wrowsum_off + (bits_w == 1 ? 0 : round256((size_t)N * 4));
+  q.total = q.tmp_off + (bits_w == 1 ? 0 : round256((size_t)M * N * bits_w * 4));
   return q;
 }
 
@@ -116,8 +121,9 @@ size_t bmx_workspace_bytes(int op, const int64_t* dims, int ndims) {
     }
     case BMX_OP_QUANT_GEMM: {
       if (ndims != 5 || dims[0] < 0 || dims[1] < 0 || dims[2] <= 0 || dims[2] >= kMaxK) return 0;
-      if (dims[3] < 1 || dims[3] > 8 || dims[4] != 1) return 0;
-      return quant_ws(dims[0] > 0 ? dims[0] : 1, dims[1] > 0 ? dims[1] : 1, dims[2], (int)dims[3])
+      if (dims[3] < 1 || dims[3] > 8 || dims[4] < 1 || dims[4] > 8) return 0;
+      return quant_ws(dims[0] > 0 ? dims[0] : 1, dims[1] > 0 ? dims[1] : 1, dims[2], (int)dims[3],
+                      (int)dims[4])
           .total;
     }
     default: return 0;
@@ -340,9 +346,10 @@ int bmx_quant_gemm(const float* a, int64_t lda, int bits_a, const float* w, int6
                    int64_t ldo, void* workspace, size_t workspace_bytes, void* stream) {
   if (M < 0 || N < 0) return BMX_ERR_SHAPE;
   if (K <= 0 || K >= kMaxK) return BMX_ERR_SHAPE;
-  if (bits_a < 1 || bits_a > 8 || bits_w != 1) return BMX_ERR_UNSUPPORTED;
-  if ((int64_t)K * ((1 << bits_a) - 1) >= ((int64_t)1 << 31)) return BMX_ERR_SHAPE;
-  if ((int64_t)M * bits_a >= ((int64_t)1 << 31)) return BMX_ERR_SHAPE;
+  if (bits_a < 1 || bits_a > 8 || bits_w < 1 || bits_w > 8) return BMX_ERR_UNSUPPORTED;
+  if ((int64_t)K * ((1 << bits_a) - 1) * ((1 << bits_w) - 1) >= ((int64_t)1 << 31)) return BMX_ERR_SHAPE;
+  if ((int64_t)M * bits_a >= ((int64_t)1 << 31) || (int64_t)N * bits_w >= ((int64_t)1 << 31))
+    return BMX_ERR_SHAPE;
   if (M == 0 || N == 0) return BMX_OK;
   if (!a || !w) return BMX_ERR_NULL;
   if (!out_i32_scaled && !out_f32) return BMX_ERR_NULL;
@@ -350,7 +357,7 @@ int bmx_quant_gemm(const float* a, int64_t lda, int bits_a, const float* w, int6
   if (misaligned(a, 4) || misaligned(w, 4) || misaligned(out_i32_scaled, 4) ||
       misaligned(out_f32, 4))
     return BMX_ERR_ALIGN;
-  const QuantWs q = quant_ws(M, N, K, bits_a);
+  const QuantWs q = quant_ws(M, N, K, bits_a, bits_w);
   if (!workspace || workspace_bytes < q.total) return BMX_ERR_WORKSPACE;
   if (misaligned(workspace, 16)) return BMX_ERR_ALIGN;
   hipStream_t s = (hipStream_t)stream;
@@ -360,6 +367,23 @@ int bmx_quant_gemm(const float* a, int64_t lda, int bits_a, const float* w, int6
   int32_t* rowsum = (int32_t*)(ws + q.rowsum_off);
   const int64_t Kw = bmx::words_for(K);
   const int64_t ldp = bmx::padded_words(K);
+  if (bits_w > 1) {
+    // k-bit weights: quantise both operands into bit planes, run the 1-bit-weight form against
+    // every weight plane (they are N * bits_w columns of one GEMM), add the planes up weighted
+    // by their powers of two: sum_r 2^r (2 sum_p 2^p pc(A_p & W_r) - rowsum) = S
+    uint64_t* wplanes = wb;
+    int32_t* wrowsum = (int32_t*)(ws + q.wrowsum_off);
+    int32_t* tmp = (int32_t*)(ws + q.tmp_off);
+    hipError_t e = bmx::launch_quant_pack(a, M, K, lda, bits_a, planes, ldp, rowsum, nullptr, 0, 0, nullptr, 0, s);
+    if (e != hipSuccess) return BMX_ERR_HIP;
+    e = bmx::launch_quant_pack(w, N, K, ldw, bits_w, wplanes, ldp, wrowsum, nullptr, 0, 0, nullptr, 0, s, true);
+    if (e != hipSuccess) return BMX_ERR_HIP;
+    e = bmx::launch_plane_gemm((const uint32_t*)planes, ldp * 2, bits_a, rowsum, wplanes, ldp, M, N * bits_w, K,
+                               tmp, nullptr, (int64_t)N * bits_w, s);
+    if (e != hipSuccess) return BMX_ERR_HIP;
+    const float denom = (float)(((1 << bits_a) - 1) * ((1 << bits_w) - 1));
+    return hip_status(bmx::launch_quant_combine(tmp, M, N, bits_w, denom, out_i32_scaled, out_f32, ldo, s));
+  }
   // one launch quantises + plane-packs the activations and sign-packs the weights
   hipError_t e = bmx::launch_quant_pack(a, M, K, lda, bits_a, planes, ldp, rowsum, w, N, ldw, wb, Kw, s);
   if (e != hipSuccess) return BMX_ERR_HIP;

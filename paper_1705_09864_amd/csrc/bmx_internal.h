@@ -83,7 +83,9 @@ hipError_t launch_pack_rows_padded(const float* x, int64_t rows, int64_t cols, i
 hipError_t launch_quant_pack(const float* a, int64_t M, int64_t K, int64_t lda, int bits,
                              uint64_t* planes, int64_t ld_words, int32_t* rowsum, const float* w,
                              int64_t wrows, int64_t ldw, uint64_t* wbits, int64_t wb_ld,
-                             hipStream_t s);
+                             hipStream_t s, bool affine = false);
+hipError_t launch_quant_combine(const int32_t* T, int64_t M, int64_t N, int bw, float denom, int32_t* S,
+                                float* out, int64_t ldo, hipStream_t s);
 
 // gemm.hip -------------------------------------------------------------------
 // out = K - 2*popcount(A ^ B); exactly one of C_i32 / C_f32 / C_bits non-null;

@@ -338,6 +338,28 @@ hipError_t launch_pack_conv_weights(const float* w, int O, int C, int KH, int KW
   return hipGetLastError();
 }
 
+// k-bit weights: T[m][n * bw + r] holds the 1-bit-weight form against weight plane r;
+// S[m][n] = sum_r 2^r T[m][n * bw + r], out = float(S) / denom.
+__global__ void __launch_bounds__(256)
+quant_combine_kernel(const int32_t* __restrict__ T, int64_t M, int64_t N, int bw, float denom,
+                     int32_t* __restrict__ S, float* __restrict__ out, int64_t ldo) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= M * N) return;
+  const int64_t m = i / N, n = i - m * N;
+  const int32_t* t = T + (m * N + n) * bw;
+  int32_t acc = 0;
+  for (int r = 0; r < bw; ++r) acc += t[r] << r;
+  if (S) S[m * ldo + n] = acc;
+  if (out) out[m * ldo + n] = (float)acc / denom;
+}
+
+hipError_t launch_quant_combine(const int32_t* T, int64_t M, int64_t N, int bw, float denom, int32_t* S,
+                                float* out, int64_t ldo, hipStream_t s) {
+  hipLaunchKernelGGL(quant_combine_kernel, dim3((unsigned)ceil_div(M * N, 256)), dim3(256), 0, s, T, M, N, bw,
+                     denom, S, out, ldo);
+  return hipGetLastError();
+}
+
 // alpha[r] = mean |w[r][:]|, one workgroup per row, fp64 accumulation.
 __global__ void __launch_bounds__(256)
 alpha_mean_abs_kernel(const float* __restrict__ w, int64_t rows, int64_t cols, int64_t ldw,
@@ -377,7 +399,7 @@ __global__ void __launch_bounds__(256)
 quant_pack_kernel(const float* __restrict__ a, int64_t M, int64_t K, int64_t lda, int bits,
                   uint64_t* __restrict__ planes, int64_t ld_words, int32_t* __restrict__ rowsum,
                   const float* __restrict__ w, int64_t wrows, int64_t ldw,
-                  uint64_t* __restrict__ wbits, int64_t wb_ld, int64_t wsegs_per_block) {
+                  uint64_t* __restrict__ wbits, int64_t wb_ld, int64_t wsegs_per_block, int affine) {
   __shared__ int32_t part[4];
   if ((int64_t)blockIdx.x >= M) {
     const int64_t Kw = words_for(K);
@@ -397,11 +419,17 @@ quant_pack_kernel(const float* __restrict__ a, int64_t M, int64_t K, int64_t lda
     if ((w0 + kSegWords) * 64 <= K) {
 #pragma unroll
       for (int j = 0; j < kSegWords; ++j) v[j] = ar[(w0 + j) * 64 + lane];
+      // (signed operand: [-1, 1] onto [0, 1] first, two fp32 operations)
+      if (affine) {
+#pragma unroll
+        for (int j = 0; j < kSegWords; ++j) v[j] = __fmul_rn(__fadd_rn(v[j], 1.0f), 0.5f);
+      }
     } else {
 #pragma unroll
       for (int j = 0; j < kSegWords; ++j) {
         const int64_t k = (w0 + j) * 64 + lane;
-        v[j] = (k < K) ? ar[k] : 0.0f;
+        const float t = (k < K) ? ar[k] : 0.0f;
+        v[j] = (affine && k < K) ? __fmul_rn(__fadd_rn(t, 1.0f), 0.5f) : t;
       }
     }
     int q[kSegWords];
@@ -430,7 +458,7 @@ quant_pack_kernel(const float* __restrict__ a, int64_t M, int64_t K, int64_t lda
 hipError_t launch_quant_pack(const float* a, int64_t M, int64_t K, int64_t lda, int bits,
                              uint64_t* planes, int64_t ld_words, int32_t* rowsum, const float* w,
                              int64_t wrows, int64_t ldw, uint64_t* wbits, int64_t wb_ld,
-                             hipStream_t s) {
+                             hipStream_t s, bool affine) {
   int64_t wblocks = 0, per = 1;
   if (wrows > 0) {
     const int64_t segs = wrows * ceil_div(words_for(K), kSegWords);
@@ -439,7 +467,7 @@ hipError_t launch_quant_pack(const float* a, int64_t M, int64_t K, int64_t lda, 
     per = ceil_div(segs, wblocks);
   }
   hipLaunchKernelGGL(quant_pack_kernel, dim3((unsigned)(M + wblocks)), dim3(256), 0, s, a, M, K, lda,
-                     bits, planes, ld_words, rowsum, w, wrows, ldw, wbits, wb_ld, per);
+                     bits, planes, ld_words, rowsum, w, wrows, ldw, wbits, wb_ld, per, affine ? 1 : 0);
   return hipGetLastError();
 }
 

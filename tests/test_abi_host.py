@@ -39,7 +39,9 @@ def test_workspace_query():
     q = B.workspace_bytes(B.OP_QUANT_GEMM, (1024, 1024, 4096, 2, 1))
     assert q == 2 * 1024 * 64 * 8 + 1024 * 64 * 8 + 4096  # plane rows, weight bits, row sums
     assert B.workspace_bytes(B.OP_QUANT_GEMM, (4, 4, 64, 9, 1)) == 0      # bits_a out of range
-    assert B.workspace_bytes(B.OP_QUANT_GEMM, (4, 4, 64, 2, 2)) == 0      # k-bit weights unsupported
+    assert B.workspace_bytes(B.OP_QUANT_GEMM, (4, 4, 64, 2, 9)) == 0      # bits_w out of range
+    # k-bit weights: both operands as planes, row sums, one int32 result per weight plane
+    assert B.workspace_bytes(B.OP_QUANT_GEMM, (4, 4, 64, 2, 2)) == 2 * 4 * 16 * 8 + 2 * 4 * 16 * 8 + 256 + 256 + 256
     assert B.workspace_bytes(B.OP_BINARY_CONV2D, (1, 3, 8, 8, 2, 4, 4, 1, 0)) == 0  # even kernel
     # packed-bit convolution: nothing where the convolution kernel writes the bits itself (3 x 3
     # over at most 256 channels), else the fp32 result of the two-kernel route
@@ -160,7 +162,9 @@ def test_quant_and_alpha_validation():
     big = 1 << 24
     assert f(P, 64, 0, P, 64, 1, 4, 4, 64, P, P, 4, P, big, NULL) == E_UNSUP
     assert f(P, 64, 9, P, 64, 1, 4, 4, 64, P, P, 4, P, big, NULL) == E_UNSUP
-    assert f(P, 64, 2, P, 64, 2, 4, 4, 64, P, P, 4, P, big, NULL) == E_UNSUP
+    assert f(P, 64, 2, P, 64, 9, 4, 4, 64, P, P, 4, P, big, NULL) == E_UNSUP
+    assert f(P, 64, 2, P, 64, 0, 4, 4, 64, P, P, 4, P, big, NULL) == E_UNSUP
+    assert f(P, 1 << 20, 8, P, 1 << 20, 8, 4, 4, 1 << 20, P, P, 4, P, big, NULL) == E_SHAPE   # K * 255 * 255 >= 2^31
     assert f(P, 64, 2, P, 64, 1, 4, 4, 64, NULL, NULL, 4, P, big, NULL) == E_NULL
     assert f(P, 63, 2, P, 64, 1, 4, 4, 64, P, P, 4, P, big, NULL) == E_LD
     assert f(P, 64, 2, P, 64, 1, 4, 4, 64, P, P, 4, P, 100, NULL) == E_WS

@@ -298,6 +298,26 @@ def test_quant_gemm_small(bits):
     assert_f32_close(of.cpu().numpy(), r32)
 
 
+@pytest.mark.parametrize("engine", [0, 1])
+@pytest.mark.parametrize("ba,bw", [(1, 2), (2, 2), (2, 3), (3, 2), (4, 4), (8, 8), (2, 8)])
+def test_quant_gemm_kbit_weights(ba, bw, engine):
+    """k-bit weights: w in [-1, 1] through the affine pair around Eq. 1.  Integer S exact, the
+    float within 1e-6; tie and clamp inputs on both operands, ragged shapes, the matrix-core and
+    the xor/popcount engine."""
+    rng = np.random.default_rng(10 * ba + bw)
+    M, N, K = 37, 45, 333
+    a = rng.uniform(0, 1, (M, K)).astype(np.float32)
+    a[0, :6] = [1 / 6, 5 / 6, 0.5, 0.0, 1.0, 0.25]
+    w = rng.uniform(-1, 1, (N, K)).astype(np.float32)
+    w[0, :8] = [0.0, -0.0, 1.0, -1.0, 1.5, -2.0, 1 / 3, -1 / 3]      # ties of u = 1/2, clamps
+    rS, r64, r32 = oracle.quant_gemm(a, w, ba, bw)
+    with tuned(k7=engine):
+        S, of = B.quant_gemm(dev(a), dev(w), ba, bits_w=bw)
+    np.testing.assert_array_equal(S.cpu().numpy(), rS)
+    assert_f32_close(of.cpu().numpy(), r32)
+    assert_f32_close(of.cpu().numpy(), r64, atol=1e-9)
+
+
 def test_config5_quant_gemm():
     c = synth.config5(small=True)
     S, of = B.quant_gemm(dev(c["a"]), dev(c["w"]), 2)
