@@ -129,9 +129,9 @@ int bmx_binary_fc_packed(const uint64_t* xp, int64_t ldx_w, const uint64_t* Wp, 
  * of Sec. 2.2.3).  Wp is a matrix of O rows of bmx_conv_weight_row_words(C, KH, KW) words:
  * row o holds filter o, tap (kh, kw) at words (kh*KW + kw)*ceil(C/64) .., word cw of a tap
  * holding channels 64*cw .. 64*cw+63 (missing channels = 0 bits), followed by zero words up
- * to a whole register chunk, and for some K by the same filter expanded into matrix-core
- * operands (the rest of the row).  This K order (tap-major, channel-minor), the row length
- * and what lies behind the bits are private to the pair pack/conv; a dot product does not
+ * to a whole register chunk, and for some K by two words of per-filter constants.  This K
+ * order (tap-major, channel-minor), the row length and what lies behind the bits are private
+ * to the pair pack/conv; a dot product does not
  * depend on a permutation applied to both operands.
  * bmx_conv_weight_row_words returns the row length in words (0 if KH, KW or C are outside
  * the supported set); the caller allocates O times that many words. */

@@ -39,16 +39,15 @@ __host__ __device__ static inline int64_t conv_weight_bits_words(int64_t kwords)
   const int ch = conv_weight_chunk_dwords(kwords);
   return ceil_div(2 * kwords, ch) * ch / 2;
 }
-// For the K the matrix-core convolution kernel takes (9, 18 or 36 words) a row carries, behind
-// its chunk-padded bits, the same filter already expanded to FP4 operands: for word j and half
-// h the four dwords (half >> d) & 0x11111111, d = 0..3 (16 bytes at dword 2 * bits_words +
-// 8 * j + 4 * h), then the float K - 2 * popcount(filter), then a pad word: the weights are
-// packed offline (Sec. 2.2.3), so the expansion costs nothing per layer call.
-__host__ __device__ static inline bool conv_weight_has_fp4(int64_t kwords) {
+// For the K the short-K matrix-core convolution kernel takes (9, 18 or 36 words) a row carries,
+// behind its chunk-padded bits, two more words: the float K - 2 * popcount(filter) in the first
+// dword, zeros after it (the kernel's epilogue constant, computed once with the offline weight
+// pack of Sec. 2.2.3; rows stay a whole number of 16 bytes).
+__host__ __device__ static inline bool conv_weight_short_k(int64_t kwords) {
   return kwords == 9 || kwords == 18 || kwords == 36;
 }
 __host__ __device__ static inline int64_t conv_weight_row_words(int64_t kwords) {
-  return conv_weight_bits_words(kwords) + (conv_weight_has_fp4(kwords) ? 4 * kwords + 2 : 0);
+  return conv_weight_bits_words(kwords) + (conv_weight_short_k(kwords) ? 2 : 0);
 }
 
 // pack.hip -------------------------------------------------------------------
@@ -111,7 +110,7 @@ bool launch_plane_gemm_mfma(const uint64_t* planes_rows, int64_t lda_w, int bits
 bool launch_conv_mfma(const uint64_t* Xp, int Nimg, int C, int H, int W, const uint64_t* Wp, int O, int KH,
                       int KW, int stride, int pad, const float* alpha, int32_t* out_i32, float* out_f32,
                       hipStream_t s, hipError_t* err);
-// conv_mfma.hip: the convolution on the FP4 matrix cores with the pre-expanded filters of a
+// conv_mfma.hip: the convolution on the FP4 matrix cores with the expanded filters of a
 // workgroup in LDS (K of 9, 18 or 36 words).  Returns false outside its domain.  With out_bits
 // the result leaves as the packed image of the next convolution (halo out_pad, written too):
 // bit o = (alpha[o] * dot >= thr[o]), thr null = 0.

@@ -279,13 +279,13 @@ hipError_t launch_binary_conv2d(const uint64_t* Xp, int N, int C, int H, int W, 
   if (path == 1 && !stationary_ok) path = 0;
   if (path == 2 && !image32) path = 0;
   if (path == 0) path = stationary_ok ? 1 : (image32 ? 2 : 3);
-  // K of 9, 18 or 36 words: the matrix-core kernel with the pre-expanded filters in LDS.
+  // K of 9, 18 or 36 words: the matrix-core kernel with the expanded filters in LDS.
   // Measured with inputs and outputs rotating through HBM, against the stationary kernel:
   // 6.4 against 6.7 us on 16 x 64 x 56 x 56 -> 64 filters, 17.0 against 24.4 us on four times
   // the batch, 9.6 against 10.9 us on 8 x 64 x 56 x 56 -> 256, 6.3 against 7.9 us on
   // 16 x 128 x 28 x 28 -> 128; at 36 words 15.6 against 16.8 us for the GEMM-shaped matrix-core
   // kernel (64 x 256 x 14 x 14 -> 256) and 8.2 against 8.6 us at stride 2.
-  if ((conv_path == 5 || (conv_path == 0 && conv_weight_has_fp4(kwords))) && gemm_engine != 1) {
+  if ((conv_path == 5 || (conv_path == 0 && conv_weight_short_k(kwords))) && gemm_engine != 1) {
     hipError_t err = hipSuccess;
     if (launch_conv_mfma_ws(Xp, N, C, H, W, Wp, O, KH, KW, stride, pad, alpha, out_i32, out_f32, nullptr, nullptr, 0,
                             s, &err))

@@ -7,10 +7,9 @@
 // v_mfma_scale_f32_32x32x64_f8f6f4 with both operands FP4: a bit becomes a nibble of code 1
 // (0.5), the block scales of 2 make it 1.0, products and fp32 sums are exact integers.
 //
-// Shape.  The filters arrive already expanded (the weight pack does it offline, Sec. 2.2.3):
-// a workgroup copies the FP4 operands of its 32 * TM filters into LDS once, and every MFMA
-// step reads its A operand from there (16 bytes per lane), so filters cost no registers and
-// no VALU work.  A wave walks over blocks of 32 output pixels: it fetches the pixels' KW
+// Shape.  A workgroup expands the bits of its 32 * TM filters into FP4 operands in LDS once
+// (a few dozen VALU instructions per thread), and every MFMA step reads its A operand from
+// there (16 bytes per lane), so filters cost no registers and no VALU work per pixel block.  A wave walks over blocks of 32 output pixels: it fetches the pixels' KW
 // words (one MFMA step of K = 64 consumes exactly one 64-bit word: lane (r, h) supplies half
 // h of the word of pixel r), expands them (8 VALU instructions per word) and issues KW * TM
 // MFMAs.  Lanes run along pixels (operand B), so the NCHW stores are two 128-byte runs per
@@ -35,8 +34,8 @@ constexpr int kMaxWsWords = 36;
 
 struct WsParams {
   const uint64_t* Xp;  // halo-padded packed image
-  const uint32_t* Wp;  // [O][ld_dw] dwords: bits, then the FP4 section at dword fp4_dw
-  int ld_dw, fp4_dw;
+  const uint32_t* Wp;  // [O][ld_dw] dwords: the filter's bits, at dword c0_dw the float K - 2 * popcount
+  int ld_dw, c0_dw;
   const float* alpha;  // [O] or null
   int32_t* out_i32;
   float* out_f32;
@@ -91,7 +90,8 @@ __device__ __forceinline__ PixelBlock locate(const WsParams& p, int b, int r) {
   return pb;
 }
 
-// LDS.  Filters: row i of the workgroup's block holds its 8 * KW expanded dwords, the float
+// LDS.  Filters: row i of the workgroup's block holds its 8 * KW expanded dwords (for word j
+// and half h the four dwords (half >> d) & 0x11111111 at 8 j + 4 h + d), the float
 // K - 2 * popcount and alpha; the row stride of 8 * KW + 4 dwords (4, 12 or 20 mod 32) lets
 // eight lanes read eight different bank groups with one 16-byte read each.
 // Pixels: a wave-private tile [32 pixels][KW words] through which the words, fetched with
@@ -175,32 +175,40 @@ conv_mfma_ws_kernel(const WsParams p) {
     }
   }
 
-  // ---- the workgroup's filters: 16-byte pieces, neighbouring threads on neighbouring pieces;
-  // all of a thread's loads are issued before the first is written to LDS (one after the
-  // other, every piece would cost a full memory round trip: 6 of 9 us at K = 36 words)
-  constexpr int kPieces = 32 * TM * (2 * KW + 1);
-  constexpr int kCopies = (kPieces + 255) / 256;
+  // ---- the workgroup's filters: neighbouring threads on neighbouring words; all of a thread's
+  // loads are issued before the first is written to LDS (one after the other, every load
+  // would cost a full memory round trip: 6 of 9 us at K = 36 words)
+  // one unit = one 64-bit word of a filter's bits, expanded on the way: 8 bytes read, the two
+  // halves' four planes (32 bytes) written
+  constexpr int kUnits = 32 * TM * KW;
+  constexpr int kCopies = (kUnits + 255) / 256;
   {
-    v4i buf[kCopies];
+    uint64_t buf[kCopies];
 #pragma unroll
     for (int t = 0; t < kCopies; ++t) {
-      const int c = min((int)threadIdx.x + 256 * t, kPieces - 1);
-      const int row = c / (2 * KW + 1), piece = c - row * (2 * KW + 1);
+      const int c = min((int)threadIdx.x + 256 * t, kUnits - 1);
+      const int row = c / KW, j = c - row * KW;
       // rows past the last filter repeat it; their results are never stored
-      buf[t] = *(const v4i*)(p.Wp + (int64_t)min(m0 + row, p.O - 1) * p.ld_dw + p.fp4_dw + 4 * piece);
+      buf[t] = *(const uint64_t*)(p.Wp + (int64_t)min(m0 + row, p.O - 1) * p.ld_dw + 2 * j);
     }
-    float myalpha = 1.0f;  // thread t < 32 * TM carries alpha of row t
-    if ((int)threadIdx.x < 32 * TM && p.alpha) myalpha = p.alpha[min(m0 + (int)threadIdx.x, p.O - 1)];
-    float mythr = 0.0f;
-    if (BITS && (int)threadIdx.x < 32 * TM && p.thr) mythr = p.thr[min(m0 + (int)threadIdx.x, p.O - 1)];
+    float myc0 = 0.0f, myalpha = 1.0f, mythr = 0.0f;  // thread t < 32 * TM carries the constants of row t
+    if ((int)threadIdx.x < 32 * TM) {
+      const int m = min(m0 + (int)threadIdx.x, p.O - 1);
+      myc0 = __uint_as_float(p.Wp[(int64_t)m * p.ld_dw + p.c0_dw]);
+      if (p.alpha) myalpha = p.alpha[m];
+      if (BITS && p.thr) mythr = p.thr[m];
+    }
 #pragma unroll
     for (int t = 0; t < kCopies; ++t) {
       const int c = (int)threadIdx.x + 256 * t;
-      const int row = c / (2 * KW + 1), piece = c - row * (2 * KW + 1);
-      if (c < kPieces) *(v4i_alias*)(filt + row * FS + 4 * piece) = buf[t];
+      const int row = c / KW, j = c - row * KW;
+      if (c < kUnits) {
+        *(v4i_alias*)(filt + row * FS + 8 * j) = expand4((uint32_t)buf[t]);
+        *(v4i_alias*)(filt + row * FS + 8 * j + 4) = expand4((uint32_t)(buf[t] >> 32));
+      }
     }
-    __syncthreads();
     if ((int)threadIdx.x < 32 * TM) {
+      filt[(int)threadIdx.x * FS + 8 * KW] = __float_as_uint(myc0);
       filt[(int)threadIdx.x * FS + 8 * KW + 1] = __float_as_uint(myalpha);
       if (BITS) filt[(int)threadIdx.x * FS + 8 * KW + 2] = __float_as_uint(mythr);
     }
@@ -308,7 +316,7 @@ bool conv_mfma_ws_takes(int Nimg, int C, int H, int W, int O, int KH, int KW, in
   const int Wo = (W + 2 * pad - KW) / stride + 1;
   const int Cw = (int)words_for(C);
   const int kwords = KH * KW * Cw;
-  if (!conv_weight_has_fp4(kwords)) return false;
+  if (!conv_weight_short_k(kwords)) return false;
   const int64_t P = (int64_t)Nimg * Ho * Wo;
   if (P >= ((int64_t)1 << 31) || (int64_t)C * KH * KW >= ((int64_t)1 << 22)) return false;
   if ((int64_t)Nimg * (Ho + 2 * out_pad) * (Wo + 2 * out_pad) >= ((int64_t)1 << 31)) return false;
@@ -332,7 +340,7 @@ bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, cons
   p.Xp = Xp;
   p.Wp = (const uint32_t*)Wp;
   p.ld_dw = 2 * (int)conv_weight_row_words(kwords);
-  p.fp4_dw = 2 * (int)conv_weight_bits_words(kwords);
+  p.c0_dw = 2 * (int)conv_weight_bits_words(kwords);
   p.alpha = alpha;
   p.out_i32 = out_i32;
   p.out_f32 = out_f32;

@@ -274,12 +274,11 @@ hipError_t launch_pack_nchw(const float* x, int N, int C, int H, int W, int pad,
 // Offline weight packing for the convolution: one thread per word of the bit section.
 // Wp[o][(kh*KW + kw)*Cw + cw] bit c = (w[o][64cw + c][kh][kw] >= 0); rows are ld words apart
 // and the words between the data and ldb (the chunk-padded bit section) are written as zero.
-// With fp4 set the thread of data word j also writes that word's two expanded halves into the
-// FP4 section behind the bits, and the row's K - 2 * popcount is summed with atomics into the
-// float slot the launcher zeroed.
+// With consts set the row's K - 2 * popcount is summed with atomics into the float slot behind
+// the bits, which the launcher's first kernel set to K.
 __global__ void __launch_bounds__(256)
 pack_conv_weights_kernel(const float* __restrict__ w, int O, int C, int KH, int KW, int Cw, int ld, int ldb,
-                         int fp4, uint64_t* __restrict__ Wp) {
+                         int consts, uint64_t* __restrict__ Wp) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t total = (int64_t)O * ldb;
   if (idx >= total) return;
@@ -302,15 +301,8 @@ pack_conv_weights_kernel(const float* __restrict__ w, int O, int C, int KH, int 
   }
   uint64_t* row = Wp + o * ld;
   row[j] = word;
-  if (fp4 && j < kwords) {
-    uint32_t* e = (uint32_t*)(row + ldb) + 8 * j;
-    for (int h = 0; h < 2; ++h) {
-      const uint32_t half = (uint32_t)(word >> (32 * h));
-      for (int d = 0; d < 4; ++d) e[4 * h + d] = (half >> d) & 0x11111111u;
-    }
-    // (integers below 2^24: the float sum is exact in any order)
-    atomicAdd((float*)((uint32_t*)(row + ldb) + 8 * kwords), -2.0f * (float)__popcll(word));
-  }
+  if (consts && j < kwords)  // (integers below 2^24: the float sum is exact in any order)
+    atomicAdd((float*)(row + ldb), -2.0f * (float)__popcll(word));
 }
 
 // The float slot of every row starts at K (C * KH * KW); the pad word behind it at zero.
@@ -318,7 +310,7 @@ __global__ void __launch_bounds__(256)
 init_conv_weight_consts_kernel(int O, int ld, int ldb, int kwords, float K, uint64_t* __restrict__ Wp) {
   const int o = blockIdx.x * blockDim.x + threadIdx.x;
   if (o >= O) return;
-  uint32_t* c = (uint32_t*)(Wp + (int64_t)o * ld + ldb) + 8 * kwords;
+  uint32_t* c = (uint32_t*)(Wp + (int64_t)o * ld + ldb);
   c[0] = __float_as_uint(K);
   c[1] = c[2] = c[3] = 0;
 }
@@ -328,13 +320,13 @@ hipError_t launch_pack_conv_weights(const float* w, int O, int C, int KH, int KW
   const int Cw = (int)words_for(C);
   const int kwords = KH * KW * Cw;
   const int ld = (int)conv_weight_row_words(kwords), ldb = (int)conv_weight_bits_words(kwords);
-  const int fp4 = conv_weight_has_fp4(kwords) ? 1 : 0;
-  if (fp4)
+  const int consts = conv_weight_short_k(kwords) ? 1 : 0;
+  if (consts)
     hipLaunchKernelGGL(init_conv_weight_consts_kernel, dim3((unsigned)ceil_div(O, 256)), dim3(256), 0, s, O, ld,
                        ldb, kwords, (float)((int64_t)C * KH * KW), Wp);
   const int64_t total = (int64_t)O * ldb;
   hipLaunchKernelGGL(pack_conv_weights_kernel, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, s,
-                     w, O, C, KH, KW, Cw, ld, ldb, fp4, Wp);
+                     w, O, C, KH, KW, Cw, ld, ldb, consts, Wp);
   return hipGetLastError();
 }
 

@@ -553,8 +553,8 @@ def test_conv_short_k_matrix_core(N, C, H, W, O, s, p):
 
 def test_conv_weight_rows_are_zero_padded():
     """Packed filter rows are as long as bmx_conv_weight_row_words says: the bits (zero past the
-    data up to a whole register chunk), and for K of 9, 18 or 36 words the same filter expanded
-    to FP4 nibbles with K - 2 * popcount behind it."""
+    data up to a whole register chunk), and for K of 9, 18 or 36 words two more words holding the
+    float K - 2 * popcount(filter) and zeros."""
     rng = np.random.default_rng(3)
     for (O, C, k) in [(3, 64, 3), (2, 256, 3), (2, 130, 5), (4, 1, 1), (5, 100, 3)]:
         w = rng.standard_normal((O, C, k, k)).astype(np.float32)
@@ -567,13 +567,9 @@ def test_conv_weight_rows_are_zero_padded():
         if kwords not in (9, 18, 36):
             assert (Wp[:, kwords:] == 0).all()
             continue
-        ldb = Wp.shape[1] - 4 * kwords - 2
-        assert ldb >= kwords and (Wp[:, kwords:ldb] == 0).all()
-        fp4 = Wp[:, ldb:ldb + 4 * kwords].copy().view(np.uint32).reshape(O, kwords, 2, 4)
-        halves = ref.copy().view(np.uint32).reshape(O, kwords, 2)
-        for d in range(4):
-            np.testing.assert_array_equal(fp4[:, :, :, d], (halves >> d) & 0x11111111)
-        consts = Wp[:, ldb + 4 * kwords:].copy().view(np.float32)
+        ldb = Wp.shape[1] - 2
+        assert ldb >= kwords and (Wp[:, kwords:ldb] == 0).all() and Wp.shape[1] % 2 == 0
+        consts = Wp[:, ldb:].copy().view(np.float32)
         pc = np.array([[bin(int(v)).count("1") for v in row] for row in ref]).sum(axis=1)
         np.testing.assert_array_equal(consts[:, 0], (C * k * k - 2 * pc).astype(np.float32))
         assert (consts[:, 1:] == 0).all()
