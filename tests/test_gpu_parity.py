@@ -710,3 +710,55 @@ def test_conv_chain_on_packed_images(N, C, H, W, O1, O2, s1):
     assert_f32_close(got.cpu().numpy(), r2f)
     goti = B.binary_conv2d_packed(img, O1, W2p, O2, 3, 3, 1, 1, integer_out=True)
     np.testing.assert_array_equal(goti.cpu().numpy(), r2i)
+
+
+# ------------------------------------------------------------------ seeded random shapes
+def _random_conv_shapes(seed, count):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        k = int(rng.choice([1, 3, 3, 3, 5, 7]))
+        s = int(rng.choice([1, 2]))
+        p = int(rng.integers(0, k))
+        C = int(rng.choice([1, 3, 31, 64, 65, 100, 128, 200, 256, 300]))
+        H, W = int(rng.integers(1, 13)), int(rng.integers(1, 13))
+        if H + 2 * p < k or W + 2 * p < k:
+            continue
+        out.append((int(rng.integers(1, 4)), C, H, W, int(rng.choice([1, 2, 31, 32, 33, 64, 70, 130])), k, s, p))
+    return out
+
+
+@pytest.mark.parametrize("N,C,H,W,O,k,s,p", _random_conv_shapes(2024, 48))
+def test_conv_random_shapes(N, C, H, W, O, k, s, p):
+    """Seeded random layer shapes across every kernel the dispatcher can pick (1x1 to 7x7, one
+    to five channel words, ragged filter and pixel counts): integer output exact, scaled output
+    within tolerance, and the packed-image output equal to packing the float one."""
+    rng = np.random.default_rng(N + 7 * C + 11 * H + 13 * W + 17 * O + k + s + p)
+    x = rng.standard_normal((N, C, H, W)).astype(np.float32)
+    w = rng.standard_normal((O, C, k, k)).astype(np.float32)
+    alpha = oracle.alpha_mean_abs(w)
+    ri, rf = oracle.binary_conv2d(x, w, s, p, alpha)
+    np.testing.assert_array_equal(run_conv(x, w, s, p, integer_out=True), ri)
+    assert_f32_close(run_conv(x, w, s, p, alpha=alpha), rf)
+    Wp, xp = B.pack_conv_weights(dev(w)), B.pack_nchw(dev(x), p)
+    img = B.binary_conv2d_bits(xp, C, Wp, O, k, k, s, p, alpha=dev(alpha), out_pad=1)
+    np.testing.assert_array_equal(host_u64(img), packed_image(rf >= 0.0, 1))
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_fc_random_shapes(seed):
+    """Seeded random fully connected layers through the fp32 entry point (pack + GEMM) and the
+    packed one, every output kind."""
+    rng = np.random.default_rng(900 + seed)
+    batch, fin, fout = int(rng.integers(1, 300)), int(rng.integers(1, 3000)), int(rng.integers(1, 400))
+    x = rng.standard_normal((batch, fin)).astype(np.float32)
+    w = rng.standard_normal((fout, fin)).astype(np.float32)
+    alpha = oracle.alpha_mean_abs(w)
+    ri, rf = oracle.binary_fc(x, w, alpha)
+    Wp = B.binarize_pack(dev(w), 1)
+    np.testing.assert_array_equal(B.binary_fc(dev(x), Wp, integer_out=True).cpu().numpy(), ri)
+    assert_f32_close(B.binary_fc(dev(x), Wp, alpha=dev(alpha)).cpu().numpy(), rf)
+    Xp = B.binarize_pack(dev(x), 1)
+    np.testing.assert_array_equal(B.binary_fc_packed(Xp, fin, Wp, mode="i32").cpu().numpy(), ri)
+    bits = B.binary_fc_packed(Xp, fin, Wp, alpha=dev(alpha), mode="bits")
+    np.testing.assert_array_equal(host_u64(bits), oracle.binarize_pack(rf, 1))
