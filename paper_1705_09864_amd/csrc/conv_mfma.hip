@@ -22,6 +22,7 @@ namespace bmx {
 
 namespace {
 
+typedef unsigned v2u __attribute__((ext_vector_type(2)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
@@ -113,9 +114,8 @@ template <int KW, int TM, int WPS, bool BITS>
 __global__ void __launch_bounds__(256, WPS)
 conv_mfma_ws_kernel(const WsParams p) {
   constexpr int NI = (KW + 1) / 2;  // load instructions per block: two words per pixel each
-  constexpr int FS = Lds<KW>::kFilterStride, PS = Lds<KW>::kPixelStride;
+  constexpr int FS = Lds<KW>::kFilterStride;
   __shared__ __attribute__((aligned(16))) uint32_t filt[32 * TM * FS];
-  __shared__ uint32_t tiles[4][32 * PS];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int r = lane & 31, h = lane >> 5;
@@ -125,7 +125,6 @@ conv_mfma_ws_kernel(const WsParams p) {
   const int cc = min(chunk, p.nchunks);
   const int b0 = (int)(((int64_t)cc * p.nblocks) / p.nchunks);
   const int b1 = (int)(((int64_t)min(cc + 1, p.nchunks) * p.nblocks) / p.nchunks);
-  uint32_t* tile = tiles[wave];
 
   // words 2i + h of the pixel's patch, i = 0 .. NI-1 (the odd KW's last one only for h = 0)
   auto fetch = [&](const PixelBlock& pb, uint64_t (&st)[NI]) {
@@ -133,13 +132,17 @@ conv_mfma_ws_kernel(const WsParams p) {
     for (int i = 0; i < NI; ++i)
       st[i] = (2 * i + 1 < KW || h == 0) ? pb.xb[h ? p.off[2 * i + 1 < KW ? 2 * i + 1 : 0] : p.off[2 * i]] : 0;
   };
-  // staged words -> tile -> dword h of every word of pixel r
+  // staged words -> dword h of every word of pixel r.  Lane (r, 0) holds word 2i and lane (r, 1)
+  // word 2i + 1, each as (lo, hi): swapping the upper half-wave of the lo registers with the
+  // lower half-wave of the hi registers (v_permlane32_swap, one instruction) leaves dword h of
+  // word 2i in the first and dword h of word 2i + 1 in the second.
   auto transpose = [&](const uint64_t (&st)[NI], uint32_t (&raw)[KW]) {
 #pragma unroll
-    for (int i = 0; i < NI; ++i)
-      if (2 * i + 1 < KW || h == 0) *(u64_alias*)(tile + r * PS + 2 * (2 * i + h)) = st[i];
-#pragma unroll
-    for (int j = 0; j < KW; ++j) raw[j] = tile[r * PS + 2 * j + h];
+    for (int i = 0; i < NI; ++i) {
+      const v2u t = __builtin_amdgcn_permlane32_swap((uint32_t)st[i], (uint32_t)(st[i] >> 32), false, false);
+      raw[2 * i] = t[0];
+      if (2 * i + 1 < KW) raw[2 * i + 1] = t[1];
+    }
   };
 
   // the first block's pixel words are requested before anything else (waves of the last
