@@ -26,9 +26,8 @@ typedef unsigned v2u __attribute__((ext_vector_type(2)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
-// 64-bit stores into the dword-typed LDS tiles: without may_alias the compiler is entitled to
-// move the 32-bit reads of the same memory across them (type-based alias analysis)
-typedef uint64_t __attribute__((may_alias)) u64_alias;
+// 16-byte accesses to the dword-typed LDS array: without may_alias the compiler is entitled to
+// move the 32-bit accesses of the same memory across them (type-based alias analysis)
 typedef v4i __attribute__((may_alias)) v4i_alias;
 
 constexpr int kMaxWsWords = 36;
@@ -95,16 +94,13 @@ __device__ __forceinline__ PixelBlock locate(const WsParams& p, int b, int r) {
 // and half h the four dwords (half >> d) & 0x11111111 at 8 j + 4 h + d), the float
 // K - 2 * popcount and alpha; the row stride of 8 * KW + 4 dwords (4, 12 or 20 mod 32) lets
 // eight lanes read eight different bank groups with one 16-byte read each.
-// Pixels: a wave-private tile [32 pixels][KW words] through which the words, fetched with
-// neighbouring lanes on neighbouring addresses (lane (r, hh) takes word 2i + hh of pixel r;
-// a load in which every lane gathers its own pixel's words costs the memory pipeline one
-// access per lane), are turned into the MFMA's order (dword h of every word of pixel r).  Its
-// row stride is 2 * odd dwords, free of bank conflicts beyond the two-way one of 64 lanes
-// on 32 banks.
+// Pixels need no LDS: the words are fetched with neighbouring lanes on neighbouring addresses
+// (lane (r, hh) takes word 2i + hh of pixel r; a load in which every lane gathers its own
+// pixel's words costs the memory pipeline one access per lane) and reach the MFMA's order
+// (dword h of every word of pixel r) by a swap between the half-waves, see `transpose`.
 template <int KW>
 struct Lds {
-  static constexpr int kFilterStride = 8 * KW + 4;                       // dwords
-  static constexpr int kPixelStride = ((KW % 2) ? 2 * KW : 2 * KW + 2);  // dwords; 2 * odd
+  static constexpr int kFilterStride = 8 * KW + 4;  // dwords
 };
 
 // WPS: waves per SIMD the register allocation is held to.
