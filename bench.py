@@ -403,7 +403,7 @@ def main():
             oq = torch.empty((200, 64, 8, 8), dtype=torch.float32, device="cuda")
             wsq = torch.empty(B.workspace_bytes(B.OP_BINARY_CONV2D, (200, cin, 12, 12, 64, 5, 5, 1, 0)),
                               dtype=torch.uint8, device="cuda")
-            other["paper_sec3_1_conv5x5_cin%d_call" % cin] = (alu if cin == 64 else mfma)(
+            other["paper_sec3_1_conv5x5_cin%d_call" % cin] = mfma(
                 2.0 * 64 * 12800 * 25 * cin, kernel_us(
                     lambda: B.binary_conv2d(xq, Wq, 64, 5, 5, 1, 0, alpha=alq, out=oq, workspace=wsq)))
 

@@ -551,12 +551,32 @@ def test_conv_short_k_matrix_core(N, C, H, W, O, s, p):
             np.testing.assert_array_equal(run_conv(x, w, s, p), ri.astype(np.float32))
 
 
+@pytest.mark.parametrize("N,C,H,W,O,s,p", [(1, 1, 5, 5, 1, 1, 0), (2, 64, 12, 12, 64, 1, 0), (3, 20, 9, 11, 70, 2, 2),
+                                           (200, 64, 12, 12, 64, 1, 0), (2, 50, 30, 17, 33, 1, 4)])
+def test_conv_short_k_matrix_core_5x5(N, C, H, W, O, s, p):
+    """5 x 5 kernels over one channel word (K = 25 words, the first point of the paper's
+    Sec. 3.1 sweep) on the same kernel: an odd word count, several blocks per wave, every
+    output kind."""
+    rng = np.random.default_rng(N + 10 * C + 100 * H + 1000 * O + s + p)
+    x = rng.standard_normal((N, C, H, W)).astype(np.float32)
+    w = rng.standard_normal((O, C, 5, 5)).astype(np.float32)
+    alpha = oracle.alpha_mean_abs(w)
+    ri, rf = oracle.binary_conv2d(x, w, s, p, alpha)
+    for per_wave in (0, 3, 101):
+        with tuned(k5=5, k1=per_wave):
+            np.testing.assert_array_equal(run_conv(x, w, s, p, integer_out=True), ri)
+            assert_f32_close(run_conv(x, w, s, p, alpha=alpha), rf)
+    Wp, xp = B.pack_conv_weights(dev(w)), B.pack_nchw(dev(x), p)
+    img = B.binary_conv2d_bits(xp, C, Wp, O, 5, 5, s, p, alpha=dev(alpha), out_pad=2)
+    np.testing.assert_array_equal(host_u64(img), packed_image(rf >= 0.0, 2))
+
+
 def test_conv_weight_rows_are_zero_padded():
     """Packed filter rows are as long as bmx_conv_weight_row_words says: the bits (zero past the
     data up to a whole register chunk), and for K of 9, 18 or 36 words two more words holding the
-    float K - 2 * popcount(filter) and zeros."""
+    float K - 2 * popcount(filter) and zeros (also for 25 words)."""
     rng = np.random.default_rng(3)
-    for (O, C, k) in [(3, 64, 3), (2, 256, 3), (2, 130, 5), (4, 1, 1), (5, 100, 3)]:
+    for (O, C, k) in [(3, 64, 3), (2, 256, 3), (2, 130, 5), (4, 1, 1), (5, 100, 3), (3, 40, 5)]:
         w = rng.standard_normal((O, C, k, k)).astype(np.float32)
         Wp = host_u64(B.pack_conv_weights(dev(w)))
         kwords = k * k * ((C + 63) // 64)
@@ -564,7 +584,7 @@ def test_conv_weight_rows_are_zero_padded():
         ref = oracle.binarize_pack(np.transpose(w, (0, 2, 3, 1)).reshape(O * k * k, C), 1)
         ref = ref.reshape(O, kwords)
         np.testing.assert_array_equal(Wp[:, :kwords], ref)
-        if kwords not in (9, 18, 36):
+        if kwords not in (9, 18, 25, 36):
             assert (Wp[:, kwords:] == 0).all()
             continue
         ldb = Wp.shape[1] - 2
