@@ -50,6 +50,7 @@ def test_workspace_query():
     assert B.workspace_bytes(B.OP_BINARY_CONV2D_BITS, (2, 64, 8, 8, 5, 5, 5, 1, 2, 1)) == 0   # 25 words too
     assert B.workspace_bytes(B.OP_BINARY_CONV2D_BITS, (2, 65, 8, 8, 5, 5, 5, 1, 2, 1)) == 2 * 5 * 8 * 8 * 4
     assert B.workspace_bytes(B.OP_BINARY_CONV2D_BITS, (2, 300, 8, 8, 5, 3, 3, 1, 1, 1)) == 2 * 5 * 8 * 8 * 4
+    assert B.workspace_bytes(B.OP_BINARY_CONV2D_BITS, (2, 150, 8, 8, 5, 3, 3, 1, 1, 1)) == 0   # 27 words
     assert B.workspace_bytes(B.OP_BINARY_CONV2D_BITS, (2, 64, 8, 8, 5, 3, 3, 1, 1, 7)) == 0   # out_pad out of range
     assert B.workspace_bytes(B.OP_BINARY_CONV2D_BITS, (2, 64, 8, 8, 5, 3, 3, 1, 1)) == 0      # too few dims
     assert B.workspace_bytes(99, (1, 2, 3)) == 0

@@ -515,7 +515,7 @@ def test_conv_every_path(path):
 
 
 WS_CONV_CASES = [
-    # N, C, H, W, O, s, p   (3x3 with 9, 18 or 36 words of K: the short-K matrix-core kernel)
+    # N, C, H, W, O, s, p   (3x3 with 9, 18, 27 or 36 words of K: the short-K matrix-core kernel)
     (1, 1, 3, 3, 1, 1, 0),
     (2, 3, 5, 5, 4, 1, 1),
     (1, 20, 8, 5, 3, 2, 1),
@@ -528,6 +528,8 @@ WS_CONV_CASES = [
     (1, 256, 14, 14, 19, 1, 2),
     (5, 200, 9, 9, 256, 1, 1),
     (64, 256, 14, 14, 40, 2, 1),
+    (2, 192, 14, 14, 70, 1, 1),
+    (3, 130, 9, 11, 33, 2, 1),
 ]
 
 
@@ -576,7 +578,7 @@ def test_conv_weight_rows_are_zero_padded():
     data up to a whole register chunk), and for K of 9, 18 or 36 words two more words holding the
     float K - 2 * popcount(filter) and zeros (also for 25 words)."""
     rng = np.random.default_rng(3)
-    for (O, C, k) in [(3, 64, 3), (2, 256, 3), (2, 130, 5), (4, 1, 1), (5, 100, 3), (3, 40, 5)]:
+    for (O, C, k) in [(3, 64, 3), (2, 256, 3), (2, 130, 5), (4, 1, 1), (5, 100, 3), (3, 40, 5), (3, 130, 3)]:
         w = rng.standard_normal((O, C, k, k)).astype(np.float32)
         Wp = host_u64(B.pack_conv_weights(dev(w)))
         kwords = k * k * ((C + 63) // 64)
@@ -584,7 +586,7 @@ def test_conv_weight_rows_are_zero_padded():
         ref = oracle.binarize_pack(np.transpose(w, (0, 2, 3, 1)).reshape(O * k * k, C), 1)
         ref = ref.reshape(O, kwords)
         np.testing.assert_array_equal(Wp[:, :kwords], ref)
-        if kwords not in (9, 18, 25, 36):
+        if kwords not in (9, 18, 25, 27, 36):
             assert (Wp[:, kwords:] == 0).all()
             continue
         ldb = Wp.shape[1] - 2
@@ -675,7 +677,7 @@ def packed_image(bits_nchw, out_pad):
 
 CONV_BITS_CASES = [c + (op,) for c, op in zip(
     [(N, C, H, W, O, 3, s, p) for (N, C, H, W, O, s, p) in WS_CONV_CASES] + CONV_CASES,
-    [1, 0, 2, 1, 3, 1, 0, 1, 2, 1, 1, 6] + [1, 0, 1, 2, 1, 0, 1, 1, 3, 1, 1, 0, 2])]
+    [1, 0, 2, 1, 3, 1, 0, 1, 2, 1, 1, 6, 1, 2] + [1, 0, 1, 2, 1, 0, 1, 1, 3, 1, 1, 0, 2])]
 
 
 @pytest.mark.parametrize("N,C,H,W,O,k,s,p,out_pad", CONV_BITS_CASES)
