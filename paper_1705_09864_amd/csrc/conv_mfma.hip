@@ -30,7 +30,7 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 // move the 32-bit accesses of the same memory across them (type-based alias analysis)
 typedef v4i __attribute__((may_alias)) v4i_alias;
 
-constexpr int kMaxWsWords = 36;
+constexpr int kMaxWsWords = 50;
 
 struct WsParams {
   const uint64_t* Xp;  // halo-padded packed image
@@ -375,7 +375,7 @@ bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, cons
   // the blocks dealt out evenly: every workgroup copies its filters once
   // and no CU is left with a second round of a few workgroups (configuration 4: 11.5 -> 10.8 us,
   // 64 x 128 x 28 x 28: 12.2 -> 10.1 us).
-  const int resident_waves = 256 * 4 * (kwords == 9 ? 4 : kwords == 36 ? 2 : 3);
+  const int resident_waves = 256 * 4 * (kwords == 9 ? 4 : kwords >= 36 ? 2 : 3);
   p.nchunks = (int)std::min<int64_t>(p.nblocks, std::max(1, resident_waves / m_tiles));
   if (conv_filters_per_wave >= 100) p.nchunks = std::min(p.nblocks, conv_filters_per_wave);  // (tuning hook reused: chunks)
   else if (conv_filters_per_wave > 0) p.nchunks = (int)ceil_div(p.nblocks, conv_filters_per_wave);  // (or blocks per wave)
@@ -384,6 +384,7 @@ bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, cons
     else if (kwords == 18) launch_ws<18, 1, 3, true>(p, m_tiles, s);
     else if (kwords == 25) launch_ws<25, 1, 3, true>(p, m_tiles, s);
     else if (kwords == 27) launch_ws<27, 1, 3, true>(p, m_tiles, s);
+    else if (kwords == 50) launch_ws<50, 1, 2, true>(p, m_tiles, s);
     else launch_ws<36, 1, 2, true>(p, m_tiles, s);
   } else if (kwords == 9) {
     if (TM == 2) launch_ws<9, 2, 2>(p, m_tiles, s);
@@ -394,6 +395,8 @@ bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, cons
     launch_ws<25, 1, 3>(p, m_tiles, s);
   } else if (kwords == 27) {
     launch_ws<27, 1, 3>(p, m_tiles, s);
+  } else if (kwords == 50) {
+    launch_ws<50, 1, 2>(p, m_tiles, s);
   } else {
     launch_ws<36, 1, 2>(p, m_tiles, s);
   }

@@ -48,7 +48,7 @@ def test_workspace_query():
     assert B.workspace_bytes(B.OP_BINARY_CONV2D_BITS, (16, 64, 56, 56, 64, 3, 3, 1, 1, 1)) == 0
     assert B.workspace_bytes(B.OP_BINARY_CONV2D_BITS, (2, 256, 14, 14, 40, 3, 3, 2, 1, 0)) == 0
     assert B.workspace_bytes(B.OP_BINARY_CONV2D_BITS, (2, 64, 8, 8, 5, 5, 5, 1, 2, 1)) == 0   # 25 words too
-    assert B.workspace_bytes(B.OP_BINARY_CONV2D_BITS, (2, 65, 8, 8, 5, 5, 5, 1, 2, 1)) == 2 * 5 * 8 * 8 * 4
+    assert B.workspace_bytes(B.OP_BINARY_CONV2D_BITS, (2, 129, 8, 8, 5, 5, 5, 1, 2, 1)) == 2 * 5 * 8 * 8 * 4
     assert B.workspace_bytes(B.OP_BINARY_CONV2D_BITS, (2, 300, 8, 8, 5, 3, 3, 1, 1, 1)) == 2 * 5 * 8 * 8 * 4
     assert B.workspace_bytes(B.OP_BINARY_CONV2D_BITS, (2, 150, 8, 8, 5, 3, 3, 1, 1, 1)) == 0   # 27 words
     assert B.workspace_bytes(B.OP_BINARY_CONV2D_BITS, (2, 64, 8, 8, 5, 3, 3, 1, 1, 7)) == 0   # out_pad out of range
@@ -137,7 +137,7 @@ def test_conv_validation():
 def test_conv_bits_validation():
     f = B.lib().bmx_binary_conv2d_bits
     big = 1 << 24
-    args = dict(N=2, C=65, H=8, W=8, O=4, KH=5, KW=5, s=1, p=1, op=1)
+    args = dict(N=2, C=129, H=8, W=8, O=4, KH=5, KW=5, s=1, p=1, op=1)
 
     def call(xp=P, Wp=P, alpha=NULL, thr=NULL, out=P, ws=P, wsb=big, **kw):
         a = dict(args, **kw)
@@ -154,7 +154,7 @@ def test_conv_bits_validation():
     assert call(Wp=NULL) == E_NULL
     assert call(out=NULL) == E_NULL
     assert call(N=0) == OK
-    # 5 x 5 over two channel words goes through the fp32 result: the workspace is checked before any launch
+    # 5 x 5 over three channel words goes through the fp32 result: the workspace is checked before any launch
     assert call(ws=NULL) == E_WS
     assert call(wsb=64) == E_WS
 

@@ -554,11 +554,12 @@ def test_conv_short_k_matrix_core(N, C, H, W, O, s, p):
 
 
 @pytest.mark.parametrize("N,C,H,W,O,s,p", [(1, 1, 5, 5, 1, 1, 0), (2, 64, 12, 12, 64, 1, 0), (3, 20, 9, 11, 70, 2, 2),
-                                           (200, 64, 12, 12, 64, 1, 0), (2, 50, 30, 17, 33, 1, 4)])
+                                           (200, 64, 12, 12, 64, 1, 0), (2, 50, 30, 17, 33, 1, 4),
+                                           (2, 100, 13, 9, 40, 1, 2), (200, 128, 12, 12, 64, 1, 0)])
 def test_conv_short_k_matrix_core_5x5(N, C, H, W, O, s, p):
-    """5 x 5 kernels over one channel word (K = 25 words, the first point of the paper's
-    Sec. 3.1 sweep) on the same kernel: an odd word count, several blocks per wave, every
-    output kind."""
+    """5 x 5 kernels over one or two channel words (K = 25 and 50 words, the first two points of
+    the paper's Sec. 3.1 sweep) on the same kernel: an odd word count, several blocks per wave,
+    every output kind."""
     rng = np.random.default_rng(N + 10 * C + 100 * H + 1000 * O + s + p)
     x = rng.standard_normal((N, C, H, W)).astype(np.float32)
     w = rng.standard_normal((O, C, 5, 5)).astype(np.float32)
@@ -578,7 +579,7 @@ def test_conv_weight_rows_are_zero_padded():
     data up to a whole register chunk), and for K of 9, 18 or 36 words two more words holding the
     float K - 2 * popcount(filter) and zeros (also for 25 words)."""
     rng = np.random.default_rng(3)
-    for (O, C, k) in [(3, 64, 3), (2, 256, 3), (2, 130, 5), (4, 1, 1), (5, 100, 3), (3, 40, 5), (3, 130, 3)]:
+    for (O, C, k) in [(3, 64, 3), (2, 256, 3), (2, 130, 5), (4, 1, 1), (5, 100, 3), (3, 40, 5), (3, 130, 3), (3, 70, 5)]:
         w = rng.standard_normal((O, C, k, k)).astype(np.float32)
         Wp = host_u64(B.pack_conv_weights(dev(w)))
         kwords = k * k * ((C + 63) // 64)
@@ -586,7 +587,7 @@ def test_conv_weight_rows_are_zero_padded():
         ref = oracle.binarize_pack(np.transpose(w, (0, 2, 3, 1)).reshape(O * k * k, C), 1)
         ref = ref.reshape(O, kwords)
         np.testing.assert_array_equal(Wp[:, :kwords], ref)
-        if kwords not in (9, 18, 25, 27, 36):
+        if kwords not in (9, 18, 25, 27, 36, 50):
             assert (Wp[:, kwords:] == 0).all()
             continue
         ldb = Wp.shape[1] - 2
