@@ -44,7 +44,7 @@ __host__ __device__ static inline int64_t conv_weight_bits_words(int64_t kwords)
 // dword, zeros after it (the kernel's epilogue constant, computed once with the offline weight
 // pack of Sec. 2.2.3; rows stay a whole number of 16 bytes).
 __host__ __device__ static inline bool conv_weight_short_k(int64_t kwords) {
-  return kwords == 9 || kwords == 18 || kwords == 25 || kwords == 27 || kwords == 36 || kwords == 50;
+  return kwords == 9 || kwords == 18 || kwords == 25 || kwords == 27 || kwords == 36 || kwords == 49 || kwords == 50;
 }
 __host__ __device__ static inline int64_t conv_weight_row_words(int64_t kwords) {
   return conv_weight_bits_words(kwords) + (conv_weight_short_k(kwords) ? 2 : 0);

@@ -384,6 +384,7 @@ bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, cons
     else if (kwords == 18) launch_ws<18, 1, 3, true>(p, m_tiles, s);
     else if (kwords == 25) launch_ws<25, 1, 3, true>(p, m_tiles, s);
     else if (kwords == 27) launch_ws<27, 1, 3, true>(p, m_tiles, s);
+    else if (kwords == 49) launch_ws<49, 1, 2, true>(p, m_tiles, s);
     else if (kwords == 50) launch_ws<50, 1, 2, true>(p, m_tiles, s);
     else launch_ws<36, 1, 2, true>(p, m_tiles, s);
   } else if (kwords == 9) {
@@ -395,6 +396,8 @@ bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, cons
     launch_ws<25, 1, 3>(p, m_tiles, s);
   } else if (kwords == 27) {
     launch_ws<27, 1, 3>(p, m_tiles, s);
+  } else if (kwords == 49) {
+    launch_ws<49, 1, 2>(p, m_tiles, s);
   } else if (kwords == 50) {
     launch_ws<50, 1, 2>(p, m_tiles, s);
   } else {

@@ -574,12 +574,30 @@ def test_conv_short_k_matrix_core_5x5(N, C, H, W, O, s, p):
     np.testing.assert_array_equal(host_u64(img), packed_image(rf >= 0.0, 2))
 
 
+@pytest.mark.parametrize("N,C,H,W,O,s,p", [(1, 1, 7, 7, 1, 1, 0), (2, 64, 15, 14, 70, 1, 3), (3, 3, 40, 33, 64, 2, 3)])
+def test_conv_short_k_matrix_core_7x7(N, C, H, W, O, s, p):
+    """7 x 7 kernels over one channel word (K = 49 words; the first layer of a ResNet has this
+    shape class) on the short-K kernel, forced, several blocks per wave."""
+    rng = np.random.default_rng(N + 10 * C + 100 * H + 1000 * O + s + p)
+    x = rng.standard_normal((N, C, H, W)).astype(np.float32)
+    w = rng.standard_normal((O, C, 7, 7)).astype(np.float32)
+    alpha = oracle.alpha_mean_abs(w)
+    ri, rf = oracle.binary_conv2d(x, w, s, p, alpha)
+    for per_wave in (0, 2, 101):
+        with tuned(k5=5, k1=per_wave):
+            np.testing.assert_array_equal(run_conv(x, w, s, p, integer_out=True), ri)
+            assert_f32_close(run_conv(x, w, s, p, alpha=alpha), rf)
+    Wp, xp = B.pack_conv_weights(dev(w)), B.pack_nchw(dev(x), p)
+    img = B.binary_conv2d_bits(xp, C, Wp, O, 7, 7, s, p, alpha=dev(alpha), out_pad=1)
+    np.testing.assert_array_equal(host_u64(img), packed_image(rf >= 0.0, 1))
+
+
 def test_conv_weight_rows_are_zero_padded():
     """Packed filter rows are as long as bmx_conv_weight_row_words says: the bits (zero past the
     data up to a whole register chunk), and for K of 9, 18 or 36 words two more words holding the
     float K - 2 * popcount(filter) and zeros (also for 25 words)."""
     rng = np.random.default_rng(3)
-    for (O, C, k) in [(3, 64, 3), (2, 256, 3), (2, 130, 5), (4, 1, 1), (5, 100, 3), (3, 40, 5), (3, 130, 3), (3, 70, 5)]:
+    for (O, C, k) in [(3, 64, 3), (2, 256, 3), (2, 130, 5), (4, 1, 1), (5, 100, 3), (3, 40, 5), (3, 130, 3), (3, 70, 5), (2, 20, 7)]:
         w = rng.standard_normal((O, C, k, k)).astype(np.float32)
         Wp = host_u64(B.pack_conv_weights(dev(w)))
         kwords = k * k * ((C + 63) // 64)
@@ -587,7 +605,7 @@ def test_conv_weight_rows_are_zero_padded():
         ref = oracle.binarize_pack(np.transpose(w, (0, 2, 3, 1)).reshape(O * k * k, C), 1)
         ref = ref.reshape(O, kwords)
         np.testing.assert_array_equal(Wp[:, :kwords], ref)
-        if kwords not in (9, 18, 25, 27, 36, 50):
+        if kwords not in (9, 18, 25, 27, 36, 49, 50):
             assert (Wp[:, kwords:] == 0).all()
             continue
         ldb = Wp.shape[1] - 2
