@@ -183,9 +183,8 @@ int bmx_binary_conv2d_packed(const uint64_t* xp, int N, int C, int H, int W, con
  *   workspace >= bmx_workspace_bytes(BMX_OP_BINARY_CONV2D_BITS, {N,C,H,W,O,KH,KW,stride,pad,
  *          out_pad}, 10): 0 where the convolution kernel writes the bits itself (3 x 3 kernels
  *          over at most 256 channels, 5 x 5 over at most 128, 7 x 7 over at most 64; Wp 16-byte
- *          aligned),
- *          else room for the fp32 result, which then passes through the channel pack with the
- *          same compare. */
+ *          aligned), else room for the fp32 result, which then passes through the channel pack
+ *          with the same compare. */
 int bmx_binary_conv2d_bits(const uint64_t* xp, int N, int C, int H, int W, const uint64_t* Wp, int O,
                            int KH, int KW, int stride, int pad, const float* alpha, const float* thr,
                            uint64_t* out_xp, int out_pad, void* workspace, size_t workspace_bytes,
