@@ -11,8 +11,11 @@
  *     throws or aborts.  All argument checks run on the host before any launch;
  *     on an error return no kernel was launched and no output was touched.
  *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
- *     allocates nothing and keeps no state between calls.  Scratch memory is
- *     passed in by the caller (`workspace`, sized with bmx_workspace_bytes).
+ *     allocates nothing.  Scratch memory is passed in by the caller (`workspace`,
+ *     sized with bmx_workspace_bytes).
+ *   - Results never depend on earlier calls.  The library does hold process-wide
+ *     state of one kind, which does not change a result: the kernel-selection
+ *     settings of bmx_tune_set (a measurement and test hook, see there).
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
  *     are asynchronous on it; the caller synchronises.
  *   - Inputs and outputs must not overlap.
@@ -47,7 +50,7 @@ extern "C" {
 #define BMX_OK 0
 #define BMX_ERR_NULL (-1)        /* a required pointer is NULL */
 #define BMX_ERR_SHAPE (-2)       /* negative size, K <= 0, K >= 2^24, empty conv output, or more
-                                    than 2^31 - 1 output pixels / 65535 images / 2^18 filters */
+                                    than 2^31 - 1 output pixels / 65535 images / 262140 filters */
 #define BMX_ERR_LD (-3)          /* a leading dimension is smaller than the row it must hold */
 #define BMX_ERR_ALIGN (-4)       /* pointer not aligned (packed: 8 bytes, fp32/int32: 4 bytes) */
 #define BMX_ERR_UNSUPPORTED (-5) /* pack_dim, kernel size, stride, bit width outside the contract */
@@ -59,6 +62,7 @@ extern "C" {
 #define BMX_OP_BINARY_CONV2D 2 /* dims = {N, C, H, W, O, KH, KW, stride, pad} */
 #define BMX_OP_QUANT_GEMM 3    /* dims = {M, N, K, bits_a, bits_w} */
 #define BMX_OP_BINARY_CONV2D_BITS 4 /* dims = {N, C, H, W, O, KH, KW, stride, pad, out_pad} */
+#define BMX_OP_XNOR_GEMM_W32 5 /* dims = {M, N, K} */
 
 /* Sign-binarise and bit-pack (Sec. 1: binarisation with the sign function, 64
  * values per word; Sec. 3.1: the per-forward-pass input binarisation step).
@@ -90,6 +94,25 @@ int bmx_xnor_gemm(const uint64_t* A, int64_t lda_w, const uint64_t* B, int64_t l
  * which is what the listing of Sec. 2.2.1 accumulates.  Arguments as for bmx_xnor_gemm. */
 int bmx_xnor_gemm_count(const uint64_t* A, int64_t lda_w, const uint64_t* B, int64_t ldb_w, int32_t* C,
                         int64_t ldc, int M, int N, int K, void* stream);
+
+/* The 32-bit BINARY_WORD flavour (Sec. 2.2.1: 32 values per word on x86 and ARMv7, 64 on x64).
+ * A row of 32-bit words holds element k in bit (k mod 32) of dword floor(k / 32), least
+ * significant bit first, unused tail bits 0; rows are ld_dwords >= ceil(K/32) dwords apart and
+ * 4-byte aligned.  Little-endian, that is byte for byte the 64-bit row, except that a row may end
+ * in (or be strided by) an odd number of dwords and need not start 8-byte aligned.
+ * bmx_widen_words32: copy such rows into the library's 64-bit layout (the missing upper half of
+ *   a last odd dword becomes 0), for any call that takes packed operands.
+ *   in uint32 [rows, ld_dwords];  out uint64 [rows, out_ld_words], out_ld_words >= ceil(K/64).
+ * bmx_xnor_gemm_w32: bmx_xnor_gemm on operands of 32-bit words (the xnor_32 kernel of the
+ *   paper's Sec. 3.1 evaluation).  An operand whose rows are whole 64-bit words already (even
+ *   dword count and stride, 8-byte aligned base) is read in place; any other is widened into
+ *   `workspace` first.  workspace >= bmx_workspace_bytes(BMX_OP_XNOR_GEMM_W32, {M, N, K}, 3),
+ *   16-byte aligned; it may be NULL when both operands are read in place. */
+int bmx_widen_words32(const uint32_t* in, int64_t rows, int64_t K, int64_t ld_dwords, uint64_t* out,
+                      int64_t out_ld_words, void* stream);
+int bmx_xnor_gemm_w32(const uint32_t* A, int64_t lda_dw, const uint32_t* B, int64_t ldb_dw, int32_t* C,
+                      int64_t ldc, int M, int N, int K, void* workspace, size_t workspace_bytes,
+                      void* stream);
 
 /* Binary fully connected layer (Sec. 2, QFullyConnected): binarise + pack the fp32
  * activations, xnor GEMM against pre-packed weights, optional scale.
@@ -182,9 +205,10 @@ int bmx_binary_conv2d_packed(const uint64_t* xp, int N, int C, int H, int W, con
  *          sign of the next layer's zero padding), missing channels 0 bits.  0 <= out_pad <= 6.
  *   workspace >= bmx_workspace_bytes(BMX_OP_BINARY_CONV2D_BITS, {N,C,H,W,O,KH,KW,stride,pad,
  *          out_pad}, 10): 0 where the convolution kernel writes the bits itself (3 x 3 kernels
- *          over at most 256 channels, 5 x 5 over at most 128, 7 x 7 over at most 64; Wp 16-byte
- *          aligned), else room for the fp32 result, which then passes through the channel pack
- *          with the same compare. */
+ *          over at most 256 channels, 5 x 5 over at most 128, 7 x 7 over at most 64), else room
+ *          for the fp32 result, which then passes through the channel pack with the same compare.
+ *          For the shapes whose query answers 0, Wp must be 16-byte aligned (BMX_ERR_ALIGN
+ *          otherwise): a workspace sized by the query is always enough. */
 int bmx_binary_conv2d_bits(const uint64_t* xp, int N, int C, int H, int W, const uint64_t* Wp, int O,
                            int KH, int KW, int stride, int pad, const float* alpha, const float* thr,
                            uint64_t* out_xp, int out_pad, void* workspace, size_t workspace_bytes,
@@ -222,8 +246,11 @@ size_t bmx_workspace_bytes(int op, const int64_t* dims, int ndims);
 
 /* Kernel-selection hook for measurements and for tests that must reach every kernel
  * variant; not part of the layers the paper defines.  Results never depend on it: every
- * engine and shape computes the same integers (Sec. 2.2.2).  Process-wide, not thread safe;
- * value 0 restores the automatic choice.  Returns BMX_ERR_UNSUPPORTED for an unknown key.
+ * engine and shape computes the same integers (Sec. 2.2.2).  The settings are process-wide
+ * state that every later call on any thread sees until they are set back; the hook is not
+ * thread safe and must not run concurrently with any other call of the library.  Value 0
+ * restores the automatic choice; bmx_tune_set(0, 0) restores it for every key at once.
+ * Returns BMX_ERR_UNSUPPORTED for an unknown key.
  *   key 1  filters per wave of the register-stationary convolution kernel; for the short-K
  *          matrix-core kernel, pixel blocks per wave (below 100) or the number of waves the
  *          blocks are dealt out to per filter tile (100 and above)

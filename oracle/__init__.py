@@ -67,6 +67,18 @@ def _f32(a):
     return a
 
 
+def _rows(a):
+    """A 2-D float32 array and its leading dimension in elements.  A view whose rows are further
+    apart than their length (x[:, :K] of a wider buffer) is passed as it is, so that the C
+    functions' leading-dimension arguments are exercised; anything else is made contiguous."""
+    a = np.asarray(a, dtype=np.float32)
+    if a.ndim == 2 and a.shape[0] > 1 and a.strides[1] == 4 and a.strides[0] % 4 == 0 \
+            and a.strides[0] >= 4 * a.shape[1]:
+        return a, a.strides[0] // 4
+    a = np.ascontiguousarray(a)
+    return a, (a.shape[1] if a.ndim == 2 else a.size)
+
+
 def num_threads():
     return int(lib().orc_num_threads())
 
@@ -80,13 +92,13 @@ def sign(x):
 
 def binarize_pack(x, pack_dim=1, out_ld_words=None, fill=0):
     """x: 2-D float32.  Returns uint64 [R, out_ld_words]; words past ceil(K/64) keep ``fill``."""
-    x = _f32(x)
+    x, ldx = _rows(x)
     rows, cols = x.shape
     R, K = (rows, cols) if pack_dim else (cols, rows)
     Kw = (K + 63) // 64
     ld = Kw if out_ld_words is None else int(out_ld_words)
     out = np.full((R, ld), fill, dtype=np.uint64)
-    lib().orc_binarize_pack(_ptr(x), _i64(rows), _i64(cols), _i64(cols), _int(pack_dim),
+    lib().orc_binarize_pack(_ptr(x), _i64(rows), _i64(cols), _i64(ldx), _int(pack_dim),
                             _ptr(out), _i64(ld))
     return out
 
@@ -111,24 +123,24 @@ def xnor_gemm(A, B, K):
 
 
 def alpha_mean_abs(w):
-    w = _f32(w)
-    w2 = w.reshape(w.shape[0], -1)
+    w = np.asarray(w, dtype=np.float32)
+    w2, ldw = _rows(w if w.ndim == 2 else np.ascontiguousarray(w).reshape(w.shape[0], -1))
     alpha = np.empty(w2.shape[0], dtype=np.float32)
-    lib().orc_alpha_mean_abs(_ptr(w2), _i64(w2.shape[0]), _i64(w2.shape[1]), _i64(w2.shape[1]),
+    lib().orc_alpha_mean_abs(_ptr(w2), _i64(w2.shape[0]), _i64(w2.shape[1]), _i64(ldw),
                              _ptr(alpha))
     return alpha
 
 
 def binary_fc(x, w, alpha=None):
     """x: [batch, in], w: [out, in] float32.  Returns (int32 [batch,out], float32 [batch,out])."""
-    x, w = _f32(x), _f32(w)
+    (x, ldx), (w, ldw) = _rows(x), _rows(w)
     batch, fin = x.shape
     fout = w.shape[0]
     assert w.shape[1] == fin
     al = None if alpha is None else _f32(alpha)
     oi = np.empty((batch, fout), dtype=np.int32)
     of = np.empty((batch, fout), dtype=np.float32)
-    lib().orc_binary_fc(_ptr(x), _i64(fin), _ptr(w), _i64(fin), _ptr(al), _i64(batch), _i64(fin),
+    lib().orc_binary_fc(_ptr(x), _i64(ldx), _ptr(w), _i64(ldw), _ptr(al), _i64(batch), _i64(fin),
                         _i64(fout), _ptr(oi), _ptr(of), _i64(fout))
     return oi, of
 
@@ -186,7 +198,7 @@ def quantize(x, bits):
 def quant_gemm(a, w, bits_a, bits_w=1):
     """a: [M,K] in [0,1], w: [N,K] (bits_w = 1: any sign; bits_w > 1: in [-1,1]).  Returns
     (S int32, out float64, out float32), all [M,N]."""
-    a, w = _f32(a), _f32(w)
+    (a, lda), (w, ldw) = _rows(a), _rows(w)
     if bits_w != 1:
         M, K = a.shape
         N = w.shape[0]
@@ -194,7 +206,7 @@ def quant_gemm(a, w, bits_a, bits_w=1):
         S = np.empty((M, N), dtype=np.int32)
         o64 = np.empty((M, N), dtype=np.float64)
         o32 = np.empty((M, N), dtype=np.float32)
-        lib().orc_quant_gemm_kw(_ptr(a), _i64(K), _int(bits_a), _ptr(w), _i64(K), _int(bits_w), _i64(M),
+        lib().orc_quant_gemm_kw(_ptr(a), _i64(lda), _int(bits_a), _ptr(w), _i64(ldw), _int(bits_w), _i64(M),
                                 _i64(N), _i64(K), _ptr(S), _ptr(o64), _ptr(o32), _i64(N))
         return S, o64, o32
     M, K = a.shape
@@ -203,6 +215,6 @@ def quant_gemm(a, w, bits_a, bits_w=1):
     S = np.empty((M, N), dtype=np.int32)
     o64 = np.empty((M, N), dtype=np.float64)
     o32 = np.empty((M, N), dtype=np.float32)
-    lib().orc_quant_gemm(_ptr(a), _i64(K), _int(bits_a), _ptr(w), _i64(K), _i64(M), _i64(N),
+    lib().orc_quant_gemm(_ptr(a), _i64(lda), _int(bits_a), _ptr(w), _i64(ldw), _i64(M), _i64(N),
                          _i64(K), _ptr(S), _ptr(o64), _ptr(o32), _i64(N))
     return S, o64, o32

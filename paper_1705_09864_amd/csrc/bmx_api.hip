@@ -27,11 +27,15 @@ int conv_check(int N, int C, int H, int W, int O, int KH, int KW, int stride, in
   g->Ho = (H + 2 * pad - KH) / stride + 1;
   g->Wo = (W + 2 * pad - KW) / stride + 1;
   g->Cw = (int)bmx::words_for(C);
-  if ((int64_t)N * g->Ho * g->Wo >= ((int64_t)1 << 31) || N > 65535 || O >= (1 << 18))
+  // (filters: the one-thread-per-output kernel puts four of them on a workgroup of grid.y)
+  if ((int64_t)N * g->Ho * g->Wo >= ((int64_t)1 << 31) || N > 65535 || O > 4 * 65535)
     return BMX_ERR_SHAPE;
   if ((int64_t)(H + 2 * pad) * (W + 2 * pad) >= ((int64_t)1 << 31)) return BMX_ERR_SHAPE;
   return BMX_OK;
 }
+
+// 64-bit row length (even: 16-byte rows) that rows of 32-bit words are widened to
+inline int64_t w32_row_words(int64_t K) { return (bmx::words_for(K) + 1) / 2 * 2; }
 
 struct QuantWs {
   size_t planes_off, wb_off, rowsum_off, wrowsum_off, tmp_off, total;
@@ -63,6 +67,11 @@ extern "C" {
 
 // Kernel-selection hook (keys documented at its declaration).
 int bmx_tune_set(int key, int value) {
+  if (key == 0) {  // everything back to the automatic choice
+    bmx::conv_filters_per_wave = bmx::gemm_tune_rows = bmx::gemm_tune_ksplit = bmx::gemm_tune_order = 0;
+    bmx::conv_path = bmx::gemm_engine = bmx::gemm_mfma_ksplit = bmx::gemm_mfma_tile = 0;
+    return BMX_OK;
+  }
   if (key == 1) bmx::conv_filters_per_wave = value;
   else if (key == 2) bmx::gemm_tune_rows = value;
   else if (key == 3) bmx::gemm_tune_ksplit = value;
@@ -118,6 +127,12 @@ size_t bmx_workspace_bytes(int op, const int64_t* dims, int ndims) {
         return 0;  // the convolution kernel writes the bits itself
       const size_t n = dims[0] > 0 ? (size_t)dims[0] : 1;
       return round256(n * (dims[4] > 0 ? dims[4] : 1) * g.Ho * g.Wo * 4);
+    }
+    case BMX_OP_XNOR_GEMM_W32: {
+      if (ndims != 3 || dims[0] < 0 || dims[1] < 0 || dims[2] <= 0 || dims[2] >= kMaxK) return 0;
+      const int64_t ld = w32_row_words(dims[2]);
+      return round256((size_t)(dims[0] > 0 ? dims[0] : 1) * ld * 8) +
+             round256((size_t)(dims[1] > 0 ? dims[1] : 1) * ld * 8);
     }
     case BMX_OP_QUANT_GEMM: {
       if (ndims != 5 || dims[0] < 0 || dims[1] < 0 || dims[2] <= 0 || dims[2] >= kMaxK) return 0;
@@ -185,10 +200,60 @@ int bmx_xnor_gemm_count(const uint64_t* A, int64_t lda_w, const uint64_t* B, int
   return xnor_gemm_checked(A, lda_w, B, ldb_w, C, ldc, M, N, K, stream, true);
 }
 
-int bmx_binary_fc(const float* x, int64_t ldx, const uint64_t* Wp, int64_t ldw_w,
-                  const float* alpha, int batch, int in_features, int out_features,
-                  int32_t* out_i32, float* out_f32, int64_t ldo, void* workspace,
-                  size_t workspace_bytes, void* stream) {
+int bmx_widen_words32(const uint32_t* in, int64_t rows, int64_t K, int64_t ld_dwords, uint64_t* out,
+                      int64_t out_ld_words, void* stream) {
+  if (rows < 0) return BMX_ERR_SHAPE;
+  if (K <= 0 || K >= kMaxK) return BMX_ERR_SHAPE;
+  if (rows == 0) return BMX_OK;
+  if (rows * bmx::words_for(K) >= ((int64_t)1 << 38)) return BMX_ERR_SHAPE;
+  if (!in || !out) return BMX_ERR_NULL;
+  if (ld_dwords < (K + 31) / 32 || out_ld_words < bmx::words_for(K)) return BMX_ERR_LD;
+  if (misaligned(in, 4) || misaligned(out, 8)) return BMX_ERR_ALIGN;
+  return hip_status(bmx::launch_widen_words32(in, rows, K, ld_dwords, out, out_ld_words, (hipStream_t)stream));
+}
+
+int bmx_xnor_gemm_w32(const uint32_t* A, int64_t lda_dw, const uint32_t* B, int64_t ldb_dw, int32_t* C,
+                      int64_t ldc, int M, int N, int K, void* workspace, size_t workspace_bytes,
+                      void* stream) {
+  if (M < 0 || N < 0) return BMX_ERR_SHAPE;
+  if (K <= 0 || K >= kMaxK) return BMX_ERR_SHAPE;
+  if (M == 0 || N == 0) return BMX_OK;
+  if (!A || !B || !C) return BMX_ERR_NULL;
+  const int64_t Kd = ((int64_t)K + 31) / 32;
+  if (lda_dw < Kd || ldb_dw < Kd || ldc < N) return BMX_ERR_LD;
+  if (misaligned(A, 4) || misaligned(B, 4) || misaligned(C, 4)) return BMX_ERR_ALIGN;
+  // An operand whose rows are whole, 8-byte aligned 64-bit words already IS the 64-bit layout
+  // (same bytes); any other (odd dword count or stride, 4-byte aligned base) is widened first.
+  auto direct = [&](const uint32_t* X, int64_t ld) { return !misaligned(X, 8) && (ld & 1) == 0 && (Kd & 1) == 0; };
+  const bool da = direct(A, lda_dw), db = direct(B, ldb_dw);
+  const int64_t ldw = w32_row_words(K);
+  const size_t a_bytes = round256((size_t)M * ldw * 8), b_bytes = round256((size_t)N * ldw * 8);
+  const uint64_t *A64 = (const uint64_t*)A, *B64 = (const uint64_t*)B;
+  int64_t lda_w = lda_dw / 2, ldb_w = ldb_dw / 2;
+  hipStream_t s = (hipStream_t)stream;
+  if (!da || !db) {
+    if (!workspace || workspace_bytes < a_bytes + b_bytes) return BMX_ERR_WORKSPACE;
+    if (misaligned(workspace, 16)) return BMX_ERR_ALIGN;
+  }
+  if (!da) {
+    uint64_t* wa = (uint64_t*)workspace;
+    if (bmx::launch_widen_words32(A, M, K, lda_dw, wa, ldw, s) != hipSuccess) return BMX_ERR_HIP;
+    A64 = wa;
+    lda_w = ldw;
+  }
+  if (!db) {
+    uint64_t* wb = (uint64_t*)((char*)workspace + a_bytes);
+    if (bmx::launch_widen_words32(B, N, K, ldb_dw, wb, ldw, s) != hipSuccess) return BMX_ERR_HIP;
+    B64 = wb;
+    ldb_w = ldw;
+  }
+  return xnor_gemm_checked(A64, lda_w, B64, ldb_w, C, ldc, M, N, K, stream, false);
+}
+
+namespace {
+// Argument checks shared by the two fully connected entry points (zero-sized problems pass).
+int fc_check(const float* x, int64_t ldx, const uint64_t* Wp, int64_t ldw_w, const float* alpha, int batch,
+             int in_features, int out_features, int32_t* out_i32, float* out_f32, int64_t ldo) {
   if (batch < 0 || out_features < 0) return BMX_ERR_SHAPE;
   if (in_features <= 0 || in_features >= kMaxK) return BMX_ERR_SHAPE;
   if (batch == 0 || out_features == 0) return BMX_OK;
@@ -200,19 +265,36 @@ int bmx_binary_fc(const float* x, int64_t ldx, const uint64_t* Wp, int64_t ldw_w
   if (misaligned(x, 4) || misaligned(Wp, 8) || misaligned(alpha, 4) || misaligned(out_i32, 4) ||
       misaligned(out_f32, 4))
     return BMX_ERR_ALIGN;
-  const int64_t dims[3] = {batch, in_features, out_features};
-  const size_t need = bmx_workspace_bytes(BMX_OP_BINARY_FC, dims, 3);
-  if (!workspace || workspace_bytes < need) return BMX_ERR_WORKSPACE;
-  if (misaligned(workspace, 16)) return BMX_ERR_ALIGN;
-  hipStream_t s = (hipStream_t)stream;
-  // activations packed into chunk-padded rows: the scalar side of the GEMM kernel
-  uint64_t* xp = (uint64_t*)workspace;
+  return BMX_OK;
+}
+
+// Pack the activations into chunk-padded rows at xp (the scalar side of the GEMM kernel reads
+// whole chunks), then the GEMM with the epilogue.
+int fc_launch(const float* x, int64_t ldx, const uint64_t* Wp, int64_t ldw_w, const float* alpha, int batch,
+              int in_features, int out_features, int32_t* out_i32, float* out_f32, int64_t ldo, uint64_t* xp,
+              hipStream_t s) {
   const int64_t ldp = bmx::padded_words(in_features);
   hipError_t e = bmx::launch_pack_rows_padded(x, batch, in_features, ldx, xp, ldp, s);
   if (e != hipSuccess) return BMX_ERR_HIP;
   return hip_status(bmx::launch_xnor_gemm((const uint32_t*)xp, true, ldp * 2, Wp, ldw_w, batch,
                                           out_features, in_features, alpha, out_i32, out_f32,
                                           nullptr, nullptr, ldo, s));
+}
+}  // namespace
+
+int bmx_binary_fc(const float* x, int64_t ldx, const uint64_t* Wp, int64_t ldw_w,
+                  const float* alpha, int batch, int in_features, int out_features,
+                  int32_t* out_i32, float* out_f32, int64_t ldo, void* workspace,
+                  size_t workspace_bytes, void* stream) {
+  const int rc = fc_check(x, ldx, Wp, ldw_w, alpha, batch, in_features, out_features, out_i32, out_f32, ldo);
+  if (rc != BMX_OK) return rc;
+  if (batch == 0 || out_features == 0) return BMX_OK;
+  const int64_t dims[3] = {batch, in_features, out_features};
+  const size_t need = bmx_workspace_bytes(BMX_OP_BINARY_FC, dims, 3);
+  if (!workspace || workspace_bytes < need) return BMX_ERR_WORKSPACE;
+  if (misaligned(workspace, 16)) return BMX_ERR_ALIGN;
+  return fc_launch(x, ldx, Wp, ldw_w, alpha, batch, in_features, out_features, out_i32, out_f32, ldo,
+                   (uint64_t*)workspace, (hipStream_t)stream);
 }
 
 int bmx_binary_fc_packed(const uint64_t* xp, int64_t ldx_w, const uint64_t* Wp, int64_t ldw_w,
@@ -291,15 +373,18 @@ int bmx_binary_conv2d_bits(const uint64_t* xp, int N, int C, int H, int W, const
   ConvGeom g;
   const int rc = conv_check(N, C, H, W, O, KH, KW, stride, pad, &g);
   if (rc != BMX_OK) return rc;
-  if (O <= 0) return BMX_ERR_SHAPE;
   if (out_pad < 0 || out_pad > 6) return BMX_ERR_UNSUPPORTED;
   if (N > 65535 || bmx::words_for(O) > 65535 ||
       (int64_t)(g.Ho + 2 * out_pad) * (g.Wo + 2 * out_pad) >= ((int64_t)1 << 31))
     return BMX_ERR_SHAPE;
-  if (N == 0) return BMX_OK;
+  if (N == 0 || O == 0) return BMX_OK;  // an image of zero channels has no words
   if (!xp || !Wp || !out_xp) return BMX_ERR_NULL;
   if (misaligned(xp, 8) || misaligned(Wp, 8) || misaligned(alpha, 4) || misaligned(thr, 4) ||
       misaligned(out_xp, 8))
+    return BMX_ERR_ALIGN;
+  // where the size query answered 0 the kernel that writes the bits itself must run, and it
+  // reads filter rows in 16-byte pieces
+  if (bmx::conv_mfma_ws_takes(N, C, H, W, O, KH, KW, stride, pad, out_pad) && misaligned(Wp, 16))
     return BMX_ERR_ALIGN;
   hipStream_t s = (hipStream_t)stream;
   hipError_t err = hipSuccess;

@@ -59,6 +59,9 @@ hipError_t launch_pack_rows(const float* x, int64_t rows, int64_t cols, int64_t 
 // matrix stride ncol*out_ld.  Serves pack_dim = 0 and the NCHW channel pack.
 hipError_t launch_unpack_pm1(const uint64_t* bits, int64_t rows, int64_t K, int64_t ld_words, float* out,
                              int64_t ldo, hipStream_t s);
+// Rows of ceil(K/32) 32-bit words, ld_dw apart -> rows of ceil(K/64) 64-bit words, out_ld apart.
+hipError_t launch_widen_words32(const uint32_t* in, int64_t rows, int64_t K, int64_t ld_dw, uint64_t* out,
+                                int64_t out_ld, hipStream_t s);
 hipError_t launch_pack_strided(const float* x, int64_t batch, int64_t K, int64_t ncol, int64_t ldx,
                                int64_t batch_stride, uint64_t* out, int64_t out_ld, hipStream_t s);
 // NCHW channel pack into the halo-padded layout xp [N][H+2*pad][W+2*pad][Cw]; the halo is

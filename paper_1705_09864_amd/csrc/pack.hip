@@ -129,6 +129,32 @@ hipError_t launch_unpack_pm1(const uint64_t* bits, int64_t rows, int64_t K, int6
   return hipGetLastError();
 }
 
+// Rows of 32-bit words (the 32-bit BINARY_WORD flavour of Sec. 2.2.1) -> rows of 64-bit words:
+// word w of a row is dwords 2w (low half) and 2w + 1 (high half, zero when the row has an odd
+// number of dwords).  With bits LSB first and little-endian words this moves no bit: element k
+// is bit k % 32 of dword k / 32 and bit k % 64 of word k / 64 alike.  One thread per word.
+__global__ void __launch_bounds__(256)
+widen_words32_kernel(const uint32_t* __restrict__ in, int64_t rows, int64_t Kd, int64_t ld_dw,
+                     uint64_t* __restrict__ out, int64_t out_ld) {
+  const int64_t Kw = (Kd + 1) / 2;
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= rows * Kw) return;
+  const int64_t r = i / Kw, w = i - r * Kw;
+  const uint32_t* row = in + r * ld_dw;
+  const uint32_t lo = row[2 * w];
+  const uint32_t hi = 2 * w + 1 < Kd ? row[2 * w + 1] : 0u;
+  out[r * out_ld + w] = ((uint64_t)hi << 32) | lo;
+}
+
+hipError_t launch_widen_words32(const uint32_t* in, int64_t rows, int64_t K, int64_t ld_dw, uint64_t* out,
+                                int64_t out_ld, hipStream_t s) {
+  const int64_t Kd = (K + 31) / 32;
+  const int64_t total = rows * ((Kd + 1) / 2);
+  hipLaunchKernelGGL(widen_words32_kernel, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, s, in, rows, Kd,
+                     ld_dw, out, out_ld);
+  return hipGetLastError();
+}
+
 // Strided pack (the matrix is stored K x ncol, pack down the columns): a wave packs one
 // word of 64 consecutive columns: lanes span columns, so every load instruction is a
 // coalesced 256-byte read of one K row, and all 64 row loads of a lane are issued before

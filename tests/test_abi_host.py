@@ -149,11 +149,17 @@ def test_conv_bits_validation():
     assert call(op=-1) == E_UNSUP
     assert call(op=7) == E_UNSUP
     assert call(C=0) == E_SHAPE
-    assert call(O=0) == E_SHAPE
+    assert call(O=0) == OK                         # zero counts launch nothing, like everywhere
+    assert call(O=4 * 65535 + 1) == E_SHAPE
     assert call(xp=NULL) == E_NULL
     assert call(Wp=NULL) == E_NULL
     assert call(out=NULL) == E_NULL
     assert call(N=0) == OK
+    # where the size query answers 0 (the kernel that writes the bits itself), the filter rows are
+    # read in 16-byte pieces: an 8-byte aligned Wp is refused, not sent down the other route with
+    # a workspace the query never asked for
+    assert B.workspace_bytes(B.OP_BINARY_CONV2D_BITS, (2, 64, 8, 8, 4, 3, 3, 1, 1, 1)) == 0
+    assert call(C=64, KH=3, KW=3, Wp=P + 8, ws=NULL, wsb=0) == E_ALIGN
     # 5 x 5 over three channel words goes through the fp32 result: the workspace is checked before any launch
     assert call(ws=NULL) == E_WS
     assert call(wsb=64) == E_WS
@@ -178,6 +184,30 @@ def test_quant_and_alpha_validation():
     assert g(P, 0, 8, 8, P, NULL) == OK
 
 
+def test_words32_validation():
+    L = B.lib()
+    f = L.bmx_widen_words32
+    assert f(P, -1, 96, 3, P, 2, NULL) == E_SHAPE
+    assert f(P, 4, 0, 3, P, 2, NULL) == E_SHAPE
+    assert f(P, 0, 96, 3, P, 2, NULL) == OK
+    assert f(NULL, 4, 96, 3, P, 2, NULL) == E_NULL
+    assert f(P, 4, 96, 2, P, 2, NULL) == E_LD          # 96 bits need 3 dwords
+    assert f(P, 4, 96, 3, P, 1, NULL) == E_LD          # and 2 words
+    assert f(P + 2, 4, 96, 3, P, 2, NULL) == E_ALIGN
+    assert f(P, 4, 96, 3, P + 4, 2, NULL) == E_ALIGN
+    g = L.bmx_xnor_gemm_w32
+    assert g(P, 3, P, 3, P, 5, 0, 5, 96, NULL, 0, NULL) == OK
+    assert g(P, 3, P, 3, P, 5, 4, 5, 0, NULL, 0, NULL) == E_SHAPE
+    assert g(P, 2, P, 3, P, 5, 4, 5, 96, P, 1 << 20, NULL) == E_LD
+    assert g(P, 3, P, 3, P, 4, 4, 5, 96, P, 1 << 20, NULL) == E_LD
+    assert g(NULL, 3, P, 3, P, 5, 4, 5, 96, P, 1 << 20, NULL) == E_NULL
+    assert g(P, 3, P, 3, P, 5, 4, 5, 96, NULL, 0, NULL) == E_WS       # odd dword rows must be widened
+    assert g(P, 3, P, 3, P, 5, 4, 5, 96, P, 64, NULL) == E_WS
+    assert g(P + 1, 3, P, 3, P, 5, 4, 5, 96, P, 1 << 20, NULL) == E_ALIGN
+    assert B.workspace_bytes(B.OP_XNOR_GEMM_W32, (4, 5, 96)) == 256 + 256    # 4 x 2 and 5 x 2 words
+    assert B.workspace_bytes(B.OP_XNOR_GEMM_W32, (4, 5, 0)) == 0
+
+
 def test_fc_packed_validation():
     f = B.lib().bmx_binary_fc_packed
     ok = dict(xp=P, ldx=8, Wp=P, ldw=8, alpha=NULL, b=4, fin=512, fout=70, oi=NULL, of=NULL, ob=P, thr=NULL,
@@ -200,3 +230,37 @@ def test_fc_packed_validation():
     assert call(ldo=1) == E_LD                                          # 70 features need 2 words
     assert call(ob=NULL, of=P, ldo=69) == E_LD
     assert call(ob=P + 4) == E_ALIGN and call(xp=P + 4) == E_ALIGN
+
+
+def test_binding_refuses_tensors_the_c_abi_would_misread():
+    """The wrappers see tensors, the C ABI only addresses: a host tensor, a wrong element type or
+    a transposed view must be refused on the host, before any address reaches the library."""
+    import torch
+    x = torch.zeros((4, 128), dtype=torch.float32)             # lives on the host
+    with pytest.raises(ValueError, match="GPU"):
+        B.binarize_pack(x, 1)
+    with pytest.raises(ValueError, match="GPU"):
+        B.xnor_gemm(torch.zeros((4, 2), dtype=torch.int64), torch.zeros((4, 2), dtype=torch.int64), 128)
+    with pytest.raises(ValueError, match="GPU"):
+        B.binary_conv2d(torch.zeros((1, 3, 5, 5)), torch.zeros((2, 10), dtype=torch.int64), 2, 3, 3)
+    with pytest.raises(ValueError, match="torch tensor"):
+        B.alpha_mean_abs([[1.0, 2.0]])
+    # dtype and layout are checked on "meta" tensors here: no GPU in this test, and the checks
+    # must fire before a data pointer is taken
+    for bad, what in ((torch.zeros((4, 128), dtype=torch.float64), "dtype"),
+                      (torch.zeros((128, 4), dtype=torch.float32).t(), "stride")):
+        with pytest.raises(ValueError):
+            B._chk(_FakeCuda(bad), B._F32, "x")
+    ok = _FakeCuda(torch.zeros((4, 200), dtype=torch.float32)[:, :128])   # rows further apart: fine
+    assert B._chk(ok, B._F32, "x") is ok and B._ld(ok) == 200
+
+
+class _FakeCuda:
+    """A host tensor that claims to live on the GPU, to reach the checks behind the device test."""
+
+    def __init__(self, t):
+        self._t = t
+        self.is_cuda = True
+
+    def __getattr__(self, name):
+        return getattr(self._t, name)

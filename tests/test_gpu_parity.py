@@ -50,10 +50,31 @@ def test_pack_rows(rows, K):
 
 def test_pack_rows_special_values():
     v = np.array([0.0, -0.0, 1e-45, -1e-45, 1.1754942e-38, -1.1754942e-38, np.inf, -np.inf,
-                  1.0, -1.0, 3e38, -3e38], dtype=np.float32)
+                  1.0, -1.0, 3e38, -3e38, np.nan, -np.nan, 2.5, -2.5], dtype=np.float32)
     x = np.tile(v, 16)[None, :].copy()
     got = host_u64(B.binarize_pack(dev(x), 1))
     np.testing.assert_array_equal(got, oracle.binarize_pack(x, 1))  # negative denormals stay -1
+    # the pattern itself, from the reading of the sign function: (x >= 0) as an IEEE compare,
+    # so +-0, positive denormals and +inf give 1, NaN of either sign gives 0
+    assert got[0, 0] & np.uint64(0xFFFF) == np.uint64(0b0100_0101_0101_0111)
+    # the same values down a strided column and through the channel pack of a convolution
+    col = np.tile(v, 8)[:, None] * np.ones((1, 3), dtype=np.float32)
+    np.testing.assert_array_equal(host_u64(B.binarize_pack(dev(col), 0)), oracle.binarize_pack(col, 0))
+
+
+def test_conv_special_values_in_the_image():
+    """NaN, +-0, denormals and infinities in a convolution input: the channel pack takes the same
+    IEEE compare as the row pack, and the layer equals the oracle's (which binarises the
+    zero-padded float image element by element)."""
+    v = np.array([0.0, -0.0, 1e-45, -1e-45, np.inf, -np.inf, np.nan, -np.nan, 1.0, -1.0], dtype=np.float32)
+    rng = np.random.default_rng(41)
+    x = rng.choice(v, size=(2, 70, 9, 7)).astype(np.float32)
+    w = rng.standard_normal((5, 70, 3, 3)).astype(np.float32)
+    ri, _ = oracle.binary_conv2d(x, w, 1, 1)
+    np.testing.assert_array_equal(run_conv(x, w, 1, 1, integer_out=True), ri)
+    xp = host_u64(B.pack_nchw(dev(x), 0))
+    rows = np.transpose(x, (0, 2, 3, 1)).reshape(-1, 70)
+    np.testing.assert_array_equal(xp.reshape(-1, 2), oracle.binarize_pack(rows, 1))
 
 
 def test_pack_rows_strided_and_poisoned():
@@ -247,9 +268,10 @@ def test_config2_conv_full():
     alpha = oracle.alpha_mean_abs(c["w"])
     assert_f32_close(B.alpha_mean_abs(dev(c["w"])).cpu().numpy(), alpha)
     ri, rf = oracle.binary_conv2d(c["x"], c["w"], 1, 1, alpha)
-    # automatic (register-stationary popcount kernel at this K), popcount GEMM kernel, FP4 and
-    # int8 matrix cores
-    for choice in (dict(), dict(k5=2), dict(k5=4), dict(k5=4, k7=2)):
+    # automatic (the short-K FP4 matrix-core kernel with its filters in LDS; k5=5 names it),
+    # register-stationary xor/popcount kernel, xor/popcount GEMM kernel, GEMM-shaped FP4 and
+    # int8 matrix-core kernels
+    for choice in (dict(), dict(k5=1), dict(k5=5), dict(k5=2), dict(k5=4), dict(k5=4, k7=2)):
         with tuned(**choice):
             got = run_conv(c["x"], c["w"], 1, 1, alpha=alpha)
             assert got.shape == (16, 64, 56, 56)
@@ -264,9 +286,9 @@ def test_config4_conv_full(stride):
     assert 0.60 < frac_pos < 0.635                     # skewed sign balance, P(|z| >= 0.5) = 0.617
     alpha = oracle.alpha_mean_abs(c["w"])
     ri, rf = oracle.binary_conv2d(c["x"], c["w"], stride, 1, alpha)
-    # automatic (FP4 matrix cores at this K), register-stationary popcount kernel, popcount GEMM
-    # kernel, int8 matrix cores
-    for choice in (dict(), dict(k5=1), dict(k5=2), dict(k5=4, k7=2)):
+    # automatic (the short-K FP4 matrix-core kernel, 36 words of K), register-stationary
+    # xor/popcount kernel, xor/popcount GEMM kernel, GEMM-shaped FP4 and int8 matrix-core kernels
+    for choice in (dict(), dict(k5=1), dict(k5=2), dict(k5=4), dict(k5=4, k7=2)):
         with tuned(**choice):
             got = run_conv(c["x"], c["w"], stride, 1, alpha=alpha)
             assert got.shape == (64, 256, 14 // stride, 14 // stride)
@@ -327,23 +349,18 @@ def test_config5_quant_gemm():
     assert_f32_close(of.cpu().numpy(), r32)
 
 
-def test_config5_quant_gemm_full_size_sampled_rows():
-    """Full 1024 x 1024 x 4096 on the GPU; the oracle recomputes 96 sampled rows of a."""
+def test_config5_quant_gemm_full_size():
+    """Full 1024 x 1024 x 4096, 2-bit activations x 1-bit weights: every element of S and of the
+    scaled output against the oracle, on every GEMM engine."""
     c = synth.config5()
-    rows = np.random.default_rng(9).choice(1024, 96, replace=False)
-    rS, r64, r32 = oracle.quant_gemm(c["a"][rows], c["w"], 2)
-    first = None
+    rS, r64, r32 = oracle.quant_gemm(c["a"], c["w"], 2)
+    assert (np.abs(rS) <= 3 * 4096).all()
     for engine in GEMM_ENGINES:
         with tuned(**engine):
             S, of = B.quant_gemm(dev(c["a"]), dev(c["w"]), 2)
-        np.testing.assert_array_equal(S.cpu().numpy()[rows], rS)
-        assert_f32_close(of.cpu().numpy()[rows], r64, atol=1e-9)
-        assert_f32_close(of.cpu().numpy()[rows], r32)
-        Sall = S.cpu().numpy()
-        assert (np.abs(Sall) <= 3 * 4096).all()
-        # the rows the oracle did not recompute: every engine gives the same integers
-        first = Sall if first is None else first
-        np.testing.assert_array_equal(Sall, first)
+        np.testing.assert_array_equal(S.cpu().numpy(), rS)
+        assert_f32_close(of.cpu().numpy(), r64, atol=1e-9)
+        assert_f32_close(of.cpu().numpy(), r32)
 
 
 def test_quant_gemm_long_k_leaves_fp4_range():
@@ -803,3 +820,59 @@ def test_fc_random_shapes(seed):
     np.testing.assert_array_equal(B.binary_fc_packed(Xp, fin, Wp, mode="i32").cpu().numpy(), ri)
     bits = B.binary_fc_packed(Xp, fin, Wp, alpha=dev(alpha), mode="bits")
     np.testing.assert_array_equal(host_u64(bits), oracle.binarize_pack(rf, 1))
+
+
+# ------------------------------------------------------------------ 32-bit BINARY_WORD rows
+def words32(x, ld_dw=None, fill=0xCDCDCDCD):
+    """Rows of 32-bit words straight from the definition (element k = bit k % 32 of dword k / 32,
+    numpy.packbits, little bit order), ld_dw dwords apart, spare dwords poisoned."""
+    bits = (x >= 0).astype(np.uint8)
+    R, K = bits.shape
+    Kd = (K + 31) // 32
+    padded = np.zeros((R, Kd * 32), dtype=np.uint8)
+    padded[:, :K] = bits
+    w = np.packbits(padded, axis=1, bitorder="little").view("<u4").reshape(R, Kd)
+    out = np.full((R, Kd if ld_dw is None else ld_dw), fill, dtype=np.uint32)
+    out[:, :Kd] = w
+    return out
+
+
+@pytest.mark.parametrize("K", [1, 32, 33, 64, 96, 100, 333, 1000, 1024, 2048 + 32, 4096 + 96])
+@pytest.mark.parametrize("layout", ["tight", "wide_odd", "wide_even", "offset"])
+def test_words32_gemm_and_fc(K, layout):
+    """Operands stored as rows of 32-bit words (Sec. 2.2.1, the 32-bit BINARY_WORD flavour): odd
+    and even dword counts, odd and even strides with garbage behind the rows, and a base that is
+    only 4-byte aligned.  The GEMM must equal the oracle's float layer on the unpacked signs."""
+    rng = np.random.default_rng(K * 7 + len(layout))
+    M, N = 37, 70
+    a = rng.standard_normal((M, K)).astype(np.float32)
+    b = rng.standard_normal((N, K)).astype(np.float32)
+    alpha = oracle.alpha_mean_abs(b)
+    ri, rf = oracle.binary_fc(a, b, alpha)
+    Kd = (K + 31) // 32
+    ld = {"tight": Kd, "wide_odd": Kd + 1 + (Kd & 1), "wide_even": Kd + 2 - (Kd & 1), "offset": Kd + 1}[layout]
+    A32, B32 = words32(a, ld), words32(b, ld)
+
+    def put(w):
+        if layout != "offset":
+            return dev(w.view(np.int32))
+        flat = torch.empty(w.size + 1, dtype=torch.int32, device="cuda")   # rows start one dword in
+        flat[1:] = dev(w.view(np.int32)).flatten()
+        return flat[1:].view(w.shape)
+
+    Ad, Bd = put(A32), put(B32)
+    got = B.xnor_gemm_w32(Ad, Bd, K).cpu().numpy()
+    np.testing.assert_array_equal(got, ri)
+    # widened rows feed every call that takes packed operands
+    Aw, Bw = B.widen_words32(Ad, K), B.widen_words32(Bd, K)
+    np.testing.assert_array_equal(host_u64(Aw), oracle.binarize_pack(a, 1))
+    np.testing.assert_array_equal(B.xnor_gemm(Aw, Bw, K).cpu().numpy(), ri)
+    f = B.binary_fc_packed(Aw, K, Bw, alpha=dev(alpha), mode="f32").cpu().numpy()
+    assert_f32_close(f, rf)
+    bits = B.binary_fc_packed(Aw, K, Bw, alpha=dev(alpha), mode="bits")
+    np.testing.assert_array_equal(host_u64(bits), oracle.binarize_pack(rf, 1))
+    if Kd % 2 == 0 and layout in ("tight", "wide_even"):
+        # whole 64-bit words already: the same memory read in place through the 64-bit entry point
+        as64 = Ad.view(torch.int64) if layout == "tight" else None
+        if as64 is not None:
+            np.testing.assert_array_equal(B.xnor_gemm(as64, Bd.view(torch.int64), K).cpu().numpy(), ri)

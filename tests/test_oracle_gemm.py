@@ -156,3 +156,31 @@ def test_statistics_at_config1_scale():
     oi, _ = oracle.binary_fc(c["a"], c["w_kn"].T.copy())
     assert abs(oi.mean()) < 1.0
     assert abs(oi.std() - np.sqrt(512)) < 1.0
+
+
+def test_leading_dimensions_wider_than_the_rows():
+    """Every oracle function that takes a leading dimension, fed a view into a wider buffer
+    whose spare columns hold values that would change the result if they were read: packing
+    against numpy.packbits, the FC layer against numpy's matmul on +-1, alpha against a numpy
+    fp64 mean, the quantised GEMM against Python integers."""
+    rng = np.random.default_rng(77)
+    rows, K, ld = 7, 150, 211
+    buf = rng.standard_normal((rows, ld)).astype(np.float32)
+    x = buf[:, :K]
+    assert not x.flags["C_CONTIGUOUS"]
+    np.testing.assert_array_equal(oracle.binarize_pack(x, 1), np_pack_rows(x.copy()))
+    np.testing.assert_array_equal(oracle.binarize_pack(x, 0), np_pack_rows(x.T.copy()))
+    wbuf = rng.uniform(-1, 1, (5, ld + 3)).astype(np.float32)
+    w = wbuf[:, 2:2 + K]
+    sx, sw = np.where(x >= 0, 1.0, -1.0), np.where(w >= 0, 1.0, -1.0)
+    alpha = oracle.alpha_mean_abs(w)
+    np.testing.assert_array_equal(alpha, np.abs(w.astype(np.float64)).mean(axis=1).astype(np.float32))
+    oi, of = oracle.binary_fc(x, w, alpha)
+    np.testing.assert_array_equal(oi, (sx @ sw.T).astype(np.int32))
+    np.testing.assert_array_equal(of, alpha[None, :] * (sx @ sw.T).astype(np.float32))
+    abuf = rng.uniform(0, 1, (4, ld)).astype(np.float32)
+    a = abuf[:, 5:5 + K]
+    S, _, _ = oracle.quant_gemm(a, w, 2)
+    q = [[int(np.floor(float(np.float32(3.0) * v) + 0.5)) for v in row] for row in a]  # the fp32 product, then exact
+    want = [[sum(qq * (1 if ww >= 0 else -1) for qq, ww in zip(qr, wr)) for wr in w] for qr in q]
+    np.testing.assert_array_equal(S, np.array(want, dtype=np.int32))
