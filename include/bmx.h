@@ -12,10 +12,12 @@
  *     on an error return no kernel was launched and no output was touched.
  *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
  *     allocates nothing.  Scratch memory is passed in by the caller (`workspace`,
- *     sized with bmx_workspace_bytes).
+ *     sized with bmx_workspace_bytes); the one exception, bmx_binary_fc_static,
+ *     says so at its declaration.
  *   - Results never depend on earlier calls.  The library does hold process-wide
- *     state of one kind, which does not change a result: the kernel-selection
- *     settings of bmx_tune_set (a measurement and test hook, see there).
+ *     state of two kinds, neither of which changes a result: the kernel-selection
+ *     settings of bmx_tune_set (a measurement and test hook, see there) and
+ *     per-device addresses looked up once (bmx_binary_fc_static).
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
  *     are asynchronous on it; the caller synchronises.
  *   - Inputs and outputs must not overlap.
@@ -127,6 +129,22 @@ int bmx_binary_fc(const float* x, int64_t ldx, const uint64_t* Wp, int64_t ldw_w
                   const float* alpha, int batch, int in_features, int out_features,
                   int32_t* out_i32, float* out_f32, int64_t ldo, void* workspace,
                   size_t workspace_bytes, void* stream);
+
+/* bmx_binary_fc for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and
+ * results as bmx_binary_fc minus the workspace: the packed activations live in a 4 MiB array
+ * inside the library's device code (one copy per GPU, held until the process ends).  The call
+ * allocates and frees nothing.
+ *   - batch * 128 * ceil(in_features / 1024) bytes (the packed, chunk-padded activations, i.e.
+ *     bmx_workspace_bytes(BMX_OP_BINARY_FC, ..)) must not exceed 4 MiB: BMX_ERR_WORKSPACE
+ *     otherwise, before any launch.
+ *   - Every call on one GPU shares that GPU's array: calls that overlap on one GPU (two streams,
+ *     two threads) race; calls on one stream are ordered and safe.
+ *   - The first call on a device looks the array's address up (hipGetSymbolAddress); make one
+ *     call on each device before capturing a graph. */
+int bmx_binary_fc_static(const float* x, int64_t ldx, const uint64_t* Wp, int64_t ldw_w,
+                         const float* alpha, int batch, int in_features, int out_features,
+                         int32_t* out_i32, float* out_f32, int64_t ldo, void* stream);
 
 /* Binary fully connected layer on already packed activations, for chains of binary layers
  * (Sec. 2: QActivation -> QFullyConnected blocks): the layer's result can leave as the packed

@@ -21,7 +21,7 @@ EXPORTS = ["bmx_binarize_pack", "bmx_xnor_gemm", "bmx_binary_fc", "bmx_pack_conv
            "bmx_binary_conv2d_packed", "bmx_workspace_bytes", "bmx_status_string", "bmx_version",
            "bmx_conv_weight_row_words", "bmx_binary_fc_packed", "bmx_tune_set",
            "bmx_binary_conv2d_bits", "bmx_xnor_gemm_count", "bmx_unpack_pm1", "bmx_widen_words32",
-           "bmx_xnor_gemm_w32"]
+           "bmx_xnor_gemm_w32", "bmx_binary_fc_static"]
 
 _i64, _int, _p, _sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
 
@@ -72,6 +72,8 @@ def lib():
         L.bmx_widen_words32.restype = _int
         L.bmx_xnor_gemm_w32.argtypes = [_p, _i64, _p, _i64, _p, _i64, _int, _int, _int, _p, _sz, _p]
         L.bmx_xnor_gemm_w32.restype = _int
+        L.bmx_binary_fc_static.argtypes = [_p, _i64, _p, _i64, _p, _int, _int, _int, _p, _p, _i64, _p]
+        L.bmx_binary_fc_static.restype = _int
         L.bmx_tune_set.argtypes = [_int, _int]
         L.bmx_tune_set.restype = _int
         for name in EXPORTS[:9]:
@@ -235,6 +237,23 @@ def binary_fc(x, Wp, alpha=None, integer_out=False, out=None, workspace=None, st
     _check(lib().bmx_binary_fc(_ptr(x), _ld(x), _ptr(Wp), _ld(Wp), _ptr(alpha), batch, fin, fout,
                                _ptr(oi), _ptr(of), _ld(out), _ptr(ws), ws_bytes, _stream(stream)),
            "bmx_binary_fc")
+    return out
+
+
+def binary_fc_static(x, Wp, alpha=None, integer_out=False, out=None, stream=None):
+    """bmx_binary_fc on the library's own scratch array: the call itself allocates nothing, so
+    `out` must be given."""
+    _chk(x, _F32, "binary_fc_static x")
+    _chk(Wp, _U64, "binary_fc_static Wp")
+    _chk(alpha, _F32, "binary_fc_static alpha", dense=True)
+    if out is None:
+        raise ValueError("binary_fc_static: pass the output tensor (the call allocates nothing)")
+    _chk(out, _I32 if integer_out else _F32, "binary_fc_static out")
+    batch, fin = x.shape
+    fout = Wp.shape[0]
+    oi, of = (out, None) if integer_out else (None, out)
+    _check(lib().bmx_binary_fc_static(_ptr(x), _ld(x), _ptr(Wp), _ld(Wp), _ptr(alpha), batch, fin, fout,
+                                      _ptr(oi), _ptr(of), _ld(out), _stream(stream)), "bmx_binary_fc_static")
     return out
 
 

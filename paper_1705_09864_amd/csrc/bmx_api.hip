@@ -4,6 +4,14 @@
 #include "../../include/bmx.h"
 #include "bmx_internal.h"
 
+#include <mutex>
+
+// Scratch memory of bmx_binary_fc_static, the entry point for callers that cannot allocate: one
+// copy per GPU the library runs on, held until the process ends.  In host code this name is only
+// a handle for hipGetSymbolAddress, never an address to hand to a kernel.
+#define BMX_STATIC_SCRATCH_BYTES (4u << 20)
+static __device__ __align__(256) unsigned char scratch[BMX_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 constexpr int64_t kMaxK = (int64_t)1 << 24;  // float(dot) stays exact below this
@@ -295,6 +303,37 @@ int bmx_binary_fc(const float* x, int64_t ldx, const uint64_t* Wp, int64_t ldw_w
   if (misaligned(workspace, 16)) return BMX_ERR_ALIGN;
   return fc_launch(x, ldx, Wp, ldw_w, alpha, batch, in_features, out_features, out_i32, out_f32, ldo,
                    (uint64_t*)workspace, (hipStream_t)stream);
+}
+
+int bmx_binary_fc_static(const float* x, int64_t ldx, const uint64_t* Wp, int64_t ldw_w,
+                         const float* alpha, int batch, int in_features, int out_features,
+                         int32_t* out_i32, float* out_f32, int64_t ldo, void* stream) {
+  const int rc = fc_check(x, ldx, Wp, ldw_w, alpha, batch, in_features, out_features, out_i32, out_f32, ldo);
+  if (rc != BMX_OK) return rc;
+  if (batch == 0 || out_features == 0) return BMX_OK;
+  const int64_t dims[3] = {batch, in_features, out_features};
+  if (bmx_workspace_bytes(BMX_OP_BINARY_FC, dims, 3) > (size_t)BMX_STATIC_SCRATCH_BYTES)
+    return BMX_ERR_WORKSPACE;  // the packed activations do not fit the library's own scratch
+  // The address of this GPU's copy of the array, asked for once per device (with that device
+  // current) and kept: every GPU holds its own copy at its own address.
+  static std::mutex mu;
+  static void* resolved[64];
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return BMX_ERR_HIP;
+  void* ptr = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(mu);
+    if (!resolved[dev]) {
+      void* p = nullptr;
+      if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return BMX_ERR_HIP;
+      resolved[dev] = p;
+    }
+    ptr = resolved[dev];
+  }
+  // (the pack kernel writes every word of every padded row it hands to the GEMM, so nothing of
+  // a previous call's contents is ever read and nothing needs clearing)
+  return fc_launch(x, ldx, Wp, ldw_w, alpha, batch, in_features, out_features, out_i32, out_f32, ldo,
+                   (uint64_t*)ptr, (hipStream_t)stream);
 }
 
 int bmx_binary_fc_packed(const uint64_t* xp, int64_t ldx_w, const uint64_t* Wp, int64_t ldw_w,
