@@ -1,35 +1,42 @@
 """Benchmark of the binary-layer hot path on one MI355X.
 
-Workload: configuration 2 of the benchmark set, the ResNet-18 stage convolution (x [16,64,56,56] fp32,
-3x3, stride 1, pad 1, 64 filters, alpha epilogue, fp32 NCHW output).  One step is one call of
-bmx_binary_conv2d: channel pack of the activations + implicit-GEMM xor/popcount convolution
-with the alpha epilogue.  Weights are packed and alpha is computed once, outside the step
-(the paper packs weights offline with its model converter).  Inputs are seeded synthetic
-tensors that are resident in HBM before the timed region starts.
+Workload (headline): configuration 3 of the benchmark set, the largest one, the AlexNet classifier
+pair: batch 256, 9216 -> 4096 then 4096 -> 4096, fp32 activations in, fp32 out, alpha per output
+row.  One step is the whole configuration: bmx_binary_fc on the input (binarise + pack, xnor GEMM,
+alpha epilogue), then bmx_binary_fc on the first layer's fp32 output.  Weights are packed and
+alpha is computed once, outside the step (the paper packs weights offline with its model
+converter, Sec. 2.2.3).  Inputs are seeded synthetic tensors resident in HBM before the timed
+region starts.
 
-HBM residency.  One step touches 26 MB, far less than the 256 MB memory-side cache of the
-part, so a loop over one buffer set would measure the cache.  The steps therefore rotate
-over enough copies of (input, workspace, output) to exceed that cache; the cache-hot rate
-(one buffer set) is reported beside it in `config`.
+HBM residency.  One step touches about 25 MB (activations, packed weights, outputs), far less
+than the 256 MB memory-side cache of the part, so a loop over one buffer set would measure the
+cache.  Every timed figure here therefore rotates over enough independent copies of all its
+buffers, weights included, to exceed that cache; the cache-hot rate of the headline is reported
+beside it in `config` and labelled as such.
 
-The kernels run for a few microseconds each, less than the host needs to enqueue them, so
-the K timed steps are captured once into a HIP graph (the library launches on the capturing
-stream) and the timed region is one replay of that graph: exactly K steps, device-bound.
-The eager (host-enqueued) rate is reported next to it.
+The kernels run for a few microseconds each, less than the host needs to enqueue them, so the K
+timed steps are captured once into a HIP graph (the library launches on the capturing stream) and
+the timed region is one replay of that graph: exactly K steps, device-bound.  Kernel durations are
+measured the same way (events on the launch stream around one replay of back-to-back launches on
+the rotating buffers).
 
-Prints ONE JSON line.  `value` is 2*M*N*K binary operations per second over the whole step;
-`roofline` prices the dominant kernel (the convolution).  It runs on the FP4 matrix cores,
-where its 3.7 G multiply-adds x 2 are 0.37 us of work against 1.66 us for the 13.3 MB it must
-move, so HBM is the roof that bounds it; the fractions of the VALU xor+popcount peak and of
-the FP4 peak are given beside it, and `--tune 5=1` puts the xor/popcount kernel in its place.
-Its duration is measured with HIP events on the launch stream around K back-to-back launches
-on the same rotating buffers; `cpu_baseline` times the CPU oracle on the same layer on the
-host cores; `other_configs` gives event-timed figures for configurations 1, 3, 4, 5 of the set.
+Prints ONE JSON line.  `value` is 2*M*N*K binary operations per second over the whole step.
+`roofline` prices the dominant kernel, the first layer's GEMM; every other kernel and every other
+configuration carries the same kind of block (`bound` = the roof with the larger ideal time for
+that launch: HBM bytes, matrix-core flops of the operand type that ran, or VALU xor+popcount
+operations).  `cpu_baseline` times the CPU oracle on the host cores, per configuration, and the
+paper's own method (xnor + popcount on 64-bit words, OpenMP) beside it.
+
+`--phase NAME` runs one section only (headline, config1, config2, config4, config5, sec31,
+packs, probe): the workload of the per-configuration rocprofv3 summaries under profiles/.
 """
 import argparse
+import ctypes
 import json
 import os
+import subprocess
 import sys
+import tempfile
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
@@ -40,7 +47,45 @@ if ROOT not in sys.path:
 # v_bcnt_u32_b32 (popcount-accumulate) handle 32 bit pairs = 64 binary ops per 2 lane-ops.
 VALU_PEAK_BINOPS = 256 * 64 * 2.4e9 * 32
 HBM_PEAK = 8.0e12
+FP4_PEAK = 10.1e15   # dense FP4 matrix-core peak, flop/s
+INT8_PEAK = 5.0e15   # dense int8 matrix-core peak, op/s
 MALL_BYTES = 256 << 20  # memory-side cache the rotation has to exceed
+PHASES = ("headline", "config1", "config2", "config4", "config5", "sec31", "packs", "probe")
+
+
+def roofline_block(kernel, us, binops=0.0, nbytes=0.0, mfma_flops=None):
+    """Roofline of one launch.  The engine is read off the kernel's name: FP4 / int8 matrix cores
+    (flops against that operand type's dense peak) or the VALU xor+popcount form (binary ops
+    against 256 CUs x 64 lanes x 2.4 GHz x 32); every kernel also has its algorithmic HBM bytes.
+    `bound` is the roof whose ideal time for this launch is larger, `frac` = ideal / measured."""
+    t = us * 1e-6
+    if "fp4" in kernel or "conv_mfma_ws" in kernel:
+        bound, peak, unit, work = "mfma", FP4_PEAK, "TFLOP/s", (binops if mfma_flops is None else mfma_flops)
+        dtype = "fp4 e2m1 x fp4 e2m1 -> fp32"
+    elif "int8" in kernel:
+        bound, peak, unit, work, dtype = "mfma", INT8_PEAK, "TOP/s", (binops if mfma_flops is None else mfma_flops), "i8 x i8 -> i32"
+    elif binops > 0:
+        bound, peak, unit, work, dtype = "alu", VALU_PEAK_BINOPS, "Tbinop/s", binops, "u32 xor/and + popcount -> i32"
+    else:
+        bound, peak, unit, work, dtype = "hbm", HBM_PEAK, "GB/s", 0.0, "f32 compare -> bits"
+    t_compute = work / peak if work else 0.0
+    t_hbm = nbytes / HBM_PEAK
+    d = {"kernel": kernel, "avg_us": us, "dtype": dtype}
+    if t_hbm >= t_compute:
+        d.update({"bound": "hbm", "achieved": nbytes / t / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+                  "frac": t_hbm / t})
+    else:
+        d.update({"bound": bound, "achieved": work / t / 1e12, "peak": peak / 1e12, "unit": unit,
+                  "frac": t_compute / t})
+    d["algorithmic_bytes_per_launch"] = int(nbytes)
+    if work:
+        d["algorithmic_ops_per_launch"] = work
+        d["frac_of_%s_peak" % ("valu_xor_popcount" if bound == "alu" else "matrix_core")] = t_compute / t
+        d["frac_of_hbm_peak"] = t_hbm / t
+    if binops and bound != "alu":
+        # a comparison, not a roofline: the same binary ops against the VALU xor+popcount peak
+        d["binops_vs_valu_xor_popcount_peak"] = binops / t / VALU_PEAK_BINOPS
+    return d
 
 
 def main():
@@ -50,8 +95,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-configs", action="store_true")
+    ap.add_argument("--phase", choices=("all",) + PHASES, default="all",
+                    help="run one section only (the workload of a per-configuration profile)")
+    ap.add_argument("--eager", action="store_true",
+                    help="with --phase: issue the timed launches eagerly instead of replaying a graph")
     ap.add_argument("--traffic-probe", action="store_true",
-                    help="run the steps eagerly next to a plain 256 MiB device copy and exit: the "
+                    help="run the headline steps eagerly next to a plain 256 MiB device copy and exit: the "
                          "workload for the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
                     help="pin a kernel choice through bmx_tune_set for the whole run (A/B measurements)")
@@ -71,7 +120,9 @@ def main():
     for kv in args.tune:
         k, v = kv.split("=")
         assert B.lib().bmx_tune_set(int(k), int(v)) == 0
+    want = (lambda name: args.phase in ("all", name))
 
+    # ------------------------------------------------------------------ timing helpers
     def graph_of(fns):
         """Capture the calls in `fns`, in order (library launches on the capturing stream)."""
         g = torch.cuda.CUDAGraph()
@@ -82,395 +133,493 @@ def main():
         torch.cuda.synchronize()
         return g
 
-    def event_us(g, reps, rounds=3):
-        """Average microseconds per captured call over one replay (best of `rounds`)."""
-        g.replay()
+    def event_us(run, reps, rounds=3):
+        """Average microseconds per call over `run()` (reps calls), best of `rounds`."""
+        run()
         torch.cuda.synchronize()
         best = float("inf")
         for _ in range(rounds):
             e0 = torch.cuda.Event(enable_timing=True)
             e1 = torch.cuda.Event(enable_timing=True)
             e0.record()
-            g.replay()
+            run()
             e1.record()
             torch.cuda.synchronize()
             best = min(best, e0.elapsed_time(e1) * 1e3 / reps)
         return best
 
-    def kernel_us(fn, reps=100):
-        for _ in range(3):
-            fn()
-        torch.cuda.synchronize()
-        return event_us(graph_of([fn] * reps), reps)
+    def nsets_for(bytes_per_set, cap=512):
+        return int(min(cap, MALL_BYTES // max(int(bytes_per_set), 1) + 2))
 
-    def rotating_us(make_fn, nsets, reps):
-        fns = [make_fn(i % nsets) for i in range(reps)]
-        for f in fns[:nsets]:
+    def rotating_us(calls, reps=None):
+        """calls[i] runs the measured call on buffer set i.  The sets together exceed the
+        memory-side cache, so every launch finds its inputs in HBM.  Returns (us per call, name
+        of the last kernel the call launched)."""
+        reps = reps or K_STEPS
+        reps = max(reps, len(calls))
+        fns = [calls[i % len(calls)] for i in range(reps)]
+        for f in calls:
             f()
+        name = B.last_kernel()
         torch.cuda.synchronize()
-        return event_us(graph_of(fns), reps)
+        if args.eager:
+            us = event_us(lambda: [f() for f in fns], reps, rounds=2)
+        else:
+            g = graph_of(fns)
+            us = event_us(g.replay, reps)
+            del g
+        return us, name
 
-    # ------------------------------------------------------------------ config 2 (headline)
-    c = synth.config2()
-    x_h, w_h = c["x"], c["w"]
-    N, C, H, W = x_h.shape
-    O, _, KH, KW = w_h.shape
-    stride, pad = c["stride"], c["pad"]
-    Ho, Wo = B.conv_out_hw(H, W, KH, KW, stride, pad)
-    M_, N_, K_ = O, N * Ho * Wo, C * KH * KW
-    binops = 2.0 * M_ * N_ * K_
+    def dev(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
-    w = torch.from_numpy(w_h).cuda()
-    Wp = B.pack_conv_weights(w)
-    alpha = B.alpha_mean_abs(w)
-    ws_bytes = B.workspace_bytes(B.OP_BINARY_CONV2D, (N, C, H, W, O, KH, KW, stride, pad))
-    Cw = (C + 63) // 64
-    out_bytes = N * O * Ho * Wo * 4
-    step_bytes = x_h.nbytes + ws_bytes + out_bytes
-    nsets = MALL_BYTES // step_bytes + 2
-    x0 = torch.from_numpy(x_h).cuda()
-    xs = [x0] + [x0.clone() for _ in range(nsets - 1)]
-    wss = [torch.empty(ws_bytes, dtype=torch.uint8, device="cuda") for _ in range(nsets)]
-    outs = [torch.empty((N, O, Ho, Wo), dtype=torch.float32, device="cuda") for _ in range(nsets)]
-    xps = [t.view(torch.int64)[: N * (H + 2 * pad) * (W + 2 * pad) * Cw].view(
-        N, H + 2 * pad, W + 2 * pad, Cw) for t in wss]
+    def with_tune(kv, fn):
+        for k, v in kv.items():
+            assert B.lib().bmx_tune_set(k, v) == 0
+        try:
+            return fn()
+        finally:
+            B.lib().bmx_tune_set(0, 0)
+            for kv2 in args.tune:  # the run-wide pins stay
+                k, v = kv2.split("=")
+                B.lib().bmx_tune_set(int(k), int(v))
 
-    def make_step(i):
-        return lambda: B.binary_conv2d(xs[i], Wp, O, KH, KW, stride, pad, alpha=alpha, out=outs[i],
-                                       workspace=wss[i])
+    f32 = lambda *shape: torch.empty(shape, dtype=torch.float32, device="cuda")
+    i32 = lambda *shape: torch.empty(shape, dtype=torch.int32, device="cuda")
+    u8 = lambda n: torch.empty(int(n), dtype=torch.uint8, device="cuda")
 
-    steps = [make_step(i % nsets) for i in range(K_STEPS)]
-    if args.traffic_probe:
-        # the copy of known size that calibrates the counters: reads 256 MiB, writes 256 MiB
-        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
-        dst = torch.empty_like(src)
-        for _ in range(5):
-            dst.copy_(src)
+    # ------------------------------------------------------------------ clock and VALU peak, measured
+    probe = None
+    if want("probe") or args.phase == "all":
+        out3 = torch.zeros(3, dtype=torch.int64, device="cuda")
+        iters, wgs = 4000, 256 * 8  # eight waves per SIMD
+        khz = B.probe_valu(wgs, iters, out3)
+        us = event_us(lambda: B.probe_valu(wgs, iters, out3), 1, rounds=5)
+        cyc, ticks = int(out3[0].item()), int(out3[1].item())
+        ops = wgs * 256.0 * iters * 128 * 64
+        probe = {"kernel": B.last_kernel(), "us": us, "measured_valu_xor_popcount_peak_Tbinop_s": ops / us / 1e6,
+                 "vs_nominal_peak_at_2.4GHz": ops / (us * 1e-6) / VALU_PEAK_BINOPS,
+                 "shader_clock_GHz_observed_under_load": (cyc / max(ticks, 1)) * khz * 1e3 / 1e9,
+                 "wall_clock_kHz": khz, "waves_per_simd": 8}
+        probe_peak = ops / (us * 1e-6)
+    else:
+        probe_peak = None
+
+    def add_measured_peak(block):
+        """Second denominator for a VALU-bound kernel: the peak the probe reached in this run."""
+        if probe_peak and block.get("bound") == "alu":
+            block["frac_of_measured_valu_peak"] = block["achieved"] * 1e12 / probe_peak
+        return block
+
+    line = {"metric": "binary GOPS (2*M*N*K xnor-popcount)", "unit": "GOPS", "n_gpus": 1,
+            "steps": K_STEPS, "warmup": args.warmup, "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "data": "synthetic"}
+    other = {}
+    cpu = None
+
+    # ------------------------------------------------------------------ configuration 3 (headline)
+    c3 = synth.config3()
+    Bt, F0, F1, F2 = 256, 9216, 4096, 4096
+    ops1, ops2 = 2.0 * Bt * F1 * F0, 2.0 * Bt * F2 * F1
+    if want("headline") or args.traffic_probe:
+        w1, w2 = dev(c3["w1"]), dev(c3["w2"])
+        W1p0, W2p0 = B.binarize_pack(w1, 1), B.binarize_pack(w2, 1)
+        al1, al2 = B.alpha_mean_abs(w1), B.alpha_mean_abs(w2)
+        del w2
+        ws_bytes = B.workspace_bytes(B.OP_BINARY_FC, (Bt, F0, F1))
+        x0 = dev(c3["x"])
+        step_bytes = (x0.numel() * 4 + ws_bytes + Bt * F1 * 4 + Bt * F2 * 4 + W1p0.numel() * 8 + W2p0.numel() * 8)
+        nsets = nsets_for(step_bytes)
+        xs = [x0] + [x0.clone() for _ in range(nsets - 1)]
+        W1s = [W1p0] + [W1p0.clone() for _ in range(nsets - 1)]
+        W2s = [W2p0] + [W2p0.clone() for _ in range(nsets - 1)]
+        wss = [u8(ws_bytes) for _ in range(nsets)]
+        h1s = [f32(Bt, F1) for _ in range(nsets)]
+        h2s = [f32(Bt, F2) for _ in range(nsets)]
+
+        def make_step(i):
+            def step():
+                B.binary_fc(xs[i], W1s[i], alpha=al1, out=h1s[i], workspace=wss[i])
+                B.binary_fc(h1s[i], W2s[i], alpha=al2, out=h2s[i], workspace=wss[i])
+            return step
+
+        steps = [make_step(i % nsets) for i in range(K_STEPS)]
+        if args.traffic_probe:
+            # the copy of known size that calibrates the counters: reads 256 MiB, writes 256 MiB
+            src = u8(256 << 20).fill_(1)
+            dst = torch.empty_like(src)
+            for _ in range(5):
+                dst.copy_(src)
+            for f in steps:
+                f()
+            torch.cuda.synchronize()
+            print(json.dumps({"traffic_probe": True, "steps": K_STEPS, "copy_bytes_each_way": 256 << 20,
+                              "buffer_sets_rotated": int(nsets)}))
+            return
+        for i in range(args.warmup):
+            steps[i % K_STEPS]()
+        torch.cuda.synchronize()
+        if args.eager:
+            t0 = time.perf_counter()
+            for f in steps:
+                f()
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+        else:
+            g_steps = graph_of(steps)
+            g_steps.replay()  # untimed replay: graph upload
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            g_steps.replay()
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            del g_steps
+        ms_per_step = dt / K_STEPS * 1e3
+        value = (ops1 + ops2) / (dt / K_STEPS) / 1e9
+
+        # cache-hot (one buffer set) and eager (host enqueues every launch) step rates: context
+        hot_us = event_us(graph_of([steps[0]] * K_STEPS).replay, K_STEPS)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
         for f in steps:
             f()
         torch.cuda.synchronize()
-        print(json.dumps({"traffic_probe": True, "steps": K_STEPS, "copy_bytes_each_way": 256 << 20,
-                          "buffer_sets_rotated": int(nsets)}))
-        return
-    for i in range(args.warmup):
-        steps[i % K_STEPS]()
-    torch.cuda.synchronize()
-    g_steps = graph_of(steps)
-    g_steps.replay()  # untimed replay: graph upload
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    g_steps.replay()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt / K_STEPS * 1e3
-    value = binops / (dt / K_STEPS) / 1e9
+        eager_ms = (time.perf_counter() - t0) / K_STEPS * 1e3
+        del steps
 
-    # cache-hot rate (one buffer set) and eager rate (host enqueues every launch): context
-    hot_us = kernel_us(steps[0], K_STEPS)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for f in steps:
-        f()
-    torch.cuda.synchronize()
-    eager_ms = (time.perf_counter() - t0) / K_STEPS * 1e3
+        # the step's kernels one by one, on the same rotating buffers
+        Kw0p = ws_bytes // (Bt * 8)  # chunk-padded row length of the packed activations, in words
+        xps = [t.view(torch.int64)[: Bt * Kw0p].view(Bt, Kw0p) for t in wss]
+        gemm1_us, gemm1_name = rotating_us([(lambda i=i: B.binary_fc_packed(
+            xps[i], F0, W1s[i], alpha=al1, mode="f32", out=h1s[i])) for i in range(nsets)])
+        pack1_us, pack1_name = rotating_us([(lambda i=i: B.binarize_pack(xs[i], 1, out=xps[i])) for i in range(nsets)])
+        Kw1 = F1 // 64
+        h1ps = [t.view(torch.int64)[: Bt * Kw1].view(Bt, Kw1) for t in wss]
+        gemm2_us, gemm2_name = rotating_us([(lambda i=i: B.binary_fc_packed(
+            h1ps[i], F1, W2s[i], alpha=al2, mode="f32", out=h2s[i])) for i in range(nsets)])
+        pack2_us, pack2_name = rotating_us([(lambda i=i: B.binarize_pack(h1s[i], 1, out=h1ps[i])) for i in range(nsets)])
+        fc1_us, _ = rotating_us([(lambda i=i: B.binary_fc(xs[i], W1s[i], alpha=al1, out=h1s[i], workspace=wss[i]))
+                                 for i in range(nsets)])
+        fc2_us, _ = rotating_us([(lambda i=i: B.binary_fc(h1s[i], W2s[i], alpha=al2, out=h2s[i], workspace=wss[i]))
+                                 for i in range(nsets)])
+        gemm1_bytes = Bt * (F0 // 8) + F1 * (F0 // 8) + Bt * F1 * 4   # packed x, packed W1 in; fp32 out
+        gemm2_bytes = Bt * (F1 // 8) + F2 * (F1 // 8) + Bt * F2 * 4
+        pack1_bytes = Bt * F0 * 4 + Bt * (F0 // 8)
+        pack2_bytes = Bt * F1 * 4 + Bt * (F1 // 8)
+        roofline = roofline_block(gemm1_name, gemm1_us, binops=ops1, nbytes=gemm1_bytes)
+        traffic, tsrc = None, None
+        tpath = os.path.join(ROOT, "profiles", "traffic_fc1_gemm_config3.txt")
+        if os.path.exists(tpath):  # scaled FETCH_SIZE + WRITE_SIZE of this kernel, from its rocprofv3 --pmc runs
+            for ln in open(tpath):
+                if ln.startswith("hbm_bytes_per_launch:"):
+                    traffic = int(ln.split(":")[1])
+                    tsrc = "profiles/traffic_fc1_gemm_config3.txt (rocprofv3 --pmc, not measured in this run)"
+        roofline["traffic"] = traffic
+        roofline["traffic_source"] = tsrc
+        kernels = {
+            "fc1_pack": roofline_block(pack1_name, pack1_us, nbytes=pack1_bytes),
+            "fc1_gemm": dict(roofline),
+            "fc2_pack": roofline_block(pack2_name, pack2_us, nbytes=pack2_bytes),
+            "fc2_gemm": roofline_block(gemm2_name, gemm2_us, binops=ops2, nbytes=gemm2_bytes),
+        }
+        # the same GEMMs on the xor/popcount engine (north_star's VALU target names it)
+        for tag, Wl, xl, hl, fin, al_, ops_, nb in (("fc1", W1s, xps, h1s, F0, al1, ops1, gemm1_bytes),
+                                                     ("fc2", W2s, h1ps, h2s, F1, al2, ops2, gemm2_bytes)):
+            us_, nm_ = with_tune({7: 1}, lambda: rotating_us([(lambda i=i: B.binary_fc_packed(
+                xl[i], fin, Wl[i], alpha=al_, mode="f32", out=hl[i])) for i in range(nsets)], reps=60))
+            kernels[tag + "_gemm_popcount_engine"] = add_measured_peak(roofline_block(nm_, us_, binops=ops_, nbytes=nb))
+        # the two layers handing packed sign bits to each other instead of fp32 activations
+        bits1 = [B.binary_fc_packed(xps[i], F0, W1s[i], alpha=al1, mode="bits") for i in range(nsets)]
 
-    # The same K steps with independent batches dealt over four streams (branches of one graph):
-    # what a server that overlaps batches would see.  Context only; `value` is the in-order rate.
-    n_str = 4
-    g4 = torch.cuda.CUDAGraph()
-    st4 = [torch.cuda.Stream() for _ in range(n_str)]
-    with torch.cuda.graph(g4, stream=st4[0]):
-        for s_ in st4[1:]:
-            s_.wait_stream(st4[0])
-        for i, f in enumerate(steps):  # steps on one buffer set stay on one stream, in order
-            with torch.cuda.stream(st4[(i % nsets) % n_str]):
-                f()
-        for s_ in st4[1:]:
-            st4[0].wait_stream(s_)
-    torch.cuda.synchronize()
-    g4.replay()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    g4.replay()
-    torch.cuda.synchronize()
-    overlapped_ms = (time.perf_counter() - t0) / K_STEPS * 1e3
-    del g4
+        def chain_bits(i):
+            def run():
+                B.binarize_pack(xs[i], 1, out=xps[i])
+                B.binary_fc_packed(xps[i], F0, W1s[i], alpha=al1, mode="bits", out=bits1[i])
+                B.binary_fc_packed(bits1[i], F1, W2s[i], alpha=al2, mode="f32", out=h2s[i])
+            return run
 
-    conv_us = rotating_us(lambda i: (lambda: B.binary_conv2d_packed(
-        xps[i], C, Wp, O, KH, KW, stride, pad, alpha=alpha, out=outs[i])), nsets, K_STEPS)
-    pack_us = rotating_us(lambda i: (lambda: B.pack_nchw(xs[i], pad, out=xps[i])), nsets, K_STEPS)
-    achieved = binops / (conv_us * 1e-6)
-    pack_bytes = x_h.nbytes + xps[0].numel() * 8
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic_conv2d_config2.txt")
-    if os.path.exists(tpath):  # scaled FETCH_SIZE + WRITE_SIZE of the convolution kernel
-        for ln in open(tpath):
-            if ln.startswith("hbm_bytes_per_launch:"):
-                traffic = int(ln.split(":")[1])
-    popcount_conv = any(kv.split("=") == ["5", "1"] for kv in args.tune)
-    # bytes the convolution kernel must move: packed image in, packed filters in, fp32 out
-    conv_bytes = xps[0].numel() * 8 + Wp.numel() * 8 + out_bytes
-    if popcount_conv:
-        roofline = {"bound": "alu", "kernel": "conv_stationary_kernel<9,2> (implicit-GEMM xor+popcount)",
-                    "achieved": achieved / 1e12, "peak": VALU_PEAK_BINOPS / 1e12, "unit": "Tbinop/s",
-                    "frac": achieved / VALU_PEAK_BINOPS}
-    else:
-        roofline = {"bound": "hbm", "kernel": "conv_mfma_ws_kernel<9,1,4,false> (implicit GEMM on the FP4 matrix cores)",
-                    "achieved": conv_bytes / (conv_us * 1e-6) / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
-                    "frac": conv_bytes / (conv_us * 1e-6) / HBM_PEAK,
-                    "algorithmic_bytes_per_launch": conv_bytes,
-                    "binops_frac_of_valu_xor_popcount_peak": achieved / VALU_PEAK_BINOPS,
-                    "flops_frac_of_fp4_matrix_core_peak": achieved / 10.1e15}
-    roofline.update({"traffic": traffic, "avg_us": conv_us,
-                "algorithmic_binops_per_launch": binops,
-                "output_bytes_per_launch": out_bytes,
-                "pack_kernel": {"kernel": "pack_nchw_kernel", "bound": "hbm",
-                                "achieved": pack_bytes / (pack_us * 1e-6) / 1e9,
-                                "peak": HBM_PEAK / 1e9, "unit": "GB/s",
-                                "frac": pack_bytes / (pack_us * 1e-6) / HBM_PEAK, "avg_us": pack_us,
-                                "algorithmic_bytes_per_launch": pack_bytes}})
-    del xs, wss, outs, xps, steps, g_steps
+        chain_bits_us, _ = rotating_us([chain_bits(i) for i in range(nsets)])
+        line.update({"value": value, "ms_per_step": ms_per_step,
+                     "dtype": "f32 in -> sign bits (u64 words) -> %s -> f32 out" % roofline["dtype"],
+                     "config": {"workload": "config3: binary FC pair, batch 256, 9216 -> 4096 -> 4096, fp32 in, alpha per "
+                                            "output row, fp32 out (GEMM views 256 x 4096 x 9216 and 256 x 4096 x 4096)",
+                                "step": "bmx_binary_fc (pack + xnor GEMM + alpha) on x, then bmx_binary_fc on its fp32 output",
+                                "kernels": [pack1_name, gemm1_name, pack2_name, gemm2_name],
+                                "timed_region": "K eager steps" if args.eager else "one replay of a HIP graph holding the K steps",
+                                "buffer_sets_rotated": int(nsets), "bytes_per_buffer_set": int(step_bytes),
+                                "ms_per_step_cache_hot": hot_us * 1e-3, "ms_per_step_eager": eager_ms,
+                                "fc1_call_us_hbm_resident": fc1_us, "fc2_call_us_hbm_resident": fc2_us,
+                                "step_us_via_packed_sign_bits_between_layers": chain_bits_us,
+                                "gops_fc1_call": ops1 / fc1_us / 1e3, "gops_fc2_call": ops2 / fc2_us / 1e3},
+                     "roofline": roofline, "kernels": kernels})
+        del xs, W1s, W2s, wss, h1s, h2s, xps, h1ps, bits1
+        torch.cuda.empty_cache()
 
-    # ------------------------------------------------------------------ other configurations
-    other = None
-    if not args.no_other_configs:
-        other = {}
+        del w1
+        torch.cuda.empty_cache()
 
-        def alu(ops, us):
-            return {"us": us, "Tbinop_s": ops / us / 1e6, "frac_valu": ops / (us * 1e-6) / VALU_PEAK_BINOPS}
+    run_others = not args.no_other_configs
 
-        MFMA_FP4_PEAK = 10.1e15  # dense FP4 matrix-core peak, flop/s
-
-        def mfma(ops, us, mfma_flops=None):
-            # kernels that run on the matrix cores (bits expanded to FP4 nibbles in registers):
-            # binary ops as for the popcount path, plus the multiply-adds actually issued (all
-            # bit planes of a k-bit operand in one pass) against the FP4 matrix-core peak
-            d = alu(ops, us)
-            d["engine"] = "FP4 matrix cores"
-            d["frac_mfma_fp4"] = (mfma_flops if mfma_flops is not None else ops) / (us * 1e-6) / MFMA_FP4_PEAK
-            return d
-
-        def popcount_engine(fn):
-            B.lib().bmx_tune_set(7, 1)
-            try:
-                return kernel_us(fn, 50)
-            finally:
-                B.lib().bmx_tune_set(7, 0)
-
-        def hbm(nbytes, us):
-            return {"us": us, "GB_s": nbytes / us / 1e3, "frac_hbm": nbytes / (us * 1e-6) / HBM_PEAK}
-
-        # config 1: FC GEMM 64 x 256 x 512 (launch-latency bound)
-        c1 = synth.config1()
-        a1 = torch.from_numpy(c1["a"]).cuda()
-        W1p = B.binarize_pack(torch.from_numpy(c1["w_kn"]).cuda(), 0)
-        o1 = torch.empty((64, 256), dtype=torch.int32, device="cuda")
-        ws1 = torch.empty(B.workspace_bytes(B.OP_BINARY_FC, (64, 512, 256)), dtype=torch.uint8, device="cuda")
-        other["config1_fc_call_64x256x512"] = alu(2.0 * 64 * 256 * 512, kernel_us(
-            lambda: B.binary_fc(a1, W1p, integer_out=True, out=o1, workspace=ws1)))
-        # config 3: AlexNet classifier layers: GEMM kernel alone (pre-packed activations),
-        # the layer call (pack + GEMM + alpha), and the big weight pack
-        c3 = synth.config3()
-        x3 = torch.from_numpy(c3["x"]).cuda()
-        w31 = torch.from_numpy(c3["w1"]).cuda()
-        w32 = torch.from_numpy(c3["w2"]).cuda()
-        W31p, W32p = B.binarize_pack(w31, 1), B.binarize_pack(w32, 1)
-        al1, al2 = B.alpha_mean_abs(w31), B.alpha_mean_abs(w32)
-        h1 = torch.empty((256, 4096), dtype=torch.float32, device="cuda")
-        h2 = torch.empty((256, 4096), dtype=torch.float32, device="cuda")
-        i3 = torch.empty((256, 4096), dtype=torch.int32, device="cuda")
-        ws3 = torch.empty(B.workspace_bytes(B.OP_BINARY_FC, (256, 9216, 4096)), dtype=torch.uint8, device="cuda")
-        other["config3_fc1_call_256x4096x9216"] = mfma(2.0 * 256 * 4096 * 9216, kernel_us(
-            lambda: B.binary_fc(x3, W31p, alpha=al1, out=h1, workspace=ws3), 50))
-        other["config3_fc2_call_256x4096x4096"] = mfma(2.0 * 256 * 4096 * 4096, kernel_us(
-            lambda: B.binary_fc(h1, W32p, alpha=al2, out=h2, workspace=ws3), 50))
-        X3p, H1p = B.binarize_pack(x3, 1), B.binarize_pack(h1, 1)
-        other["config3_fc1_gemm_kernel"] = mfma(2.0 * 256 * 4096 * 9216, kernel_us(
-            lambda: B.xnor_gemm(X3p, W31p, 9216, out=i3), 50))
-        other["config3_fc2_gemm_kernel"] = mfma(2.0 * 256 * 4096 * 4096, kernel_us(
-            lambda: B.xnor_gemm(H1p, W32p, 4096, out=i3), 50))
-        # the same products on the xor/popcount kernel (the engine is kept where it wins)
-        other["config3_fc1_gemm_kernel_popcount_engine"] = alu(2.0 * 256 * 4096 * 9216, popcount_engine(
-            lambda: B.xnor_gemm(X3p, W31p, 9216, out=i3)))
-        other["config3_fc2_gemm_kernel_popcount_engine"] = alu(2.0 * 256 * 4096 * 4096, popcount_engine(
-            lambda: B.xnor_gemm(H1p, W32p, 4096, out=i3)))
-        # the two layers chained: through fp32 activations (pack + GEMM, twice) and through
-        # packed sign bits handed from layer to layer (one pack, two GEMMs)
-        chain_ops = 2.0 * 256 * 4096 * (9216 + 4096)
-
-        def chain_fp32():
-            B.binary_fc(x3, W31p, alpha=al1, out=h1, workspace=ws3)
-            B.binary_fc(h1, W32p, alpha=al2, out=h2, workspace=ws3)
-
-        bits1 = B.binary_fc_packed(X3p, 9216, W31p, alpha=al1, mode="bits")
-
-        def chain_bits():
-            B.binarize_pack(x3, 1, out=X3p)
-            B.binary_fc_packed(X3p, 9216, W31p, alpha=al1, mode="bits", out=bits1)
-            B.binary_fc_packed(bits1, 4096, W32p, alpha=al2, mode="f32", out=h2)
-
-        other["config3_chain_via_fp32_activations"] = mfma(chain_ops, kernel_us(chain_fp32, 50))
-        other["config3_chain_via_packed_bits"] = mfma(chain_ops, kernel_us(chain_bits, 50))
-        other["config3_activation_pack_256x9216"] = hbm(x3.numel() * 4 + X3p.numel() * 8, kernel_us(
-            lambda: B.binarize_pack(x3, 1, out=X3p)))
-        other["config3_weight_pack_4096x9216_cache_assisted"] = hbm(w31.numel() * 4 + W31p.numel() * 8, kernel_us(
-            lambda: B.binarize_pack(w31, 1, out=W31p), 20))
-        del w31, w32
-        # a 1 GiB row pack: larger than the memory-side cache, the sustained HBM figure
-        big = torch.empty((8192, 32768), dtype=torch.float32, device="cuda").normal_()
+    if want("packs") and run_others:
+        # weight pack of the first layer (151 MB fp32 -> 4.7 MB), three copies rotating, and a
+        # 1 GiB row pack: the sustained HBM figures of the pack kernel
+        w1 = dev(c3["w1"])
+        W1p0 = B.binarize_pack(w1, 1)
+        wcopies = [w1] + [w1.clone() for _ in range(2)]
+        us_, nm_ = rotating_us([(lambda i=i: B.binarize_pack(wcopies[i], 1, out=W1p0)) for i in range(3)], reps=30)
+        other["config3_weight_pack_4096x9216"] = roofline_block(nm_, us_, nbytes=w1.numel() * 4 + W1p0.numel() * 8)
+        del wcopies, w1
+        big = f32(8192, 32768).normal_()
         bigp = B.binarize_pack(big, 1)
-        other["row_pack_1GiB_hbm_resident"] = hbm(big.numel() * 4 + bigp.numel() * 8, kernel_us(
-            lambda: B.binarize_pack(big, 1, out=bigp), 5))
+        us_, nm_ = rotating_us([lambda: B.binarize_pack(big, 1, out=bigp)], reps=5)
+        other["row_pack_1GiB"] = roofline_block(nm_, us_, nbytes=big.numel() * 4 + bigp.numel() * 8)
         del big, bigp
-        # config 4: deep conv stage, stride 1 and 2 (conv kernel alone, and pack alone)
-        for s4 in (1, 2):
-            c4 = synth.config4(stride=s4)
-            x4 = torch.from_numpy(c4["x"]).cuda()
-            w4 = torch.from_numpy(c4["w"]).cuda()
-            W4p, al4 = B.pack_conv_weights(w4), B.alpha_mean_abs(w4)
-            xp4 = B.pack_nchw(x4, 1)
-            ho4, wo4 = B.conv_out_hw(14, 14, 3, 3, s4, 1)
-            o4 = torch.empty((64, 256, ho4, wo4), dtype=torch.float32, device="cuda")
-            ops4 = 2.0 * 256 * 64 * ho4 * wo4 * 2304
-            other["config4_conv_s%d_kernel" % s4] = mfma(ops4, kernel_us(
-                lambda: B.binary_conv2d_packed(xp4, 256, W4p, 256, 3, 3, s4, 1, alpha=al4, out=o4)))
-            ws4 = torch.empty(B.workspace_bytes(B.OP_BINARY_CONV2D, (64, 256, 14, 14, 256, 3, 3, s4, 1)),
-                              dtype=torch.uint8, device="cuda")
-            other["config4_conv_s%d_call" % s4] = mfma(ops4, kernel_us(
-                lambda: B.binary_conv2d(x4, W4p, 256, 3, 3, s4, 1, alpha=al4, out=o4, workspace=ws4)))
-            B.lib().bmx_tune_set(5, 1)  # the register-stationary xor/popcount kernel beside it
-            try:
-                other["config4_conv_s%d_kernel_popcount_engine" % s4] = alu(ops4, kernel_us(
-                    lambda: B.binary_conv2d_packed(xp4, 256, W4p, 256, 3, 3, s4, 1, alpha=al4, out=o4)))
-            finally:
-                B.lib().bmx_tune_set(5, 0)
-            if s4 == 1:
-                other["config4_pack_nchw"] = hbm(x4.numel() * 4 + xp4.numel() * 8, kernel_us(
-                    lambda: B.pack_nchw(x4, 1, out=xp4)))
-        # configuration-2 blocks chained (Sec. 2: QActivation -> QConvolution -> BatchNorm, three in
-        # a row, 64 -> 64 channels on 16 x 56 x 56): every layer through an fp32 feature map
-        # (pack + convolution each), or handing the next layer its packed image (one pack, the
-        # BatchNorm folded into a per-channel threshold)
-        xc = torch.from_numpy(x_h).cuda()
-        wc = [torch.empty((64, 64, 3, 3), dtype=torch.float32, device="cuda").normal_() for _ in range(3)]
+        torch.cuda.empty_cache()
+
+    # ------------------------------------------------------------------ configuration 1
+    if want("config1") and run_others:
+        c1 = synth.config1()
+        n1 = nsets_for(64 * 512 * 4 + 256 * 8 * 8 + 64 * 256 * 4 + 4096, cap=400)
+        a1 = [dev(c1["a"]) for _ in range(n1)]
+        W1p = [B.binarize_pack(dev(c1["w_kn"]), 0) for _ in range(n1)]
+        o1 = [i32(64, 256) for _ in range(n1)]
+        ws1 = [u8(B.workspace_bytes(B.OP_BINARY_FC, (64, 512, 256))) for _ in range(n1)]
+        us_, nm_ = rotating_us([(lambda i=i: B.binary_fc(a1[i], W1p[i], integer_out=True, out=o1[i], workspace=ws1[i]))
+                                for i in range(n1)])
+        blk = roofline_block(nm_, us_, binops=2.0 * 64 * 256 * 512, nbytes=64 * 64 + 256 * 64 + 64 * 256 * 4)
+        blk["note"] = "whole call (pack + GEMM): two launches of about 2.4 us each; 13 ns of arithmetic"
+        other["config1_fc_call_64x256x512"] = blk
+        del a1, W1p, o1, ws1
+
+    # ------------------------------------------------------------------ convolutions (configs 2, 4)
+    def conv_config(tag, c, popcount_path):
+        x_h, w_h = c["x"], c["w"]
+        N, C, H, W = x_h.shape
+        O, _, KH, KW = w_h.shape
+        stride, pad = c["stride"], c["pad"]
+        Ho, Wo = B.conv_out_hw(H, W, KH, KW, stride, pad)
+        binops = 2.0 * O * N * Ho * Wo * C * KH * KW
+        w = dev(w_h)
+        Wp0, alpha = B.pack_conv_weights(w), B.alpha_mean_abs(w)
+        ws_bytes = B.workspace_bytes(B.OP_BINARY_CONV2D, (N, C, H, W, O, KH, KW, stride, pad))
+        Cw = (C + 63) // 64
+        out_bytes = N * O * Ho * Wo * 4
+        n = nsets_for(x_h.nbytes + ws_bytes + out_bytes + Wp0.numel() * 8)
+        x0 = dev(x_h)
+        xs = [x0] + [x0.clone() for _ in range(n - 1)]
+        Wps = [Wp0] + [Wp0.clone() for _ in range(n - 1)]
+        wss = [u8(ws_bytes) for _ in range(n)]
+        outs = [f32(N, O, Ho, Wo) for _ in range(n)]
+        xps = [t.view(torch.int64)[: N * (H + 2 * pad) * (W + 2 * pad) * Cw].view(N, H + 2 * pad, W + 2 * pad, Cw)
+               for t in wss]
+        call_us, _ = rotating_us([(lambda i=i: B.binary_conv2d(xs[i], Wps[i], O, KH, KW, stride, pad, alpha=alpha,
+                                                               out=outs[i], workspace=wss[i])) for i in range(n)])
+        conv_calls = [(lambda i=i: B.binary_conv2d_packed(xps[i], C, Wps[i], O, KH, KW, stride, pad, alpha=alpha,
+                                                          out=outs[i])) for i in range(n)]
+        conv_us, conv_name = rotating_us(conv_calls)
+        pack_us, pack_name = rotating_us([(lambda i=i: B.pack_nchw(xs[i], pad, out=xps[i])) for i in range(n)])
+        conv_bytes = xps[0].numel() * 8 + Wp0.numel() * 8 + out_bytes
+        pack_bytes = x_h.nbytes + xps[0].numel() * 8
+        d = {"call_us_hbm_resident": call_us, "gops_call": binops / call_us / 1e3, "buffer_sets_rotated": n,
+             "conv_kernel": roofline_block(conv_name, conv_us, binops=binops, nbytes=conv_bytes),
+             "pack_kernel": roofline_block(pack_name, pack_us, nbytes=pack_bytes)}
+        us_, nm_ = with_tune({5: popcount_path}, lambda: rotating_us(conv_calls, reps=60))
+        d["conv_kernel_popcount_engine"] = add_measured_peak(roofline_block(nm_, us_, binops=binops, nbytes=conv_bytes))
+        other[tag] = d
+
+    if want("config2") and run_others:
+        conv_config("config2_conv3x3_16x64x56x56_64filters", synth.config2(), 1)
+        # three configuration-2 blocks in a row (Sec. 2: QActivation -> QConvolution -> BatchNorm):
+        # through fp32 feature maps (pack + convolution each) or handing the next layer its packed
+        # image (one pack, the BatchNorm folded into a per-channel threshold)
+        n = nsets_for(2 * 12845056 + 430592 * 3)
+        x_h = synth.config2()["x"]
+        xc = [dev(x_h) for _ in range(n)]
+        wc = [f32(64, 64, 3, 3).normal_() for _ in range(3)]
         Wc = [B.pack_conv_weights(t) for t in wc]
         alc = [B.alpha_mean_abs(t) for t in wc]
-        thc = torch.empty((64,), dtype=torch.float32, device="cuda").normal_()
-        wsc = torch.empty(B.workspace_bytes(B.OP_BINARY_CONV2D, (16, 64, 56, 56, 64, 3, 3, 1, 1)),
-                          dtype=torch.uint8, device="cuda")
-        fa = torch.empty((16, 64, 56, 56), dtype=torch.float32, device="cuda")
-        fb = torch.empty_like(fa)
-        xpc = B.pack_nchw(xc, 1)
-        ia = torch.empty_like(xpc)
-        ib = torch.empty_like(xpc)
+        thc = f32(64).normal_()
+        wsc = [u8(B.workspace_bytes(B.OP_BINARY_CONV2D, (16, 64, 56, 56, 64, 3, 3, 1, 1))) for _ in range(n)]
+        fa = [f32(16, 64, 56, 56) for _ in range(n)]
+        fb = [f32(16, 64, 56, 56) for _ in range(n)]
+        xpc = [B.pack_nchw(xc[i], 1) for i in range(n)]
+        ia = [torch.empty_like(xpc[0]) for _ in range(n)]
+        ib = [torch.empty_like(xpc[0]) for _ in range(n)]
         ops_c = 3 * 2.0 * 64 * 16 * 56 * 56 * 576
 
-        def blocks_fp32():
-            B.binary_conv2d(xc, Wc[0], 64, 3, 3, 1, 1, alpha=alc[0], out=fa, workspace=wsc)
-            B.binary_conv2d(fa, Wc[1], 64, 3, 3, 1, 1, alpha=alc[1], out=fb, workspace=wsc)
-            B.binary_conv2d(fb, Wc[2], 64, 3, 3, 1, 1, alpha=alc[2], out=fa, workspace=wsc)
+        def blocks_fp32(i):
+            def run():
+                B.binary_conv2d(xc[i], Wc[0], 64, 3, 3, 1, 1, alpha=alc[0], out=fa[i], workspace=wsc[i])
+                B.binary_conv2d(fa[i], Wc[1], 64, 3, 3, 1, 1, alpha=alc[1], out=fb[i], workspace=wsc[i])
+                B.binary_conv2d(fb[i], Wc[2], 64, 3, 3, 1, 1, alpha=alc[2], out=fa[i], workspace=wsc[i])
+            return run
 
-        def blocks_packed():
-            B.pack_nchw(xc, 1, out=xpc)
-            B.binary_conv2d_bits(xpc, 64, Wc[0], 64, 3, 3, 1, 1, alpha=alc[0], thr=thc, out_pad=1, out=ia)
-            B.binary_conv2d_bits(ia, 64, Wc[1], 64, 3, 3, 1, 1, alpha=alc[1], thr=thc, out_pad=1, out=ib)
-            B.binary_conv2d_packed(ib, 64, Wc[2], 64, 3, 3, 1, 1, alpha=alc[2], out=fa)
+        def blocks_packed(i):
+            def run():
+                B.pack_nchw(xc[i], 1, out=xpc[i])
+                B.binary_conv2d_bits(xpc[i], 64, Wc[0], 64, 3, 3, 1, 1, alpha=alc[0], thr=thc, out_pad=1, out=ia[i])
+                B.binary_conv2d_bits(ia[i], 64, Wc[1], 64, 3, 3, 1, 1, alpha=alc[1], thr=thc, out_pad=1, out=ib[i])
+                B.binary_conv2d_packed(ib[i], 64, Wc[2], 64, 3, 3, 1, 1, alpha=alc[2], out=fa[i])
+            return run
 
-        other["config2_three_blocks_via_fp32_maps"] = mfma(ops_c, kernel_us(blocks_fp32, 50))
-        other["config2_three_blocks_via_packed_images"] = mfma(ops_c, kernel_us(blocks_packed, 50))
-        other["config2_conv_to_packed_image_kernel"] = mfma(ops_c / 3, kernel_us(
-            lambda: B.binary_conv2d_bits(xpc, 64, Wc[0], 64, 3, 3, 1, 1, alpha=alc[0], thr=thc, out_pad=1, out=ia)))
-        del xc, fa, fb
-        # config 5: 2-bit x 1-bit GEMM, whole call (quantise + plane pack + weight pack + GEMM)
+        us_a, _ = rotating_us([blocks_fp32(i) for i in range(n)], reps=60)
+        us_b, _ = rotating_us([blocks_packed(i) for i in range(n)], reps=60)
+        other["config2_three_blocks_in_a_row"] = {"via_fp32_feature_maps_us": us_a, "via_packed_images_us": us_b,
+                                                  "gops_via_fp32": ops_c / us_a / 1e3, "gops_via_packed": ops_c / us_b / 1e3}
+        del xc, fa, fb, xpc, ia, ib, wsc
+
+    if want("config4") and run_others:
+        conv_config("config4_conv3x3_64x256x14x14_256filters_stride1", synth.config4(stride=1), 1)
+        conv_config("config4_conv3x3_64x256x14x14_256filters_stride2", synth.config4(stride=2), 1)
+
+    # ------------------------------------------------------------------ configuration 5
+    if want("config5") and run_others:
         c5 = synth.config5()
-        a5 = torch.from_numpy(c5["a"]).cuda()
-        w5 = torch.from_numpy(c5["w"]).cuda()
-        ws5 = torch.empty(B.workspace_bytes(B.OP_QUANT_GEMM, (1024, 1024, 4096, 2, 1)), dtype=torch.uint8,
-                          device="cuda")
-        o5 = torch.empty((1024, 1024), dtype=torch.float32, device="cuda")
-        other["config5_quant_gemm_call_2planes"] = mfma(2.0 * 2 * 1024 * 1024 * 4096, kernel_us(
-            lambda: B.quant_gemm(a5, w5, 2, want_int=False, out_float=o5, workspace=ws5), 20),
-            mfma_flops=2.0 * 1024 * 1024 * 4096)
-        other["config5_quant_gemm_call_2planes_popcount_engine"] = alu(2.0 * 2 * 1024 * 1024 * 4096, popcount_engine(
-            lambda: B.quant_gemm(a5, w5, 2, want_int=False, out_float=o5, workspace=ws5)))
+        M5, N5, K5 = 1024, 1024, 4096
+        wsb = B.workspace_bytes(B.OP_QUANT_GEMM, (M5, N5, K5, 2, 1))
+        n = nsets_for(2 * M5 * K5 * 4 + wsb + M5 * N5 * 4)
+        a5 = [dev(c5["a"]) for _ in range(n)]
+        w5 = [dev(c5["w"]) for _ in range(n)]
+        ws5 = [u8(wsb) for _ in range(n)]
+        o5 = [f32(M5, N5) for _ in range(n)]
+        calls5 = [(lambda i=i: B.quant_gemm(a5[i], w5[i], 2, want_int=False, out_float=o5[i], workspace=ws5[i]))
+                  for i in range(n)]
+        us_, nm_ = rotating_us(calls5, reps=60)
+        binops5 = 2.0 * 2 * M5 * N5 * K5            # two plane pairs
+        d = {"call_us_hbm_resident": us_, "gops_call": binops5 / us_ / 1e3, "buffer_sets_rotated": n,
+             "note": "whole call: quantise + plane pack of a and sign pack of w (one launch), then the plane GEMM",
+             # priced as if the GEMM kernel had the whole call to itself (the split per kernel is in profiles/)
+             "gemm_kernel_upper_bound": roofline_block(nm_, us_, binops=binops5, nbytes=3 * M5 * K5 // 8 + M5 * N5 * 4,
+                                                       mfma_flops=2.0 * M5 * N5 * K5),
+             "whole_call_vs_hbm": roofline_block("quant_pack_kernel + " + nm_, us_, nbytes=2 * M5 * K5 * 4 + M5 * N5 * 4)}
+        us_, nm_ = with_tune({7: 1}, lambda: rotating_us(calls5, reps=40))
+        d["call_popcount_engine"] = add_measured_peak(roofline_block(nm_, us_, binops=binops5,
+                                                                     nbytes=3 * M5 * K5 // 8 + M5 * N5 * 4))
+        other["config5_quant_gemm_2bit_x_1bit_1024x1024x4096"] = d
+        del a5, w5, ws5, o5
 
-        # the paper's own efficiency workload (Sec. 3.1): 5x5 kernels, 64 filters, batch 200,
-        # 8x8 outputs -> GEMM view M = 64, N = 12800, K = 25 * C_in, C_in swept
-        for cin in (64, 128, 256, 512):
-            xq = torch.empty((200, cin, 12, 12), dtype=torch.float32, device="cuda").normal_()
-            wq = torch.empty((64, cin, 5, 5), dtype=torch.float32, device="cuda").normal_()
-            Wq, alq = B.pack_conv_weights(wq), B.alpha_mean_abs(wq)
-            oq = torch.empty((200, 64, 8, 8), dtype=torch.float32, device="cuda")
-            wsq = torch.empty(B.workspace_bytes(B.OP_BINARY_CONV2D, (200, cin, 12, 12, 64, 5, 5, 1, 0)),
-                              dtype=torch.uint8, device="cuda")
-            other["paper_sec3_1_conv5x5_cin%d_call" % cin] = mfma(
-                2.0 * 64 * 12800 * 25 * cin, kernel_us(
-                    lambda: B.binary_conv2d(xq, Wq, 64, 5, 5, 1, 0, alpha=alq, out=oq, workspace=wsq)))
-
-        # Sec. 3.1's other two sweeps at 256 input channels, batch 200: filter count (5x5) and
-        # kernel size (64 filters), whole calls
+    # ------------------------------------------------------------------ the paper's Sec. 3.1 workloads
+    if want("sec31") and run_others:
         def conv_call(cin, cout, k):
             hw = 8 + k - 1
-            xq = torch.empty((200, cin, hw, hw), dtype=torch.float32, device="cuda").normal_()
-            wq = torch.empty((cout, cin, k, k), dtype=torch.float32, device="cuda").normal_()
+            wq = f32(cout, cin, k, k).normal_()
             Wq, alq = B.pack_conv_weights(wq), B.alpha_mean_abs(wq)
-            oq = torch.empty((200, cout, 8, 8), dtype=torch.float32, device="cuda")
-            wsq = torch.empty(B.workspace_bytes(B.OP_BINARY_CONV2D, (200, cin, hw, hw, cout, k, k, 1, 0)),
-                              dtype=torch.uint8, device="cuda")
-            us = kernel_us(lambda: B.binary_conv2d(xq, Wq, cout, k, k, 1, 0, alpha=alq, out=oq, workspace=wsq))
-            return alu(2.0 * cout * 12800 * k * k * cin, us)
+            wsb = B.workspace_bytes(B.OP_BINARY_CONV2D, (200, cin, hw, hw, cout, k, k, 1, 0))
+            n = nsets_for(200 * cin * hw * hw * 4 + wsb + 200 * cout * 64 * 4, cap=64)
+            xq = [f32(200, cin, hw, hw).normal_() for _ in range(n)]
+            oq = [f32(200, cout, 8, 8) for _ in range(n)]
+            wsq = [u8(wsb) for _ in range(n)]
+            us, nm = rotating_us([(lambda i=i: B.binary_conv2d(xq[i], Wq, cout, k, k, 1, 0, alpha=alq, out=oq[i],
+                                                               workspace=wsq[i])) for i in range(n)], reps=60)
+            ops = 2.0 * cout * 12800 * k * k * cin
+            return {"call_us_hbm_resident": us, "gops_call": ops / us / 1e3, "conv_kernel": nm}
 
+        # 5x5 kernels, 64 filters, batch 200, 8x8 outputs: GEMM view M = 64, N = 12800, K = 25 * C_in
+        for cin in (64, 128, 256, 512):
+            other["paper_sec3_1_conv5x5_cin%d_call" % cin] = conv_call(cin, 64, 5)
         for cout in (16, 128, 512):
             other["paper_sec3_1_conv5x5_cin256_filters%d_call" % cout] = conv_call(256, cout, 5)
         for k in (1, 3, 7):
             other["paper_sec3_1_conv%dx%d_cin256_call" % (k, k)] = conv_call(256, 64, k)
 
     # ------------------------------------------------------------------ CPU oracle beside it
-    cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.phase == "all":
         import oracle
-        alpha_h = oracle.alpha_mean_abs(w_h)
-        oracle.binary_conv2d(x_h[:1], w_h, stride, pad, alpha_h)  # page in
-        reps, t_cpu = 0, 0.0
-        while t_cpu < 10.0 and reps < 400:
-            t1 = time.perf_counter()
-            oracle.binary_conv2d(x_h, w_h, stride, pad, alpha_h)
-            t_cpu += time.perf_counter() - t1
-            reps += 1
-        cpu = {"value": binops * reps / t_cpu / 1e9, "unit": "GOPS", "cores": oracle.num_threads(),
-               "kind": "oracle", "sample": "%d full passes of the config-2 layer (%.3f s each)"
-               % (reps, t_cpu / reps)}
-        # the paper's own method on the same host cores (Sec. 2.2.1: xnor + popcount over 64-bit
-        # words), GEMM only on the layer's im2col view, as the paper times it (Sec. 3.1)
-        col = oracle.im2col(x_h, KH, KW, stride, pad)
-        Ap = oracle.binarize_pack(w_h.reshape(O, -1), 1)
-        Bp = oracle.binarize_pack(col, 1)
-        del col
-        oracle.xnor_gemm(Ap, Bp, C * KH * KW)
-        t1 = time.perf_counter()
-        for _ in range(5):
-            oracle.xnor_gemm(Ap, Bp, C * KH * KW)
-        t_x = (time.perf_counter() - t1) / 5
-        cpu["xnor_popcount_gemm_only"] = {"value": binops / t_x / 1e9, "unit": "GOPS",
-                                          "sample": "5 passes of the 64 x 50176 x 576 GEMM on packed words (%.4f s each), "
-                                                    "packing not timed" % t_x}
+        gomp = None
+        try:
+            gomp = ctypes.CDLL("libgomp.so.1")
+        except OSError:
+            pass
+        cores = oracle.num_threads()
 
-    line = {"metric": "binary GOPS (2*M*N*K xnor-popcount)", "value": value, "unit": "GOPS",
-            "n_gpus": 1, "steps": K_STEPS, "warmup": args.warmup, "ms_per_step": ms_per_step,
-            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u64 bits -> i32",
-            "data": "synthetic",
-            "config": {"workload": "config2: binary conv2d 3x3 s1 p1, x[16,64,56,56], 64 filters, "
-                                   "alpha epilogue, fp32 out (GEMM view M=64 N=50176 K=576)",
-                       "step": "bmx_binary_conv2d = channel pack + implicit-GEMM conv + alpha",
-                       "kernels": "pack_nchw_kernel + " + ("conv_stationary_kernel<9,2>" if popcount_conv
-                                                           else "conv_mfma_ws_kernel<9,1,4,false>"),
-                       "timed_region": "one replay of a HIP graph holding the K steps",
-                       "buffer_sets_rotated": int(nsets),
-                       "ms_per_step_cache_hot": hot_us * 1e-3,
-                       "ms_per_step_eager": eager_ms,
-                       "ms_per_step_batches_overlapped_on_streams": overlapped_ms,
-                       "streams_for_overlap": n_str},
-            "roofline": roofline, "cpu_baseline": cpu, "other_configs": other}
+        def timed(fn, budget_s, max_reps=1000):
+            fn()  # page in
+            reps, t = 0, 0.0
+            while t < budget_s and reps < max_reps:
+                t1 = time.perf_counter()
+                fn()
+                t += time.perf_counter() - t1
+                reps += 1
+            return t / reps, reps
+
+        def entry(ops, fn, budget_s, what):
+            s, reps = timed(fn, budget_s)
+            return {"value": ops / s / 1e9, "unit": "GOPS", "cores": cores, "seconds_per_pass": s,
+                    "sample": "%d full passes of %s" % (reps, what)}
+
+        a1h, a2h = oracle.alpha_mean_abs(c3["w1"]), oracle.alpha_mean_abs(c3["w2"])
+
+        def chain():
+            _, r1 = oracle.binary_fc(c3["x"], c3["w1"], a1h)
+            oracle.binary_fc(r1, c3["w2"], a2h)
+
+        cpu = entry(ops1 + ops2, chain, 6.0, "the config-3 layer pair")
+        cpu["kind"] = "oracle"
+        per = {}
+        c1 = synth.config1()
+        w1t = c1["w_kn"].T.copy()
+        per["config1"] = entry(2.0 * 64 * 256 * 512, lambda: oracle.binary_fc(c1["a"], w1t), 0.5, "the config-1 layer")
+        c2 = synth.config2()
+        al2h = oracle.alpha_mean_abs(c2["w"])
+        ops_c2 = 2.0 * 64 * 50176 * 576
+        per["config2"] = entry(ops_c2, lambda: oracle.binary_conv2d(c2["x"], c2["w"], 1, 1, al2h), 2.0, "the config-2 layer")
+        for s4 in (1, 2):
+            c4 = synth.config4(stride=s4)
+            al4h = oracle.alpha_mean_abs(c4["w"])
+            ho = 14 // s4
+            per["config4_stride%d" % s4] = entry(2.0 * 256 * 64 * ho * ho * 2304,
+                                                 lambda: oracle.binary_conv2d(c4["x"], c4["w"], s4, 1, al4h), 2.0,
+                                                 "the config-4 layer, stride %d" % s4)
+        c5 = synth.config5()
+        per["config5"] = entry(2.0 * 2 * 1024 * 1024 * 4096, lambda: oracle.quant_gemm(c5["a"], c5["w"], 2), 2.0,
+                               "the config-5 GEMM (2 plane pairs counted)")
+        if gomp is not None:  # one thread, for the two small configurations
+            gomp.omp_set_num_threads(1)
+            try:
+                e = entry(2.0 * 64 * 256 * 512, lambda: oracle.binary_fc(c1["a"], w1t), 0.3, "the config-1 layer")
+                e["cores"] = 1
+                per["config1_one_thread"] = e
+                e = entry(ops_c2, lambda: oracle.binary_conv2d(c2["x"], c2["w"], 1, 1, al2h), 1.0, "the config-2 layer")
+                e["cores"] = 1
+                per["config2_one_thread"] = e
+            finally:
+                gomp.omp_set_num_threads(cores)
+        cpu["per_config"] = per
+
+        # the paper's own method on the same host cores (Sec. 2.2.1: xnor + popcount over 64-bit
+        # words, OpenMP), GEMM only, packing not timed, as the paper times it (Sec. 3.1)
+        try:
+            so = os.path.join(tempfile.mkdtemp(prefix="bmx_host_xnor_"), "host_xnor.so")
+            subprocess.check_call(["gcc", "-O3", "-march=native", "-fopenmp", "-fPIC", "-shared",
+                                   os.path.join(ROOT, "bench_host_xnor.c"), "-o", so])
+            hx = ctypes.CDLL(so)
+            hx.host_xnor_gemm.argtypes = [ctypes.c_void_p] * 3 + [ctypes.c_long] * 4 + [ctypes.c_int]
+            hx.host_xnor_threads.restype = ctypes.c_int
+            xn = {}
+            for tag, a_f, b_f in (("config3_fc1_gemm_256x4096x9216", c3["x"], c3["w1"]),
+                                  ("config2_gemm_view_64x50176x576", c2["w"].reshape(64, -1),
+                                   oracle.im2col(c2["x"], 3, 3, 1, 1))):
+                Ap, Bp = oracle.binarize_pack(a_f, 1), oracle.binarize_pack(b_f, 1)
+                M_, N_, Kw_, K_ = Ap.shape[0], Bp.shape[0], Ap.shape[1], a_f.shape[1]
+                Cc = np.empty((M_, N_), dtype=np.int32)
+                for thr_ in (0, 1):
+                    s, reps = timed(lambda: hx.host_xnor_gemm(Ap.ctypes.data, Bp.ctypes.data, Cc.ctypes.data,
+                                                              M_, N_, Kw_, K_, thr_), 1.0)
+                    xn[tag + ("_one_thread" if thr_ else "")] = {
+                        "value": 2.0 * M_ * N_ * K_ / s / 1e9, "unit": "GOPS",
+                        "cores": 1 if thr_ else int(hx.host_xnor_threads()), "seconds_per_pass": s,
+                        "sample": "%d passes of the GEMM on packed 64-bit words, packing not timed" % reps}
+            cpu["host_xnor_popcount_gemm"] = dict(xn, kind="uint64 xor + popcount GEMM with OpenMP (bench_host_xnor.c): "
+                                                            "the paper's method on this host, context only, not the oracle")
+        except (OSError, subprocess.CalledProcessError) as e:  # no host compiler: the figure is context only
+            cpu["host_xnor_popcount_gemm"] = {"error": str(e)}
+
+    if "value" not in line:  # a phase without the headline: the line still parses
+        line.update({"value": None, "ms_per_step": None, "dtype": None, "config": {"workload": "phase " + args.phase},
+                     "roofline": None})
+    line["valu_probe"] = probe
+    line["cpu_baseline"] = cpu
+    line["other_configs"] = other or None
     print(json.dumps(line))
 
 

@@ -282,6 +282,20 @@ size_t bmx_workspace_bytes(int op, const int64_t* dims, int ndims);
  *          kernels */
 int bmx_tune_set(int key, int value);
 
+/* Measurement hooks (not part of the layers the paper defines).
+ * bmx_last_kernel: name, template arguments and launch shape of the last compute kernel the
+ *   calling thread launched through this library ("" before the first); a static buffer
+ *   overwritten by the thread's next call.  Benchmarks label their figures with it.
+ * bmx_probe_valu: a register-only chain of v_xor_b32 + v_bcnt_u32_b32 pairs (the inner loop of
+ *   the xor/popcount kernels with nothing around it), `workgroups` workgroups of 256 lanes, each
+ *   lane 128 * iters pairs, i.e. workgroups * 256 * iters * 128 * 64 binary operations per
+ *   launch.  Timed by the caller, it gives the VALU xor+popcount peak actually reachable; the
+ *   first wave also writes out3[0] = shader clock cycles and out3[1] = constant-rate wall clock
+ *   ticks (*wall_clock_khz per millisecond) it spent in the chain, whose ratio is the shader
+ *   clock observed under load.  out3: device, 3 x uint64, 8-byte aligned. */
+const char* bmx_last_kernel(void);
+int bmx_probe_valu(int workgroups, int iters, unsigned long long* out3, int* wall_clock_khz, void* stream);
+
 /* Static, human-readable name of a status code. */
 const char* bmx_status_string(int status);
 

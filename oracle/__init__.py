@@ -31,7 +31,11 @@ def _cpu_tag():
     return hashlib.sha1(flags.encode()).hexdigest()[:10]
 
 
-_LIB = os.path.join(_HERE, "libbmx_oracle.%s.so" % _cpu_tag())
+# BMX_ORACLE_SANITIZE=1 builds and loads a second copy of the oracle with AddressSanitizer and
+# UndefinedBehaviorSanitizer (host code only; run the CPU tests with
+# LD_PRELOAD=$(gcc -print-file-name=libasan.so) so that the runtime is loaded first).
+_SANITIZE = os.environ.get("BMX_ORACLE_SANITIZE", "") not in ("", "0")
+_LIB = os.path.join(_HERE, "libbmx_oracle.%s%s.so" % (_cpu_tag(), ".san" if _SANITIZE else ""))
 _lib = None
 
 _i64 = ctypes.c_int64
@@ -45,6 +49,9 @@ def build(force=False):
         return _LIB
     cmd = ["g++", "-O3", "-march=native", "-fopenmp", "-std=c++17", "-fPIC", "-shared",
            _SRC, "-o", _LIB]
+    if _SANITIZE:
+        cmd[1:2] = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+                    "-fno-omit-frame-pointer"]
     subprocess.check_call(cmd)
     return _LIB
 

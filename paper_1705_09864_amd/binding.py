@@ -21,7 +21,8 @@ EXPORTS = ["bmx_binarize_pack", "bmx_xnor_gemm", "bmx_binary_fc", "bmx_pack_conv
            "bmx_binary_conv2d_packed", "bmx_workspace_bytes", "bmx_status_string", "bmx_version",
            "bmx_conv_weight_row_words", "bmx_binary_fc_packed", "bmx_tune_set",
            "bmx_binary_conv2d_bits", "bmx_xnor_gemm_count", "bmx_unpack_pm1", "bmx_widen_words32",
-           "bmx_xnor_gemm_w32", "bmx_binary_fc_static"]
+           "bmx_xnor_gemm_w32", "bmx_binary_fc_static", "bmx_last_kernel",
+           "bmx_probe_valu"]
 
 _i64, _int, _p, _sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
 
@@ -74,6 +75,9 @@ def lib():
         L.bmx_xnor_gemm_w32.restype = _int
         L.bmx_binary_fc_static.argtypes = [_p, _i64, _p, _i64, _p, _int, _int, _int, _p, _p, _i64, _p]
         L.bmx_binary_fc_static.restype = _int
+        L.bmx_last_kernel.restype = ctypes.c_char_p
+        L.bmx_probe_valu.argtypes = [_int, _int, _p, ctypes.POINTER(_int), _p]
+        L.bmx_probe_valu.restype = _int
         L.bmx_tune_set.argtypes = [_int, _int]
         L.bmx_tune_set.restype = _int
         for name in EXPORTS[:9]:
@@ -84,6 +88,21 @@ def lib():
 
 def status_string(status):
     return lib().bmx_status_string(int(status)).decode()
+
+
+def last_kernel():
+    """Name and launch shape of the last compute kernel this thread launched through the library."""
+    return lib().bmx_last_kernel().decode()
+
+
+def probe_valu(workgroups, iters, out3, stream=None):
+    """Launch the register-only xor+popcount chain; returns the wall-clock rate in kHz.  out3 is
+    an int64 device tensor of 3 elements (cycles, wall ticks, sink)."""
+    _chk(out3, _U64, "probe_valu out3", dense=True)
+    khz = _int(0)
+    _check(lib().bmx_probe_valu(int(workgroups), int(iters), _ptr(out3), ctypes.byref(khz), _stream(stream)),
+           "bmx_probe_valu")
+    return int(khz.value)
 
 
 def version():

@@ -4,6 +4,8 @@
 #include "../../include/bmx.h"
 #include "bmx_internal.h"
 
+#include <cstdarg>
+#include <cstdio>
 #include <mutex>
 
 // Scratch memory of bmx_binary_fc_static, the entry point for callers that cannot allocate: one
@@ -67,6 +69,13 @@ QuantWs quant_ws(int64_t M, int64_t N, int64_t K, int bits_a, int bits_w) {
 }  // namespace
 
 namespace bmx {
+static thread_local char last_kernel_name[160] = "";
+void note_kernel(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(last_kernel_name, sizeof(last_kernel_name), fmt, ap);
+  va_end(ap);
+}
 extern int conv_filters_per_wave, conv_path;
 extern int gemm_tune_rows, gemm_tune_ksplit, gemm_tune_order;
 }
@@ -92,7 +101,21 @@ int bmx_tune_set(int key, int value) {
   return BMX_OK;
 }
 
-int bmx_version(void) { return 100; }
+int bmx_version(void) { return 200; }
+
+const char* bmx_last_kernel(void) { return bmx::last_kernel_name; }
+
+int bmx_probe_valu(int workgroups, int iters, unsigned long long* out3, int* wall_clock_khz, void* stream) {
+  if (workgroups <= 0 || iters <= 0 || workgroups > (1 << 20) || iters > (1 << 24)) return BMX_ERR_SHAPE;
+  if (!out3 || !wall_clock_khz) return BMX_ERR_NULL;
+  if (misaligned(out3, 8)) return BMX_ERR_ALIGN;
+  int dev = 0, khz = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess)
+    return BMX_ERR_HIP;
+  *wall_clock_khz = khz;
+  return hip_status(bmx::launch_probe_valu(workgroups, iters, out3, (hipStream_t)stream));
+}
 
 const char* bmx_status_string(int status) {
   switch (status) {

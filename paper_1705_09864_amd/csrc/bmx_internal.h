@@ -21,6 +21,10 @@ __device__ static inline uint32_t fast_div(uint32_t n, FastDiv f) {
 
 __host__ __device__ static inline int64_t words_for(int64_t k) { return (k + 63) / 64; }
 
+// Name (with template arguments and launch shape) of the kernel the calling thread launched
+// last: what bmx_last_kernel() reports, so that measurements label themselves.
+void note_kernel(const char* fmt, ...) __attribute__((format(printf, 1, 2)));
+
 // Packed rows that feed the scalar side of the GEMM kernel are zero padded to whole
 // 32-dword chunks, so that every chunk of a row can be fetched with two 64-byte scalar loads.
 __host__ __device__ static inline int64_t padded_words(int64_t K) {
@@ -88,6 +92,9 @@ hipError_t launch_quant_pack(const float* a, int64_t M, int64_t K, int64_t lda, 
                              hipStream_t s, bool affine = false);
 hipError_t launch_quant_combine(const int32_t* T, int64_t M, int64_t N, int bw, float denom, int32_t* S,
                                 float* out, int64_t ldo, hipStream_t s);
+
+// probe.hip: register-only xor + popcount chain, for the peak and clock measurement hook.
+hipError_t launch_probe_valu(int workgroups, int iters, unsigned long long* out3, hipStream_t s);
 
 // gemm.hip -------------------------------------------------------------------
 // out = K - 2*popcount(A ^ B); exactly one of C_i32 / C_f32 / C_bits non-null;

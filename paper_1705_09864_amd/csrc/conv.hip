@@ -230,6 +230,8 @@ conv_general_kernel(const uint64_t* __restrict__ Xp, const uint64_t* __restrict_
 template <int KW>
 void launch_stationary(const ConvParams& p, int64_t groups, int cblocks, hipStream_t s) {
   dim3 grid((unsigned)ceil_div(groups, 4), (unsigned)cblocks);
+  note_kernel("conv_stationary_kernel<%d,%s> grid %u x %u x 256, %d filters per wave", KW,
+              p.out_f32 ? (p.alpha ? "f32*alpha" : "f32") : "i32", grid.x, grid.y, p.cn);
   if (p.out_f32 && p.alpha)
     hipLaunchKernelGGL((conv_stationary_kernel<KW, kOutF32Alpha>), grid, dim3(256), 0, s, p);
   else if (p.out_f32)
@@ -354,6 +356,7 @@ hipError_t launch_binary_conv2d(const uint64_t* Xp, int N, int C, int H, int W, 
     return hipGetLastError();
   }
   dim3 grid((unsigned)groups, (unsigned)ceil_div(O, 4));
+  note_kernel("conv_general_kernel grid %u x %u x 256", grid.x, grid.y);
   hipLaunchKernelGGL(conv_general_kernel, grid, dim3(256), 0, s, Xp, Wp, alpha, out_i32, out_f32, P,
                      O, Ho * Wo, Wo, Hp, Wpp, Cw, stride, KH, KW, C * KH * KW, ld_words, d1, d2);
   return hipGetLastError();

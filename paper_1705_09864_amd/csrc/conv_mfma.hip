@@ -303,6 +303,8 @@ conv_mfma_ws_kernel(const WsParams p) {
 template <int KW, int TM, int WPS, bool BITS = false>
 void launch_ws(const WsParams& p, int m_tiles, hipStream_t s) {
   const int chunks = p.nchunks;
+  note_kernel("conv_mfma_ws_kernel<%d,%d,%d,%s> grid %d x %d x 256", KW, TM, WPS, BITS ? "true" : "false",
+              (int)ceil_div(chunks, 4), m_tiles);
   hipLaunchKernelGGL((conv_mfma_ws_kernel<KW, TM, WPS, BITS>), dim3((unsigned)ceil_div(chunks, 4), (unsigned)m_tiles),
                      dim3(256), 0, s, p);
 }

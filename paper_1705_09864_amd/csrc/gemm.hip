@@ -386,6 +386,8 @@ void launch_rs(const GemmParams& p, int S, hipStream_t s) {
     raised = true;
   }
   dim3 grid((unsigned)(ceil_div(p.N, 64) * p.row_blocks));
+  note_kernel("gemm_kernel<%d,%d,%s,%s,%s> grid %u x %d", R, CH, OP_AND ? "and" : "xor", PF ? "prefetch" : "noprefetch",
+              CONV ? "conv" : "gemm", grid.x, 64 * S);
   hipLaunchKernelGGL(kern, grid, dim3(64 * S), lds_bytes, s, p);
 }
 

@@ -512,6 +512,8 @@ namespace {
 
 template <int TM, int TN, int PL, bool XNOR, bool CONV>
 void launch_engine(const MfmaParams& p, bool f4, int64_t tiles, int S, size_t lds, hipStream_t s) {
+  note_kernel("gemm_mfma_kernel<%d,%d,%d,%s,%s,%s> grid %lld x %d", TM, TN, PL, XNOR ? "xnor" : "planes",
+              CONV ? "conv" : "gemm", f4 ? "fp4" : "int8", (long long)tiles, 64 * S);
   if (f4)
     hipLaunchKernelGGL((gemm_mfma_kernel<TM, TN, PL, XNOR, CONV, true>), dim3((unsigned)tiles), dim3(64 * S), lds,
                        s, p);

@@ -71,6 +71,7 @@ static void launch_pack_rows_grid(const float* x, int64_t rows, int64_t cols, in
     const int64_t spr = ceil_div(words_per_row, 32);
     int64_t blocks = ceil_div(rows * spr, 4);
     blocks = blocks < cap ? blocks : cap;
+    note_kernel("pack_rows_kernel<32,nontemporal> grid %lld x 256", (long long)blocks);
     hipLaunchKernelGGL((pack_rows_kernel<32, true>), dim3((unsigned)blocks), dim3(256), 0, s, x, rows, cols, ldx,
                        out, out_ld, words_per_row, spr, ceil_div(rows * spr, blocks));
     return;
@@ -78,6 +79,7 @@ static void launch_pack_rows_grid(const float* x, int64_t rows, int64_t cols, in
   const int64_t spr = ceil_div(words_per_row, kSegWords);
   int64_t blocks = ceil_div(rows * spr, 4);
   blocks = blocks < cap ? blocks : cap;
+  note_kernel("pack_rows_kernel<16,cached> grid %lld x 256", (long long)blocks);
   hipLaunchKernelGGL((pack_rows_kernel<kSegWords, false>), dim3((unsigned)blocks), dim3(256), 0, s, x, rows, cols,
                      ldx, out, out_ld, words_per_row, spr, ceil_div(rows * spr, blocks));
 }
@@ -199,6 +201,7 @@ hipError_t launch_pack_strided(const float* x, int64_t batch, int64_t K, int64_t
   const int64_t groups = ceil_div(ncol, 64);
   const int64_t blocks = ceil_div(batch * Kw * groups, 4);
   const int64_t cap = 256 * 6;  // the kernel holds 64 loaded values per lane: 6 waves per SIMD
+  note_kernel("pack_strided_kernel grid %lld x 256", (long long)(blocks < cap ? blocks : cap));
   hipLaunchKernelGGL(pack_strided_kernel, dim3((unsigned)(blocks < cap ? blocks : cap)), dim3(256), 0,
                      s, x, batch, K, ncol, ldx, batch_stride, out, out_ld, Kw, groups);
   return hipGetLastError();
@@ -283,6 +286,7 @@ hipError_t launch_pack_nchw_thr(const float* x, int N, int C, int H, int W, int 
   const int Cw = (int)words_for(C);
   const int HW = H * W;
   dim3 grid((unsigned)ceil_div(HW, 256), (unsigned)Cw, (unsigned)N);
+  note_kernel("pack_nchw_kernel<%s> grid %u x %u x %u x 256", thr ? "thr" : "sign", grid.x, grid.y, grid.z);
   if (thr)
     hipLaunchKernelGGL(pack_nchw_kernel<true>, grid, dim3(256), 0, s, x, C, HW, W, pad, H + 2 * pad,
                        W + 2 * pad, Cw, thr, xp);
@@ -484,6 +488,7 @@ hipError_t launch_quant_pack(const float* a, int64_t M, int64_t K, int64_t lda, 
     if (wblocks > 256 * 8) wblocks = 256 * 8;
     per = ceil_div(segs, wblocks);
   }
+  note_kernel("quant_pack_kernel grid %lld x 256", (long long)(M + wblocks));
   hipLaunchKernelGGL(quant_pack_kernel, dim3((unsigned)(M + wblocks)), dim3(256), 0, s, a, M, K, lda,
                      bits, planes, ld_words, rowsum, w, wrows, ldw, wbits, wb_ld, per, affine ? 1 : 0);
   return hipGetLastError();
