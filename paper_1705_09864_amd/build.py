@@ -8,11 +8,14 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libbmx.so")
-SOURCES = ["bmx_api.hip", "pack.hip", "gemm.hip", "gemm_mfma.hip", "conv.hip", "conv_mfma.hip", "probe.hip"]
+SOURCES = ["bmx_api.hip", "pack.hip", "gemm.hip", "gemm_mfma.hip", "gemm_fp4.hip", "conv.hip", "conv_mfma.hip", "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # packed-fp32 VALU forms are kept out of generated code on the test machines
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # host-pass errors inside kernel bodies are reported, not deferred (deferred, they leave the
+         # kernel's host stub undefined without a word)
+         "-fno-gpu-defer-diag",
          "-Wno-unused-command-line-argument"]
 
 
@@ -98,7 +101,9 @@ def build(force=True, verbose=False):
         objs = list(ex.map(compile_one, SOURCES))
     check_scalar_loads()
     check_codegen()
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB]
+    # (-z defs: an undefined symbol, e.g. a kernel stub the host pass dropped, fails the link here
+    # instead of the first call)
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-Wl,-z,defs"] + objs + ["-o", LIB]
     subprocess.check_call(cmd)
     return LIB
 

@@ -114,6 +114,15 @@ bool launch_xnor_gemm_mfma(const uint64_t* A, int64_t lda_w, const uint64_t* B, 
                            int N, int K, const float* alpha_n, int32_t* C_i32, float* C_f32,
                            uint64_t* C_bits, const float* thr_n, int64_t ldc, hipStream_t s, hipError_t* err,
                            bool as_count = false);
+// gemm_fp4.hip: the same products with 64 x 64 of C per wave, operands staged through LDS by
+// the load unit, K split over the waves of a workgroup (FP4 only; planes = 1 with rowsum null is
+// the xnor form, otherwise the plane form with 1 or 2 planes).  Returns false when it does not
+// take the problem.
+bool launch_gemm_fp4(const uint64_t* A, int64_t lda_w, int planes, const int32_t* rowsum, const uint64_t* B,
+                     int64_t ldb_w, int M, int N, int K, const float* alpha_n, int32_t* C_i32, float* C_f32,
+                     uint64_t* C_bits, const float* thr_n, int64_t ldc, bool as_count, hipStream_t s,
+                     hipError_t* err);
+extern int gemm_fp4_split;
 bool launch_plane_gemm_mfma(const uint64_t* planes_rows, int64_t lda_w, int bits, const int32_t* rowsum,
                             const uint64_t* Wb, int64_t ldb_w, int M, int N, int K, int32_t* S_out,
                             float* out_f32, int64_t ldo, hipStream_t s, hipError_t* err);

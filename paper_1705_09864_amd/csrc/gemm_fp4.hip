@@ -1,0 +1,533 @@
+// xnor GEMM and bit-plane GEMM on the FP4 matrix cores: 64 x 64 of C per wave, operands staged
+// through LDS by the load unit itself, K split over the waves of a workgroup.
+// Paper: Sec. 2.2.1 / Sec. 2.2.2 (Eq. 2): C[m][n] = K - 2 * popcount(A[m] xor B[n]); Sec. 2.1
+// (Eq. 1) for the k-bit activations of the plane form.
+//
+// Arithmetic (as in gemm_mfma.hip): with bits a, b in {0, 1},
+//     K - 2 * pc(a xor b) = K - 2 * pc(a) - 2 * pc(b) + 4 * sum_k a * b,
+// the sum on v_mfma_scale_f32_32x32x64_f8f6f4 with both operands FP4 (E2M1).  A bit stays where
+// it stands in its nibble (worth 0.5, 1 or 2 there; the nibble's top bit is shifted down) and
+// the block scale of each MFMA brings the product back to 1, so one 32-bit word of bits becomes
+// the four 8-nibble operand dwords of four MFMAs with five VALU instructions.  Products and
+// fp32 sums are exact integers below 2^24.  Bit planes of a k-bit activation are separate A
+// operands of the same rows whose block scale carries the plane's power of two: every plane
+// costs what a 1-bit operand costs, and the planes add up in the accumulator.
+//
+// What bounds this kernel is not the matrix core but everything around it: the VALU work of
+// turning bits into nibbles, the loads, and fixed costs of a few-microsecond launch.  Hence:
+//   - 2 x 2 blocks of 32 x 32 per wave: an expanded operand block serves two MFMAs, 5 VALU
+//     instructions of expansion and 1 of row popcount per MFMA (a 32 x 32 tile needs 12).
+//   - Operands travel global memory -> LDS without passing registers (global_load_lds_dwordx4:
+//     lane i of the instruction writes LDS bytes [16 i, 16 i + 16) of its destination).  A load
+//     covers 16 rows x 64 bytes, 4 lanes per row: whole 64-byte runs, so the memory pipeline
+//     works at its coalesced rate, where the MFMA layout (lane = row) costs an access per lane.
+//     Which 16-byte piece a lane fetches is permuted (piece = slot xor ((row >> 1) & 3)), so
+//     that the MFMA-layout reads, lane (r, h) <- piece 2 g + h of row r, fall on all banks.
+//   - A wave owns its staging area and its range of K: no barrier in the main loop.  The words
+//     of a 64-byte segment are read into registers, the next segment's loads are issued into
+//     the same area, and the 32 MFMAs of the segment run with those loads in flight.
+//   - Skinny problems (the fully connected layers: 256 rows) have too few 64 x 64 tiles to
+//     fill the chip, so the S waves of a workgroup split K and add their partial tiles through
+//     LDS once: every wave writes its 64 registers, then finishes 1/S of the tile (sum of S
+//     partials, the popcount terms, scale, store).  Fat problems run four tiles per workgroup
+//     and no split.
+//   - Workgroups are numbered so that tiles sharing rows of B (the large operand: weights) sit
+//     on one XCD and run back to back: workgroup b runs on XCD b % 8.
+#include "bmx_internal.h"
+
+namespace bmx {
+
+namespace {
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef int v4i_alias __attribute__((ext_vector_type(4), may_alias));
+typedef __attribute__((address_space(3))) void* lds_ptr;
+
+struct Fp4Params {
+  const uint64_t* A;  // [M * PL][lda] words (plane pl of row m is row m * PL + pl), tail bits zero
+  const uint64_t* B;  // [N][ldb] words
+  uint32_t lda_bytes, ldb_bytes;  // row strides, multiples of 16
+  int M, N, Kw, Kreal;            // Kw data words per row
+  int g_base, g_rem;  // groups of four words (256 bits = the K of four MFMAs) per wave: g_base, the first g_rem waves one more
+  int tiles_m, tiles_n, tiles_per_xcd;
+  FastDiv div_tiles_m;
+  const float* alpha;     // per column n, or null
+  const float* thr;       // packed-bit output: per column threshold of the sign decision, or null (0)
+  const int32_t* rowsum;  // plane form: sum_k q[m][k]
+  float levels;           // plane form: 2^bits - 1
+  int as_count;           // int32 output holds the xnor count (dot + K) / 2
+  int32_t* C_i32;
+  float* C_f32;
+  uint32_t* C_bits;  // packed sign bits, addressed in 32-bit halves of the output words
+  int ldc;           // elements per row (C_bits: 64-bit words per row); M * ldc < 2^31
+};
+
+// One nibble plane of four words of bits as the four operand dwords of one MFMA.
+//   n = 0: w & 0x11111111 (0.5)   n = 1: w & 0x22222222 (1.0)   n = 2: w & 0x44444444 (2.0)
+//   n = 3: (w >> 3) & 0x11111111 (0.5), hi = w >> 3 computed once per word
+__device__ __forceinline__ v8i nibble_plane(const uint4& w, const uint4& hi, int n) {
+  v8i e;
+  if (n == 3) {
+    e[0] = (int)(hi.x & 0x11111111u);
+    e[1] = (int)(hi.y & 0x11111111u);
+    e[2] = (int)(hi.z & 0x11111111u);
+    e[3] = (int)(hi.w & 0x11111111u);
+  } else {
+    const uint32_t m = 0x11111111u << n;
+    e[0] = (int)(w.x & m);
+    e[1] = (int)(w.y & m);
+    e[2] = (int)(w.z & m);
+    e[3] = (int)(w.w & m);
+  }
+  e[4] = e[5] = e[6] = e[7] = 0;
+  return e;
+}
+
+__device__ __forceinline__ int popcount4(const uint4& w) {
+  return __builtin_popcount(w.x) + __builtin_popcount(w.y) + __builtin_popcount(w.z) + __builtin_popcount(w.w);
+}
+
+// Request segment `seg` (64 bytes of every row of the wave's NB staged blocks) into the staging
+// area at dst: per block two loads of 16 rows, lane i of a load writing LDS bytes [16 i, 16 i + 16)
+// of its destination.  voff: a lane's byte offset of its piece in segment 0 of its row.
+template <int NA, int NB>
+__device__ __forceinline__ void issue_segment(const Fp4Params& p, uint4* dst, const uint32_t* voff /* [NB][2] */,
+                                              int piece0, int piece1, int seg) {
+  const char* abase = (const char*)p.A + (uint32_t)seg * 64u;
+  const char* bbase = (const char*)p.B + (uint32_t)seg * 64u;
+  if (8 * seg + 8 <= p.Kw) {
+#pragma unroll
+    for (int b = NB - 1; b >= 0; --b)  // (B first: its rows are the ones that come from far away)
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+        __builtin_amdgcn_global_load_lds((b < NA ? abase : bbase) + voff[2 * b + t], (lds_ptr)(dst + b * 128 + t * 64),
+                                         16, 0, 0);
+  } else {
+    // the row ends inside this segment: a piece that starts beyond its last word is not fetched
+    // (the reader zeroes it); its lane repeats the segment's first piece instead
+#pragma unroll
+    for (int b = NB - 1; b >= 0; --b)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const int pc = t ? piece1 : piece0;
+        const uint32_t back = 8 * seg + 2 * pc >= p.Kw ? 16u * pc : 0u;
+        __builtin_amdgcn_global_load_lds((b < NA ? abase : bbase) + (voff[2 * b + t] - back),
+                                         (lds_ptr)(dst + b * 128 + t * 64), 16, 0, 0);
+      }
+  }
+}
+
+#ifdef BMX_FP4_STAMPS
+// Profiling builds only: per-wave shader-clock stamps at the phase boundaries of the kernel.
+}  // namespace
+unsigned long long* fp4_stamps = nullptr;
+namespace {
+#define FP4_STAMP(k) do { if (stamps && lane == 0) stamps[(size_t)(blockIdx.x * (blockDim.x >> 6) + wave) * 8 + (k)] = __builtin_readcyclecounter(); } while (0)
+#else
+#define FP4_STAMP(k) do { } while (0)
+#endif
+
+// Output kinds of the xnor form (the plane form stores S and / or S / levels as its pointers say).
+constexpr int kOutF32 = 0, kOutI32 = 1, kOutBits = 2;
+
+// TM x TN blocks of 32 x 32 per wave; PL bit planes per A row; XNOR: the xnor form (row
+// popcounts from the words themselves), else the plane form (row sums given); OUT: what the
+// xnor form stores; SPLIT: K split over the S waves of the workgroup (else a tile per wave).
+// One instantiation per combination keeps each kernel's code short: the instruction cache
+// starts cold at every launch, and a launch lasts a few microseconds.
+template <int TM, int TN, int PL, bool XNOR, int OUT, bool SPLIT>
+__global__ void __launch_bounds__(512)
+gemm_fp4_kernel(const Fp4Params p, const int S_arg
+#ifdef BMX_FP4_STAMPS
+                , unsigned long long* stamps
+#endif
+) {
+  extern __shared__ uint4 lds[];
+  constexpr int NA = TM * PL, NB = NA + TN;  // staged blocks of 32 rows: A's, then B's
+  constexpr int kStage = NB * 128;           // uint4 per staged segment: NB blocks x 32 rows x 64 bytes
+  constexpr int kGroups = TM * TN * 4;       // a wave's accumulators in units of four registers
+  constexpr int kCnt = (TM + TN) * 8;        // uint4 holding a wave's 32 (TM + TN) popcounts
+  // LDS per wave: its staging areas (two where that costs no more than the partial tile needs
+  // anyway), overlaid after the main loop by its partial tile + counts
+#ifndef BMX_FP4_AHEAD
+#define BMX_FP4_AHEAD 1
+#endif
+  constexpr int kBufs = (NB <= 4 && BMX_FP4_AHEAD == 2) ? 2 : 1;
+  constexpr int kSlot = kBufs * kStage > kGroups * 64 + kCnt ? kBufs * kStage : kGroups * 64 + kCnt;
+  const int S = SPLIT ? S_arg : 1;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int r = lane & 31, h = lane >> 5;
+  FP4_STAMP(0);
+  const int ks = SPLIT ? wave : 0;          // this wave's part of K
+  const int tile_in_wg = SPLIT ? 0 : wave;  // without a split every wave has a tile of its own
+  const int tiles_per_wg = SPLIT ? 1 : (int)(blockDim.x >> 6);
+  // workgroup b sits on XCD b % 8: give every XCD a contiguous run of tiles, rows of C fastest
+  const int lin = ((int)(blockIdx.x & 7) * p.tiles_per_xcd + (int)(blockIdx.x >> 3)) * tiles_per_wg + tile_in_wg;
+  const bool live = lin < p.tiles_m * p.tiles_n;
+  if (!SPLIT && !live) return;  // (no barrier ahead without a split)
+  const int tile_n = live ? (int)fast_div((uint32_t)lin, p.div_tiles_m) : 0;
+  const int tile_m = live ? lin - tile_n * p.tiles_m : 0;
+  const int m0 = tile_m * (32 * TM), n0 = tile_n * (32 * TN);
+
+  // ---- this wave's K range in groups of four words.  The first g_rem waves carry one group
+  // more: waves w and w + 4 share a SIMD, so with the extras up front the SIMDs stay level (36
+  // groups over 8 waves: 5 5 5 5 4 4 4 4, nine per SIMD).
+  const int g_lo = ks * p.g_base + min(ks, p.g_rem), g_hi = g_lo + p.g_base + (ks < p.g_rem ? 1 : 0);
+  const int seg_lo = g_lo >> 1, seg_hi = (g_hi + 1) >> 1;  // 64-byte segments [seg_lo, seg_hi) of two groups
+
+  // ---- loader: lane i of load t of a block fetches, for local row 16 t + i / 4, the piece
+  // (i % 4) xor ((row >> 1) & 3) of the segment; voff = byte offset of that piece in segment 0.
+  uint4* const stage = lds + wave * kSlot;
+  int piece[2];
+  uint32_t voff[NB][2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) piece[t] = (lane & 3) ^ (((16 * t + (lane >> 2)) >> 1) & 3);
+#pragma unroll
+  for (int b = NB - 1; b >= 0; --b)  // (B first: its rows are the ones that come from far away)
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int rl = 16 * t + (lane >> 2);
+      if (b < NA) {  // block b = row block b / PL, plane b % PL
+        const int m = min(m0 + 32 * (b / PL) + rl, p.M - 1);
+        voff[b][t] = (uint32_t)(m * PL + (b % PL)) * p.lda_bytes + 16u * piece[t];
+      } else {
+        const int n = min(n0 + 32 * (b - NA) + rl, p.N - 1);
+        voff[b][t] = (uint32_t)n * p.ldb_bytes + 16u * piece[t];
+      }
+    }
+  // reader: lane (r, h) takes piece 2 g + h of row r for group g of the segment
+  int rd[2];
+#pragma unroll
+  for (int g = 0; g < 2; ++g) rd[g] = (r >> 4) * 64 + (r & 15) * 4 + ((2 * g + h) ^ ((r >> 1) & 3));
+
+  // with two staging areas the first two segments go out together: their latencies overlap
+  if (seg_lo < seg_hi) issue_segment<NA, NB>(p, stage, &voff[0][0], piece[0], piece[1], seg_lo);
+  if (kBufs == 2 && seg_lo + 1 < seg_hi) issue_segment<NA, NB>(p, stage + kStage, &voff[0][0], piece[0], piece[1], seg_lo + 1);
+  FP4_STAMP(1);
+
+  v16f acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+  int pa[TM], pb[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) pa[i] = 0;
+#pragma unroll
+  for (int j = 0; j < TN; ++j) pb[j] = 0;
+
+  for (int seg = seg_lo; seg < seg_hi; ++seg) {
+    // the segment's words into registers (the compiler waits for the loads in flight: it tracks
+    // LDS writes of the load unit), then the segment after next is requested into the area
+    // these words came from
+    const int buf = kBufs == 2 ? (seg - seg_lo) & 1 : 0;
+    const uint4* src = stage + buf * kStage;
+    uint4 w[NB][2];
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int g = 0; g < 2; ++g) w[b][g] = src[b * 128 + rd[g]];
+    if (8 * seg + 8 > p.Kw) {  // last segment of a row that ends inside it: words past the row are zero
+#pragma unroll
+      for (int g = 0; g < 2; ++g) {
+        const int left = p.Kw - (8 * seg + 2 * (2 * g + h));  // valid words of this lane's piece
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+          if (left < 2) w[b][g].z = w[b][g].w = 0;
+          if (left < 1) w[b][g].x = w[b][g].y = 0;
+        }
+      }
+    }
+    asm volatile("" ::: "memory");  // the reads stay above the loads that overwrite their source
+#ifdef BMX_FP4_STAMPS
+    if (seg == seg_lo) { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); FP4_STAMP(2); }
+#endif
+    if (seg + kBufs < seg_hi) issue_segment<NA, NB>(p, stage + buf * kStage, &voff[0][0], piece[0], piece[1], seg + kBufs);
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+      const int kg = 2 * seg + g;
+      if (kg < g_lo || kg >= g_hi) continue;  // wave-uniform: a range may start or end mid-segment
+      if (XNOR) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) pa[i] += popcount4(w[i][g]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) pb[j] += popcount4(w[NA + j][g]);
+      }
+      uint4 hi[NB];
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
+        hi[b] = make_uint4(w[b][g].x >> 3, w[b][g].y >> 3, w[b][g].z >> 3, w[b][g].w >> 3);
+#pragma unroll
+      for (int n = 0; n < 4; ++n) {
+        v8i ea[NA], eb[TN];
+#pragma unroll
+        for (int b = 0; b < NA; ++b) ea[b] = nibble_plane(w[b][g], hi[b], n);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) eb[j] = nibble_plane(w[NA + j][g], hi[NA + j], n);
+        // E8M0 block scales: planes 0 and 3 hold 0.5 (x 2), plane 1 holds 1, plane 2 holds 2 (x 1/2)
+        const int sc = n == 1 ? 127 : (n == 2 ? 126 : 128);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int pl = 0; pl < PL; ++pl)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+              acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ea[i * PL + pl], eb[j], acc[i][j], 4, 4, 0,
+                                                                         sc + pl, 0, sc);
+      }
+    }
+  }
+  FP4_STAMP(3);
+
+  // ---- epilogue.  Register v of lane (r, h) in block (i, j) is C[32 i + 8 (v / 4) + 4 h + v % 4][32 j + r].
+  // tot: the full-K sum of the MFMA results; ra, cb: pc(A row), pc(B column) over the full K
+  // (plane form: ra = the row sum of the quantised activations).
+  auto finish = [&](int i, int j, int v, float tot, int ra, int cb, float al, float th) {
+    const int mi = 32 * i + 8 * (v >> 2) + 4 * h + (v & 3);
+    const int m = m0 + mi, n = n0 + 32 * j + r;
+    const uint32_t idx = (uint32_t)(m * p.ldc + n);
+    if (!XNOR) {
+      if (m < p.M && n < p.N && live) {
+        const int sv = 2 * (int)tot - ra;
+        if (p.C_i32) __builtin_nontemporal_store(sv, p.C_i32 + idx);
+        if (p.C_f32) __builtin_nontemporal_store((float)sv / p.levels, p.C_f32 + idx);
+      }
+      return;
+    }
+    const float dot = (float)(p.Kreal - 2 * ra - 2 * cb) + 4.0f * tot;  // exact: integers below 2^24
+    if (OUT == kOutBits) {
+      // the 64-lane mask of the sign decision: its low half is 32 columns of row m, its high half
+      // the same columns of the row four below
+      const uint64_t mask = __ballot(live && n < p.N && al * dot >= th);
+      if (r == 0 && m < p.M && live)
+        p.C_bits[(uint32_t)(m * (2 * p.ldc) + (n >> 5))] = h ? (uint32_t)(mask >> 32) : (uint32_t)mask;
+    } else if (m < p.M && n < p.N && live) {
+      if (OUT == kOutI32) __builtin_nontemporal_store(p.as_count ? ((int)dot + p.Kreal) >> 1 : (int)dot, p.C_i32 + idx);
+      else __builtin_nontemporal_store(al * dot, p.C_f32 + idx);
+    }
+  };
+  // per-column constants of this lane (column 32 j + r)
+  float aln[TN], thn[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int n = min(n0 + 32 * j + r, p.N - 1);
+    aln[j] = (XNOR && p.alpha) ? p.alpha[n] : 1.0f;
+    thn[j] = (XNOR && OUT == kOutBits && p.thr) ? p.thr[n] : 0.0f;
+  }
+  // popcounts: a lane counted its half of K for row / column r; the other half sits 32 lanes away
+  if (XNOR) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) pa[i] += __shfl_xor(pa[i], 32);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) pb[j] += __shfl_xor(pb[j], 32);
+  }
+
+  if (!SPLIT) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int mi = 32 * i + 8 * (v >> 2) + 4 * h + (v & 3);
+        const int ra = XNOR ? __shfl(pa[i], mi & 31) : p.rowsum[min(m0 + mi, p.M - 1)];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) finish(i, j, v, acc[i][j][v], ra, pb[j], aln[j], thn[j]);
+      }
+    return;
+  }
+
+  // ---- K split: every wave writes its partial tile and its popcounts over its own staging
+  // areas (nothing of another wave's lies there), then finishes the accumulator groups
+  // g = wave, wave + S, ... : S partials in, one store out.
+  float4* part = (float4*)lds;
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        part[wave * kSlot + ((i * TN + j) * 4 + q) * 64 + lane] =
+            make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+  int* cnt = (int*)(part + wave * kSlot + kGroups * 64);  // [32 TM] row counts, [32 TN] column counts
+  if (XNOR && h == 0) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) cnt[32 * i + r] = pa[i];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) cnt[32 * TM + 32 * j + r] = pb[j];
+  }
+  __syncthreads();
+  FP4_STAMP(4);
+  // full-K popcounts: lane l sums row l of the tile (TM = 2: 64 rows) and column l over the S
+  // waves' counts, one conflict-free read each; a lane then picks the rows and the column of
+  // its own results out of other lanes' registers
+  int pa_tot = 0, pb_tot = 0;
+  if (XNOR) {
+    static_assert(TM == 2 && TN == 2, "one lane per row and per column of the tile");
+    int ca[8], cb8[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      const int* c = (const int*)(part + (s < S ? s : S - 1) * kSlot + kGroups * 64);
+      ca[s] = c[lane];
+      cb8[s] = c[32 * TM + lane];
+    }
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      pa_tot += s < S ? ca[s] : 0;
+      pb_tot += s < S ? cb8[s] : 0;
+    }
+  }
+  for (int g = wave; g < kGroups; g += S) {
+    const int blk = g >> 2, q = g & 3, i = blk / TN, j = blk % TN;
+    const int row0 = 32 * i + 8 * q + 4 * h;  // this lane's four rows: row0 .. row0 + 3
+    // all reads first (partials past S repeat the last one and count as nothing), so that the
+    // LDS round trips overlap instead of adding up
+    float4 t[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) t[s] = part[(s < S ? s : S - 1) * kSlot + g * 64 + lane];
+    float4 tot = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      const bool on = s < S;
+      tot.x += on ? t[s].x : 0.f;
+      tot.y += on ? t[s].y : 0.f;
+      tot.z += on ? t[s].z : 0.f;
+      tot.w += on ? t[s].w : 0.f;
+    }
+#ifdef BMX_FP4_STAMPS
+    if (g == wave) { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); FP4_STAMP(7); }
+#endif
+    int ra[4], cb = 0;
+    if (XNOR) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) ra[e] = __shfl(pa_tot, row0 + e);
+      cb = __shfl(pb_tot, 32 * j + r);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) ra[e] = p.rowsum[min(m0 + row0 + e, p.M - 1)];
+    }
+    const float al = j == 0 ? aln[0] : aln[TN - 1], th = j == 0 ? thn[0] : thn[TN - 1];
+    finish(i, j, 4 * q, tot.x, ra[0], cb, al, th);
+    finish(i, j, 4 * q + 1, tot.y, ra[1], cb, al, th);
+    finish(i, j, 4 * q + 2, tot.z, ra[2], cb, al, th);
+    finish(i, j, 4 * q + 3, tot.w, ra[3], cb, al, th);
+  }
+  FP4_STAMP(5);
+#ifdef BMX_FP4_STAMPS
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  FP4_STAMP(6);
+#endif
+}
+
+template <int TM, int TN, int PL, bool XNOR, int OUT, bool SPLIT>
+hipError_t launch_tile(const Fp4Params& p, int S, int tiles_per_wg, int64_t blocks, hipStream_t s) {
+  constexpr int NB = TM * PL + TN, kStage = NB * 128, kGroups = TM * TN * 4, kCnt = (TM + TN) * 8;
+  constexpr int bufs = (NB <= 4 && BMX_FP4_AHEAD == 2) ? 2 : 1;
+  constexpr int slot = bufs * kStage > kGroups * 64 + kCnt ? bufs * kStage : kGroups * 64 + kCnt;
+  const int waves = SPLIT ? S : tiles_per_wg;
+  const size_t lds = (size_t)waves * slot * 16;
+  auto kern = gemm_fp4_kernel<TM, TN, PL, XNOR, OUT, SPLIT>;
+  if (lds > 64 * 1024) {  // more than the default limit of dynamic LDS: raised once per device
+    static bool raised[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (!raised[dev]) {
+      const hipError_t e =
+          hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+      if (e != hipSuccess) return e;
+      raised[dev] = true;
+    }
+  }
+  note_kernel("gemm_fp4_kernel<%d,%d,%d,%s,%s> grid %lld x %d, K split %d, fp4", TM, TN, PL, XNOR ? "xnor" : "planes",
+              !XNOR ? "S" : (OUT == kOutF32 ? "f32" : (OUT == kOutI32 ? "i32" : "bits")), (long long)blocks, 64 * waves,
+              SPLIT ? S : 1);
+#ifdef BMX_FP4_STAMPS
+  hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(64 * waves), lds, s, p, S, fp4_stamps);
+#else
+  hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(64 * waves), lds, s, p, S);
+#endif
+  return hipGetLastError();
+}
+
+template <int PL, bool XNOR, int OUT>
+hipError_t launch_split(const Fp4Params& p, int S, int tiles_per_wg, int64_t blocks, hipStream_t s) {
+  if (S > 1) return launch_tile<2, 2, PL, XNOR, OUT, true>(p, S, tiles_per_wg, blocks, s);
+  return launch_tile<2, 2, PL, XNOR, OUT, false>(p, S, tiles_per_wg, blocks, s);
+}
+
+}  // namespace
+
+int gemm_fp4_split = 0;  // 0 = automatic; settable for sweeps and for the tests of every split
+
+// Takes the problem when both operands have 16-byte aligned rows, sums stay exact in fp32, the
+// operands can be addressed with 32-bit byte offsets, and there are enough 64 x 64 tiles for
+// the tile shape to pay; false otherwise (the caller then uses the 32 x 32 kernel).
+bool launch_gemm_fp4(const uint64_t* A, int64_t lda_w, int planes, const int32_t* rowsum, const uint64_t* B,
+                     int64_t ldb_w, int M, int N, int K, const float* alpha_n, int32_t* C_i32, float* C_f32,
+                     uint64_t* C_bits, const float* thr_n, int64_t ldc, bool as_count, hipStream_t s,
+                     hipError_t* err) {
+  if (gemm_engine == 1 || gemm_engine == 2 || gemm_engine == 4) return false;
+  if (planes < 1 || planes > 2) return false;
+  if ((lda_w & 1) || (ldb_w & 1) || ((uintptr_t)A & 15) || ((uintptr_t)B & 15)) return false;
+  if ((int64_t)K * ((1 << planes) - 1) >= ((int64_t)1 << 24)) return false;
+  if ((int64_t)M * planes * lda_w * 8 >= ((int64_t)1 << 32) || (int64_t)N * ldb_w * 8 >= ((int64_t)1 << 32))
+    return false;
+  // (outputs are addressed with 32-bit element indices, rows rounded up to whole tiles)
+  if (((int64_t)M + 64) * ldc * (C_bits ? 2 : 1) >= ((int64_t)1 << 31)) return false;
+  const int tiles_m = (int)ceil_div(M, 64), tiles_n = (int)ceil_div(N, 64);
+  const int64_t tiles = (int64_t)tiles_m * tiles_n;
+  if (gemm_engine != 5 && tiles < 64) return false;
+  if (tiles >= ((int64_t)1 << 28)) return false;
+  Fp4Params p;
+  p.A = A;
+  p.B = B;
+  p.lda_bytes = (uint32_t)(lda_w * 8);
+  p.ldb_bytes = (uint32_t)(ldb_w * 8);
+  p.M = M;
+  p.N = N;
+  p.Kw = (int)words_for(K);
+  p.Kreal = K;
+  const int ngroups = (int)ceil_div(p.Kw, 4);
+  p.tiles_m = tiles_m;
+  p.tiles_n = tiles_n;
+  p.div_tiles_m = make_fast_div((uint32_t)tiles_m);
+  p.alpha = alpha_n;
+  p.thr = thr_n;
+  p.rowsum = rowsum;
+  p.levels = (float)((1u << planes) - 1u);
+  p.as_count = as_count ? 1 : 0;
+  p.C_i32 = C_i32;
+  p.C_f32 = C_f32;
+  p.C_bits = (uint32_t*)C_bits;
+  p.ldc = (int)ldc;
+  // K split: about two waves per SIMD (2048 in all), at most eight per tile, and every wave
+  // keeps at least one 64-byte segment
+  int S = gemm_fp4_split;
+  if (S <= 0) {
+    S = (int)(2048 / tiles);
+    S = S > 8 ? 8 : S;
+  }
+  S = S > 8 ? 8 : S;
+  if (S > ngroups / 2) S = ngroups / 2;
+  if (S < 1) S = 1;
+  p.g_base = ngroups / S;
+  p.g_rem = ngroups - p.g_base * S;
+  const int tiles_per_wg = 4;
+  const int64_t wgs = S > 1 ? tiles : ceil_div(tiles, tiles_per_wg);
+  p.tiles_per_xcd = (int)ceil_div(wgs, 8);
+  const int64_t blocks = 8 * (int64_t)p.tiles_per_xcd;
+  if (planes == 1 && rowsum == nullptr) {
+    if (C_bits) *err = launch_split<1, true, kOutBits>(p, S, tiles_per_wg, blocks, s);
+    else if (C_i32) *err = launch_split<1, true, kOutI32>(p, S, tiles_per_wg, blocks, s);
+    else *err = launch_split<1, true, kOutF32>(p, S, tiles_per_wg, blocks, s);
+  } else if (planes == 1) {
+    *err = launch_split<1, false, kOutF32>(p, S, tiles_per_wg, blocks, s);
+  } else {
+    *err = launch_split<2, false, kOutF32>(p, S, tiles_per_wg, blocks, s);
+  }
+  return true;
+}
+
+}  // namespace bmx

@@ -504,7 +504,9 @@ gemm_mfma_kernel(const MfmaParams p) {
 
 }  // namespace
 
-int gemm_engine = 0;  // 0 = automatic, 1 = xor/popcount kernel, 2 = int8 matrix cores, 3 = FP4 matrix cores
+// 0 = automatic, 1 = xor/popcount kernel, 2 = int8 matrix cores, 3 = FP4 matrix cores (either
+// kernel), 4 = FP4 on this file's kernel, 5 = FP4 on the 64 x 64 per wave kernel whatever the size
+int gemm_engine = 0;
 int gemm_mfma_ksplit = 0;
 int gemm_mfma_tile = 0;  // 1 forces the 32 x 32 per wave variant, 2 the 64 x 64 one
 
@@ -561,6 +563,9 @@ bool launch_xnor_gemm_mfma(const uint64_t* A, int64_t lda_w, const uint64_t* B, 
                            uint64_t* C_bits, const float* thr_n, int64_t ldc, hipStream_t s, hipError_t* err,
                            bool as_count) {
   if (gemm_engine == 1) return false;
+  if (launch_gemm_fp4(A, lda_w, 1, nullptr, B, ldb_w, M, N, K, alpha_n, C_i32, C_f32, C_bits, thr_n, ldc, as_count,
+                      s, err))
+    return true;
   // 16-byte row pieces are loaded as one vector: rows must start 16-byte aligned
   if ((lda_w & 1) || (ldb_w & 1) || ((uintptr_t)A & 15) || ((uintptr_t)B & 15)) return false;
   MfmaParams p;
@@ -605,6 +610,9 @@ bool launch_plane_gemm_mfma(const uint64_t* planes_rows, int64_t lda_w, int bits
                             const uint64_t* Wb, int64_t ldb_w, int M, int N, int K, int32_t* S_out,
                             float* out_f32, int64_t ldo, hipStream_t s, hipError_t* err) {
   if (gemm_engine == 1 || bits > 2) return false;
+  if (launch_gemm_fp4(planes_rows, lda_w, bits, rowsum, Wb, ldb_w, M, N, K, nullptr, S_out, out_f32, nullptr, nullptr,
+                      ldo, false, s, err))
+    return true;
   if ((lda_w & 1) || (ldb_w & 1) || ((uintptr_t)planes_rows & 15) || ((uintptr_t)Wb & 15)) return false;
   MfmaParams p;
   p.A = planes_rows;

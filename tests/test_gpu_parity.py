@@ -876,3 +876,66 @@ def test_words32_gemm_and_fc(K, layout):
         as64 = Ad.view(torch.int64) if layout == "tight" else None
         if as64 is not None:
             np.testing.assert_array_equal(B.xnor_gemm(as64, Bd.view(torch.int64), K).cpu().numpy(), ri)
+
+
+# ------------------------------------------------------------------ 64 x 64 per wave FP4 kernel (LDS-staged operands)
+@pytest.mark.parametrize("split", [0, 1, 2, 3, 5, 8])
+def test_gemm_fp4_lds_staged_kernel(split):
+    """The matrix-core GEMM kernel with 64 x 64 of C per wave, operands staged through LDS by the
+    load unit and K split over the waves of a workgroup, forced through the tuning hook whatever
+    the size: ragged tiles in M and N, rows that end inside a 64-byte segment (every residue of
+    the word count mod 8), row strides wider than the rows with garbage behind them, every K
+    split, every output kind, and the plane form with 1 and 2 bit planes."""
+    rng = np.random.default_rng(300 + split)
+    with tuned(k7=5, k10=split):
+        for (M, N, K) in [(1, 1, 1), (37, 70, 5000), (8, 64, 1024), (100, 129, 3072 + 64), (64, 64, 63),
+                          (65, 33, 1025), (130, 200, 2048 + 128), (700, 801, 1100), (256, 512, 9216),
+                          (31, 190, 64 * 7), (33, 65, 64 * 9), (64, 128, 64 * 10), (5, 300, 64 * 11),
+                          (70, 70, 64 * 12 + 1), (129, 64, 64 * 13), (64, 65, 64 * 14), (66, 66, 64 * 15)]:
+            a = rng.standard_normal((M, K)).astype(np.float32)
+            b = rng.standard_normal((N, K)).astype(np.float32)
+            A, Bm = oracle.binarize_pack(a, 1), oracle.binarize_pack(b, 1)
+            ld = (A.shape[1] + 1) // 2 * 2 + 2 * (K % 3)            # even, sometimes wider than the row
+            Ad = np.full((M, ld), POISON, dtype=np.uint64); Ad[:, :A.shape[1]] = A
+            Bd = np.full((N, ld), POISON, dtype=np.uint64); Bd[:, :A.shape[1]] = Bm
+            want = oracle.xnor_gemm(A, Bm, K)
+            got = B.xnor_gemm(dev(Ad.view(np.int64)), dev(Bd.view(np.int64)), K).cpu().numpy()
+            assert "gemm_fp4_kernel" in B.last_kernel()
+            np.testing.assert_array_equal(got, want)
+            cnt = B.xnor_gemm(dev(Ad.view(np.int64)), dev(Bd.view(np.int64)), K, count=True).cpu().numpy()
+            np.testing.assert_array_equal(2 * cnt - K, want)
+        for (batch, fin, fout) in [(19, 2500, 75), (70, 4096, 130), (256, 1100, 300)]:
+            x = rng.standard_normal((batch, fin)).astype(np.float32)
+            w = rng.uniform(-1, 1, (fout, fin)).astype(np.float32)
+            alpha = rng.standard_normal(fout).astype(np.float32)
+            alpha[::3] = 0.0
+            ri, rf = oracle.binary_fc(x, w, alpha)
+            Wp = B.binarize_pack(dev(w), 1)
+            if Wp.shape[1] % 2:                                      # 16-byte rows for the matrix-core kernels
+                Wp = torch.cat([Wp, torch.zeros_like(Wp[:, :1])], dim=1).contiguous()
+            np.testing.assert_array_equal(B.binary_fc(dev(x), Wp, integer_out=True).cpu().numpy(), ri)
+            assert "gemm_fp4_kernel" in B.last_kernel()
+            assert_f32_close(B.binary_fc(dev(x), Wp, alpha=dev(alpha)).cpu().numpy(), rf)
+            Xp = B.binarize_pack(dev(x), 1)
+            if Xp.shape[1] % 2:
+                Xp = torch.cat([Xp, torch.zeros_like(Xp[:, :1])], dim=1).contiguous()
+            thr = (rng.standard_normal(fout) * np.sqrt(fin)).astype(np.float32)
+            out = dev(np.full((batch, (fout + 63) // 64 + 1), -1, dtype=np.int64))
+            B.binary_fc_packed(Xp, fin, Wp, alpha=dev(alpha), mode="bits", thr=dev(thr), out=out)
+            assert "gemm_fp4_kernel" in B.last_kernel()
+            want = np.where(rf >= thr[None, :], 1.0, -1.0).astype(np.float32)
+            got = host_u64(out)
+            np.testing.assert_array_equal(got[:, :-1], oracle.binarize_pack(want, 1))
+            assert (got[:, -1] == np.uint64(0xFFFFFFFFFFFFFFFF)).all()
+        for bits in (1, 2):
+            for (M, N, K) in [(21, 70, 2200), (1, 1, 1), (33, 65, 1024), (100, 130, 4096 + 200), (256, 256, 64 * 9)]:
+                a = rng.uniform(0, 1, (M, K)).astype(np.float32)
+                a[rng.random(a.shape) < 0.05] = 0.5
+                wq = rng.standard_normal((N, K)).astype(np.float32)
+                Sg, fg = B.quant_gemm(dev(a), dev(wq), bits)
+                # (the sign-packed weight rows of the workspace are ceil(K/64) words: an odd count is
+                # not 16-byte aligned and goes to the xor/popcount kernel)
+                assert "gemm_fp4_kernel" in B.last_kernel() or ((K + 63) // 64) % 2 == 1
+                rS, r64, r32 = oracle.quant_gemm(a, wq, bits)
+                np.testing.assert_array_equal(Sg.cpu().numpy(), rS)
+                assert_f32_close(fg.cpu().numpy(), r32)
