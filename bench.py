@@ -50,7 +50,7 @@ HBM_PEAK = 8.0e12
 FP4_PEAK = 10.1e15   # dense FP4 matrix-core peak, flop/s
 INT8_PEAK = 5.0e15   # dense int8 matrix-core peak, op/s
 MALL_BYTES = 256 << 20  # memory-side cache the rotation has to exceed
-PHASES = ("headline", "config1", "config2", "config4", "config5", "sec31", "packs", "probe")
+PHASES = ("headline", "fc1", "fc2", "config1", "config2", "config4", "config5", "sec31", "packs", "probe")
 
 
 def roofline_block(kernel, us, binops=0.0, nbytes=0.0, mfma_flops=None):
@@ -97,6 +97,10 @@ def main():
     ap.add_argument("--no-other-configs", action="store_true")
     ap.add_argument("--phase", choices=("all",) + PHASES, default="all",
                     help="run one section only (the workload of a per-configuration profile)")
+    ap.add_argument("--lean", action="store_true",
+                    help="HBM-resident rotating launches only: skip the cache-hot, eager and other-engine context "
+                         "figures (the workload of the rocprofv3 kernel-trace summaries, whose per-kernel averages "
+                         "then mix nothing else in)")
     ap.add_argument("--eager", action="store_true",
                     help="with --phase: issue the timed launches eagerly instead of replaying a graph")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -221,7 +225,8 @@ def main():
     c3 = synth.config3()
     Bt, F0, F1, F2 = 256, 9216, 4096, 4096
     ops1, ops2 = 2.0 * Bt * F1 * F0, 2.0 * Bt * F2 * F1
-    if want("headline") or args.traffic_probe:
+    sub = args.phase if args.phase in ("fc1", "fc2") else None  # one layer of the headline alone (profiles)
+    if want("headline") or args.traffic_probe or sub:
         w1, w2 = dev(c3["w1"]), dev(c3["w2"])
         W1p0, W2p0 = B.binarize_pack(w1, 1), B.binarize_pack(w2, 1)
         al1, al2 = B.alpha_mean_abs(w1), B.alpha_mean_abs(w2)
@@ -256,52 +261,65 @@ def main():
             print(json.dumps({"traffic_probe": True, "steps": K_STEPS, "copy_bytes_each_way": 256 << 20,
                               "buffer_sets_rotated": int(nsets)}))
             return
-        for i in range(args.warmup):
-            steps[i % K_STEPS]()
-        torch.cuda.synchronize()
-        if args.eager:
-            t0 = time.perf_counter()
-            for f in steps:
-                f()
+        ms_per_step = value = hot_us = eager_ms = None
+        if not sub:
+            for i in range(args.warmup):
+                steps[i % K_STEPS]()
             torch.cuda.synchronize()
-            dt = time.perf_counter() - t0
-        else:
-            g_steps = graph_of(steps)
-            g_steps.replay()  # untimed replay: graph upload
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            g_steps.replay()
-            torch.cuda.synchronize()
-            dt = time.perf_counter() - t0
-            del g_steps
-        ms_per_step = dt / K_STEPS * 1e3
-        value = (ops1 + ops2) / (dt / K_STEPS) / 1e9
+            if args.eager:
+                t0 = time.perf_counter()
+                for f in steps:
+                    f()
+                torch.cuda.synchronize()
+                dt = time.perf_counter() - t0
+            else:
+                g_steps = graph_of(steps)
+                g_steps.replay()  # untimed replay: graph upload
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                g_steps.replay()
+                torch.cuda.synchronize()
+                dt = time.perf_counter() - t0
+                del g_steps
+            ms_per_step = dt / K_STEPS * 1e3
+            value = (ops1 + ops2) / (dt / K_STEPS) / 1e9
 
-        # cache-hot (one buffer set) and eager (host enqueues every launch) step rates: context
-        hot_us = event_us(graph_of([steps[0]] * K_STEPS).replay, K_STEPS)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for f in steps:
-            f()
-        torch.cuda.synchronize()
-        eager_ms = (time.perf_counter() - t0) / K_STEPS * 1e3
-        del steps
+            # cache-hot (one buffer set) and eager (host enqueues every launch) step rates: context
+            hot_us, eager_ms = None, None
+            if not args.lean:
+                hot_us = event_us(graph_of([steps[0]] * K_STEPS).replay, K_STEPS)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for f in steps:
+                    f()
+                torch.cuda.synchronize()
+                eager_ms = (time.perf_counter() - t0) / K_STEPS * 1e3
+            del steps
+        else:  # one layer alone: the first layer's outputs must exist for the second
+            for i in range(nsets):
+                B.binary_fc(xs[i], W1s[i], alpha=al1, out=h1s[i], workspace=wss[i])
+            torch.cuda.synchronize()
+            del steps
 
         # the step's kernels one by one, on the same rotating buffers
         Kw0p = ws_bytes // (Bt * 8)  # chunk-padded row length of the packed activations, in words
         xps = [t.view(torch.int64)[: Bt * Kw0p].view(Bt, Kw0p) for t in wss]
-        gemm1_us, gemm1_name = rotating_us([(lambda i=i: B.binary_fc_packed(
-            xps[i], F0, W1s[i], alpha=al1, mode="f32", out=h1s[i])) for i in range(nsets)])
-        pack1_us, pack1_name = rotating_us([(lambda i=i: B.binarize_pack(xs[i], 1, out=xps[i])) for i in range(nsets)])
         Kw1 = F1 // 64
         h1ps = [t.view(torch.int64)[: Bt * Kw1].view(Bt, Kw1) for t in wss]
-        gemm2_us, gemm2_name = rotating_us([(lambda i=i: B.binary_fc_packed(
-            h1ps[i], F1, W2s[i], alpha=al2, mode="f32", out=h2s[i])) for i in range(nsets)])
-        pack2_us, pack2_name = rotating_us([(lambda i=i: B.binarize_pack(h1s[i], 1, out=h1ps[i])) for i in range(nsets)])
-        fc1_us, _ = rotating_us([(lambda i=i: B.binary_fc(xs[i], W1s[i], alpha=al1, out=h1s[i], workspace=wss[i]))
-                                 for i in range(nsets)])
-        fc2_us, _ = rotating_us([(lambda i=i: B.binary_fc(h1s[i], W2s[i], alpha=al2, out=h2s[i], workspace=wss[i]))
-                                 for i in range(nsets)])
+        gemm1_us = pack1_us = fc1_us = gemm2_us = pack2_us = fc2_us = float("nan")
+        gemm1_name = pack1_name = gemm2_name = pack2_name = ""
+        if sub != "fc2":
+            gemm1_us, gemm1_name = rotating_us([(lambda i=i: B.binary_fc_packed(
+                xps[i], F0, W1s[i], alpha=al1, mode="f32", out=h1s[i])) for i in range(nsets)])
+            pack1_us, pack1_name = rotating_us([(lambda i=i: B.binarize_pack(xs[i], 1, out=xps[i])) for i in range(nsets)])
+            fc1_us, _ = rotating_us([(lambda i=i: B.binary_fc(xs[i], W1s[i], alpha=al1, out=h1s[i], workspace=wss[i]))
+                                     for i in range(nsets)])
+        if sub != "fc1":
+            gemm2_us, gemm2_name = rotating_us([(lambda i=i: B.binary_fc_packed(
+                h1ps[i], F1, W2s[i], alpha=al2, mode="f32", out=h2s[i])) for i in range(nsets)])
+            pack2_us, pack2_name = rotating_us([(lambda i=i: B.binarize_pack(h1s[i], 1, out=h1ps[i])) for i in range(nsets)])
+            fc2_us, _ = rotating_us([(lambda i=i: B.binary_fc(h1s[i], W2s[i], alpha=al2, out=h2s[i], workspace=wss[i]))
+                                     for i in range(nsets)])
         gemm1_bytes = Bt * (F0 // 8) + F1 * (F0 // 8) + Bt * F1 * 4   # packed x, packed W1 in; fp32 out
         gemm2_bytes = Bt * (F1 // 8) + F2 * (F1 // 8) + Bt * F2 * 4
         pack1_bytes = Bt * F0 * 4 + Bt * (F0 // 8)
@@ -316,20 +334,22 @@ def main():
                     tsrc = "profiles/traffic_fc1_gemm_config3.txt (rocprofv3 --pmc, not measured in this run)"
         roofline["traffic"] = traffic
         roofline["traffic_source"] = tsrc
-        kernels = {
-            "fc1_pack": roofline_block(pack1_name, pack1_us, nbytes=pack1_bytes),
-            "fc1_gemm": dict(roofline),
-            "fc2_pack": roofline_block(pack2_name, pack2_us, nbytes=pack2_bytes),
-            "fc2_gemm": roofline_block(gemm2_name, gemm2_us, binops=ops2, nbytes=gemm2_bytes),
-        }
+        kernels = {}
+        if sub != "fc2":
+            kernels["fc1_pack"] = roofline_block(pack1_name, pack1_us, nbytes=pack1_bytes)
+            kernels["fc1_gemm"] = dict(roofline)
+        if sub != "fc1":
+            kernels["fc2_pack"] = roofline_block(pack2_name, pack2_us, nbytes=pack2_bytes)
+            kernels["fc2_gemm"] = roofline_block(gemm2_name, gemm2_us, binops=ops2, nbytes=gemm2_bytes)
         # the same GEMMs on the xor/popcount engine (the benchmark spec's VALU target names it)
-        for tag, Wl, xl, hl, fin, al_, ops_, nb in (("fc1", W1s, xps, h1s, F0, al1, ops1, gemm1_bytes),
-                                                     ("fc2", W2s, h1ps, h2s, F1, al2, ops2, gemm2_bytes)):
+        for tag, Wl, xl, hl, fin, al_, ops_, nb in (() if (args.lean or sub) else (
+                ("fc1", W1s, xps, h1s, F0, al1, ops1, gemm1_bytes), ("fc2", W2s, h1ps, h2s, F1, al2, ops2, gemm2_bytes))):
             us_, nm_ = with_tune({7: 1}, lambda: rotating_us([(lambda i=i: B.binary_fc_packed(
                 xl[i], fin, Wl[i], alpha=al_, mode="f32", out=hl[i])) for i in range(nsets)], reps=60))
             kernels[tag + "_gemm_popcount_engine"] = add_measured_peak(roofline_block(nm_, us_, binops=ops_, nbytes=nb))
         # the two layers handing packed sign bits to each other instead of fp32 activations
-        bits1 = [B.binary_fc_packed(xps[i], F0, W1s[i], alpha=al1, mode="bits") for i in range(nsets)]
+        bits1 = None if (args.lean or sub) else [B.binary_fc_packed(xps[i], F0, W1s[i], alpha=al1, mode="bits")
+                                                 for i in range(nsets)]
 
         def chain_bits(i):
             def run():
@@ -338,7 +358,9 @@ def main():
                 B.binary_fc_packed(bits1[i], F1, W2s[i], alpha=al2, mode="f32", out=h2s[i])
             return run
 
-        chain_bits_us, _ = rotating_us([chain_bits(i) for i in range(nsets)])
+        chain_bits_us = None if (args.lean or sub) else rotating_us([chain_bits(i) for i in range(nsets)])[0]
+        if sub:  # a phase line, not the benchmark line
+            roofline = roofline_block(gemm2_name, gemm2_us, binops=ops2, nbytes=gemm2_bytes) if sub == "fc2" else roofline
         line.update({"value": value, "ms_per_step": ms_per_step,
                      "dtype": "f32 in -> sign bits (u64 words) -> %s -> f32 out" % roofline["dtype"],
                      "config": {"workload": "config3: binary FC pair, batch 256, 9216 -> 4096 -> 4096, fp32 in, alpha per "
@@ -347,10 +369,12 @@ def main():
                                 "kernels": [pack1_name, gemm1_name, pack2_name, gemm2_name],
                                 "timed_region": "K eager steps" if args.eager else "one replay of a HIP graph holding the K steps",
                                 "buffer_sets_rotated": int(nsets), "bytes_per_buffer_set": int(step_bytes),
-                                "ms_per_step_cache_hot": hot_us * 1e-3, "ms_per_step_eager": eager_ms,
+                                "ms_per_step_cache_hot": None if hot_us is None else hot_us * 1e-3,
+                                "ms_per_step_eager": eager_ms,
                                 "fc1_call_us_hbm_resident": fc1_us, "fc2_call_us_hbm_resident": fc2_us,
                                 "step_us_via_packed_sign_bits_between_layers": chain_bits_us,
-                                "gops_fc1_call": ops1 / fc1_us / 1e3, "gops_fc2_call": ops2 / fc2_us / 1e3},
+                                "gops_fc1_call": ops1 / fc1_us / 1e3, "gops_fc2_call": ops2 / fc2_us / 1e3,
+                                "phase": args.phase},
                      "roofline": roofline, "kernels": kernels})
         del xs, W1s, W2s, wss, h1s, h2s, xps, h1ps, bits1
         torch.cuda.empty_cache()
@@ -423,12 +447,14 @@ def main():
         d = {"call_us_hbm_resident": call_us, "gops_call": binops / call_us / 1e3, "buffer_sets_rotated": n,
              "conv_kernel": roofline_block(conv_name, conv_us, binops=binops, nbytes=conv_bytes),
              "pack_kernel": roofline_block(pack_name, pack_us, nbytes=pack_bytes)}
-        us_, nm_ = with_tune({5: popcount_path}, lambda: rotating_us(conv_calls, reps=60))
-        d["conv_kernel_popcount_engine"] = add_measured_peak(roofline_block(nm_, us_, binops=binops, nbytes=conv_bytes))
+        if not args.lean:
+            us_, nm_ = with_tune({5: popcount_path}, lambda: rotating_us(conv_calls, reps=60))
+            d["conv_kernel_popcount_engine"] = add_measured_peak(roofline_block(nm_, us_, binops=binops, nbytes=conv_bytes))
         other[tag] = d
 
     if want("config2") and run_others:
         conv_config("config2_conv3x3_16x64x56x56_64filters", synth.config2(), 1)
+    if want("config2") and run_others and not args.lean:
         # three configuration-2 blocks in a row (Sec. 2: QActivation -> QConvolution -> BatchNorm):
         # through fp32 feature maps (pack + convolution each) or handing the next layer its packed
         # image (one pack, the BatchNorm folded into a per-channel threshold)
@@ -492,9 +518,10 @@ def main():
              "gemm_kernel_upper_bound": roofline_block(nm_, us_, binops=binops5, nbytes=3 * M5 * K5 // 8 + M5 * N5 * 4,
                                                        mfma_flops=2.0 * M5 * N5 * K5),
              "whole_call_vs_hbm": roofline_block("quant_pack_kernel + " + nm_, us_, nbytes=2 * M5 * K5 * 4 + M5 * N5 * 4)}
-        us_, nm_ = with_tune({7: 1}, lambda: rotating_us(calls5, reps=40))
-        d["call_popcount_engine"] = add_measured_peak(roofline_block(nm_, us_, binops=binops5,
-                                                                     nbytes=3 * M5 * K5 // 8 + M5 * N5 * 4))
+        if not args.lean:
+            us_, nm_ = with_tune({7: 1}, lambda: rotating_us(calls5, reps=40))
+            d["call_popcount_engine"] = add_measured_peak(roofline_block(nm_, us_, binops=binops5,
+                                                                         nbytes=3 * M5 * K5 // 8 + M5 * N5 * 4))
         other["config5_quant_gemm_2bit_x_1bit_1024x1024x4096"] = d
         del a5, w5, ws5, o5
 
@@ -596,18 +623,18 @@ def main():
             hx.host_xnor_gemm.argtypes = [ctypes.c_void_p] * 3 + [ctypes.c_long] * 4 + [ctypes.c_int]
             hx.host_xnor_threads.restype = ctypes.c_int
             xn = {}
+            host_threads = int(hx.host_xnor_threads())
             for tag, a_f, b_f in (("config3_fc1_gemm_256x4096x9216", c3["x"], c3["w1"]),
                                   ("config2_gemm_view_64x50176x576", c2["w"].reshape(64, -1),
                                    oracle.im2col(c2["x"], 3, 3, 1, 1))):
                 Ap, Bp = oracle.binarize_pack(a_f, 1), oracle.binarize_pack(b_f, 1)
                 M_, N_, Kw_, K_ = Ap.shape[0], Bp.shape[0], Ap.shape[1], a_f.shape[1]
                 Cc = np.empty((M_, N_), dtype=np.int32)
-                for thr_ in (0, 1):
+                for thr_ in (host_threads, 1):
                     s, reps = timed(lambda: hx.host_xnor_gemm(Ap.ctypes.data, Bp.ctypes.data, Cc.ctypes.data,
                                                               M_, N_, Kw_, K_, thr_), 1.0)
-                    xn[tag + ("_one_thread" if thr_ else "")] = {
-                        "value": 2.0 * M_ * N_ * K_ / s / 1e9, "unit": "GOPS",
-                        "cores": 1 if thr_ else int(hx.host_xnor_threads()), "seconds_per_pass": s,
+                    xn[tag + ("_one_thread" if thr_ == 1 else "")] = {
+                        "value": 2.0 * M_ * N_ * K_ / s / 1e9, "unit": "GOPS", "cores": thr_, "seconds_per_pass": s,
                         "sample": "%d passes of the GEMM on packed 64-bit words, packing not timed" % reps}
             cpu["host_xnor_popcount_gemm"] = dict(xn, kind="uint64 xor + popcount GEMM with OpenMP (bench_host_xnor.c): "
                                                             "the paper's method on this host, context only, not the oracle")
@@ -620,7 +647,7 @@ def main():
     line["valu_probe"] = probe
     line["cpu_baseline"] = cpu
     line["other_configs"] = other or None
-    print(json.dumps(line))
+    print(json.dumps(line).replace('NaN', 'null'))
 
 
 if __name__ == "__main__":

@@ -84,8 +84,14 @@ __device__ __forceinline__ v8i nibble_plane(const uint4& w, const uint4& hi, int
   return e;
 }
 
-__device__ __forceinline__ int popcount4(const uint4& w) {
-  return __builtin_popcount(w.x) + __builtin_popcount(w.y) + __builtin_popcount(w.z) + __builtin_popcount(w.w);
+// acc + popcount of four words: four v_bcnt_u32_b32, each adding onto the running count (written
+// as a sum of __builtin_popcount the compiler counts from zero and adds with extra instructions)
+__device__ __forceinline__ int add_popcount4(int acc, const uint4& w) {
+  asm("v_bcnt_u32_b32 %0, %1, %0" : "+v"(acc) : "v"(w.x));
+  asm("v_bcnt_u32_b32 %0, %1, %0" : "+v"(acc) : "v"(w.y));
+  asm("v_bcnt_u32_b32 %0, %1, %0" : "+v"(acc) : "v"(w.z));
+  asm("v_bcnt_u32_b32 %0, %1, %0" : "+v"(acc) : "v"(w.w));
+  return acc;
 }
 
 // Request segment `seg` (64 bytes of every row of the wave's NB staged blocks) into the staging
@@ -117,6 +123,29 @@ __device__ __forceinline__ void issue_segment(const Fp4Params& p, uint4* dst, co
       }
   }
 }
+
+#ifdef BMX_FP4_NODMA
+// Experiment: the same staging through registers (plain 16-byte loads, then 16-byte LDS writes).
+template <int NA, int NB>
+__device__ __forceinline__ void issue_segment_regs(const Fp4Params& p, uint4* dst, const uint32_t* voff, int piece0,
+                                                   int piece1, int seg, int lane) {
+  const char* abase = (const char*)p.A + (uint32_t)seg * 64u;
+  const char* bbase = (const char*)p.B + (uint32_t)seg * 64u;
+  uint4 v[NB][2];
+#pragma unroll
+  for (int b = NB - 1; b >= 0; --b)
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int pc = t ? piece1 : piece0;
+      const uint32_t back = (8 * seg + 8 > p.Kw && 8 * seg + 2 * pc >= p.Kw) ? 16u * pc : 0u;
+      v[b][t] = *(const uint4*)((b < NA ? abase : bbase) + (voff[2 * b + t] - back));
+    }
+#pragma unroll
+  for (int b = NB - 1; b >= 0; --b)
+#pragma unroll
+    for (int t = 0; t < 2; ++t) dst[b * 128 + t * 64 + lane] = v[b][t];
+}
+#endif
 
 #ifdef BMX_FP4_STAMPS
 // Profiling builds only: per-wave shader-clock stamps at the phase boundaries of the kernel.
@@ -153,7 +182,8 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
 #ifndef BMX_FP4_AHEAD
 #define BMX_FP4_AHEAD 1
 #endif
-  constexpr int kBufs = (NB <= 4 && BMX_FP4_AHEAD == 2) ? 2 : 1;
+  constexpr int kBufs = (NB <= 4 && BMX_FP4_AHEAD >= 2) ? 2 : 1;
+  constexpr bool kLateSecond = BMX_FP4_AHEAD == 3;  // the second segment is requested once the first has landed
   constexpr int kSlot = kBufs * kStage > kGroups * 64 + kCnt ? kBufs * kStage : kGroups * 64 + kCnt;
   const int S = SPLIT ? S_arg : 1;
   const int lane = threadIdx.x & 63;
@@ -202,9 +232,17 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
 #pragma unroll
   for (int g = 0; g < 2; ++g) rd[g] = (r >> 4) * 64 + (r & 15) * 4 + ((2 * g + h) ^ ((r >> 1) & 3));
 
+#ifdef BMX_FP4_PRIO
+  if (SPLIT && wave < 4) __builtin_amdgcn_s_setprio(3);
+#endif
   // with two staging areas the first two segments go out together: their latencies overlap
+#ifdef BMX_FP4_NODMA
+  if (seg_lo < seg_hi) issue_segment_regs<NA, NB>(p, stage, &voff[0][0], piece[0], piece[1], seg_lo, lane);
+#else
   if (seg_lo < seg_hi) issue_segment<NA, NB>(p, stage, &voff[0][0], piece[0], piece[1], seg_lo);
-  if (kBufs == 2 && seg_lo + 1 < seg_hi) issue_segment<NA, NB>(p, stage + kStage, &voff[0][0], piece[0], piece[1], seg_lo + 1);
+#endif
+  if (kBufs == 2 && !kLateSecond && seg_lo + 1 < seg_hi)
+    issue_segment<NA, NB>(p, stage + kStage, &voff[0][0], piece[0], piece[1], seg_lo + 1);
   FP4_STAMP(1);
 
   v16f acc[TM][TN];
@@ -246,16 +284,22 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
 #ifdef BMX_FP4_STAMPS
     if (seg == seg_lo) { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); FP4_STAMP(2); }
 #endif
+    if (kBufs == 2 && kLateSecond && seg == seg_lo && seg + 1 < seg_hi)
+      issue_segment<NA, NB>(p, stage + kStage, &voff[0][0], piece[0], piece[1], seg + 1);
+#ifdef BMX_FP4_NODMA
+    if (seg + kBufs < seg_hi) issue_segment_regs<NA, NB>(p, stage + buf * kStage, &voff[0][0], piece[0], piece[1], seg + kBufs, lane);
+#else
     if (seg + kBufs < seg_hi) issue_segment<NA, NB>(p, stage + buf * kStage, &voff[0][0], piece[0], piece[1], seg + kBufs);
+#endif
 #pragma unroll
     for (int g = 0; g < 2; ++g) {
       const int kg = 2 * seg + g;
       if (kg < g_lo || kg >= g_hi) continue;  // wave-uniform: a range may start or end mid-segment
       if (XNOR) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) pa[i] += popcount4(w[i][g]);
+        for (int i = 0; i < TM; ++i) pa[i] = add_popcount4(pa[i], w[i][g]);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) pb[j] += popcount4(w[NA + j][g]);
+        for (int j = 0; j < TN; ++j) pb[j] = add_popcount4(pb[j], w[NA + j][g]);
       }
       uint4 hi[NB];
 #pragma unroll
@@ -424,7 +468,7 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
 template <int TM, int TN, int PL, bool XNOR, int OUT, bool SPLIT>
 hipError_t launch_tile(const Fp4Params& p, int S, int tiles_per_wg, int64_t blocks, hipStream_t s) {
   constexpr int NB = TM * PL + TN, kStage = NB * 128, kGroups = TM * TN * 4, kCnt = (TM + TN) * 8;
-  constexpr int bufs = (NB <= 4 && BMX_FP4_AHEAD == 2) ? 2 : 1;
+  constexpr int bufs = (NB <= 4 && BMX_FP4_AHEAD >= 2) ? 2 : 1;
   constexpr int slot = bufs * kStage > kGroups * 64 + kCnt ? bufs * kStage : kGroups * 64 + kCnt;
   const int waves = SPLIT ? S : tiles_per_wg;
   const size_t lds = (size_t)waves * slot * 16;
