@@ -159,7 +159,9 @@ def main():
         """calls[i] runs the measured call on buffer set i.  The sets together exceed the
         memory-side cache, so every launch finds its inputs in HBM.  Returns (us per call, name
         of the last kernel the call launched)."""
-        reps = reps or K_STEPS
+        # (at least 200 launches per figure whatever K is: the replay's fixed cost, some tens of
+        # microseconds of graph launch, must not weigh on a per-launch average of a few microseconds)
+        reps = reps or max(K_STEPS, 200)
         reps = max(reps, len(calls))
         fns = [calls[i % len(calls)] for i in range(reps)]
         for f in calls:

@@ -280,7 +280,8 @@ size_t bmx_workspace_bytes(int op, const int64_t* dims, int ndims);
  *   key 7  GEMM engine: 1 xor/popcount, 2 int8 matrix cores, 3 FP4 matrix cores (kernel chosen by
  *          size), 4 FP4 with 32 x 32 or 64 x 64 per wave and operands through registers, 5 FP4 with
  *          64 x 64 per wave and operands staged through LDS whatever the size
- *   key 10 K-split waves of the latter kernel
+ *   key 10 K-split waves of the latter kernel, key 11 = 2: its partial tiles cross LDS as fp32
+ *          even where fp16 pairs would be exact
  *   key 8  K-split waves, key 9  tile variant (1: 32 x 32, 2: 64 x 64 per wave) of the matrix-core
  *          kernels */
 int bmx_tune_set(int key, int value);

@@ -33,6 +33,8 @@
 //     and no split.
 //   - Workgroups are numbered so that tiles sharing rows of B (the large operand: weights) sit
 //     on one XCD and run back to back: workgroup b runs on XCD b % 8.
+#include <type_traits>
+
 #include "bmx_internal.h"
 
 namespace bmx {
@@ -42,6 +44,7 @@ namespace {
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef int v4i_alias __attribute__((ext_vector_type(4), may_alias));
+typedef __fp16 half2_t __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) void* lds_ptr;
 
 struct Fp4Params {
@@ -162,10 +165,12 @@ constexpr int kOutF32 = 0, kOutI32 = 1, kOutBits = 2;
 
 // TM x TN blocks of 32 x 32 per wave; PL bit planes per A row; XNOR: the xnor form (row
 // popcounts from the words themselves), else the plane form (row sums given); OUT: what the
-// xnor form stores; SPLIT: K split over the S waves of the workgroup (else a tile per wave).
+// xnor form stores; SPLIT: K split over the S waves of the workgroup (else a tile per wave);
+// HALF: the partial tiles of a split cross LDS as fp16 pairs (exact while a wave's sums stay
+// at or below 2048, which the launcher checks).
 // One instantiation per combination keeps each kernel's code short: the instruction cache
 // starts cold at every launch, and a launch lasts a few microseconds.
-template <int TM, int TN, int PL, bool XNOR, int OUT, bool SPLIT>
+template <int TM, int TN, int PL, bool XNOR, int OUT, bool SPLIT, bool HALF>
 __global__ void __launch_bounds__(512)
 gemm_fp4_kernel(const Fp4Params p, const int S_arg
 #ifdef BMX_FP4_STAMPS
@@ -184,7 +189,8 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
 #endif
   constexpr int kBufs = (NB <= 4 && BMX_FP4_AHEAD >= 2) ? 2 : 1;
   constexpr bool kLateSecond = BMX_FP4_AHEAD == 3;  // the second segment is requested once the first has landed
-  constexpr int kSlot = kBufs * kStage > kGroups * 64 + kCnt ? kBufs * kStage : kGroups * 64 + kCnt;
+  constexpr int kPart = HALF ? kGroups * 32 : kGroups * 64;  // uint4 holding a wave's partial tile
+  constexpr int kSlot = kBufs * kStage > kPart + kCnt ? kBufs * kStage : kPart + kCnt;
   const int S = SPLIT ? S_arg : 1;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -350,8 +356,13 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
       if (r == 0 && m < p.M && live)
         p.C_bits[(uint32_t)(m * (2 * p.ldc) + (n >> 5))] = h ? (uint32_t)(mask >> 32) : (uint32_t)mask;
     } else if (m < p.M && n < p.N && live) {
+#ifdef BMX_FP4_PLAIN_STORES
+      if (OUT == kOutI32) p.C_i32[idx] = p.as_count ? ((int)dot + p.Kreal) >> 1 : (int)dot;
+      else p.C_f32[idx] = al * dot;
+#else
       if (OUT == kOutI32) __builtin_nontemporal_store(p.as_count ? ((int)dot + p.Kreal) >> 1 : (int)dot, p.C_i32 + idx);
       else __builtin_nontemporal_store(al * dot, p.C_f32 + idx);
+#endif
     }
   };
   // per-column constants of this lane (column 32 j + r)
@@ -387,15 +398,24 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
   // areas (nothing of another wave's lies there), then finishes the accumulator groups
   // g = wave, wave + S, ... : S partials in, one store out.
   float4* part = (float4*)lds;
+  uint2* part16 = (uint2*)lds;  // HALF: four sums as two fp16 pairs, 8 bytes per lane and group
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
-        part[wave * kSlot + ((i * TN + j) * 4 + q) * 64 + lane] =
-            make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
-  int* cnt = (int*)(part + wave * kSlot + kGroups * 64);  // [32 TM] row counts, [32 TN] column counts
+      for (int q = 0; q < 4; ++q) {
+        const int g = (i * TN + j) * 4 + q;
+        if constexpr (HALF) {
+          const half2_t lo = __builtin_amdgcn_cvt_pkrtz(acc[i][j][4 * q], acc[i][j][4 * q + 1]);
+          const half2_t hi = __builtin_amdgcn_cvt_pkrtz(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+          part16[(wave * kSlot) * 2 + g * 64 + lane] = make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
+        } else {
+          part[wave * kSlot + g * 64 + lane] =
+              make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+        }
+      }
+  int* cnt = (int*)(part + wave * kSlot + kPart);  // [32 TM] row counts, [32 TN] column counts
   if (XNOR && h == 0) {
 #pragma unroll
     for (int i = 0; i < TM; ++i) cnt[32 * i + r] = pa[i];
@@ -404,60 +424,84 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
   }
   __syncthreads();
   FP4_STAMP(4);
-  // full-K popcounts: lane l sums row l of the tile (TM = 2: 64 rows) and column l over the S
-  // waves' counts, one conflict-free read each; a lane then picks the rows and the column of
-  // its own results out of other lanes' registers
-  int pa_tot = 0, pb_tot = 0;
-  if (XNOR) {
-    static_assert(TM == 2 && TN == 2, "one lane per row and per column of the tile");
-    int ca[8], cb8[8];
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      const int* c = (const int*)(part + (s < S ? s : S - 1) * kSlot + kGroups * 64);
-      ca[s] = c[lane];
-      cb8[s] = c[32 * TM + lane];
-    }
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      pa_tot += s < S ? ca[s] : 0;
-      pb_tot += s < S ? cb8[s] : 0;
-    }
-  }
-  for (int g = wave; g < kGroups; g += S) {
-    const int blk = g >> 2, q = g & 3, i = blk / TN, j = blk % TN;
-    const int row0 = 32 * i + 8 * q + 4 * h;  // this lane's four rows: row0 .. row0 + 3
-    // all reads first (partials past S repeat the last one and count as nothing), so that the
-    // LDS round trips overlap instead of adding up
-    float4 t[8];
-#pragma unroll
-    for (int s = 0; s < 8; ++s) t[s] = part[(s < S ? s : S - 1) * kSlot + g * 64 + lane];
-    float4 tot = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      const bool on = s < S;
-      tot.x += on ? t[s].x : 0.f;
-      tot.y += on ? t[s].y : 0.f;
-      tot.z += on ? t[s].z : 0.f;
-      tot.w += on ? t[s].w : 0.f;
-    }
-#ifdef BMX_FP4_STAMPS
-    if (g == wave) { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); FP4_STAMP(7); }
-#endif
-    int ra[4], cb = 0;
+  // FULL: all eight waves split K (the usual case): no partial has to be masked out
+  auto reduce = [&](auto full_tag) {
+    constexpr bool FULL = decltype(full_tag)::value;
+    // full-K popcounts: lane l sums row l of the tile (TM = 2: 64 rows) and column l over the S
+    // waves' counts, one conflict-free read each; a lane then picks the rows and the column of
+    // its own results out of other lanes' registers
+    int pa_tot = 0, pb_tot = 0;
     if (XNOR) {
+      static_assert(TM == 2 && TN == 2, "one lane per row and per column of the tile");
+      int ca[8], cb8[8];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) ra[e] = __shfl(pa_tot, row0 + e);
-      cb = __shfl(pb_tot, 32 * j + r);
-    } else {
+      for (int s = 0; s < 8; ++s) {
+        const int* c = (const int*)(part + (FULL || s < S ? s : S - 1) * kSlot + kPart);
+        ca[s] = c[lane];
+        cb8[s] = c[32 * TM + lane];
+      }
 #pragma unroll
-      for (int e = 0; e < 4; ++e) ra[e] = p.rowsum[min(m0 + row0 + e, p.M - 1)];
+      for (int s = 0; s < 8; ++s) {
+        pa_tot += (FULL || s < S) ? ca[s] : 0;
+        pb_tot += (FULL || s < S) ? cb8[s] : 0;
+      }
     }
-    const float al = j == 0 ? aln[0] : aln[TN - 1], th = j == 0 ? thn[0] : thn[TN - 1];
-    finish(i, j, 4 * q, tot.x, ra[0], cb, al, th);
-    finish(i, j, 4 * q + 1, tot.y, ra[1], cb, al, th);
-    finish(i, j, 4 * q + 2, tot.z, ra[2], cb, al, th);
-    finish(i, j, 4 * q + 3, tot.w, ra[3], cb, al, th);
-  }
+    for (int g = wave; g < kGroups; g += S) {
+      const int blk = g >> 2, q = g & 3, i = blk / TN, j = blk % TN;
+      const int row0 = 32 * i + 8 * q + 4 * h;  // this lane's four rows: row0 .. row0 + 3
+      // all reads first (partials past S repeat the last one and count as nothing), so that the
+      // LDS round trips overlap instead of adding up
+      float4 tot = make_float4(0.f, 0.f, 0.f, 0.f);
+      if constexpr (HALF) {
+        uint2 t[8];
+#pragma unroll
+        for (int s = 0; s < 8; ++s) t[s] = part16[((FULL || s < S ? s : S - 1) * kSlot) * 2 + g * 64 + lane];
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+          const bool on = FULL || s < S;
+          const half2_t lo = __builtin_bit_cast(half2_t, t[s].x), hi = __builtin_bit_cast(half2_t, t[s].y);
+          tot.x += on ? (float)lo[0] : 0.f;
+          tot.y += on ? (float)lo[1] : 0.f;
+          tot.z += on ? (float)hi[0] : 0.f;
+          tot.w += on ? (float)hi[1] : 0.f;
+        }
+      } else {
+        float4 t[8];
+#pragma unroll
+        for (int s = 0; s < 8; ++s) t[s] = part[(FULL || s < S ? s : S - 1) * kSlot + g * 64 + lane];
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+          const bool on = FULL || s < S;
+          tot.x += on ? t[s].x : 0.f;
+          tot.y += on ? t[s].y : 0.f;
+          tot.z += on ? t[s].z : 0.f;
+          tot.w += on ? t[s].w : 0.f;
+        }
+      }
+#if defined(BMX_FP4_STAMPS) && !defined(BMX_FP4_STAMP_FIRST_STORES)
+      if (g == wave) { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); FP4_STAMP(7); }
+#endif
+      int ra[4], cb = 0;
+      if (XNOR) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ra[e] = __shfl(pa_tot, row0 + e);
+        cb = __shfl(pb_tot, 32 * j + r);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ra[e] = p.rowsum[min(m0 + row0 + e, p.M - 1)];
+      }
+      const float al = j == 0 ? aln[0] : aln[TN - 1], th = j == 0 ? thn[0] : thn[TN - 1];
+      finish(i, j, 4 * q, tot.x, ra[0], cb, al, th);
+      finish(i, j, 4 * q + 1, tot.y, ra[1], cb, al, th);
+      finish(i, j, 4 * q + 2, tot.z, ra[2], cb, al, th);
+      finish(i, j, 4 * q + 3, tot.w, ra[3], cb, al, th);
+#ifdef BMX_FP4_STAMP_FIRST_STORES
+      if (g == wave) FP4_STAMP(7);
+#endif
+    }
+  };
+  if (S == 8) reduce(std::true_type{});
+  else reduce(std::false_type{});
   FP4_STAMP(5);
 #ifdef BMX_FP4_STAMPS
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -465,14 +509,19 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
 #endif
 }
 
-template <int TM, int TN, int PL, bool XNOR, int OUT, bool SPLIT>
+}  // namespace
+int gemm_fp4_half = 0;  // 2 = keep fp32 partials (tests of both forms)
+namespace {
+
+template <int TM, int TN, int PL, bool XNOR, int OUT, bool SPLIT, bool HALF>
 hipError_t launch_tile(const Fp4Params& p, int S, int tiles_per_wg, int64_t blocks, hipStream_t s) {
   constexpr int NB = TM * PL + TN, kStage = NB * 128, kGroups = TM * TN * 4, kCnt = (TM + TN) * 8;
   constexpr int bufs = (NB <= 4 && BMX_FP4_AHEAD >= 2) ? 2 : 1;
-  constexpr int slot = bufs * kStage > kGroups * 64 + kCnt ? bufs * kStage : kGroups * 64 + kCnt;
+  constexpr int part = HALF ? kGroups * 32 : kGroups * 64;
+  constexpr int slot = bufs * kStage > part + kCnt ? bufs * kStage : part + kCnt;
   const int waves = SPLIT ? S : tiles_per_wg;
   const size_t lds = (size_t)waves * slot * 16;
-  auto kern = gemm_fp4_kernel<TM, TN, PL, XNOR, OUT, SPLIT>;
+  auto kern = gemm_fp4_kernel<TM, TN, PL, XNOR, OUT, SPLIT, HALF>;
   if (lds > 64 * 1024) {  // more than the default limit of dynamic LDS: raised once per device
     static bool raised[64] = {};
     int dev = 0;
@@ -484,9 +533,9 @@ hipError_t launch_tile(const Fp4Params& p, int S, int tiles_per_wg, int64_t bloc
       raised[dev] = true;
     }
   }
-  note_kernel("gemm_fp4_kernel<%d,%d,%d,%s,%s> grid %lld x %d, K split %d, fp4", TM, TN, PL, XNOR ? "xnor" : "planes",
+  note_kernel("gemm_fp4_kernel<%d,%d,%d,%s,%s> grid %lld x %d, K split %d%s, fp4", TM, TN, PL, XNOR ? "xnor" : "planes",
               !XNOR ? "S" : (OUT == kOutF32 ? "f32" : (OUT == kOutI32 ? "i32" : "bits")), (long long)blocks, 64 * waves,
-              SPLIT ? S : 1);
+              SPLIT ? S : 1, HALF ? " (fp16 partials)" : "");
 #ifdef BMX_FP4_STAMPS
   hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(64 * waves), lds, s, p, S, fp4_stamps);
 #else
@@ -497,8 +546,14 @@ hipError_t launch_tile(const Fp4Params& p, int S, int tiles_per_wg, int64_t bloc
 
 template <int PL, bool XNOR, int OUT>
 hipError_t launch_split(const Fp4Params& p, int S, int tiles_per_wg, int64_t blocks, hipStream_t s) {
-  if (S > 1) return launch_tile<2, 2, PL, XNOR, OUT, true>(p, S, tiles_per_wg, blocks, s);
-  return launch_tile<2, 2, PL, XNOR, OUT, false>(p, S, tiles_per_wg, blocks, s);
+  if (S > 1) {
+    // a wave's partial sums are at most (its bits of K) x (2^PL - 1): whole numbers up to 2048
+    // are exact in fp16
+    const int64_t most = (int64_t)(p.g_base + (p.g_rem ? 1 : 0)) * 256 * ((1 << PL) - 1);
+    if (most <= 2048 && gemm_fp4_half != 2) return launch_tile<2, 2, PL, XNOR, OUT, true, true>(p, S, tiles_per_wg, blocks, s);
+    return launch_tile<2, 2, PL, XNOR, OUT, true, false>(p, S, tiles_per_wg, blocks, s);
+  }
+  return launch_tile<2, 2, PL, XNOR, OUT, false, false>(p, S, tiles_per_wg, blocks, s);
 }
 
 }  // namespace
