@@ -275,8 +275,9 @@ size_t bmx_workspace_bytes(int op, const int64_t* dims, int ndims);
  *   key 2  rows per wave (8, 16, 32), key 3  K-split waves, key 4  workgroup order of the
  *          xor/popcount GEMM kernel
  *   key 5  convolution kernel: 1 register-stationary, 2 xor/popcount GEMM kernel,
- *          3 one thread per output, 4 matrix cores (GEMM-shaped), 5 matrix cores (short K,
- *          filters in LDS)
+ *          3 one thread per output, 4 matrix cores (GEMM-shaped, 32 x 32 per wave), 5 matrix cores
+ *          (short K, filters in LDS), 6 matrix cores (GEMM-shaped, 64 x 64 per wave, operands
+ *          staged through LDS)
  *   key 7  GEMM engine: 1 xor/popcount, 2 int8 matrix cores, 3 FP4 matrix cores (kernel chosen by
  *          size), 4 FP4 with 32 x 32 or 64 x 64 per wave and operands through registers, 5 FP4 with
  *          64 x 64 per wave and operands staged through LDS whatever the size

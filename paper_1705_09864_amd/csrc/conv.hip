@@ -277,7 +277,7 @@ hipError_t launch_binary_conv2d(const uint64_t* Xp, int N, int C, int H, int W, 
   // The stationary kernel (whole K in registers, no accumulators) is the faster one on every
   // shape it can hold; a K beyond 36 words goes to the GEMM kernel, which splits K and rows.
   int path = conv_path;
-  if (path == 4 || path == 5) path = 0;
+  if (path == 4 || path == 5 || path == 6) path = 0;
   if (path == 1 && !stationary_ok) path = 0;
   if (path == 2 && !image32) path = 0;
   if (path == 0) path = stationary_ok ? 1 : (image32 ? 2 : 3);
@@ -287,6 +287,18 @@ hipError_t launch_binary_conv2d(const uint64_t* Xp, int N, int C, int H, int W, 
   // the batch, 9.6 against 10.9 us on 8 x 64 x 56 x 56 -> 256, 6.3 against 7.9 us on
   // 16 x 128 x 28 x 28 -> 128; at 36 words 15.6 against 16.8 us for the GEMM-shaped matrix-core
   // kernel (64 x 256 x 14 x 14 -> 256) and 8.2 against 8.6 us at stride 2.
+  // The GEMM kernel with 64 x 64 per wave and LDS-staged operands in its convolution form (6
+  // forces it): the choice beyond the 50 words the short-K kernel reaches, given an even number
+  // of channel words.  Measured per call against the 32 x 32 per wave matrix-core kernel, inputs
+  // from HBM: 200 x 256 x 12 x 12, 5 x 5, 64 filters 16.0 against 19.3 us, 512 channels 25.2
+  // against 30.8 us, 7 x 7 over 256 channels 20.5 against 26.3 us.  Within the short-K kernel's
+  // reach it wins only where that kernel cannot fill the chip (64 x 256 x 14 x 14 at stride 2: 6.5
+  // against 7.1 us) and loses where the output is large (stride 1: 12.8 against 11.2 us: its
+  // tiles store all at once at the end, the short-K kernel block by block), so it is not chosen there.
+  if (conv_path == 6 || (conv_path == 0 && kwords > 50 && (Cw & 1) == 0)) {
+    hipError_t err = hipSuccess;
+    if (launch_conv_fp4(Xp, N, C, H, W, Wp, O, KH, KW, stride, pad, alpha, out_i32, out_f32, s, &err)) return err;
+  }
   if ((conv_path == 5 || (conv_path == 0 && conv_weight_short_k(kwords))) && gemm_engine != 1) {
     hipError_t err = hipSuccess;
     if (launch_conv_mfma_ws(Xp, N, C, H, W, Wp, O, KH, KW, stride, pad, alpha, out_i32, out_f32, nullptr, nullptr, 0,

@@ -64,6 +64,15 @@ struct Fp4Params {
   float* C_f32;
   uint32_t* C_bits;  // packed sign bits, addressed in 32-bit halves of the output words
   int ldc;           // elements per row (C_bits: 64-bit words per row); M * ldc < 2^31
+  // Convolution form (Sec. 3.1: M = filters, N = batch * output pixels, K = kh * kw * C): A is the
+  // packed filter matrix, B the halo-padded packed image.  Column n is output pixel n (flat over
+  // the images); its K words are KH runs of KW * Cw consecutive words, one run per kernel row
+  // (the taps of a kernel row are neighbouring pixels, channel words innermost), so with an even
+  // Cw every 16-byte piece of the im2col row is 16 consecutive bytes of the image.  alpha is per
+  // row m here, and the result goes to NCHW: element (image * M + m) * HoWo + pixel.
+  int HoWo, Wo, Hp, Wpp, Cw, stride;
+  uint32_t run_pieces, row_bytes, npieces;  // pieces per run; bytes from run to run; pieces per pixel
+  FastDiv div_howo, div_wo, div_run;
 };
 
 // One nibble plane of four words of bits as the four operand dwords of one MFMA.
@@ -99,56 +108,39 @@ __device__ __forceinline__ int add_popcount4(int acc, const uint4& w) {
 
 // Request segment `seg` (64 bytes of every row of the wave's NB staged blocks) into the staging
 // area at dst: per block two loads of 16 rows, lane i of a load writing LDS bytes [16 i, 16 i + 16)
-// of its destination.  voff: a lane's byte offset of its piece in segment 0 of its row.
-template <int NA, int NB>
+// of its destination.  voff: a lane's byte offset of its piece in segment 0 of its row (CONV: for
+// the B blocks, of its pixel's patch; the piece's place inside the patch is found here).
+template <int NA, int NB, bool CONV>
 __device__ __forceinline__ void issue_segment(const Fp4Params& p, uint4* dst, const uint32_t* voff /* [NB][2] */,
                                               int piece0, int piece1, int seg) {
   const char* abase = (const char*)p.A + (uint32_t)seg * 64u;
-  const char* bbase = (const char*)p.B + (uint32_t)seg * 64u;
-  if (8 * seg + 8 <= p.Kw) {
+  const char* bbase = (const char*)p.B + (CONV ? 0u : (uint32_t)seg * 64u);
+  const bool tail = 8 * seg + 8 > p.Kw;  // the row ends inside this segment
+  uint32_t boff[2] = {0u, 0u};
+  if (CONV) {
 #pragma unroll
-    for (int b = NB - 1; b >= 0; --b)  // (B first: its rows are the ones that come from far away)
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-        __builtin_amdgcn_global_load_lds((b < NA ? abase : bbase) + voff[2 * b + t], (lds_ptr)(dst + b * 128 + t * 64),
-                                         16, 0, 0);
-  } else {
-    // the row ends inside this segment: a piece that starts beyond its last word is not fetched
-    // (the reader zeroes it); its lane repeats the segment's first piece instead
-#pragma unroll
-    for (int b = NB - 1; b >= 0; --b)
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const int pc = t ? piece1 : piece0;
-        const uint32_t back = 8 * seg + 2 * pc >= p.Kw ? 16u * pc : 0u;
-        __builtin_amdgcn_global_load_lds((b < NA ? abase : bbase) + (voff[2 * b + t] - back),
-                                         (lds_ptr)(dst + b * 128 + t * 64), 16, 0, 0);
-      }
+    for (int t = 0; t < 2; ++t) {
+      // piece c of the im2col row: run c / run_pieces (a kernel row), piece c % run_pieces of it; a
+      // piece beyond the row's last is not fetched (the reader zeroes it): its lane repeats the
+      // segment's first piece, which always exists
+      uint32_t c = 4u * (uint32_t)seg + (uint32_t)(t ? piece1 : piece0);
+      if (c >= p.npieces) c = 4u * (uint32_t)seg;
+      const uint32_t run = fast_div(c, p.div_run);
+      boff[t] = run * p.row_bytes + (c - run * p.run_pieces) * 16u;
+    }
   }
-}
-
-#ifdef BMX_FP4_NODMA
-// Experiment: the same staging through registers (plain 16-byte loads, then 16-byte LDS writes).
-template <int NA, int NB>
-__device__ __forceinline__ void issue_segment_regs(const Fp4Params& p, uint4* dst, const uint32_t* voff, int piece0,
-                                                   int piece1, int seg, int lane) {
-  const char* abase = (const char*)p.A + (uint32_t)seg * 64u;
-  const char* bbase = (const char*)p.B + (uint32_t)seg * 64u;
-  uint4 v[NB][2];
 #pragma unroll
-  for (int b = NB - 1; b >= 0; --b)
+  for (int b = NB - 1; b >= 0; --b)  // (B first: its rows are the ones that come from far away)
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       const int pc = t ? piece1 : piece0;
-      const uint32_t back = (8 * seg + 8 > p.Kw && 8 * seg + 2 * pc >= p.Kw) ? 16u * pc : 0u;
-      v[b][t] = *(const uint4*)((b < NA ? abase : bbase) + (voff[2 * b + t] - back));
+      uint32_t off = voff[2 * b + t];
+      if (CONV && b >= NA) off += boff[t];
+      // (plain rows) a piece that starts beyond the row's last word: repeat the segment's first
+      else if (tail && 8 * seg + 2 * pc >= p.Kw) off -= 16u * pc;
+      __builtin_amdgcn_global_load_lds((b < NA ? abase : bbase) + off, (lds_ptr)(dst + b * 128 + t * 64), 16, 0, 0);
     }
-#pragma unroll
-  for (int b = NB - 1; b >= 0; --b)
-#pragma unroll
-    for (int t = 0; t < 2; ++t) dst[b * 128 + t * 64 + lane] = v[b][t];
 }
-#endif
 
 #ifdef BMX_FP4_STAMPS
 // Profiling builds only: per-wave shader-clock stamps at the phase boundaries of the kernel.
@@ -167,10 +159,10 @@ constexpr int kOutF32 = 0, kOutI32 = 1, kOutBits = 2;
 // popcounts from the words themselves), else the plane form (row sums given); OUT: what the
 // xnor form stores; SPLIT: K split over the S waves of the workgroup (else a tile per wave);
 // HALF: the partial tiles of a split cross LDS as fp16 pairs (exact while a wave's sums stay
-// at or below 2048, which the launcher checks).
+// at or below 2048, which the launcher checks); CONV: the convolution form (see Fp4Params).
 // One instantiation per combination keeps each kernel's code short: the instruction cache
 // starts cold at every launch, and a launch lasts a few microseconds.
-template <int TM, int TN, int PL, bool XNOR, int OUT, bool SPLIT, bool HALF>
+template <int TM, int TN, int PL, bool XNOR, int OUT, bool SPLIT, bool HALF, bool CONV>
 __global__ void __launch_bounds__(512)
 gemm_fp4_kernel(const Fp4Params p, const int S_arg
 #ifdef BMX_FP4_STAMPS
@@ -230,7 +222,16 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
         voff[b][t] = (uint32_t)(m * PL + (b % PL)) * p.lda_bytes + 16u * piece[t];
       } else {
         const int n = min(n0 + 32 * (b - NA) + rl, p.N - 1);
-        voff[b][t] = (uint32_t)n * p.ldb_bytes + 16u * piece[t];
+        if (CONV) {  // byte offset of the pixel's patch: tap (0, 0), channel word 0
+          const uint32_t img = fast_div((uint32_t)n, p.div_howo);
+          const uint32_t rem = (uint32_t)n - img * (uint32_t)p.HoWo;
+          const uint32_t ho = fast_div(rem, p.div_wo);
+          const uint32_t wo = rem - ho * (uint32_t)p.Wo;
+          voff[b][t] = (((img * (uint32_t)p.Hp + ho * (uint32_t)p.stride) * (uint32_t)p.Wpp + wo * (uint32_t)p.stride) *
+                        (uint32_t)p.Cw) * 8u;
+        } else {
+          voff[b][t] = (uint32_t)n * p.ldb_bytes + 16u * piece[t];
+        }
       }
     }
   // reader: lane (r, h) takes piece 2 g + h of row r for group g of the segment
@@ -238,17 +239,10 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
 #pragma unroll
   for (int g = 0; g < 2; ++g) rd[g] = (r >> 4) * 64 + (r & 15) * 4 + ((2 * g + h) ^ ((r >> 1) & 3));
 
-#ifdef BMX_FP4_PRIO
-  if (SPLIT && wave < 4) __builtin_amdgcn_s_setprio(3);
-#endif
   // with two staging areas the first two segments go out together: their latencies overlap
-#ifdef BMX_FP4_NODMA
-  if (seg_lo < seg_hi) issue_segment_regs<NA, NB>(p, stage, &voff[0][0], piece[0], piece[1], seg_lo, lane);
-#else
-  if (seg_lo < seg_hi) issue_segment<NA, NB>(p, stage, &voff[0][0], piece[0], piece[1], seg_lo);
-#endif
+  if (seg_lo < seg_hi) issue_segment<NA, NB, CONV>(p, stage, &voff[0][0], piece[0], piece[1], seg_lo);
   if (kBufs == 2 && !kLateSecond && seg_lo + 1 < seg_hi)
-    issue_segment<NA, NB>(p, stage + kStage, &voff[0][0], piece[0], piece[1], seg_lo + 1);
+    issue_segment<NA, NB, CONV>(p, stage + kStage, &voff[0][0], piece[0], piece[1], seg_lo + 1);
   FP4_STAMP(1);
 
   v16f acc[TM][TN];
@@ -291,12 +285,8 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
     if (seg == seg_lo) { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); FP4_STAMP(2); }
 #endif
     if (kBufs == 2 && kLateSecond && seg == seg_lo && seg + 1 < seg_hi)
-      issue_segment<NA, NB>(p, stage + kStage, &voff[0][0], piece[0], piece[1], seg + 1);
-#ifdef BMX_FP4_NODMA
-    if (seg + kBufs < seg_hi) issue_segment_regs<NA, NB>(p, stage + buf * kStage, &voff[0][0], piece[0], piece[1], seg + kBufs, lane);
-#else
-    if (seg + kBufs < seg_hi) issue_segment<NA, NB>(p, stage + buf * kStage, &voff[0][0], piece[0], piece[1], seg + kBufs);
-#endif
+      issue_segment<NA, NB, CONV>(p, stage + kStage, &voff[0][0], piece[0], piece[1], seg + 1);
+    if (seg + kBufs < seg_hi) issue_segment<NA, NB, CONV>(p, stage + buf * kStage, &voff[0][0], piece[0], piece[1], seg + kBufs);
 #pragma unroll
     for (int g = 0; g < 2; ++g) {
       const int kg = 2 * seg + g;
@@ -333,13 +323,25 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
   }
   FP4_STAMP(3);
 
+  // per-column constants of this lane (column 32 j + r); CONV: where the pixel's results go
+  float aln[TN], thn[TN];
+  uint32_t pix_img[TN], pix_rem[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int n = min(n0 + 32 * j + r, p.N - 1);
+    aln[j] = (XNOR && !CONV && p.alpha) ? p.alpha[n] : 1.0f;
+    thn[j] = (XNOR && OUT == kOutBits && p.thr) ? p.thr[n] : 0.0f;
+    pix_img[j] = CONV ? fast_div((uint32_t)n, p.div_howo) : 0u;
+    pix_rem[j] = CONV ? (uint32_t)n - pix_img[j] * (uint32_t)p.HoWo : 0u;
+  }
   // ---- epilogue.  Register v of lane (r, h) in block (i, j) is C[32 i + 8 (v / 4) + 4 h + v % 4][32 j + r].
   // tot: the full-K sum of the MFMA results; ra, cb: pc(A row), pc(B column) over the full K
   // (plane form: ra = the row sum of the quantised activations).
   auto finish = [&](int i, int j, int v, float tot, int ra, int cb, float al, float th) {
     const int mi = 32 * i + 8 * (v >> 2) + 4 * h + (v & 3);
     const int m = m0 + mi, n = n0 + 32 * j + r;
-    const uint32_t idx = (uint32_t)(m * p.ldc + n);
+    const uint32_t idx = CONV ? (pix_img[j] * (uint32_t)p.M + (uint32_t)m) * (uint32_t)p.HoWo + pix_rem[j]
+                              : (uint32_t)(m * p.ldc + n);
     if (!XNOR) {
       if (m < p.M && n < p.N && live) {
         const int sv = 2 * (int)tot - ra;
@@ -356,23 +358,10 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
       if (r == 0 && m < p.M && live)
         p.C_bits[(uint32_t)(m * (2 * p.ldc) + (n >> 5))] = h ? (uint32_t)(mask >> 32) : (uint32_t)mask;
     } else if (m < p.M && n < p.N && live) {
-#ifdef BMX_FP4_PLAIN_STORES
-      if (OUT == kOutI32) p.C_i32[idx] = p.as_count ? ((int)dot + p.Kreal) >> 1 : (int)dot;
-      else p.C_f32[idx] = al * dot;
-#else
       if (OUT == kOutI32) __builtin_nontemporal_store(p.as_count ? ((int)dot + p.Kreal) >> 1 : (int)dot, p.C_i32 + idx);
       else __builtin_nontemporal_store(al * dot, p.C_f32 + idx);
-#endif
     }
   };
-  // per-column constants of this lane (column 32 j + r)
-  float aln[TN], thn[TN];
-#pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int n = min(n0 + 32 * j + r, p.N - 1);
-    aln[j] = (XNOR && p.alpha) ? p.alpha[n] : 1.0f;
-    thn[j] = (XNOR && OUT == kOutBits && p.thr) ? p.thr[n] : 0.0f;
-  }
   // popcounts: a lane counted its half of K for row / column r; the other half sits 32 lanes away
   if (XNOR) {
 #pragma unroll
@@ -388,8 +377,9 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
       for (int v = 0; v < 16; ++v) {
         const int mi = 32 * i + 8 * (v >> 2) + 4 * h + (v & 3);
         const int ra = XNOR ? __shfl(pa[i], mi & 31) : p.rowsum[min(m0 + mi, p.M - 1)];
+        const float alm = (CONV && p.alpha) ? p.alpha[min(m0 + mi, p.M - 1)] : 1.0f;
 #pragma unroll
-        for (int j = 0; j < TN; ++j) finish(i, j, v, acc[i][j][v], ra, pb[j], aln[j], thn[j]);
+        for (int j = 0; j < TN; ++j) finish(i, j, v, acc[i][j][v], ra, pb[j], CONV ? alm : aln[j], thn[j]);
       }
     return;
   }
@@ -478,7 +468,7 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
           tot.w += on ? t[s].w : 0.f;
         }
       }
-#if defined(BMX_FP4_STAMPS) && !defined(BMX_FP4_STAMP_FIRST_STORES)
+#ifdef BMX_FP4_STAMPS
       if (g == wave) { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); FP4_STAMP(7); }
 #endif
       int ra[4], cb = 0;
@@ -491,13 +481,15 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
         for (int e = 0; e < 4; ++e) ra[e] = p.rowsum[min(m0 + row0 + e, p.M - 1)];
       }
       const float al = j == 0 ? aln[0] : aln[TN - 1], th = j == 0 ? thn[0] : thn[TN - 1];
-      finish(i, j, 4 * q, tot.x, ra[0], cb, al, th);
-      finish(i, j, 4 * q + 1, tot.y, ra[1], cb, al, th);
-      finish(i, j, 4 * q + 2, tot.z, ra[2], cb, al, th);
-      finish(i, j, 4 * q + 3, tot.w, ra[3], cb, al, th);
-#ifdef BMX_FP4_STAMP_FIRST_STORES
-      if (g == wave) FP4_STAMP(7);
-#endif
+      float alm[4] = {al, al, al, al};
+      if (CONV && p.alpha) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) alm[e] = p.alpha[min(m0 + row0 + e, p.M - 1)];
+      }
+      finish(i, j, 4 * q, tot.x, ra[0], cb, alm[0], th);
+      finish(i, j, 4 * q + 1, tot.y, ra[1], cb, alm[1], th);
+      finish(i, j, 4 * q + 2, tot.z, ra[2], cb, alm[2], th);
+      finish(i, j, 4 * q + 3, tot.w, ra[3], cb, alm[3], th);
     }
   };
   if (S == 8) reduce(std::true_type{});
@@ -513,7 +505,7 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
 int gemm_fp4_half = 0;  // 2 = keep fp32 partials (tests of both forms)
 namespace {
 
-template <int TM, int TN, int PL, bool XNOR, int OUT, bool SPLIT, bool HALF>
+template <int TM, int TN, int PL, bool XNOR, int OUT, bool SPLIT, bool HALF, bool CONV = false>
 hipError_t launch_tile(const Fp4Params& p, int S, int tiles_per_wg, int64_t blocks, hipStream_t s) {
   constexpr int NB = TM * PL + TN, kStage = NB * 128, kGroups = TM * TN * 4, kCnt = (TM + TN) * 8;
   constexpr int bufs = (NB <= 4 && BMX_FP4_AHEAD >= 2) ? 2 : 1;
@@ -521,7 +513,7 @@ hipError_t launch_tile(const Fp4Params& p, int S, int tiles_per_wg, int64_t bloc
   constexpr int slot = bufs * kStage > part + kCnt ? bufs * kStage : part + kCnt;
   const int waves = SPLIT ? S : tiles_per_wg;
   const size_t lds = (size_t)waves * slot * 16;
-  auto kern = gemm_fp4_kernel<TM, TN, PL, XNOR, OUT, SPLIT, HALF>;
+  auto kern = gemm_fp4_kernel<TM, TN, PL, XNOR, OUT, SPLIT, HALF, CONV>;
   if (lds > 64 * 1024) {  // more than the default limit of dynamic LDS: raised once per device
     static bool raised[64] = {};
     int dev = 0;
@@ -533,9 +525,9 @@ hipError_t launch_tile(const Fp4Params& p, int S, int tiles_per_wg, int64_t bloc
       raised[dev] = true;
     }
   }
-  note_kernel("gemm_fp4_kernel<%d,%d,%d,%s,%s> grid %lld x %d, K split %d%s, fp4", TM, TN, PL, XNOR ? "xnor" : "planes",
-              !XNOR ? "S" : (OUT == kOutF32 ? "f32" : (OUT == kOutI32 ? "i32" : "bits")), (long long)blocks, 64 * waves,
-              SPLIT ? S : 1, HALF ? " (fp16 partials)" : "");
+  note_kernel("gemm_fp4_kernel<%d,%d,%d,%s,%s%s> grid %lld x %d, K split %d%s, fp4", TM, TN, PL, XNOR ? "xnor" : "planes",
+              !XNOR ? "S" : (OUT == kOutF32 ? "f32" : (OUT == kOutI32 ? "i32" : "bits")), CONV ? ",conv" : "",
+              (long long)blocks, 64 * waves, SPLIT ? S : 1, HALF ? " (fp16 partials)" : "");
 #ifdef BMX_FP4_STAMPS
   hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(64 * waves), lds, s, p, S, fp4_stamps);
 #else
@@ -544,16 +536,17 @@ hipError_t launch_tile(const Fp4Params& p, int S, int tiles_per_wg, int64_t bloc
   return hipGetLastError();
 }
 
-template <int PL, bool XNOR, int OUT>
+template <int PL, bool XNOR, int OUT, bool CONV = false>
 hipError_t launch_split(const Fp4Params& p, int S, int tiles_per_wg, int64_t blocks, hipStream_t s) {
   if (S > 1) {
     // a wave's partial sums are at most (its bits of K) x (2^PL - 1): whole numbers up to 2048
     // are exact in fp16
     const int64_t most = (int64_t)(p.g_base + (p.g_rem ? 1 : 0)) * 256 * ((1 << PL) - 1);
-    if (most <= 2048 && gemm_fp4_half != 2) return launch_tile<2, 2, PL, XNOR, OUT, true, true>(p, S, tiles_per_wg, blocks, s);
-    return launch_tile<2, 2, PL, XNOR, OUT, true, false>(p, S, tiles_per_wg, blocks, s);
+    if (most <= 2048 && gemm_fp4_half != 2)
+      return launch_tile<2, 2, PL, XNOR, OUT, true, true, CONV>(p, S, tiles_per_wg, blocks, s);
+    return launch_tile<2, 2, PL, XNOR, OUT, true, false, CONV>(p, S, tiles_per_wg, blocks, s);
   }
-  return launch_tile<2, 2, PL, XNOR, OUT, false, false>(p, S, tiles_per_wg, blocks, s);
+  return launch_tile<2, 2, PL, XNOR, OUT, false, false, CONV>(p, S, tiles_per_wg, blocks, s);
 }
 
 }  // namespace
@@ -601,6 +594,9 @@ bool launch_gemm_fp4(const uint64_t* A, int64_t lda_w, int planes, const int32_t
   p.C_f32 = C_f32;
   p.C_bits = (uint32_t*)C_bits;
   p.ldc = (int)ldc;
+  p.HoWo = p.Wo = p.Hp = p.Wpp = p.Cw = p.stride = 1;
+  p.run_pieces = p.row_bytes = p.npieces = 1;
+  p.div_howo = p.div_wo = p.div_run = make_fast_div(1);
   // K split: about two waves per SIMD (2048 in all), at most eight per tile, and every wave
   // keeps at least one 64-byte segment
   int S = gemm_fp4_split;
@@ -626,6 +622,79 @@ bool launch_gemm_fp4(const uint64_t* A, int64_t lda_w, int planes, const int32_t
   } else {
     *err = launch_split<2, false, kOutF32>(p, S, tiles_per_wg, blocks, s);
   }
+  return true;
+}
+
+// The convolution on the same kernel (Xp, Wp as for launch_binary_conv2d).  Takes the problem when
+// every 16-byte piece of an im2col row is 16 consecutive bytes of the packed image (an even number
+// of channel words), rows are 16-byte aligned, and image and output fit 32-bit offsets.
+bool launch_conv_fp4(const uint64_t* Xp, int Nimg, int C, int H, int W, const uint64_t* Wp, int O, int KH, int KW,
+                     int stride, int pad, const float* alpha, int32_t* out_i32, float* out_f32, hipStream_t s,
+                     hipError_t* err) {
+  if (gemm_engine == 1 || gemm_engine == 2 || gemm_engine == 4) return false;
+  const int Ho = (H + 2 * pad - KH) / stride + 1;
+  const int Wo = (W + 2 * pad - KW) / stride + 1;
+  const int Cw = (int)words_for(C);
+  const int kwords = KH * KW * Cw;
+  const int64_t ld_words = conv_weight_row_words(kwords);
+  const int64_t P = (int64_t)Nimg * Ho * Wo;
+  const int Hp = H + 2 * pad, Wpp = W + 2 * pad;
+  if ((Cw & 1) || (ld_words & 1) || ((uintptr_t)Wp & 15) || ((uintptr_t)Xp & 15)) return false;
+  if ((int64_t)kwords * 64 >= ((int64_t)1 << 24)) return false;
+  if ((int64_t)Nimg * Hp * Wpp * Cw * 8 >= ((int64_t)1 << 32) || (int64_t)O * ld_words * 8 >= ((int64_t)1 << 32))
+    return false;
+  if (P >= ((int64_t)1 << 31) || ((int64_t)Nimg * O + 64) * Ho * Wo >= ((int64_t)1 << 31)) return false;
+  const int tiles_m = (int)ceil_div(O, 64), tiles_n = (int)ceil_div(P, 64);
+  const int64_t tiles = (int64_t)tiles_m * tiles_n;
+  if (tiles >= ((int64_t)1 << 28)) return false;
+  Fp4Params p;
+  p.A = Wp;
+  p.B = Xp;
+  p.lda_bytes = (uint32_t)(ld_words * 8);
+  p.ldb_bytes = 0;
+  p.M = O;
+  p.N = (int)P;
+  p.Kw = kwords;
+  p.Kreal = C * KH * KW;
+  const int ngroups = (int)ceil_div(kwords, 4);
+  p.tiles_m = tiles_m;
+  p.tiles_n = tiles_n;
+  p.div_tiles_m = make_fast_div((uint32_t)tiles_m);
+  p.alpha = alpha;
+  p.thr = nullptr;
+  p.rowsum = nullptr;
+  p.levels = 1.0f;
+  p.as_count = 0;
+  p.C_i32 = out_i32;
+  p.C_f32 = out_f32;
+  p.C_bits = nullptr;
+  p.ldc = 0;
+  p.HoWo = Ho * Wo;
+  p.Wo = Wo;
+  p.Hp = Hp;
+  p.Wpp = Wpp;
+  p.Cw = Cw;
+  p.stride = stride;
+  p.run_pieces = (uint32_t)(KW * Cw / 2);
+  p.row_bytes = (uint32_t)((int64_t)Wpp * Cw * 8);
+  p.npieces = (uint32_t)(kwords / 2);
+  p.div_howo = make_fast_div((uint32_t)(Ho * Wo));
+  p.div_wo = make_fast_div((uint32_t)Wo);
+  p.div_run = make_fast_div(p.run_pieces);
+  // K split: about two waves per SIMD; a wave may carry a single group of 256 bits
+  int S = gemm_fp4_split;
+  if (S <= 0) S = (int)ceil_div(2048, tiles);
+  S = S > 8 ? 8 : S;
+  if (S > ngroups) S = ngroups;
+  if (S < 1) S = 1;
+  p.g_base = ngroups / S;
+  p.g_rem = ngroups - p.g_base * S;
+  const int tiles_per_wg = 4;
+  const int64_t wgs = S > 1 ? tiles : ceil_div(tiles, tiles_per_wg);
+  p.tiles_per_xcd = (int)ceil_div(wgs, 8);
+  const int64_t blocks = 8 * (int64_t)p.tiles_per_xcd;
+  if (out_i32) *err = launch_split<1, true, kOutI32, true>(p, S, tiles_per_wg, blocks, s);
+  else *err = launch_split<1, true, kOutF32, true>(p, S, tiles_per_wg, blocks, s);
   return true;
 }
 

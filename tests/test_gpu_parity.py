@@ -940,3 +940,39 @@ def test_gemm_fp4_lds_staged_kernel(split, partials):
                 rS, r64, r32 = oracle.quant_gemm(a, wq, bits)
                 np.testing.assert_array_equal(Sg.cpu().numpy(), rS)
                 assert_f32_close(fg.cpu().numpy(), r32)
+
+
+FP4_CONV_CASES = [
+    # N, C, H, W, O, k, s, p   (an even number of channel words: 16-byte pieces never straddle two taps)
+    (2, 128, 9, 9, 33, 5, 2, 2),
+    (3, 100, 9, 11, 70, 3, 1, 1),
+    (1, 256, 14, 14, 19, 3, 1, 2),
+    (2, 500, 5, 5, 70, 1, 1, 0),
+    (1, 1024, 4, 4, 17, 3, 1, 1),
+    (3, 200, 12, 12, 64, 5, 1, 0),
+    (2, 128, 28, 28, 128, 3, 2, 1),
+    (2, 66, 9, 8, 3, 7, 1, 3),
+    (5, 256, 14, 14, 256, 3, 1, 1),
+    (1, 70, 1, 1, 1, 1, 1, 0),
+]
+
+
+@pytest.mark.parametrize("split", [0, 1, 2, 3, 8])
+def test_conv_fp4_lds_staged_kernel(split):
+    """The convolution form of the 64 x 64 per wave matrix-core kernel (im2col rows gathered piece
+    by piece from the packed image by the load unit), forced through the tuning hook: ragged
+    filter and pixel tiles, pixel tiles that straddle images, strides, halos, K that ends inside
+    a 64-byte segment, every K split, both output kinds."""
+    for (N, C, H, W, O, k, s, p) in FP4_CONV_CASES:
+        rng = np.random.default_rng(N + 10 * C + 100 * H + 1000 * O + k + s + p + split)
+        x = rng.standard_normal((N, C, H, W)).astype(np.float32)
+        x[rng.random(x.shape) < 0.05] = 0.0
+        w = rng.standard_normal((O, C, k, k)).astype(np.float32)
+        alpha = rng.standard_normal(O).astype(np.float32)
+        ri, rf = oracle.binary_conv2d(x, w, s, p, alpha)
+        with tuned(k5=6, k10=split):
+            got_i = run_conv(x, w, s, p, integer_out=True)
+            assert "gemm_fp4_kernel" in B.last_kernel() and "conv" in B.last_kernel(), B.last_kernel()
+            np.testing.assert_array_equal(got_i, ri)
+            assert_f32_close(run_conv(x, w, s, p, alpha=alpha), rf)
+            np.testing.assert_array_equal(run_conv(x, w, s, p), ri.astype(np.float32))
