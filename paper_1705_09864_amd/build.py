@@ -32,8 +32,9 @@ def device_asm(src):
 
 
 def check_scalar_loads():
-    """Scan the compiled device code of every source for registers of a hand-placed scalar
-    load that are touched while the load is still in flight (see isa_check.py)."""
+    """Scan the compiled device code of every source for registers of an inline-asm scalar
+    load that are touched while the load is still in flight (see isa_check.py; the kernels have
+    no such load, the scan guards against one coming back)."""
     try:
         from . import isa_check
     except ImportError:  # run as a script

@@ -43,7 +43,7 @@ __host__ __device__ static inline int64_t conv_weight_bits_words(int64_t kwords)
   const int ch = conv_weight_chunk_dwords(kwords);
   return ceil_div(2 * kwords, ch) * ch / 2;
 }
-// For the K the short-K matrix-core convolution kernel takes (9, 18 or 36 words) a row carries,
+// For the K the short-K matrix-core convolution kernel takes (the list below) a row carries,
 // behind its chunk-padded bits, two more words: the float K - 2 * popcount(filter) in the first
 // dword, zeros after it (the kernel's epilogue constant, computed once with the offline weight
 // pack of Sec. 2.2.3; rows stay a whole number of 16 bytes).
@@ -133,7 +133,7 @@ bool launch_conv_mfma(const uint64_t* Xp, int Nimg, int C, int H, int W, const u
                       int KW, int stride, int pad, const float* alpha, int32_t* out_i32, float* out_f32,
                       hipStream_t s, hipError_t* err);
 // conv_mfma.hip: the convolution on the FP4 matrix cores with the expanded filters of a
-// workgroup in LDS (K of 9, 18 or 36 words).  Returns false outside its domain.  With out_bits
+// workgroup in LDS (K as conv_weight_short_k lists).  Returns false outside its domain.  With out_bits
 // the result leaves as the packed image of the next convolution (halo out_pad, written too):
 // bit o = (alpha[o] * dot >= thr[o]), thr null = 0.
 bool conv_mfma_ws_takes(int Nimg, int C, int H, int W, int O, int KH, int KW, int stride, int pad,

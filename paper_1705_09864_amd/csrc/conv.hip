@@ -120,7 +120,10 @@ conv_stationary_kernel(const ConvParams p) {
   }
   const int o0 = blockIdx.y * p.cn;
   const int nrows = min(p.cn, p.O - o0);
-  const_f32_ptr alpha = (const_f32_ptr)uniform_addr((uint64_t)(uintptr_t)p.alpha + 4 * (int64_t)o0);
+  // alpha of the wave's filters: filter o0 + i in lane i (at most 64 filters per wave), handed
+  // out with readlane as a row completes
+  float alpha_lane = 1.0f;
+  if (OUT == kOutF32Alpha) alpha_lane = p.alpha[o0 + min(lane, nrows - 1)];
   // Rows o0 .. o0+nrows-1 are a stream of nrows * NSEG segments (row_pad_dw dwords of
   // padding follow the last segment of every row).
   const int nseg_total = nrows * NSEG;
@@ -134,42 +137,25 @@ conv_stationary_kernel(const ConvParams p) {
   const int64_t ostride = (int64_t)p.HoWo * 4;
 
   ScalarSeg<SEG> buf[2];
-  float sc[2] = {1.0f, 1.0f};  // alpha of the row whose last segment sits in buf[k]
   int pc = 0;
-  asm volatile("" : "+v"(pc));
   const_u32_ptr src = stream;
   int left = nseg_total - 1;  // segments after the one at src
-  const_f32_ptr aptr = alpha;  // alpha of the row whose last segment is requested next
-  int rows_left = nrows - 1;   // rows after the one at aptr
-  buf[0].issue(src, pc);
-  if (OUT == kOutF32Alpha && NSEG == 1) asm volatile("s_load_dword %0, %1, 0x0" : "=s"(sc[0]) : "s"(aptr));
+  buf[0].issue(src);
   for (int t = 0; t < nseg_total; t += 2 * NSEG) {  // two rows per trip
 #pragma unroll
     for (int i = 0; i < 2 * NSEG; ++i) {
       const int cur = i & 1, nxt = cur ^ 1;
       const int seg_in_row = i % NSEG;
       const int row = t / NSEG + i / NSEG;  // row within the wave's range (uniform)
-      buf[cur].wait();
-      if (OUT == kOutF32Alpha) asm volatile("" : "+s"(sc[cur]));
-      // prefetch the following segment; past the end of this wave's stream the last
-      // segment is fetched again, so nothing beyond the weights is ever read
+      // the following segment; past the end of this wave's stream the last segment is fetched
+      // again, so nothing beyond the weights is ever read
       src += (left > 0) ? (SEG + (seg_in_row == NSEG - 1 ? p.row_pad_dw : 0)) : 0;
       left -= 1;
-      buf[nxt].issue(src, pc);
-      if (OUT == kOutF32Alpha && (i + 1) % NSEG == NSEG - 1) {
-        // the segment just requested ends a row: fetch that row's alpha with it
-        if (NSEG == 1 || (i + 1) / NSEG > 0 || t > 0) {  // not the very first row
-          aptr = (const_f32_ptr)((uint64_t)aptr + ((rows_left > 0) ? 4u : 0u));
-          rows_left -= 1;
-        }
-        asm volatile("s_load_dword %0, %1, 0x0" : "=s"(sc[nxt]) : "s"(aptr));
-      }
+      buf[cur].landed(src);
+      buf[nxt].issue(src);
       if (seg_in_row == 0) pc = seg_popcount<SEG, true>(buf[cur], b, pc);
       else pc = seg_popcount<SEG, false>(buf[cur], b + seg_in_row * SEG, pc);
       if (seg_in_row == NSEG - 1) {
-        // The finished count passes through an ordered asm statement: every VALU read of
-        // buf[cur] is thereby issued before the next trip overwrites that buffer.
-        asm volatile("" : "+v"(pc));
         if (row < nrows) {
           int dot;  // K - 2 * popcount in one VALU op (both operands are below 2^23)
           asm("v_mad_i32_i24 %0, %1, -2, %2" : "=v"(dot) : "v"(pc), "s"(p.Kreal));
@@ -177,7 +163,8 @@ conv_stationary_kernel(const ConvParams p) {
           // (non-temporal: the output is written once and never read here; measured 6.5
           // against 7.8 us on the 16 x 64 x 56 x 56 layer)
           if (OUT == kOutF32Alpha) {
-            const float v = sc[cur] * (float)dot;
+            const float a = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, alpha_lane), row));
+            const float v = a * (float)dot;
             asm volatile("global_store_dword %0, %1, %2 nt" ::"v"(ooff), "v"(v), "s"(obase) : "memory");
           } else if (OUT == kOutF32) {
             const float v = (float)dot;
@@ -190,11 +177,6 @@ conv_stationary_kernel(const ConvParams p) {
       }
     }
   }
-  // Drain the last prefetch (it went to buffer 0).  Its destination registers must stay
-  // allocated until the data has landed: were they dead here, the tail of the loop could be
-  // given the same registers while the load is still in flight.
-  buf[0].wait();
-  if (OUT == kOutF32Alpha) asm volatile("" : "+s"(sc[0]));
 }
 
 // General shape: any number of K words, one thread per output, taps addressed with the
@@ -274,14 +256,15 @@ hipError_t launch_binary_conv2d(const uint64_t* Xp, int N, int C, int H, int W, 
   const bool stationary_ok =
       fits32 && (kwords == 1 || kwords == 2 || kwords == 4 || kwords == 9 || kwords == 18 ||
                  kwords == 25 || kwords == 27 || kwords == 36);
-  // The stationary kernel (whole K in registers, no accumulators) is the faster one on every
-  // shape it can hold; a K beyond 36 words goes to the GEMM kernel, which splits K and rows.
+  // Of the popcount kernels the stationary one (whole K in registers, no accumulators) is the
+  // faster on every shape it can hold; a K beyond 36 words goes to the popcount GEMM kernel,
+  // which splits K and rows.
   int path = conv_path;
   if (path == 4 || path == 5 || path == 6) path = 0;
   if (path == 1 && !stationary_ok) path = 0;
   if (path == 2 && !image32) path = 0;
   if (path == 0) path = stationary_ok ? 1 : (image32 ? 2 : 3);
-  // K of 9, 18 or 36 words: the matrix-core kernel with the expanded filters in LDS.
+  // K of 9, 18, 25, 27, 36, 49 or 50 words: the matrix-core kernel with the expanded filters in LDS.
   // Measured with inputs and outputs rotating through HBM, against the stationary kernel:
   // 6.4 against 6.7 us on 16 x 64 x 56 x 56 -> 64 filters, 17.0 against 24.4 us on four times
   // the batch, 9.6 against 10.9 us on 8 x 64 x 56 x 56 -> 256, 6.3 against 7.9 us on
@@ -353,6 +336,7 @@ hipError_t launch_binary_conv2d(const uint64_t* Xp, int N, int C, int H, int W, 
       cn = 8;
       while (cn < O && cn < 64 && groups * ceil_div(O, cn) > 5 * 1024) cn += 2;
     }
+    if (cn > 64) cn = 64;  // the kernel keeps a wave's alphas one per lane
     p.cn = cn;
     const int cblocks = (int)ceil_div(O, cn);
     switch (kwords) {

@@ -1,4 +1,5 @@
-// Binary convolution on the FP4 matrix cores for short K (9, 18 or 36 words).
+// Binary convolution on the FP4 matrix cores for short K (9, 18, 25, 27, 36,
+// 49 or 50 words: 3 x 3, 5 x 5 and 7 x 7 filters over up to 256, 128 and 64 channels).
 // Paper: Sec. 3.1 (M = filters, N = batch * output pixels, K = kh * kw * C), result
 // out = alpha[o] * (K - 2 * popcount(filter xor patch)) (Sec. 2.2.2, Eq. 2).
 //

@@ -78,23 +78,24 @@ struct GemmParams {
   FastDiv div_howo, div_wo, div_rw;  // div_rw: by KW * Cw, the words of one kernel row
 };
 
-// One CH-dword chunk of an A row in SGPRs.  The loads are volatile asm so that their
-// position relative to the waits is exactly as written.
+// One CH-dword chunk of an A row in SGPRs: ordinary loads through the constant address space
+// from a wave-uniform address, so the compiler emits the scalar loads, waits for them and keeps
+// their registers itself (see ScalarSeg for how the pipeline order is expressed).
 template <int CH>
 struct ARow {
   static_assert(CH == 32 || CH == 24, "chunk is two scalar loads: 16 + 16 or 16 + 8 dwords");
   u32x16 lo;
   typename std::conditional<CH == 32, u32x16, u32x8>::type hi;
   __device__ __forceinline__ void issue(const_u32_ptr src) {
-    asm volatile("s_load_dwordx16 %0, %1, 0x0" : "=s"(lo) : "s"(src));
-    if constexpr (CH == 32) asm volatile("s_load_dwordx16 %0, %1, 0x40" : "=s"(hi) : "s"(src));
-    else asm volatile("s_load_dwordx8 %0, %1, 0x40" : "=s"(hi) : "s"(src));
+    lo = *(const_u32x16_ptr)src;
+    if constexpr (CH == 32) hi = *(const_u32x16_ptr)(src + 16);
+    else hi = *(const_u32x8_ptr)(src + 16);
   }
-  // after s_waitcnt lgkmcnt(0): make every later use depend on this point (and keep the
-  // destination registers allocated up to it)
-  __device__ __forceinline__ void landed() {
-    asm volatile("" : "+s"(lo));
-    asm volatile("" : "+s"(hi));
+  // The chunk's first use (the compiler's wait goes in front of it); `next`, the address of the
+  // request that follows, is defined here, so that request stays below this point.
+  __device__ __forceinline__ void landed(const_u32_ptr& next) {
+    asm volatile("" : "+s"(lo), "+s"(next));
+    asm volatile("" : "+s"(hi), "+s"(next));
   }
   template <int J>
   __device__ __forceinline__ uint32_t get() const {
@@ -120,9 +121,7 @@ __device__ __forceinline__ void row_steps(ARow<CH> (&buf)[2], const uint32_t (&b
                                           const_u32_ptr& src, uint64_t row_bytes, int& rows_valid,
                                           const_u32_ptr next_chunk_row0) {
   if constexpr (r < R) {
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    buf[r & 1].landed();
-    // Request the next row of this chunk (rows past the block's last valid row repeat
+    // The next request: the next row of this chunk (rows past the block's last valid row repeat
     // it), or row 0 of the wave's next chunk after the last row.
     // (the select is kept opaque so that it stays two scalar instructions per row instead
     // of R loop-invariant values that would not fit the scalar register file)
@@ -132,6 +131,7 @@ __device__ __forceinline__ void row_steps(ARow<CH> (&buf)[2], const uint32_t (&b
     } else {
       src = next_chunk_row0;
     }
+    buf[r & 1].landed(src);
     buf[(r + 1) & 1].issue(src);
     row_popcount<CH, OP_AND>(buf[r & 1], b, acc[r]);
     row_steps<R, CH, OP_AND, r + 1>(buf, b, acc, src, row_bytes, rows_valid, next_chunk_row0);
@@ -274,11 +274,7 @@ gemm_kernel(const GemmParams p) {
       warm = warm_row[(int64_t)cn * CH];
       row_steps<R, CH, OP_AND>(buf, b, acc, src, row_bytes, rows_valid, next_row0);
     }
-    // Drain the last prefetch.  Its destination registers must stay allocated until the
-    // data has landed: were they dead here, the code that follows could be given the same
-    // registers while the load is still in flight.
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    buf[0].landed();
+    // The last request (row 0 of the last chunk again) is never used.
     asm volatile("" ::"v"(warm));
   }
 

@@ -20,12 +20,21 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
 
-// SEG dwords of wave-uniform data held in SGPRs, fetched with explicit scalar loads.
-// Scalar loads return out of order, so the only usable wait is lgkmcnt(0); issuing the
-// loads and waiting for them are therefore separate, explicitly placed steps: wait for the
-// current buffer, then issue the next one, then compute.  The loads are written as
-// volatile asm so that the compiler neither tracks them (it would merge both buffers into
-// one wait) nor moves them.
+typedef const u32x2 __attribute__((address_space(4))) * const_u32x2_ptr;
+typedef const u32x4 __attribute__((address_space(4))) * const_u32x4_ptr;
+typedef const u32x8 __attribute__((address_space(4))) * const_u32x8_ptr;
+typedef const u32x16 __attribute__((address_space(4))) * const_u32x16_ptr;
+
+// SEG dwords of wave-uniform data held in SGPRs.  The loads are ordinary loads through the
+// constant address space from a wave-uniform address, which the compiler turns into
+// s_load_dwordxN and tracks itself: it places the s_waitcnt before the first instruction that
+// touches a destination register and never reuses those registers while a load is in flight.
+// Scalar loads return out of order, so that wait is lgkmcnt(0) and covers every scalar load
+// issued before it; the software pipeline (wait for the current buffer, then request the next
+// one, then compute) is therefore expressed through data dependences the compiler can see:
+// landed() passes the buffer and the address of the next request through one empty asm
+// statement, which is the first use of the buffer (the wait goes in front of it) and the
+// definition of the address (the next request cannot be moved above it).
 template <int SEG>
 struct ScalarSeg {
   static constexpr int n16 = SEG / 16, r16 = SEG % 16;
@@ -39,31 +48,20 @@ struct ScalarSeg {
   u32x2 a2;
   uint32_t a1;
 
-  // `tie` is an accumulator the following VALU work depends on: threading it through the
-  // first load keeps that work behind the issue point.
-  __device__ __forceinline__ void issue(const_u32_ptr src, int& tie) {
-    asm volatile("" : "+v"(tie));
-    if constexpr (n16) asm volatile("s_load_dwordx16 %0, %1, 0x0" : "=s"(a16) : "s"(src));
-    if constexpr (n8) asm volatile("s_load_dwordx8 %0, %1, %2" : "=s"(a8) : "s"(src), "i"(64 * n16));
-    if constexpr (n4)
-      asm volatile("s_load_dwordx4 %0, %1, %2" : "=s"(a4) : "s"(src), "i"(64 * n16 + 32 * n8));
-    if constexpr (n2)
-      asm volatile("s_load_dwordx2 %0, %1, %2" : "=s"(a2)
-                   : "s"(src), "i"(64 * n16 + 32 * n8 + 16 * n4));
-    if constexpr (n1)
-      asm volatile("s_load_dword %0, %1, %2" : "=s"(a1)
-                   : "s"(src), "i"(64 * n16 + 32 * n8 + 16 * n4 + 8 * n2));
-    asm volatile("" : "+v"(tie));
+  __device__ __forceinline__ void issue(const_u32_ptr src) {
+    if constexpr (n16) a16 = *(const_u32x16_ptr)src;
+    if constexpr (n8) a8 = *(const_u32x8_ptr)(src + 16 * n16);
+    if constexpr (n4) a4 = *(const_u32x4_ptr)(src + 16 * n16 + 8 * n8);
+    if constexpr (n2) a2 = *(const_u32x2_ptr)(src + 16 * n16 + 8 * n8 + 4 * n4);
+    if constexpr (n1) a1 = src[16 * n16 + 8 * n8 + 4 * n4 + 2 * n2];
   }
-  // All outstanding scalar loads have landed after this; every piece is threaded through
-  // an asm statement so that no use can be placed before the wait.
-  __device__ __forceinline__ void wait() {
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    if constexpr (n16) asm volatile("" : "+s"(a16));
-    if constexpr (n8) asm volatile("" : "+s"(a8));
-    if constexpr (n4) asm volatile("" : "+s"(a4));
-    if constexpr (n2) asm volatile("" : "+s"(a2));
-    if constexpr (n1) asm volatile("" : "+s"(a1));
+  // The buffer's first use; `next` (the address of the request that follows) is defined here.
+  __device__ __forceinline__ void landed(const_u32_ptr& next) {
+    if constexpr (n16) asm volatile("" : "+s"(a16), "+s"(next));
+    if constexpr (n8) asm volatile("" : "+s"(a8), "+s"(next));
+    if constexpr (n4) asm volatile("" : "+s"(a4), "+s"(next));
+    if constexpr (n2) asm volatile("" : "+s"(a2), "+s"(next));
+    if constexpr (n1) asm volatile("" : "+s"(a1), "+s"(next));
   }
   template <int J>
   __device__ __forceinline__ uint32_t get() const {

@@ -1,10 +1,15 @@
-"""Static check of compiled ISA for the hand-placed scalar loads.
+"""Static checks of the compiled gfx950 code.
 
-The kernels issue s_load_dwordxN from inline asm and wait for them with a hand-placed
-s_waitcnt lgkmcnt(0); the compiler does not know that the destination SGPRs are in flight in
-between.  This scan walks every kernel linearly and reports any instruction that reads or
-writes an SGPR of an inline-asm scalar load between its issue and the next
-s_waitcnt ... lgkmcnt(0).  (Unconditional branches and s_endpgm end a straight-line run.)
+scan(): a guard for scalar loads written as inline asm.  The compiler does not know that the
+destination SGPRs of such a load are in flight until the next s_waitcnt lgkmcnt(0); the scan
+walks every kernel linearly and reports any instruction that reads or writes an SGPR of an
+inline-asm scalar load between its issue and that wait.  (Unconditional branches and s_endpgm
+end a straight-line run.)  The kernels here fetch their wave-uniform operands with ordinary
+constant-address-space loads, which the compiler tracks itself, so the scan finds no such load
+at all; it stays in the build as a guard against one coming back.
+
+kernel_stats(): spill counts and instruction histograms per kernel, for the code-generation
+checks of the build.
 """
 import re, sys
 

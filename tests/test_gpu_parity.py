@@ -611,8 +611,9 @@ def test_conv_short_k_matrix_core_7x7(N, C, H, W, O, s, p):
 
 def test_conv_weight_rows_are_zero_padded():
     """Packed filter rows are as long as bmx_conv_weight_row_words says: the bits (zero past the
-    data up to a whole register chunk), and for K of 9, 18 or 36 words two more words holding the
-    float K - 2 * popcount(filter) and zeros (also for 25 words)."""
+    data up to a whole register chunk), and for the K the short-K matrix-core kernel takes
+    (9, 18, 25, 27, 36, 49 or 50 words) two more words holding the float K - 2 * popcount(filter)
+    and zeros."""
     rng = np.random.default_rng(3)
     for (O, C, k) in [(3, 64, 3), (2, 256, 3), (2, 130, 5), (4, 1, 1), (5, 100, 3), (3, 40, 5), (3, 130, 3), (3, 70, 5), (2, 20, 7)]:
         w = rng.standard_normal((O, C, k, k)).astype(np.float32)

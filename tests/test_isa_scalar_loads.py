@@ -1,9 +1,10 @@
-"""The hand-placed scalar loads of the kernels, checked in the compiled gfx950 code.
+"""The scanner for hand-placed scalar loads, and the code-generation checks of the build.
 
-The xor/popcount kernels issue s_load_dwordxN from inline asm and wait with a hand-placed
-s_waitcnt lgkmcnt(0).  The compiler does not know that the destination SGPRs are in flight in
-between, so nothing it schedules there may touch them.  The scanner is first shown to catch a
-planted violation in a small listing, then run over the real device code of every source.
+A scalar load written as inline asm is invisible to the compiler between its issue and the
+s_waitcnt that follows: nothing scheduled there may touch its destination SGPRs.  The kernels
+use compiler-tracked constant-address-space loads instead; the scanner guards against a
+hand-placed load coming back.  It is first shown to catch a planted violation in a small
+listing, then run over the real device code of every source (where it must find nothing).
 """
 import os
 import shutil
