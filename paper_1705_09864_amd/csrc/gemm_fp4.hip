@@ -33,6 +33,7 @@
 //     and no split.
 //   - Workgroups are numbered so that tiles sharing rows of B (the large operand: weights) sit
 //     on one XCD and run back to back: workgroup b runs on XCD b % 8.
+#include <algorithm>
 #include <type_traits>
 
 #include "bmx_internal.h"
@@ -54,7 +55,7 @@ struct Fp4Params {
   int M, N, Kw, Kreal;            // Kw data words per row
   int g_base, g_rem;  // groups of four words (256 bits = the K of four MFMAs) per wave: g_base, the first g_rem waves one more
   int tiles_m, tiles_n, tiles_per_xcd;
-  FastDiv div_tiles_m;
+  int band;  // rows of tiles per band of the tile order
   const float* alpha;     // per column n, or null
   const float* thr;       // packed-bit output: per column threshold of the sign decision, or null (0)
   const int32_t* rowsum;  // plane form: sum_k q[m][k]
@@ -148,7 +149,10 @@ __device__ __forceinline__ void issue_segment(const Fp4Params& p, uint4* dst, co
 unsigned long long* fp4_stamps = nullptr;
 namespace {
 #define FP4_STAMP(k) do { if (stamps && lane == 0) stamps[(size_t)(blockIdx.x * (blockDim.x >> 6) + wave) * 8 + (k)] = __builtin_readcyclecounter(); } while (0)
+// (without a split, slots 4 and 5 take the constant 100 MHz counter at the loop's ends: with the shader-clock stamps 1 and 3 that gives the clock the loop ran at)
+#define FP4_REALTIME(k) do { if (!SPLIT && stamps && lane == 0) stamps[(size_t)(blockIdx.x * (blockDim.x >> 6) + wave) * 8 + (k)] = __builtin_amdgcn_s_memrealtime(); } while (0)
 #else
+#define FP4_REALTIME(k) do { } while (0)
 #define FP4_STAMP(k) do { } while (0)
 #endif
 
@@ -174,15 +178,11 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
   constexpr int kStage = NB * 128;           // uint4 per staged segment: NB blocks x 32 rows x 64 bytes
   constexpr int kGroups = TM * TN * 4;       // a wave's accumulators in units of four registers
   constexpr int kCnt = (TM + TN) * 8;        // uint4 holding a wave's 32 (TM + TN) popcounts
-  // LDS per wave: its staging areas (two where that costs no more than the partial tile needs
-  // anyway), overlaid after the main loop by its partial tile + counts
-#ifndef BMX_FP4_AHEAD
-#define BMX_FP4_AHEAD 1
-#endif
-  constexpr int kBufs = (NB <= 4 && BMX_FP4_AHEAD >= 2) ? 2 : 1;
-  constexpr bool kLateSecond = BMX_FP4_AHEAD == 3;  // the second segment is requested once the first has landed
+  // LDS per wave: its staging area, overlaid after the main loop of a split by its partial tile
+  // + counts.  (A second staging area, two segments' loads in flight, bought nothing at any
+  // size: 8192^3 254 against 248 us, the fully connected layers 9.3 against 8.9 us.)
   constexpr int kPart = HALF ? kGroups * 32 : kGroups * 64;  // uint4 holding a wave's partial tile
-  constexpr int kSlot = kBufs * kStage > kPart + kCnt ? kBufs * kStage : kPart + kCnt;
+  constexpr int kSlot = (!SPLIT || kStage > kPart + kCnt) ? kStage : kPart + kCnt;
   const int S = SPLIT ? S_arg : 1;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -195,8 +195,17 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
   const int lin = ((int)(blockIdx.x & 7) * p.tiles_per_xcd + (int)(blockIdx.x >> 3)) * tiles_per_wg + tile_in_wg;
   const bool live = lin < p.tiles_m * p.tiles_n;
   if (!SPLIT && !live) return;  // (no barrier ahead without a split)
-  const int tile_n = live ? (int)fast_div((uint32_t)lin, p.div_tiles_m) : 0;
-  const int tile_m = live ? lin - tile_n * p.tiles_m : 0;
+  // Within an XCD's run the tiles go band by band: a band is `band` rows of tiles high, and
+  // inside it the rows of C run fastest, so the few hundred tiles in flight on an XCD at any time
+  // form a block about as wide as high and share their operand rows through its L2.
+  int tile_m = 0, tile_n = 0;
+  if (live) {
+    const int per_band = p.band * p.tiles_n;
+    const int bnd = lin / per_band, within = lin - bnd * per_band;
+    const int rows = min(p.band, p.tiles_m - bnd * p.band);
+    tile_n = within / rows;
+    tile_m = bnd * p.band + (within - tile_n * rows);
+  }
   const int m0 = tile_m * (32 * TM), n0 = tile_n * (32 * TN);
 
   // ---- this wave's K range in groups of four words.  The first g_rem waves carry one group
@@ -239,11 +248,9 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
 #pragma unroll
   for (int g = 0; g < 2; ++g) rd[g] = (r >> 4) * 64 + (r & 15) * 4 + ((2 * g + h) ^ ((r >> 1) & 3));
 
-  // with two staging areas the first two segments go out together: their latencies overlap
   if (seg_lo < seg_hi) issue_segment<NA, NB, CONV>(p, stage, &voff[0][0], piece[0], piece[1], seg_lo);
-  if (kBufs == 2 && !kLateSecond && seg_lo + 1 < seg_hi)
-    issue_segment<NA, NB, CONV>(p, stage + kStage, &voff[0][0], piece[0], piece[1], seg_lo + 1);
   FP4_STAMP(1);
+  FP4_REALTIME(4);
 
   v16f acc[TM][TN];
 #pragma unroll
@@ -260,15 +267,13 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
 
   for (int seg = seg_lo; seg < seg_hi; ++seg) {
     // the segment's words into registers (the compiler waits for the loads in flight: it tracks
-    // LDS writes of the load unit), then the segment after next is requested into the area
-    // these words came from
-    const int buf = kBufs == 2 ? (seg - seg_lo) & 1 : 0;
-    const uint4* src = stage + buf * kStage;
+    // LDS writes of the load unit), then the next segment is requested into the area these
+    // words came from
     uint4 w[NB][2];
 #pragma unroll
     for (int b = 0; b < NB; ++b)
 #pragma unroll
-      for (int g = 0; g < 2; ++g) w[b][g] = src[b * 128 + rd[g]];
+      for (int g = 0; g < 2; ++g) w[b][g] = stage[b * 128 + rd[g]];
     if (8 * seg + 8 > p.Kw) {  // last segment of a row that ends inside it: words past the row are zero
 #pragma unroll
       for (int g = 0; g < 2; ++g) {
@@ -280,13 +285,15 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
         }
       }
     }
-    asm volatile("" ::: "memory");  // the reads stay above the loads that overwrite their source
+    // The reads have to be complete, not merely issued, before the loads that overwrite their
+    // source are requested: LDS reads wait in the LDS queue behind those of the CU's other waves,
+    // and with that queue long enough a load's data (a few hundred cycles for an L2 hit) can
+    // arrive first.
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #ifdef BMX_FP4_STAMPS
     if (seg == seg_lo) { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); FP4_STAMP(2); }
 #endif
-    if (kBufs == 2 && kLateSecond && seg == seg_lo && seg + 1 < seg_hi)
-      issue_segment<NA, NB, CONV>(p, stage + kStage, &voff[0][0], piece[0], piece[1], seg + 1);
-    if (seg + kBufs < seg_hi) issue_segment<NA, NB, CONV>(p, stage + buf * kStage, &voff[0][0], piece[0], piece[1], seg + kBufs);
+    if (seg + 1 < seg_hi) issue_segment<NA, NB, CONV>(p, stage, &voff[0][0], piece[0], piece[1], seg + 1);
 #pragma unroll
     for (int g = 0; g < 2; ++g) {
       const int kg = 2 * seg + g;
@@ -322,6 +329,7 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
     }
   }
   FP4_STAMP(3);
+  FP4_REALTIME(5);
 
   // per-column constants of this lane (column 32 j + r); CONV: where the pixel's results go
   float aln[TN], thn[TN];
@@ -337,13 +345,15 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
   // ---- epilogue.  Register v of lane (r, h) in block (i, j) is C[32 i + 8 (v / 4) + 4 h + v % 4][32 j + r].
   // tot: the full-K sum of the MFMA results; ra, cb: pc(A row), pc(B column) over the full K
   // (plane form: ra = the row sum of the quantised activations).
-  auto finish = [&](int i, int j, int v, float tot, int ra, int cb, float al, float th) {
+  // inside: the tile lies wholly inside C (wave-uniform), so no element needs its bounds tested
+  auto finish = [&](auto inside_tag, int i, int j, int v, float tot, int ra, int cb, float al, float th) {
+    constexpr bool INSIDE = decltype(inside_tag)::value;
     const int mi = 32 * i + 8 * (v >> 2) + 4 * h + (v & 3);
     const int m = m0 + mi, n = n0 + 32 * j + r;
     const uint32_t idx = CONV ? (pix_img[j] * (uint32_t)p.M + (uint32_t)m) * (uint32_t)p.HoWo + pix_rem[j]
                               : (uint32_t)(m * p.ldc + n);
     if (!XNOR) {
-      if (m < p.M && n < p.N && live) {
+      if (INSIDE || (m < p.M && n < p.N && live)) {
         const int sv = 2 * (int)tot - ra;
         if (p.C_i32) __builtin_nontemporal_store(sv, p.C_i32 + idx);
         if (p.C_f32) __builtin_nontemporal_store((float)sv / p.levels, p.C_f32 + idx);
@@ -357,7 +367,7 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
       const uint64_t mask = __ballot(live && n < p.N && al * dot >= th);
       if (r == 0 && m < p.M && live)
         p.C_bits[(uint32_t)(m * (2 * p.ldc) + (n >> 5))] = h ? (uint32_t)(mask >> 32) : (uint32_t)mask;
-    } else if (m < p.M && n < p.N && live) {
+    } else if (INSIDE || (m < p.M && n < p.N && live)) {
       if (OUT == kOutI32) __builtin_nontemporal_store(p.as_count ? ((int)dot + p.Kreal) >> 1 : (int)dot, p.C_i32 + idx);
       else __builtin_nontemporal_store(al * dot, p.C_f32 + idx);
     }
@@ -371,16 +381,29 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
   }
 
   if (!SPLIT) {
+    // the row terms of every result register first (a shuffle each: fetched one by one between
+    // the stores, each would cost an LDS round trip), then nothing but arithmetic and stores
+    int ra[TM][16];
+    float alm[TM][16];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int mi = 32 * i + 8 * (v >> 2) + 4 * h + (v & 3);
-        const int ra = XNOR ? __shfl(pa[i], mi & 31) : p.rowsum[min(m0 + mi, p.M - 1)];
-        const float alm = (CONV && p.alpha) ? p.alpha[min(m0 + mi, p.M - 1)] : 1.0f;
-#pragma unroll
-        for (int j = 0; j < TN; ++j) finish(i, j, v, acc[i][j][v], ra, pb[j], CONV ? alm : aln[j], thn[j]);
+        ra[i][v] = XNOR ? __shfl(pa[i], mi & 31) : p.rowsum[min(m0 + mi, p.M - 1)];
+        alm[i][v] = (CONV && p.alpha) ? p.alpha[min(m0 + mi, p.M - 1)] : 1.0f;
       }
+    auto store_tile = [&](auto inside_tag) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            finish(inside_tag, i, j, v, acc[i][j][v], ra[i][v], pb[j], CONV ? alm[i][v] : aln[j], thn[j]);
+    };
+    if (m0 + 32 * TM <= p.M && n0 + 32 * TN <= p.N) store_tile(std::true_type{});
+    else store_tile(std::false_type{});
     return;
   }
 
@@ -486,10 +509,10 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
 #pragma unroll
         for (int e = 0; e < 4; ++e) alm[e] = p.alpha[min(m0 + row0 + e, p.M - 1)];
       }
-      finish(i, j, 4 * q, tot.x, ra[0], cb, alm[0], th);
-      finish(i, j, 4 * q + 1, tot.y, ra[1], cb, alm[1], th);
-      finish(i, j, 4 * q + 2, tot.z, ra[2], cb, alm[2], th);
-      finish(i, j, 4 * q + 3, tot.w, ra[3], cb, alm[3], th);
+      finish(std::false_type{}, i, j, 4 * q, tot.x, ra[0], cb, alm[0], th);
+      finish(std::false_type{}, i, j, 4 * q + 1, tot.y, ra[1], cb, alm[1], th);
+      finish(std::false_type{}, i, j, 4 * q + 2, tot.z, ra[2], cb, alm[2], th);
+      finish(std::false_type{}, i, j, 4 * q + 3, tot.w, ra[3], cb, alm[3], th);
     }
   };
   if (S == 8) reduce(std::true_type{});
@@ -505,12 +528,11 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
 int gemm_fp4_half = 0;  // 2 = keep fp32 partials (tests of both forms)
 namespace {
 
-template <int TM, int TN, int PL, bool XNOR, int OUT, bool SPLIT, bool HALF, bool CONV = false>
+template <int TM, int TN, int PL, bool XNOR, int OUT, bool SPLIT, bool HALF, bool CONV>
 hipError_t launch_tile(const Fp4Params& p, int S, int tiles_per_wg, int64_t blocks, hipStream_t s) {
   constexpr int NB = TM * PL + TN, kStage = NB * 128, kGroups = TM * TN * 4, kCnt = (TM + TN) * 8;
-  constexpr int bufs = (NB <= 4 && BMX_FP4_AHEAD >= 2) ? 2 : 1;
   constexpr int part = HALF ? kGroups * 32 : kGroups * 64;
-  constexpr int slot = bufs * kStage > part + kCnt ? bufs * kStage : part + kCnt;
+  constexpr int slot = (!SPLIT || kStage > part + kCnt) ? kStage : part + kCnt;
   const int waves = SPLIT ? S : tiles_per_wg;
   const size_t lds = (size_t)waves * slot * 16;
   auto kern = gemm_fp4_kernel<TM, TN, PL, XNOR, OUT, SPLIT, HALF, CONV>;
@@ -535,6 +557,10 @@ hipError_t launch_tile(const Fp4Params& p, int S, int tiles_per_wg, int64_t bloc
 #endif
   return hipGetLastError();
 }
+
+}  // namespace
+int gemm_fp4_band = 0;  // 0 = automatic (16), else rows of tiles per band of the tile order
+namespace {
 
 template <int PL, bool XNOR, int OUT, bool CONV = false>
 hipError_t launch_split(const Fp4Params& p, int S, int tiles_per_wg, int64_t blocks, hipStream_t s) {
@@ -584,7 +610,7 @@ bool launch_gemm_fp4(const uint64_t* A, int64_t lda_w, int planes, const int32_t
   const int ngroups = (int)ceil_div(p.Kw, 4);
   p.tiles_m = tiles_m;
   p.tiles_n = tiles_n;
-  p.div_tiles_m = make_fast_div((uint32_t)tiles_m);
+  p.band = gemm_fp4_band > 0 ? std::min(gemm_fp4_band, tiles_m) : std::min(16, tiles_m);
   p.alpha = alpha_n;
   p.thr = thr_n;
   p.rowsum = rowsum;
@@ -659,7 +685,7 @@ bool launch_conv_fp4(const uint64_t* Xp, int Nimg, int C, int H, int W, const ui
   const int ngroups = (int)ceil_div(kwords, 4);
   p.tiles_m = tiles_m;
   p.tiles_n = tiles_n;
-  p.div_tiles_m = make_fast_div((uint32_t)tiles_m);
+  p.band = gemm_fp4_band > 0 ? std::min(gemm_fp4_band, tiles_m) : std::min(16, tiles_m);
   p.alpha = alpha;
   p.thr = nullptr;
   p.rowsum = nullptr;

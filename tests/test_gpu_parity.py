@@ -880,6 +880,33 @@ def test_words32_gemm_and_fc(K, layout):
 
 
 # ------------------------------------------------------------------ 64 x 64 per wave FP4 kernel (LDS-staged operands)
+def test_gemm_fp4_chip_filling_problem_exact():
+    """A GEMM large enough to keep every SIMD busy with several waves for many segments
+    (4096 x 4096 x 4096: 4096 tiles of 64 x 64, 8 segments each, no K split), repeated so that
+    the LDS queues stay long: every element against the popcount engine (an independent kernel),
+    96 sampled rows against the oracle.  A wave's staging area is overwritten by the next
+    segment's loads; the kernel has to wait for its LDS reads to complete before it requests them,
+    and under this load a missing wait shows as a few wrong counts."""
+    rng = np.random.default_rng(4096)
+    M = N = K = 4096
+    A = rng.integers(0, 2 ** 63, size=(M, K // 64), dtype=np.int64) * 2 + rng.integers(0, 2, size=(M, K // 64), dtype=np.int64)
+    Bm = rng.integers(0, 2 ** 63, size=(N, K // 64), dtype=np.int64) * 2 + rng.integers(0, 2, size=(N, K // 64), dtype=np.int64)
+    Ad, Bd = dev(A), dev(Bm)
+    with tuned(k7=1):
+        ref = B.xnor_gemm(Ad, Bd, K)
+        assert "gemm_kernel" in B.last_kernel()
+    for band in (0, 3, 1000):                      # tile order: automatic bands, ragged bands, none
+        with tuned(k12=band):
+            for rep in range(6):
+                got = B.xnor_gemm(Ad, Bd, K)
+                assert "gemm_fp4_kernel" in B.last_kernel() and "K split 1," in B.last_kernel()
+                assert torch.equal(got, ref), "band %d repetition %d: %d elements differ" % (
+                    band, rep, int((got != ref).sum()))
+    rows = np.sort(rng.choice(M, size=96, replace=False))
+    want = oracle.xnor_gemm(A[rows].view(np.uint64), Bm.view(np.uint64), K)
+    np.testing.assert_array_equal(ref[torch.from_numpy(rows).cuda()].cpu().numpy(), want)
+
+
 @pytest.mark.parametrize("split,partials", [(0, 0), (1, 0), (2, 0), (3, 0), (5, 0), (8, 0), (8, 2), (3, 2)])
 def test_gemm_fp4_lds_staged_kernel(split, partials):
     """The matrix-core GEMM kernel with 64 x 64 of C per wave, operands staged through LDS by the
