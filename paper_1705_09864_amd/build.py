@@ -53,10 +53,13 @@ def check_scalar_loads():
 
 
 def check_codegen():
-    """Two properties of the generated code that a harmless-looking source change can lose
-    without any test failing, only the clock: no kernel spills vector registers (the 64 x 64
-    matrix-core GEMM tile aside, which parks a dozen loop-invariant values), and the
-    convolution kernel with its filters in LDS reads each MFMA's filter operand with one
+    """Properties of the generated code that a harmless-looking source change can lose without
+    any test failing, only the clock: no kernel spills vector registers (the 64 x 64 tile of the
+    register-operand matrix-core GEMM aside, which parks a dozen loop-invariant values); no
+    kernel touches scratch memory (the same kernel and one convolution form of the popcount
+    GEMM aside: a small array indexed at run time lands there, and every scratch access also
+    waits for all stores issued before it, which cost the K-split GEMM 0.7 us per launch); and
+    the convolution kernel with its filters in LDS reads each MFMA's filter operand with one
     ds_read_b128 (split into dword pairs, the rows meet four ways on the banks)."""
     import re
     try:
@@ -65,6 +68,10 @@ def check_codegen():
         sys.path.insert(0, HERE)
         import isa_check
     for src in SOURCES:
+        for name, nbytes in isa_check.scratch_bytes(device_asm(src)).items():
+            known = "gemm_mfma_kernelILi2ELi2E" in name or "gemm_kernelILi16ELi32ELb0ELb0ELb1E" in name
+            if nbytes and not known:
+                raise RuntimeError("%s: kernel %s uses %d bytes of scratch memory per lane" % (src, name, nbytes))
         for name, (spills, ops) in isa_check.kernel_stats(device_asm(src)).items():
             allowed = 16 if "gemm_mfma_kernelILi2ELi2E" in name else 0
             if spills > allowed:

@@ -55,7 +55,9 @@ struct Fp4Params {
   int M, N, Kw, Kreal;            // Kw data words per row
   int g_base, g_rem;  // groups of four words (256 bits = the K of four MFMAs) per wave: g_base, the first g_rem waves one more
   int tiles_m, tiles_n, tiles_per_xcd;
-  int band;  // rows of tiles per band of the tile order
+  // tile order: bands of `band` rows of tiles (the last band has last_rows), see the kernel
+  int band, per_band, last_band, last_rows;
+  FastDiv div_per_band, div_band, div_last;
   const float* alpha;     // per column n, or null
   const float* thr;       // packed-bit output: per column threshold of the sign decision, or null (0)
   const int32_t* rowsum;  // plane form: sum_k q[m][k]
@@ -178,11 +180,21 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
   constexpr int kStage = NB * 128;           // uint4 per staged segment: NB blocks x 32 rows x 64 bytes
   constexpr int kGroups = TM * TN * 4;       // a wave's accumulators in units of four registers
   constexpr int kCnt = (TM + TN) * 8;        // uint4 holding a wave's 32 (TM + TN) popcounts
-  // LDS per wave: its staging area, overlaid after the main loop of a split by its partial tile
-  // + counts.  (A second staging area, two segments' loads in flight, bought nothing at any
-  // size: 8192^3 254 against 248 us, the fully connected layers 9.3 against 8.9 us.)
+  // LDS per wave: with a split, two staging areas used in turn, overlaid after the main loop by
+  // the wave's partial tile + counts; without one (where LDS would cap the waves per CU), and
+  // for the two-plane form, a single area.  Only one segment's loads are ever in flight.  (Two segments in flight bought nothing
+  // at any size: 8192^3 254 against 248 us, the fully connected layers 9.3 against 8.9 us.)
+  constexpr int kAreas = (SPLIT && NB <= 4) ? 2 : 1;  // (six staged blocks: two areas x eight waves exceed the LDS)
   constexpr int kPart = HALF ? kGroups * 32 : kGroups * 64;  // uint4 holding a wave's partial tile
-  constexpr int kSlot = (!SPLIT || kStage > kPart + kCnt) ? kStage : kPart + kCnt;
+  constexpr int kSlot = (!SPLIT || kAreas * kStage > kPart + kCnt) ? kAreas * kStage : kPart + kCnt;
+  // Everything the wave needs before its first load, named in one statement at the top: the
+  // compiler then fetches the kernel arguments in one batch of scalar loads with one wait instead
+  // of one memory round trip per group of first uses.
+  asm volatile("" ::"s"(p.A), "s"(p.B), "s"(p.lda_bytes), "s"(p.ldb_bytes), "s"(p.M), "s"(p.N), "s"(p.Kw), "s"(p.g_base),
+               "s"(p.g_rem), "s"(p.tiles_m), "s"(p.tiles_n), "s"(p.tiles_per_xcd), "s"(p.band), "s"(p.per_band),
+               "s"(p.last_band), "s"(p.last_rows), "s"(p.div_per_band.mul), "s"(p.div_per_band.sh1),
+               "s"(p.div_per_band.sh2), "s"(p.div_band.mul), "s"(p.div_band.sh1), "s"(p.div_band.sh2),
+               "s"(p.div_last.mul), "s"(p.div_last.sh1), "s"(p.div_last.sh2), "s"(S_arg));
   const int S = SPLIT ? S_arg : 1;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -199,12 +211,11 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
   // inside it the rows of C run fastest, so the few hundred tiles in flight on an XCD at any time
   // form a block about as wide as high and share their operand rows through its L2.
   int tile_m = 0, tile_n = 0;
-  if (live) {
-    const int per_band = p.band * p.tiles_n;
-    const int bnd = lin / per_band, within = lin - bnd * per_band;
-    const int rows = min(p.band, p.tiles_m - bnd * p.band);
-    tile_n = within / rows;
-    tile_m = bnd * p.band + (within - tile_n * rows);
+  if (live) {  // (divisions by multiply-high with constants from the host: this runs before the first load)
+    const int bnd = (int)fast_div((uint32_t)lin, p.div_per_band), within = lin - bnd * p.per_band;
+    const bool last = bnd == p.last_band;
+    tile_n = (int)fast_div((uint32_t)within, last ? p.div_last : p.div_band);
+    tile_m = bnd * p.band + (within - tile_n * (last ? p.last_rows : p.band));
   }
   const int m0 = tile_m * (32 * TM), n0 = tile_n * (32 * TN);
 
@@ -251,6 +262,21 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
   if (seg_lo < seg_hi) issue_segment<NA, NB, CONV>(p, stage, &voff[0][0], piece[0], piece[1], seg_lo);
   FP4_STAMP(1);
   FP4_REALTIME(4);
+  // The epilogue's constants are requested now, behind the first segment: fetched where they are
+  // used, each would put a trip to memory between the main loop and the stores.  Per column of
+  // this lane (column 32 j + r): alpha and the threshold of the sign decision; per row of the
+  // tile, row m0 + l in lane l: the row sum of the plane form, alpha of the convolution form.
+  static_assert(TM == 2, "one lane per row of the tile");
+  // (plain variables, not arrays: indexed by a run-time j in the reduction below, an array is
+  // put into scratch memory, whose every access also waits for the stores issued before it)
+  static_assert(TN == 2, "two column blocks");
+  const int n_c0 = min(n0 + r, p.N - 1), n_c1 = min(n0 + 32 + r, p.N - 1);
+  float aln0 = (XNOR && !CONV && p.alpha) ? p.alpha[n_c0] : 1.0f;
+  float aln1 = (XNOR && !CONV && p.alpha) ? p.alpha[n_c1] : 1.0f;
+  float thn0 = (XNOR && OUT == kOutBits && p.thr) ? p.thr[n_c0] : 0.0f;
+  float thn1 = (XNOR && OUT == kOutBits && p.thr) ? p.thr[n_c1] : 0.0f;
+  const int rowsum_lane = XNOR ? 0 : p.rowsum[min(m0 + lane, p.M - 1)];
+  const float alpha_lane = (CONV && p.alpha) ? p.alpha[min(m0 + lane, p.M - 1)] : 1.0f;
 
   v16f acc[TM][TN];
 #pragma unroll
@@ -267,13 +293,13 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
 
   for (int seg = seg_lo; seg < seg_hi; ++seg) {
     // the segment's words into registers (the compiler waits for the loads in flight: it tracks
-    // LDS writes of the load unit), then the next segment is requested into the area these
-    // words came from
+    // LDS writes of the load unit)
+    const uint4* src = stage + (kAreas == 2 ? ((seg - seg_lo) & 1) * kStage : 0);
     uint4 w[NB][2];
 #pragma unroll
     for (int b = 0; b < NB; ++b)
 #pragma unroll
-      for (int g = 0; g < 2; ++g) w[b][g] = stage[b * 128 + rd[g]];
+      for (int g = 0; g < 2; ++g) w[b][g] = src[b * 128 + rd[g]];
     if (8 * seg + 8 > p.Kw) {  // last segment of a row that ends inside it: words past the row are zero
 #pragma unroll
       for (int g = 0; g < 2; ++g) {
@@ -285,15 +311,20 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
         }
       }
     }
-    // The reads have to be complete, not merely issued, before the loads that overwrite their
-    // source are requested: LDS reads wait in the LDS queue behind those of the CU's other waves,
-    // and with that queue long enough a load's data (a few hundred cycles for an L2 hit) can
-    // arrive first.
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    // The next segment is requested before this one is multiplied.  Its loads must not land on
+    // words that are still to be read, and a read that has merely been issued may still wait in
+    // the LDS queue behind those of the CU's other waves when the data arrives (a few hundred
+    // cycles for an L2 hit; seen as a few wrong counts in a chip-filling GEMM).  With two areas
+    // the loads go to the other one, whose last reads were consumed by the MFMAs of the previous
+    // segment; with one area the reads are waited for first.
+    if (kAreas == 1) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    else asm volatile("" ::: "memory");
 #ifdef BMX_FP4_STAMPS
     if (seg == seg_lo) { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); FP4_STAMP(2); }
 #endif
-    if (seg + 1 < seg_hi) issue_segment<NA, NB, CONV>(p, stage, &voff[0][0], piece[0], piece[1], seg + 1);
+    if (seg + 1 < seg_hi)
+      issue_segment<NA, NB, CONV>(p, stage + (kAreas == 2 ? ((seg + 1 - seg_lo) & 1) * kStage : 0), &voff[0][0], piece[0],
+                                  piece[1], seg + 1);
 #pragma unroll
     for (int g = 0; g < 2; ++g) {
       const int kg = 2 * seg + g;
@@ -330,15 +361,19 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
   }
   FP4_STAMP(3);
   FP4_REALTIME(5);
+  // The constants requested before the loop are taken in here, in one place: met for the first
+  // time in the branches of the epilogue, each would get a wait of its own there, and such a
+  // wait also sits out every store issued before it.
+  asm volatile("" : "+v"(aln0), "+v"(aln1), "+v"(thn0), "+v"(thn1));
+  int rowsum_l = rowsum_lane;
+  float alpha_l = alpha_lane;
+  asm volatile("" : "+v"(rowsum_l), "+v"(alpha_l));
 
-  // per-column constants of this lane (column 32 j + r); CONV: where the pixel's results go
-  float aln[TN], thn[TN];
+  // CONV: where this lane's pixels' results go
   uint32_t pix_img[TN], pix_rem[TN];
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
     const int n = min(n0 + 32 * j + r, p.N - 1);
-    aln[j] = (XNOR && !CONV && p.alpha) ? p.alpha[n] : 1.0f;
-    thn[j] = (XNOR && OUT == kOutBits && p.thr) ? p.thr[n] : 0.0f;
     pix_img[j] = CONV ? fast_div((uint32_t)n, p.div_howo) : 0u;
     pix_rem[j] = CONV ? (uint32_t)n - pix_img[j] * (uint32_t)p.HoWo : 0u;
   }
@@ -390,8 +425,8 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int mi = 32 * i + 8 * (v >> 2) + 4 * h + (v & 3);
-        ra[i][v] = XNOR ? __shfl(pa[i], mi & 31) : p.rowsum[min(m0 + mi, p.M - 1)];
-        alm[i][v] = (CONV && p.alpha) ? p.alpha[min(m0 + mi, p.M - 1)] : 1.0f;
+        ra[i][v] = XNOR ? __shfl(pa[i], mi & 31) : __shfl(rowsum_l, mi);
+        alm[i][v] = CONV ? __shfl(alpha_l, mi) : 1.0f;
       }
     auto store_tile = [&](auto inside_tag) {
 #pragma unroll
@@ -400,7 +435,7 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
         for (int v = 0; v < 16; ++v)
 #pragma unroll
           for (int j = 0; j < TN; ++j)
-            finish(inside_tag, i, j, v, acc[i][j][v], ra[i][v], pb[j], CONV ? alm[i][v] : aln[j], thn[j]);
+            finish(inside_tag, i, j, v, acc[i][j][v], ra[i][v], pb[j], CONV ? alm[i][v] : (j ? aln1 : aln0), j ? thn1 : thn0);
     };
     if (m0 + 32 * TM <= p.M && n0 + 32 * TN <= p.N) store_tile(std::true_type{});
     else store_tile(std::false_type{});
@@ -443,7 +478,7 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
     // full-K popcounts: lane l sums row l of the tile (TM = 2: 64 rows) and column l over the S
     // waves' counts, one conflict-free read each; a lane then picks the rows and the column of
     // its own results out of other lanes' registers
-    int pa_tot = 0, pb_tot = 0;
+    int pa_tot = rowsum_l, pb_tot = 0;  // (plane form: the row sum stands where the row count would)
     if (XNOR) {
       static_assert(TM == 2 && TN == 2, "one lane per row and per column of the tile");
       int ca[8], cb8[8];
@@ -495,19 +530,14 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
       if (g == wave) { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); FP4_STAMP(7); }
 #endif
       int ra[4], cb = 0;
-      if (XNOR) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) ra[e] = __shfl(pa_tot, row0 + e);
-        cb = __shfl(pb_tot, 32 * j + r);
-      } else {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) ra[e] = p.rowsum[min(m0 + row0 + e, p.M - 1)];
-      }
-      const float al = j == 0 ? aln[0] : aln[TN - 1], th = j == 0 ? thn[0] : thn[TN - 1];
+      for (int e = 0; e < 4; ++e) ra[e] = __shfl(pa_tot, row0 + e);
+      if (XNOR) cb = __shfl(pb_tot, 32 * j + r);
+      const float al = j == 0 ? aln0 : aln1, th = j == 0 ? thn0 : thn1;
       float alm[4] = {al, al, al, al};
-      if (CONV && p.alpha) {
+      if (CONV) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) alm[e] = p.alpha[min(m0 + row0 + e, p.M - 1)];
+        for (int e = 0; e < 4; ++e) alm[e] = __shfl(alpha_l, row0 + e);
       }
       finish(std::false_type{}, i, j, 4 * q, tot.x, ra[0], cb, alm[0], th);
       finish(std::false_type{}, i, j, 4 * q + 1, tot.y, ra[1], cb, alm[1], th);
@@ -532,7 +562,8 @@ template <int TM, int TN, int PL, bool XNOR, int OUT, bool SPLIT, bool HALF, boo
 hipError_t launch_tile(const Fp4Params& p, int S, int tiles_per_wg, int64_t blocks, hipStream_t s) {
   constexpr int NB = TM * PL + TN, kStage = NB * 128, kGroups = TM * TN * 4, kCnt = (TM + TN) * 8;
   constexpr int part = HALF ? kGroups * 32 : kGroups * 64;
-  constexpr int slot = (!SPLIT || kStage > part + kCnt) ? kStage : part + kCnt;
+  constexpr int areas = (SPLIT && NB <= 4) ? 2 : 1;
+  constexpr int slot = (!SPLIT || areas * kStage > part + kCnt) ? areas * kStage : part + kCnt;
   const int waves = SPLIT ? S : tiles_per_wg;
   const size_t lds = (size_t)waves * slot * 16;
   auto kern = gemm_fp4_kernel<TM, TN, PL, XNOR, OUT, SPLIT, HALF, CONV>;
@@ -561,6 +592,16 @@ hipError_t launch_tile(const Fp4Params& p, int S, int tiles_per_wg, int64_t bloc
 }  // namespace
 int gemm_fp4_band = 0;  // 0 = automatic (16), else rows of tiles per band of the tile order
 namespace {
+
+void set_tile_order(Fp4Params& p) {
+  p.band = gemm_fp4_band > 0 ? std::min(gemm_fp4_band, p.tiles_m) : std::min(16, p.tiles_m);
+  p.per_band = p.band * p.tiles_n;
+  p.last_band = (p.tiles_m - 1) / p.band;
+  p.last_rows = p.tiles_m - p.last_band * p.band;
+  p.div_per_band = make_fast_div((uint32_t)p.per_band);
+  p.div_band = make_fast_div((uint32_t)p.band);
+  p.div_last = make_fast_div((uint32_t)p.last_rows);
+}
 
 template <int PL, bool XNOR, int OUT, bool CONV = false>
 hipError_t launch_split(const Fp4Params& p, int S, int tiles_per_wg, int64_t blocks, hipStream_t s) {
@@ -610,7 +651,7 @@ bool launch_gemm_fp4(const uint64_t* A, int64_t lda_w, int planes, const int32_t
   const int ngroups = (int)ceil_div(p.Kw, 4);
   p.tiles_m = tiles_m;
   p.tiles_n = tiles_n;
-  p.band = gemm_fp4_band > 0 ? std::min(gemm_fp4_band, tiles_m) : std::min(16, tiles_m);
+  set_tile_order(p);
   p.alpha = alpha_n;
   p.thr = thr_n;
   p.rowsum = rowsum;
@@ -685,7 +726,7 @@ bool launch_conv_fp4(const uint64_t* Xp, int Nimg, int C, int H, int W, const ui
   const int ngroups = (int)ceil_div(kwords, 4);
   p.tiles_m = tiles_m;
   p.tiles_n = tiles_n;
-  p.band = gemm_fp4_band > 0 ? std::min(gemm_fp4_band, tiles_m) : std::min(16, tiles_m);
+  set_tile_order(p);
   p.alpha = alpha;
   p.thr = nullptr;
   p.rowsum = nullptr;

@@ -111,3 +111,16 @@ def kernel_stats(path):
         if m and cur_meta:
             spills[cur_meta] = int(m.group(1))
     return {k: (spills.get(k, 0), v) for k, v in body.items() if k in spills}
+
+
+def scratch_bytes(path):
+    """Per kernel of a device listing: bytes of private (scratch) memory per lane, from the
+    metadata.  Returns {mangled name: bytes}."""
+    out = {}
+    text = open(path).read()
+    for block in text.split("  - .agpr_count:")[1:]:
+        n = re.search(r"\.name:\s+(\S+)", block)
+        v = re.search(r"\.private_segment_fixed_size:\s+(\d+)", block)
+        if n and v:
+            out[n.group(1)] = int(v.group(1))
+    return out
