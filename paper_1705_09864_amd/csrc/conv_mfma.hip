@@ -48,6 +48,7 @@ struct WsParams {
   int P;  // N * Ho * Wo
   int O, HoWo, Wo, Hp, Wpp, Cw, stride;
   int nblocks, nchunks;  // blocks of 32 pixels in all; waves they are dealt out to (evenly)
+  int blk_q, blk_r;      // nblocks / nchunks and nblocks % nchunks
   FastDiv div_howo, div_wo;
   int off[kMaxWsWords];  // word offset of K-word j relative to the pixel base
 };
@@ -73,7 +74,7 @@ struct PixelBlock {
   const uint64_t* xb;  // base of the pixel's patch (tap (0, 0), channel word 0)
   int64_t obase;       // element index of (image, filter 0, pixel)
   int64_t bword;       // packed-bit output: index of the pixel's first word
-  bool valid;
+  int valid;
 };
 
 __device__ __forceinline__ PixelBlock locate(const WsParams& p, int b, int r) {
@@ -104,12 +105,25 @@ struct Lds {
   static constexpr int kFilterStride = 8 * KW + 4;  // dwords
 };
 
+#ifdef BMX_WS_STAMPS
+// Profiling builds only: per-wave shader-clock stamps at the phase boundaries of the kernel.
+}  // namespace
+unsigned long long* ws_stamps = nullptr;
+namespace {
+#define WS_STAMP(k) do { if (stamps && lane == 0) stamps[(size_t)((blockIdx.y * gridDim.x + blockIdx.x) * 4 + wave) * 8 + (k)] = __builtin_readcyclecounter(); } while (0)
+#define WS_STAMP_ARG , unsigned long long* stamps
+#else
+#define WS_STAMP(k) do { } while (0)
+#define WS_STAMP_ARG
+#endif
+
 // WPS: waves per SIMD the register allocation is held to.
 // BITS: the result leaves as packed sign bits (see WsParams::out_bits); the workgroups also
 // write the constant halo words of the output image.
+
 template <int KW, int TM, int WPS, bool BITS>
 __global__ void __launch_bounds__(256, WPS)
-conv_mfma_ws_kernel(const WsParams p) {
+conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
   constexpr int NI = (KW + 1) / 2;  // load instructions per block: two words per pixel each
   constexpr int FS = Lds<KW>::kFilterStride;
   __shared__ __attribute__((aligned(16))) uint32_t filt[32 * TM * FS];
@@ -118,10 +132,12 @@ conv_mfma_ws_kernel(const WsParams p) {
   const int r = lane & 31, h = lane >> 5;
   const int m0 = blockIdx.y * (32 * TM);
   const int chunk = blockIdx.x * 4 + wave;
-  // chunk c takes blocks [c * nblocks / nchunks, (c + 1) * nblocks / nchunks)
+  // the blocks are dealt out evenly: chunk c takes blk_q of them, the first blk_r chunks one more
+  // (no division here: this runs before the wave's first load)
   const int cc = min(chunk, p.nchunks);
-  const int b0 = (int)(((int64_t)cc * p.nblocks) / p.nchunks);
-  const int b1 = (int)(((int64_t)min(cc + 1, p.nchunks) * p.nblocks) / p.nchunks);
+  const int b0 = cc * p.blk_q + min(cc, p.blk_r);
+  const int b1 = cc < p.nchunks ? b0 + p.blk_q + (cc < p.blk_r ? 1 : 0) : b0;
+  WS_STAMP(0);
 
   // words 2i + h of the pixel's patch, i = 0 .. NI-1 (the odd KW's last one only for h = 0)
   auto fetch = [&](const PixelBlock& pb, uint64_t (&st)[NI]) {
@@ -147,6 +163,7 @@ conv_mfma_ws_kernel(const WsParams p) {
   PixelBlock cur = locate(p, b0 < b1 ? b0 : 0, r);
   uint64_t st[NI];
   fetch(cur, st);
+  WS_STAMP(1);
 
   // (behind the first fetch, so that its index arithmetic runs under the loads)
   if (BITS && p.opad > 0 && (m0 & 63) == 0) {
@@ -213,16 +230,19 @@ conv_mfma_ws_kernel(const WsParams p) {
       if (BITS) filt[(int)threadIdx.x * FS + 8 * KW + 2] = __float_as_uint(mythr);
     }
   }
+  WS_STAMP(2);
   __syncthreads();
+  WS_STAMP(3);
   if (b0 >= b1) return;
 
   // ---- blocks of 32 output pixels
   for (int b = b0; b < b1; ++b) {
     uint32_t raw[KW];
     transpose(st, raw);
-    // the next block's words are requested before this block is multiplied
+    // the next block's words are requested before this block is multiplied (after the wave's
+    // last block there is nothing to request)
     const PixelBlock nxt = locate(p, min(b + 1, b1 - 1), r);
-    fetch(nxt, st);
+    if (b + 1 < b1) fetch(nxt, st);
     // (the filter reads below are the same in every trip: an opaque copy of their base keeps
     // the compiler from hoisting all of them out of the loop and into registers for good)
     // (counted in 16-byte pieces from the aligned base, so that the read is one ds_read_b128:
@@ -230,24 +250,54 @@ conv_mfma_ws_kernel(const WsParams p) {
     int fbase = r * (FS / 4) + h;
     asm volatile("" : "+v"(fbase));
     int pb = 0;
-    v16f acc[TM];
+    // Two accumulator chains per filter block, steps alternating between them and added at the
+    // end: an MFMA that adds onto the result of the one before it can only start when that one
+    // has finished, twice the time it takes to issue.  The filter operands are read a group of
+    // steps ahead: read where they are used, every pair of MFMAs would wait out an LDS round trip.
+    constexpr int G = KW > 36 ? 2 : 4, NG = (KW + G - 1) / G;  // (two steps ahead where registers are short)
+    v16f acc[TM][2];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][e] = 0.0f;
+      for (int c = 0; c < 2; ++c)
 #pragma unroll
-    for (int j = 0; j < KW; ++j) {
-      pb += __builtin_popcount(raw[j]);
-      const v8i eb = widen(expand4(raw[j]));
+        for (int e = 0; e < 16; ++e) acc[i][c][e] = 0.0f;
+    v4i abuf[2][G][TM];
+    auto load_group = [&](int g, v4i (&dst)[G][TM]) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i) {
-        const v4i a = ((const v4i_alias*)filt)[fbase + 8 * i * FS + 2 * j];
-        acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(a), eb, acc[i], 4, 4, 0, 128, 0, 128);
+      for (int t = 0; t < G; ++t)
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+          if (g * G + t < KW) dst[t][i] = ((const v4i_alias*)filt)[fbase + 8 * i * FS + 2 * (g * G + t)];
+    };
+    load_group(0, abuf[0]);
+#pragma unroll
+#ifdef BMX_WS_SKIP_MFMA
+    for (int g = 0; g < 1; ++g) {
+#else
+    for (int g = 0; g < NG; ++g) {
+#endif
+      if (g + 1 < NG) load_group(g + 1, abuf[(g + 1) & 1]);
+#pragma unroll
+      for (int t = 0; t < G; ++t) {
+        const int j = g * G + t;
+        if (j < KW) {
+          pb += __builtin_popcount(raw[j]);
+          const v8i eb = widen(expand4(raw[j]));
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+            acc[i][j & 1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(abuf[g & 1][t][i]), eb, acc[i][j & 1], 4, 4,
+                                                                           0, 128, 0, 128);
+        }
       }
-      // keep the operands of step j + 4 and later behind this MFMA: gathered at the top of the
-      // block (the scheduler's preference) they would hold 8 * KW registers at once
-      if (j % 4 == 3) __builtin_amdgcn_sched_barrier(0);
+      // keep the operands of the groups that follow behind these MFMAs: gathered at the top of
+      // the block (the scheduler's preference) they would hold 8 * KW registers at once
+      __builtin_amdgcn_sched_barrier(0);
     }
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][0][e] += acc[i][1][e];  // exact: whole numbers below 2^24
     pb += __shfl_xor(pb, 32);
     // out = alpha * (K - 2 pc(filter) - 2 pc(patch) + 4 * sum): exact integers in fp32 up to
     // the single rounding of the alpha product.  (The row constants of all result registers
@@ -271,7 +321,7 @@ conv_mfma_ws_kernel(const WsParams p) {
         for (int v = 0; v < 16; ++v) {
           const int mi = 8 * (v / 4) + 4 * h + (v % 4);
           const float th = __uint_as_float(filt[(32 * i + mi) * FS + 8 * KW + 2]);
-          const float t = fmaf(4.0f, acc[i][v], c0[v]) - pb2;
+          const float t = fmaf(4.0f, acc[i][0][v], c0[v]) - pb2;
           if (al[v] * t >= th && m0 + 32 * i + mi < p.O) mask |= 1u << mi;
         }
         mask |= (uint32_t)__shfl_xor((int)mask, 32);
@@ -285,20 +335,29 @@ conv_mfma_ws_kernel(const WsParams p) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int m = m0 + 32 * i + 8 * (v / 4) + 4 * h + (v % 4);
-          const float t = fmaf(4.0f, acc[i][v], c0[v]) - pb2;
+          const float t = fmaf(4.0f, acc[i][0][v], c0[v]) - pb2;
           if (cur.valid && m < p.O) __builtin_nontemporal_store((int)t, p.out_i32 + cur.obase + (int64_t)m * p.HoWo);
         }
       } else {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int m = m0 + 32 * i + 8 * (v / 4) + 4 * h + (v % 4);
-          const float t = fmaf(4.0f, acc[i][v], c0[v]) - pb2;
+          const float t = fmaf(4.0f, acc[i][0][v], c0[v]) - pb2;
+#ifdef BMX_WS_SKIP_STORES
+          if (cur.valid && m < p.O && t == 1.2345e30f) __builtin_nontemporal_store(al[v] * t, p.out_f32 + cur.obase + (int64_t)m * p.HoWo);
+#else
           if (cur.valid && m < p.O) __builtin_nontemporal_store(al[v] * t, p.out_f32 + cur.obase + (int64_t)m * p.HoWo);
+#endif
         }
       }
     }
     cur = nxt;
   }
+  WS_STAMP(6);
+#ifdef BMX_WS_STAMPS
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  WS_STAMP(7);
+#endif
 }
 
 template <int KW, int TM, int WPS, bool BITS = false>
@@ -306,8 +365,13 @@ void launch_ws(const WsParams& p, int m_tiles, hipStream_t s) {
   const int chunks = p.nchunks;
   note_kernel("conv_mfma_ws_kernel<%d,%d,%d,%s> grid %d x %d x 256", KW, TM, WPS, BITS ? "true" : "false",
               (int)ceil_div(chunks, 4), m_tiles);
+#ifdef BMX_WS_STAMPS
+  hipLaunchKernelGGL((conv_mfma_ws_kernel<KW, TM, WPS, BITS>), dim3((unsigned)ceil_div(chunks, 4), (unsigned)m_tiles),
+                     dim3(256), 0, s, p, ws_stamps);
+#else
   hipLaunchKernelGGL((conv_mfma_ws_kernel<KW, TM, WPS, BITS>), dim3((unsigned)ceil_div(chunks, 4), (unsigned)m_tiles),
                      dim3(256), 0, s, p);
+#endif
 }
 
 }  // namespace
@@ -373,32 +437,34 @@ bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, cons
   // for measurements only: it lost to 32 everywhere, 8.0 against 7.2 us on 16 x 64 x 56 x 56)
   const int TM = (kwords == 9 && O > 32 && gemm_mfma_tile == 2 && !out_bits) ? 2 : 1;
   const int m_tiles = (int)ceil_div(O, 32 * TM);
-  // Waves: one per block while all of them are resident at once (4, 3 and 2 workgroups per CU
-  // for 9, 18 and 36 words); beyond that, as many waves as are resident in one round,
-  // the blocks dealt out evenly: every workgroup copies its filters once
-  // and no CU is left with a second round of a few workgroups (configuration 4: 11.5 -> 10.8 us,
-  // 64 x 128 x 28 x 28: 12.2 -> 10.1 us).
-  const int resident_waves = 256 * 4 * (kwords == 9 ? 4 : kwords >= 36 ? 2 : 3);
+  // Waves: one per block while all of them are resident at once (3 workgroups per CU for 9 and
+  // 18 words, 2 beyond: what the registers of two accumulator chains and the filter operands
+  // read ahead allow); beyond that, as many waves as are resident in one round, the blocks dealt
+  // out evenly: every workgroup copies its filters once and no CU is left with a second round of
+  // a few workgroups.
+  const int resident_waves = 256 * 4 * (kwords <= 18 ? 3 : 2);
   p.nchunks = (int)std::min<int64_t>(p.nblocks, std::max(1, resident_waves / m_tiles));
   if (conv_filters_per_wave >= 100) p.nchunks = std::min(p.nblocks, conv_filters_per_wave);  // (tuning hook reused: chunks)
   else if (conv_filters_per_wave > 0) p.nchunks = (int)ceil_div(p.nblocks, conv_filters_per_wave);  // (or blocks per wave)
+  p.blk_q = p.nblocks / p.nchunks;
+  p.blk_r = p.nblocks % p.nchunks;
   if (out_bits) {
-    if (kwords == 9) launch_ws<9, 1, 4, true>(p, m_tiles, s);
+    if (kwords == 9) launch_ws<9, 1, 3, true>(p, m_tiles, s);
     else if (kwords == 18) launch_ws<18, 1, 3, true>(p, m_tiles, s);
-    else if (kwords == 25) launch_ws<25, 1, 3, true>(p, m_tiles, s);
-    else if (kwords == 27) launch_ws<27, 1, 3, true>(p, m_tiles, s);
+    else if (kwords == 25) launch_ws<25, 1, 2, true>(p, m_tiles, s);
+    else if (kwords == 27) launch_ws<27, 1, 2, true>(p, m_tiles, s);
     else if (kwords == 49) launch_ws<49, 1, 2, true>(p, m_tiles, s);
     else if (kwords == 50) launch_ws<50, 1, 2, true>(p, m_tiles, s);
     else launch_ws<36, 1, 2, true>(p, m_tiles, s);
   } else if (kwords == 9) {
     if (TM == 2) launch_ws<9, 2, 2>(p, m_tiles, s);
-    else launch_ws<9, 1, 4>(p, m_tiles, s);
+    else launch_ws<9, 1, 3>(p, m_tiles, s);
   } else if (kwords == 18) {
     launch_ws<18, 1, 3>(p, m_tiles, s);
   } else if (kwords == 25) {
-    launch_ws<25, 1, 3>(p, m_tiles, s);
+    launch_ws<25, 1, 2>(p, m_tiles, s);
   } else if (kwords == 27) {
-    launch_ws<27, 1, 3>(p, m_tiles, s);
+    launch_ws<27, 1, 2>(p, m_tiles, s);
   } else if (kwords == 49) {
     launch_ws<49, 1, 2>(p, m_tiles, s);
   } else if (kwords == 50) {

@@ -56,6 +56,7 @@ struct Fp4Params {
   int g_base, g_rem;  // groups of four words (256 bits = the K of four MFMAs) per wave: g_base, the first g_rem waves one more
   int tiles_m, tiles_n, tiles_per_xcd;
   // tile order: bands of `band` rows of tiles (the last band has last_rows), see the kernel
+  int two_areas;  // a second staging area per wave lies behind the waves' first ones
   int band, per_band, last_band, last_rows;
   FastDiv div_per_band, div_band, div_last;
   const float* alpha;     // per column n, or null
@@ -180,13 +181,13 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
   constexpr int kStage = NB * 128;           // uint4 per staged segment: NB blocks x 32 rows x 64 bytes
   constexpr int kGroups = TM * TN * 4;       // a wave's accumulators in units of four registers
   constexpr int kCnt = (TM + TN) * 8;        // uint4 holding a wave's 32 (TM + TN) popcounts
-  // LDS per wave: with a split, two staging areas used in turn, overlaid after the main loop by
-  // the wave's partial tile + counts; without one (where LDS would cap the waves per CU), and
-  // for the two-plane form, a single area.  Only one segment's loads are ever in flight.  (Two segments in flight bought nothing
-  // at any size: 8192^3 254 against 248 us, the fully connected layers 9.3 against 8.9 us.)
-  constexpr int kAreas = (SPLIT && NB <= 4) ? 2 : 1;  // (six staged blocks: two areas x eight waves exceed the LDS)
+  // LDS: per wave a staging area, overlaid after the main loop of a split by the wave's partial
+  // tile + counts; behind those, where the launcher found room for it without giving up waves
+  // per CU (p.two_areas), a second staging area per wave, used in turn with the first.  Only one
+  // segment's loads are ever in flight.  (Two segments in flight bought nothing at any size:
+  // 8192^3 254 against 248 us, the fully connected layers 9.3 against 8.9 us.)
   constexpr int kPart = HALF ? kGroups * 32 : kGroups * 64;  // uint4 holding a wave's partial tile
-  constexpr int kSlot = (!SPLIT || kAreas * kStage > kPart + kCnt) ? kAreas * kStage : kPart + kCnt;
+  constexpr int kSlot = (!SPLIT || kStage > kPart + kCnt) ? kStage : kPart + kCnt;
   // Everything the wave needs before its first load, named in one statement at the top: the
   // compiler then fetches the kernel arguments in one batch of scalar loads with one wait instead
   // of one memory round trip per group of first uses.
@@ -228,6 +229,8 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
   // ---- loader: lane i of load t of a block fetches, for local row 16 t + i / 4, the piece
   // (i % 4) xor ((row >> 1) & 3) of the segment; voff = byte offset of that piece in segment 0.
   uint4* const stage = lds + wave * kSlot;
+  const bool two = p.two_areas != 0;
+  uint4* const stage2 = two ? lds + (int)(blockDim.x >> 6) * kSlot + wave * kStage : stage;
   int piece[2];
   uint32_t voff[NB][2];
 #pragma unroll
@@ -294,7 +297,7 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
   for (int seg = seg_lo; seg < seg_hi; ++seg) {
     // the segment's words into registers (the compiler waits for the loads in flight: it tracks
     // LDS writes of the load unit)
-    const uint4* src = stage + (kAreas == 2 ? ((seg - seg_lo) & 1) * kStage : 0);
+    const uint4* src = ((seg - seg_lo) & 1) ? stage2 : stage;
     uint4 w[NB][2];
 #pragma unroll
     for (int b = 0; b < NB; ++b)
@@ -317,14 +320,13 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
     // cycles for an L2 hit; seen as a few wrong counts in a chip-filling GEMM).  With two areas
     // the loads go to the other one, whose last reads were consumed by the MFMAs of the previous
     // segment; with one area the reads are waited for first.
-    if (kAreas == 1) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if (!two) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     else asm volatile("" ::: "memory");
 #ifdef BMX_FP4_STAMPS
     if (seg == seg_lo) { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); FP4_STAMP(2); }
 #endif
     if (seg + 1 < seg_hi)
-      issue_segment<NA, NB, CONV>(p, stage + (kAreas == 2 ? ((seg + 1 - seg_lo) & 1) * kStage : 0), &voff[0][0], piece[0],
-                                  piece[1], seg + 1);
+      issue_segment<NA, NB, CONV>(p, ((seg + 1 - seg_lo) & 1) ? stage2 : stage, &voff[0][0], piece[0], piece[1], seg + 1);
 #pragma unroll
     for (int g = 0; g < 2; ++g) {
       const int kg = 2 * seg + g;
@@ -559,13 +561,19 @@ int gemm_fp4_half = 0;  // 2 = keep fp32 partials (tests of both forms)
 namespace {
 
 template <int TM, int TN, int PL, bool XNOR, int OUT, bool SPLIT, bool HALF, bool CONV>
-hipError_t launch_tile(const Fp4Params& p, int S, int tiles_per_wg, int64_t blocks, hipStream_t s) {
+hipError_t launch_tile(const Fp4Params& p_in, int S, int tiles_per_wg, int64_t blocks, hipStream_t s) {
   constexpr int NB = TM * PL + TN, kStage = NB * 128, kGroups = TM * TN * 4, kCnt = (TM + TN) * 8;
   constexpr int part = HALF ? kGroups * 32 : kGroups * 64;
-  constexpr int areas = (SPLIT && NB <= 4) ? 2 : 1;
-  constexpr int slot = (!SPLIT || areas * kStage > part + kCnt) ? areas * kStage : part + kCnt;
+  constexpr int slot = (!SPLIT || kStage > part + kCnt) ? kStage : part + kCnt;
   const int waves = SPLIT ? S : tiles_per_wg;
-  const size_t lds = (size_t)waves * slot * 16;
+  // A second staging area per wave where it costs no workgroup per CU: the registers allow 12
+  // waves per CU, the 160 KB of LDS as many workgroups as fit.
+  Fp4Params p = p_in;
+  const int by_regs = std::max(1, 12 / waves);
+  const int wgs_one = std::min<int>(by_regs, (160 * 1024) / (waves * slot * 16));
+  const int wgs_two = std::min<int>(by_regs, (160 * 1024) / (waves * (slot + kStage) * 16));
+  p.two_areas = (SPLIT && wgs_two >= 1 && wgs_two == wgs_one && gemm_fp4_areas != 1) ? 1 : 0;
+  const size_t lds = (size_t)waves * (slot + (p.two_areas ? kStage : 0)) * 16;
   auto kern = gemm_fp4_kernel<TM, TN, PL, XNOR, OUT, SPLIT, HALF, CONV>;
   if (lds > 64 * 1024) {  // more than the default limit of dynamic LDS: raised once per device
     static bool raised[64] = {};
@@ -591,6 +599,7 @@ hipError_t launch_tile(const Fp4Params& p, int S, int tiles_per_wg, int64_t bloc
 
 }  // namespace
 int gemm_fp4_band = 0;  // 0 = automatic (16), else rows of tiles per band of the tile order
+int gemm_fp4_areas = 0;  // 1 = never a second staging area (tests of both forms)
 namespace {
 
 void set_tile_order(Fp4Params& p) {
