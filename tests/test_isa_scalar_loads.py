@@ -66,9 +66,9 @@ def test_compiled_kernels_have_no_inflight_hazard():
 @pytest.mark.skipif(shutil.which(hip_build.HIPCC) is None and not os.path.exists(hip_build.HIPCC),
                     reason="hipcc not available")
 def test_compiled_kernels_keep_registers_and_wide_lds_reads():
-    """No vector-register spills, and one 16-byte LDS read per MFMA filter operand in the
+    """No vector-register spills, no scratch memory, and one 16-byte LDS read per MFMA filter operand in the
     short-K convolution kernel (see build.check_codegen)."""
     hip_build.check_scalar_loads()   # makes sure the device listings exist
     hip_build.check_codegen()
     stats = isa_check.kernel_stats(hip_build.device_asm("conv_mfma.hip"))
-    assert any("conv_mfma_ws_kernelILi9ELi1ELi4ELb0" in k for k in stats)
+    assert any("conv_mfma_ws_kernelILi9ELi1ELi3ELb0" in k for k in stats)
