@@ -142,7 +142,7 @@ bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, cons
                          int KH, int KW, int stride, int pad, const float* alpha, int32_t* out_i32,
                          float* out_f32, uint64_t* out_bits, const float* thr, int out_pad, hipStream_t s,
                          hipError_t* err);
-extern int gemm_engine, gemm_mfma_ksplit, gemm_mfma_tile, conv_filters_per_wave, conv_path;
+extern int gemm_engine, gemm_mfma_ksplit, gemm_mfma_tile, conv_filters_per_wave, conv_path, conv_ws_x4;
 // S = 2*sum_p 2^p pc(plane_p & wb) - rowsum; out_f32 = float(S) / float(2^bits - 1).
 // planes_rows as written by launch_quant_pack (lda_dw dwords per row, chunk padded).
 hipError_t launch_plane_gemm(const uint32_t* planes_rows, int64_t lda_dw, int bits,

@@ -5,17 +5,20 @@
 //
 // Same arithmetic as the matrix-core GEMM: with bits a, b in {0, 1},
 // K - 2 * pc(a xor b) = K - 2 * pc(a) - 2 * pc(b) + 4 * sum a * b, the sum on
-// v_mfma_scale_f32_32x32x64_f8f6f4 with both operands FP4: a bit becomes a nibble of code 1
-// (0.5), the block scales of 2 make it 1.0, products and fp32 sums are exact integers.
+// v_mfma_scale_f32_32x32x64_f8f6f4 with both operands FP4 (E2M1): a set bit becomes a nibble
+// worth 0.5, 1 or 2 on the pixel side and the reciprocal on the filter side (see expand_pixel),
+// so products are 0 or 1 and the fp32 sums exact integers.
 //
 // Shape.  A workgroup expands the bits of its 32 * TM filters into FP4 operands in LDS once
 // (a few dozen VALU instructions per thread), and every MFMA step reads its A operand from
-// there (16 bytes per lane), so filters cost no registers and no VALU work per pixel block.  A wave walks over blocks of 32 output pixels: it fetches the pixels' KW
-// words (one MFMA step of K = 64 consumes exactly one 64-bit word: lane (r, h) supplies half
-// h of the word of pixel r), expands them (8 VALU instructions per word) and issues KW * TM
+// there (16 bytes per lane), so filters cost no registers and no VALU work per pixel block.
+// A wave walks over blocks of 32 output pixels: it fetches the pixels' KW words (one MFMA step
+// of K = 64 consumes exactly one 64-bit word: lane (r, h) supplies half h of the word of pixel
+// r), expands them (5 VALU instructions per word, 1 for the popcount) and issues KW * TM
 // MFMAs.  Lanes run along pixels (operand B), so the NCHW stores are two 128-byte runs per
 // instruction.
 #include <algorithm>
+#include <type_traits>
 
 #include "bmx_internal.h"
 
@@ -24,6 +27,7 @@ namespace bmx {
 namespace {
 
 typedef unsigned v2u __attribute__((ext_vector_type(2)));
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
@@ -49,6 +53,7 @@ struct WsParams {
   int O, HoWo, Wo, Hp, Wpp, Cw, stride;
   int nblocks, nchunks;  // blocks of 32 pixels in all; waves they are dealt out to (evenly)
   int blk_q, blk_r;      // nblocks / nchunks and nblocks % nchunks
+  int x4;                // K-words 2 q, 2 q + 1 are 16 consecutive, 16-byte aligned bytes of the image
   FastDiv div_howo, div_wo;
   int off[kMaxWsWords];  // word offset of K-word j relative to the pixel base
 };
@@ -62,18 +67,37 @@ __device__ __forceinline__ v8i widen(v4i e) {
   return x;
 }
 
-__device__ __forceinline__ v4i expand4(uint32_t w) {
+// The four bit planes of a dword as the four operand dwords of an MFMA step (nibble i of dword
+// d = bit 4 i + d).  The pixel side leaves planes 0 to 2 where they stand in their nibbles
+// (E2M1 codes 1, 2, 4 = 0.5, 1, 2) and shifts only the plane under the nibble's sign bit: five
+// VALU instructions instead of seven, in a kernel whose VALU work outweighs its MFMA time.  The
+// filter side, expanded once per workgroup, carries the reciprocal weights (2, 1, 0.5, 2), so
+// that every product of a set pixel bit and a set filter bit is 1.
+__device__ __forceinline__ v4i expand_pixel(uint32_t w) {
   v4i e;
-#pragma unroll
-  for (int d = 0; d < 4; ++d) e[d] = (int)((w >> d) & 0x11111111u);
+  e[0] = (int)(w & 0x11111111u);
+  e[1] = (int)(w & 0x22222222u);
+  e[2] = (int)(w & 0x44444444u);
+  e[3] = (int)((w >> 3) & 0x11111111u);
+  return e;
+}
+__device__ __forceinline__ v4i expand_filter(uint32_t w) {
+  v4i e;
+  e[0] = (int)((w & 0x11111111u) << 2);
+  e[1] = (int)(w & 0x22222222u);
+  e[2] = (int)((w >> 2) & 0x11111111u);
+  e[3] = (int)((w >> 1) & 0x44444444u);
   return e;
 }
 
-// Where lane (r, hh) finds the patch of pixel r of a block, and where the block's results go.
+// Where lane (r, hh) finds the patch of pixel r of a block, and where the block's results go:
+// 32-bit offsets from wave-uniform bases (the launcher takes only problems whose packed image and
+// output stay below 4 GiB), so that loads and stores use the scalar-base + lane-offset form and
+// need one 32-bit add each instead of 64-bit address arithmetic.
 struct PixelBlock {
-  const uint64_t* xb;  // base of the pixel's patch (tap (0, 0), channel word 0)
-  int64_t obase;       // element index of (image, filter 0, pixel)
-  int64_t bword;       // packed-bit output: index of the pixel's first word
+  uint32_t xoff;   // byte offset of the pixel's patch (tap (0, 0), channel word 0) in the packed image
+  uint32_t obase;  // element index of (image, filter 0, pixel) in the output
+  uint32_t bword;  // packed-bit output: index of the pixel's first word
   int valid;
 };
 
@@ -85,15 +109,15 @@ __device__ __forceinline__ PixelBlock locate(const WsParams& p, int b, int r) {
   const uint32_t rem = (uint32_t)nc - img * (uint32_t)p.HoWo;
   const uint32_t ho = fast_div(rem, p.div_wo);
   const uint32_t wo = rem - ho * (uint32_t)p.Wo;
-  pb.xb = p.Xp + (((int64_t)img * p.Hp + ho * p.stride) * p.Wpp + wo * p.stride) * p.Cw;
-  pb.obase = (int64_t)img * p.O * p.HoWo + rem;
-  pb.bword = (((int64_t)img * p.oHp + ho + p.opad) * p.oWp + wo + p.opad) * p.oCw;
+  pb.xoff = (((img * (uint32_t)p.Hp + ho * (uint32_t)p.stride) * (uint32_t)p.Wpp + wo * (uint32_t)p.stride) * (uint32_t)p.Cw) * 8u;
+  pb.obase = img * (uint32_t)p.O * (uint32_t)p.HoWo + rem;
+  pb.bword = ((img * (uint32_t)p.oHp + ho + (uint32_t)p.opad) * (uint32_t)p.oWp + wo + (uint32_t)p.opad) * (uint32_t)p.oCw;
   pb.valid = n < p.P;
   return pb;
 }
 
 // LDS.  Filters: row i of the workgroup's block holds its 8 * KW expanded dwords (for word j
-// and half h the four dwords (half >> d) & 0x11111111 at 8 j + 4 h + d), the float
+// and half h the four dwords of expand_filter(half) at 8 j + 4 h + d), the float
 // K - 2 * popcount and alpha; the row stride of 8 * KW + 4 dwords (4, 12 or 20 mod 32) lets
 // eight lanes read eight different bank groups with one 16-byte read each.
 // Pixels need no LDS: the words are fetched with neighbouring lanes on neighbouring addresses
@@ -121,10 +145,15 @@ namespace {
 // BITS: the result leaves as packed sign bits (see WsParams::out_bits); the workgroups also
 // write the constant halo words of the output image.
 
-template <int KW, int TM, int WPS, bool BITS>
+// X4: the pixel words are fetched 16 bytes at a time (an even number of channel words, so that
+// K-words 2 q and 2 q + 1 are neighbours in the image and 16-byte aligned).
+template <int KW, int TM, int WPS, bool BITS, bool X4>
 __global__ void __launch_bounds__(256, WPS)
 conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
-  constexpr int NI = (KW + 1) / 2;  // load instructions per block: two words per pixel each
+  static_assert(!X4 || KW % 2 == 0, "pairs of words");
+  // load instructions per block: two words per pixel each, or four
+  constexpr int NI = X4 ? (KW + 3) / 4 : (KW + 1) / 2;
+  typedef typename std::conditional<X4, v4u, uint64_t>::type Staged;
   constexpr int FS = Lds<KW>::kFilterStride;
   __shared__ __attribute__((aligned(16))) uint32_t filt[32 * TM * FS];
   const int lane = threadIdx.x & 63;
@@ -139,29 +168,74 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
   const int b1 = cc < p.nchunks ? b0 + p.blk_q + (cc < p.blk_r ? 1 : 0) : b0;
   WS_STAMP(0);
 
-  // words 2i + h of the pixel's patch, i = 0 .. NI-1 (the odd KW's last one only for h = 0)
-  auto fetch = [&](const PixelBlock& pb, uint64_t (&st)[NI]) {
+  // words 2i + h of the pixel's patch, i = 0 .. NI-1 (the odd KW's last one only for h = 0);
+  // X4: words 4i + 2h and 4i + 2h + 1 in one load
+  auto fetch = [&](const PixelBlock& pb, Staged (&st)[NI]) {
+    const char* const xbytes = (const char*)p.Xp;
 #pragma unroll
-    for (int i = 0; i < NI; ++i)
-      st[i] = (2 * i + 1 < KW || h == 0) ? pb.xb[h ? p.off[2 * i + 1 < KW ? 2 * i + 1 : 0] : p.off[2 * i]] : 0;
+    for (int i = 0; i < NI; ++i) {
+      if constexpr (X4) {
+        const bool there = 4 * i + 2 < KW || h == 0;
+        const uint32_t off = (uint32_t)(h ? p.off[4 * i + 2 < KW ? 4 * i + 2 : 0] : p.off[4 * i]) * 8u;
+        st[i] = there ? *(const v4u*)(xbytes + (pb.xoff + off)) : v4u{0u, 0u, 0u, 0u};
+      } else {
+        const uint32_t off = (uint32_t)(h ? p.off[2 * i + 1 < KW ? 2 * i + 1 : 0] : p.off[2 * i]) * 8u;
+        st[i] = (2 * i + 1 < KW || h == 0) ? *(const uint64_t*)(xbytes + (pb.xoff + off)) : 0;
+      }
+    }
   };
   // staged words -> dword h of every word of pixel r.  Lane (r, 0) holds word 2i and lane (r, 1)
   // word 2i + 1, each as (lo, hi): swapping the upper half-wave of the lo registers with the
   // lower half-wave of the hi registers (v_permlane32_swap, one instruction) leaves dword h of
-  // word 2i in the first and dword h of word 2i + 1 in the second.
-  auto transpose = [&](const uint64_t (&st)[NI], uint32_t (&raw)[KW]) {
+  // word 2i in the first and dword h of word 2i + 1 in the second.  (X4: lane (r, 0) holds words
+  // 4i and 4i + 1, lane (r, 1) words 4i + 2 and 4i + 3; the same swap on each of the two.)
+  auto transpose = [&](const Staged (&st)[NI], uint32_t (&raw)[KW]) {
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
-      const v2u t = __builtin_amdgcn_permlane32_swap((uint32_t)st[i], (uint32_t)(st[i] >> 32), false, false);
-      raw[2 * i] = t[0];
-      if (2 * i + 1 < KW) raw[2 * i + 1] = t[1];
+      if constexpr (X4) {
+        const v2u t = __builtin_amdgcn_permlane32_swap(st[i][0], st[i][1], false, false);
+        const v2u u = __builtin_amdgcn_permlane32_swap(st[i][2], st[i][3], false, false);
+        raw[4 * i] = t[0];
+        raw[4 * i + 1] = u[0];
+        if (4 * i + 2 < KW) {
+          raw[4 * i + 2] = t[1];
+          raw[4 * i + 3] = u[1];
+        }
+      } else {
+        const v2u t = __builtin_amdgcn_permlane32_swap((uint32_t)st[i], (uint32_t)(st[i] >> 32), false, false);
+        raw[2 * i] = t[0];
+        if (2 * i + 1 < KW) raw[2 * i + 1] = t[1];
+      }
     }
   };
 
-  // the first block's pixel words are requested before anything else (waves of the last
-  // workgroup that have no block fetch block 0 and drop it)
+  // ---- the workgroup's filters: neighbouring threads on neighbouring words; all of a thread's
+  // loads are issued before the first is written to LDS (one after the other, every load
+  // would cost a full memory round trip: 6 of 9 us at K = 36 words)
+  // one unit = one 64-bit word of a filter's bits, expanded on the way: 8 bytes read, the two
+  // halves' four planes (32 bytes) written
+  constexpr int kUnits = 32 * TM * KW;
+  constexpr int kCopies = (kUnits + 255) / 256;
+  uint64_t buf[kCopies];
+#pragma unroll
+  for (int t = 0; t < kCopies; ++t) {
+    const int c = min((int)threadIdx.x + 256 * t, kUnits - 1);
+    const int row = c / KW, j = c - row * KW;
+    // rows past the last filter repeat it; their results are never stored
+    buf[t] = *(const uint64_t*)(p.Wp + (int64_t)min(m0 + row, p.O - 1) * p.ld_dw + 2 * j);
+  }
+  float myc0 = 0.0f, myalpha = 1.0f, mythr = 0.0f;  // thread t < 32 * TM carries the constants of row t
+  if ((int)threadIdx.x < 32 * TM) {
+    const int m = min(m0 + (int)threadIdx.x, p.O - 1);
+    myc0 = __uint_as_float(p.Wp[(int64_t)m * p.ld_dw + p.c0_dw]);
+    if (p.alpha) myalpha = p.alpha[m];
+    if (BITS && p.thr) mythr = p.thr[m];
+  }
+  // the first block's pixel words are requested right behind the filter words, which the
+  // whole workgroup waits for at its barrier (waves of the last workgroup that have no block
+  // fetch block 0 and drop it)
   PixelBlock cur = locate(p, b0 < b1 ? b0 : 0, r);
-  uint64_t st[NI];
+  Staged st[NI];
   fetch(cur, st);
   WS_STAMP(1);
 
@@ -192,36 +266,14 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
     }
   }
 
-  // ---- the workgroup's filters: neighbouring threads on neighbouring words; all of a thread's
-  // loads are issued before the first is written to LDS (one after the other, every load
-  // would cost a full memory round trip: 6 of 9 us at K = 36 words)
-  // one unit = one 64-bit word of a filter's bits, expanded on the way: 8 bytes read, the two
-  // halves' four planes (32 bytes) written
-  constexpr int kUnits = 32 * TM * KW;
-  constexpr int kCopies = (kUnits + 255) / 256;
   {
-    uint64_t buf[kCopies];
-#pragma unroll
-    for (int t = 0; t < kCopies; ++t) {
-      const int c = min((int)threadIdx.x + 256 * t, kUnits - 1);
-      const int row = c / KW, j = c - row * KW;
-      // rows past the last filter repeat it; their results are never stored
-      buf[t] = *(const uint64_t*)(p.Wp + (int64_t)min(m0 + row, p.O - 1) * p.ld_dw + 2 * j);
-    }
-    float myc0 = 0.0f, myalpha = 1.0f, mythr = 0.0f;  // thread t < 32 * TM carries the constants of row t
-    if ((int)threadIdx.x < 32 * TM) {
-      const int m = min(m0 + (int)threadIdx.x, p.O - 1);
-      myc0 = __uint_as_float(p.Wp[(int64_t)m * p.ld_dw + p.c0_dw]);
-      if (p.alpha) myalpha = p.alpha[m];
-      if (BITS && p.thr) mythr = p.thr[m];
-    }
 #pragma unroll
     for (int t = 0; t < kCopies; ++t) {
       const int c = (int)threadIdx.x + 256 * t;
       const int row = c / KW, j = c - row * KW;
       if (c < kUnits) {
-        *(v4i_alias*)(filt + row * FS + 8 * j) = expand4((uint32_t)buf[t]);
-        *(v4i_alias*)(filt + row * FS + 8 * j + 4) = expand4((uint32_t)(buf[t] >> 32));
+        *(v4i_alias*)(filt + row * FS + 8 * j) = expand_filter((uint32_t)buf[t]);
+        *(v4i_alias*)(filt + row * FS + 8 * j + 4) = expand_filter((uint32_t)(buf[t] >> 32));
       }
     }
     if ((int)threadIdx.x < 32 * TM) {
@@ -254,12 +306,15 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
     // end: an MFMA that adds onto the result of the one before it can only start when that one
     // has finished, twice the time it takes to issue.  The filter operands are read a group of
     // steps ahead: read where they are used, every pair of MFMAs would wait out an LDS round trip.
-    constexpr int G = KW > 36 ? 2 : 4, NG = (KW + G - 1) / G;  // (two steps ahead where registers are short)
-    v16f acc[TM][2];
+    // (with two filter blocks per wave their two chains are independent already, and registers
+    // are short: one chain each, operands two steps ahead)
+    constexpr int CH = TM == 1 ? 2 : 1;
+    constexpr int G = (KW > 36 || TM == 2) ? 2 : 4, NG = (KW + G - 1) / G;
+    v16f acc[TM][CH];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int c = 0; c < 2; ++c)
+      for (int c = 0; c < CH; ++c)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[i][c][e] = 0.0f;
     v4i abuf[2][G][TM];
@@ -283,21 +338,23 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
         const int j = g * G + t;
         if (j < KW) {
           pb += __builtin_popcount(raw[j]);
-          const v8i eb = widen(expand4(raw[j]));
+          const v8i eb = widen(expand_pixel(raw[j]));
 #pragma unroll
           for (int i = 0; i < TM; ++i)
-            acc[i][j & 1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(abuf[g & 1][t][i]), eb, acc[i][j & 1], 4, 4,
-                                                                           0, 128, 0, 128);
+            acc[i][j % CH] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(abuf[g & 1][t][i]), eb, acc[i][j % CH], 4, 4,
+                                                                            0, 127, 0, 127);  // (block scales of 1)
         }
       }
       // keep the operands of the groups that follow behind these MFMAs: gathered at the top of
       // the block (the scheduler's preference) they would hold 8 * KW registers at once
       __builtin_amdgcn_sched_barrier(0);
     }
+    if constexpr (CH == 2) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][0][e] += acc[i][1][e];  // exact: whole numbers below 2^24
+        for (int e = 0; e < 16; ++e) acc[i][0][e] += acc[i][1][e];  // exact: whole numbers below 2^24
+    }
     pb += __shfl_xor(pb, 32);
     // out = alpha * (K - 2 pc(filter) - 2 pc(patch) + 4 * sum): exact integers in fp32 up to
     // the single rounding of the alpha product.  (The row constants of all result registers
@@ -331,23 +388,42 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
           dst[0] = mask;
           if ((mb & 32) == 0 && mb + 32 >= p.O) dst[1] = 0;  // nobody else owns the upper half
         }
-      } else if (p.out_i32) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int m = m0 + 32 * i + 8 * (v / 4) + 4 * h + (v % 4);
-          const float t = fmaf(4.0f, acc[i][0][v], c0[v]) - pb2;
-          if (cur.valid && m < p.O) __builtin_nontemporal_store((int)t, p.out_i32 + cur.obase + (int64_t)m * p.HoWo);
-        }
       } else {
+        // Register v goes to row m0 + 32 i + 8 (v / 4) + 4 h + v % 4, pixel r: one wave-uniform
+        // base for the whole output and a 32-bit lane offset per register (the block's offset
+        // plus a multiple of the row pitch).  A block wholly inside the output (the usual case)
+        // stores without bounds tests.
+        const uint32_t pitch = (uint32_t)p.HoWo * 4u;
+        const uint32_t lane_off = cur.obase * 4u + (uint32_t)(m0 + 32 * i + 4 * h) * pitch;
+        const bool inside = b * 32 + 32 <= p.P && m0 + 32 * TM <= p.O;
+        auto put = [&](auto inside_tag, auto int_tag) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int m = m0 + 32 * i + 8 * (v / 4) + 4 * h + (v % 4);
-          const float t = fmaf(4.0f, acc[i][0][v], c0[v]) - pb2;
+          for (int v = 0; v < 16; ++v) {
+            const int mi = 8 * (v / 4) + (v % 4);
+            const uint32_t off = lane_off + (uint32_t)mi * pitch;
+            const float t = fmaf(4.0f, acc[i][0][v], c0[v]) - pb2;
 #ifdef BMX_WS_SKIP_STORES
-          if (cur.valid && m < p.O && t == 1.2345e30f) __builtin_nontemporal_store(al[v] * t, p.out_f32 + cur.obase + (int64_t)m * p.HoWo);
-#else
-          if (cur.valid && m < p.O) __builtin_nontemporal_store(al[v] * t, p.out_f32 + cur.obase + (int64_t)m * p.HoWo);
+            if (t != 1.2345e30f) continue;
 #endif
+            if (decltype(inside_tag)::value || (cur.valid && m0 + 32 * i + mi + 4 * h < p.O)) {
+              // (written out: the compiler builds a 64-bit vector address for a non-temporal
+              // store even from a uniform base and a 32-bit offset)
+              if constexpr (decltype(int_tag)::value) {
+                const int iv = (int)t;
+                asm volatile("global_store_dword %0, %1, %2 nt" ::"v"(off), "v"(iv), "s"(p.out_i32) : "memory");
+              } else {
+                const float fv = al[v] * t;
+                asm volatile("global_store_dword %0, %1, %2 nt" ::"v"(off), "v"(fv), "s"(p.out_f32) : "memory");
+              }
+            }
+          }
+        };
+        if (p.out_i32) {
+          if (inside) put(std::true_type{}, std::true_type{});
+          else put(std::false_type{}, std::true_type{});
+        } else {
+          if (inside) put(std::true_type{}, std::false_type{});
+          else put(std::false_type{}, std::false_type{});
         }
       }
     }
@@ -360,18 +436,28 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
 #endif
 }
 
-template <int KW, int TM, int WPS, bool BITS = false>
-void launch_ws(const WsParams& p, int m_tiles, hipStream_t s) {
+template <int KW, int TM, int WPS, bool BITS, bool X4>
+void launch_ws_form(const WsParams& p, int m_tiles, hipStream_t s) {
   const int chunks = p.nchunks;
-  note_kernel("conv_mfma_ws_kernel<%d,%d,%d,%s> grid %d x %d x 256", KW, TM, WPS, BITS ? "true" : "false",
-              (int)ceil_div(chunks, 4), m_tiles);
+  note_kernel("conv_mfma_ws_kernel<%d,%d,%d,%s%s> grid %d x %d x 256", KW, TM, WPS, BITS ? "true" : "false",
+              X4 ? ",x4" : "", (int)ceil_div(chunks, 4), m_tiles);
 #ifdef BMX_WS_STAMPS
-  hipLaunchKernelGGL((conv_mfma_ws_kernel<KW, TM, WPS, BITS>), dim3((unsigned)ceil_div(chunks, 4), (unsigned)m_tiles),
+  hipLaunchKernelGGL((conv_mfma_ws_kernel<KW, TM, WPS, BITS, X4>), dim3((unsigned)ceil_div(chunks, 4), (unsigned)m_tiles),
                      dim3(256), 0, s, p, ws_stamps);
 #else
-  hipLaunchKernelGGL((conv_mfma_ws_kernel<KW, TM, WPS, BITS>), dim3((unsigned)ceil_div(chunks, 4), (unsigned)m_tiles),
+  hipLaunchKernelGGL((conv_mfma_ws_kernel<KW, TM, WPS, BITS, X4>), dim3((unsigned)ceil_div(chunks, 4), (unsigned)m_tiles),
                      dim3(256), 0, s, p);
 #endif
+}
+
+// WPS_X4: waves per SIMD of the form with 16-byte pixel loads, which needs fewer registers.
+template <int KW, int TM, int WPS, bool BITS = false, int WPS_X4 = WPS>
+void launch_ws(const WsParams& p, int m_tiles, hipStream_t s) {
+  // 16-byte pixel loads where the word count can come from an even number of channel words
+  if constexpr (KW == 18 || KW == 36 || KW == 50) {
+    if (p.x4) return launch_ws_form<KW, TM, WPS_X4, BITS, true>(p, m_tiles, s);
+  }
+  launch_ws_form<KW, TM, WPS, BITS, false>(p, m_tiles, s);
 }
 
 }  // namespace
@@ -387,6 +473,10 @@ bool conv_mfma_ws_takes(int Nimg, int C, int H, int W, int O, int KH, int KW, in
   if (P >= ((int64_t)1 << 31) || (int64_t)C * KH * KW >= ((int64_t)1 << 22)) return false;
   if ((int64_t)Nimg * (Ho + 2 * out_pad) * (Wo + 2 * out_pad) >= ((int64_t)1 << 31)) return false;
   if ((int64_t)(KH * (W + 2 * pad) + KW) * Cw >= ((int64_t)1 << 30)) return false;
+  // packed image, output and packed-bit output are addressed with 32-bit byte offsets
+  if ((int64_t)Nimg * (H + 2 * pad) * (W + 2 * pad) * Cw * 8 >= ((int64_t)1 << 32)) return false;
+  if (((int64_t)Nimg * O + 64) * Ho * Wo * 4 >= ((int64_t)1 << 32)) return false;
+  if ((int64_t)Nimg * (Ho + 2 * out_pad) * (Wo + 2 * out_pad) * words_for(O) * 8 >= ((int64_t)1 << 32)) return false;
   return ceil_div(O, 32) <= 65535;
 }
 
@@ -435,42 +525,45 @@ bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, cons
   p.nblocks = (int)ceil_div(P, 32);
   // (64 filters per workgroup, two accumulator sets sharing every expanded pixel word, is kept
   // for measurements only: it lost to 32 everywhere, 8.0 against 7.2 us on 16 x 64 x 56 x 56)
+  // (also tried at 36 words: the compiler needs more than 256 registers for it and spills 185)
   const int TM = (kwords == 9 && O > 32 && gemm_mfma_tile == 2 && !out_bits) ? 2 : 1;
   const int m_tiles = (int)ceil_div(O, 32 * TM);
-  // Waves: one per block while all of them are resident at once (3 workgroups per CU for 9 and
-  // 18 words, 2 beyond: what the registers of two accumulator chains and the filter operands
-  // read ahead allow); beyond that, as many waves as are resident in one round, the blocks dealt
-  // out evenly: every workgroup copies its filters once and no CU is left with a second round of
-  // a few workgroups.
-  const int resident_waves = 256 * 4 * (kwords <= 18 ? 3 : 2);
+  // Waves: one per block while all of them are resident at once (workgroups per CU as the
+  // registers allow: 4 at 9 words, 3 up to 27 and, with 16-byte pixel loads and fp32 or int32
+  // results, at 36, else 2); beyond that, as many waves as are resident in one round, the
+  // blocks dealt out evenly: every workgroup copies its filters once and no CU is left with a
+  // second round of a few workgroups.
+  p.x4 = ((Cw & 1) == 0 && ((uintptr_t)Xp & 15) == 0 && conv_ws_x4 != 1) ? 1 : 0;
+  const int per_simd = kwords == 9 ? 4 : kwords <= 27 ? 3 : (kwords == 36 && p.x4 && !out_bits) ? 3 : 2;
+  const int resident_waves = 256 * 4 * per_simd;
   p.nchunks = (int)std::min<int64_t>(p.nblocks, std::max(1, resident_waves / m_tiles));
   if (conv_filters_per_wave >= 100) p.nchunks = std::min(p.nblocks, conv_filters_per_wave);  // (tuning hook reused: chunks)
   else if (conv_filters_per_wave > 0) p.nchunks = (int)ceil_div(p.nblocks, conv_filters_per_wave);  // (or blocks per wave)
   p.blk_q = p.nblocks / p.nchunks;
   p.blk_r = p.nblocks % p.nchunks;
   if (out_bits) {
-    if (kwords == 9) launch_ws<9, 1, 3, true>(p, m_tiles, s);
+    if (kwords == 9) launch_ws<9, 1, 4, true>(p, m_tiles, s);
     else if (kwords == 18) launch_ws<18, 1, 3, true>(p, m_tiles, s);
-    else if (kwords == 25) launch_ws<25, 1, 2, true>(p, m_tiles, s);
-    else if (kwords == 27) launch_ws<27, 1, 2, true>(p, m_tiles, s);
+    else if (kwords == 25) launch_ws<25, 1, 3, true>(p, m_tiles, s);
+    else if (kwords == 27) launch_ws<27, 1, 3, true>(p, m_tiles, s);
     else if (kwords == 49) launch_ws<49, 1, 2, true>(p, m_tiles, s);
     else if (kwords == 50) launch_ws<50, 1, 2, true>(p, m_tiles, s);
     else launch_ws<36, 1, 2, true>(p, m_tiles, s);
   } else if (kwords == 9) {
     if (TM == 2) launch_ws<9, 2, 2>(p, m_tiles, s);
-    else launch_ws<9, 1, 3>(p, m_tiles, s);
+    else launch_ws<9, 1, 4>(p, m_tiles, s);
   } else if (kwords == 18) {
     launch_ws<18, 1, 3>(p, m_tiles, s);
   } else if (kwords == 25) {
-    launch_ws<25, 1, 2>(p, m_tiles, s);
+    launch_ws<25, 1, 3>(p, m_tiles, s);
   } else if (kwords == 27) {
-    launch_ws<27, 1, 2>(p, m_tiles, s);
+    launch_ws<27, 1, 3>(p, m_tiles, s);
   } else if (kwords == 49) {
     launch_ws<49, 1, 2>(p, m_tiles, s);
   } else if (kwords == 50) {
     launch_ws<50, 1, 2>(p, m_tiles, s);
   } else {
-    launch_ws<36, 1, 2>(p, m_tiles, s);
+    launch_ws<36, 1, 2, false, 3>(p, m_tiles, s);
   }
   *err = hipGetLastError();
   return true;

@@ -287,8 +287,9 @@ def test_config4_conv_full(stride):
     alpha = oracle.alpha_mean_abs(c["w"])
     ri, rf = oracle.binary_conv2d(c["x"], c["w"], stride, 1, alpha)
     # automatic (the short-K FP4 matrix-core kernel, 36 words of K), register-stationary
-    # xor/popcount kernel, xor/popcount GEMM kernel, GEMM-shaped FP4 and int8 matrix-core kernels
-    for choice in (dict(), dict(k5=1), dict(k5=2), dict(k5=4), dict(k5=4, k7=2)):
+    # xor/popcount kernel, xor/popcount GEMM kernel, GEMM-shaped FP4 and int8 matrix-core kernels,
+    # the 64 x 64 per wave FP4 kernel's convolution form
+    for choice in (dict(), dict(k14=1), dict(k5=1), dict(k5=2), dict(k5=4), dict(k5=4, k7=2), dict(k5=6)):
         with tuned(**choice):
             got = run_conv(c["x"], c["w"], stride, 1, alpha=alpha)
             assert got.shape == (64, 256, 14 // stride, 14 // stride)
@@ -563,8 +564,10 @@ def test_conv_short_k_matrix_core(N, C, H, W, O, s, p):
     w = rng.standard_normal((O, C, 3, 3)).astype(np.float32)
     alpha = oracle.alpha_mean_abs(w)
     ri, rf = oracle.binary_conv2d(x, w, s, p, alpha)
-    for tile, per_wave in ((0, 0), (2, 3), (0, 7), (0, 101)):
-        with tuned(k5=5, k9=tile, k1=per_wave):
+    # (narrow = 1: pixel words fetched 8 bytes at a time also where an even number of channel
+    # words lets the kernel fetch 16)
+    for tile, per_wave, narrow in ((0, 0, 0), (2, 3, 0), (0, 7, 0), (0, 101, 0), (0, 0, 1), (0, 3, 1)):
+        with tuned(k5=5, k9=tile, k1=per_wave, k14=narrow):
             np.testing.assert_array_equal(run_conv(x, w, s, p, integer_out=True), ri)
             assert_f32_close(run_conv(x, w, s, p, alpha=alpha), rf)
             np.testing.assert_array_equal(run_conv(x, w, s, p), ri.astype(np.float32))
@@ -582,8 +585,8 @@ def test_conv_short_k_matrix_core_5x5(N, C, H, W, O, s, p):
     w = rng.standard_normal((O, C, 5, 5)).astype(np.float32)
     alpha = oracle.alpha_mean_abs(w)
     ri, rf = oracle.binary_conv2d(x, w, s, p, alpha)
-    for per_wave in (0, 3, 101):
-        with tuned(k5=5, k1=per_wave):
+    for per_wave, narrow in ((0, 0), (3, 0), (101, 0), (0, 1), (3, 1)):
+        with tuned(k5=5, k1=per_wave, k14=narrow):
             np.testing.assert_array_equal(run_conv(x, w, s, p, integer_out=True), ri)
             assert_f32_close(run_conv(x, w, s, p, alpha=alpha), rf)
     Wp, xp = B.pack_conv_weights(dev(w)), B.pack_nchw(dev(x), p)
