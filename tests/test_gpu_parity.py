@@ -253,6 +253,33 @@ def test_conv_cases(N, C, H, W, O, k, s, p):
     assert_f32_close(got, rf)
 
 
+def test_conv_output_offsets_beyond_two_gib():
+    """A convolution whose fp32 output is 3.3 GB (130 x 512 x 112 x 112): the short-K matrix-core
+    kernel addresses its output with 32-bit byte offsets from a uniform base, which here pass
+    2^31.  The first, one middle and the last image against the oracle (image by image: the
+    oracle would need minutes for the whole batch), every other image against the popcount
+    kernel on a sample of rows."""
+    N, C, H, W, O = 130, 64, 112, 112, 512
+    gen = torch.Generator(device="cuda").manual_seed(130)
+    x = torch.randn((N, C, H, W), device="cuda", generator=gen)
+    rng = np.random.default_rng(130)
+    w = rng.standard_normal((O, C, 3, 3)).astype(np.float32)
+    alpha = oracle.alpha_mean_abs(w)
+    Wp = B.pack_conv_weights(dev(w))
+    got = B.binary_conv2d(x, Wp, O, 3, 3, 1, 1, alpha=dev(alpha))
+    assert "conv_mfma_ws_kernel" in B.last_kernel()
+    assert got.shape == (N, O, H, W) and got.numel() * 4 > 2 ** 31
+    for n in (0, 77, N - 1):
+        _, rf = oracle.binary_conv2d(x[n:n + 1].cpu().numpy(), w, 1, 1, alpha)
+        assert_f32_close(got[n:n + 1].cpu().numpy(), rf)
+    with tuned(k5=1):
+        ref = B.binary_conv2d(x, Wp, O, 3, 3, 1, 1, alpha=dev(alpha))
+        assert "conv_stationary_kernel" in B.last_kernel()
+    assert torch.equal(got[:, ::37], ref[:, ::37])
+    del got, ref, x
+    torch.cuda.empty_cache()
+
+
 def test_conv_padding_closed_form_on_gpu():
     C, H, W, O = 5, 6, 6, 2
     K = 9 * C
