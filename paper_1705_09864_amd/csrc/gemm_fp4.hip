@@ -24,15 +24,19 @@
 //     Which 16-byte piece a lane fetches is permuted (piece = slot xor ((row >> 1) & 3)), so
 //     that the MFMA-layout reads, lane (r, h) <- piece 2 g + h of row r, fall on all banks.
 //   - A wave owns its staging area and its range of K: no barrier in the main loop.  The words
-//     of a 64-byte segment are read into registers, the next segment's loads are issued into
-//     the same area, and the 32 MFMAs of the segment run with those loads in flight.
+//     of a 64-byte segment are read into registers, the next segment's loads are issued (into
+//     the same area once those reads have completed, or into a second area used in turn), and
+//     the 32 MFMAs of the segment run with those loads in flight.
 //   - Skinny problems (the fully connected layers: 256 rows) have too few 64 x 64 tiles to
 //     fill the chip, so the S waves of a workgroup split K and add their partial tiles through
 //     LDS once: every wave writes its 64 registers, then finishes 1/S of the tile (sum of S
 //     partials, the popcount terms, scale, store).  Fat problems run four tiles per workgroup
 //     and no split.
-//   - Workgroups are numbered so that tiles sharing rows of B (the large operand: weights) sit
-//     on one XCD and run back to back: workgroup b runs on XCD b % 8.
+//   - Workgroups are numbered so that tiles sharing operand rows sit on one XCD and run back
+//     to back (workgroup b runs on XCD b % 8): every XCD gets a contiguous run of tiles, walked
+//     in bands of 16 rows of tiles.
+//   - The convolution form gathers the B operand (im2col rows) from the halo-padded packed
+//     image, 16 bytes per lane, through the same loads.
 #include <algorithm>
 #include <type_traits>
 
