@@ -49,7 +49,10 @@ VALU_PEAK_BINOPS = 256 * 64 * 2.4e9 * 32
 HBM_PEAK = 8.0e12
 FP4_PEAK = 10.1e15   # dense FP4 matrix-core peak, flop/s
 INT8_PEAK = 5.0e15   # dense int8 matrix-core peak, op/s
-MALL_BYTES = 256 << 20  # memory-side cache the rotation has to exceed
+MALL_BYTES = 256 << 20  # memory-side cache
+# what a rotation over buffer sets has to cover: with 1.1 times the cache a cyclic walk still finds
+# much of its data there (the fc1 GEMM: 8.5 us at 285 MB, 9.3 at 590 MB, 9.5 at 1.2 GB)
+ROTATE_BYTES = 4 * MALL_BYTES
 PHASES = ("headline", "fc1", "fc2", "config1", "config2", "config4", "config5", "sec31", "packs", "biggemm", "probe")
 
 
@@ -153,7 +156,7 @@ def main():
         return best
 
     def nsets_for(bytes_per_set, cap=512):
-        return int(min(cap, MALL_BYTES // max(int(bytes_per_set), 1) + 2))
+        return int(min(cap, ROTATE_BYTES // max(int(bytes_per_set), 1) + 2))
 
     def rotating_us(calls, reps=None):
         """calls[i] runs the measured call on buffer set i.  The sets together exceed the
@@ -236,7 +239,9 @@ def main():
         ws_bytes = B.workspace_bytes(B.OP_BINARY_FC, (Bt, F0, F1))
         x0 = dev(c3["x"])
         step_bytes = (x0.numel() * 4 + ws_bytes + Bt * F1 * 4 + Bt * F2 * 4 + W1p0.numel() * 8 + W2p0.numel() * 8)
-        nsets = nsets_for(step_bytes)
+        # enough sets that the smallest single-kernel timing below (the second layer's pack: its
+        # fp32 input and its packed output) also walks through more than the memory-side cache
+        nsets = nsets_for(Bt * F1 * 4 + Bt * F1 // 8, cap=128)
         xs = [x0] + [x0.clone() for _ in range(nsets - 1)]
         W1s = [W1p0] + [W1p0.clone() for _ in range(nsets - 1)]
         W2s = [W2p0] + [W2p0.clone() for _ in range(nsets - 1)]
@@ -387,12 +392,12 @@ def main():
     run_others = not args.no_other_configs
 
     if want("packs") and run_others:
-        # weight pack of the first layer (151 MB fp32 -> 4.7 MB), three copies rotating, and a
+        # weight pack of the first layer (151 MB fp32 -> 4.7 MB), eight copies rotating, and a
         # 1 GiB row pack: the sustained HBM figures of the pack kernel
         w1 = dev(c3["w1"])
         W1p0 = B.binarize_pack(w1, 1)
-        wcopies = [w1] + [w1.clone() for _ in range(2)]
-        us_, nm_ = rotating_us([(lambda i=i: B.binarize_pack(wcopies[i], 1, out=W1p0)) for i in range(3)], reps=30)
+        wcopies = [w1] + [w1.clone() for _ in range(7)]
+        us_, nm_ = rotating_us([(lambda i=i: B.binarize_pack(wcopies[i], 1, out=W1p0)) for i in range(8)], reps=32)
         other["config3_weight_pack_4096x9216"] = roofline_block(nm_, us_, nbytes=w1.numel() * 4 + W1p0.numel() * 8)
         del wcopies, w1
         big = f32(8192, 32768).normal_()
@@ -405,13 +410,13 @@ def main():
     # ------------------------------------------------------------------ a chip-filling xnor GEMM
     if want("biggemm") and run_others:
         # 8192^3 on packed operands (no configuration of the set: the matrix-core kernel away from
-        # launch costs).  16 MB of operands, 268 MB of int32 results per launch, two sets rotating.
+        # launch costs).  16 MB of operands, 268 MB of int32 results per launch, four sets rotating.
         Mb = Nb = Kb = 8192
         gen = torch.Generator(device="cuda").manual_seed(8192)
-        Ab = [torch.randint(-2 ** 62, 2 ** 62, (Mb, Kb // 64), dtype=torch.int64, device="cuda", generator=gen) for _ in range(2)]
-        Bb = [torch.randint(-2 ** 62, 2 ** 62, (Nb, Kb // 64), dtype=torch.int64, device="cuda", generator=gen) for _ in range(2)]
-        Cb = [i32(Mb, Nb) for _ in range(2)]
-        us_, nm_ = rotating_us([(lambda i=i: B.xnor_gemm(Ab[i], Bb[i], Kb, out=Cb[i])) for i in range(2)], reps=12)
+        Ab = [torch.randint(-2 ** 62, 2 ** 62, (Mb, Kb // 64), dtype=torch.int64, device="cuda", generator=gen) for _ in range(4)]
+        Bb = [torch.randint(-2 ** 62, 2 ** 62, (Nb, Kb // 64), dtype=torch.int64, device="cuda", generator=gen) for _ in range(4)]
+        Cb = [i32(Mb, Nb) for _ in range(4)]
+        us_, nm_ = rotating_us([(lambda i=i: B.xnor_gemm(Ab[i], Bb[i], Kb, out=Cb[i])) for i in range(4)], reps=12)
         blk = roofline_block(nm_, us_, binops=2.0 * Mb * Nb * Kb, nbytes=2 * Mb * Kb // 8 + Mb * Nb * 4)
         blk["note"] = ("268 MB of results per launch: 34 us of HBM time at the peak rate beside 109 us of matrix-core "
                        "time; the shader clock under this load was measured at 1.8 - 2.0 GHz, against the 2.4 GHz "
@@ -448,7 +453,9 @@ def main():
         ws_bytes = B.workspace_bytes(B.OP_BINARY_CONV2D, (N, C, H, W, O, KH, KW, stride, pad))
         Cw = (C + 63) // 64
         out_bytes = N * O * Ho * Wo * 4
-        n = nsets_for(x_h.nbytes + ws_bytes + out_bytes + Wp0.numel() * 8)
+        # (enough sets that each kernel timed alone, the pack on x and the packed image, the
+        # convolution on the packed image and the output, also walks through more than the cache)
+        n = nsets_for(min(x_h.nbytes + ws_bytes, ws_bytes + out_bytes + Wp0.numel() * 8), cap=128)
         x0 = dev(x_h)
         xs = [x0] + [x0.clone() for _ in range(n - 1)]
         Wps = [Wp0] + [Wp0.clone() for _ in range(n - 1)]

@@ -283,7 +283,7 @@ size_t bmx_workspace_bytes(int op, const int64_t* dims, int ndims);
  *          64 x 64 per wave and operands staged through LDS whatever the size
  *   key 10 K-split waves of the latter kernel, key 11 = 2: its partial tiles cross LDS as fp32
  *          even where fp16 pairs would be exact, key 12 rows of tiles per band of its tile order
- *          (automatic: 16), key 13 = 1: one LDS staging area per wave even where a second fits
+ *          (automatic: 16)
  *   key 14 = 1: the short-K matrix-core convolution kernel fetches pixel words 8 bytes at a time
  *          even where 16 would do
  *   key 8  K-split waves, key 9  tile variant (1: 32 x 32, 2: 64 x 64 per wave) of the matrix-core

@@ -24,9 +24,9 @@
 //     Which 16-byte piece a lane fetches is permuted (piece = slot xor ((row >> 1) & 3)), so
 //     that the MFMA-layout reads, lane (r, h) <- piece 2 g + h of row r, fall on all banks.
 //   - A wave owns its staging area and its range of K: no barrier in the main loop.  The words
-//     of a 64-byte segment are read into registers, the next segment's loads are issued (into
-//     the same area once those reads have completed, or into a second area used in turn), and
-//     the 32 MFMAs of the segment run with those loads in flight.
+//     of a 64-byte segment are read into registers, the next segment's loads are issued into
+//     the same area once those reads have completed, and the 32 MFMAs of the segment run with
+//     those loads in flight.
 //   - Skinny problems (the fully connected layers: 256 rows) have too few 64 x 64 tiles to
 //     fill the chip, so the S waves of a workgroup split K and add their partial tiles through
 //     LDS once: every wave writes its 64 registers, then finishes 1/S of the tile (sum of S
@@ -60,7 +60,6 @@ struct Fp4Params {
   int g_base, g_rem;  // groups of four words (256 bits = the K of four MFMAs) per wave: g_base, the first g_rem waves one more
   int tiles_m, tiles_n, tiles_per_xcd;
   // tile order: bands of `band` rows of tiles (the last band has last_rows), see the kernel
-  int two_areas;  // a second staging area per wave lies behind the waves' first ones
   int band, per_band, last_band, last_rows;
   FastDiv div_per_band, div_band, div_last;
   const float* alpha;     // per column n, or null
@@ -185,11 +184,8 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
   constexpr int kStage = NB * 128;           // uint4 per staged segment: NB blocks x 32 rows x 64 bytes
   constexpr int kGroups = TM * TN * 4;       // a wave's accumulators in units of four registers
   constexpr int kCnt = (TM + TN) * 8;        // uint4 holding a wave's 32 (TM + TN) popcounts
-  // LDS: per wave a staging area, overlaid after the main loop of a split by the wave's partial
-  // tile + counts; behind those, where the launcher found room for it without giving up waves
-  // per CU (p.two_areas), a second staging area per wave, used in turn with the first.  Only one
-  // segment's loads are ever in flight.  (Two segments in flight bought nothing at any size:
-  // 8192^3 254 against 248 us, the fully connected layers 9.3 against 8.9 us.)
+  // LDS per wave: its staging area, overlaid after the main loop of a split by its partial tile
+  // + counts.
   constexpr int kPart = HALF ? kGroups * 32 : kGroups * 64;  // uint4 holding a wave's partial tile
   constexpr int kSlot = (!SPLIT || kStage > kPart + kCnt) ? kStage : kPart + kCnt;
   // Everything the wave needs before its first load, named in one statement at the top: the
@@ -199,7 +195,7 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
                "s"(p.g_rem), "s"(p.tiles_m), "s"(p.tiles_n), "s"(p.tiles_per_xcd), "s"(p.band), "s"(p.per_band),
                "s"(p.last_band), "s"(p.last_rows), "s"(p.div_per_band.mul), "s"(p.div_per_band.sh1),
                "s"(p.div_per_band.sh2), "s"(p.div_band.mul), "s"(p.div_band.sh1), "s"(p.div_band.sh2),
-               "s"(p.div_last.mul), "s"(p.div_last.sh1), "s"(p.div_last.sh2), "s"(S_arg));
+               "s"(p.div_last.mul), "s"(p.div_last.sh1), "s"(p.div_last.sh2), "s"(S_arg), "s"(p.alpha), "s"(p.thr), "s"(p.rowsum));
   const int S = SPLIT ? S_arg : 1;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -233,8 +229,6 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
   // ---- loader: lane i of load t of a block fetches, for local row 16 t + i / 4, the piece
   // (i % 4) xor ((row >> 1) & 3) of the segment; voff = byte offset of that piece in segment 0.
   uint4* const stage = lds + wave * kSlot;
-  const bool two = p.two_areas != 0;
-  uint4* const stage2 = two ? lds + (int)(blockDim.x >> 6) * kSlot + wave * kStage : stage;
   int piece[2];
   uint32_t voff[NB][2];
 #pragma unroll
@@ -266,11 +260,9 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
 #pragma unroll
   for (int g = 0; g < 2; ++g) rd[g] = (r >> 4) * 64 + (r & 15) * 4 + ((2 * g + h) ^ ((r >> 1) & 3));
 
-  if (seg_lo < seg_hi) issue_segment<NA, NB, CONV>(p, stage, &voff[0][0], piece[0], piece[1], seg_lo);
-  FP4_STAMP(1);
-  FP4_REALTIME(4);
-  // The epilogue's constants are requested now, behind the first segment: fetched where they are
-  // used, each would put a trip to memory between the main loop and the stores.  Per column of
+  // The epilogue's constants are requested first of all (fetched where they are used, each would
+  // put a trip to memory between the main loop and the stores; and ahead of the segments'
+  // loads they do not disturb the count of loads in flight that the main loop relies on).  Per column of
   // this lane (column 32 j + r): alpha and the threshold of the sign decision; per row of the
   // tile, row m0 + l in lane l: the row sum of the plane form, alpha of the convolution form.
   static_assert(TM == 2, "one lane per row of the tile");
@@ -284,6 +276,10 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
   float thn1 = (XNOR && OUT == kOutBits && p.thr) ? p.thr[n_c1] : 0.0f;
   const int rowsum_lane = XNOR ? 0 : p.rowsum[min(m0 + lane, p.M - 1)];
   const float alpha_lane = (CONV && p.alpha) ? p.alpha[min(m0 + lane, p.M - 1)] : 1.0f;
+
+  if (seg_lo < seg_hi) issue_segment<NA, NB, CONV>(p, stage, &voff[0][0], piece[0], piece[1], seg_lo);
+  FP4_STAMP(1);
+  FP4_REALTIME(4);
 
   v16f acc[TM][TN];
 #pragma unroll
@@ -301,12 +297,11 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
   for (int seg = seg_lo; seg < seg_hi; ++seg) {
     // the segment's words into registers (the compiler waits for the loads in flight: it tracks
     // LDS writes of the load unit)
-    const uint4* src = ((seg - seg_lo) & 1) ? stage2 : stage;
     uint4 w[NB][2];
 #pragma unroll
     for (int b = 0; b < NB; ++b)
 #pragma unroll
-      for (int g = 0; g < 2; ++g) w[b][g] = src[b * 128 + rd[g]];
+      for (int g = 0; g < 2; ++g) w[b][g] = stage[b * 128 + rd[g]];
     if (8 * seg + 8 > p.Kw) {  // last segment of a row that ends inside it: words past the row are zero
 #pragma unroll
       for (int g = 0; g < 2; ++g) {
@@ -318,19 +313,20 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
         }
       }
     }
-    // The next segment is requested before this one is multiplied.  Its loads must not land on
-    // words that are still to be read, and a read that has merely been issued may still wait in
-    // the LDS queue behind those of the CU's other waves when the data arrives (a few hundred
-    // cycles for an L2 hit; seen as a few wrong counts in a chip-filling GEMM).  With two areas
-    // the loads go to the other one, whose last reads were consumed by the MFMAs of the previous
-    // segment; with one area the reads are waited for first.
-    if (!two) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    else asm volatile("" ::: "memory");
+    // The next segment is requested before this one is multiplied, into the area just read.  Its
+    // loads must not land on words that are still to be read, and a read that has merely been
+    // issued may still wait in the LDS queue behind those of the CU's other waves when the data
+    // arrives (a few hundred cycles for an L2 hit; seen as a few wrong counts in a chip-filling
+    // GEMM): the reads are waited for first.  (A second area per wave used in turn, which needs
+    // no wait, and two segments' loads in flight on top of that, with counted waits written out
+    // because the compiler waits for every pending load of the load unit before an LDS read it
+    // knows of, both measured no faster with operands that really come from HBM: 9.5 and 9.9
+    // against 9.5 us on the first fully connected layer.)
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #ifdef BMX_FP4_STAMPS
     if (seg == seg_lo) { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); FP4_STAMP(2); }
 #endif
-    if (seg + 1 < seg_hi)
-      issue_segment<NA, NB, CONV>(p, ((seg + 1 - seg_lo) & 1) ? stage2 : stage, &voff[0][0], piece[0], piece[1], seg + 1);
+    if (seg + 1 < seg_hi) issue_segment<NA, NB, CONV>(p, stage, &voff[0][0], piece[0], piece[1], seg + 1);
 #pragma unroll
     for (int g = 0; g < 2; ++g) {
       const int kg = 2 * seg + g;
@@ -565,19 +561,12 @@ int gemm_fp4_half = 0;  // 2 = keep fp32 partials (tests of both forms)
 namespace {
 
 template <int TM, int TN, int PL, bool XNOR, int OUT, bool SPLIT, bool HALF, bool CONV>
-hipError_t launch_tile(const Fp4Params& p_in, int S, int tiles_per_wg, int64_t blocks, hipStream_t s) {
+hipError_t launch_tile(const Fp4Params& p, int S, int tiles_per_wg, int64_t blocks, hipStream_t s) {
   constexpr int NB = TM * PL + TN, kStage = NB * 128, kGroups = TM * TN * 4, kCnt = (TM + TN) * 8;
   constexpr int part = HALF ? kGroups * 32 : kGroups * 64;
   constexpr int slot = (!SPLIT || kStage > part + kCnt) ? kStage : part + kCnt;
   const int waves = SPLIT ? S : tiles_per_wg;
-  // A second staging area per wave where it costs no workgroup per CU: the registers allow 12
-  // waves per CU, the 160 KB of LDS as many workgroups as fit.
-  Fp4Params p = p_in;
-  const int by_regs = std::max(1, 12 / waves);
-  const int wgs_one = std::min<int>(by_regs, (160 * 1024) / (waves * slot * 16));
-  const int wgs_two = std::min<int>(by_regs, (160 * 1024) / (waves * (slot + kStage) * 16));
-  p.two_areas = (SPLIT && wgs_two >= 1 && wgs_two == wgs_one && gemm_fp4_areas != 1) ? 1 : 0;
-  const size_t lds = (size_t)waves * (slot + (p.two_areas ? kStage : 0)) * 16;
+  const size_t lds = (size_t)waves * slot * 16;
   auto kern = gemm_fp4_kernel<TM, TN, PL, XNOR, OUT, SPLIT, HALF, CONV>;
   if (lds > 64 * 1024) {  // more than the default limit of dynamic LDS: raised once per device
     static bool raised[64] = {};
@@ -603,7 +592,6 @@ hipError_t launch_tile(const Fp4Params& p_in, int S, int tiles_per_wg, int64_t b
 
 }  // namespace
 int gemm_fp4_band = 0;  // 0 = automatic (16), else rows of tiles per band of the tile order
-int gemm_fp4_areas = 0;  // 1 = never a second staging area (tests of both forms)
 namespace {
 
 void set_tile_order(Fp4Params& p) {
