@@ -103,6 +103,21 @@ __device__ __forceinline__ v8i nibble_plane(const uint4& w, const uint4& hi, int
   return e;
 }
 
+// Nibble plane n of two bit planes at once: nibble i of a dword = (bit 4 i + n of p1) * 2 + (bit
+// 4 i + n of p0), the 2-bit value in the nibble's two low bits.
+__device__ __forceinline__ v8i nibble_pair(const uint4& p0, const uint4& p1, int n) {
+  const uint32_t a0[4] = {p0.x, p0.y, p0.z, p0.w}, a1[4] = {p1.x, p1.y, p1.z, p1.w};
+  v8i e;
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    const uint32_t lo = (a0[d] >> n) & 0x11111111u;
+    const uint32_t hi = n == 0 ? (a1[d] & 0x11111111u) << 1 : (a1[d] >> (n - 1)) & 0x22222222u;
+    e[d] = (int)(lo | hi);
+  }
+  e[4] = e[5] = e[6] = e[7] = 0;
+  return e;
+}
+
 // acc + popcount of four words: four v_bcnt_u32_b32, each adding onto the running count (written
 // as a sum of __builtin_popcount the compiler counts from zero and adds with extra instructions)
 __device__ __forceinline__ int add_popcount4(int acc, const uint4& w) {
@@ -343,21 +358,35 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
         hi[b] = make_uint4(w[b][g].x >> 3, w[b][g].y >> 3, w[b][g].z >> 3, w[b][g].w >> 3);
 #pragma unroll
       for (int n = 0; n < 4; ++n) {
-        v8i ea[NA], eb[TN];
-#pragma unroll
-        for (int b = 0; b < NA; ++b) ea[b] = nibble_plane(w[b][g], hi[b], n);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) eb[j] = nibble_plane(w[NA + j][g], hi[NA + j], n);
         // E8M0 block scales: planes 0 and 3 hold 0.5 (x 2), plane 1 holds 1, plane 2 holds 2 (x 1/2)
         const int sc = n == 1 ? 127 : (n == 2 ? 126 : 128);
+        v8i eb[TN];
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+        for (int j = 0; j < TN; ++j) eb[j] = nibble_plane(w[NA + j][g], hi[NA + j], n);
+        if constexpr (PL == 2) {
+          // two bit planes: one operand whose nibbles hold the 2-bit value itself (E2M1 codes 0 to 3
+          // = 0, 0.5, 1, 1.5; block scale 2), so a row block costs one MFMA per column block, not two
+          v8i ea[TM];
 #pragma unroll
-          for (int pl = 0; pl < PL; ++pl)
+          for (int i = 0; i < TM; ++i) ea[i] = nibble_pair(w[2 * i][g], w[2 * i + 1][g], n);
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-              acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ea[i * PL + pl], eb[j], acc[i][j], 4, 4, 0,
-                                                                         sc + pl, 0, sc);
+              acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ea[i], eb[j], acc[i][j], 4, 4, 0, 128, 0, sc);
+        } else {
+          v8i ea[NA];
+#pragma unroll
+          for (int b = 0; b < NA; ++b) ea[b] = nibble_plane(w[b][g], hi[b], n);
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int pl = 0; pl < PL; ++pl)
+#pragma unroll
+              for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ea[i * PL + pl], eb[j], acc[i][j], 4, 4, 0,
+                                                                           sc + pl, 0, sc);
+        }
       }
     }
   }
