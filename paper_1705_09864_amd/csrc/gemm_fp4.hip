@@ -9,9 +9,9 @@
 // it stands in its nibble (worth 0.5, 1 or 2 there; the nibble's top bit is shifted down) and
 // the block scale of each MFMA brings the product back to 1, so one 32-bit word of bits becomes
 // the four 8-nibble operand dwords of four MFMAs with five VALU instructions.  Products and
-// fp32 sums are exact integers below 2^24.  Bit planes of a k-bit activation are separate A
-// operands of the same rows whose block scale carries the plane's power of two: every plane
-// costs what a 1-bit operand costs, and the planes add up in the accumulator.
+// fp32 sums are exact integers below 2^24.  The two bit planes of a 2-bit activation are staged
+// as separate rows and folded into one operand while being expanded: a nibble then holds the
+// 2-bit value itself (E2M1 codes 0 to 3 = 0, 0.5, 1, 1.5; block scale 2).
 //
 // What bounds this kernel is not the matrix core but everything around it: the VALU work of
 // turning bits into nibbles, the loads, and fixed costs of a few-microsecond launch.  Hence:
