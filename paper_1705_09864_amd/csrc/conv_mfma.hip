@@ -327,11 +327,7 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
     };
     load_group(0, abuf[0]);
 #pragma unroll
-#ifdef BMX_WS_SKIP_MFMA
-    for (int g = 0; g < 1; ++g) {
-#else
     for (int g = 0; g < NG; ++g) {
-#endif
       if (g + 1 < NG) load_group(g + 1, abuf[(g + 1) & 1]);
 #pragma unroll
       for (int t = 0; t < G; ++t) {
@@ -402,9 +398,6 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
             const int mi = 8 * (v / 4) + (v % 4);
             const uint32_t off = lane_off + (uint32_t)mi * pitch;
             const float t = fmaf(4.0f, acc[i][0][v], c0[v]) - pb2;
-#ifdef BMX_WS_SKIP_STORES
-            if (t != 1.2345e30f) continue;
-#endif
             if (decltype(inside_tag)::value || (cur.valid && m0 + 32 * i + mi + 4 * h < p.O)) {
               // (written out: the compiler builds a 64-bit vector address for a non-temporal
               // store even from a uniform base and a 32-bit offset)
