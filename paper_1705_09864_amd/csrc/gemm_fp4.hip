@@ -539,10 +539,20 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
         for (int s = 0; s < 8; ++s) {
           const bool on = FULL || s < S;
           const half2_t lo = __builtin_bit_cast(half2_t, t[s].x), hi = __builtin_bit_cast(half2_t, t[s].y);
-          tot.x += on ? (float)lo[0] : 0.f;
-          tot.y += on ? (float)lo[1] : 0.f;
-          tot.z += on ? (float)hi[0] : 0.f;
-          tot.w += on ? (float)hi[1] : 0.f;
+          if constexpr (FULL) {
+            // v_dot2_f32_f16 with (1, 0) or (0, 1) picks a half, widens it and adds it in one
+            // instruction (exact: whole numbers up to 2048, fp32 accumulation)
+            const half2_t first = {(__fp16)1.0f, (__fp16)0.0f}, second = {(__fp16)0.0f, (__fp16)1.0f};
+            tot.x = __builtin_amdgcn_fdot2(lo, first, tot.x, false);
+            tot.y = __builtin_amdgcn_fdot2(lo, second, tot.y, false);
+            tot.z = __builtin_amdgcn_fdot2(hi, first, tot.z, false);
+            tot.w = __builtin_amdgcn_fdot2(hi, second, tot.w, false);
+          } else {
+            tot.x += on ? (float)lo[0] : 0.f;
+            tot.y += on ? (float)lo[1] : 0.f;
+            tot.z += on ? (float)hi[0] : 0.f;
+            tot.w += on ? (float)hi[1] : 0.f;
+          }
         }
       } else {
         float4 t[8];
