@@ -518,7 +518,11 @@ bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, cons
   p.nblocks = (int)ceil_div(P, 32);
   // (64 filters per workgroup, two accumulator sets sharing every expanded pixel word, is kept
   // for measurements only: it lost to 32 everywhere, 8.0 against 7.2 us on 16 x 64 x 56 x 56)
-  // (also tried at 36 words: the compiler needs more than 256 registers for it and spills 185)
+  // (also tried at 36 words.  As written the compiler runs the first filter block's whole chain
+  // before the second's and parks the second's operands in scratch, 185 registers' worth; with
+  // the two accumulators tied together after every group of steps it needs 167 registers and
+  // none in scratch, and then takes 8.9 us against 8.6 on 64 x 256 x 14 x 14 with 256 filters: the busiest SIMD
+  // has 144 MFMAs either way, and the workgroup's filter copy is twice as long)
   const int TM = (kwords == 9 && O > 32 && gemm_mfma_tile == 2 && !out_bits) ? 2 : 1;
   const int m_tiles = (int)ceil_div(O, 32 * TM);
   // Waves: one per block while all of them are resident at once (workgroups per CU as the
