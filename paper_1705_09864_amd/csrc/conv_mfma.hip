@@ -3,18 +3,20 @@
 // Paper: Sec. 3.1 (M = filters, N = batch * output pixels, K = kh * kw * C), result
 // out = alpha[o] * (K - 2 * popcount(filter xor patch)) (Sec. 2.2.2, Eq. 2).
 //
-// Same arithmetic as the matrix-core GEMM: with bits a, b in {0, 1},
-// K - 2 * pc(a xor b) = K - 2 * pc(a) - 2 * pc(b) + 4 * sum a * b, the sum on
-// v_mfma_scale_f32_32x32x64_f8f6f4 with both operands FP4 (E2M1): a set bit becomes a nibble
-// worth 0.5, 1 or 2 on the pixel side and the reciprocal on the filter side (see expand_pixel),
-// so products are 0 or 1 and the fp32 sums exact integers.
+// With the filter's bits read as f = +-1 and the patch's bits as x in {0, 1},
+// K - 2 * pc(filter xor patch) = sum f (2 x - 1) = (K - 2 * pc(filter)) + 2 * sum f x: the sum on
+// v_mfma_scale_f32_32x32x64_f8f6f4 with both operands FP4 (E2M1), the constant per filter
+// (stored behind the filter's bits by the weight pack), and no popcount of the patch at all.
+// A set pixel bit becomes a nibble worth 0.5, 1 or 2, a filter bit a nibble of the reciprocal
+// magnitude whose sign bit is the inverted bit (see expand_pixel), so products are 0 or +-1
+// and the fp32 sums exact integers.
 //
 // Shape.  A workgroup expands the bits of its 32 * TM filters into FP4 operands in LDS once
 // (a few dozen VALU instructions per thread), and every MFMA step reads its A operand from
 // there (16 bytes per lane), so filters cost no registers and no VALU work per pixel block.
 // A wave walks over blocks of 32 output pixels: it fetches the pixels' KW words (one MFMA step
 // of K = 64 consumes exactly one 64-bit word: lane (r, h) supplies half h of the word of pixel
-// r), expands them (5 VALU instructions per word, 1 for the popcount) and issues KW * TM
+// r), expands them (5 VALU instructions per word) and issues KW * TM
 // MFMAs.  Lanes run along pixels (operand B), so the NCHW stores are two 128-byte runs per
 // instruction.
 #include <algorithm>
@@ -53,7 +55,7 @@ struct WsParams {
   int O, HoWo, Wo, Hp, Wpp, Cw, stride;
   int nblocks, nchunks;  // blocks of 32 pixels in all; waves they are dealt out to (evenly)
   int blk_q, blk_r;      // nblocks / nchunks and nblocks % nchunks
-  int x4;                // K-words 2 q, 2 q + 1 are 16 consecutive, 16-byte aligned bytes of the image
+  int x4;                // 1: K-words 2 q, 2 q + 1 are 16 consecutive, 16-byte aligned bytes of the image; 2: 4 q .. 4 q + 3 are 32
   FastDiv div_howo, div_wo;
   int off[kMaxWsWords];  // word offset of K-word j relative to the pixel base
 };
@@ -71,8 +73,9 @@ __device__ __forceinline__ v8i widen(v4i e) {
 // d = bit 4 i + d).  The pixel side leaves planes 0 to 2 where they stand in their nibbles
 // (E2M1 codes 1, 2, 4 = 0.5, 1, 2) and shifts only the plane under the nibble's sign bit: five
 // VALU instructions instead of seven, in a kernel whose VALU work outweighs its MFMA time.  The
-// filter side, expanded once per workgroup, carries the reciprocal weights (2, 1, 0.5, 2), so
-// that every product of a set pixel bit and a set filter bit is 1.
+// filter side, expanded once per workgroup, carries the reciprocal magnitudes (2, 1, 0.5, 2)
+// with the sign of the filter value (bit set: +, bit clear: -, the nibble's sign bit being
+// the inverted filter bit), so that a set pixel bit contributes +1 or -1 and a clear one nothing.
 __device__ __forceinline__ v4i expand_pixel(uint32_t w) {
   v4i e;
   e[0] = (int)(w & 0x11111111u);
@@ -82,11 +85,12 @@ __device__ __forceinline__ v4i expand_pixel(uint32_t w) {
   return e;
 }
 __device__ __forceinline__ v4i expand_filter(uint32_t w) {
+  const uint32_t nw = ~w;
   v4i e;
-  e[0] = (int)((w & 0x11111111u) << 2);
-  e[1] = (int)(w & 0x22222222u);
-  e[2] = (int)((w >> 2) & 0x11111111u);
-  e[3] = (int)((w >> 1) & 0x44444444u);
+  e[0] = (int)(((nw << 3) & 0x88888888u) | 0x44444444u);
+  e[1] = (int)(((nw << 2) & 0x88888888u) | 0x22222222u);
+  e[2] = (int)(((nw << 1) & 0x88888888u) | 0x11111111u);
+  e[3] = (int)((nw & 0x88888888u) | 0x44444444u);
   return e;
 }
 
@@ -101,17 +105,36 @@ struct PixelBlock {
   int valid;
 };
 
+// Products of a wave-uniform factor and a per-lane factor that both stay below 2^24 (the
+// launcher checks) on the 24-bit multiplier: a full 32-bit product takes the vector ALU four
+// times as long, and every wave of the launch runs this at the same moment, ahead of its first
+// load.  (Written out: the compiler proves the range of few of these factors and falls back
+// to the full product for the rest.)
+__device__ __forceinline__ uint32_t mul24(uint32_t uniform, uint32_t lane) {
+  uint32_t r;
+  asm("v_mul_u32_u24 %0, %1, %2" : "=v"(r) : "s"(uniform), "v"(lane));
+  return r;
+}
+__device__ __forceinline__ uint32_t mad24(uint32_t uniform, uint32_t lane, uint32_t add) {
+  uint32_t r;
+  asm("v_mad_u32_u24 %0, %1, %2, %3" : "=v"(r) : "s"(uniform), "v"(lane), "v"(add));
+  return r;
+}
+
 __device__ __forceinline__ PixelBlock locate(const WsParams& p, int b, int r) {
   PixelBlock pb;
   const int n = b * 32 + r;
   const int nc = min(n, p.P - 1);  // lanes past the last pixel repeat it and store nothing
   const uint32_t img = fast_div((uint32_t)nc, p.div_howo);
-  const uint32_t rem = (uint32_t)nc - img * (uint32_t)p.HoWo;
+  const uint32_t rem = (uint32_t)nc - mul24((uint32_t)p.HoWo, img);
   const uint32_t ho = fast_div(rem, p.div_wo);
-  const uint32_t wo = rem - ho * (uint32_t)p.Wo;
-  pb.xoff = (((img * (uint32_t)p.Hp + ho * (uint32_t)p.stride) * (uint32_t)p.Wpp + wo * (uint32_t)p.stride) * (uint32_t)p.Cw) * 8u;
-  pb.obase = img * (uint32_t)p.O * (uint32_t)p.HoWo + rem;
-  pb.bword = ((img * (uint32_t)p.oHp + ho + (uint32_t)p.opad) * (uint32_t)p.oWp + wo + (uint32_t)p.opad) * (uint32_t)p.oCw;
+  const uint32_t wo = rem - mul24((uint32_t)p.Wo, ho);
+  const uint32_t row = mad24((uint32_t)p.Hp, img, mul24((uint32_t)p.stride, ho));  // row of the padded image stack
+  const uint32_t row_bytes = (uint32_t)(p.Wpp * p.Cw) * 8u, step_bytes = (uint32_t)(p.stride * p.Cw) * 8u;  // (wave-uniform)
+  pb.xoff = mad24(row_bytes, row, mul24(step_bytes, wo));
+  pb.obase = img * (uint32_t)(p.O * p.HoWo) + rem;
+  const uint32_t orow = mad24((uint32_t)p.oHp, img, ho + (uint32_t)p.opad);
+  pb.bword = mad24((uint32_t)p.oWp, orow, wo + (uint32_t)p.opad) * (uint32_t)p.oCw;
   pb.valid = n < p.P;
   return pb;
 }
@@ -134,28 +157,44 @@ struct Lds {
 }  // namespace
 unsigned long long* ws_stamps = nullptr;
 namespace {
-#define WS_STAMP(k) do { if (stamps && lane == 0) stamps[(size_t)((blockIdx.y * gridDim.x + blockIdx.x) * 4 + wave) * 8 + (k)] = __builtin_readcyclecounter(); } while (0)
+#define WS_STAMP(k) do { if (stamps && lane == 0) stamps[(size_t)((blockIdx.y * gridDim.x + blockIdx.x) * 4 + wave) * 16 + (k)] = __builtin_readcyclecounter(); } while (0)
 #define WS_STAMP_ARG , unsigned long long* stamps
+constexpr int kWs36Waves = 2;  // (the stamps need registers of their own)
+// (the constant 100 MHz counter, which all parts of the chip share: for times between waves)
+#define WS_REALTIME(k) do { if (stamps && lane == 0) stamps[(size_t)((blockIdx.y * gridDim.x + blockIdx.x) * 4 + wave) * 16 + (k)] = __builtin_amdgcn_s_memrealtime(); } while (0)
 #else
 #define WS_STAMP(k) do { } while (0)
+#define WS_REALTIME(k) do { } while (0)
 #define WS_STAMP_ARG
+constexpr int kWs36Waves = 3;  // waves per SIMD at 36 words, 16-byte pixel loads, fp32 or int32 results
 #endif
 
 // WPS: waves per SIMD the register allocation is held to.
 // BITS: the result leaves as packed sign bits (see WsParams::out_bits); the workgroups also
 // write the constant halo words of the output image.
 
-// X4: the pixel words are fetched 16 bytes at a time (an even number of channel words, so that
-// K-words 2 q and 2 q + 1 are neighbours in the image and 16-byte aligned).
-template <int KW, int TM, int WPS, bool BITS, bool X4>
+// X4: the pixel words are fetched 16 bytes at a time (1: an even number of channel words, so that
+// K-words 2 q and 2 q + 1 are neighbours in the image and 16-byte aligned; 2: a multiple of four
+// channel words, so that K-words 4 q .. 4 q + 3 are 32 consecutive bytes and the two half-waves'
+// addresses differ by 16 in every load: a uniform base per load and one lane offset for all).
+template <int KW, int TM, int WPS, bool BITS, int X4>
 __global__ void __launch_bounds__(256, WPS)
 conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
-  static_assert(!X4 || KW % 2 == 0, "pairs of words");
+  static_assert((!X4 || KW % 2 == 0) && (X4 != 2 || KW % 4 == 0), "pairs of words, or fours");
   // load instructions per block: two words per pixel each, or four
   constexpr int NI = X4 ? (KW + 3) / 4 : (KW + 1) / 2;
-  typedef typename std::conditional<X4, v4u, uint64_t>::type Staged;
+  typedef typename std::conditional<X4 != 0, v4u, uint64_t>::type Staged;
   constexpr int FS = Lds<KW>::kFilterStride;
   __shared__ __attribute__((aligned(16))) uint32_t filt[32 * TM * FS];
+  // The arguments span six or seven 64-byte lines that no cache holds when the kernel starts,
+  // and the compiler fetches them in groups of first use, one memory round trip per group.
+  // Fields at most 64 bytes apart, named in one statement here, bring all lines in with the
+  // first group; the groups that follow hit the scalar cache.
+  static_assert(offsetof(WsParams, Nimg) <= 64 && offsetof(WsParams, blk_q) - offsetof(WsParams, Nimg) <= 64 &&
+                    offsetof(WsParams, off) + 7 * 4 - offsetof(WsParams, blk_q) <= 64 &&
+                    sizeof(WsParams) - (offsetof(WsParams, off) + 39 * 4) <= 64 && kMaxWsWords > 39,
+                "a named field in every 64 bytes");
+  asm volatile("" ::"s"(p.Xp), "s"(p.Nimg), "s"(p.blk_q), "s"(p.off[7]), "s"(p.off[23]), "s"(p.off[39]));
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int r = lane & 31, h = lane >> 5;
@@ -167,6 +206,7 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
   const int b0 = cc * p.blk_q + min(cc, p.blk_r);
   const int b1 = cc < p.nchunks ? b0 + p.blk_q + (cc < p.blk_r ? 1 : 0) : b0;
   WS_STAMP(0);
+  WS_REALTIME(4);
 
   // words 2i + h of the pixel's patch, i = 0 .. NI-1 (the odd KW's last one only for h = 0);
   // X4: words 4i + 2h and 4i + 2h + 1 in one load
@@ -174,7 +214,9 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
     const char* const xbytes = (const char*)p.Xp;
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
-      if constexpr (X4) {
+      if constexpr (X4 == 2) {
+        st[i] = *(const v4u*)((xbytes + (size_t)((uint32_t)p.off[4 * i] * 8u)) + (size_t)(pb.xoff + 16u * (uint32_t)h));
+      } else if constexpr (X4 == 1) {
         const bool there = 4 * i + 2 < KW || h == 0;
         const uint32_t off = (uint32_t)(h ? p.off[4 * i + 2 < KW ? 4 * i + 2 : 0] : p.off[4 * i]) * 8u;
         st[i] = there ? *(const v4u*)(xbytes + (pb.xoff + off)) : v4u{0u, 0u, 0u, 0u};
@@ -217,19 +259,22 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
   constexpr int kUnits = 32 * TM * KW;
   constexpr int kCopies = (kUnits + 255) / 256;
   uint64_t buf[kCopies];
+  const uint32_t ld_bytes = (uint32_t)p.ld_dw * 4u;
 #pragma unroll
   for (int t = 0; t < kCopies; ++t) {
     const int c = min((int)threadIdx.x + 256 * t, kUnits - 1);
-    const int row = c / KW, j = c - row * KW;
+    const uint32_t row = (uint32_t)c / KW, j = (uint32_t)c - mul24(KW, row);
     // rows past the last filter repeat it; their results are never stored
-    buf[t] = *(const uint64_t*)(p.Wp + (int64_t)min(m0 + row, p.O - 1) * p.ld_dw + 2 * j);
+    // (a 32-bit byte offset from the uniform base: no 64-bit address arithmetic per load)
+    const uint32_t frow = (uint32_t)min(m0 + (int)row, p.O - 1);
+    buf[t] = *(const uint64_t*)((const char*)p.Wp + (size_t)mad24(ld_bytes, frow, 8u * j));
   }
   float myc0 = 0.0f, myalpha = 1.0f, mythr = 0.0f;  // thread t < 32 * TM carries the constants of row t
   if ((int)threadIdx.x < 32 * TM) {
-    const int m = min(m0 + (int)threadIdx.x, p.O - 1);
-    myc0 = __uint_as_float(p.Wp[(int64_t)m * p.ld_dw + p.c0_dw]);
-    if (p.alpha) myalpha = p.alpha[m];
-    if (BITS && p.thr) mythr = p.thr[m];
+    const uint32_t m = (uint32_t)min(m0 + (int)threadIdx.x, p.O - 1);
+    myc0 = *(const float*)((const char*)p.Wp + (size_t)(mul24(ld_bytes, m) + (uint32_t)p.c0_dw * 4u));
+    if (p.alpha) myalpha = *(const float*)((const char*)p.alpha + (size_t)(m * 4u));
+    if (BITS && p.thr) mythr = *(const float*)((const char*)p.thr + (size_t)(m * 4u));
   }
   // the first block's pixel words are requested right behind the filter words, which the
   // whole workgroup waits for at its barrier (waves of the last workgroup that have no block
@@ -270,10 +315,12 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
 #pragma unroll
     for (int t = 0; t < kCopies; ++t) {
       const int c = (int)threadIdx.x + 256 * t;
-      const int row = c / KW, j = c - row * KW;
+      // word j of row c / KW at dword row * FS + 8 j = 8 c + 4 row, as FS = 8 KW + 4
+      static_assert(FS == 8 * KW + 4, "the index below");
+      const int at = 8 * c + 4 * (c / KW);
       if (c < kUnits) {
-        *(v4i_alias*)(filt + row * FS + 8 * j) = expand_filter((uint32_t)buf[t]);
-        *(v4i_alias*)(filt + row * FS + 8 * j + 4) = expand_filter((uint32_t)(buf[t] >> 32));
+        *(v4i_alias*)(filt + at) = expand_filter((uint32_t)buf[t]);
+        *(v4i_alias*)(filt + at + 4) = expand_filter((uint32_t)(buf[t] >> 32));
       }
     }
     if ((int)threadIdx.x < 32 * TM) {
@@ -301,7 +348,7 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
     // split into dword pairs, the lanes of eight rows would meet on four banks)
     int fbase = r * (FS / 4) + h;
     asm volatile("" : "+v"(fbase));
-    int pb = 0;
+    if (b == b0) WS_STAMP(10);
     // Two accumulator chains per filter block, steps alternating between them and added at the
     // end: an MFMA that adds onto the result of the one before it can only start when that one
     // has finished, twice the time it takes to issue.  The filter operands are read a group of
@@ -333,7 +380,6 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
       for (int t = 0; t < G; ++t) {
         const int j = g * G + t;
         if (j < KW) {
-          pb += __builtin_popcount(raw[j]);
           const v8i eb = widen(expand_pixel(raw[j]));
 #pragma unroll
           for (int i = 0; i < TM; ++i)
@@ -345,18 +391,18 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
       // the block (the scheduler's preference) they would hold 8 * KW registers at once
       __builtin_amdgcn_sched_barrier(0);
     }
+    if (b == b0) WS_STAMP(8);
     if constexpr (CH == 2) {
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[i][0][e] += acc[i][1][e];  // exact: whole numbers below 2^24
     }
-    pb += __shfl_xor(pb, 32);
-    // out = alpha * (K - 2 pc(filter) - 2 pc(patch) + 4 * sum): exact integers in fp32 up to
-    // the single rounding of the alpha product.  (The row constants of all result registers
-    // in one batch of LDS reads: read one by one inside the store loop, every value would pay
-    // a full LDS round trip.)
-    const float pb2 = 2.0f * (float)pb;
+    if (b == b0) WS_STAMP(9);
+    // out = alpha * ((K - 2 pc(filter)) + 2 * sum): exact integers in fp32 up to the single
+    // rounding of the alpha product.  (The row constants of all result registers in one batch
+    // of LDS reads: read one by one inside the store loop, every value would pay a full LDS
+    // round trip.)
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
       float c0[16], al[16];
@@ -374,7 +420,7 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
         for (int v = 0; v < 16; ++v) {
           const int mi = 8 * (v / 4) + 4 * h + (v % 4);
           const float th = __uint_as_float(filt[(32 * i + mi) * FS + 8 * KW + 2]);
-          const float t = fmaf(4.0f, acc[i][0][v], c0[v]) - pb2;
+          const float t = fmaf(2.0f, acc[i][0][v], c0[v]);
           if (al[v] * t >= th && m0 + 32 * i + mi < p.O) mask |= 1u << mi;
         }
         mask |= (uint32_t)__shfl_xor((int)mask, 32);
@@ -397,7 +443,7 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
           for (int v = 0; v < 16; ++v) {
             const int mi = 8 * (v / 4) + (v % 4);
             const uint32_t off = lane_off + (uint32_t)mi * pitch;
-            const float t = fmaf(4.0f, acc[i][0][v], c0[v]) - pb2;
+            const float t = fmaf(2.0f, acc[i][0][v], c0[v]);
             if (decltype(inside_tag)::value || (cur.valid && m0 + 32 * i + mi + 4 * h < p.O)) {
               // (written out: the compiler builds a 64-bit vector address for a non-temporal
               // store even from a uniform base and a 32-bit offset)
@@ -426,14 +472,15 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
 #ifdef BMX_WS_STAMPS
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   WS_STAMP(7);
+  WS_REALTIME(5);
 #endif
 }
 
-template <int KW, int TM, int WPS, bool BITS, bool X4>
+template <int KW, int TM, int WPS, bool BITS, int X4>
 void launch_ws_form(const WsParams& p, int m_tiles, hipStream_t s) {
   const int chunks = p.nchunks;
   note_kernel("conv_mfma_ws_kernel<%d,%d,%d,%s%s> grid %d x %d x 256", KW, TM, WPS, BITS ? "true" : "false",
-              X4 ? ",x4" : "", (int)ceil_div(chunks, 4), m_tiles);
+              X4 == 2 ? ",x4 runs" : X4 ? ",x4" : "", (int)ceil_div(chunks, 4), m_tiles);
 #ifdef BMX_WS_STAMPS
   hipLaunchKernelGGL((conv_mfma_ws_kernel<KW, TM, WPS, BITS, X4>), dim3((unsigned)ceil_div(chunks, 4), (unsigned)m_tiles),
                      dim3(256), 0, s, p, ws_stamps);
@@ -448,9 +495,12 @@ template <int KW, int TM, int WPS, bool BITS = false, int WPS_X4 = WPS>
 void launch_ws(const WsParams& p, int m_tiles, hipStream_t s) {
   // 16-byte pixel loads where the word count can come from an even number of channel words
   if constexpr (KW == 18 || KW == 36 || KW == 50) {
-    if (p.x4) return launch_ws_form<KW, TM, WPS_X4, BITS, true>(p, m_tiles, s);
+    if constexpr (KW == 36) {
+      if (p.x4 == 2) return launch_ws_form<KW, TM, WPS_X4, BITS, 2>(p, m_tiles, s);
+    }
+    if (p.x4) return launch_ws_form<KW, TM, WPS_X4, BITS, 1>(p, m_tiles, s);
   }
-  launch_ws_form<KW, TM, WPS, BITS, false>(p, m_tiles, s);
+  launch_ws_form<KW, TM, WPS, BITS, 0>(p, m_tiles, s);
 }
 
 }  // namespace
@@ -469,6 +519,12 @@ bool conv_mfma_ws_takes(int Nimg, int C, int H, int W, int O, int KH, int KW, in
   // packed image, output and packed-bit output are addressed with 32-bit byte offsets
   if ((int64_t)Nimg * (H + 2 * pad) * (W + 2 * pad) * Cw * 8 >= ((int64_t)1 << 32)) return false;
   if (((int64_t)Nimg * O + 64) * Ho * Wo * 4 >= ((int64_t)1 << 32)) return false;
+  // the packed filters as well, and the factors of the kernel's 24-bit products
+  if ((int64_t)(O + 64) * 2 * conv_weight_row_words(kwords) * 4 >= ((int64_t)1 << 32)) return false;
+  const int64_t lim24 = (int64_t)1 << 24;
+  if ((int64_t)Nimg * (H + 2 * pad) >= lim24 || (int64_t)(W + 2 * pad) * Cw * 8 >= lim24 || (int64_t)stride * Cw * 8 >= lim24 ||
+      (int64_t)Ho * Wo >= lim24 || (int64_t)Nimg * (Ho + 2 * out_pad) >= lim24 || (int64_t)Wo + 2 * out_pad >= lim24 || O >= lim24)
+    return false;
   if ((int64_t)Nimg * (Ho + 2 * out_pad) * (Wo + 2 * out_pad) * words_for(O) * 8 >= ((int64_t)1 << 32)) return false;
   return ceil_div(O, 32) <= 65535;
 }
@@ -531,7 +587,8 @@ bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, cons
   // blocks dealt out evenly: every workgroup copies its filters once and no CU is left with a
   // second round of a few workgroups.
   p.x4 = ((Cw & 1) == 0 && ((uintptr_t)Xp & 15) == 0 && conv_ws_x4 != 1) ? 1 : 0;
-  const int per_simd = kwords == 9 ? 4 : kwords <= 27 ? 3 : (kwords == 36 && p.x4 && !out_bits) ? 3 : 2;
+  if (p.x4 && (Cw & 3) == 0 && conv_ws_x4 != 2) p.x4 = 2;
+  const int per_simd = kwords == 9 ? 4 : kwords <= 27 ? 3 : (kwords == 36 && p.x4 && !out_bits) ? kWs36Waves : 2;
   const int resident_waves = 256 * 4 * per_simd;
   p.nchunks = (int)std::min<int64_t>(p.nblocks, std::max(1, resident_waves / m_tiles));
   if (conv_filters_per_wave >= 100) p.nchunks = std::min(p.nblocks, conv_filters_per_wave);  // (tuning hook reused: chunks)
@@ -560,7 +617,7 @@ bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, cons
   } else if (kwords == 50) {
     launch_ws<50, 1, 2>(p, m_tiles, s);
   } else {
-    launch_ws<36, 1, 2, false, 3>(p, m_tiles, s);
+    launch_ws<36, 1, 2, false, kWs36Waves>(p, m_tiles, s);
   }
   *err = hipGetLastError();
   return true;

@@ -316,7 +316,7 @@ def test_config4_conv_full(stride):
     # automatic (the short-K FP4 matrix-core kernel, 36 words of K), register-stationary
     # xor/popcount kernel, xor/popcount GEMM kernel, GEMM-shaped FP4 and int8 matrix-core kernels,
     # the 64 x 64 per wave FP4 kernel's convolution form
-    for choice in (dict(), dict(k14=1), dict(k5=1), dict(k5=2), dict(k5=4), dict(k5=4, k7=2), dict(k5=6)):
+    for choice in (dict(), dict(k14=1), dict(k14=2), dict(k5=1), dict(k5=2), dict(k5=4), dict(k5=4, k7=2), dict(k5=6)):
         with tuned(**choice):
             got = run_conv(c["x"], c["w"], stride, 1, alpha=alpha)
             assert got.shape == (64, 256, 14 // stride, 14 // stride)
@@ -593,7 +593,9 @@ def test_conv_short_k_matrix_core(N, C, H, W, O, s, p):
     ri, rf = oracle.binary_conv2d(x, w, s, p, alpha)
     # (narrow = 1: pixel words fetched 8 bytes at a time also where an even number of channel
     # words lets the kernel fetch 16)
-    for tile, per_wave, narrow in ((0, 0, 0), (2, 3, 0), (0, 7, 0), (0, 101, 0), (0, 0, 1), (0, 3, 1)):
+    # (narrow = 2: 16 at a time, but not in the form for channel-word counts that are multiples
+    # of four, which those cases take by themselves)
+    for tile, per_wave, narrow in ((0, 0, 0), (2, 3, 0), (0, 7, 0), (0, 101, 0), (0, 0, 1), (0, 3, 1), (0, 0, 2), (0, 3, 2)):
         with tuned(k5=5, k9=tile, k1=per_wave, k14=narrow):
             np.testing.assert_array_equal(run_conv(x, w, s, p, integer_out=True), ri)
             assert_f32_close(run_conv(x, w, s, p, alpha=alpha), rf)
@@ -766,14 +768,17 @@ def test_conv_packed_bits(N, C, H, W, O, k, s, p, out_pad):
     Wp = B.pack_conv_weights(dev(w))
     xp = B.pack_nchw(dev(x), p)
     shape = (N, Ho + 2 * out_pad, Wo + 2 * out_pad, (O + 63) // 64)
-    for al, th, ref in ((alpha, thr, rf >= thr[None, :, None, None]),
-                        (alpha, None, rf >= 0.0),
-                        (None, thr, ri.astype(np.float32) >= thr[None, :, None, None]),
-                        (None, None, ri >= 0)):
-        out = dev(np.full(shape, -1, dtype=np.int64))
-        B.binary_conv2d_bits(xp, C, Wp, O, k, k, s, p, alpha=None if al is None else dev(al),
-                             thr=None if th is None else dev(th), out_pad=out_pad, out=out)
-        np.testing.assert_array_equal(host_u64(out), packed_image(ref, out_pad))
+    # (four channel words: also the general form of the 16-byte pixel loads)
+    for narrow in ((0, 2) if k == 3 and 192 < C <= 256 else (0,)):
+        for al, th, ref in ((alpha, thr, rf >= thr[None, :, None, None]),
+                            (alpha, None, rf >= 0.0),
+                            (None, thr, ri.astype(np.float32) >= thr[None, :, None, None]),
+                            (None, None, ri >= 0)):
+            out = dev(np.full(shape, -1, dtype=np.int64))
+            with tuned(k14=narrow):
+                B.binary_conv2d_bits(xp, C, Wp, O, k, k, s, p, alpha=None if al is None else dev(al),
+                                     thr=None if th is None else dev(th), out_pad=out_pad, out=out)
+            np.testing.assert_array_equal(host_u64(out), packed_image(ref, out_pad))
 
 
 @pytest.mark.parametrize("N,C,H,W,O1,O2,s1", [(2, 64, 20, 20, 64, 48, 1), (3, 100, 17, 13, 130, 70, 2),
