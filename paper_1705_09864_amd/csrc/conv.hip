@@ -236,7 +236,7 @@ FastDiv make_fast_div(uint32_t d) {
 
 int conv_filters_per_wave = 0;  // 0 = automatic; settable for tuning sweeps
 int conv_path = 0;              // 0 = automatic, 1 = stationary, 2 = GEMM kernel, 3 = general
-int conv_ws_x4 = 0;             // 1 = the short-K matrix-core kernel never fetches pixel words 16 bytes at a time; 2 = never in its form for runs of four channel words
+int conv_ws_x4 = 0;             // 1 = the short-K matrix-core kernel never fetches pixel words 16 bytes at a time; 2 = never in its form for runs of four channel words; 3 = never in its form with one block per wave
 
 hipError_t launch_binary_conv2d(const uint64_t* Xp, int N, int C, int H, int W, const uint64_t* Wp,
                                 int O, int KH, int KW, int stride, int pad, const float* alpha,

@@ -177,7 +177,11 @@ constexpr int kWs36Waves = 3;  // waves per SIMD at 36 words, 16-byte pixel load
 // K-words 2 q and 2 q + 1 are neighbours in the image and 16-byte aligned; 2: a multiple of four
 // channel words, so that K-words 4 q .. 4 q + 3 are 32 consecutive bytes and the two half-waves'
 // addresses differ by 16 in every load: a uniform base per load and one lane offset for all).
-template <int KW, int TM, int WPS, bool BITS, int X4>
+// ONE: every wave has exactly one block (the launcher's choice when all of them are resident
+// at once at four waves per SIMD): nothing is fetched ahead, one accumulator chain (the other
+// waves of the SIMD fill the matrix pipe while a wave waits for its own last MFMA), operands
+// two steps ahead; which is what lets the wave live in 128 registers.
+template <int KW, int TM, int WPS, bool BITS, int X4, bool ONE = false>
 __global__ void __launch_bounds__(256, WPS)
 conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
   static_assert((!X4 || KW % 2 == 0) && (X4 != 2 || KW % 4 == 0), "pairs of words, or fours");
@@ -340,8 +344,11 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
     transpose(st, raw);
     // the next block's words are requested before this block is multiplied (after the wave's
     // last block there is nothing to request)
-    const PixelBlock nxt = locate(p, min(b + 1, b1 - 1), r);
-    if (b + 1 < b1) fetch(nxt, st);
+    PixelBlock nxt = cur;
+    if constexpr (!ONE) {
+      nxt = locate(p, min(b + 1, b1 - 1), r);
+      if (b + 1 < b1) fetch(nxt, st);
+    }
     // (the filter reads below are the same in every trip: an opaque copy of their base keeps
     // the compiler from hoisting all of them out of the loop and into registers for good)
     // (counted in 16-byte pieces from the aligned base, so that the read is one ds_read_b128:
@@ -355,8 +362,8 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
     // steps ahead: read where they are used, every pair of MFMAs would wait out an LDS round trip.
     // (with two filter blocks per wave their two chains are independent already, and registers
     // are short: one chain each, operands two steps ahead)
-    constexpr int CH = TM == 1 ? 2 : 1;
-    constexpr int G = (KW > 36 || TM == 2) ? 2 : 4, NG = (KW + G - 1) / G;
+    constexpr int CH = (TM == 1 && !ONE) ? 2 : 1;
+    constexpr int G = (KW > 36 || TM == 2 || ONE) ? 2 : 4, NG = (KW + G - 1) / G;
     v16f acc[TM][CH];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -466,6 +473,7 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
         }
       }
     }
+    if constexpr (ONE) break;
     cur = nxt;
   }
   WS_STAMP(6);
@@ -476,16 +484,16 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
 #endif
 }
 
-template <int KW, int TM, int WPS, bool BITS, int X4>
+template <int KW, int TM, int WPS, bool BITS, int X4, bool ONE = false>
 void launch_ws_form(const WsParams& p, int m_tiles, hipStream_t s) {
   const int chunks = p.nchunks;
-  note_kernel("conv_mfma_ws_kernel<%d,%d,%d,%s%s> grid %d x %d x 256", KW, TM, WPS, BITS ? "true" : "false",
-              X4 == 2 ? ",x4 runs" : X4 ? ",x4" : "", (int)ceil_div(chunks, 4), m_tiles);
+  note_kernel("conv_mfma_ws_kernel<%d,%d,%d,%s%s%s> grid %d x %d x 256", KW, TM, WPS, BITS ? "true" : "false",
+              X4 == 2 ? ",x4 runs" : X4 ? ",x4" : "", ONE ? ",one block" : "", (int)ceil_div(chunks, 4), m_tiles);
 #ifdef BMX_WS_STAMPS
-  hipLaunchKernelGGL((conv_mfma_ws_kernel<KW, TM, WPS, BITS, X4>), dim3((unsigned)ceil_div(chunks, 4), (unsigned)m_tiles),
+  hipLaunchKernelGGL((conv_mfma_ws_kernel<KW, TM, WPS, BITS, X4, ONE>), dim3((unsigned)ceil_div(chunks, 4), (unsigned)m_tiles),
                      dim3(256), 0, s, p, ws_stamps);
 #else
-  hipLaunchKernelGGL((conv_mfma_ws_kernel<KW, TM, WPS, BITS, X4>), dim3((unsigned)ceil_div(chunks, 4), (unsigned)m_tiles),
+  hipLaunchKernelGGL((conv_mfma_ws_kernel<KW, TM, WPS, BITS, X4, ONE>), dim3((unsigned)ceil_div(chunks, 4), (unsigned)m_tiles),
                      dim3(256), 0, s, p);
 #endif
 }
@@ -591,6 +599,12 @@ bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, cons
   const int per_simd = kwords == 9 ? 4 : kwords <= 27 ? 3 : (kwords == 36 && p.x4 && !out_bits) ? kWs36Waves : 2;
   const int resident_waves = 256 * 4 * per_simd;
   p.nchunks = (int)std::min<int64_t>(p.nblocks, std::max(1, resident_waves / m_tiles));
+  // At 36 words over four channel words: when a wave per block fits at four waves per SIMD but
+  // not at three, the form that holds one block in 128 registers; no wave is then left with
+  // a second block to run alone after the others have gone.
+  const bool one36 = kwords == 36 && p.x4 == 2 && !out_bits && TM == 1 && p.nchunks < p.nblocks &&
+                     (int64_t)p.nblocks * m_tiles <= 256 * 4 * 4 && conv_filters_per_wave == 0 && conv_ws_x4 != 3;
+  if (one36) p.nchunks = p.nblocks;
   if (conv_filters_per_wave >= 100) p.nchunks = std::min(p.nblocks, conv_filters_per_wave);  // (tuning hook reused: chunks)
   else if (conv_filters_per_wave > 0) p.nchunks = (int)ceil_div(p.nblocks, conv_filters_per_wave);  // (or blocks per wave)
   p.blk_q = p.nblocks / p.nchunks;
@@ -616,6 +630,8 @@ bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, cons
     launch_ws<49, 1, 2>(p, m_tiles, s);
   } else if (kwords == 50) {
     launch_ws<50, 1, 2>(p, m_tiles, s);
+  } else if (one36) {
+    launch_ws_form<36, 1, 4, false, 2, true>(p, m_tiles, s);
   } else {
     launch_ws<36, 1, 2, false, kWs36Waves>(p, m_tiles, s);
   }

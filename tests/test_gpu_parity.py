@@ -316,7 +316,7 @@ def test_config4_conv_full(stride):
     # automatic (the short-K FP4 matrix-core kernel, 36 words of K), register-stationary
     # xor/popcount kernel, xor/popcount GEMM kernel, GEMM-shaped FP4 and int8 matrix-core kernels,
     # the 64 x 64 per wave FP4 kernel's convolution form
-    for choice in (dict(), dict(k14=1), dict(k14=2), dict(k5=1), dict(k5=2), dict(k5=4), dict(k5=4, k7=2), dict(k5=6)):
+    for choice in (dict(), dict(k14=1), dict(k14=2), dict(k14=3), dict(k5=1), dict(k5=2), dict(k5=4), dict(k5=4, k7=2), dict(k5=6)):
         with tuned(**choice):
             got = run_conv(c["x"], c["w"], stride, 1, alpha=alpha)
             assert got.shape == (64, 256, 14 // stride, 14 // stride)
@@ -575,6 +575,7 @@ WS_CONV_CASES = [
     (64, 256, 14, 14, 40, 2, 1),
     (2, 192, 14, 14, 70, 1, 1),
     (3, 130, 9, 11, 33, 2, 1),
+    (70, 200, 14, 14, 250, 1, 1),     # 429 blocks x 8 filter tiles: a wave per block at four waves per SIMD
 ]
 
 
@@ -595,7 +596,9 @@ def test_conv_short_k_matrix_core(N, C, H, W, O, s, p):
     # words lets the kernel fetch 16)
     # (narrow = 2: 16 at a time, but not in the form for channel-word counts that are multiples
     # of four, which those cases take by themselves)
-    for tile, per_wave, narrow in ((0, 0, 0), (2, 3, 0), (0, 7, 0), (0, 101, 0), (0, 0, 1), (0, 3, 1), (0, 0, 2), (0, 3, 2)):
+    # (narrow = 3: never the form that holds one block per wave in 128 registers)
+    for tile, per_wave, narrow in ((0, 0, 0), (2, 3, 0), (0, 7, 0), (0, 101, 0), (0, 0, 1), (0, 3, 1), (0, 0, 2), (0, 3, 2),
+                                   (0, 0, 3)):
         with tuned(k5=5, k9=tile, k1=per_wave, k14=narrow):
             np.testing.assert_array_equal(run_conv(x, w, s, p, integer_out=True), ri)
             assert_f32_close(run_conv(x, w, s, p, alpha=alpha), rf)
@@ -746,7 +749,7 @@ def packed_image(bits_nchw, out_pad):
 
 CONV_BITS_CASES = [c + (op,) for c, op in zip(
     [(N, C, H, W, O, 3, s, p) for (N, C, H, W, O, s, p) in WS_CONV_CASES] + CONV_CASES,
-    [1, 0, 2, 1, 3, 1, 0, 1, 2, 1, 1, 6, 1, 2] + [1, 0, 1, 2, 1, 0, 1, 1, 3, 1, 1, 0, 2])]
+    [1, 0, 2, 1, 3, 1, 0, 1, 2, 1, 1, 6, 1, 2, 1] + [1, 0, 1, 2, 1, 0, 1, 1, 3, 1, 1, 0, 2])]
 
 
 @pytest.mark.parametrize("N,C,H,W,O,k,s,p,out_pad", CONV_BITS_CASES)
