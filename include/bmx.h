@@ -283,7 +283,8 @@ size_t bmx_workspace_bytes(int op, const int64_t* dims, int ndims);
  *          64 x 64 per wave and operands staged through LDS whatever the size
  *   key 10 K-split waves of the latter kernel, key 11 = 2: its partial tiles cross LDS as fp32
  *          even where fp16 pairs would be exact, key 12 rows of tiles per band of its tile order
- *          (automatic: 16)
+ *          (automatic: 16), key 13 = 1: never its form with 128 x 64 of C per wave, 2: that form
+ *          wherever it exists (xnor products without a K split, int32 or fp32 results)
  *   key 14 = 1: the short-K matrix-core convolution kernel fetches pixel words 8 bytes at a time
  *          even where 16 would do; 2: 16 at a time, but never in the form for channel-word
  *          counts that are multiples of four; 3: never in the form that holds one block per wave

@@ -86,7 +86,7 @@ extern "C" {
 int bmx_tune_set(int key, int value) {
   if (key == 0) {  // everything back to the automatic choice
     bmx::conv_filters_per_wave = bmx::gemm_tune_rows = bmx::gemm_tune_ksplit = bmx::gemm_tune_order = 0;
-    bmx::conv_path = bmx::gemm_engine = bmx::gemm_mfma_ksplit = bmx::gemm_mfma_tile = bmx::gemm_fp4_split = bmx::gemm_fp4_half = bmx::gemm_fp4_band = bmx::conv_ws_x4 = 0;
+    bmx::conv_path = bmx::gemm_engine = bmx::gemm_mfma_ksplit = bmx::gemm_mfma_tile = bmx::gemm_fp4_split = bmx::gemm_fp4_half = bmx::gemm_fp4_band = bmx::gemm_fp4_tall = bmx::conv_ws_x4 = 0;
     return BMX_OK;
   }
   if (key == 1) bmx::conv_filters_per_wave = value;
@@ -100,6 +100,7 @@ int bmx_tune_set(int key, int value) {
   else if (key == 10) bmx::gemm_fp4_split = value;
   else if (key == 11) bmx::gemm_fp4_half = value;
   else if (key == 12) bmx::gemm_fp4_band = value;
+  else if (key == 13) bmx::gemm_fp4_tall = value;
   else if (key == 14) bmx::conv_ws_x4 = value;
   else return BMX_ERR_UNSUPPORTED;
   return BMX_OK;

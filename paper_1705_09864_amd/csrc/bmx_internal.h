@@ -125,7 +125,7 @@ bool launch_gemm_fp4(const uint64_t* A, int64_t lda_w, int planes, const int32_t
 bool launch_conv_fp4(const uint64_t* Xp, int Nimg, int C, int H, int W, const uint64_t* Wp, int O, int KH, int KW,
                      int stride, int pad, const float* alpha, int32_t* out_i32, float* out_f32, hipStream_t s,
                      hipError_t* err);
-extern int gemm_fp4_split, gemm_fp4_half, gemm_fp4_band;
+extern int gemm_fp4_split, gemm_fp4_half, gemm_fp4_band, gemm_fp4_tall;
 bool launch_plane_gemm_mfma(const uint64_t* planes_rows, int64_t lda_w, int bits, const int32_t* rowsum,
                             const uint64_t* Wb, int64_t ldb_w, int M, int N, int K, int32_t* S_out,
                             float* out_f32, int64_t ldo, hipStream_t s, hipError_t* err);

@@ -280,7 +280,7 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
   // loads they do not disturb the count of loads in flight that the main loop relies on).  Per column of
   // this lane (column 32 j + r): alpha and the threshold of the sign decision; per row of the
   // tile, row m0 + l in lane l: the row sum of the plane form, alpha of the convolution form.
-  static_assert(TM == 2, "one lane per row of the tile");
+  static_assert(TM == 2 || (XNOR && !SPLIT && !CONV), "one lane per row of the tile");
   // (plain variables, not arrays: indexed by a run-time j in the reduction below, an array is
   // put into scratch memory, whose every access also waits for the stores issued before it)
   static_assert(TN == 2, "two column blocks");
@@ -511,7 +511,7 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
     // its own results out of other lanes' registers
     int pa_tot = rowsum_l, pb_tot = 0;  // (plane form: the row sum stands where the row count would)
     if (XNOR) {
-      static_assert(TM == 2 && TN == 2, "one lane per row and per column of the tile");
+      static_assert((TM == 2 && TN == 2) || !SPLIT, "one lane per row and per column of the tile");
       int ca[8], cb8[8];
 #pragma unroll
       for (int s = 0; s < 8; ++s) {
@@ -659,6 +659,7 @@ hipError_t launch_split(const Fp4Params& p, int S, int tiles_per_wg, int64_t blo
 }  // namespace
 
 int gemm_fp4_split = 0;  // 0 = automatic; settable for sweeps and for the tests of every split
+int gemm_fp4_tall = 0;   // 0 = automatic; 1 = never 128 x 64 of C per wave; 2 = wherever the form exists
 
 // Takes the problem when both operands have 16-byte aligned rows, sums stay exact in fp32, the
 // operands can be addressed with 32-bit byte offsets, and there are enough 64 x 64 tiles for
@@ -717,6 +718,24 @@ bool launch_gemm_fp4(const uint64_t* A, int64_t lda_w, int planes, const int32_t
   p.g_base = ngroups / S;
   p.g_rem = ngroups - p.g_base * S;
   const int tiles_per_wg = 4;
+  // Chip-filling xnor products without a split: 128 x 64 of C per wave.  Six expanded operand
+  // blocks then serve eight MFMAs instead of four serving four: 4.5 VALU instructions per MFMA
+  // instead of 6, in a loop that the vector ALU's issue slot bounds, not the matrix pipe.  The
+  // form needs 231 registers, so two waves share a SIMD where three of the square form do, and
+  // the two come out level except where a SIMD works through many tiles (half as many tile
+  // starts and ends per MFMA): 8192^3 214 against 222 us, 4096^3 38.6 against 34.1 us.  Taken
+  // from four rounds of tiles on.
+  if (planes == 1 && rowsum == nullptr && !C_bits && S == 1 && gemm_fp4_tall != 1 &&
+      (gemm_fp4_tall == 2 || ceil_div(M, 128) * (int64_t)tiles_n >= 8192) &&
+      ((int64_t)M + 128) * ldc < ((int64_t)1 << 31)) {
+    p.tiles_m = (int)ceil_div(M, 128);
+    set_tile_order(p);
+    p.tiles_per_xcd = (int)ceil_div(ceil_div((int64_t)p.tiles_m * tiles_n, tiles_per_wg), 8);
+    const int64_t tall_blocks = 8 * (int64_t)p.tiles_per_xcd;
+    if (C_i32) *err = launch_tile<4, 2, 1, true, kOutI32, false, false, false>(p, 1, tiles_per_wg, tall_blocks, s);
+    else *err = launch_tile<4, 2, 1, true, kOutF32, false, false, false>(p, 1, tiles_per_wg, tall_blocks, s);
+    return true;
+  }
   const int64_t wgs = S > 1 ? tiles : ceil_div(tiles, tiles_per_wg);
   p.tiles_per_xcd = (int)ceil_div(wgs, 8);
   const int64_t blocks = 8 * (int64_t)p.tiles_per_xcd;

@@ -933,16 +933,56 @@ def test_gemm_fp4_chip_filling_problem_exact():
     with tuned(k7=1):
         ref = B.xnor_gemm(Ad, Bd, K)
         assert "gemm_kernel" in B.last_kernel()
-    for band in (0, 3, 1000):                      # tile order: automatic bands, ragged bands, none
-        with tuned(k12=band):
+    # tile order: automatic bands, ragged bands, none; tile: 64 x 64 per wave (the automatic
+    # choice at this size) and 128 x 64
+    for band, tall in ((0, 0), (3, 0), (1000, 0), (0, 2), (3, 2)):
+        with tuned(k12=band, k13=tall):
             for rep in range(6):
                 got = B.xnor_gemm(Ad, Bd, K)
-                assert "gemm_fp4_kernel" in B.last_kernel() and "K split 1," in B.last_kernel()
-                assert torch.equal(got, ref), "band %d repetition %d: %d elements differ" % (
-                    band, rep, int((got != ref).sum()))
+                assert "gemm_fp4_kernel<%d,2,1" % (4 if tall else 2) in B.last_kernel() and "K split 1," in B.last_kernel()
+                assert torch.equal(got, ref), "band %d tall %d repetition %d: %d elements differ" % (
+                    band, tall, rep, int((got != ref).sum()))
     rows = np.sort(rng.choice(M, size=96, replace=False))
     want = oracle.xnor_gemm(A[rows].view(np.uint64), Bm.view(np.uint64), K)
     np.testing.assert_array_equal(ref[torch.from_numpy(rows).cuda()].cpu().numpy(), want)
+
+
+def test_gemm_fp4_tall_tile():
+    """The same kernel with 128 x 64 of C per wave (no K split; the automatic choice only for
+    chip-filling products), forced on small and ragged problems: fewer rows than a tile, ragged
+    tiles in M and N, rows that end inside a 64-byte segment, strides wider than the rows with
+    garbage behind them, int32, xnor-count and scaled fp32 results."""
+    rng = np.random.default_rng(1313)
+    with tuned(k7=5, k10=1, k13=2):
+        for (M, N, K) in [(1, 1, 1), (37, 70, 5000), (127, 64, 1024), (128, 129, 3072 + 64), (129, 64, 63),
+                          (65, 33, 1025), (130, 200, 2048 + 128), (700, 801, 1100), (256, 512, 9216),
+                          (300, 190, 64 * 7), (33, 65, 64 * 9), (513, 128, 64 * 10), (5, 300, 64 * 11),
+                          (70, 70, 64 * 12 + 1), (257, 64, 64 * 13), (64, 65, 64 * 14), (191, 66, 64 * 15)]:
+            a = rng.standard_normal((M, K)).astype(np.float32)
+            b = rng.standard_normal((N, K)).astype(np.float32)
+            A, Bm = oracle.binarize_pack(a, 1), oracle.binarize_pack(b, 1)
+            ld = (A.shape[1] + 1) // 2 * 2 + 2 * (K % 3)            # even, sometimes wider than the row
+            Ad = np.full((M, ld), POISON, dtype=np.uint64); Ad[:, :A.shape[1]] = A
+            Bd = np.full((N, ld), POISON, dtype=np.uint64); Bd[:, :A.shape[1]] = Bm
+            want = oracle.xnor_gemm(A, Bm, K)
+            got = B.xnor_gemm(dev(Ad.view(np.int64)), dev(Bd.view(np.int64)), K).cpu().numpy()
+            assert "gemm_fp4_kernel<4,2,1" in B.last_kernel()
+            np.testing.assert_array_equal(got, want)
+            cnt = B.xnor_gemm(dev(Ad.view(np.int64)), dev(Bd.view(np.int64)), K, count=True).cpu().numpy()
+            np.testing.assert_array_equal(2 * cnt - K, want)
+        for (batch, fin, fout) in [(19, 2500, 75), (200, 4096, 130), (256, 1100, 300)]:
+            x = rng.standard_normal((batch, fin)).astype(np.float32)
+            w = rng.uniform(-1, 1, (fout, fin)).astype(np.float32)
+            alpha = rng.standard_normal(fout).astype(np.float32)
+            alpha[::3] = 0.0
+            ri, rf = oracle.binary_fc(x, w, alpha)
+            Wp = B.binarize_pack(dev(w), 1)
+            if Wp.shape[1] % 2:                                      # 16-byte rows for the matrix-core kernels
+                Wp = torch.cat([Wp, torch.zeros_like(Wp[:, :1])], dim=1).contiguous()
+            np.testing.assert_array_equal(B.binary_fc(dev(x), Wp, integer_out=True).cpu().numpy(), ri)
+            assert "gemm_fp4_kernel<4,2,1" in B.last_kernel()
+            assert_f32_close(B.binary_fc(dev(x), Wp, alpha=dev(alpha)).cpu().numpy(), rf)
+            assert "gemm_fp4_kernel<4,2,1" in B.last_kernel()
 
 
 @pytest.mark.parametrize("split,partials", [(0, 0), (1, 0), (2, 0), (3, 0), (5, 0), (7, 0), (8, 0), (8, 2), (3, 2)])
