@@ -478,8 +478,13 @@ def main():
         ws1 = [u8(B.workspace_bytes(B.OP_BINARY_FC, (64, 512, 256))) for _ in range(n1)]
         us_, nm_ = rotating_us([(lambda i=i: B.binary_fc(a1[i], W1p[i], integer_out=True, out=o1[i], workspace=ws1[i]))
                                 for i in range(n1)])
-        blk = roofline_block(nm_, us_, binops=2.0 * 64 * 256 * 512, nbytes=64 * 64 + 256 * 64 + 64 * 256 * 4)
-        blk["note"] = "whole call (pack + GEMM): two launches of about 2.4 us each; 13 ns of arithmetic"
+        # (fp32 activations in, packed weights in, int32 out: what the one-launch form moves)
+        blk = roofline_block(nm_, us_, binops=2.0 * 64 * 256 * 512, nbytes=64 * 512 * 4 + 256 * 64 + 64 * 256 * 4)
+        blk["note"] = ("whole call in one launch (sign bits of a batch row in LDS, xor + popcount per output feature); "
+                       "13 ns of arithmetic behind a launch and two trips to memory")
+        two_us, two_nm = with_tune({15: 1}, lambda: rotating_us(
+            [(lambda i=i: B.binary_fc(a1[i], W1p[i], integer_out=True, out=o1[i], workspace=ws1[i])) for i in range(n1)]))
+        blk["general_path_two_launches"] = {"kernel": two_nm, "call_us": two_us}
         other["config1_fc_call_64x256x512"] = blk
         del a1, W1p, o1, ws1
 

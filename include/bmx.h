@@ -288,6 +288,7 @@ size_t bmx_workspace_bytes(int op, const int64_t* dims, int ndims);
  *   key 14 = 1: the short-K matrix-core convolution kernel fetches pixel words 8 bytes at a time
  *          even where 16 would do; 2: 16 at a time, but never in the form for channel-word
  *          counts that are multiples of four; 3: never in the form that holds one block per wave
+ *   key 15 = 1: bmx_binary_fc never takes its one-launch form for very small layers
  *   key 8  K-split waves, key 9  tile variant (1: 32 x 32, 2: 64 x 64 per wave) of the matrix-core
  *          kernels */
 int bmx_tune_set(int key, int value);

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libbmx.so")
-SOURCES = ["bmx_api.hip", "pack.hip", "gemm.hip", "gemm_mfma.hip", "gemm_fp4.hip", "conv.hip", "conv_mfma.hip", "probe.hip"]
+SOURCES = ["bmx_api.hip", "pack.hip", "gemm.hip", "gemm_mfma.hip", "gemm_fp4.hip", "conv.hip", "conv_mfma.hip", "fc_small.hip", "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # packed-fp32 VALU forms are kept out of generated code on the test machines

@@ -86,7 +86,7 @@ extern "C" {
 int bmx_tune_set(int key, int value) {
   if (key == 0) {  // everything back to the automatic choice
     bmx::conv_filters_per_wave = bmx::gemm_tune_rows = bmx::gemm_tune_ksplit = bmx::gemm_tune_order = 0;
-    bmx::conv_path = bmx::gemm_engine = bmx::gemm_mfma_ksplit = bmx::gemm_mfma_tile = bmx::gemm_fp4_split = bmx::gemm_fp4_half = bmx::gemm_fp4_band = bmx::gemm_fp4_tall = bmx::conv_ws_x4 = 0;
+    bmx::conv_path = bmx::gemm_engine = bmx::gemm_mfma_ksplit = bmx::gemm_mfma_tile = bmx::gemm_fp4_split = bmx::gemm_fp4_half = bmx::gemm_fp4_band = bmx::gemm_fp4_tall = bmx::conv_ws_x4 = bmx::fc_small = 0;
     return BMX_OK;
   }
   if (key == 1) bmx::conv_filters_per_wave = value;
@@ -102,6 +102,7 @@ int bmx_tune_set(int key, int value) {
   else if (key == 12) bmx::gemm_fp4_band = value;
   else if (key == 13) bmx::gemm_fp4_tall = value;
   else if (key == 14) bmx::conv_ws_x4 = value;
+  else if (key == 15) bmx::fc_small = value;
   else return BMX_ERR_UNSUPPORTED;
   return BMX_OK;
 }
@@ -309,6 +310,9 @@ int fc_check(const float* x, int64_t ldx, const uint64_t* Wp, int64_t ldw_w, con
 int fc_launch(const float* x, int64_t ldx, const uint64_t* Wp, int64_t ldw_w, const float* alpha, int batch,
               int in_features, int out_features, int32_t* out_i32, float* out_f32, int64_t ldo, uint64_t* xp,
               hipStream_t s) {
+  hipError_t small = hipSuccess;  // a layer of a few microseconds or less: one launch, no workspace
+  if (bmx::launch_fc_small(x, ldx, Wp, ldw_w, alpha, batch, in_features, out_features, out_i32, out_f32, ldo, s, &small))
+    return hip_status(small);
   const int64_t ldp = bmx::padded_words(in_features);
   hipError_t e = bmx::launch_pack_rows_padded(x, batch, in_features, ldx, xp, ldp, s);
   if (e != hipSuccess) return BMX_ERR_HIP;

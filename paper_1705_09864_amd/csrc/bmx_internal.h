@@ -126,6 +126,13 @@ bool launch_conv_fp4(const uint64_t* Xp, int Nimg, int C, int H, int W, const ui
                      int stride, int pad, const float* alpha, int32_t* out_i32, float* out_f32, hipStream_t s,
                      hipError_t* err);
 extern int gemm_fp4_split, gemm_fp4_half, gemm_fp4_band, gemm_fp4_tall;
+// fc_small.hip: the whole fully connected layer (sign bits of the fp32 input, xor + popcount,
+// scale) in one launch, for layers too small to be worth two; false when the layer is not
+// small enough (nothing launched then).
+bool launch_fc_small(const float* x, int64_t ldx, const uint64_t* Wp, int64_t ldw_w, const float* alpha, int batch,
+                     int in_features, int out_features, int32_t* out_i32, float* out_f32, int64_t ldo,
+                     hipStream_t s, hipError_t* err);
+extern int fc_small;
 bool launch_plane_gemm_mfma(const uint64_t* planes_rows, int64_t lda_w, int bits, const int32_t* rowsum,
                             const uint64_t* Wb, int64_t ldb_w, int M, int N, int K, int32_t* S_out,
                             float* out_f32, int64_t ldo, hipStream_t s, hipError_t* err);

@@ -173,9 +173,14 @@ def test_config1_fc_gemm_exact():
     Wp = B.binarize_pack(dev(w_kn), 0)                # pack down the K rows -> [256, 8]
     np.testing.assert_array_equal(host_u64(Wp), oracle.binarize_pack(w_kn, 0))
     got = B.binary_fc(dev(a), Wp, integer_out=True).cpu().numpy()
+    assert "fc_small_kernel" in B.last_kernel()       # the one-launch form of very small layers
     ref, _ = oracle.binary_fc(a, w_kn.T.copy())
     assert got.dtype == np.int32 and got.shape == (64, 256)
     np.testing.assert_array_equal(got, ref)
+    with tuned(k15=1):                                 # the general path: pack, then the GEMM
+        got = B.binary_fc(dev(a), Wp, integer_out=True).cpu().numpy()
+        assert "fc_small_kernel" not in B.last_kernel()
+        np.testing.assert_array_equal(got, ref)
     # the same through pack + xnor_gemm
     Ap = B.binarize_pack(dev(a), 1)
     np.testing.assert_array_equal(B.xnor_gemm(Ap, Wp, 512).cpu().numpy(), ref)
@@ -200,6 +205,42 @@ def test_config3_fc_chain(small):
             assert_f32_close(h2.cpu().numpy(), r2f)
             i2 = B.binary_fc(h1, W2p, integer_out=True)
             np.testing.assert_array_equal(i2.cpu().numpy(), r2i)
+
+
+@pytest.mark.parametrize("batch,fin,fout", [(1, 1, 1), (64, 512, 256), (7, 65, 3), (100, 1000, 70), (4096, 64, 1),
+                                            (3, 64 * 33 + 5, 7), (2, 65536, 16), (33, 4000, 257), (1, 130, 5000)])
+def test_fc_small_layers_one_launch(batch, fin, fout):
+    """bmx_binary_fc on layers small enough for its one-launch form (sign bits of a batch row in
+    LDS, xor + popcount per output feature): K tails inside a word, more and fewer than four
+    words per wave, more than 256 output features, rows of x and of the output further apart
+    than their length with poison between them, special values in x; int32 and scaled fp32."""
+    rng = np.random.default_rng(batch + 3 * fin + 7 * fout)
+    x = rng.standard_normal((batch, fin)).astype(np.float32)
+    x.flat[:: 7] = 0.0
+    x.flat[3:: 11] = -0.0
+    x.flat[5:: 13] = np.nan
+    x.flat[1:: 17] = np.inf
+    x.flat[2:: 19] = -np.inf
+    w = rng.uniform(-1, 1, (fout, fin)).astype(np.float32)
+    alpha = rng.standard_normal(fout).astype(np.float32)
+    alpha[::3] = 0.0
+    ri, rf = oracle.binary_fc(x, w, alpha)
+    Wp = B.binarize_pack(dev(w), 1)
+    xw = torch.full((batch, fin + 5), float("nan"), dtype=torch.float32, device="cuda")   # rows fin + 5 apart
+    xw[:, :fin] = dev(x)
+    oi = torch.full((batch, fout + 3), -7, dtype=torch.int32, device="cuda")
+    of = torch.full((batch, fout + 3), 123.0, dtype=torch.float32, device="cuda")
+    B.binary_fc(xw[:, :fin], Wp, integer_out=True, out=oi[:, :fout])
+    assert "fc_small_kernel" in B.last_kernel()
+    B.binary_fc(xw[:, :fin], Wp, alpha=dev(alpha), out=of[:, :fout])
+    assert "fc_small_kernel" in B.last_kernel()
+    np.testing.assert_array_equal(oi[:, :fout].cpu().numpy(), ri)
+    np.testing.assert_array_equal(of[:, :fout].cpu().numpy(), rf)      # one fp32 multiply: bit-identical
+    assert (oi[:, fout:] == -7).all() and (of[:, fout:] == 123.0).all()
+    np.testing.assert_array_equal(B.binary_fc(dev(x), Wp).cpu().numpy(), ri.astype(np.float32))
+    with tuned(k15=1):
+        np.testing.assert_array_equal(B.binary_fc(dev(x), Wp, integer_out=True).cpu().numpy(), ri)
+        assert "fc_small_kernel" not in B.last_kernel()
 
 
 @pytest.mark.parametrize("batch,fin,fout", [(1, 1, 1), (5, 27, 3), (3, 180, 70), (66, 1000, 130)])

@@ -21,17 +21,26 @@ def _layer(seed, batch, fin, fout):
 def test_static_scratch_fc_matches_workspace_fc():
     # the first call fills far more of the array than the second reads; the second has a K tail
     # inside a word and rows that end inside a padded chunk
-    for seed, (batch, fin, fout) in enumerate([(200, 5000, 300), (37, 1000, 70), (256, 9216, 512), (3, 65, 5)]):
-        x, Wp, alpha = _layer(100 + seed, batch, fin, fout)
-        want_f = B.binary_fc(x, Wp, alpha=alpha)
-        want_i = B.binary_fc(x, Wp, integer_out=True)
-        got_f = torch.full((batch, fout), float("nan"), dtype=torch.float32, device="cuda")
-        got_i = torch.full((batch, fout), -7, dtype=torch.int32, device="cuda")
-        B.binary_fc_static(x, Wp, alpha=alpha, out=got_f)
-        B.binary_fc_static(x, Wp, integer_out=True, out=got_i)
-        torch.cuda.synchronize()
-        assert torch.equal(got_i, want_i), (batch, fin, fout)
-        assert torch.equal(got_f, want_f), (batch, fin, fout)          # one fp32 multiply of equal integers
+    # (very small layers take a one-launch kernel that packs into LDS and never touches the array:
+    # first with that kernel switched off, so that every call goes through the array, then as is)
+    for small_off in (1, 0):
+        assert B.lib().bmx_tune_set(15, small_off) == 0
+        try:
+            for seed, (batch, fin, fout) in enumerate([(200, 5000, 300), (37, 1000, 70), (256, 9216, 512), (3, 65, 5)]):
+                x, Wp, alpha = _layer(100 + seed, batch, fin, fout)
+                want_f = B.binary_fc(x, Wp, alpha=alpha)
+                want_i = B.binary_fc(x, Wp, integer_out=True)
+                got_f = torch.full((batch, fout), float("nan"), dtype=torch.float32, device="cuda")
+                got_i = torch.full((batch, fout), -7, dtype=torch.int32, device="cuda")
+                B.binary_fc_static(x, Wp, alpha=alpha, out=got_f)
+                if small_off:
+                    assert "fc_small" not in B.last_kernel()
+                B.binary_fc_static(x, Wp, integer_out=True, out=got_i)
+                torch.cuda.synchronize()
+                assert torch.equal(got_i, want_i), (batch, fin, fout)
+                assert torch.equal(got_f, want_f), (batch, fin, fout)          # one fp32 multiply of equal integers
+        finally:
+            B.lib().bmx_tune_set(15, 0)
 
 
 def test_static_scratch_limit_and_errors():
