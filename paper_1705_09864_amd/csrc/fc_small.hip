@@ -73,7 +73,8 @@ bool launch_fc_small(const float* x, int64_t ldx, const uint64_t* Wp, int64_t ld
                      int in_features, int out_features, int32_t* out_i32, float* out_f32, int64_t ldo,
                      hipStream_t s, hipError_t* err) {
   const int64_t Kw = words_for(in_features);
-  if (fc_small == 1 || Kw > 1024 || (int64_t)out_features * Kw > 256 * 64 || batch > 4096) return false;
+  // (a GEMM engine pinned through the tuning hook is what the caller wants to run)
+  if (fc_small == 1 || gemm_engine != 0 || Kw > 1024 || (int64_t)out_features * Kw > 256 * 64 || batch > 4096) return false;
   note_kernel("fc_small_kernel grid %d x 256", batch);
   hipLaunchKernelGGL(fc_small_kernel, dim3((unsigned)batch), dim3(256), (size_t)Kw * 8, s, x, ldx, Wp, ldw_w, alpha,
                      in_features, (int)Kw, out_features, out_i32, out_f32, ldo);
