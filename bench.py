@@ -331,18 +331,23 @@ def main():
                 # has its own workspace; steps that share a set sit on the same lane): what a
                 # serving loop that overlaps batches gets out of the same kernels.  Context, not
                 # the headline: `value` is the chain of dependent launches above.
+                # (at least 200 steps per replay: the fixed cost of a replay with side streams
+                # would otherwise weigh on a per-step figure of some twenty microseconds)
+                n_l = max(K_STEPS, 200)
+                steps_l = [make_step(i % nsets) for i in range(n_l)]
                 for lanes in (2, 4):
                     if nsets % lanes == 0:
-                        gl = graph_of_lanes(steps, lanes)
+                        gl = graph_of_lanes(steps_l, lanes)
                         gl.replay()
-                        for i in range(K_STEPS, nsets):
+                        for i in range(n_l, nsets):
                             make_step(i)()
                         torch.cuda.synchronize()
                         t0 = time.perf_counter()
                         gl.replay()
                         torch.cuda.synchronize()
-                        lanes_us[lanes] = (time.perf_counter() - t0) / K_STEPS * 1e6
+                        lanes_us[lanes] = (time.perf_counter() - t0) / n_l * 1e6
                         del gl
+                del steps_l
             del steps
         else:  # one layer alone: the first layer's outputs must exist for the second
             for i in range(nsets):
