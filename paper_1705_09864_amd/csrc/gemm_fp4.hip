@@ -525,9 +525,57 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
         pb_tot += (FULL || s < S) ? cb8[s] : 0;
       }
     }
-    for (int g = wave; g < kGroups; g += S) {
+    // the popcount terms, scale and stores of accumulator group g, whose four sums are tot
+    auto finish_group = [&](int g, float4 tot) {
       const int blk = g >> 2, q = g & 3, i = blk / TN, j = blk % TN;
       const int row0 = 32 * i + 8 * q + 4 * h;  // this lane's four rows: row0 .. row0 + 3
+      int ra[4], cb = 0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) ra[e] = __shfl(pa_tot, row0 + e);
+      if (XNOR) cb = __shfl(pb_tot, 32 * j + r);
+      const float al = j == 0 ? aln0 : aln1, th = j == 0 ? thn0 : thn1;
+      float alm[4] = {al, al, al, al};
+      if (CONV) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) alm[e] = __shfl(alpha_l, row0 + e);
+      }
+      finish(std::false_type{}, i, j, 4 * q, tot.x, ra[0], cb, alm[0], th);
+      finish(std::false_type{}, i, j, 4 * q + 1, tot.y, ra[1], cb, alm[1], th);
+      finish(std::false_type{}, i, j, 4 * q + 2, tot.z, ra[2], cb, alm[2], th);
+      finish(std::false_type{}, i, j, 4 * q + 3, tot.w, ra[3], cb, alm[3], th);
+    };
+    if constexpr (FULL && HALF) {
+      // Eight waves, fp16 partials (the fully connected layers): a wave has exactly kGroups / 8
+      // groups, and the partials of all of them are requested before the first is summed, so
+      // that the second group's LDS round trip runs under the first group's sums and stores.
+      constexpr int NG = kGroups / 8;
+      uint2 t[NG][8];
+#pragma unroll
+      for (int it = 0; it < NG; ++it)
+#pragma unroll
+        for (int s = 0; s < 8; ++s) t[it][s] = part16[(s * kSlot) * 2 + (wave + 8 * it) * 64 + lane];
+#pragma unroll
+      for (int it = 0; it < NG; ++it) {
+        float4 tot = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+          // v_dot2_f32_f16 with (1, 0) or (0, 1) picks a half, widens it and adds it in one
+          // instruction (exact: whole numbers up to 2048, fp32 accumulation)
+          const half2_t lo = __builtin_bit_cast(half2_t, t[it][s].x), hi = __builtin_bit_cast(half2_t, t[it][s].y);
+          const half2_t first = {(__fp16)1.0f, (__fp16)0.0f}, second = {(__fp16)0.0f, (__fp16)1.0f};
+          tot.x = __builtin_amdgcn_fdot2(lo, first, tot.x, false);
+          tot.y = __builtin_amdgcn_fdot2(lo, second, tot.y, false);
+          tot.z = __builtin_amdgcn_fdot2(hi, first, tot.z, false);
+          tot.w = __builtin_amdgcn_fdot2(hi, second, tot.w, false);
+        }
+#ifdef BMX_FP4_STAMPS
+        if (it == 0) { FP4_STAMP(7); }
+#endif
+        finish_group(wave + 8 * it, tot);
+      }
+      return;
+    }
+    for (int g = wave; g < kGroups; g += S) {
       // all reads first (partials past S repeat the last one and count as nothing), so that the
       // LDS round trips overlap instead of adding up
       float4 tot = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -539,20 +587,10 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
         for (int s = 0; s < 8; ++s) {
           const bool on = FULL || s < S;
           const half2_t lo = __builtin_bit_cast(half2_t, t[s].x), hi = __builtin_bit_cast(half2_t, t[s].y);
-          if constexpr (FULL) {
-            // v_dot2_f32_f16 with (1, 0) or (0, 1) picks a half, widens it and adds it in one
-            // instruction (exact: whole numbers up to 2048, fp32 accumulation)
-            const half2_t first = {(__fp16)1.0f, (__fp16)0.0f}, second = {(__fp16)0.0f, (__fp16)1.0f};
-            tot.x = __builtin_amdgcn_fdot2(lo, first, tot.x, false);
-            tot.y = __builtin_amdgcn_fdot2(lo, second, tot.y, false);
-            tot.z = __builtin_amdgcn_fdot2(hi, first, tot.z, false);
-            tot.w = __builtin_amdgcn_fdot2(hi, second, tot.w, false);
-          } else {
-            tot.x += on ? (float)lo[0] : 0.f;
-            tot.y += on ? (float)lo[1] : 0.f;
-            tot.z += on ? (float)hi[0] : 0.f;
-            tot.w += on ? (float)hi[1] : 0.f;
-          }
+          tot.x += on ? (float)lo[0] : 0.f;
+          tot.y += on ? (float)lo[1] : 0.f;
+          tot.z += on ? (float)hi[0] : 0.f;
+          tot.w += on ? (float)hi[1] : 0.f;
         }
       } else {
         float4 t[8];
@@ -570,20 +608,7 @@ gemm_fp4_kernel(const Fp4Params p, const int S_arg
 #ifdef BMX_FP4_STAMPS
       if (g == wave) { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); FP4_STAMP(7); }
 #endif
-      int ra[4], cb = 0;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) ra[e] = __shfl(pa_tot, row0 + e);
-      if (XNOR) cb = __shfl(pb_tot, 32 * j + r);
-      const float al = j == 0 ? aln0 : aln1, th = j == 0 ? thn0 : thn1;
-      float alm[4] = {al, al, al, al};
-      if (CONV) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) alm[e] = __shfl(alpha_l, row0 + e);
-      }
-      finish(std::false_type{}, i, j, 4 * q, tot.x, ra[0], cb, alm[0], th);
-      finish(std::false_type{}, i, j, 4 * q + 1, tot.y, ra[1], cb, alm[1], th);
-      finish(std::false_type{}, i, j, 4 * q + 2, tot.z, ra[2], cb, alm[2], th);
-      finish(std::false_type{}, i, j, 4 * q + 3, tot.w, ra[3], cb, alm[3], th);
+      finish_group(g, tot);
     }
   };
   if (S == 8) reduce(std::true_type{});
