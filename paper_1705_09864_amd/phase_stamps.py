@@ -51,7 +51,8 @@ def main(argv):
     if "--build" in argv:
         print(build_stamped())
         return
-    if not os.path.exists(STAMPED):
+    sources = [os.path.join(_build.CSRC, f) for f in os.listdir(_build.CSRC)]
+    if _build._stale(STAMPED, sources):  # missing, or older than a source file
         build_stamped()
     import numpy as np
     import torch
