@@ -31,6 +31,21 @@ def test_status_strings():
     assert "unknown" in B.status_string(-99)
 
 
+def test_tune_keys():
+    """The measurement hook takes the keys the header documents and no others, and key 0 puts
+    every choice back to automatic (no kernel runs here: the settings only steer later calls)."""
+    L = B.lib()
+    text = open(os.path.join(ROOT, "include", "bmx.h")).read()
+    documented = {int(k) for k in re.findall(r"\bkey (\d+)\b", text[text.index("bmx_tune_set(0, 0)"):text.index("int bmx_tune_set")])}
+    try:
+        for key in range(1, 40):
+            rc = L.bmx_tune_set(key, 1)
+            assert rc == (OK if key in documented else E_UNSUP), key
+        assert {1, 5, 7, 10, 13, 14, 15} <= documented
+    finally:
+        assert L.bmx_tune_set(0, 0) == OK
+
+
 def test_workspace_query():
     assert B.workspace_bytes(B.OP_BINARY_FC, (256, 9216, 4096)) == 256 * 144 * 8
     assert B.workspace_bytes(B.OP_BINARY_FC, (5, 65, 3)) == 5 * 16 * 8 + 128  # 5 rows padded to 16 words, rounded up to 256 B
