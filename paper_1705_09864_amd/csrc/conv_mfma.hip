@@ -177,10 +177,10 @@ constexpr int kWs36Waves = 3;  // waves per SIMD at 36 words, 16-byte pixel load
 // K-words 2 q and 2 q + 1 are neighbours in the image and 16-byte aligned; 2: a multiple of four
 // channel words, so that K-words 4 q .. 4 q + 3 are 32 consecutive bytes and the two half-waves'
 // addresses differ by 16 in every load: a uniform base per load and one lane offset for all).
-// ONE: every wave has exactly one block (the launcher's choice when all of them are resident
-// at once at four waves per SIMD): nothing is fetched ahead, one accumulator chain (the other
-// waves of the SIMD fill the matrix pipe while a wave waits for its own last MFMA), operands
-// two steps ahead; which is what lets the wave live in 128 registers.
+// ONE: every wave has exactly one block (the launcher's choice whenever the blocks are dealt out
+// one per wave, and at 36 words also when that takes four waves per SIMD instead of three):
+// nothing is fetched ahead and no next block is located, which is what lets the wave live in
+// about 100 registers.
 template <int KW, int TM, int WPS, bool BITS, int X4, bool ONE = false>
 __global__ void __launch_bounds__(256, WPS)
 conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
@@ -362,8 +362,8 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
     // steps ahead: read where they are used, every pair of MFMAs would wait out an LDS round trip.
     // (with two filter blocks per wave their two chains are independent already, and registers
     // are short: one chain each, operands two steps ahead)
-    constexpr int CH = (TM == 1 && !ONE) ? 2 : 1;
-    constexpr int G = (KW > 36 || TM == 2 || ONE) ? 2 : 4, NG = (KW + G - 1) / G;
+    constexpr int CH = TM == 1 ? 2 : 1;
+    constexpr int G = (KW > 36 || TM == 2) ? 2 : 4, NG = (KW + G - 1) / G;
     v16f acc[TM][CH];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -610,7 +610,8 @@ bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, cons
   p.blk_q = p.nblocks / p.nchunks;
   p.blk_r = p.nblocks % p.nchunks;
   if (out_bits) {
-    if (kwords == 9) launch_ws<9, 1, 4, true>(p, m_tiles, s);
+    if (kwords == 9 && p.nchunks == p.nblocks && conv_ws_x4 != 3) launch_ws_form<9, 1, 4, true, 0, true>(p, m_tiles, s);
+    else if (kwords == 9) launch_ws<9, 1, 4, true>(p, m_tiles, s);
     else if (kwords == 18) launch_ws<18, 1, 3, true>(p, m_tiles, s);
     else if (kwords == 25) launch_ws<25, 1, 3, true>(p, m_tiles, s);
     else if (kwords == 27) launch_ws<27, 1, 3, true>(p, m_tiles, s);
@@ -619,6 +620,8 @@ bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, cons
     else launch_ws<36, 1, 2, true>(p, m_tiles, s);
   } else if (kwords == 9) {
     if (TM == 2) launch_ws<9, 2, 2>(p, m_tiles, s);
+    // (a wave per block: the form that fetches nothing ahead and keeps one accumulator chain)
+    else if (p.nchunks == p.nblocks && conv_ws_x4 != 3) launch_ws_form<9, 1, 4, false, 0, true>(p, m_tiles, s);
     else launch_ws<9, 1, 4>(p, m_tiles, s);
   } else if (kwords == 18) {
     launch_ws<18, 1, 3>(p, m_tiles, s);
@@ -630,7 +633,7 @@ bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, cons
     launch_ws<49, 1, 2>(p, m_tiles, s);
   } else if (kwords == 50) {
     launch_ws<50, 1, 2>(p, m_tiles, s);
-  } else if (one36) {
+  } else if (one36) {  // (with a wave per block anyway the other form is as fast: 5.2 against 5.3 us at stride 2)
     launch_ws_form<36, 1, 4, false, 2, true>(p, m_tiles, s);
   } else {
     launch_ws<36, 1, 2, false, kWs36Waves>(p, m_tiles, s);
