@@ -177,10 +177,11 @@ constexpr int kWs36Waves = 3;  // waves per SIMD at 36 words, 16-byte pixel load
 // K-words 2 q and 2 q + 1 are neighbours in the image and 16-byte aligned; 2: a multiple of four
 // channel words, so that K-words 4 q .. 4 q + 3 are 32 consecutive bytes and the two half-waves'
 // addresses differ by 16 in every load: a uniform base per load and one lane offset for all).
-// ONE: every wave has exactly one block (the launcher's choice whenever the blocks are dealt out
-// one per wave, and at 36 words also when that takes four waves per SIMD instead of three):
-// nothing is fetched ahead and no next block is located, which is what lets the wave live in
-// about 100 registers.
+// ONE: every wave has exactly one block (the launcher's choice when the blocks are dealt out
+// one per wave and there are two or more waves per SIMD, and at 36 words also when that takes
+// four waves per SIMD instead of three): nothing is fetched ahead and no next block located,
+// one accumulator chain (the SIMD's other waves fill the matrix pipe while a wave waits for its
+// own last MFMA), a scalar base per output row; the wave lives in under 100 registers.
 template <int KW, int TM, int WPS, bool BITS, int X4, bool ONE = false>
 __global__ void __launch_bounds__(256, WPS)
 conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
@@ -362,7 +363,7 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
     // steps ahead: read where they are used, every pair of MFMAs would wait out an LDS round trip.
     // (with two filter blocks per wave their two chains are independent already, and registers
     // are short: one chain each, operands two steps ahead)
-    constexpr int CH = TM == 1 ? 2 : 1;
+    constexpr int CH = (TM == 1 && !ONE) ? 2 : 1;
     constexpr int G = (KW > 36 || TM == 2) ? 2 : 4, NG = (KW + G - 1) / G;
     v16f acc[TM][CH];
 #pragma unroll
@@ -449,17 +450,21 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
             const int mi = 8 * (v / 4) + (v % 4);
-            const uint32_t off = lane_off + (uint32_t)mi * pitch;
+            // (ONE: the row's share of the address goes into the uniform base, on the scalar ALU,
+            // and all sixteen stores share one lane offset; with several blocks per wave the
+            // compiler would keep sixteen such bases across the block loop and run out of SGPRs)
+            const uint32_t off = ONE ? lane_off : lane_off + (uint32_t)mi * pitch;
+            const size_t row_bytes = ONE ? (size_t)mi * pitch : 0;
             const float t = fmaf(2.0f, acc[i][0][v], c0[v]);
             if (decltype(inside_tag)::value || (cur.valid && m0 + 32 * i + mi + 4 * h < p.O)) {
               // (written out: the compiler builds a 64-bit vector address for a non-temporal
               // store even from a uniform base and a 32-bit offset)
               if constexpr (decltype(int_tag)::value) {
                 const int iv = (int)t;
-                asm volatile("global_store_dword %0, %1, %2 nt" ::"v"(off), "v"(iv), "s"(p.out_i32) : "memory");
+                asm volatile("global_store_dword %0, %1, %2 nt" ::"v"(off), "v"(iv), "s"((const char*)p.out_i32 + row_bytes) : "memory");
               } else {
                 const float fv = al[v] * t;
-                asm volatile("global_store_dword %0, %1, %2 nt" ::"v"(off), "v"(fv), "s"(p.out_f32) : "memory");
+                asm volatile("global_store_dword %0, %1, %2 nt" ::"v"(off), "v"(fv), "s"((const char*)p.out_f32 + row_bytes) : "memory");
               }
             }
           }
@@ -610,7 +615,8 @@ bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, cons
   p.blk_q = p.nblocks / p.nchunks;
   p.blk_r = p.nblocks % p.nchunks;
   if (out_bits) {
-    if (kwords == 9 && p.nchunks == p.nblocks && conv_ws_x4 != 3) launch_ws_form<9, 1, 4, true, 0, true>(p, m_tiles, s);
+    if (kwords == 9 && p.nchunks == p.nblocks && (int64_t)p.nblocks * m_tiles >= 2048 && conv_ws_x4 != 3)
+      launch_ws_form<9, 1, 4, true, 0, true>(p, m_tiles, s);
     else if (kwords == 9) launch_ws<9, 1, 4, true>(p, m_tiles, s);
     else if (kwords == 18) launch_ws<18, 1, 3, true>(p, m_tiles, s);
     else if (kwords == 25) launch_ws<25, 1, 3, true>(p, m_tiles, s);
@@ -621,7 +627,9 @@ bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, cons
   } else if (kwords == 9) {
     if (TM == 2) launch_ws<9, 2, 2>(p, m_tiles, s);
     // (a wave per block: the form that fetches nothing ahead and keeps one accumulator chain)
-    else if (p.nchunks == p.nblocks && conv_ws_x4 != 3) launch_ws_form<9, 1, 4, false, 0, true>(p, m_tiles, s);
+    // (from two waves per SIMD on: a wave alone on its SIMD is better off with two chains)
+    else if (p.nchunks == p.nblocks && (int64_t)p.nblocks * m_tiles >= 2048 && conv_ws_x4 != 3)
+      launch_ws_form<9, 1, 4, false, 0, true>(p, m_tiles, s);
     else launch_ws<9, 1, 4>(p, m_tiles, s);
   } else if (kwords == 18) {
     launch_ws<18, 1, 3>(p, m_tiles, s);
