@@ -157,11 +157,11 @@ struct Lds {
 }  // namespace
 unsigned long long* ws_stamps = nullptr;
 namespace {
-#define WS_STAMP(k) do { if (stamps && lane == 0) stamps[(size_t)((blockIdx.y * gridDim.x + blockIdx.x) * 4 + wave) * 16 + (k)] = __builtin_readcyclecounter(); } while (0)
+#define WS_STAMP(k) do { if (stamps && lane == 0) stamps[(size_t)((blockIdx.y * gridDim.x + blockIdx.x) * (blockDim.x >> 6) + wave) * 16 + (k)] = __builtin_readcyclecounter(); } while (0)
 #define WS_STAMP_ARG , unsigned long long* stamps
 constexpr int kWs36Waves = 2;  // (the stamps need registers of their own)
 // (the constant 100 MHz counter, which all parts of the chip share: for times between waves)
-#define WS_REALTIME(k) do { if (stamps && lane == 0) stamps[(size_t)((blockIdx.y * gridDim.x + blockIdx.x) * 4 + wave) * 16 + (k)] = __builtin_amdgcn_s_memrealtime(); } while (0)
+#define WS_REALTIME(k) do { if (stamps && lane == 0) stamps[(size_t)((blockIdx.y * gridDim.x + blockIdx.x) * (blockDim.x >> 6) + wave) * 16 + (k)] = __builtin_amdgcn_s_memrealtime(); } while (0)
 #else
 #define WS_STAMP(k) do { } while (0)
 #define WS_REALTIME(k) do { } while (0)
@@ -182,9 +182,15 @@ constexpr int kWs36Waves = 3;  // waves per SIMD at 36 words, 16-byte pixel load
 // four waves per SIMD instead of three): nothing is fetched ahead and no next block located,
 // one accumulator chain (the SIMD's other waves fill the matrix pipe while a wave waits for its
 // own last MFMA), a scalar base per output row; the wave lives in under 100 registers.
-template <int KW, int TM, int WPS, bool BITS, int X4, bool ONE = false>
-__global__ void __launch_bounds__(256, WPS)
+// NW: waves per workgroup (4, or 8 with WPS even): twice the waves share one copy of the filter
+// block, so that each expands half as much of it and a CU holds half as many copies.  Worth
+// 0.5 us where four waves per SIMD contend for the vector ALU over 36 words (64 x 256 x 14 x 14,
+// 256 filters: 8.5 -> 8.0 us), nothing at 9 words, and sixteen waves leave CUs empty there (8.7).
+template <int KW, int TM, int WPS, bool BITS, int X4, bool ONE = false, int NW = 4>
+__global__ void __launch_bounds__(64 * NW, WPS * 4 / NW)
 conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
+  static_assert(NW == 4 || (NW == 8 && WPS % 2 == 0), "whole workgroups per CU");
+  constexpr int kThreads = 64 * NW;
   static_assert((!X4 || KW % 2 == 0) && (X4 != 2 || KW % 4 == 0), "pairs of words, or fours");
   // load instructions per block: two words per pixel each, or four
   constexpr int NI = X4 ? (KW + 3) / 4 : (KW + 1) / 2;
@@ -204,7 +210,7 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int r = lane & 31, h = lane >> 5;
   const int m0 = blockIdx.y * (32 * TM);
-  const int chunk = blockIdx.x * 4 + wave;
+  const int chunk = blockIdx.x * NW + wave;
   // the blocks are dealt out evenly: chunk c takes blk_q of them, the first blk_r chunks one more
   // (no division here: this runs before the wave's first load)
   const int cc = min(chunk, p.nchunks);
@@ -262,12 +268,12 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
   // one unit = one 64-bit word of a filter's bits, expanded on the way: 8 bytes read, the two
   // halves' four planes (32 bytes) written
   constexpr int kUnits = 32 * TM * KW;
-  constexpr int kCopies = (kUnits + 255) / 256;
+  constexpr int kCopies = (kUnits + kThreads - 1) / kThreads;
   uint64_t buf[kCopies];
   const uint32_t ld_bytes = (uint32_t)p.ld_dw * 4u;
 #pragma unroll
   for (int t = 0; t < kCopies; ++t) {
-    const int c = min((int)threadIdx.x + 256 * t, kUnits - 1);
+    const int c = min((int)threadIdx.x + kThreads * t, kUnits - 1);
     const uint32_t row = (uint32_t)c / KW, j = (uint32_t)c - mul24(KW, row);
     // rows past the last filter repeat it; their results are never stored
     // (a 32-bit byte offset from the uniform base: no 64-bit address arithmetic per load)
@@ -299,7 +305,7 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
     const uint64_t ones = (cw == p.oCw - 1 && (p.O & 63)) ? (((uint64_t)1 << (p.O & 63)) - 1) : ~(uint64_t)0;
     const int nh = p.oHp * p.oWp - p.HoWo;
     uint64_t* ob = (uint64_t*)p.out_bits;
-    for (int i = blockIdx.x * 256 + threadIdx.x; i < nh * p.Nimg; i += gridDim.x * 256) {
+    for (int i = blockIdx.x * kThreads + threadIdx.x; i < nh * p.Nimg; i += gridDim.x * kThreads) {
       const int n = i / nh, k = i - n * nh;
       int hh, ww;
       if (k < 2 * p.opad * p.oWp) {  // rows above and below
@@ -319,7 +325,7 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
   {
 #pragma unroll
     for (int t = 0; t < kCopies; ++t) {
-      const int c = (int)threadIdx.x + 256 * t;
+      const int c = (int)threadIdx.x + kThreads * t;
       // word j of row c / KW at dword row * FS + 8 j = 8 c + 4 row, as FS = 8 KW + 4
       static_assert(FS == 8 * KW + 4, "the index below");
       const int at = 8 * c + 4 * (c / KW);
@@ -489,17 +495,17 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
 #endif
 }
 
-template <int KW, int TM, int WPS, bool BITS, int X4, bool ONE = false>
+template <int KW, int TM, int WPS, bool BITS, int X4, bool ONE = false, int NW = 4>
 void launch_ws_form(const WsParams& p, int m_tiles, hipStream_t s) {
   const int chunks = p.nchunks;
-  note_kernel("conv_mfma_ws_kernel<%d,%d,%d,%s%s%s> grid %d x %d x 256", KW, TM, WPS, BITS ? "true" : "false",
-              X4 == 2 ? ",x4 runs" : X4 ? ",x4" : "", ONE ? ",one block" : "", (int)ceil_div(chunks, 4), m_tiles);
+  note_kernel("conv_mfma_ws_kernel<%d,%d,%d,%s%s%s> grid %d x %d x %d", KW, TM, WPS, BITS ? "true" : "false",
+              X4 == 2 ? ",x4 runs" : X4 ? ",x4" : "", ONE ? ",one block" : "", (int)ceil_div(chunks, NW), m_tiles, 64 * NW);
 #ifdef BMX_WS_STAMPS
-  hipLaunchKernelGGL((conv_mfma_ws_kernel<KW, TM, WPS, BITS, X4, ONE>), dim3((unsigned)ceil_div(chunks, 4), (unsigned)m_tiles),
-                     dim3(256), 0, s, p, ws_stamps);
+  hipLaunchKernelGGL((conv_mfma_ws_kernel<KW, TM, WPS, BITS, X4, ONE, NW>), dim3((unsigned)ceil_div(chunks, NW), (unsigned)m_tiles),
+                     dim3(64 * NW), 0, s, p, ws_stamps);
 #else
-  hipLaunchKernelGGL((conv_mfma_ws_kernel<KW, TM, WPS, BITS, X4, ONE>), dim3((unsigned)ceil_div(chunks, 4), (unsigned)m_tiles),
-                     dim3(256), 0, s, p);
+  hipLaunchKernelGGL((conv_mfma_ws_kernel<KW, TM, WPS, BITS, X4, ONE, NW>), dim3((unsigned)ceil_div(chunks, NW), (unsigned)m_tiles),
+                     dim3(64 * NW), 0, s, p);
 #endif
 }
 
@@ -642,7 +648,7 @@ bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, cons
   } else if (kwords == 50) {
     launch_ws<50, 1, 2>(p, m_tiles, s);
   } else if (one36) {  // (with a wave per block anyway the other form is as fast: 5.2 against 5.3 us at stride 2)
-    launch_ws_form<36, 1, 4, false, 2, true>(p, m_tiles, s);
+    launch_ws_form<36, 1, 4, false, 2, true, 8>(p, m_tiles, s);
   } else {
     launch_ws<36, 1, 2, false, kWs36Waves>(p, m_tiles, s);
   }
