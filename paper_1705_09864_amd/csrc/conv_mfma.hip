@@ -368,7 +368,8 @@ conv_mfma_ws_kernel(const WsParams p WS_STAMP_ARG) {
     // has finished, twice the time it takes to issue.  The filter operands are read a group of
     // steps ahead: read where they are used, every pair of MFMAs would wait out an LDS round trip.
     // (with two filter blocks per wave their two chains are independent already, and registers
-    // are short: one chain each, operands two steps ahead)
+    // are short: one chain each, operands two steps ahead; the one-block form runs with two or
+    // more waves per SIMD, whose chains interleave: one chain, and no sixteen additions)
     constexpr int CH = (TM == 1 && !ONE) ? 2 : 1;
     constexpr int G = (KW > 36 || TM == 2) ? 2 : 4, NG = (KW + G - 1) / G;
     v16f acc[TM][CH];
@@ -612,8 +613,8 @@ bool launch_conv_mfma_ws(const uint64_t* Xp, int Nimg, int C, int H, int W, cons
   const int resident_waves = 256 * 4 * per_simd;
   p.nchunks = (int)std::min<int64_t>(p.nblocks, std::max(1, resident_waves / m_tiles));
   // At 36 words over four channel words: when a wave per block fits at four waves per SIMD but
-  // not at three, the form that holds one block in 128 registers; no wave is then left with
-  // a second block to run alone after the others have gone.
+  // not at three, the form that holds one block in under 100 registers (in workgroups of eight
+  // waves); no wave is then left with a second block to run alone after the others have gone.
   const bool one36 = kwords == 36 && p.x4 == 2 && !out_bits && TM == 1 && p.nchunks < p.nblocks &&
                      (int64_t)p.nblocks * m_tiles <= 256 * 4 * 4 && conv_filters_per_wave == 0 && conv_ws_x4 != 3;
   if (one36) p.nchunks = p.nblocks;
